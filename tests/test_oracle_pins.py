@@ -1,0 +1,305 @@
+"""Pins for the CPU oracle: things fixed by the paper's operator definition and by mathematics,
+none of which restate the oracle's own formula.  All run without a GPU."""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import dense_bruteforce, ref_c, ref_numpy
+from paper_2511_21862_amd import accounting
+from paper_2511_21862_amd import workloads as W
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def run(b, fn=ref_numpy.attn_mixed, **kw):
+    return fn(b.q, b.k_cache, b.v_cache, b.block_tables, b.seq_lens, b.query_start_loc, b.ctx_lens, **kw)
+
+
+def bits(x):
+    out = W.f32_to_bf16_bits(np.atleast_1d(np.asarray(x, dtype=np.float32)))
+    return out[0] if np.ndim(x) == 0 else out
+
+
+def f64(u):
+    return W.bf16_bits_to_f32(u).astype(np.float64)
+
+
+def tiny(seed, Hq=4, Hkv=2, hd=16, q_lens=(1, 5, 1), ctx_lens=(20, 7, 0), nblk=16, poison=False, **kw):
+    return W.build_batch(Hq=Hq, Hkv=Hkv, hd=hd, q_lens=q_lens, ctx_lens=ctx_lens, num_blocks=nblk, seed=seed,
+                         poison=poison, **kw)
+
+
+# --------------------------------------------------------------------------- brute force
+def test_config1_matches_dense_bruteforce_and_c():
+    b = W.config1(poison=True)
+    o = run(b)
+    assert np.isfinite(o).all()
+    assert np.abs(o - run(b, dense_bruteforce.attn_mixed_dense)).max() <= 1e-12
+    assert np.abs(o - run(b, ref_c.attn_mixed)).max() <= 1e-12
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_tiny_cases_match_dense_bruteforce(seed):
+    rng = np.random.default_rng(100 + seed)
+    Hq = int(rng.choice([1, 4, 8]))
+    Hkv = int(rng.choice([h for h in (1, 2, 4, 8) if Hq % h == 0]))
+    hd = int(rng.choice([8, 16, 64])) if seed % 4 else 128
+    n = int(rng.integers(1, 4))
+    ql = [int(rng.choice([1, 1, int(rng.integers(1, 49))])) for _ in range(n)]
+    ctx = [int(rng.integers(0, 71)) for _ in range(n)]
+    if seed == 0:
+        ql, ctx = [1, 1], [129, 0]          # seq 130 and the one-key decode
+    b = W.build_batch(Hq=Hq, Hkv=Hkv, hd=hd, q_lens=ql, ctx_lens=ctx, num_blocks=24, seed=seed, poison=True)
+    o = run(b)
+    assert np.abs(o - run(b, dense_bruteforce.attn_mixed_dense)).max() <= 1e-12
+    assert np.abs(o - run(b, ref_c.attn_mixed)).max() <= 1e-12
+
+
+# --------------------------------------------------------------------------- library special cases
+def test_prefill_without_context_equals_torch_sdpa_causal():
+    b = tiny(1, Hq=2, Hkv=2, hd=16, q_lens=(23,), ctx_lens=(0,))
+    k, v = W.gather_logical(b, 0)
+    Q = torch.from_numpy(f64(b.q)).permute(1, 0, 2)[None]          # [1, H, L, hd]
+    K = torch.from_numpy(f64(k)).permute(1, 0, 2)[None]
+    V = torch.from_numpy(f64(v)).permute(1, 0, 2)[None]
+    ref = torch.nn.functional.scaled_dot_product_attention(Q, K, V, is_causal=True)[0].permute(1, 0, 2).numpy()
+    assert np.abs(run(b) - ref).max() <= 1e-12
+
+
+def test_decode_equals_torch_sdpa_single_query_no_mask():
+    b = tiny(2, Hq=4, Hkv=4, hd=32, q_lens=(1,), ctx_lens=(52,))
+    k, v = W.gather_logical(b, 0)
+    Q = torch.from_numpy(f64(b.q)).permute(1, 0, 2)[None]
+    K = torch.from_numpy(f64(k)).permute(1, 0, 2)[None]
+    V = torch.from_numpy(f64(v)).permute(1, 0, 2)[None]
+    ref = torch.nn.functional.scaled_dot_product_attention(Q, K, V, is_causal=False)[0].permute(1, 0, 2).numpy()
+    assert np.abs(run(b) - ref).max() <= 1e-12
+
+
+def test_chunk_on_prior_context_equals_sdpa_with_explicit_mask_and_gqa_repeat():
+    b = tiny(3, Hq=4, Hkv=2, hd=16, q_lens=(9,), ctx_lens=(30,))
+    k, v = W.gather_logical(b, 0)
+    L, c, ctx = 39, 9, 30
+    Q = torch.from_numpy(f64(b.q)).permute(1, 0, 2)[None]
+    K = torch.from_numpy(f64(k)).permute(1, 0, 2).repeat_interleave(2, dim=0)[None]   # kv head h//2
+    V = torch.from_numpy(f64(v)).permute(1, 0, 2).repeat_interleave(2, dim=0)[None]
+    mask = torch.arange(L)[None, :] <= (torch.arange(c)[:, None] + ctx)
+    ref = torch.nn.functional.scaled_dot_product_attention(Q, K, V, attn_mask=mask)[0].permute(1, 0, 2).numpy()
+    assert np.abs(run(b) - ref).max() <= 1e-12
+
+
+# --------------------------------------------------------------------------- softmax
+def test_probability_rows_sum_to_one_and_have_causal_length():
+    b = W.config1()
+    _, probs = run(b, return_probs=True)
+    expect_len = []
+    for i in range(b.num_seqs):
+        for t in range(int(b.q_lens[i])):
+            expect_len += [int(b.ctx_lens[i]) + t + 1] * b.Hq
+    assert [len(p) for p in probs] == expect_len
+    assert max(abs(p.sum() - 1.0) for p in probs) <= 1e-14
+    assert all((p >= 0).all() for p in probs)
+
+
+def test_adding_a_constant_to_every_score_changes_nothing():
+    b = tiny(4, Hq=2, Hkv=1, hd=16, q_lens=(1, 6), ctx_lens=(33, 12))
+    for s in range(b.num_seqs):
+        k, v = W.gather_logical(b, s)
+        k[:, :, 15] = bits(1.0)                       # every key carries a 1 in the last feature
+        W.scatter_logical(b, s, k, v)
+    b.q[:, :, 15] = bits(0.0)
+    base = run(b)
+    b.q[:, :, 15] = bits(96.0)                        # +96*scale on every score of every row
+    shifted = run(b)
+    assert np.abs(base - shifted).max() <= 1e-12
+    b.q[:, :, 15] = bits(3000.0)                      # would overflow exp() without max-subtraction
+    assert np.abs(base - run(b)).max() <= 1e-9
+
+
+# --------------------------------------------------------------------------- closed forms
+def test_golden_two_key_rational_example():
+    exp = np.loadtxt(os.path.join(GOLD, "two_key_softmax.txt"))
+    b = W.build_batch(Hq=1, Hkv=1, hd=8, q_lens=[1], ctx_lens=[1], num_blocks=2, seed=0)
+    k = np.zeros((2, 1, 8), np.float32)
+    k[1, 0, 0] = 1.0
+    v = np.zeros((2, 1, 8), np.float32)
+    v[0, 0, :4] = [1, -2, 4, 0]
+    v[1, 0, :4] = [-3, 2, 0.5, 8]
+    W.scatter_logical(b, 0, bits(k), bits(v))
+    b.q[:] = bits(np.eye(1, 8, dtype=np.float32))[None]
+    for fn in (ref_numpy.attn_mixed, ref_c.attn_mixed, dense_bruteforce.attn_mixed_dense):
+        o = run(b, fn, scale=math.log(3.0))
+        assert np.abs(o[0, 0, :4] - exp[:, 1]).max() <= 1e-15
+        assert np.abs(o[0, 0, 4:]).max() == 0.0
+
+
+def test_constant_v_returns_v():
+    b = tiny(5, q_lens=(1, 7), ctx_lens=(40, 3))
+    row = bits(np.linspace(-2, 2, b.hd, dtype=np.float32))
+    for s in range(b.num_seqs):
+        k, v = W.gather_logical(b, s)
+        v[:] = row
+        W.scatter_logical(b, s, k, v)
+    o = run(b)
+    assert np.abs(o - f64(row)[None, None, :]).max() <= 1e-14
+
+
+def test_zero_query_gives_mean_of_visible_values():
+    b = tiny(6, Hq=2, Hkv=1, hd=8, q_lens=(4,), ctx_lens=(10,))
+    b.q[:] = 0
+    _, v = W.gather_logical(b, 0)
+    o = run(b)
+    for t in range(4):
+        assert np.abs(o[t, 0] - f64(v[: 10 + t + 1, 0]).mean(axis=0)).max() <= 1e-14
+        assert np.abs(o[t, 1] - o[t, 0]).max() == 0.0
+    assert np.abs(run(b, scale=0.0) - o).max() <= 1e-14      # scale 0 with any q: same thing
+
+
+def test_single_key_decode_returns_v0():
+    b = tiny(7, Hq=2, Hkv=2, hd=8, q_lens=(1,), ctx_lens=(0,))
+    _, v = W.gather_logical(b, 0)
+    o = run(b)
+    assert np.array_equal(o[0], f64(v[0]))
+
+
+def test_dominant_key_selects_its_value_row():
+    b = tiny(8, Hq=1, Hkv=1, hd=8, q_lens=(1,), ctx_lens=(19,))
+    k, v = W.gather_logical(b, 0)
+    k[:] = 0
+    k[11, 0, 0] = bits(1.0)
+    W.scatter_logical(b, 0, k, v)
+    b.q[:] = 0
+    b.q[0, 0, 0] = bits(1.0)
+    o = run(b, scale=50.0)                                    # key 11 scores 50 above the rest
+    assert np.abs(o[0, 0] - f64(v[11, 0])).max() <= 20 * math.exp(-50.0) * 10
+
+
+# --------------------------------------------------------------------------- paging
+def test_output_is_invariant_under_permuting_physical_blocks_and_poison():
+    clean = W.config1(poison=False)
+    dirty = W.config1(poison=True)
+    o = run(clean)
+    assert np.array_equal(o, run(dirty))                      # unowned slots are never read
+    assert np.array_equal(o, run(W.permute_blocks(clean, 9)))
+    assert np.array_equal(run(dirty, ref_c.attn_mixed), run(W.permute_blocks(dirty, 10), ref_c.attn_mixed))
+
+
+def test_causal_future_keys_do_not_matter():
+    b = tiny(9, Hq=2, Hkv=1, hd=8, q_lens=(6,), ctx_lens=(5,))
+    o = run(b)
+    k, v = W.gather_logical(b, 0)
+    k[8:] = bits(np.full_like(k[8:], 7.0, dtype=np.float32))   # keys 8.. are invisible to rows 0..2 (pos 5..7)
+    v[8:] = bits(np.full_like(v[8:], -9.0, dtype=np.float32))
+    W.scatter_logical(b, 0, k, v)
+    o2 = run(b)
+    assert np.array_equal(o[:3], o2[:3])
+    assert not np.array_equal(o[3], o2[3])                     # row 3 (pos 8) does see key 8
+
+
+# --------------------------------------------------------------------------- decode == prefill row, chunking
+def _same_sequence(Hq, Hkv, hd, L, splits, seed):
+    """The same L-token sequence presented as chunks [ctx, ctx+c) for each (ctx, c) in splits."""
+    rng = np.random.default_rng(seed)
+    k = bits(rng.standard_normal((L, Hkv, hd), dtype=np.float32))
+    v = bits(rng.standard_normal((L, Hkv, hd), dtype=np.float32))
+    qfull = bits(rng.standard_normal((L, Hq, hd), dtype=np.float32))
+    outs = []
+    for n, (ctx, c) in enumerate(splits):
+        b = W.build_batch(Hq=Hq, Hkv=Hkv, hd=hd, q_lens=[c], ctx_lens=[ctx], num_blocks=8, seed=seed + n)
+        W.scatter_logical(b, 0, k[: ctx + c], v[: ctx + c])
+        b.q[:] = qfull[ctx: ctx + c]
+        outs.append(run(b))
+    return outs
+
+
+def test_decode_equals_last_row_of_full_prefill():
+    full, dec = _same_sequence(4, 2, 16, 45, [(0, 45), (44, 1)], 11)
+    assert np.abs(full[-1] - dec[0]).max() <= 1e-13
+
+
+def test_chunk_rows_equal_rows_of_full_prefill():
+    full, a, b2, c = _same_sequence(4, 1, 16, 50, [(0, 50), (0, 17), (17, 20), (37, 13)], 12)
+    assert np.abs(np.concatenate([a, b2, c]) - full).max() <= 1e-13
+
+
+# --------------------------------------------------------------------------- GQA
+def test_gqa_equals_mha_with_repeated_kv_heads():
+    b = tiny(13, Hq=8, Hkv=2, hd=16, q_lens=(1, 5), ctx_lens=(21, 9))
+    o = run(b)
+    m = W.build_batch(Hq=8, Hkv=8, hd=16, q_lens=b.q_lens, ctx_lens=b.ctx_lens, num_blocks=16, seed=99)
+    m.q[:] = b.q
+    for s in range(b.num_seqs):
+        k, v = W.gather_logical(b, s)
+        W.scatter_logical(m, s, np.repeat(k, 4, axis=1), np.repeat(v, 4, axis=1))   # head h uses kv head h//4
+    assert np.abs(o - run(m)).max() <= 1e-14
+
+
+def test_kv_head_mapping_is_contiguous_groups():
+    # heads 0,1 must read kv head 0 and heads 2,3 kv head 1: make kv head 1 constant
+    b = tiny(14, Hq=4, Hkv=2, hd=8, q_lens=(1,), ctx_lens=(9,))
+    k, v = W.gather_logical(b, 0)
+    v[:, 1, :] = bits(5.0)
+    W.scatter_logical(b, 0, k, v)
+    o = run(b)
+    assert np.abs(o[0, 2:] - 5.0).max() <= 1e-14 and np.abs(o[0, :2] - 5.0).min() > 1e-3
+
+
+# --------------------------------------------------------------------------- batch structure
+def test_sequences_are_independent_and_order_permutes_rows():
+    b = tiny(15, q_lens=(1, 5, 1, 3), ctx_lens=(20, 7, 0, 31), nblk=24)
+    o = run(b)
+    order = [2, 0, 3, 1]
+    s = W.subset(b, order)
+    os_ = run(s)
+    assert np.array_equal(os_, o[s.extra["rows"]])
+    one = W.subset(b, [3])
+    assert np.array_equal(run(one), o[one.extra["rows"]])
+
+
+def test_empty_cases():
+    b = tiny(16, q_lens=(0, 1), ctx_lens=(5, 8))
+    o = run(b)
+    assert o.shape == (1, 4, 16)
+    e = W.build_batch(Hq=4, Hkv=2, hd=16, q_lens=[], ctx_lens=[], num_blocks=4, seed=0)
+    assert run(e).shape == (0, 4, 16) and run(e, ref_c.attn_mixed).shape == (0, 4, 16)
+
+
+# --------------------------------------------------------------------------- block copy
+def test_block_copy_oracles_agree_and_leave_other_blocks_alone():
+    b = tiny(17, nblk=12)
+    src = np.array([3, 7, 0, 11], np.int64)
+    dst = np.array([1, 2, 5, 4], np.int64)
+    outs = []
+    for fn in (ref_numpy.block_copy, ref_c.block_copy):
+        kd = np.full((8,) + b.k_shape()[1:], 0xABCD, np.uint16)
+        vd = np.full((8,) + b.v_shape()[1:], 0xABCD, np.uint16)
+        fn(b.k_cache, b.v_cache, kd, vd, src, dst)
+        outs.append((kd, vd))
+        for s, d in zip(src, dst):
+            assert kd[d].tobytes() == b.k_cache[s].tobytes() and vd[d].tobytes() == b.v_cache[s].tobytes()
+        for d in (0, 3, 6, 7):
+            assert (kd[d] == 0xABCD).all() and (vd[d] == 0xABCD).all()
+    assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
+
+
+# --------------------------------------------------------------------------- accounting vs Table 2
+def test_accounting_matches_table2_golden_values():
+    rows = np.loadtxt(os.path.join(GOLD, "table2_attention.txt"), dtype=np.int64)
+    for Hq, Hkv, hd, Sq, Skv, flops, nbytes in rows:
+        D_h = int(Hq * hd)
+        assert accounting.table2_flops(D_h, int(Sq), int(Skv)) == flops
+        assert accounting.table2_bytes(D_h, int(Sq), int(Skv), int(Hq), int(Hkv)) == nbytes
+        w = accounting.batch_work(int(Hq), int(Hkv), int(hd), 16, [int(Skv)], [int(Sq)])
+        assert w["flops_table2"] == flops
+        # batch_work adds only the block-table entries on top of the Table-2 bytes
+        assert w["bytes_total"] - ((int(Skv) + 15) // 16) * 4 == nbytes
+
+
+def test_causal_flops_count_visible_pairs():
+    w = accounting.batch_work(4, 1, 64, 16, [32], [32])
+    assert w["flops_causal"] == 4 * 256 * (32 * 33 // 2)       # 0.54 MFLOP for the tiny prefill chunk
+    w = accounting.batch_work(32, 8, 128, 16, [100 + 512], [512])
+    assert w["flops_causal"] == 4 * 4096 * (512 * 100 + 512 * 513 // 2)
