@@ -1,0 +1,194 @@
+#!/usr/bin/env python3
+"""Benchmark of the mixed-batch paged-attention step on ONE MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg3|cfg3-prefill|cfg4|cfg5|cfg5-prefill]
+
+A step = one pass of the whole path over one synthetic batch already resident in HBM: host
+planning (ooco_plan) + ooco_attn_mixed (prefill kernel, decode kernel, merge kernel).  Steps
+rotate over copies of the batch placed in disjoint physical blocks so that no step finds its KV
+in the 256 MB last-level cache.  Prints ONE JSON line (see the design doc for the fields).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
+
+
+def make_workload(name):
+    from paper_2511_21862_amd import workloads as W
+
+    if name == "cfg2":
+        return W.config2(device="cuda"), "decode"
+    if name == "cfg2-n01":          # same shape, N(0,1) values (outputs O(0.05) instead of O(0.002))
+        return W.config2(device="cuda", value_std=1.0), "decode"
+    if name == "cfg3":
+        return W.config3(device="cuda"), "decode"
+    if name == "cfg3-prefill":
+        return W.config3(device="cuda", n_decode=0), "prefill"
+    if name == "cfg4":
+        return W.config4(device="cuda"), "decode"
+    if name == "cfg5":
+        return W.config5(device="cuda"), "decode"
+    if name == "cfg5-prefill":
+        return W.config5(device="cuda", n_decode=0, num_blocks=4096), "prefill"
+    raise SystemExit(f"unknown workload {name}")
+
+
+def cpu_baseline(b, max_seconds=25.0):
+    """The oracle as it stands, timed on this machine's host cores on (a sample of) the same batch."""
+    from oracle import ref_c
+    from paper_2511_21862_amd import workloads as W
+
+    # ~0.6 M KV-token*rows per second on 8 cores was seen for 32 heads; bound the sample by work
+    work = b.seq_lens.astype(np.float64) * np.maximum(b.q_lens, 1) * (b.Hq / 32.0)
+    order = np.arange(b.num_seqs)
+    budget = 4.0e6
+    keep, acc = [], 0.0
+    for i in order:
+        if b.q_lens[i] == 0:
+            continue
+        w = work[i] if b.q_lens[i] == 1 else b.q_lens[i] * (b.ctx_lens[i] + b.q_lens[i] / 2.0) * (b.Hq / 32.0)
+        if keep and acc + w > budget:
+            continue
+        keep.append(int(i))
+        acc += w
+    sub = W.subset(b, keep)
+    args = (sub.q, sub.k_cache, sub.v_cache, sub.block_tables, sub.seq_lens, sub.query_start_loc, sub.ctx_lens)
+    times = []
+    threads = 0
+    t_all = time.perf_counter()
+    for _ in range(3):
+        t0 = time.perf_counter()
+        _, threads = ref_c.attn_mixed(*args, return_threads=True)
+        times.append(time.perf_counter() - t0)
+        if time.perf_counter() - t_all > max_seconds:
+            break
+    t = float(np.median(times))
+    return {
+        "value": sub.total_q / t, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+        "sample": f"{len(keep)} of {b.num_seqs} sequences ({sub.total_q} of {b.total_q} query tokens, "
+                  f"{int(sub.seq_lens.sum())} KV tokens), float64 C/OpenMP oracle, median of {len(times)} runs, "
+                  f"{t:.3f} s each",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--replan-every-step", type=int, default=1)
+    ap.add_argument("--opt", action="append", default=[], help="name=value passed to ooco_set_option")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        raise SystemExit("bench.py: this build measures one GPU only (no collectives, no sharding); run with --gpus 1")
+
+    import torch
+
+    from paper_2511_21862_amd import accounting
+    from paper_2511_21862_amd import binding as B
+    from paper_2511_21862_amd import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    b, dominant = make_workload(a.workload)
+    work = accounting.batch_work(b.Hq, b.Hkv, b.hd, b.BS, b.seq_lens, b.q_lens)
+    tables = W.replica_tables(b, 4)
+    dev = lambda x: torch.from_numpy(np.ascontiguousarray(x)).cuda()
+    bts = [dev(t) for t in tables]
+    sl, qsl, cl = dev(b.seq_lens), dev(b.query_start_loc), dev(b.ctx_lens)
+    out = torch.empty((b.total_q, b.Hq, b.hd), dtype=torch.bfloat16, device="cuda")
+    ctx = B.Context(b.Hq, b.Hkv, b.hd, b.BS, b.num_blocks, b.max_blocks_per_seq, workspace_bytes=512 << 20)
+    for o in a.opt:
+        k, v = o.split("=")
+        ctx.set_option(k, int(v))
+    stream = torch.cuda.current_stream()
+
+    def step(i):
+        if a.replan_every_step or i == 0:
+            ctx.plan(b.seq_lens, b.query_start_loc, b.ctx_lens)
+        ctx.attn_mixed(b.q, b.k_cache, b.v_cache, bts[i % len(bts)], sl, qsl, cl, out, stream)
+
+    step(0)
+    info = ctx.plan_info()
+    for i in range(a.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(a.steps):
+        step(i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / a.steps * 1e3
+
+    # per-kernel durations: the same K steps again with HIP events recorded around each kernel on
+    # the launch stream (inside the library), so that the event overhead stays out of `value`
+    ctx.set_option("profile", 1)
+    prof = {"prefill_ms": 0.0, "decode_ms": 0.0, "merge_ms": 0.0, "calls": 0}
+    done = 0
+    while done < a.steps:
+        n = min(512, a.steps - done)
+        for i in range(n):
+            step(done + i)
+        r = ctx.profile_read()
+        for k in prof:
+            prof[k] += r[k]
+        done += n
+    ctx.set_option("profile", 0)
+    kern = {k: prof[k] / max(prof["calls"], 1) for k in ("prefill_ms", "decode_ms", "merge_ms")}
+
+    if dominant == "decode":
+        alg = work["bytes_decode"]
+        dur = kern["decode_ms"] * 1e-3
+        achieved = alg / dur / 1e9 if dur > 0 else 0.0
+        roofline = {"bound": "hbm", "kernel": "decode_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                    "algorithmic_bytes_per_launch": alg, "kernel_ms": kern["decode_ms"]}
+    else:
+        alg = work["flops_causal_prefill"]
+        dur = kern["prefill_ms"] * 1e-3
+        achieved = alg / dur / 1e12 if dur > 0 else 0.0
+        roofline = {"bound": "mfma", "kernel": "prefill_kernel", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                    "algorithmic_flops_per_launch": alg, "kernel_ms": kern["prefill_ms"]}
+    traffic_file = os.path.join(ROOT, "profiles", f"traffic_{a.workload}.json")
+    if os.path.exists(traffic_file):
+        roofline["traffic"] = json.load(open(traffic_file)).get("hbm_bytes_per_launch")
+
+    line = {
+        "metric": "mixed-batch attention tokens/s + achieved HBM GB/s (% of peak), 1 MI355X",
+        "value": b.total_q / (dt / a.steps),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": b.name, "bench_name": a.workload, "num_seqs": b.num_seqs, "decode_seqs": work["decode_seqs"],
+                   "prefill_chunks": work["prefill_chunks"], "q_tokens": work["q_tokens"], "kv_tokens": work["kv_tokens"],
+                   "Hq": b.Hq, "Hkv": b.Hkv, "head_dim": b.hd, "block_size": b.BS, "replicas": len(bts),
+                   "plan": info, "replan_every_step": bool(a.replan_every_step)},
+        "hbm_gbs_whole_step": work["bytes_total"] / (dt / a.steps) / 1e9,
+        "hbm_frac_whole_step": work["bytes_total"] / (dt / a.steps) / 1e9 / HBM_PEAK_GBS,
+        "kv_tokens_per_s": work["kv_tokens"] / (dt / a.steps),
+        "tflops_causal_whole_step": work["flops_causal"] / (dt / a.steps) / 1e12,
+        "kernel_ms": kern,
+        "roofline": roofline,
+    }
+    if not a.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(b)
+    ctx.close()
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

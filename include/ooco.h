@@ -1,0 +1,183 @@
+/* ooco.h -- C ABI of the MI355X (gfx950) mixed-batch paged-attention library.
+ *
+ * The library runs the attention step of a latency-relaxed serving instance: one call covers
+ * many offline *decode* requests (one query token each, reading the request's whole KV cache)
+ * together with online *prefill chunks* (several query rows with causal attention on top of
+ * already-cached context), all over one non-contiguous ("paged") KV pool.
+ *   - mixed placement of online/offline prefill and offline decode on one instance:
+ *     paper Section 3.2.1; iteration-level batching of requests of different lengths over a
+ *     non-contiguous KV pool: Section 2.1; decode = one token per request reading the entire
+ *     KV cache, prefill = causal forward over all input tokens, GQA: Section 2.3;
+ *     attention as one fused softmax(QK^T)V operator whose scores never reach memory:
+ *     Section 3.3.1 and Table 2 (Attention row).
+ * ooco_kv_block_copy moves whole KV blocks between pools (swap-out / swap-in of the requests
+ * evicted when an online request preempts offline work, Section 3.4.1; local half of KV
+ * migration, Section 3.4.3).
+ *
+ * Everything is plain C: integers, sizes and raw pointers.  Each pointer argument is marked
+ * HOST or DEVICE.  The caller owns every buffer it passes; the library neither frees nor
+ * keeps them beyond the stream work of the call.  All entry points return an ooco_status;
+ * nothing aborts or throws across this boundary.  Calls that launch GPU work are asynchronous
+ * on the given HIP stream: inputs must stay alive and unmodified, and outputs must not be
+ * read, until the stream has passed the work of the call.
+ *
+ * ---------------------------------------------------------------------------------------
+ * Data layout (bf16 = upper 16 bits of IEEE binary32; all tensors contiguous)
+ *
+ *   q, out       [total_q_tokens][Hq][hd]
+ *   k_cache      [num_blocks][Hkv][hd/8][BS][8]
+ *                element (block b, kv head h, dim d, slot s) at
+ *                (((b*Hkv + h)*(hd/8) + d/8)*BS + s)*8 + d%8
+ *   v_cache      [num_blocks][Hkv][hd][BS]
+ *                element (b, h, d, s) at ((b*Hkv + h)*hd + d)*BS + s
+ *   block_tables int32 [num_seqs][max_blocks_per_seq]
+ *   seq_lens, ctx_lens int32 [num_seqs];  query_start_loc int32 [num_seqs+1]
+ *
+ * BS = 16 tokens per block.  Token j of sequence i is in physical block
+ * block_tables[i][j / BS], slot j % BS.  One (block, kv head) tile of K and of V is one
+ * contiguous 16*hd*2-byte run whose inner order is the operand order of the CDNA4 bf16 MFMA
+ * instructions, so that a 64-lane wave fetches it with fully contiguous 8/16-byte loads and
+ * feeds the matrix cores without any shuffle.  A block of K (all kv heads) is one contiguous
+ * Hkv*16*hd*2-byte run; the same holds for V.
+ *
+ * Semantics of one sequence i with q_len_i = query_start_loc[i+1] - query_start_loc[i]:
+ *   ctx_lens[i] = tokens cached before this step, seq_lens[i] = ctx_lens[i] + q_len_i.
+ *   Query row t (0 <= t < q_len_i) sits at position ctx_lens[i] + t and attends keys
+ *   0 .. ctx_lens[i] + t (its own key included; the K/V of this step's tokens are already in
+ *   the cache).  Query head h uses kv head h / (Hq/Hkv).  q_len_i == 1 is a decode request,
+ *   q_len_i > 1 a prefill chunk, q_len_i == 0 contributes nothing.  Cache slots past
+ *   seq_lens[i], unreferenced blocks and unused block-table columns are never used as values
+ *   (they may hold NaN/Inf or invalid ids).
+ *   out = softmax(scale * q K^T) V with fp32 accumulation, rounded to bf16 (nearest even).
+ */
+#ifndef OOCO_H
+#define OOCO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ooco_ctx ooco_ctx; /* opaque; owns only its workspace and plan buffers */
+
+typedef enum {
+    OOCO_OK = 0,
+    OOCO_EINVAL = -1,   /* bad argument value (null pointer, negative size, bad option) */
+    OOCO_ESHAPE = -2,   /* inconsistent shapes / lengths / unsupported head geometry    */
+    OOCO_ENOMEM = -3,   /* allocation failed or workspace too small                     */
+    OOCO_EHIP = -4,     /* a HIP runtime call or kernel launch failed                   */
+    OOCO_ENOTIMPL = -5
+} ooco_status;
+
+/* Creates a context for one attention-layer geometry on the current HIP device.
+ *   num_q_heads % num_kv_heads == 0, group size num_q_heads/num_kv_heads <= 16,
+ *   head_dim in {64, 128}, block_size == 16, num_blocks > 0, max_blocks_per_seq > 0.
+ *   softmax_scale <= 0 selects 1/sqrt(head_dim).
+ *   workspace: DEVICE memory for split-KV partial results, 256-byte aligned, owned by the
+ *   caller and alive until ooco_ctx_destroy; NULL lets the library allocate workspace_bytes
+ *   itself (0 = a default of 128 MiB) and free it in ooco_ctx_destroy.
+ * On failure *out is NULL and ooco_last_error(NULL) describes the reason. */
+ooco_status ooco_ctx_create(ooco_ctx **out, int num_q_heads, int num_kv_heads, int head_dim,
+                            int block_size, int64_t num_blocks, int max_blocks_per_seq,
+                            float softmax_scale, void *workspace /*DEVICE or NULL*/,
+                            size_t workspace_bytes);
+
+/* Frees the context and whatever it allocated (never the caller's buffers).  Synchronises with
+ * the work the context has enqueued.  NULL is accepted. */
+ooco_status ooco_ctx_destroy(ooco_ctx *ctx);
+
+/* Message of the last failure on this context (or, with ctx == NULL, of the calling thread's
+ * last failed ooco_ctx_create).  The string is owned by the library and valid until the next
+ * call on the same context / thread. */
+const char *ooco_last_error(const ooco_ctx *ctx);
+
+/* Tuning knobs.  Names: "decode_split_blocks" (KV blocks per decode work item; 0 = automatic
+ * balance from the batch's lengths), "decode_target_items" (automatic mode: desired number of
+ * decode work items per kv head; 0 = from the device's CU count), "force_splits" (>0: cut every
+ * decode sequence into exactly this many parts, for testing the split/merge path).
+ * These take effect at the next ooco_plan.  "profile" (0/1, immediate): when set, every
+ * ooco_attn_mixed records HIP events on its stream around its three kernels (prefill, decode,
+ * merge) for ooco_profile_read; at most 1024 calls between two reads.
+ * Unknown name -> OOCO_EINVAL. */
+ooco_status ooco_set_option(ooco_ctx *ctx, const char *name, int64_t value);
+
+/* Waits for the profiled calls made since the last read and returns the summed event-to-event
+ * times in milliseconds: ms_sum[0] = prefill kernel, [1] = decode kernel, [2] = merge kernel
+ * (HOST double[3]), and the number of calls (HOST).  Either pointer may be NULL.  Resets the sums. */
+ooco_status ooco_profile_read(ooco_ctx *ctx, double *ms_sum /*HOST*/, int64_t *calls /*HOST*/);
+
+/* Builds the work lists for one batch from HOST copies of the length arrays (the serving
+ * scheduler knows every request's length on the CPU; Section 3.3.2 / Algorithm 2 reason about
+ * them there): classifies sequences into decode / prefill, cuts decode KV ranges into balanced
+ * splits and lists prefill query tiles.  Pure host work plus the staging of the lists in pinned
+ * memory; they are uploaded on the stream of the next ooco_attn_mixed.
+ *   h_seq_lens, h_ctx_lens: HOST int32 [num_seqs]; h_query_start_loc: HOST int32 [num_seqs+1].
+ * Checks: query_start_loc starts at 0 and is non-decreasing, ctx + q_len == seq_len,
+ * 0 <= lengths, ceil(seq_len/BS) <= max_blocks_per_seq -> OOCO_ESHAPE otherwise;
+ * OOCO_ENOMEM when the workspace cannot hold the partial results of the plan. */
+ooco_status ooco_plan(ooco_ctx *ctx, int num_seqs, const int32_t *h_seq_lens /*HOST*/,
+                      const int32_t *h_query_start_loc /*HOST*/, const int32_t *h_ctx_lens /*HOST*/);
+
+/* The planner of ooco_plan as a pure HOST function (no context, no device): validates the length
+ * arrays exactly as ooco_plan does and reports the work lists it would build for the given
+ * geometry, CU count, workspace size and option values.  For schedulers that want to know the
+ * split of a batch in advance, and for testing the planner without a GPU.
+ *   decode_items_out: HOST int32 [decode_cap][6] = (seq, q_row, blk_begin, blk_end, seq_len, part)
+ *   prefill_tiles_out: HOST int32 [prefill_cap][5] = (seq, q_row0, rows, pos0, seq_len)
+ *   counts: HOST int64 [4] = (decode items, prefill tiles, merged sequences, partial results)
+ *   msg: HOST buffer of msg_cap bytes receiving the error text.  Any output pointer may be NULL. */
+ooco_status ooco_plan_dry_run(int num_q_heads, int num_kv_heads, int head_dim, int block_size,
+                              int max_blocks_per_seq, int num_cus, size_t workspace_bytes,
+                              int64_t split_blocks, int64_t target_items, int64_t force_splits,
+                              int num_seqs, const int32_t *h_seq_lens /*HOST*/,
+                              const int32_t *h_query_start_loc /*HOST*/, const int32_t *h_ctx_lens /*HOST*/,
+                              int32_t *decode_items_out /*HOST*/, int64_t decode_cap,
+                              int32_t *prefill_tiles_out /*HOST*/, int64_t prefill_cap,
+                              int64_t *counts /*HOST*/, char *msg /*HOST*/, size_t msg_cap);
+
+/* Numbers describing the current plan (any pointer may be NULL): decode work items (per kv
+ * head), prefill tiles, decode sequences that need the merge pass, bytes of workspace used. */
+ooco_status ooco_plan_info(const ooco_ctx *ctx, int64_t *decode_items, int64_t *prefill_tiles,
+                           int64_t *merged_seqs, int64_t *workspace_used);
+
+/* The mixed-batch attention step (operation defined at the top of this file).
+ *   q, out: DEVICE bf16 [total_q_tokens][Hq][hd]; k_cache, v_cache: DEVICE, read-only here;
+ *   block_tables, seq_lens, query_start_loc, ctx_lens: DEVICE int32 (shapes above).
+ *   stream: a hipStream_t (NULL = the default stream).
+ * If ooco_plan was called for this batch (same num_seqs and total_q_tokens) its work lists are
+ * used and the three DEVICE length arrays are trusted to equal the planned HOST copies.
+ * Without a current plan the call copies the length arrays to the host, waits for that copy
+ * (one stream synchronisation) and plans by itself.
+ * Writes every row of out (and the context's workspace), nothing else.  num_seqs == 0 or
+ * total_q_tokens == 0 returns OOCO_OK without launching anything.
+ * Same context + same plan + same inputs give bit-identical output on every call (no
+ * floating-point atomics).  One context serves one stream at a time.
+ * Errors: OOCO_EINVAL for null pointers / negative sizes, OOCO_ESHAPE when sizes contradict
+ * the plan, OOCO_EHIP when a launch fails (message holds hipGetErrorString). */
+ooco_status ooco_attn_mixed(ooco_ctx *ctx, const void *q /*DEVICE*/, const void *k_cache /*DEVICE*/,
+                            const void *v_cache /*DEVICE*/, const int32_t *block_tables /*DEVICE*/,
+                            const int32_t *seq_lens /*DEVICE*/, const int32_t *query_start_loc /*DEVICE*/,
+                            const int32_t *ctx_lens /*DEVICE*/, void *out /*DEVICE*/, int num_seqs,
+                            int total_q_tokens, void *stream);
+
+/* Whole-block copy for preemption eviction / restore:
+ *   for p in [0, num_pairs):  k_dst[dst_block_ids[p]] <- k_src[src_block_ids[p]]  (one block =
+ *   Hkv*BS*hd bf16, all slots, garbage tail included) and the same for V.  Bit-exact.
+ *   k_src, v_src, k_dst, v_dst: DEVICE pools with the cache layout of this context (the
+ *   destination pool may be smaller or the same allocation as the source);
+ *   src_block_ids, dst_block_ids: DEVICE int64 [num_pairs].
+ * dst ids must be pairwise distinct, and when source and destination are the same allocation
+ * no dst id may equal any src id; neither is checked (ids live on the device) and violating
+ * it gives unspecified block contents.  Ids must lie inside their pools (unchecked).
+ * num_pairs == 0 returns OOCO_OK without a launch.  ctx supplies the block geometry. */
+ooco_status ooco_kv_block_copy(ooco_ctx *ctx, const void *k_src /*DEVICE*/, const void *v_src /*DEVICE*/,
+                               void *k_dst /*DEVICE*/, void *v_dst /*DEVICE*/,
+                               const int64_t *src_block_ids /*DEVICE*/,
+                               const int64_t *dst_block_ids /*DEVICE*/, int64_t num_pairs, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OOCO_H */

@@ -1,0 +1,218 @@
+"""Thin ctypes binding over libooco.so: argument marshalling only.
+
+Function names equal the C entry points of include/ooco.h.  Device arguments are torch
+tensors (used purely as device allocations: `.data_ptr()`), host arguments numpy int32 arrays.
+Importing this module fails when the HIP library has not been built -- there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libooco.so")
+
+OOCO_OK, OOCO_EINVAL, OOCO_ESHAPE, OOCO_ENOMEM, OOCO_EHIP, OOCO_ENOTIMPL = 0, -1, -2, -3, -4, -5
+_STATUS_NAMES = {0: "OOCO_OK", -1: "OOCO_EINVAL", -2: "OOCO_ESHAPE", -3: "OOCO_ENOMEM", -4: "OOCO_EHIP",
+                 -5: "OOCO_ENOTIMPL"}
+
+EXPORTS = ["ooco_ctx_create", "ooco_ctx_destroy", "ooco_last_error", "ooco_set_option", "ooco_plan",
+           "ooco_plan_dry_run", "ooco_plan_info", "ooco_profile_read", "ooco_attn_mixed", "ooco_kv_block_copy"]
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2511_21862_amd.build` "
+                      "(the HIP library is the only implementation; there is no fallback)")
+
+_lib = ctypes.CDLL(LIB_PATH)
+_P = ctypes.c_void_p
+_lib.ooco_ctx_create.restype = ctypes.c_int
+_lib.ooco_ctx_create.argtypes = [ctypes.POINTER(_P), ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                 ctypes.c_int64, ctypes.c_int, ctypes.c_float, _P, ctypes.c_size_t]
+_lib.ooco_ctx_destroy.restype = ctypes.c_int
+_lib.ooco_ctx_destroy.argtypes = [_P]
+_lib.ooco_last_error.restype = ctypes.c_char_p
+_lib.ooco_last_error.argtypes = [_P]
+_lib.ooco_set_option.restype = ctypes.c_int
+_lib.ooco_set_option.argtypes = [_P, ctypes.c_char_p, ctypes.c_int64]
+_lib.ooco_plan.restype = ctypes.c_int
+_lib.ooco_plan.argtypes = [_P, ctypes.c_int, _P, _P, _P]
+_lib.ooco_plan_dry_run.restype = ctypes.c_int
+_lib.ooco_plan_dry_run.argtypes = ([ctypes.c_int] * 6 + [ctypes.c_size_t] + [ctypes.c_int64] * 3 + [ctypes.c_int, _P, _P, _P]
+                                   + [_P, ctypes.c_int64, _P, ctypes.c_int64, _P, ctypes.c_char_p, ctypes.c_size_t])
+_lib.ooco_plan_info.restype = ctypes.c_int
+_lib.ooco_plan_info.argtypes = [_P] + [ctypes.POINTER(ctypes.c_int64)] * 4
+_lib.ooco_profile_read.restype = ctypes.c_int
+_lib.ooco_profile_read.argtypes = [_P, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
+_lib.ooco_attn_mixed.restype = ctypes.c_int
+_lib.ooco_attn_mixed.argtypes = [_P] * 9 + [ctypes.c_int, ctypes.c_int, _P]
+_lib.ooco_kv_block_copy.restype = ctypes.c_int
+_lib.ooco_kv_block_copy.argtypes = [_P] * 7 + [ctypes.c_int64, _P]
+
+
+class OocoError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{_STATUS_NAMES.get(status, status)}: {message}")
+        self.status = status
+        self.message = message
+
+
+def _dev(t) -> int:
+    """Device pointer of a torch tensor (None -> NULL)."""
+    if t is None:
+        return 0
+    if isinstance(t, int):
+        return t
+    if not t.is_contiguous():
+        raise ValueError("tensors passed to libooco must be contiguous")
+    return t.data_ptr()
+
+
+def _host_i32(a):
+    if a is None:
+        return None, 0
+    arr = np.ascontiguousarray(a, dtype=np.int32)
+    return arr, arr.ctypes.data
+
+
+def _stream_handle(stream) -> int:
+    if stream is None:
+        import torch
+
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def ooco_last_error(ctx) -> str:
+    s = _lib.ooco_last_error(ctx)
+    return s.decode() if s else ""
+
+
+def _check(ctx, status: int):
+    if status != OOCO_OK:
+        raise OocoError(status, ooco_last_error(ctx))
+
+
+def ooco_ctx_create(num_q_heads, num_kv_heads, head_dim, block_size, num_blocks, max_blocks_per_seq,
+                    softmax_scale=0.0, workspace=None, workspace_bytes=0):
+    h = _P()
+    st = _lib.ooco_ctx_create(ctypes.byref(h), num_q_heads, num_kv_heads, head_dim, block_size, num_blocks,
+                              max_blocks_per_seq, softmax_scale, _dev(workspace), workspace_bytes)
+    _check(None, st)
+    return h
+
+
+def ooco_ctx_destroy(ctx) -> None:
+    _check(None, _lib.ooco_ctx_destroy(ctx))
+
+
+def ooco_set_option(ctx, name: str, value: int) -> None:
+    _check(ctx, _lib.ooco_set_option(ctx, name.encode() if name is not None else None, value))
+
+
+def ooco_plan(ctx, num_seqs, h_seq_lens, h_query_start_loc, h_ctx_lens) -> None:
+    a, pa = _host_i32(h_seq_lens)
+    b, pb = _host_i32(h_query_start_loc)
+    c, pc = _host_i32(h_ctx_lens)
+    _check(ctx, _lib.ooco_plan(ctx, num_seqs, pa, pb, pc))
+
+
+def ooco_plan_dry_run(num_q_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, num_cus, workspace_bytes,
+                      h_seq_lens, h_query_start_loc, h_ctx_lens, split_blocks=0, target_items=0, force_splits=0,
+                      num_seqs=None) -> dict:
+    """Host-only planner run; returns the work lists as numpy arrays."""
+    a, pa = _host_i32(h_seq_lens)
+    b, pb = _host_i32(h_query_start_loc)
+    c, pc = _host_i32(h_ctx_lens)
+    n = len(a) if num_seqs is None else num_seqs
+    counts = np.zeros(4, dtype=np.int64)
+    msg = ctypes.create_string_buffer(512)
+
+    def call(dptr, dcap, pptr, pcap):
+        return _lib.ooco_plan_dry_run(num_q_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, num_cus,
+                                      workspace_bytes, split_blocks, target_items, force_splits, n, pa, pb, pc, dptr,
+                                      dcap, pptr, pcap, counts.ctypes.data, msg, 512)
+
+    st = call(0, 0, 0, 0)
+    if st != OOCO_OK:
+        raise OocoError(st, msg.value.decode())
+    d = np.zeros((int(counts[0]), 6), dtype=np.int32)
+    p = np.zeros((int(counts[1]), 5), dtype=np.int32)
+    st = call(d.ctypes.data, len(d), p.ctypes.data, len(p))
+    if st != OOCO_OK:
+        raise OocoError(st, msg.value.decode())
+    return dict(decode_items=d, prefill_tiles=p, merged_seqs=int(counts[2]), parts=int(counts[3]))
+
+
+def ooco_plan_info(ctx) -> dict:
+    v = [ctypes.c_int64() for _ in range(4)]
+    _check(ctx, _lib.ooco_plan_info(ctx, *[ctypes.byref(x) for x in v]))
+    return dict(decode_items=v[0].value, prefill_tiles=v[1].value, merged_seqs=v[2].value,
+                workspace_used=v[3].value)
+
+
+def ooco_profile_read(ctx) -> dict:
+    ms = (ctypes.c_double * 3)()
+    n = ctypes.c_int64()
+    _check(ctx, _lib.ooco_profile_read(ctx, ms, ctypes.byref(n)))
+    return dict(prefill_ms=ms[0], decode_ms=ms[1], merge_ms=ms[2], calls=n.value)
+
+
+def ooco_attn_mixed(ctx, q, k_cache, v_cache, block_tables, seq_lens, query_start_loc, ctx_lens, out, num_seqs,
+                    total_q_tokens, stream=None) -> None:
+    _check(ctx, _lib.ooco_attn_mixed(ctx, _dev(q), _dev(k_cache), _dev(v_cache), _dev(block_tables), _dev(seq_lens),
+                                     _dev(query_start_loc), _dev(ctx_lens), _dev(out), num_seqs, total_q_tokens,
+                                     _stream_handle(stream)))
+
+
+def ooco_kv_block_copy(ctx, k_src, v_src, k_dst, v_dst, src_block_ids, dst_block_ids, num_pairs, stream=None) -> None:
+    _check(ctx, _lib.ooco_kv_block_copy(ctx, _dev(k_src), _dev(v_src), _dev(k_dst), _dev(v_dst), _dev(src_block_ids),
+                                        _dev(dst_block_ids), num_pairs, _stream_handle(stream)))
+
+
+class Context:
+    """RAII holder of one ooco_ctx (no arithmetic here either)."""
+
+    def __init__(self, Hq, Hkv, hd, BS, num_blocks, max_blocks_per_seq, scale=0.0, workspace=None,
+                 workspace_bytes=0):
+        self.h = ooco_ctx_create(Hq, Hkv, hd, BS, num_blocks, max_blocks_per_seq, scale, workspace, workspace_bytes)
+        self._workspace = workspace
+
+    def close(self):
+        if self.h is not None:
+            ooco_ctx_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *a):
+        self.close()
+
+    def set_option(self, name, value):
+        ooco_set_option(self.h, name, value)
+
+    def plan(self, seq_lens, query_start_loc, ctx_lens):
+        ooco_plan(self.h, len(seq_lens), seq_lens, query_start_loc, ctx_lens)
+
+    def plan_info(self):
+        return ooco_plan_info(self.h)
+
+    def profile_read(self):
+        return ooco_profile_read(self.h)
+
+    def attn_mixed(self, q, k_cache, v_cache, block_tables, seq_lens, query_start_loc, ctx_lens, out, stream=None):
+        ooco_attn_mixed(self.h, q, k_cache, v_cache, block_tables, seq_lens, query_start_loc, ctx_lens, out,
+                        int(seq_lens.shape[0]), int(q.shape[0]), stream)
+
+    def kv_block_copy(self, k_src, v_src, k_dst, v_dst, src_ids, dst_ids, stream=None):
+        ooco_kv_block_copy(self.h, k_src, v_src, k_dst, v_dst, src_ids, dst_ids, int(src_ids.shape[0]), stream)

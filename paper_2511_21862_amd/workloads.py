@@ -197,7 +197,25 @@ def build_batch(
 
     return Batch(Hq=Hq, Hkv=Hkv, hd=hd, BS=BS, num_blocks=num_blocks, block_tables=block_tables,
                  seq_lens=seq_lens, ctx_lens=ctx_lens.astype(np.int32), query_start_loc=qsl,
-                 q=q, k_cache=k, v_cache=v, name=name)
+                 q=q, k_cache=k, v_cache=v, name=name, extra={"free_list": free, "free_pos": pos})
+
+
+def replica_tables(b: Batch, max_replicas: int) -> list:
+    """Block tables for further copies of the same batch (same lengths) dealt from the blocks the
+    shuffled free list still holds, so that successive timed steps touch disjoint physical
+    blocks of the pool (every block of a generated pool holds random values)."""
+    free, pos = b.extra["free_list"], int(b.extra["free_pos"])
+    nb = _blocks_needed(b.seq_lens, b.BS)
+    need = int(nb.sum())
+    tables = [b.block_tables]
+    while len(tables) < max_replicas and pos + need <= len(free):
+        bt = np.full_like(b.block_tables, -1)
+        for i in range(b.num_seqs):
+            n = int(nb[i])
+            bt[i, :n] = free[pos:pos + n]
+            pos += n
+        tables.append(bt)
+    return tables
 
 
 # ----------------------------------------------------------------------------- data movement helpers

@@ -1,0 +1,150 @@
+"""GPU parity: libooco (through the C ABI) against the float64 CPU oracle, element by element,
+on seeded inputs.  Gates: max-abs <= 2e-2, mean-abs <= 2e-3, relative L2 <= 1e-2; block copy and
+run-to-run determinism bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ref_c, ref_numpy
+from paper_2511_21862_amd import binding as B
+from paper_2511_21862_amd import workloads as W
+
+from gpu_util import assert_parity, device_meta, errors, run_gpu, say
+
+pytestmark = pytest.mark.gpu
+
+
+def oracle(b, fn=ref_c.attn_mixed, **kw):
+    return fn(b.q, b.k_cache, b.v_cache, b.block_tables, b.seq_lens, b.query_start_loc, b.ctx_lens, **kw)
+
+
+def test_config1_tiny_mixed_poisoned():
+    b = W.config1(poison=True)
+    say("case: config1 poisoned, numpy oracle")
+    ref = oracle(b, ref_numpy.attn_mixed)
+    assert_parity(run_gpu(b), ref, "config1")
+    say("case: config1 without host plan")
+    assert_parity(run_gpu(b, plan=False), ref, "config1 plan-less")
+
+
+RAGGED = [
+    # Hq, Hkv, hd, q_lens, ctx_lens
+    (4, 1, 64, [1, 1, 1, 1], [0, 15, 16, 300]),
+    (8, 2, 128, [1, 1, 1], [31, 32, 1000]),
+    (32, 8, 128, [1] * 6, [5, 511, 512, 513, 2047, 77]),
+    (64, 8, 128, [1, 1], [1500, 33]),
+    (28, 4, 128, [1, 1, 7], [700, 64, 20]),                       # group of 7 (non power of two)
+    (16, 1, 64, [1, 40], [129, 3]),                                # group of 16
+    (4, 4, 64, [1, 33], [200, 0]),                                 # MHA
+    (8, 2, 128, [2, 31, 32, 33, 65], [0, 5, 16, 100, 47]),         # ragged chunks, tiles with tails
+    (32, 8, 128, [128, 1, 96, 1], [0, 400, 333, 64]),              # mixed
+    (4, 1, 64, [0, 1, 0, 5], [4, 4, 0, 0]),                        # empty sequences inside the batch
+]
+
+
+@pytest.mark.parametrize("case", range(len(RAGGED)))
+def test_ragged_cases(case):
+    Hq, Hkv, hd, ql, ctx = RAGGED[case]
+    nblk = int(sum((c + q + 15) // 16 for c, q in zip(ctx, ql))) + 7
+    b = W.build_batch(Hq=Hq, Hkv=Hkv, hd=hd, q_lens=ql, ctx_lens=ctx, num_blocks=nblk, seed=1000 + case, poison=True)
+    say(f"case: ragged {case}: Hq={Hq} Hkv={Hkv} hd={hd} q_lens={ql} ctx={ctx}")
+    assert_parity(run_gpu(b), oracle(b), f"ragged {case}")
+
+
+@pytest.mark.parametrize("splits", [1, 2, 7, 10 ** 6])
+def test_forced_split_counts_agree(splits):
+    b = W.build_batch(Hq=32, Hkv=8, hd=128, q_lens=[1, 1, 1], ctx_lens=[2000, 130, 15], num_blocks=160, seed=77,
+                      poison=True)
+    say(f"case: forced splits {splits}")
+    ref = oracle(b)
+    assert_parity(run_gpu(b, options={"force_splits": splits}), ref, f"splits={splits}")
+
+
+def test_peaky_scores_give_order_one_outputs():
+    # scores x8: softmax concentrates on few keys, outputs are O(1) and the relative gate bites
+    b = W.build_batch(Hq=32, Hkv=8, hd=128, q_lens=[1, 1, 64], ctx_lens=[900, 3000, 500], num_blocks=300, seed=5,
+                      poison=True)
+    scale = 8.0 / np.sqrt(128.0)
+    say("case: peaky scale")
+    ref = oracle(b, scale=scale)
+    e = assert_parity(run_gpu(b, scale=scale), ref, "peaky")
+    assert np.abs(ref).mean() > 0.2
+
+
+def test_small_value_data_passes_relative_gate():
+    # N(0,1)/sqrt(128) data: outputs ~2e-3, an all-zero answer would pass the absolute gates
+    b = W.build_batch(Hq=32, Hkv=8, hd=128, q_lens=[1, 1], ctx_lens=[2047, 700], num_blocks=200, seed=6,
+                      value_std=1 / np.sqrt(128.0))
+    say("case: small values")
+    assert_parity(run_gpu(b), oracle(b), "small values")
+
+
+def test_run_to_run_and_block_permutation_determinism():
+    b = W.build_batch(Hq=32, Hkv=8, hd=128, q_lens=[1, 1, 48], ctx_lens=[3000, 100, 70], num_blocks=256, seed=8)
+    say("case: determinism")
+    o1 = run_gpu(b, options={"decode_split_blocks": 16})
+    o2 = run_gpu(b, options={"decode_split_blocks": 16})
+    assert np.array_equal(o1, o2)
+    o3 = run_gpu(W.permute_blocks(b, 3), options={"decode_split_blocks": 16})
+    assert np.array_equal(o1, o3)
+
+
+def test_block_copy_bit_exact_round_trip():
+    b = W.build_batch(Hq=32, Hkv=8, hd=128, q_lens=[1, 1, 1], ctx_lens=[500, 90, 1300], num_blocks=300, seed=9)
+    say("case: block copy")
+    d = W.to_device(b)
+    victims = [0, 2]
+    src = W.victim_block_ids(b, victims)
+    rng = np.random.default_rng(0)
+    n = len(src)
+    stage_blocks = n + 5
+    dst = rng.permutation(stage_blocks)[:n].astype(np.int64)
+    ks = torch.full((stage_blocks,) + tuple(d.k_cache.shape[1:]), -7.0, dtype=torch.bfloat16, device="cuda")
+    vs = torch.full((stage_blocks,) + tuple(d.v_cache.shape[1:]), -7.0, dtype=torch.bfloat16, device="cuda")
+    with B.Context(b.Hq, b.Hkv, b.hd, b.BS, b.num_blocks, b.max_blocks_per_seq) as ctx:
+        ctx.kv_block_copy(d.k_cache, d.v_cache, ks, vs, torch.from_numpy(src).cuda(), torch.from_numpy(dst).cuda())
+        torch.cuda.synchronize()
+        # oracle copy on the host
+        kh = np.full(ks.shape, W.f32_to_bf16_bits(np.float32([-7.0]))[0], np.uint16)
+        vh = kh.reshape(-1)[: vs.numel()].reshape(vs.shape).copy()
+        ref_c.block_copy(b.k_cache, b.v_cache, kh, vh, src, dst)
+        assert np.array_equal(ks.view(torch.int16).cpu().numpy().view(np.uint16), kh)
+        assert np.array_equal(vs.view(torch.int16).cpu().numpy().view(np.uint16), vh)
+        # restore into fresh ids of the main pool and check attention is unchanged bit for bit
+        before = run_gpu(b, ctx=ctx)
+        used = set(int(x) for x in b.block_tables[b.block_tables >= 0])
+        fresh = np.array([i for i in range(b.num_blocks) if i not in used][:n], np.int64)
+        assert len(fresh) == n
+        ctx.kv_block_copy(ks, vs, d.k_cache, d.v_cache, torch.from_numpy(dst).cuda(), torch.from_numpy(fresh).cuda())
+        torch.cuda.synchronize()
+        b2 = W.to_host(d)
+        bt = b.block_tables.copy()
+        pos = 0
+        for s in victims:
+            nb = (int(b.seq_lens[s]) + 15) // 16
+            bt[s, :nb] = fresh[pos:pos + nb]
+            pos += nb
+        b2.block_tables = bt
+        after = run_gpu(b2, ctx=ctx)
+        assert np.array_equal(before, after)
+        # zero pairs: no launch, no error
+        ctx.kv_block_copy(ks, vs, d.k_cache, d.v_cache, torch.zeros(0, dtype=torch.int64, device="cuda"),
+                          torch.zeros(0, dtype=torch.int64, device="cuda"))
+
+
+def test_errors_surface_through_the_abi():
+    b = W.config1()
+    d = W.to_device(b)
+    bt, sl, qsl, cl = device_meta(b)
+    out = torch.empty((b.total_q, b.Hq, b.hd), dtype=torch.bfloat16, device="cuda")
+    with B.Context(b.Hq, b.Hkv, b.hd, b.BS, b.num_blocks, b.max_blocks_per_seq) as ctx:
+        with pytest.raises(B.OocoError) as e:
+            B.ooco_attn_mixed(ctx.h, None, d.k_cache, d.v_cache, bt, sl, qsl, cl, out, b.num_seqs, b.total_q)
+        assert e.value.status == B.OOCO_EINVAL
+        ctx.plan(b.seq_lens, b.query_start_loc, b.ctx_lens)
+        with pytest.raises(B.OocoError) as e:
+            B.ooco_attn_mixed(ctx.h, d.q, d.k_cache, d.v_cache, bt, sl, qsl, cl, out, b.num_seqs - 1, b.total_q)
+        assert e.value.status == B.OOCO_ESHAPE
+        with pytest.raises(B.OocoError):
+            ctx.set_option("no_such_option", 1)
+        B.ooco_attn_mixed(ctx.h, d.q, d.k_cache, d.v_cache, bt, sl, qsl, cl, out, 0, 0)     # empty: OK

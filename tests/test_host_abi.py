@@ -1,0 +1,133 @@
+"""Host-side checks that need no GPU: the library loads, exports every declared symbol, and the
+planner validates lengths and covers every KV block / query row exactly once."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2511_21862_amd import binding as B
+from paper_2511_21862_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "ooco.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ooco_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = ctypes.CDLL(B.LIB_PATH)
+    names = declared_symbols()
+    assert set(names) == set(B.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_ctx_create_rejects_bad_geometry_before_touching_a_device():
+    bad = [
+        dict(num_q_heads=32, num_kv_heads=7), dict(num_q_heads=0), dict(num_q_heads=64, num_kv_heads=2),
+        dict(head_dim=96), dict(block_size=32), dict(num_blocks=0), dict(max_blocks_per_seq=0),
+    ]
+    base = dict(num_q_heads=32, num_kv_heads=8, head_dim=128, block_size=16, num_blocks=64, max_blocks_per_seq=8)
+    for kw in bad:
+        with pytest.raises(B.OocoError) as e:
+            B.ooco_ctx_create(**{**base, **kw})
+        assert e.value.status in (B.OOCO_ESHAPE, B.OOCO_EINVAL)
+        assert "ooco_ctx_create" in e.value.message
+
+
+def dry(seq, qsl, ctx, **kw):
+    args = dict(num_q_heads=32, num_kv_heads=8, head_dim=128, block_size=16, max_blocks_per_seq=8192, num_cus=256,
+                workspace_bytes=128 << 20)
+    args.update(kw)
+    return B.ooco_plan_dry_run(h_seq_lens=seq, h_query_start_loc=qsl, h_ctx_lens=ctx, **args)
+
+
+@pytest.mark.parametrize("seq,qsl,ctx,frag", [
+    ([10, 5], [1, 2, 3], [9, 4], "query_start_loc[0]"),
+    ([10, 5], [0, 2, 1], [8, 6], "decreases"),
+    ([10, 5], [0, 1, 2], [9, 3], "!= seq_len"),
+    ([10, -1], [0, 1, 1], [9, -1], "negative"),
+    ([10, 16 * 8192 + 1], [0, 1, 2], [9, 16 * 8192], "max_blocks_per_seq"),
+])
+def test_plan_rejects_inconsistent_lengths(seq, qsl, ctx, frag):
+    with pytest.raises(B.OocoError) as e:
+        dry(seq, qsl, ctx)
+    assert e.value.status == B.OOCO_ESHAPE and frag in e.value.message
+
+
+def test_plan_reports_workspace_too_small_for_forced_splits():
+    with pytest.raises(B.OocoError) as e:
+        dry([4096], [0, 1], [4095], force_splits=64, workspace_bytes=1024)
+    assert e.value.status == B.OOCO_ENOMEM
+
+
+def check_cover(b, plan):
+    d, p = plan["decode_items"], plan["prefill_tiles"]
+    nb = (b.seq_lens.astype(np.int64) + 15) // 16
+    ql = b.q_lens
+    for i in range(b.num_seqs):
+        rows = d[d[:, 0] == i]
+        if ql[i] == 1:
+            rows = rows[np.argsort(rows[:, 2])]
+            assert rows[0, 2] == 0 and rows[-1, 3] == nb[i]
+            assert (rows[1:, 2] == rows[:-1, 3]).all() and (rows[:, 3] > rows[:, 2]).all()
+            assert (rows[:, 1] == b.query_start_loc[i]).all() and (rows[:, 4] == b.seq_lens[i]).all()
+            assert (rows[:, 5] >= 0).all() if len(rows) > 1 else rows[0, 5] == -1
+        else:
+            assert len(rows) == 0
+        t = p[p[:, 0] == i]
+        if ql[i] > 1:
+            t = t[np.argsort(t[:, 1])]
+            assert t[0, 1] == b.query_start_loc[i] and (t[:, 2].sum() == ql[i])
+            assert (t[1:, 1] == t[:-1, 1] + t[:-1, 2]).all()
+            assert (t[:, 3] == b.ctx_lens[i] + (t[:, 1] - b.query_start_loc[i])).all()
+        else:
+            assert len(t) == 0
+    parts = np.sort(d[d[:, 5] >= 0][:, 5])
+    assert (parts == np.arange(len(parts))).all() and len(parts) == plan["parts"]
+
+
+def meta_only(fn, **kw):
+    """Lengths of a configuration without materialising its multi-GiB pools."""
+    import unittest.mock as m
+
+    def fake(**a):
+        ql = np.asarray(a["q_lens"], np.int32)
+        cx = np.asarray(a["ctx_lens"], np.int32)
+        qsl = np.zeros(len(ql) + 1, np.int32)
+        qsl[1:] = np.cumsum(ql)
+        return W.Batch(Hq=a["Hq"], Hkv=a["Hkv"], hd=a["hd"], BS=16, num_blocks=a["num_blocks"],
+                       block_tables=np.zeros((len(ql), 1), np.int32), seq_lens=cx + ql, ctx_lens=cx,
+                       query_start_loc=qsl, q=None, k_cache=None, v_cache=None)
+
+    with m.patch.object(W, "build_batch", side_effect=fake):
+        return fn(**kw)
+
+
+@pytest.mark.parametrize("cfg", ["config1", "config2", "config3", "config4", "config5"])
+def test_plan_covers_every_block_and_row_once(cfg):
+    b = meta_only(getattr(W, cfg))
+    for kw in (dict(), dict(force_splits=3), dict(split_blocks=5), dict(target_items=7)):
+        plan = dry(b.seq_lens, b.query_start_loc, b.ctx_lens, num_q_heads=b.Hq, num_kv_heads=b.Hkv, head_dim=b.hd,
+                   workspace_bytes=1 << 30, **kw)
+        check_cover(b, plan)
+
+
+def test_plan_is_longest_first_and_balanced():
+    b = meta_only(W.config4)
+    d = dry(b.seq_lens, b.query_start_loc, b.ctx_lens)["decode_items"]
+    sizes = d[:, 3] - d[:, 2]
+    assert (np.diff(sizes) <= 0).all()
+    # items of split sequences differ by at most a factor 2 from the quantum
+    split = sizes[d[:, 5] >= 0]
+    assert split.max() <= 2 * split.min() + 1
+
+
+def test_empty_batch_plans_to_nothing():
+    plan = dry(np.zeros(0, np.int32), np.zeros(1, np.int32), np.zeros(0, np.int32), num_seqs=0)
+    assert len(plan["decode_items"]) == 0 and len(plan["prefill_tiles"]) == 0
