@@ -4,7 +4,7 @@
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg3|cfg3-prefill|cfg4|cfg5|cfg5-prefill]
 
 A step = one pass of the whole path over one synthetic batch already resident in HBM: host
-planning (ooco_plan) + ooco_attn_mixed (prefill kernel, decode kernel, merge kernel).  Steps
+planning (ooco_plan) + ooco_attn_mixed (prefill kernel, decode kernel with its in-kernel merge).  Steps
 rotate over copies of the batch placed in disjoint physical blocks so that no step finds its KV
 in the 256 MB last-level cache.  Prints ONE JSON line (see the design doc for the fields).
 """
@@ -135,7 +135,7 @@ def main():
     # per-kernel durations: the same K steps again with HIP events recorded around each kernel on
     # the launch stream (inside the library), so that the event overhead stays out of `value`
     ctx.set_option("profile", 1)
-    prof = {"prefill_ms": 0.0, "decode_ms": 0.0, "merge_ms": 0.0, "calls": 0}
+    prof = {"prefill_ms": 0.0, "decode_ms": 0.0, "calls": 0}
     done = 0
     while done < a.steps:
         n = min(512, a.steps - done)
@@ -146,7 +146,7 @@ def main():
             prof[k] += r[k]
         done += n
     ctx.set_option("profile", 0)
-    kern = {k: prof[k] / max(prof["calls"], 1) for k in ("prefill_ms", "decode_ms", "merge_ms")}
+    kern = {k: prof[k] / max(prof["calls"], 1) for k in ("prefill_ms", "decode_ms")}
 
     if dominant == "decode":
         alg = work["bytes_decode"]

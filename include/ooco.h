@@ -93,54 +93,72 @@ ooco_status ooco_ctx_destroy(ooco_ctx *ctx);
  * call on the same context / thread. */
 const char *ooco_last_error(const ooco_ctx *ctx);
 
-/* Tuning knobs.  Names: "decode_split_blocks" (KV blocks per decode work item; 0 = automatic
- * balance from the batch's lengths), "decode_target_items" (automatic mode: desired number of
- * decode work items per kv head; 0 = from the device's CU count), "force_splits" (>0: cut every
- * decode sequence into exactly this many parts, for testing the split/merge path).
- * These take effect at the next ooco_plan.  "profile" (0/1, immediate): when set, every
- * ooco_attn_mixed records HIP events on its stream around its three kernels (prefill, decode,
- * merge) for ooco_profile_read; at most 1024 calls between two reads.
+/* Options.  The KV blocks of all decode sequences, laid end to end, are streamed in runs: the
+ * first part of that line is cut into "decode_segments" equal runs, one launched wave per run and
+ * kv head (0 = automatic, from the device's CU count and the batch size); the last
+ * "decode_tail_pct" percent (default 15; 0 = none) are cut into short runs of
+ * "decode_tail_blocks" KV blocks (default 8) which the waves fetch dynamically once their own run
+ * is done, evening out speed differences between compute units.  A run that crosses a sequence
+ * boundary, or a sequence that spans several runs, is handled by partial results merged inside
+ * the decode kernel.  These three take effect at the next ooco_plan.  "profile" (0/1, immediate): when set, every ooco_attn_mixed records HIP events
+ * on its stream around its two kernels (prefill, decode) for ooco_profile_read; at most 1024
+ * calls between two reads.  "trace" (0/1, immediate): see ooco_trace_read.  "decode_nbi" (1, 2 or
+ * 4, immediate): KV blocks per softmax step of the decode kernel (0 = default).
  * Unknown name -> OOCO_EINVAL. */
 ooco_status ooco_set_option(ooco_ctx *ctx, const char *name, int64_t value);
 
 /* Waits for the profiled calls made since the last read and returns the summed event-to-event
- * times in milliseconds: ms_sum[0] = prefill kernel, [1] = decode kernel, [2] = merge kernel
- * (HOST double[3]), and the number of calls (HOST).  Either pointer may be NULL.  Resets the sums. */
+ * times in milliseconds: ms_sum[0] = prefill kernel, ms_sum[1] = decode kernel (HOST double[2]),
+ * and the number of calls (HOST).  Either pointer may be NULL.  Resets the sums. */
 ooco_status ooco_profile_read(ooco_ctx *ctx, double *ms_sum /*HOST*/, int64_t *calls /*HOST*/);
 
-/* Builds the work lists for one batch from HOST copies of the length arrays (the serving
- * scheduler knows every request's length on the CPU; Section 3.3.2 / Algorithm 2 reason about
- * them there): classifies sequences into decode / prefill, cuts decode KV ranges into balanced
- * splits and lists prefill query tiles.  Pure host work plus the staging of the lists in pinned
- * memory; they are uploaded on the stream of the next ooco_attn_mixed.
+/* Wave-level trace of the decode kernel, for tuning.  With option "trace" = 1 every decode wave of
+ * the following ooco_attn_mixed calls stores four device time stamps (constant 100 MHz clock):
+ * wave start, first K/V tiles arrived, end of KV streaming, wave end (after partial results and
+ * merge).  ooco_trace_read synchronises the device and copies the stamps of the last traced call:
+ *   stamps: HOST uint64 [cap_waves][4], wave index = run * num_kv_heads + kv head;
+ *   waves: HOST, receives the number of decode waves of that call.
+ * Tracing adds waits to the kernel; never leave it on when measuring throughput. */
+ooco_status ooco_trace_read(ooco_ctx *ctx, uint64_t *stamps /*HOST*/, int64_t cap_waves, int64_t *waves /*HOST*/);
+
+/* Plans one batch from HOST copies of the length arrays (the serving scheduler knows every
+ * request's length on the CPU; Section 3.3.2 / Algorithm 2 reason about them there): classifies
+ * sequences into decode (q_len 1) and prefill (q_len > 1), sums their KV blocks and query tiles
+ * into two small cumulative arrays and picks the number of decode runs.  Pure host work, no
+ * device call: the arrays travel to the GPU inside the kernel arguments of the next
+ * ooco_attn_mixed (batches above 960 sequences: one small asynchronous copy on its stream).
  *   h_seq_lens, h_ctx_lens: HOST int32 [num_seqs]; h_query_start_loc: HOST int32 [num_seqs+1].
  * Checks: query_start_loc starts at 0 and is non-decreasing, ctx + q_len == seq_len,
  * 0 <= lengths, ceil(seq_len/BS) <= max_blocks_per_seq -> OOCO_ESHAPE otherwise;
- * OOCO_ENOMEM when the workspace cannot hold the partial results of the plan. */
+ * OOCO_ENOMEM when the batch exceeds the context's fixed buffers (2^20 / num_kv_heads sequences).
+ * A workspace too small for the wanted number of runs silently lowers that number. */
 ooco_status ooco_plan(ooco_ctx *ctx, int num_seqs, const int32_t *h_seq_lens /*HOST*/,
                       const int32_t *h_query_start_loc /*HOST*/, const int32_t *h_ctx_lens /*HOST*/);
 
 /* The planner of ooco_plan as a pure HOST function (no context, no device): validates the length
- * arrays exactly as ooco_plan does and reports the work lists it would build for the given
- * geometry, CU count, workspace size and option values.  For schedulers that want to know the
- * split of a batch in advance, and for testing the planner without a GPU.
- *   decode_items_out: HOST int32 [decode_cap][6] = (seq, q_row, blk_begin, blk_end, seq_len, part)
+ * arrays exactly as ooco_plan does and lists the work the kernels will derive from the plan for
+ * the given geometry, CU count, workspace size and decode run options.  For schedulers that
+ * want to know the split of a batch in advance, and for testing the planner without a GPU.
+ *   decode_pieces_out: HOST int32 [decode_cap][5] = (seq, blk_begin, blk_end, slot, run): the KV
+ *     block range of sequence seq that decode run `run` streams; slot = partial-result slot, or
+ *     -1 when the piece covers the whole sequence and writes the output directly
  *   prefill_tiles_out: HOST int32 [prefill_cap][5] = (seq, q_row0, rows, pos0, seq_len)
- *   counts: HOST int64 [4] = (decode items, prefill tiles, merged sequences, partial results)
+ *   counts: HOST int64 [5] = (decode pieces, prefill tiles, static decode runs, partial-result
+ *     slots, dynamically fetched tail runs); runs are numbered static first, then tail
  *   msg: HOST buffer of msg_cap bytes receiving the error text.  Any output pointer may be NULL. */
 ooco_status ooco_plan_dry_run(int num_q_heads, int num_kv_heads, int head_dim, int block_size,
                               int max_blocks_per_seq, int num_cus, size_t workspace_bytes,
-                              int64_t split_blocks, int64_t target_items, int64_t force_splits,
+                              int64_t decode_segments, int64_t decode_tail_pct, int64_t decode_tail_blocks,
                               int num_seqs, const int32_t *h_seq_lens /*HOST*/,
                               const int32_t *h_query_start_loc /*HOST*/, const int32_t *h_ctx_lens /*HOST*/,
-                              int32_t *decode_items_out /*HOST*/, int64_t decode_cap,
+                              int32_t *decode_pieces_out /*HOST*/, int64_t decode_cap,
                               int32_t *prefill_tiles_out /*HOST*/, int64_t prefill_cap,
                               int64_t *counts /*HOST*/, char *msg /*HOST*/, size_t msg_cap);
 
-/* Numbers describing the current plan (any pointer may be NULL): decode work items (per kv
- * head), prefill tiles, decode sequences that need the merge pass, bytes of workspace used. */
-ooco_status ooco_plan_info(const ooco_ctx *ctx, int64_t *decode_items, int64_t *prefill_tiles,
-                           int64_t *merged_seqs, int64_t *workspace_used);
+/* Numbers describing the current plan (any pointer may be NULL): decode runs (waves per kv head),
+ * prefill tiles, KV blocks of all decode sequences, bytes of workspace the partial results use. */
+ooco_status ooco_plan_info(const ooco_ctx *ctx, int64_t *decode_waves, int64_t *prefill_tiles,
+                           int64_t *decode_blocks, int64_t *workspace_used);
 
 /* The mixed-batch attention step (operation defined at the top of this file).
  *   q, out: DEVICE bf16 [total_q_tokens][Hq][hd]; k_cache, v_cache: DEVICE, read-only here;
@@ -150,6 +168,8 @@ ooco_status ooco_plan_info(const ooco_ctx *ctx, int64_t *decode_items, int64_t *
  * used and the three DEVICE length arrays are trusted to equal the planned HOST copies.
  * Without a current plan the call copies the length arrays to the host, waits for that copy
  * (one stream synchronisation) and plans by itself.
+ * Launches at most two kernels (prefill chunks, then decode with its in-kernel merge) and no
+ * copies (batches above 960 sequences: one small copy).
  * Writes every row of out (and the context's workspace), nothing else.  num_seqs == 0 or
  * total_q_tokens == 0 returns OOCO_OK without launching anything.
  * Same context + same plan + same inputs give bit-identical output on every call (no

@@ -19,7 +19,7 @@ _STATUS_NAMES = {0: "OOCO_OK", -1: "OOCO_EINVAL", -2: "OOCO_ESHAPE", -3: "OOCO_E
                  -5: "OOCO_ENOTIMPL"}
 
 EXPORTS = ["ooco_ctx_create", "ooco_ctx_destroy", "ooco_last_error", "ooco_set_option", "ooco_plan",
-           "ooco_plan_dry_run", "ooco_plan_info", "ooco_profile_read", "ooco_attn_mixed", "ooco_kv_block_copy"]
+           "ooco_plan_dry_run", "ooco_plan_info", "ooco_profile_read", "ooco_trace_read", "ooco_attn_mixed", "ooco_kv_block_copy"]
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2511_21862_amd.build` "
@@ -45,6 +45,8 @@ _lib.ooco_plan_info.restype = ctypes.c_int
 _lib.ooco_plan_info.argtypes = [_P] + [ctypes.POINTER(ctypes.c_int64)] * 4
 _lib.ooco_profile_read.restype = ctypes.c_int
 _lib.ooco_profile_read.argtypes = [_P, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
+_lib.ooco_trace_read.restype = ctypes.c_int
+_lib.ooco_trace_read.argtypes = [_P, _P, ctypes.c_int64, ctypes.POINTER(ctypes.c_int64)]
 _lib.ooco_attn_mixed.restype = ctypes.c_int
 _lib.ooco_attn_mixed.argtypes = [_P] * 9 + [ctypes.c_int, ctypes.c_int, _P]
 _lib.ooco_kv_block_copy.restype = ctypes.c_int
@@ -121,44 +123,54 @@ def ooco_plan(ctx, num_seqs, h_seq_lens, h_query_start_loc, h_ctx_lens) -> None:
 
 
 def ooco_plan_dry_run(num_q_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, num_cus, workspace_bytes,
-                      h_seq_lens, h_query_start_loc, h_ctx_lens, split_blocks=0, target_items=0, force_splits=0,
-                      num_seqs=None) -> dict:
-    """Host-only planner run; returns the work lists as numpy arrays."""
+                      h_seq_lens, h_query_start_loc, h_ctx_lens, decode_segments=0, decode_tail_pct=0,
+                      decode_tail_blocks=8, num_seqs=None) -> dict:
+    """Host-only planner run; returns the work the kernels derive from the plan as numpy arrays."""
     a, pa = _host_i32(h_seq_lens)
     b, pb = _host_i32(h_query_start_loc)
     c, pc = _host_i32(h_ctx_lens)
     n = len(a) if num_seqs is None else num_seqs
-    counts = np.zeros(4, dtype=np.int64)
+    counts = np.zeros(5, dtype=np.int64)
     msg = ctypes.create_string_buffer(512)
 
     def call(dptr, dcap, pptr, pcap):
         return _lib.ooco_plan_dry_run(num_q_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, num_cus,
-                                      workspace_bytes, split_blocks, target_items, force_splits, n, pa, pb, pc, dptr,
-                                      dcap, pptr, pcap, counts.ctypes.data, msg, 512)
+                                      workspace_bytes, decode_segments, decode_tail_pct, decode_tail_blocks, n, pa, pb, pc,
+                                      dptr, dcap, pptr, pcap,
+                                      counts.ctypes.data, msg, 512)
 
     st = call(0, 0, 0, 0)
     if st != OOCO_OK:
         raise OocoError(st, msg.value.decode())
-    d = np.zeros((int(counts[0]), 6), dtype=np.int32)
+    d = np.zeros((int(counts[0]), 5), dtype=np.int32)
     p = np.zeros((int(counts[1]), 5), dtype=np.int32)
     st = call(d.ctypes.data, len(d), p.ctypes.data, len(p))
     if st != OOCO_OK:
         raise OocoError(st, msg.value.decode())
-    return dict(decode_items=d, prefill_tiles=p, merged_seqs=int(counts[2]), parts=int(counts[3]))
+    return dict(decode_pieces=d, prefill_tiles=p, decode_runs=int(counts[2]), slots=int(counts[3]),
+                tail_runs=int(counts[4]))
 
 
 def ooco_plan_info(ctx) -> dict:
     v = [ctypes.c_int64() for _ in range(4)]
     _check(ctx, _lib.ooco_plan_info(ctx, *[ctypes.byref(x) for x in v]))
-    return dict(decode_items=v[0].value, prefill_tiles=v[1].value, merged_seqs=v[2].value,
+    return dict(decode_waves=v[0].value, prefill_tiles=v[1].value, decode_blocks=v[2].value,
                 workspace_used=v[3].value)
 
 
+def ooco_trace_read(ctx, cap_waves=1 << 16):
+    """uint64 [waves, 4] device time stamps (100 MHz) of the last traced call's decode waves."""
+    buf = np.zeros((cap_waves, 4), dtype=np.uint64)
+    n = ctypes.c_int64()
+    _check(ctx, _lib.ooco_trace_read(ctx, buf.ctypes.data, cap_waves, ctypes.byref(n)))
+    return buf[: min(n.value, cap_waves)]
+
+
 def ooco_profile_read(ctx) -> dict:
-    ms = (ctypes.c_double * 3)()
+    ms = (ctypes.c_double * 2)()
     n = ctypes.c_int64()
     _check(ctx, _lib.ooco_profile_read(ctx, ms, ctypes.byref(n)))
-    return dict(prefill_ms=ms[0], decode_ms=ms[1], merge_ms=ms[2], calls=n.value)
+    return dict(prefill_ms=ms[0], decode_ms=ms[1], calls=n.value)
 
 
 def ooco_attn_mixed(ctx, q, k_cache, v_cache, block_tables, seq_lens, query_start_loc, ctx_lens, out, num_seqs,
@@ -209,6 +221,9 @@ class Context:
 
     def profile_read(self):
         return ooco_profile_read(self.h)
+
+    def trace_read(self):
+        return ooco_trace_read(self.h)
 
     def attn_mixed(self, q, k_cache, v_cache, block_tables, seq_lens, query_start_loc, ctx_lens, out, stream=None):
         ooco_attn_mixed(self.h, q, k_cache, v_cache, block_tables, seq_lens, query_start_loc, ctx_lens, out,

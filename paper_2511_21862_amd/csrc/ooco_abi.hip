@@ -17,7 +17,9 @@ namespace {
 thread_local char g_create_error[512] = "";
 
 constexpr size_t kDefaultWorkspace = 128ull << 20;
-constexpr size_t kPlanBytes = 16ull << 20;   // pinned + device staging for the work lists
+constexpr size_t kPlanInts = 1u << 21;       // staging for cumulative arrays of very large batches
+constexpr size_t kCounterInts = 1u << 20;    // arrival counters: num_seqs * num_kv_heads must fit
+constexpr size_t kTraceWaves = 1u << 16;     // decode waves the trace buffer can hold
 constexpr int kProfSlots = 1024;             // profiled calls between two ooco_profile_read
 
 }  // namespace
@@ -27,18 +29,23 @@ namespace {
 struct PlanGeometry {
     int Hq, Hkv, hd, BS, max_blocks_per_seq, num_cus;
     size_t ws_bytes;
-    int64_t split_blocks, target_items, force_splits;
+    int64_t segments_opt;   // static runs; 0 = automatic
+    int64_t tail_pct;       // share of the decode line handed out dynamically, in percent
+    int64_t tail_blocks;    // KV blocks per dynamically fetched run
 };
 
+// The compact plan: two cumulative arrays and a few scalars (see ooco_internal.h).
 struct HostPlan {
-    std::vector<DecodeItem> d;
-    std::vector<PrefillTile> p;
-    std::vector<MergeItem> m;
-    int64_t parts = 0;
-    int total_q = 0;
+    std::vector<int32_t> dcum;   // [num_seqs+1] decode KV blocks before each sequence
+    std::vector<int32_t> tcum;   // [num_seqs+1] prefill query tiles before each sequence
+    int32_t dec_blocks = 0, static_blocks = 0, static_runs = 0, tail_runs = 0;
+    int32_t n_tiles = 0, total_q = 0, num_seqs = 0;
+    int64_t slots = 0;           // partial-result slots the decode kernel may touch
 };
 
-// Validates the length arrays and builds the three work lists.  Pure host code.
+size_t slot_bytes(const PlanGeometry &geo) { return (size_t)geo.Hq * (geo.hd + 2) * sizeof(float); }
+
+// Validates the length arrays and builds the plan.  Pure host code.
 ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_seq_lens,
                        const int32_t *h_query_start_loc, const int32_t *h_ctx_lens, HostPlan &out, char *err)
 {
@@ -49,20 +56,17 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
         va_end(ap);
         return code;
     };
-    out.d.clear();
-    out.p.clear();
-    out.m.clear();
-    out.parts = 0;
-    out.total_q = 0;
+    out = HostPlan();
     if (num_seqs < 0) return bad(OOCO_EINVAL, "ooco_plan: num_seqs=%d", num_seqs);
     if (num_seqs > 0 && (!h_seq_lens || !h_query_start_loc || !h_ctx_lens))
         return bad(OOCO_EINVAL, "ooco_plan: NULL length array");
     const int BS = geo.BS;
-
-    // ---- validation and classification
     if (num_seqs > 0 && h_query_start_loc[0] != 0)
         return bad(OOCO_ESHAPE, "ooco_plan: query_start_loc[0]=%d, expected 0", h_query_start_loc[0]);
-    int64_t dec_blocks = 0;
+    out.num_seqs = num_seqs;
+    out.dcum.assign((size_t)num_seqs + 1, 0);
+    out.tcum.assign((size_t)num_seqs + 1, 0);
+    int64_t dec_blocks = 0, tiles = 0;
     for (int i = 0; i < num_seqs; ++i) {
         const int64_t ql = (int64_t)h_query_start_loc[i + 1] - h_query_start_loc[i];
         if (ql < 0) return bad(OOCO_ESHAPE, "ooco_plan: query_start_loc decreases at sequence %d", i);
@@ -76,80 +80,76 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
             return bad(OOCO_ESHAPE, "ooco_plan: sequence %d needs %lld blocks > max_blocks_per_seq %d", i,
                        (long long)nb, geo.max_blocks_per_seq);
         if (ql == 1) dec_blocks += nb;
+        if (ql > 1) tiles += (ql + kPrefillRows - 1) / kPrefillRows;
+        if (dec_blocks > 0x7FFFFFFF / 2 || tiles > 0x7FFFFFFF / 128)
+            return bad(OOCO_ESHAPE, "ooco_plan: batch too large");
+        out.dcum[(size_t)i + 1] = (int32_t)dec_blocks;
+        out.tcum[(size_t)i + 1] = (int32_t)tiles;
     }
     out.total_q = num_seqs > 0 ? h_query_start_loc[num_seqs] : 0;
+    out.dec_blocks = (int32_t)dec_blocks;
+    out.n_tiles = (int32_t)tiles;
 
-    // ---- split quantum for decode (KV blocks per work item)
-    const size_t part_bytes = (size_t)geo.Hq * (geo.hd + 2) * sizeof(float);
-    int64_t quantum = geo.split_blocks;
-    if (quantum <= 0) {
-        // Aim at `target` wave-sized items per kv head: enough to keep every CU busy with several
-        // waves and to even out the tail, not so many that partial results cost bandwidth.
-        const int64_t target =
-            geo.target_items > 0 ? geo.target_items : std::max<int64_t>(1, (int64_t)geo.num_cus * 16 / geo.Hkv);
-        quantum = (dec_blocks + target - 1) / target;
-        quantum = std::min<int64_t>(std::max<int64_t>(quantum, 8), 512);
-    }
-    auto parts_of = [&](int64_t nb) {
-        const int64_t n = geo.force_splits > 0 ? std::min<int64_t>(geo.force_splits, nb) : (nb + quantum - 1) / quantum;
-        return std::max<int64_t>(n, 1);
-    };
-    for (;;) {
-        int64_t n_parts = 0;
-        for (int i = 0; i < num_seqs; ++i) {
-            if (h_query_start_loc[i + 1] - h_query_start_loc[i] != 1) continue;
-            const int64_t n = parts_of(((int64_t)h_seq_lens[i] + BS - 1) / BS);
-            if (n > 1) n_parts += n;
-        }
-        if ((size_t)n_parts * part_bytes <= geo.ws_bytes) break;
-        if (geo.force_splits > 0 || geo.split_blocks > 0 || quantum > (1 << 24))
-            return bad(OOCO_ENOMEM, "ooco_plan: workspace of %zu bytes cannot hold %lld partial results", geo.ws_bytes,
-                       (long long)n_parts);
-        quantum *= 2;
-    }
-
-    int64_t part = 0;
-    for (int i = 0; i < num_seqs; ++i) {
-        const int q0 = h_query_start_loc[i];
-        const int ql = h_query_start_loc[i + 1] - q0;
-        if (ql == 1) {
-            const int64_t nb = ((int64_t)h_seq_lens[i] + BS - 1) / BS;
-            const int64_t n = parts_of(nb);
-            if (n > 1) out.m.push_back(MergeItem{q0, (int32_t)part, (int32_t)n, 0});
-            for (int64_t s = 0; s < n; ++s) {
-                DecodeItem d;
-                d.seq = i;
-                d.q_row = q0;
-                d.blk_begin = (int32_t)(nb * s / n);
-                d.blk_end = (int32_t)(nb * (s + 1) / n);
-                d.seq_len = h_seq_lens[i];
-                d.part = n > 1 ? (int32_t)part++ : -1;
-                d.pad0 = d.pad1 = 0;
-                out.d.push_back(d);
+    // ---- run layout of the decode block line (see ooco_internal.h)
+    if (dec_blocks > 0) {
+        // static runs: by default three waves per CU (measured best on MI355X: enough loads in
+        // flight to saturate HBM, few enough waves that start-up and partial results stay small)
+        // and at least ~32 blocks per wave
+        const int64_t wave_slots = std::max<int64_t>(1, (int64_t)geo.num_cus * 3 / geo.Hkv);
+        int64_t runs = geo.segments_opt > 0 ? geo.segments_opt : std::min<int64_t>(wave_slots, (dec_blocks + 31) / 32);
+        runs = std::max<int64_t>(1, std::min<int64_t>(runs, dec_blocks));
+        for (;;) {
+            // dynamic tail: only when a static run is much longer than a tail run
+            int64_t tail_blk = 0, tails = 0;
+            if (geo.tail_pct > 0 && geo.tail_blocks > 0 && dec_blocks / runs >= 4 * geo.tail_blocks) {
+                tail_blk = std::min<int64_t>(dec_blocks - runs, dec_blocks * std::min<int64_t>(geo.tail_pct, 90) / 100);
+                tails = (tail_blk + geo.tail_blocks - 1) / geo.tail_blocks;
+                if (tails == 0) tail_blk = 0;
             }
-        } else if (ql > 1) {
-            for (int t0 = 0; t0 < ql; t0 += kPrefillRows) {
-                PrefillTile t;
-                t.seq = i;
-                t.q_row0 = q0 + t0;
-                t.rows = std::min(kPrefillRows, ql - t0);
-                t.pos0 = h_ctx_lens[i] + t0;
-                t.seq_len = h_seq_lens[i];
-                t.pad0 = t.pad1 = t.pad2 = 0;
-                out.p.push_back(t);
+            // partial slots: (run index) + seq < runs + tails + num_seqs; one run never splits a sequence
+            const int64_t slots = (runs + tails > 1) ? runs + tails + num_seqs : 0;
+            if ((size_t)slots * slot_bytes(geo) <= geo.ws_bytes || runs == 1) {
+                if ((size_t)slots * slot_bytes(geo) > geo.ws_bytes) {   // a single run, no tail, needs no slots
+                    tail_blk = tails = 0;
+                }
+                out.static_runs = (int32_t)runs;
+                out.static_blocks = (int32_t)(dec_blocks - tail_blk);
+                out.tail_runs = (int32_t)tails;
+                out.slots = (runs + tails > 1) ? runs + tails + num_seqs : 0;
+                break;
             }
+            runs = (runs + 1) / 2;
         }
     }
-    // longest work first: the hardware dispatches workgroups in index order
-    std::stable_sort(out.d.begin(), out.d.end(), [](const DecodeItem &a, const DecodeItem &b) {
-        return (a.blk_end - a.blk_begin) > (b.blk_end - b.blk_begin);
-    });
-    std::stable_sort(out.p.begin(), out.p.end(),
-                     [](const PrefillTile &a, const PrefillTile &b) { return (a.pos0 + a.rows) > (b.pos0 + b.rows); });
-    out.parts = part;
     return OOCO_OK;
 }
 
+// Pieces of the decode line as the kernel walks them (host mirror of the device logic).
+struct Piece {
+    int32_t seq, blk_begin, blk_end, slot, run;
+};
+std::vector<Piece> enumerate_pieces(const HostPlan &pl)
+{
+    std::vector<Piece> v;
+    const RunLayout L = {pl.dec_blocks, pl.static_blocks, pl.static_runs, pl.tail_runs};
+    for (int32_t k = 0; k < pl.static_runs + pl.tail_runs; ++k) {
+        int32_t lo, hi;
+        run_bounds(L, k, lo, hi);
+        int seq = 0;
+        while (pl.dcum[(size_t)seq + 1] <= lo) ++seq;
+        int64_t pos = lo;
+        while (pos < hi) {
+            while (pl.dcum[(size_t)seq + 1] <= pos) ++seq;
+            const int64_t cs = pl.dcum[(size_t)seq], ce = pl.dcum[(size_t)seq + 1];
+            const int64_t stop = std::min<int64_t>(hi, ce);
+            const bool whole = pos == cs && stop == ce;
+            v.push_back(Piece{seq, (int32_t)(pos - cs), (int32_t)(stop - cs), whole ? -1 : (int32_t)(k + seq), (int32_t)k});
+            pos = stop;
+            ++seq;
+        }
+    }
+    return v;
+}
 }  // namespace
 
 struct ooco_ctx {
@@ -164,32 +164,35 @@ struct ooco_ctx {
     size_t ws_bytes = 0;
     bool own_ws = false;
 
-    char *plan_h = nullptr;   // pinned host staging
-    char *plan_d = nullptr;   // device copy
+    int32_t *plan_h = nullptr;   // pinned host staging for batches beyond kInlineSeqs sequences
+    int32_t *plan_d = nullptr;   // device copy of the two cumulative arrays
+    int32_t *counters = nullptr; // arrival counters [kCounterInts], zero between calls
     hipEvent_t upload_done = nullptr;
     bool upload_pending = false;
 
     // current plan
+    HostPlan plan;
     bool plan_valid = false;
     bool plan_dirty = false;
     bool plan_one_shot = false;   // planned inside ooco_attn_mixed from device lengths
-    int plan_num_seqs = -1;
-    int plan_total_q = -1;
-    int64_t n_ditems = 0, n_ptiles = 0, n_mitems = 0, n_parts = 0;
-    size_t off_d = 0, off_p = 0, off_m = 0, plan_used = 0;
-    size_t ws_used = 0;
 
     // options
-    int64_t opt_split_blocks = 0;
-    int64_t opt_target_items = 0;
-    int64_t opt_force_splits = 0;
+    int64_t opt_segments = 0;
+    int64_t opt_tail_pct = 0;
+    int64_t opt_tail_blocks = 8;
+    uint32_t queue_base = 0;       // ticket value the next launch's tail runs start at
+    int64_t opt_nbi = 0;
+    int64_t opt_trace = 0;
+    int64_t opt_rotate = 1;
+    uint64_t *trace_d = nullptr;   // [kTraceWaves][4] decode-wave time stamps
+    int64_t trace_waves = 0;       // waves of the last traced call
     int64_t opt_profile = 0;
 
-    // per-kernel timing (option "profile"): 4 events per call in a ring
+    // per-kernel timing (option "profile"): 3 events per call
     std::vector<hipEvent_t> prof_ev;
     int64_t prof_calls = 0;
 
-    HostPlan plan;
+    KernArgs kargs;                      // staging of the kernel arguments of the current call
     std::vector<int32_t> h_len_scratch;   // for the plan-less path
     mutable char err[512] = "";
 };
@@ -206,7 +209,6 @@ ooco_status fail(const ooco_ctx *ctx, ooco_status code, const char *fmt, ...)
     return code;
 }
 
-size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 }  // namespace
 
@@ -262,14 +264,17 @@ ooco_status ooco_ctx_create(ooco_ctx **out, int num_q_heads, int num_kv_heads, i
             c->own_ws = (e == hipSuccess);
         }
     }
-    if (e == hipSuccess) e = hipHostMalloc((void **)&c->plan_h, kPlanBytes, hipHostMallocDefault);
-    if (e == hipSuccess) e = hipMalloc((void **)&c->plan_d, kPlanBytes);
+    if (e == hipSuccess) e = hipHostMalloc((void **)&c->plan_h, kPlanInts * sizeof(int32_t), hipHostMallocDefault);
+    if (e == hipSuccess) e = hipMalloc((void **)&c->plan_d, kPlanInts * sizeof(int32_t));
+    if (e == hipSuccess) e = hipMalloc((void **)&c->counters, kCounterInts * sizeof(int32_t));
+    if (e == hipSuccess) e = hipMemset(c->counters, 0, kCounterInts * sizeof(int32_t));
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->upload_done, hipEventDisableTiming);
     if (e != hipSuccess) {
         fail(nullptr, e == hipErrorOutOfMemory ? OOCO_ENOMEM : OOCO_EHIP, "ooco_ctx_create: %s", hipGetErrorString(e));
         ooco_status st = e == hipErrorOutOfMemory ? OOCO_ENOMEM : OOCO_EHIP;
         (void)hipGetLastError();
         if (c->upload_done) (void)hipEventDestroy(c->upload_done);
+        if (c->counters) (void)hipFree(c->counters);
         if (c->plan_d) (void)hipFree(c->plan_d);
         if (c->plan_h) (void)hipHostFree(c->plan_h);
         if (c->own_ws && c->ws) (void)hipFree(c->ws);
@@ -288,6 +293,8 @@ ooco_status ooco_ctx_destroy(ooco_ctx *ctx)
     if (ctx->upload_done) (void)hipEventDestroy(ctx->upload_done);
     for (hipEvent_t x : ctx->prof_ev)
         if (x) (void)hipEventDestroy(x);
+    if (ctx->trace_d) (void)hipFree(ctx->trace_d);
+    if (ctx->counters) (void)hipFree(ctx->counters);
     if (ctx->plan_d) (void)hipFree(ctx->plan_d);
     if (ctx->plan_h) (void)hipHostFree(ctx->plan_h);
     if (ctx->own_ws && ctx->ws) (void)hipFree(ctx->ws);
@@ -295,21 +302,34 @@ ooco_status ooco_ctx_destroy(ooco_ctx *ctx)
     return OOCO_OK;
 }
 
+ooco_status ooco_trace_read(ooco_ctx *ctx, uint64_t *stamps, int64_t cap_waves, int64_t *waves)
+{
+    if (!ctx) return OOCO_EINVAL;
+    if (!ctx->trace_d) return fail(ctx, OOCO_EINVAL, "ooco_trace_read: option \"trace\" was never enabled");
+    hipError_t e = hipDeviceSynchronize();
+    const int64_t n = std::min<int64_t>(cap_waves, ctx->trace_waves);
+    if (e == hipSuccess && stamps && n > 0)
+        e = hipMemcpy(stamps, ctx->trace_d, (size_t)n * 4 * sizeof(uint64_t), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return fail(ctx, OOCO_EHIP, "ooco_trace_read: %s", hipGetErrorString(e));
+    if (waves) *waves = ctx->trace_waves;
+    return OOCO_OK;
+}
+
 ooco_status ooco_profile_read(ooco_ctx *ctx, double *ms_sum, int64_t *calls)
 {
     if (!ctx) return OOCO_EINVAL;
-    double sum[3] = {0.0, 0.0, 0.0};
+    double sum[2] = {0.0, 0.0};
     for (int64_t c = 0; c < ctx->prof_calls; ++c) {
-        hipEvent_t *ev = ctx->prof_ev.data() + 4 * c;
-        hipError_t e = hipEventSynchronize(ev[3]);
-        for (int k = 0; k < 3 && e == hipSuccess; ++k) {
+        hipEvent_t *ev = ctx->prof_ev.data() + 3 * c;
+        hipError_t e = hipEventSynchronize(ev[2]);
+        for (int k = 0; k < 2 && e == hipSuccess; ++k) {
             float ms = 0.f;
             e = hipEventElapsedTime(&ms, ev[k], ev[k + 1]);
             sum[k] += ms;
         }
         if (e != hipSuccess) return fail(ctx, OOCO_EHIP, "ooco_profile_read: %s", hipGetErrorString(e));
     }
-    if (ms_sum) ms_sum[0] = sum[0], ms_sum[1] = sum[1], ms_sum[2] = sum[2];
+    if (ms_sum) ms_sum[0] = sum[0], ms_sum[1] = sum[1];
     if (calls) *calls = ctx->prof_calls;
     ctx->prof_calls = 0;
     return OOCO_OK;
@@ -322,13 +342,26 @@ ooco_status ooco_set_option(ooco_ctx *ctx, const char *name, int64_t value)
     if (!ctx) return OOCO_EINVAL;
     if (!name) return fail(ctx, OOCO_EINVAL, "ooco_set_option: name is NULL");
     if (value < 0) return fail(ctx, OOCO_EINVAL, "ooco_set_option: %s must be >= 0", name);
-    if (!strcmp(name, "decode_split_blocks"))
-        ctx->opt_split_blocks = value;
-    else if (!strcmp(name, "decode_target_items"))
-        ctx->opt_target_items = value;
-    else if (!strcmp(name, "force_splits"))
-        ctx->opt_force_splits = value;
-    else if (!strcmp(name, "profile")) {
+    if (!strcmp(name, "decode_segments"))
+        ctx->opt_segments = value;
+    else if (!strcmp(name, "decode_tail_pct"))
+        ctx->opt_tail_pct = value;
+    else if (!strcmp(name, "decode_tail_blocks"))
+        ctx->opt_tail_blocks = value;
+    else if (!strcmp(name, "trace")) {
+        if (value && !ctx->trace_d) {
+            hipError_t e = hipMalloc((void **)&ctx->trace_d, kTraceWaves * 4 * sizeof(uint64_t));
+            if (e != hipSuccess) return fail(ctx, OOCO_ENOMEM, "ooco_set_option: trace buffer: %s", hipGetErrorString(e));
+        }
+        ctx->opt_trace = value;
+        return OOCO_OK;
+    } else if (!strcmp(name, "rotate_heads")) {
+        ctx->opt_rotate = value;
+        return OOCO_OK;
+    } else if (!strcmp(name, "decode_nbi")) {
+        ctx->opt_nbi = value;
+        return OOCO_OK;
+    } else if (!strcmp(name, "profile")) {
         ctx->opt_profile = value;
         ctx->prof_calls = 0;
         return OOCO_OK;   // does not invalidate the plan
@@ -352,42 +385,13 @@ ooco_status ooco_plan(ooco_ctx *ctx, int num_seqs, const int32_t *h_seq_lens, co
     geo.max_blocks_per_seq = ctx->max_blocks_per_seq;
     geo.num_cus = ctx->num_cus;
     geo.ws_bytes = ctx->ws_bytes;
-    geo.split_blocks = ctx->opt_split_blocks;
-    geo.target_items = ctx->opt_target_items;
-    geo.force_splits = ctx->opt_force_splits;
+    geo.segments_opt = ctx->opt_segments;
+    geo.tail_pct = ctx->opt_tail_pct;
+    geo.tail_blocks = ctx->opt_tail_blocks;
     ooco_status st = build_plan(geo, num_seqs, h_seq_lens, h_query_start_loc, h_ctx_lens, ctx->plan, ctx->err);
     if (st != OOCO_OK) return st;
-    const HostPlan &pl = ctx->plan;
-
-    // layout of the lists in the staging buffer
-    const size_t off_d = 0;
-    const size_t off_p = align_up(off_d + pl.d.size() * sizeof(DecodeItem), 256);
-    const size_t off_m = align_up(off_p + pl.p.size() * sizeof(PrefillTile), 256);
-    const size_t used = align_up(off_m + pl.m.size() * sizeof(MergeItem), 256);
-    if (used > kPlanBytes)
-        return fail(ctx, OOCO_ENOMEM, "ooco_plan: work lists need %zu bytes > %zu", used, (size_t)kPlanBytes);
-
-    // the previous upload may still be reading the pinned buffer
-    if (ctx->upload_pending) {
-        hipError_t e = hipEventSynchronize(ctx->upload_done);
-        if (e != hipSuccess) return fail(ctx, OOCO_EHIP, "ooco_plan: %s", hipGetErrorString(e));
-        ctx->upload_pending = false;
-    }
-    if (!pl.d.empty()) memcpy(ctx->plan_h + off_d, pl.d.data(), pl.d.size() * sizeof(DecodeItem));
-    if (!pl.p.empty()) memcpy(ctx->plan_h + off_p, pl.p.data(), pl.p.size() * sizeof(PrefillTile));
-    if (!pl.m.empty()) memcpy(ctx->plan_h + off_m, pl.m.data(), pl.m.size() * sizeof(MergeItem));
-
-    ctx->n_ditems = (int64_t)pl.d.size();
-    ctx->n_ptiles = (int64_t)pl.p.size();
-    ctx->n_mitems = (int64_t)pl.m.size();
-    ctx->n_parts = pl.parts;
-    ctx->off_d = off_d;
-    ctx->off_p = off_p;
-    ctx->off_m = off_m;
-    ctx->plan_used = used;
-    ctx->ws_used = (size_t)pl.parts * ((size_t)ctx->Hq * (ctx->hd + 2) * sizeof(float));
-    ctx->plan_num_seqs = num_seqs;
-    ctx->plan_total_q = pl.total_q;
+    if ((size_t)num_seqs * ctx->Hkv > kCounterInts - 1 || 2 * ((size_t)num_seqs + 1) > kPlanInts)
+        return fail(ctx, OOCO_ENOMEM, "ooco_plan: %d sequences exceed the context's counter/plan buffers", num_seqs);
     ctx->plan_valid = true;
     ctx->plan_dirty = true;
     ctx->plan_one_shot = false;
@@ -395,17 +399,18 @@ ooco_status ooco_plan(ooco_ctx *ctx, int num_seqs, const int32_t *h_seq_lens, co
 }
 
 ooco_status ooco_plan_dry_run(int num_q_heads, int num_kv_heads, int head_dim, int block_size, int max_blocks_per_seq,
-                              int num_cus, size_t workspace_bytes, int64_t split_blocks, int64_t target_items,
-                              int64_t force_splits, int num_seqs, const int32_t *h_seq_lens,
-                              const int32_t *h_query_start_loc, const int32_t *h_ctx_lens, int32_t *decode_items_out,
-                              int64_t decode_cap, int32_t *prefill_tiles_out, int64_t prefill_cap, int64_t *counts,
-                              char *msg, size_t msg_cap)
+                              int num_cus, size_t workspace_bytes, int64_t decode_segments, int64_t decode_tail_pct,
+                              int64_t decode_tail_blocks, int num_seqs,
+                              const int32_t *h_seq_lens, const int32_t *h_query_start_loc, const int32_t *h_ctx_lens,
+                              int32_t *decode_pieces_out, int64_t decode_cap, int32_t *prefill_tiles_out,
+                              int64_t prefill_cap, int64_t *counts, char *msg, size_t msg_cap)
 {
     char err[512] = "";
     ooco_status st = OOCO_OK;
     HostPlan pl;
     if (num_q_heads <= 0 || num_kv_heads <= 0 || num_q_heads % num_kv_heads || (head_dim != 64 && head_dim != 128) ||
-        block_size != kBlockSize || max_blocks_per_seq <= 0 || num_cus <= 0) {
+        block_size != kBlockSize || max_blocks_per_seq <= 0 || num_cus <= 0 || decode_segments < 0 ||
+        decode_tail_pct < 0 || decode_tail_blocks < 0) {
         snprintf(err, sizeof err, "ooco_plan_dry_run: bad geometry");
         st = OOCO_ESHAPE;
     } else {
@@ -417,43 +422,51 @@ ooco_status ooco_plan_dry_run(int num_q_heads, int num_kv_heads, int head_dim, i
         geo.max_blocks_per_seq = max_blocks_per_seq;
         geo.num_cus = num_cus;
         geo.ws_bytes = workspace_bytes;
-        geo.split_blocks = split_blocks;
-        geo.target_items = target_items;
-        geo.force_splits = force_splits;
+        geo.segments_opt = decode_segments;
+        geo.tail_pct = decode_tail_pct;
+        geo.tail_blocks = decode_tail_blocks;
         st = build_plan(geo, num_seqs, h_seq_lens, h_query_start_loc, h_ctx_lens, pl, err);
     }
     if (msg && msg_cap) snprintf(msg, msg_cap, "%s", err);
     if (st != OOCO_OK) return st;
+    const std::vector<Piece> pieces = enumerate_pieces(pl);
     if (counts) {
-        counts[0] = (int64_t)pl.d.size();
-        counts[1] = (int64_t)pl.p.size();
-        counts[2] = (int64_t)pl.m.size();
-        counts[3] = pl.parts;
+        counts[0] = (int64_t)pieces.size();
+        counts[1] = pl.n_tiles;
+        counts[2] = pl.static_runs;
+        counts[3] = pl.slots;
+        counts[4] = pl.tail_runs;
     }
-    if (decode_items_out)
-        for (int64_t i = 0; i < std::min<int64_t>(decode_cap, (int64_t)pl.d.size()); ++i) {
-            const DecodeItem &d = pl.d[(size_t)i];
-            int32_t *o = decode_items_out + 6 * i;
-            o[0] = d.seq, o[1] = d.q_row, o[2] = d.blk_begin, o[3] = d.blk_end, o[4] = d.seq_len, o[5] = d.part;
+    if (decode_pieces_out)
+        for (int64_t i = 0; i < std::min<int64_t>(decode_cap, (int64_t)pieces.size()); ++i) {
+            const Piece &d = pieces[(size_t)i];
+            int32_t *o = decode_pieces_out + 5 * i;
+            o[0] = d.seq, o[1] = d.blk_begin, o[2] = d.blk_end, o[3] = d.slot, o[4] = d.run;
         }
-    if (prefill_tiles_out)
-        for (int64_t i = 0; i < std::min<int64_t>(prefill_cap, (int64_t)pl.p.size()); ++i) {
-            const PrefillTile &t = pl.p[(size_t)i];
-            int32_t *o = prefill_tiles_out + 5 * i;
-            o[0] = t.seq, o[1] = t.q_row0, o[2] = t.rows, o[3] = t.pos0, o[4] = t.seq_len;
+    if (prefill_tiles_out) {
+        int64_t n = 0;
+        for (int i = 0; i < num_seqs && n < prefill_cap; ++i) {
+            const int q0 = h_query_start_loc[i], ql = h_query_start_loc[i + 1] - q0;
+            if (ql <= 1) continue;
+            for (int t0 = 0; t0 < ql && n < prefill_cap; t0 += kPrefillRows, ++n) {
+                int32_t *o = prefill_tiles_out + 5 * n;
+                o[0] = i, o[1] = q0 + t0, o[2] = std::min(kPrefillRows, ql - t0), o[3] = h_ctx_lens[i] + t0;
+                o[4] = h_seq_lens[i];
+            }
         }
+    }
     return OOCO_OK;
 }
 
-ooco_status ooco_plan_info(const ooco_ctx *ctx, int64_t *decode_items, int64_t *prefill_tiles, int64_t *merged_seqs,
+ooco_status ooco_plan_info(const ooco_ctx *ctx, int64_t *decode_waves, int64_t *prefill_tiles, int64_t *decode_blocks,
                            int64_t *workspace_used)
 {
     if (!ctx) return OOCO_EINVAL;
     if (!ctx->plan_valid) return fail(ctx, OOCO_EINVAL, "ooco_plan_info: no current plan");
-    if (decode_items) *decode_items = ctx->n_ditems;
-    if (prefill_tiles) *prefill_tiles = ctx->n_ptiles;
-    if (merged_seqs) *merged_seqs = ctx->n_mitems;
-    if (workspace_used) *workspace_used = (int64_t)ctx->ws_used;
+    if (decode_waves) *decode_waves = ctx->plan.static_runs;
+    if (prefill_tiles) *prefill_tiles = ctx->plan.n_tiles;
+    if (decode_blocks) *decode_blocks = ctx->plan.dec_blocks;
+    if (workspace_used) *workspace_used = (int64_t)((size_t)ctx->plan.slots * (size_t)ctx->Hq * (ctx->hd + 2) * sizeof(float));
     return OOCO_OK;
 }
 
@@ -486,38 +499,58 @@ ooco_status ooco_attn_mixed(ooco_ctx *ctx, const void *q, const void *k_cache, c
         if (st != OOCO_OK) return st;
         ctx->plan_one_shot = true;
     }
-    if (ctx->plan_num_seqs != num_seqs || ctx->plan_total_q != total_q_tokens)
+    const HostPlan &pl = ctx->plan;
+    if (pl.num_seqs != num_seqs || pl.total_q != total_q_tokens)
         return fail(ctx, OOCO_ESHAPE, "ooco_attn_mixed: plan was made for %d sequences / %d query tokens, call has %d / %d",
-                    ctx->plan_num_seqs, ctx->plan_total_q, num_seqs, total_q_tokens);
+                    pl.num_seqs, pl.total_q, num_seqs, total_q_tokens);
 
-    if (ctx->plan_dirty && ctx->plan_used > 0) {
-        hipError_t e = hipMemcpyAsync(ctx->plan_d, ctx->plan_h, ctx->plan_used, hipMemcpyHostToDevice, s);
+    // The cumulative arrays ride in the kernel arguments; only very large batches need a copy.
+    const bool inline_cum = num_seqs <= kInlineSeqs;
+    const size_t n_cum = (size_t)num_seqs + 1;
+    if (!inline_cum && ctx->plan_dirty) {
+        if (ctx->upload_pending) (void)hipEventSynchronize(ctx->upload_done);
+        memcpy(ctx->plan_h, pl.dcum.data(), n_cum * sizeof(int32_t));
+        memcpy(ctx->plan_h + n_cum, pl.tcum.data(), n_cum * sizeof(int32_t));
+        hipError_t e = hipMemcpyAsync(ctx->plan_d, ctx->plan_h, 2 * n_cum * sizeof(int32_t), hipMemcpyHostToDevice, s);
         if (e == hipSuccess) e = hipEventRecord(ctx->upload_done, s);
         if (e != hipSuccess) return fail(ctx, OOCO_EHIP, "ooco_attn_mixed: plan upload: %s", hipGetErrorString(e));
         ctx->upload_pending = true;
-        ctx->plan_dirty = false;
     }
+    ctx->plan_dirty = false;
 
-    AttnParams p;
+    KernArgs &ka = ctx->kargs;
+    AttnParams &p = ka.p;
     p.q = static_cast<const uint16_t *>(q);
     p.k_cache = static_cast<const uint16_t *>(k_cache);
     p.v_cache = static_cast<const uint16_t *>(v_cache);
     p.block_tables = block_tables;
+    p.seq_lens = seq_lens;
+    p.query_start_loc = query_start_loc;
+    p.ctx_lens = ctx_lens;
     p.out = static_cast<uint16_t *>(out);
     p.part_acc = static_cast<float *>(ctx->ws);
-    p.part_ml = p.part_acc + (size_t)ctx->n_parts * ctx->Hq * ctx->hd;
-    p.ditems = reinterpret_cast<const DecodeItem *>(ctx->plan_d + ctx->off_d);
-    p.ptiles = reinterpret_cast<const PrefillTile *>(ctx->plan_d + ctx->off_p);
-    p.mitems = reinterpret_cast<const MergeItem *>(ctx->plan_d + ctx->off_m);
+    p.part_ml = p.part_acc + (size_t)pl.slots * ctx->Hq * ctx->hd;
+    p.counters = ctx->counters;
+    const bool tracing = ctx->opt_trace && ctx->trace_d && (size_t)pl.static_runs * ctx->Hkv <= kTraceWaves;
+    p.trace = tracing ? ctx->trace_d : nullptr;
+    if (tracing) ctx->trace_waves = (int64_t)pl.static_runs * ctx->Hkv;
     p.Hq = ctx->Hq;
     p.Hkv = ctx->Hkv;
     p.g = ctx->g;
     p.hd = ctx->hd;
     p.max_blocks_per_seq = ctx->max_blocks_per_seq;
     p.scale_log2e = ctx->scale * 1.4426950408889634f;
-    p.n_ditems = (int32_t)ctx->n_ditems;
-    p.n_ptiles = (int32_t)ctx->n_ptiles;
-    p.n_mitems = (int32_t)ctx->n_mitems;
+    p.num_seqs = num_seqs;
+    p.total_q = total_q_tokens;
+    p.dec_blocks = pl.dec_blocks;
+    p.static_blocks = pl.static_blocks;
+    p.static_runs = pl.static_runs;
+    p.tail_runs = pl.tail_runs;
+    p.queue = reinterpret_cast<uint32_t *>(ctx->counters + kCounterInts - 1);
+    p.queue_base = ctx->queue_base;
+    p.n_tiles = pl.n_tiles;
+    p.nbi = (int32_t)ctx->opt_nbi;
+    p.rotate_heads = (int32_t)ctx->opt_rotate;
 
     hipEvent_t *ev = nullptr;
     hipError_t e = hipSuccess;
@@ -526,20 +559,29 @@ ooco_status ooco_attn_mixed(ooco_ctx *ctx, const void *q, const void *k_cache, c
             return fail(ctx, OOCO_EINVAL, "ooco_attn_mixed: more than %d profiled calls without ooco_profile_read",
                         kProfSlots);
         if (ctx->prof_ev.empty()) {
-            ctx->prof_ev.assign((size_t)4 * kProfSlots, nullptr);
+            ctx->prof_ev.assign((size_t)3 * kProfSlots, nullptr);
             for (auto &x : ctx->prof_ev)
                 if (e == hipSuccess) e = hipEventCreate(&x);
             if (e != hipSuccess) return fail(ctx, OOCO_EHIP, "ooco_attn_mixed: %s", hipGetErrorString(e));
         }
-        ev = ctx->prof_ev.data() + 4 * ctx->prof_calls++;
+        ev = ctx->prof_ev.data() + 3 * ctx->prof_calls++;
     }
     if (ev) e = hipEventRecord(ev[0], s);
-    if (e == hipSuccess) e = launch_prefill(p, s);
+    if (e == hipSuccess && pl.n_tiles > 0) {
+        p.cum_dev = inline_cum ? nullptr : ctx->plan_d + n_cum;
+        if (inline_cum) memcpy(ka.cum, pl.tcum.data(), n_cum * sizeof(int32_t));
+        e = launch_prefill(ka, s);
+    }
     if (ev && e == hipSuccess) e = hipEventRecord(ev[1], s);
-    if (e == hipSuccess) e = launch_decode(p, s);
+    if (e == hipSuccess && pl.static_runs > 0) {
+        p.cum_dev = inline_cum ? nullptr : ctx->plan_d;
+        if (inline_cum) memcpy(ka.cum, pl.dcum.data(), n_cum * sizeof(int32_t));
+        e = launch_decode(ka, s);
+        // every wave draws one ticket per tail run it takes plus one that tells it to stop
+        if (e == hipSuccess && pl.tail_runs > 0)
+            ctx->queue_base += (uint32_t)pl.tail_runs * (uint32_t)ctx->Hkv + (uint32_t)pl.static_runs * (uint32_t)ctx->Hkv;
+    }
     if (ev && e == hipSuccess) e = hipEventRecord(ev[2], s);
-    if (e == hipSuccess) e = launch_merge(p, s);
-    if (ev && e == hipSuccess) e = hipEventRecord(ev[3], s);
     if (ctx->plan_one_shot) {
         ctx->plan_one_shot = false;
         ctx->plan_valid = false;

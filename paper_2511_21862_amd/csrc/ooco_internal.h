@@ -1,5 +1,21 @@
 // Internal declarations shared by the host side (plan, ABI) and the kernel launchers of
 // libooco.  Not part of the public ABI.
+//
+// Work decomposition (computed by every wave from a small cumulative array, no work lists):
+//   decode  - the KV blocks of all decode sequences, laid end to end in sequence order, form one
+//             line of `dec_blocks` blocks.  Its first `static_blocks` blocks are cut into
+//             `static_runs` equal runs, one per launched wave and kv head; the rest into
+//             `tail_runs` short runs that the waves fetch from a shared ticket counter when they
+//             are done with their own run, so that faster waves (XCDs differ by several percent
+//             in delivered bandwidth) end up streaming more blocks.  Where a run crosses sequence
+//             boundaries it has several pieces.
+//             cum[i] = number of decode blocks before sequence i (cum[num_seqs] = dec_blocks).
+//             A piece that does not cover its whole sequence writes a partial result into slot
+//             (run index) + i; the last piece of a sequence to finish merges the slots (arrival
+//             counter per sequence and kv head).
+//   prefill - cum[i] = number of query tiles (kPrefillRows rows each) before sequence i.
+// The cumulative array travels inside the kernel arguments (no upload, no synchronisation) when
+// the batch has at most kInlineSeqs sequences, else through a device buffer.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -7,64 +23,75 @@
 
 namespace ooco {
 
-constexpr int kBlockSize = 16;     // tokens per KV block (fixed by the cache layout)
-constexpr int kPrefillRows = 32;   // query rows per prefill tile of the simple kernel
-
-// One decode work item: query row `q_row` of sequence `seq` against KV blocks
-// [blk_begin, blk_end) of that sequence.  part < 0: the item covers the whole sequence and
-// writes bf16 output directly; otherwise it writes partial (acc, m, l) number `part`.
-struct DecodeItem {
-    int32_t seq;
-    int32_t q_row;
-    int32_t blk_begin;
-    int32_t blk_end;
-    int32_t seq_len;
-    int32_t part;
-    int32_t pad0, pad1;
-};
-
-// One prefill tile: `rows` consecutive query rows starting at global row `q_row0`, whose first
-// row sits at absolute position `pos0` of sequence `seq`.
-struct PrefillTile {
-    int32_t seq;
-    int32_t q_row0;
-    int32_t rows;
-    int32_t pos0;
-    int32_t seq_len;
-    int32_t pad0, pad1, pad2;
-};
-
-// One decode sequence whose parts [part0, part0 + nparts) must be merged into row q_row.
-struct MergeItem {
-    int32_t q_row;
-    int32_t part0;
-    int32_t nparts;
-    int32_t pad0;
-};
+constexpr int kBlockSize = 16;      // tokens per KV block (fixed by the cache layout)
+constexpr int kPrefillRows = 32;    // query rows per prefill tile
+constexpr int kInlineSeqs = 960;    // sequences whose cumulative array fits the kernel arguments
 
 struct AttnParams {
     const uint16_t *q;
     const uint16_t *k_cache;
     const uint16_t *v_cache;
     const int32_t *block_tables;
+    const int32_t *seq_lens;
+    const int32_t *query_start_loc;
+    const int32_t *ctx_lens;
     uint16_t *out;
-    float *part_acc;            // [parts][Hq][hd]
-    float *part_ml;             // [parts][Hq][2]   (running max in log2 units, sum)
-    const DecodeItem *ditems;
-    const PrefillTile *ptiles;
-    const MergeItem *mitems;
+    float *part_acc;            // [slots][Hq][hd]   un-normalised partial outputs
+    float *part_ml;             // [slots][Hq][2]    (running max in log2 units, sum)
+    int32_t *counters;          // [num_seqs][Hkv]   arrival counters, zero between calls
+    const int32_t *cum_dev;     // cumulative array in device memory, or NULL (inline array used)
+    uint64_t *trace;            // NULL, or [decode waves][4] time stamps (option "trace")
     int32_t Hq, Hkv, g, hd;
     int32_t max_blocks_per_seq;
     float scale_log2e;          // softmax scale * log2(e)
-    int32_t n_ditems, n_ptiles, n_mitems;
+    int32_t num_seqs, total_q;
+    int32_t dec_blocks, static_blocks, static_runs, tail_runs;   // decode run layout
+    int32_t n_tiles;
+    int32_t nbi;                // tuning: KV blocks per softmax step of the decode kernel
+    int32_t rotate_heads;       // tuning: kv head rotation across XCDs
+    uint32_t queue_base;        // ticket value at which this launch's tail runs start
+    uint32_t *queue;            // ticket counter for the tail runs (monotonic across launches)
 };
 
-// Launchers (ooco_kernels.hip).  Each returns the hipError_t of its launch.
-hipError_t launch_decode(const AttnParams &p, hipStream_t s);
-hipError_t launch_prefill(const AttnParams &p, hipStream_t s);
-hipError_t launch_merge(const AttnParams &p, hipStream_t s);
+struct KernArgs {
+    AttnParams p;
+    int32_t cum[kInlineSeqs + 1];
+};
+static_assert(sizeof(KernArgs) <= 4096, "kernel arguments must stay within 4 KiB");
+
+// Launchers (ooco_kernels.hip).  `a.cum` must hold the decode resp. prefill cumulative array
+// unless a.p.cum_dev is set.  Each returns the hipError_t of its launch.
+hipError_t launch_decode(const KernArgs &a, hipStream_t s);
+hipError_t launch_prefill(const KernArgs &a, hipStream_t s);
 hipError_t launch_block_copy(const void *k_src, const void *v_src, void *k_dst, void *v_dst,
                              const int64_t *src_ids, const int64_t *dst_ids, int64_t num_pairs,
                              int64_t block_bytes, hipStream_t s);
+
+// n blocks cut into s equal runs, run k = [n*k/s, n*(k+1)/s): index of the run holding block x.
+__host__ __device__ inline int32_t segment_of(int64_t x, int64_t s, int64_t n)
+{
+    return (int32_t)((((uint64_t)x + 1u) * (uint64_t)s - 1u) / (uint64_t)n);
+}
+
+// The two-level run layout of the decode line (host and device use the same functions).
+struct RunLayout {
+    int32_t dec_blocks, static_blocks, static_runs, tail_runs;
+};
+__host__ __device__ inline void run_bounds(const RunLayout &L, int32_t v, int32_t &lo, int32_t &hi)
+{
+    if (v < L.static_runs) {
+        lo = (int32_t)((int64_t)L.static_blocks * v / L.static_runs);
+        hi = (int32_t)((int64_t)L.static_blocks * (v + 1) / L.static_runs);
+    } else {
+        const int64_t t = v - L.static_runs, tb = L.dec_blocks - L.static_blocks;
+        lo = L.static_blocks + (int32_t)(tb * t / L.tail_runs);
+        hi = L.static_blocks + (int32_t)(tb * (t + 1) / L.tail_runs);
+    }
+}
+__host__ __device__ inline int32_t run_of(const RunLayout &L, int64_t x)
+{
+    if (x < L.static_blocks) return segment_of(x, L.static_runs, L.static_blocks);
+    return L.static_runs + segment_of(x - L.static_blocks, L.tail_runs, (int64_t)L.dec_blocks - L.static_blocks);
+}
 
 }  // namespace ooco

@@ -36,12 +36,82 @@ OOCO_DEV uint32_t pack2_bf16(float a, float b)
 
 OOCO_DEV float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-OOCO_DEV float xor_max(float v, int mask) { return fmaxf(v, __shfl_xor(v, mask, 64)); }
-OOCO_DEV float xor_sum(float v, int mask) { return v + __shfl_xor(v, mask, 64); }
+// Device-scope (all XCDs) relaxed store / load of one float: the store writes through to memory,
+// the load bypasses the non-coherent cache levels.
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+OOCO_DEV void store_dev2(float *ptr, float a, float b)   // ptr is 8-byte aligned
+{
+    const f32x2 v = {a, b};
+    __hip_atomic_store(reinterpret_cast<uint64_t *>(ptr), __builtin_bit_cast(uint64_t, v), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+}
+OOCO_DEV f32x2 load_dev2(const float *ptr)
+{
+    const uint64_t u = __hip_atomic_load(reinterpret_cast<uint64_t *>(const_cast<float *>(ptr)), __ATOMIC_RELAXED,
+                                         __HIP_MEMORY_SCOPE_AGENT);
+    return __builtin_bit_cast(f32x2, u);
+}
+
 
 // ------------------------------------------------------------------------------------------
-// Decode: one wave per (work item, kv head).  The wave walks KV blocks [blk_begin, blk_end) of
-// one sequence.  Per 16-token block:
+// Cross-lane reductions over the four 16-lane rows of a wave with the CDNA4 lane-swap
+// instructions (VALU only, no LDS traffic): v_permlane16_swap exchanges the odd rows of its first
+// operand with the even rows of the second, v_permlane32_swap the upper half of the first with
+// the lower half of the second; fed with two copies of one value they return both partners of
+// an xor-16 / xor-32 butterfly.  (Vector elements are copied to scalars before
+// __builtin_bit_cast: a bit_cast applied directly to an element reference reads element 0.)
+OOCO_DEV void swap16(float v, float &lo, float &hi)
+{
+    const unsigned u = __builtin_bit_cast(unsigned, v);
+    const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    const unsigned a0 = a[0], a1 = a[1];
+    lo = __builtin_bit_cast(float, a0);
+    hi = __builtin_bit_cast(float, a1);
+}
+OOCO_DEV void swap32(float v, float &lo, float &hi)
+{
+    const unsigned u = __builtin_bit_cast(unsigned, v);
+    const auto a = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    const unsigned a0 = a[0], a1 = a[1];
+    lo = __builtin_bit_cast(float, a0);
+    hi = __builtin_bit_cast(float, a1);
+}
+OOCO_DEV float rows_max(float v)
+{
+    float x, y;
+    swap16(v, x, y);
+    swap32(fmaxf(x, y), x, y);
+    return fmaxf(x, y);
+}
+OOCO_DEV float rows_sum(float v)
+{
+    float x, y;
+    swap16(v, x, y);
+    swap32(x + y, x, y);
+    return x + y;
+}
+
+// ------------------------------------------------------------------------------------------
+// Work lookup shared by both kernels: cum[] is non-decreasing with cum[0] = 0; returns the number
+// of entries j in [1, n] with cum[j] <= x, i.e. the index i with cum[i] <= x < cum[i+1].
+// All 64 lanes of the wave must call it with the same x.
+template <class CumAt>
+OOCO_DEV int count_le(CumAt cum_at, int n, int x, int lane)
+{
+    int cnt = 0;
+    for (int base = 1; base <= n; base += 64) {
+        const int idx = base + lane;
+        const int v = idx <= n ? cum_at(idx) : 0x7FFFFFFF;
+        const int c = __popcll(__ballot(v <= x));
+        cnt += c;
+        if (c < 64) break;
+    }
+    return cnt;
+}
+
+// ------------------------------------------------------------------------------------------
+// Decode: one wave per (run k of the decode block line, kv head).  A wave walks the pieces of its
+// run one after the other; a piece is a range of KV blocks of one sequence.  Per 16-token block:
 //   S^T[16 tok][16 heads] = K[16 tok][hd] · Q^T[hd][16 heads]      (hd/32 x v_mfma_f32_16x16x32_bf16)
 //   O^T[hd][16 heads]    += V^T[hd][16 tok] · P^T[16 tok][16 heads] (hd/16 x v_mfma_f32_16x16x16_bf16)
 // Head columns >= g (the GQA group size) carry zeros.  Lane l = 16*kq + col:
@@ -49,207 +119,283 @@ OOCO_DEV float xor_sum(float v, int mask) { return v + __shfl_xor(v, mask, 64); 
 //   S^T result reg r:    token 4kq + r, head col
 //   V operand, group nb: 8 B at tile offset ((16nb + col)*16 + 4kq)*2   (dim 16nb+col, tokens 4kq..+4)
 //   O^T result reg r:    dim 16nb + 4kq + r, head col
-// NBI blocks are processed per softmax step, and the loads of the next step are issued before
-// the arithmetic of the current one (two register sets).
+// One K and one V register set: the K loads of block j+1 are issued right after the QK MFMAs of
+// block j have consumed the K registers, the V loads of block j+1 right after the PV MFMAs;
+// memory latency is covered by several resident waves per SIMD (the kernel stays under 128
+// VGPRs) rather than by a second register set.
+//
+// A piece that covers its whole sequence normalises and stores bf16 output.  Any other piece
+// stores (acc, m, l) in fp32 into partial slot k + seq, then bumps the arrival counter of
+// (seq, kv head); the piece that arrives last merges all slots of the sequence in slot order
+// (so the result does not depend on which piece is last) and resets the counter.
 template <int HD, int NBI>
-__global__ __launch_bounds__(64) void decode_kernel(const AttnParams p)
+__global__ __launch_bounds__(64) void decode_kernel(const KernArgs a)
 {
     constexpr int KC = HD / 32;
     constexpr int NB = HD / 16;
+    const AttnParams &p = a.p;
     const int lane = threadIdx.x;
     const int col = lane & 15;
     const int kq = lane >> 4;
-    const int item_idx = blockIdx.x / p.Hkv;
-    const int kvh = blockIdx.x - item_idx * p.Hkv;
-    const DecodeItem it = p.ditems[item_idx];
+    // Workgroups are handed to the XCDs round-robin and the kv heads of a block lie in adjacent
+    // 4 KiB pieces of memory: rotating the head by the run index gives every XCD every kv head
+    // in turn instead of pinning XCD x to head x.
+    int run = blockIdx.x / p.Hkv;
+    int kvh = p.rotate_heads ? (int)((blockIdx.x - run * p.Hkv + run) % p.Hkv) : (int)(blockIdx.x - run * p.Hkv);
     const int g = p.g;
-    const int head = kvh * g + col;
-    const int nblk = it.blk_end - it.blk_begin;
-    const int niter = (nblk + NBI - 1) / NBI;
-
-    // Q as B operand: head col, dims 32c + 8kq .. +8
-    u32x4 qb[KC];
-    {
-        const u32x4 *qp = reinterpret_cast<const u32x4 *>(p.q + ((int64_t)it.q_row * p.Hq + (col < g ? head : 0)) * HD);
-#pragma unroll
-        for (int c = 0; c < KC; ++c) {
-            u32x4 t = qp[c * 4 + kq];
-            qb[c] = (col < g) ? t : u32x4{0u, 0u, 0u, 0u};
-        }
-    }
-
-    // rolling window of 64 physical block ids, one per lane
-    const int32_t *table = p.block_tables + (int64_t)it.seq * p.max_blocks_per_seq + it.blk_begin;
-    int wbase = 0;
-    int idv = table[min(lane, nblk - 1)];
-    int idn = table[min(64 + lane, nblk - 1)];
-
     const int64_t tile_elems = (int64_t)HD * kBlockSize;   // one (block, kv head) tile
-    struct KV {
-        u32x4 k[NBI][KC];
-        u32x2 v[NBI][NB];
-    };
+    auto cum_at = [&](int idx) -> int { return p.cum_dev ? p.cum_dev[idx] : a.cum[idx]; };
+    const RunLayout L = {p.dec_blocks, p.static_blocks, p.static_runs, p.tail_runs};
+    const unsigned tail_tasks = (unsigned)p.tail_runs * (unsigned)p.Hkv;
 
-    auto load = [&](KV &t, int iter) {
-        const int j0 = iter * NBI;
-        if (j0 - wbase >= 64) {
-            wbase += 64;
-            idv = idn;
-            idn = table[min(wbase + 64 + lane, nblk - 1)];
+    uint64_t *trace = p.trace ? p.trace + (int64_t)blockIdx.x * 4 : nullptr;   // per-wave time stamps
+    if (trace && lane == 0) trace[0] = wall_clock64();
+    bool first_piece = true;
+
+  for (;;) {   // the wave's own run first, then tail runs by ticket
+    // The ticket for the next tail run is drawn now and looked at after this run, so that the
+    // round trip of the atomic overlaps the streaming.
+    unsigned ticket = 0xFFFFFFFFu;
+    if (tail_tasks && lane == 0)
+        ticket = __hip_atomic_fetch_add(p.queue, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - p.queue_base;
+    const int head = kvh * g + col;
+    int lo, hi;
+    run_bounds(L, run, lo, hi);
+    int seq = count_le(cum_at, p.num_seqs, lo, lane);
+    int pos = lo;
+    while (pos < hi) {
+        seq = __builtin_amdgcn_readfirstlane(seq);
+        int cs = cum_at(seq), ce = cum_at(seq + 1);
+        while (ce <= pos) {   // sequences without decode blocks
+            ++seq;
+            cs = ce;
+            ce = cum_at(seq + 1);
         }
+        const int stop = min(hi, ce);
+        const int blk_begin = pos - cs;
+        const int nblk = stop - pos;
+        const bool whole = (pos == cs) && (stop == ce);
+        const int seq_len = p.seq_lens[seq];
+        const int q_row = min(max(p.query_start_loc[seq], 0), p.total_q - 1);
+
+        // Q as B operand: head col, dims 32c + 8kq .. +8
+        u32x4 qb[KC];
+        {
+            const u32x4 *qp = reinterpret_cast<const u32x4 *>(p.q + ((int64_t)q_row * p.Hq + (col < g ? head : 0)) * HD);
 #pragma unroll
-        for (int u = 0; u < NBI; ++u) {
-            const int j = min(j0 + u, nblk - 1);
+            for (int c = 0; c < KC; ++c) {
+                u32x4 t = qp[c * 4 + kq];
+                qb[c] = (col < g) ? t : u32x4{0u, 0u, 0u, 0u};
+            }
+        }
+        // rolling window of 64 physical block ids, one per lane
+        const int32_t *table = p.block_tables + (int64_t)seq * p.max_blocks_per_seq + blk_begin;
+        int wbase = 0;
+        int idv = table[min(lane, nblk - 1)];
+        int idn = table[min(64 + lane, nblk - 1)];
+
+        u32x4 kreg[NBI][KC];
+        u32x2 vreg[NBI][NB];
+        int64_t offs[NBI];
+        auto tile_off = [&](int j) -> int64_t {   // j is wave-uniform and non-decreasing
+            if (j - wbase >= 64) {
+                wbase += 64;
+                idv = idn;
+                idn = table[min(wbase + 64 + lane, nblk - 1)];
+            }
             const int pb = __builtin_amdgcn_readlane(idv, j - wbase);
-            const int64_t off = ((int64_t)pb * p.Hkv + kvh) * tile_elems;
-            const u32x4 *kp = reinterpret_cast<const u32x4 *>(p.k_cache + off);
-            const u32x2 *vp = reinterpret_cast<const u32x2 *>(p.v_cache + off);
+            return ((int64_t)pb * p.Hkv + kvh) * tile_elems;
+        };
+        // Loads are issued unconditionally (steps past the end re-read the last block, an L2 hit)
+        // so that every step has the same number of loads in flight and the waits before the
+        // MFMAs can leave the younger loads outstanding.
+        auto issue_k = [&](int step) {
 #pragma unroll
-            for (int c = 0; c < KC; ++c) t.k[u][c] = kp[c * 64 + lane];
+            for (int u = 0; u < NBI; ++u) {
+                offs[u] = tile_off(min(step * NBI + u, nblk - 1));
+                const u32x4 *kp = reinterpret_cast<const u32x4 *>(p.k_cache + offs[u]);
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) t.v[u][nb] = vp[(nb * 16 + col) * 4 + kq];
-        }
-    };
+                for (int c = 0; c < KC; ++c) kreg[u][c] = kp[c * 64 + lane];
+            }
+        };
+        auto issue_v = [&]() {
+#pragma unroll
+            for (int u = 0; u < NBI; ++u) {
+                const u32x2 *vp = reinterpret_cast<const u32x2 *>(p.v_cache + offs[u]);
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) vreg[u][nb] = vp[(nb * 16 + col) * 4 + kq];
+            }
+        };
 
-    f32x4 O[NB];
+        f32x4 O[NB];
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) O[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float m = -INFINITY, lsum = 0.f;
+        for (int nb = 0; nb < NB; ++nb) O[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        float m = -INFINITY, lsum = 0.f;
 
-    auto compute = [&](KV &t, int iter) {
-        f32x4 S[NBI];
-#pragma unroll
-        for (int u = 0; u < NBI; ++u) {
-            S[u] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int c = 0; c < KC; ++c)
-                S[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, t.k[u][c]),
-                                                               __builtin_bit_cast(bf16x8, qb[c]), S[u], 0, 0, 0);
+        const int nstep = (nblk + NBI - 1) / NBI;
+        issue_k(0);
+        issue_v();
+        if (trace && first_piece) {   // time at which the first K/V tiles of the wave have arrived
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            if (lane == 0) trace[1] = wall_clock64();
+            first_piece = false;
         }
-        float mloc = -INFINITY;
+        for (int t = 0; t < nstep; ++t) {
+            f32x4 S[NBI];
 #pragma unroll
-        for (int u = 0; u < NBI; ++u) {
-            const int j = iter * NBI + u;
-            int nvalid = it.seq_len - (it.blk_begin + j) * kBlockSize;
-            nvalid = (j < nblk) ? nvalid : 0;
-            if (nvalid < kBlockSize) {   // wave-uniform: tail block of the sequence, or past the item
+            for (int u = 0; u < NBI; ++u) {
+                S[u] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int r = 0; r < 4; ++r) S[u][r] = (4 * kq + r < nvalid) ? S[u][r] * p.scale_log2e : -INFINITY;
-                const uint32_t m0 = (4 * kq + 0 < nvalid ? 0x0000FFFFu : 0u) | (4 * kq + 1 < nvalid ? 0xFFFF0000u : 0u);
-                const uint32_t m1 = (4 * kq + 2 < nvalid ? 0x0000FFFFu : 0u) | (4 * kq + 3 < nvalid ? 0xFFFF0000u : 0u);
+                for (int c = 0; c < KC; ++c)
+                    S[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kreg[u][c]),
+                                                                   __builtin_bit_cast(bf16x8, qb[c]), S[u], 0, 0, 0);
+            }
+            issue_k(min(t + 1, nstep - 1));
+            float mloc = -INFINITY;
+#pragma unroll
+            for (int u = 0; u < NBI; ++u) {
+                const int j = t * NBI + u;
+                int nvalid = seq_len - (blk_begin + j) * kBlockSize;
+                if (NBI > 1 && j >= nblk) nvalid = 0;
+                if (nvalid < kBlockSize) {   // wave-uniform: tail block of the sequence, or past the piece
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) S[u][r] = (4 * kq + r < nvalid) ? S[u][r] * p.scale_log2e : -INFINITY;
+                    const uint32_t m0 = (4 * kq + 0 < nvalid ? 0x0000FFFFu : 0u) | (4 * kq + 1 < nvalid ? 0xFFFF0000u : 0u);
+                    const uint32_t m1 = (4 * kq + 2 < nvalid ? 0x0000FFFFu : 0u) | (4 * kq + 3 < nvalid ? 0xFFFF0000u : 0u);
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) {
+                        vreg[u][nb][0] &= m0;
+                        vreg[u][nb][1] &= m1;
+                    }
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) S[u][r] *= p.scale_log2e;
+                }
+                mloc = fmaxf(mloc, fmaxf(fmaxf(S[u][0], S[u][1]), fmaxf(S[u][2], S[u][3])));
+            }
+            mloc = rows_max(mloc);
+            const float m_new = fmaxf(m, mloc);
+            const float alpha = fast_exp2(m - m_new);
+            const bool grow = m_new > m;
+            m = m_new;
+            float psum = 0.f;
+            s16x4 P[NBI];
+#pragma unroll
+            for (int u = 0; u < NBI; ++u) {
+                float e[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) e[r] = fast_exp2(S[u][r] - m_new);
+                psum += (e[0] + e[1]) + (e[2] + e[3]);
+                const u32x2 pk = {pack2_bf16(e[0], e[1]), pack2_bf16(e[2], e[3])};
+                P[u] = __builtin_bit_cast(s16x4, pk);
+            }
+            lsum = lsum * alpha + psum;
+            if (__any(grow)) {
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) O[nb][r] *= alpha;
+            }
+#pragma unroll
+            for (int u = 0; u < NBI; ++u)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+                    O[nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, vreg[u][nb]), P[u],
+                                                                      O[nb], 0, 0, 0);
+            issue_v();
+        }
+
+        if (trace && stop == hi && lane == 0) trace[2] = wall_clock64();   // end of streaming
+        float ltot = rows_sum(lsum);
+        bool store_out = whole;
+        if (!whole) {
+            // ---- partial result into slot run + seq, then arrival count.  Partials are written
+            // and read with device-scope accesses (write-through / L2-bypassing), so that pieces
+            // running on other XCDs see them without any whole-cache write-back or invalidate.
+            if (col < g) {
+                const int64_t row = (int64_t)(run + seq) * p.Hq + head;
+                float *ap = p.part_acc + row * HD + 4 * kq;
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
-                    t.v[u][nb][0] &= m0;
-                    t.v[u][nb][1] &= m1;
+                    store_dev2(ap + nb * 16, O[nb][0], O[nb][1]);
+                    store_dev2(ap + nb * 16 + 2, O[nb][2], O[nb][3]);
                 }
-            } else {
-#pragma unroll
-                for (int r = 0; r < 4; ++r) S[u][r] *= p.scale_log2e;
+                if (kq == 0) store_dev2(p.part_ml + row * 2, m, ltot);
             }
+            const int first_run = run_of(L, cs);
+            const int nparts = run_of(L, (int64_t)ce - 1) - first_run + 1;
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the partial has reached memory before the count
+            int prev = 0;
+            if (lane == 0)
+                prev = __hip_atomic_fetch_add(p.counters + (int64_t)seq * p.Hkv + kvh, 1, __ATOMIC_RELAXED,
+                                              __HIP_MEMORY_SCOPE_AGENT);
+            prev = __builtin_amdgcn_readfirstlane(prev);
+            if (prev == nparts - 1) {   // last piece of this (sequence, kv head): merge, in slot order
+                float M = -INFINITY;
+                ltot = 0.f;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) mloc = fmaxf(mloc, S[u][r]);
-        }
-        mloc = xor_max(mloc, 16);
-        mloc = xor_max(mloc, 32);
-        const float m_new = fmaxf(m, mloc);
-        const float alpha = fast_exp2(m - m_new);
-        const bool grow = m_new > m;
-        m = m_new;
-        float psum = 0.f;
-        s16x4 P[NBI];
+                for (int nb = 0; nb < NB; ++nb) O[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+                // parts are fetched three at a time so that their memory round trips overlap
+                constexpr int MBATCH = 3;
+                for (int s0 = 0; s0 < nparts; s0 += MBATCH) {
+                    f32x2 ml[MBATCH];
+                    f32x2 t[MBATCH][NB][2];
 #pragma unroll
-        for (int u = 0; u < NBI; ++u) {
-            float e[4];
+                    for (int b = 0; b < MBATCH; ++b) {
+                        const int sidx = min(s0 + b, nparts - 1);
+                        const int64_t row = (int64_t)(first_run + sidx + seq) * p.Hq + (col < g ? head : kvh * g);
+                        ml[b] = load_dev2(p.part_ml + row * 2);
+                        const float *ap = p.part_acc + row * HD + 4 * kq;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                e[r] = fast_exp2(S[u][r] - m_new);
-                psum += e[r];
+                        for (int nb = 0; nb < NB; ++nb) {
+                            t[b][nb][0] = load_dev2(ap + nb * 16);
+                            t[b][nb][1] = load_dev2(ap + nb * 16 + 2);
+                        }
+                    }
+#pragma unroll
+                    for (int b = 0; b < MBATCH; ++b) {
+                        if (s0 + b < nparts) {
+                            const float M_new = fmaxf(M, ml[b][0]);
+                            const float w_old = fast_exp2(M - M_new), w_new = fast_exp2(ml[b][0] - M_new);
+                            M = M_new;
+                            ltot = ltot * w_old + ml[b][1] * w_new;
+#pragma unroll
+                            for (int nb = 0; nb < NB; ++nb) {
+                                O[nb][0] = O[nb][0] * w_old + t[b][nb][0][0] * w_new;
+                                O[nb][1] = O[nb][1] * w_old + t[b][nb][0][1] * w_new;
+                                O[nb][2] = O[nb][2] * w_old + t[b][nb][1][0] * w_new;
+                                O[nb][3] = O[nb][3] * w_old + t[b][nb][1][1] * w_new;
+                            }
+                        }
+                    }
+                }
+                if (lane == 0)   // ready for the next call
+                    __hip_atomic_store(p.counters + (int64_t)seq * p.Hkv + kvh, 0, __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+                store_out = true;
             }
-            u32x2 pk = {pack2_bf16(e[0], e[1]), pack2_bf16(e[2], e[3])};
-            P[u] = __builtin_bit_cast(s16x4, pk);
         }
-        lsum = lsum * alpha + psum;
-        if (__any(grow)) {
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) O[nb][r] *= alpha;
-        }
-#pragma unroll
-        for (int u = 0; u < NBI; ++u)
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-                O[nb] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, t.v[u][nb]), P[u], O[nb], 0, 0, 0);
-    };
-
-    KV A, B;
-    load(A, 0);
-    int i = 0;
-    for (; i + 1 < niter; i += 2) {
-        load(B, i + 1);
-        compute(A, i);
-        if (i + 2 < niter) load(A, i + 2);
-        compute(B, i + 1);
-    }
-    if (i < niter) compute(A, i);
-
-    float ltot = xor_sum(lsum, 16);
-    ltot = xor_sum(ltot, 32);
-    if (col < g) {
-        if (it.part < 0) {
+        if (store_out && col < g) {
             const float inv = 1.0f / ltot;
-            uint16_t *op = p.out + ((int64_t)it.q_row * p.Hq + head) * HD + 4 * kq;
+            uint16_t *op = p.out + ((int64_t)q_row * p.Hq + head) * HD + 4 * kq;
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
                 u32x2 w = {pack2_bf16(O[nb][0] * inv, O[nb][1] * inv), pack2_bf16(O[nb][2] * inv, O[nb][3] * inv)};
                 *reinterpret_cast<u32x2 *>(op + nb * 16) = w;
             }
-        } else {
-            float *ap = p.part_acc + ((int64_t)it.part * p.Hq + head) * HD + 4 * kq;
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) *reinterpret_cast<f32x4 *>(ap + nb * 16) = O[nb];
-            if (kq == 0) {
-                float *mp = p.part_ml + ((int64_t)it.part * p.Hq + head) * 2;
-                mp[0] = m;
-                mp[1] = ltot;
-            }
         }
+        pos = stop;
+        ++seq;
     }
-}
-
-// ------------------------------------------------------------------------------------------
-// Merge of split-KV partials: out = sum_s acc_s 2^(m_s-M) / sum_s l_s 2^(m_s-M), M = max_s m_s.
-// One wave per (sequence, query head); lane owns hd/64 consecutive dims.  Parts are visited in
-// order, so the result does not depend on launch timing.
-template <int HD>
-__global__ __launch_bounds__(64) void merge_kernel(const AttnParams p)
-{
-    constexpr int PER = HD / 64;
-    const int lane = threadIdx.x;
-    const int mi = blockIdx.x / p.Hq;
-    const int head = blockIdx.x - mi * p.Hq;
-    const MergeItem it = p.mitems[mi];
-    float M = -INFINITY;
-    for (int s = 0; s < it.nparts; ++s) M = fmaxf(M, p.part_ml[((int64_t)(it.part0 + s) * p.Hq + head) * 2]);
-    float L = 0.f;
-    float acc[PER];
-#pragma unroll
-    for (int d = 0; d < PER; ++d) acc[d] = 0.f;
-    for (int s = 0; s < it.nparts; ++s) {
-        const int64_t row = (int64_t)(it.part0 + s) * p.Hq + head;
-        const float w = fast_exp2(p.part_ml[row * 2] - M);
-        L += p.part_ml[row * 2 + 1] * w;
-        const float *ap = p.part_acc + row * HD + lane * PER;
-#pragma unroll
-        for (int d = 0; d < PER; ++d) acc[d] += ap[d] * w;
-    }
-    const float inv = 1.0f / L;
-    uint16_t *op = p.out + ((int64_t)it.q_row * p.Hq + head) * HD + lane * PER;
-    if constexpr (PER == 2) {
-        *reinterpret_cast<uint32_t *>(op) = pack2_bf16(acc[0] * inv, acc[1] * inv);
-    } else {
-        const uint32_t w = pack2_bf16(acc[0] * inv, 0.f);
-        op[0] = (uint16_t)(w & 0xFFFFu);
+    if (!tail_tasks) break;
+    ticket = __builtin_amdgcn_readfirstlane(ticket);
+    if (ticket >= tail_tasks) break;
+    run = p.static_runs + (int)(ticket / (unsigned)p.Hkv);
+    kvh = (int)(ticket % (unsigned)p.Hkv);
+  }
+    if (trace) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        if (lane == 0) trace[3] = wall_clock64();
     }
 }
 
@@ -262,8 +408,9 @@ __global__ __launch_bounds__(64) void merge_kernel(const AttnParams p)
 // swapped) of its block, so that S^T register r of lane (col, h) is token 16(r/8) + 8h + r%8 of
 // the pair: eight consecutive tokens per block, which is what one 16-byte V operand load holds.
 template <int HD>
-__global__ __launch_bounds__(64) void prefill_kernel(const AttnParams p)
+__global__ __launch_bounds__(64) void prefill_kernel(const KernArgs a)
 {
+    const AttnParams &p = a.p;
     constexpr int KS = HD / 16;   // k-steps of QK
     constexpr int MB = HD / 32;   // 32-dim groups of the output
     const int lane = threadIdx.x;
@@ -271,7 +418,29 @@ __global__ __launch_bounds__(64) void prefill_kernel(const AttnParams p)
     const int h = lane >> 5;
     const int tile_idx = blockIdx.x / p.Hq;
     const int head = blockIdx.x - tile_idx * p.Hq;
-    const PrefillTile tl = p.ptiles[tile_idx];
+    // tile -> (sequence, tile of the sequence); tiles of a sequence are taken last-first because
+    // the later rows of a chunk see more keys and the hardware dispatches in index order
+    struct {
+        int seq, q_row0, rows, pos0, seq_len;
+    } tl;
+    {
+        auto cum_at = [&](int idx) -> int { return p.cum_dev ? p.cum_dev[idx] : a.cum[idx]; };
+        tl.seq = __builtin_amdgcn_readfirstlane(count_le(cum_at, p.num_seqs, tile_idx, lane));
+        const int t_first = cum_at(tl.seq), t_end = cum_at(tl.seq + 1);
+        const int t = (t_end - 1) - tile_idx;             // reversed order inside the sequence
+        (void)t_first;
+        const int q0 = p.query_start_loc[tl.seq];
+        const int q_len = p.query_start_loc[tl.seq + 1] - q0;
+        const int t0 = t * kPrefillRows;
+        tl.q_row0 = min(max(q0 + t0, 0), p.total_q - 1);
+        tl.rows = max(1, min(min(kPrefillRows, q_len - t0), p.total_q - tl.q_row0));
+        tl.pos0 = p.ctx_lens[tl.seq] + t0;
+        tl.seq_len = p.seq_lens[tl.seq];
+        // keys beyond what the plan allotted to this sequence are never touched
+        const int cap = p.max_blocks_per_seq * kBlockSize;
+        tl.pos0 = min(max(tl.pos0, 0), cap - tl.rows);
+        tl.seq_len = min(tl.seq_len, cap);
+    }
     const int kvh = head / p.g;
     const int row = min(col, tl.rows - 1);
     const int pos = tl.pos0 + row;                       // this lane column's absolute position
@@ -348,7 +517,11 @@ __global__ __launch_bounds__(64) void prefill_kernel(const AttnParams p)
         float mloc = S[0];
 #pragma unroll
         for (int r = 1; r < 16; ++r) mloc = fmaxf(mloc, S[r]);
-        mloc = xor_max(mloc, 32);
+        {
+            float x, y;
+            swap32(mloc, x, y);
+            mloc = fmaxf(x, y);
+        }
         const float m_new = fmaxf(m, mloc);
         const float alpha = fast_exp2(m - m_new);
         const bool grow = m_new > m;
@@ -379,7 +552,12 @@ __global__ __launch_bounds__(64) void prefill_kernel(const AttnParams p)
                 O[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vreg[u][mb]),
                                                             __builtin_bit_cast(bf16x8, P[u]), O[mb], 0, 0, 0);
     }
-    const float ltot = xor_sum(lsum, 32);
+    float ltot;
+    {
+        float x, y;
+        swap32(lsum, x, y);
+        ltot = x + y;
+    }
     if (col < tl.rows) {
         const float inv = 1.0f / ltot;
         uint16_t *op = p.out + ((int64_t)(tl.q_row0 + col) * p.Hq + head) * HD + 4 * h;
@@ -428,36 +606,31 @@ __global__ __launch_bounds__(kCopyThreads) void block_copy_kernel(const u32x4 *k
 }
 
 // ------------------------------------------------------------------------------------------
-hipError_t launch_decode(const AttnParams &p, hipStream_t s)
+hipError_t launch_decode(const KernArgs &a, hipStream_t s)
 {
-    if (p.n_ditems == 0) return hipSuccess;
-    const dim3 grid((unsigned)((int64_t)p.n_ditems * p.Hkv)), block(64);
-    if (p.hd == 128)
-        hipLaunchKernelGGL((decode_kernel<128, 2>), grid, block, 0, s, p);
-    else
-        hipLaunchKernelGGL((decode_kernel<64, 2>), grid, block, 0, s, p);
+    if (a.p.static_runs <= 0 || a.p.dec_blocks <= 0) return hipSuccess;
+    const dim3 grid((unsigned)((int64_t)a.p.static_runs * a.p.Hkv)), block(64);
+    if (a.p.hd == 128) {
+        if (a.p.nbi == 2)
+            hipLaunchKernelGGL((decode_kernel<128, 2>), grid, block, 0, s, a);
+        else if (a.p.nbi == 4)
+            hipLaunchKernelGGL((decode_kernel<128, 4>), grid, block, 0, s, a);
+        else
+            hipLaunchKernelGGL((decode_kernel<128, 1>), grid, block, 0, s, a);
+    } else {
+        hipLaunchKernelGGL((decode_kernel<64, 1>), grid, block, 0, s, a);
+    }
     return hipGetLastError();
 }
 
-hipError_t launch_prefill(const AttnParams &p, hipStream_t s)
+hipError_t launch_prefill(const KernArgs &a, hipStream_t s)
 {
-    if (p.n_ptiles == 0) return hipSuccess;
-    const dim3 grid((unsigned)((int64_t)p.n_ptiles * p.Hq)), block(64);
-    if (p.hd == 128)
-        hipLaunchKernelGGL((prefill_kernel<128>), grid, block, 0, s, p);
+    if (a.p.n_tiles <= 0) return hipSuccess;
+    const dim3 grid((unsigned)((int64_t)a.p.n_tiles * a.p.Hq)), block(64);
+    if (a.p.hd == 128)
+        hipLaunchKernelGGL((prefill_kernel<128>), grid, block, 0, s, a);
     else
-        hipLaunchKernelGGL((prefill_kernel<64>), grid, block, 0, s, p);
-    return hipGetLastError();
-}
-
-hipError_t launch_merge(const AttnParams &p, hipStream_t s)
-{
-    if (p.n_mitems == 0) return hipSuccess;
-    const dim3 grid((unsigned)((int64_t)p.n_mitems * p.Hq)), block(64);
-    if (p.hd == 128)
-        hipLaunchKernelGGL((merge_kernel<128>), grid, block, 0, s, p);
-    else
-        hipLaunchKernelGGL((merge_kernel<64>), grid, block, 0, s, p);
+        hipLaunchKernelGGL((prefill_kernel<64>), grid, block, 0, s, a);
     return hipGetLastError();
 }
 

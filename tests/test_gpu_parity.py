@@ -51,13 +51,40 @@ def test_ragged_cases(case):
     assert_parity(run_gpu(b), oracle(b), f"ragged {case}")
 
 
-@pytest.mark.parametrize("splits", [1, 2, 7, 10 ** 6])
-def test_forced_split_counts_agree(splits):
-    b = W.build_batch(Hq=32, Hkv=8, hd=128, q_lens=[1, 1, 1], ctx_lens=[2000, 130, 15], num_blocks=160, seed=77,
-                      poison=True)
-    say(f"case: forced splits {splits}")
+@pytest.mark.parametrize("segments,tail_pct,tail_blocks", [(1, 0, 8), (2, 0, 8), (7, 15, 2), (40, 0, 8), (10 ** 6, 0, 8),
+                                                           (1, 50, 1), (3, 90, 4), (2, 30, 8)])
+def test_forced_decode_run_layouts_agree(segments, tail_pct, tail_blocks):
+    # (1, 0): no sequence split; 10**6: one wave per KV block; tail_pct > 0: part of the KV line is
+    # fetched dynamically in runs of tail_blocks blocks
+    b = W.build_batch(Hq=32, Hkv=8, hd=128, q_lens=[1, 1, 0, 1, 5], ctx_lens=[2000, 130, 7, 15, 40], num_blocks=170,
+                      seed=77, poison=True)
+    say(f"case: decode_segments {segments} tail {tail_pct}% x {tail_blocks}")
     ref = oracle(b)
-    assert_parity(run_gpu(b, options={"force_splits": splits}), ref, f"splits={splits}")
+    opts = {"decode_segments": segments, "decode_tail_pct": tail_pct, "decode_tail_blocks": tail_blocks}
+    assert_parity(run_gpu(b, options=opts), ref, f"segments={segments} tail={tail_pct}%x{tail_blocks}")
+
+
+def test_repeated_calls_reuse_counters_and_workspace():
+    b = W.build_batch(Hq=8, Hkv=2, hd=128, q_lens=[1, 1, 1], ctx_lens=[700, 90, 300], num_blocks=80, seed=78)
+    ref = oracle(b)
+    say("case: repeated calls on one context")
+    with B.Context(b.Hq, b.Hkv, b.hd, b.BS, b.num_blocks, b.max_blocks_per_seq) as ctx:
+        first = run_gpu(b, ctx=ctx, options={"decode_segments": 9, "decode_tail_pct": 40, "decode_tail_blocks": 1})
+        for seg in (9, 4, 9, 17):
+            out = run_gpu(b, ctx=ctx, options={"decode_segments": seg})
+            assert_parity(out, ref, f"repeat segments={seg}")
+            if seg == 9:
+                assert np.array_equal(out, first)
+
+
+def test_batch_above_inline_plan_limit_uses_device_plan():
+    n = 1100                                  # more sequences than fit the kernel-argument plan
+    rng = np.random.default_rng(5)
+    ql = np.where(np.arange(n) % 97 == 0, 3, 1).astype(np.int32)
+    ctx_l = rng.integers(0, 40, size=n).astype(np.int32)
+    b = W.build_batch(Hq=4, Hkv=1, hd=64, q_lens=ql, ctx_lens=ctx_l, num_blocks=3600, seed=79)
+    say("case: 1100 sequences")
+    assert_parity(run_gpu(b), oracle(b), "1100 sequences")
 
 
 def test_peaky_scores_give_order_one_outputs():
@@ -82,10 +109,10 @@ def test_small_value_data_passes_relative_gate():
 def test_run_to_run_and_block_permutation_determinism():
     b = W.build_batch(Hq=32, Hkv=8, hd=128, q_lens=[1, 1, 48], ctx_lens=[3000, 100, 70], num_blocks=256, seed=8)
     say("case: determinism")
-    o1 = run_gpu(b, options={"decode_split_blocks": 16})
-    o2 = run_gpu(b, options={"decode_split_blocks": 16})
+    o1 = run_gpu(b, options={"decode_segments": 12})
+    o2 = run_gpu(b, options={"decode_segments": 12})
     assert np.array_equal(o1, o2)
-    o3 = run_gpu(W.permute_blocks(b, 3), options={"decode_split_blocks": 16})
+    o3 = run_gpu(W.permute_blocks(b, 3), options={"decode_segments": 12})
     assert np.array_equal(o1, o3)
 
 

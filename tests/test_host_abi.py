@@ -60,24 +60,23 @@ def test_plan_rejects_inconsistent_lengths(seq, qsl, ctx, frag):
     assert e.value.status == B.OOCO_ESHAPE and frag in e.value.message
 
 
-def test_plan_reports_workspace_too_small_for_forced_splits():
-    with pytest.raises(B.OocoError) as e:
-        dry([4096], [0, 1], [4095], force_splits=64, workspace_bytes=1024)
-    assert e.value.status == B.OOCO_ENOMEM
-
-
 def check_cover(b, plan):
-    d, p = plan["decode_items"], plan["prefill_tiles"]
+    """Every KV block of every decode sequence is in exactly one piece, every query row of every
+    chunk in exactly one tile; pieces needing a merge have distinct slots."""
+    d, p = plan["decode_pieces"], plan["prefill_tiles"]
     nb = (b.seq_lens.astype(np.int64) + 15) // 16
     ql = b.q_lens
     for i in range(b.num_seqs):
         rows = d[d[:, 0] == i]
         if ql[i] == 1:
-            rows = rows[np.argsort(rows[:, 2])]
-            assert rows[0, 2] == 0 and rows[-1, 3] == nb[i]
-            assert (rows[1:, 2] == rows[:-1, 3]).all() and (rows[:, 3] > rows[:, 2]).all()
-            assert (rows[:, 1] == b.query_start_loc[i]).all() and (rows[:, 4] == b.seq_lens[i]).all()
-            assert (rows[:, 5] >= 0).all() if len(rows) > 1 else rows[0, 5] == -1
+            rows = rows[np.argsort(rows[:, 1])]
+            assert rows[0, 1] == 0 and rows[-1, 2] == nb[i]
+            assert (rows[1:, 1] == rows[:-1, 2]).all() and (rows[:, 2] > rows[:, 1]).all()
+            if len(rows) > 1:
+                assert (rows[:, 3] == rows[:, 4] + i).all()          # slot = run + seq
+                assert (np.diff(rows[:, 4]) == 1).all()              # consecutive runs
+            else:
+                assert rows[0, 3] == -1
         else:
             assert len(rows) == 0
         t = p[p[:, 0] == i]
@@ -88,8 +87,9 @@ def check_cover(b, plan):
             assert (t[:, 3] == b.ctx_lens[i] + (t[:, 1] - b.query_start_loc[i])).all()
         else:
             assert len(t) == 0
-    parts = np.sort(d[d[:, 5] >= 0][:, 5])
-    assert (parts == np.arange(len(parts))).all() and len(parts) == plan["parts"]
+    slots = d[d[:, 3] >= 0][:, 3]
+    assert len(np.unique(slots)) == len(slots)
+    assert len(slots) == 0 or slots.max() < plan["slots"]
 
 
 def meta_only(fn, **kw):
@@ -112,22 +112,44 @@ def meta_only(fn, **kw):
 @pytest.mark.parametrize("cfg", ["config1", "config2", "config3", "config4", "config5"])
 def test_plan_covers_every_block_and_row_once(cfg):
     b = meta_only(getattr(W, cfg))
-    for kw in (dict(), dict(force_splits=3), dict(split_blocks=5), dict(target_items=7)):
+    for seg, pct, blk in ((0, 15, 8), (1, 15, 8), (3, 50, 1), (7, 0, 8), (500, 15, 3), (10 ** 9, 15, 8), (2, 90, 5)):
         plan = dry(b.seq_lens, b.query_start_loc, b.ctx_lens, num_q_heads=b.Hq, num_kv_heads=b.Hkv, head_dim=b.hd,
-                   workspace_bytes=1 << 30, **kw)
+                   workspace_bytes=1 << 30, decode_segments=seg, decode_tail_pct=pct, decode_tail_blocks=blk)
         check_cover(b, plan)
 
 
-def test_plan_is_longest_first_and_balanced():
+def test_default_plan_is_equal_static_runs_plus_short_tail_runs():
+    for cfg in (W.config2, W.config4, W.config5):
+        b = meta_only(cfg)
+        plan = dry(b.seq_lens, b.query_start_loc, b.ctx_lens, num_q_heads=b.Hq, num_kv_heads=b.Hkv,
+                   workspace_bytes=1 << 30, decode_tail_pct=15)
+        d = plan["decode_pieces"]
+        R, T = plan["decode_runs"], plan["tail_runs"]
+        per_run = np.bincount(d[:, 4], weights=d[:, 2] - d[:, 1], minlength=R + T)
+        assert per_run[:R].max() - per_run[:R].min() <= 1 and per_run[:R].min() >= 1
+        assert T > 0 and per_run[R:].max() - per_run[R:].min() <= 1 and 1 <= per_run[R:].max() <= 8
+        total = per_run.sum()
+        assert 0.10 * total <= per_run[R:].sum() <= 0.16 * total           # 15 % handed out dynamically
+        assert R * b.Hkv <= 256 * 8
+        assert (np.diff(d[:, 4]) >= 0).all()
+    # no tail when asked for none, or when runs are short anyway
+    b = meta_only(W.config2)
+    assert dry(b.seq_lens, b.query_start_loc, b.ctx_lens, decode_tail_pct=0)["tail_runs"] == 0
+    assert dry(b.seq_lens, b.query_start_loc, b.ctx_lens, decode_segments=2000)["tail_runs"] == 0
+
+
+def test_small_workspace_reduces_the_number_of_runs():
     b = meta_only(W.config4)
-    d = dry(b.seq_lens, b.query_start_loc, b.ctx_lens)["decode_items"]
-    sizes = d[:, 3] - d[:, 2]
-    assert (np.diff(sizes) <= 0).all()
-    # items of split sequences differ by at most a factor 2 from the quantum
-    split = sizes[d[:, 5] >= 0]
-    assert split.max() <= 2 * split.min() + 1
+    big = dry(b.seq_lens, b.query_start_loc, b.ctx_lens, workspace_bytes=1 << 30)
+    small = dry(b.seq_lens, b.query_start_loc, b.ctx_lens, workspace_bytes=10 << 20)
+    assert small["slots"] * 32 * 130 * 4 <= 10 << 20 < big["slots"] * 32 * 130 * 4
+    assert small["decode_runs"] < big["decode_runs"]
+    check_cover(b, small)
+    tiny = dry(b.seq_lens, b.query_start_loc, b.ctx_lens, workspace_bytes=1024)
+    assert tiny["decode_runs"] == 1 and tiny["tail_runs"] == 0 and tiny["slots"] == 0
+    assert (tiny["decode_pieces"][:, 3] == -1).all()
 
 
 def test_empty_batch_plans_to_nothing():
     plan = dry(np.zeros(0, np.int32), np.zeros(1, np.int32), np.zeros(0, np.int32), num_seqs=0)
-    assert len(plan["decode_items"]) == 0 and len(plan["prefill_tiles"]) == 0
+    assert len(plan["decode_pieces"]) == 0 and len(plan["prefill_tiles"]) == 0
