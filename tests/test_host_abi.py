@@ -141,8 +141,8 @@ def test_default_plan_is_equal_static_runs_plus_short_tail_runs():
 def test_small_workspace_reduces_the_number_of_runs():
     b = meta_only(W.config4)
     big = dry(b.seq_lens, b.query_start_loc, b.ctx_lens, workspace_bytes=1 << 30)
-    small = dry(b.seq_lens, b.query_start_loc, b.ctx_lens, workspace_bytes=10 << 20)
-    assert small["slots"] * 32 * 130 * 4 <= 10 << 20 < big["slots"] * 32 * 130 * 4
+    small = dry(b.seq_lens, b.query_start_loc, b.ctx_lens, workspace_bytes=9 << 20)
+    assert small["slots"] * 32 * 130 * 4 <= 9 << 20 < big["slots"] * 32 * 130 * 4
     assert small["decode_runs"] < big["decode_runs"]
     check_cover(b, small)
     tiny = dry(b.seq_lens, b.query_start_loc, b.ctx_lens, workspace_bytes=1024)
