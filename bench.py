@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the mixed-batch paged-attention step on ONE MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg3|cfg3-prefill|cfg4|cfg5|cfg5-prefill]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg3|cfg3-prefill|cfg4|cfg4-copy|cfg5|cfg5-prefill]
 
 A step = one pass of the whole path over one synthetic batch already resident in HBM: host
 planning (ooco_plan) + ooco_attn_mixed (prefill kernel, decode kernel with its in-kernel merge).  Steps
@@ -21,6 +21,18 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
+
+
+def read_traffic(kernel, workload):
+    """HBM bytes per launch from the committed rocprofv3 counter summary of this kernel and workload
+    (profiles/<kernel>_<workload>.md, line `traffic_hbm_bytes_per_launch = N`), or None."""
+    import re
+
+    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}.md")
+    if not os.path.exists(path):
+        return None
+    m = re.search(r"^traffic_hbm_bytes_per_launch\s*=\s*(\d+)", open(path).read(), flags=re.M)
+    return int(m.group(1)) if m else None
 
 
 def make_workload(name):
@@ -81,6 +93,84 @@ def cpu_baseline(b, max_seconds=25.0):
     }
 
 
+def bench_block_copy(a):
+    """Row B1: ooco_kv_block_copy of the blocks of config 4's 64 evicted sequences into a staging
+    pool (one kernel per step; steps alternate between two staging pools)."""
+    import torch
+
+    from oracle import ref_c
+    from paper_2511_21862_amd import accounting
+    from paper_2511_21862_amd import binding as B
+    from paper_2511_21862_amd import workloads as W
+
+    b = W.config4(device="cuda")
+    src = W.victim_block_ids(b, b.extra["victims"])
+    n = len(src)
+    rng = np.random.default_rng(44)
+    stage_blocks = n + 64
+    dsts = [torch.from_numpy(rng.permutation(stage_blocks)[:n].astype(np.int64)).cuda() for _ in range(2)]
+    stages = [(torch.empty((stage_blocks,) + tuple(b.k_cache.shape[1:]), dtype=torch.bfloat16, device="cuda"),
+               torch.empty((stage_blocks,) + tuple(b.v_cache.shape[1:]), dtype=torch.bfloat16, device="cuda"))
+              for _ in range(2)]
+    src_d = torch.from_numpy(src).cuda()
+    ctx = B.Context(b.Hq, b.Hkv, b.hd, b.BS, b.num_blocks, b.max_blocks_per_seq)
+    stream = torch.cuda.current_stream()
+
+    def step(i):
+        ks, vs = stages[i % 2]
+        ctx.kv_block_copy(b.k_cache, b.v_cache, ks, vs, src_d, dsts[i % 2], stream)
+
+    for i in range(a.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(a.steps):
+        step(i)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / a.steps
+    # kernel duration by HIP events on the launch stream (torch's current stream here)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(a.steps)]
+    for i, (e0, e1) in enumerate(evs):
+        e0.record(stream)
+        step(i)
+        e1.record(stream)
+    torch.cuda.synchronize()
+    kms = float(np.mean([e0.elapsed_time(e1) for e0, e1 in evs]))
+    nbytes = accounting.block_copy_bytes(n, b.Hkv, b.hd, b.BS)
+    tokens = int(b.seq_lens[b.extra["victims"]].sum())
+    line = {
+        "metric": "KV block copy (preemption eviction) tokens/s + achieved HBM GB/s (% of peak), 1 MI355X",
+        "value": tokens / dt, "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": dt * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u8", "data": "synthetic",
+        "config": {"workload": "cfg4-eviction-copy", "bench_name": a.workload, "victim_seqs": len(b.extra["victims"]),
+                   "blocks": n, "kv_tokens": tokens, "Hkv": b.Hkv, "head_dim": b.hd, "block_size": b.BS},
+        "roofline": {"bound": "hbm", "kernel": "block_copy_kernel", "achieved": nbytes / (kms * 1e-3) / 1e9,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": nbytes / (kms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                     "traffic": None, "algorithmic_bytes_per_launch": nbytes, "kernel_ms": kms},
+    }
+    line["roofline"]["traffic"] = read_traffic("block_copy_kernel", a.workload)
+    if not a.no_cpu_baseline:
+        # host memcpy of a bounded sample of the same id lists (the C oracle's block copy)
+        m = min(n, 2048)
+        kh = np.zeros((m,) + tuple(b.k_cache.shape[1:]), np.uint16)
+        vh = np.zeros((m,) + tuple(b.v_cache.shape[1:]), np.uint16)
+        ksrc, vsrc = np.ones_like(kh), np.ones_like(vh)
+        ids = np.arange(m, dtype=np.int64)
+        perm = rng.permutation(m).astype(np.int64)
+        ts = []
+        for _ in range(3):
+            t1 = time.perf_counter()
+            ref_c.block_copy(ksrc, vsrc, kh, vh, ids, perm)
+            ts.append(time.perf_counter() - t1)
+        t = float(np.median(ts))
+        line["cpu_baseline"] = {"value": m * b.BS / t, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+                                "sample": f"{m} of {n} blocks, host memcpy per block pair (C oracle), median of 3, "
+                                          f"{t:.4f} s each, {accounting.block_copy_bytes(m, b.Hkv, b.hd, b.BS) / t / 1e9:.1f} GB/s"}
+    ctx.close()
+    print(json.dumps(line), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -102,6 +192,8 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if a.workload == "cfg4-copy":
+        return bench_block_copy(a)
     b, dominant = make_workload(a.workload)
     work = accounting.batch_work(b.Hq, b.Hkv, b.hd, b.BS, b.seq_lens, b.q_lens)
     tables = W.replica_tables(b, 4)
@@ -162,9 +254,7 @@ def main():
         roofline = {"bound": "mfma", "kernel": "prefill_kernel", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
                     "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
                     "algorithmic_flops_per_launch": alg, "kernel_ms": kern["prefill_ms"]}
-    traffic_file = os.path.join(ROOT, "profiles", f"traffic_{a.workload}.json")
-    if os.path.exists(traffic_file):
-        roofline["traffic"] = json.load(open(traffic_file)).get("hbm_bytes_per_launch")
+    roofline["traffic"] = read_traffic(roofline["kernel"], a.workload)
 
     line = {
         "metric": "mixed-batch attention tokens/s + achieved HBM GB/s (% of peak), 1 MI355X",

@@ -1,5 +1,5 @@
-// HIP kernels of libooco for gfx950 (CDNA4, wave64): split-KV decode attention, prefill-chunk
-// attention, split merge and KV block copy.
+// HIP kernels of libooco for gfx950 (CDNA4, wave64): split-KV decode attention with its in-kernel
+// merge, prefill-chunk attention and KV block copy.
 //
 // Common scheme (decode and prefill): scores are computed TRANSPOSED, S^T[token][query column]
 // = K · Q^T, and the output as O^T[dim][query column] = V^T · P^T.  A "query column" is a query
