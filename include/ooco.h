@@ -142,7 +142,8 @@ ooco_status ooco_plan(ooco_ctx *ctx, int num_seqs, const int32_t *h_seq_lens /*H
  *   decode_pieces_out: HOST int32 [decode_cap][5] = (seq, blk_begin, blk_end, slot, run): the KV
  *     block range of sequence seq that decode run `run` streams; slot = partial-result slot, or
  *     -1 when the piece covers the whole sequence and writes the output directly
- *   prefill_tiles_out: HOST int32 [prefill_cap][5] = (seq, q_row0, rows, pos0, seq_len)
+ *   prefill_tiles_out: HOST int32 [prefill_cap][5] = (seq, q_row0, rows, pos0, seq_len); a tile
+ *     holds up to 128 / (num_q_heads/num_kv_heads) query rows and runs once per kv head
  *   counts: HOST int64 [5] = (decode pieces, prefill tiles, static decode runs, partial-result
  *     slots, dynamically fetched tail runs); runs are numbered static first, then tail
  *   msg: HOST buffer of msg_cap bytes receiving the error text.  Any output pointer may be NULL. */

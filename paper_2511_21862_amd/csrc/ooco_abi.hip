@@ -67,6 +67,7 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
     out.dcum.assign((size_t)num_seqs + 1, 0);
     out.tcum.assign((size_t)num_seqs + 1, 0);
     int64_t dec_blocks = 0, tiles = 0;
+    const int tile_rows = prefill_tile_rows(geo.Hq / geo.Hkv);
     for (int i = 0; i < num_seqs; ++i) {
         const int64_t ql = (int64_t)h_query_start_loc[i + 1] - h_query_start_loc[i];
         if (ql < 0) return bad(OOCO_ESHAPE, "ooco_plan: query_start_loc decreases at sequence %d", i);
@@ -80,7 +81,7 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
             return bad(OOCO_ESHAPE, "ooco_plan: sequence %d needs %lld blocks > max_blocks_per_seq %d", i,
                        (long long)nb, geo.max_blocks_per_seq);
         if (ql == 1) dec_blocks += nb;
-        if (ql > 1) tiles += (ql + kPrefillRows - 1) / kPrefillRows;
+        if (ql > 1) tiles += (ql + tile_rows - 1) / tile_rows;
         if (dec_blocks > 0x7FFFFFFF / 2 || tiles > 0x7FFFFFFF / 128)
             return bad(OOCO_ESHAPE, "ooco_plan: batch too large");
         out.dcum[(size_t)i + 1] = (int32_t)dec_blocks;
@@ -448,9 +449,10 @@ ooco_status ooco_plan_dry_run(int num_q_heads, int num_kv_heads, int head_dim, i
         for (int i = 0; i < num_seqs && n < prefill_cap; ++i) {
             const int q0 = h_query_start_loc[i], ql = h_query_start_loc[i + 1] - q0;
             if (ql <= 1) continue;
-            for (int t0 = 0; t0 < ql && n < prefill_cap; t0 += kPrefillRows, ++n) {
+            const int tile_rows = prefill_tile_rows(num_q_heads / num_kv_heads);
+            for (int t0 = 0; t0 < ql && n < prefill_cap; t0 += tile_rows, ++n) {
                 int32_t *o = prefill_tiles_out + 5 * n;
-                o[0] = i, o[1] = q0 + t0, o[2] = std::min(kPrefillRows, ql - t0), o[3] = h_ctx_lens[i] + t0;
+                o[0] = i, o[1] = q0 + t0, o[2] = std::min(tile_rows, ql - t0), o[3] = h_ctx_lens[i] + t0;
                 o[4] = h_seq_lens[i];
             }
         }
@@ -549,6 +551,7 @@ ooco_status ooco_attn_mixed(ooco_ctx *ctx, const void *q, const void *k_cache, c
     p.queue = reinterpret_cast<uint32_t *>(ctx->counters + kCounterInts - 1);
     p.queue_base = ctx->queue_base;
     p.n_tiles = pl.n_tiles;
+    p.tile_rows = prefill_tile_rows(ctx->g);
     p.nbi = (int32_t)ctx->opt_nbi;
     p.rotate_heads = (int32_t)ctx->opt_rotate;
 

@@ -13,7 +13,8 @@
 //             A piece that does not cover its whole sequence writes a partial result into slot
 //             (run index) + i; the last piece of a sequence to finish merges the slots (arrival
 //             counter per sequence and kv head).
-//   prefill - cum[i] = number of query tiles (kPrefillRows rows each) before sequence i.
+//   prefill - cum[i] = number of query tiles (tile_rows = 128 / (Hq/Hkv) rows each, all heads of
+//             a GQA group) before sequence i; one workgroup per (tile, kv head).
 // The cumulative array travels inside the kernel arguments (no upload, no synchronisation) when
 // the batch has at most kInlineSeqs sequences, else through a device buffer.
 #pragma once
@@ -24,7 +25,7 @@
 namespace ooco {
 
 constexpr int kBlockSize = 16;      // tokens per KV block (fixed by the cache layout)
-constexpr int kPrefillRows = 32;    // query rows per prefill tile
+constexpr int kPrefillCols = 128;   // (row, head) query columns per prefill workgroup
 constexpr int kInlineSeqs = 960;    // sequences whose cumulative array fits the kernel arguments
 
 struct AttnParams {
@@ -46,7 +47,7 @@ struct AttnParams {
     float scale_log2e;          // softmax scale * log2(e)
     int32_t num_seqs, total_q;
     int32_t dec_blocks, static_blocks, static_runs, tail_runs;   // decode run layout
-    int32_t n_tiles;
+    int32_t n_tiles, tile_rows; // prefill: tiles per kv head, query rows per tile
     int32_t nbi;                // tuning: KV blocks per softmax step of the decode kernel
     int32_t rotate_heads;       // tuning: kv head rotation across XCDs
     uint32_t queue_base;        // ticket value at which this launch's tail runs start
@@ -66,6 +67,9 @@ hipError_t launch_prefill(const KernArgs &a, hipStream_t s);
 hipError_t launch_block_copy(const void *k_src, const void *v_src, void *k_dst, void *v_dst,
                              const int64_t *src_ids, const int64_t *dst_ids, int64_t num_pairs,
                              int64_t block_bytes, hipStream_t s);
+
+// Query rows of one prefill tile for a GQA group of g heads.
+__host__ __device__ inline int32_t prefill_tile_rows(int32_t g) { return kPrefillCols / g > 0 ? kPrefillCols / g : 1; }
 
 // n blocks cut into s equal runs, run k = [n*k/s, n*(k+1)/s): index of the run holding block x.
 __host__ __device__ inline int32_t segment_of(int64_t x, int64_t s, int64_t n)

@@ -400,65 +400,111 @@ __global__ __launch_bounds__(64) void decode_kernel(const KernArgs a)
 }
 
 // ------------------------------------------------------------------------------------------
-// Prefill chunk, simple form: one wave per (tile of 32 query rows, query head); K/V operands
-// come straight from global memory (L2) in operand order, two KV blocks (32 tokens) per step:
-//   S^T[32 tok][32 rows] = K · Q^T    (hd/16 x v_mfma_f32_32x32x16_bf16)
-//   O^T[hd][32 rows]    += V^T · P^T  (hd/32 x 2 x v_mfma_f32_32x32x16_bf16)
+// Prefill chunk: one workgroup of four waves per (tile of query rows, kv head).  The 128 query
+// columns of a workgroup are the (row, head) pairs of tile_rows = 128/g consecutive query rows
+// and the g query heads that share the kv head (column c = row*g + head), 32 columns per wave,
+// so every K/V tile fetched serves the whole GQA group.  KV is walked two blocks (32 tokens) per
+// step; the workgroup stages the step's K and V tiles (16 KiB for hd 128) in LDS, double
+// buffered: the global loads of step i+1 are issued before the arithmetic of step i and written
+// to the other buffer after it, one barrier per step.  Per wave and step:
+//   S^T[32 tok][32 cols] = K · Q^T    (hd/16 x v_mfma_f32_32x32x16_bf16, K operand from LDS)
+//   O^T[hd][32 cols]    += V^T · P^T  (hd/32 x 2 x v_mfma_f32_32x32x16_bf16, V operand from LDS)
 // Lane l = 32*h + col.  MFMA row i of the K operand is fed with token (i with bits 2 and 3
 // swapped) of its block, so that S^T register r of lane (col, h) is token 16(r/8) + 8h + r%8 of
-// the pair: eight consecutive tokens per block, which is what one 16-byte V operand load holds.
+// the pair: eight consecutive tokens per block, which is what one 16-byte V operand holds.
+// LDS (16-byte units, CH = 2*hd per tile): [K blk0 | K blk1 | V blk0 | V blk1]; K tiles keep the
+// cache order [hd/8][16 slots]; V tiles are stored [token half][dim] so that the 16 lanes of a
+// quarter wave read 256 contiguous bytes (no bank conflicts).
+// Two workgroups fit a CU (<= 256 VGPRs, 32 KiB LDS each): while one wave of a SIMD runs its
+// softmax on the VALU the other keeps the matrix core busy.
+constexpr int kPfThreads = 256;
+
 template <int HD>
-__global__ __launch_bounds__(64) void prefill_kernel(const KernArgs a)
+__global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a)
 {
     const AttnParams &p = a.p;
-    constexpr int KS = HD / 16;   // k-steps of QK
-    constexpr int MB = HD / 32;   // 32-dim groups of the output
-    const int lane = threadIdx.x;
+    constexpr int KS = HD / 16;        // k-steps of QK
+    constexpr int MB = HD / 32;        // 32-dim groups of the output
+    constexpr int CH = HD * 2;         // 16-byte chunks per (block, kv head) tile
+    constexpr int NCP = 4 * CH / kPfThreads;   // chunks each thread copies per step
+    __shared__ u32x4 lds[2][4 * CH];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
     const int col = lane & 31;
     const int h = lane >> 5;
-    const int tile_idx = blockIdx.x / p.Hq;
-    const int head = blockIdx.x - tile_idx * p.Hq;
+    const int g = p.g;
+    const int tile_idx = blockIdx.x / p.Hkv;
+    const int kvh = blockIdx.x - tile_idx * p.Hkv;
+
     // tile -> (sequence, tile of the sequence); tiles of a sequence are taken last-first because
     // the later rows of a chunk see more keys and the hardware dispatches in index order
-    struct {
-        int seq, q_row0, rows, pos0, seq_len;
-    } tl;
+    int seq, q_row0, rows, pos0, seq_len;
     {
         auto cum_at = [&](int idx) -> int { return p.cum_dev ? p.cum_dev[idx] : a.cum[idx]; };
-        tl.seq = __builtin_amdgcn_readfirstlane(count_le(cum_at, p.num_seqs, tile_idx, lane));
-        const int t_first = cum_at(tl.seq), t_end = cum_at(tl.seq + 1);
+        seq = __builtin_amdgcn_readfirstlane(count_le(cum_at, p.num_seqs, tile_idx, lane));
+        const int t_end = cum_at(seq + 1);
         const int t = (t_end - 1) - tile_idx;             // reversed order inside the sequence
-        (void)t_first;
-        const int q0 = p.query_start_loc[tl.seq];
-        const int q_len = p.query_start_loc[tl.seq + 1] - q0;
-        const int t0 = t * kPrefillRows;
-        tl.q_row0 = min(max(q0 + t0, 0), p.total_q - 1);
-        tl.rows = max(1, min(min(kPrefillRows, q_len - t0), p.total_q - tl.q_row0));
-        tl.pos0 = p.ctx_lens[tl.seq] + t0;
-        tl.seq_len = p.seq_lens[tl.seq];
+        const int q0 = p.query_start_loc[seq];
+        const int q_len = p.query_start_loc[seq + 1] - q0;
+        const int t0 = t * p.tile_rows;
+        q_row0 = min(max(q0 + t0, 0), p.total_q - 1);
+        rows = max(1, min(min(p.tile_rows, q_len - t0), p.total_q - q_row0));
+        seq_len = p.seq_lens[seq];
         // keys beyond what the plan allotted to this sequence are never touched
         const int cap = p.max_blocks_per_seq * kBlockSize;
-        tl.pos0 = min(max(tl.pos0, 0), cap - tl.rows);
-        tl.seq_len = min(tl.seq_len, cap);
+        pos0 = min(max(p.ctx_lens[seq] + t0, 0), cap - rows);
+        seq_len = min(seq_len, cap);
     }
-    const int kvh = head / p.g;
-    const int row = min(col, tl.rows - 1);
-    const int pos = tl.pos0 + row;                       // this lane column's absolute position
-    const int kv_end = tl.pos0 + tl.rows;                // keys visible to the tile: [0, kv_end)
+    // this lane's query column
+    const int c = wave * 32 + col;
+    const int c_row = c / g, c_head = c - c_row * g;
+    const bool c_valid = c_row < rows;
+    const int row = min(c_row, rows - 1);
+    const int head = kvh * g + c_head;
+    const int pos = pos0 + row;                          // this column's absolute position
+    // the wave's columns span rows [w_row_lo, w_row_hi]
+    const int w_row_lo = min((wave * 32) / g, rows - 1), w_row_hi = min((wave * 32 + 31) / g, rows - 1);
+    const int w_pos_lo = pos0 + w_row_lo, w_pos_hi = pos0 + w_row_hi;
+    const int kv_end = pos0 + rows;                      // keys visible to the tile: [0, kv_end)
     const int nblk = (kv_end + kBlockSize - 1) / kBlockSize;
-    const int npair = (nblk + 1) / 2;
+    const int nstep = (nblk + 1) / 2;
 
     u32x4 qb[KS];
     {
-        const u32x4 *qp = reinterpret_cast<const u32x4 *>(p.q + ((int64_t)(tl.q_row0 + row) * p.Hq + head) * HD);
+        const u32x4 *qp = reinterpret_cast<const u32x4 *>(p.q + ((int64_t)(q_row0 + row) * p.Hq + head) * HD);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) qb[ks] = qp[2 * ks + h];
     }
-    const int32_t *table = p.block_tables + (int64_t)tl.seq * p.max_blocks_per_seq;
+    const int32_t *table = p.block_tables + (int64_t)seq * p.max_blocks_per_seq;
     const int64_t tile_elems = (int64_t)HD * kBlockSize;
     // K operand row col -> block (col>>4) of the pair, slot with bits 2,3 of (col&15) swapped
     const int ku = col >> 4;
     const int kslot = (col & 3) | ((col & 4) << 1) | ((col & 8) >> 1);
+
+    // global -> register staging of one step's tiles; chunk n of thread tid is chunk tid + n*256
+    u32x4 stage[NCP];
+    auto fetch = [&](int step) {
+        const int b0 = min(2 * step, nblk - 1), b1 = min(2 * step + 1, nblk - 1);
+        const int pb0 = table[b0], pb1 = table[b1];
+#pragma unroll
+        for (int n = 0; n < NCP; ++n) {
+            const int cidx = tid + n * kPfThreads;
+            const int which = cidx / CH, r = cidx - which * CH;   // 0: K blk0, 1: K blk1, 2: V blk0, 3: V blk1
+            const int64_t off = ((int64_t)((which & 1) ? pb1 : pb0) * p.Hkv + kvh) * tile_elems;
+            if (which < 2) {
+                stage[n] = reinterpret_cast<const u32x4 *>(p.k_cache + off)[r];
+            } else {   // LDS position r = half*HD + dim  <-  cache chunk 2*dim + half
+                const int dim = r % HD, half = r / HD;
+                stage[n] = reinterpret_cast<const u32x4 *>(p.v_cache + off)[2 * dim + half];
+            }
+        }
+    };
+    auto commit = [&](int buf) {
+#pragma unroll
+        for (int n = 0; n < NCP; ++n) lds[buf][tid + n * kPfThreads] = stage[n];
+    };
 
     f32x16 O[MB];
 #pragma unroll
@@ -467,90 +513,89 @@ __global__ __launch_bounds__(64) void prefill_kernel(const KernArgs a)
         for (int r = 0; r < 16; ++r) O[mb][r] = 0.f;
     float m = -INFINITY, lsum = 0.f;
 
-    for (int pr = 0; pr < npair; ++pr) {
-        const int b0 = 2 * pr, b1 = min(2 * pr + 1, nblk - 1);
-        const int pb0 = table[b0], pb1 = table[b1];
-        const int64_t offk = ((int64_t)(ku ? pb1 : pb0) * p.Hkv + kvh) * tile_elems;
-        const u32x4 *kp = reinterpret_cast<const u32x4 *>(p.k_cache + offk);
-        u32x4 kreg[KS];
+    fetch(0);
+    commit(0);
+    __syncthreads();
+    for (int st = 0; st < nstep; ++st) {
+        const int buf = st & 1;
+        if (st + 1 < nstep) fetch(st + 1);
+        if (st * 32 <= w_pos_hi) {   // wave-uniform: some column of this wave sees keys of this step
+            f32x16 S;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) kreg[ks] = kp[(2 * ks + h) * 16 + kslot];
-        u32x4 vreg[2][MB];
+            for (int r = 0; r < 16; ++r) S[r] = 0.f;
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const u32x4 *vp = reinterpret_cast<const u32x4 *>(p.v_cache + ((int64_t)(u ? pb1 : pb0) * p.Hkv + kvh) * tile_elems);
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb) vreg[u][mb] = vp[(mb * 32 + col) * 2 + h];
-        }
-        f32x16 S;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) S[r] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-            S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kreg[ks]),
-                                                        __builtin_bit_cast(bf16x8, qb[ks]), S, 0, 0, 0);
-        const int tok0 = pr * 32 + 8 * h;                // token of register 0; register r: +16(r/8) + r%8
-        const bool need_mask = (pr * 32 + 31 > tl.pos0) || (pr * 32 + 31 >= tl.seq_len);   // wave-uniform
-        if (need_mask) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int tok = tok0 + 16 * (r / 8) + (r % 8);
-                S[r] = (tok <= pos) ? S[r] * p.scale_log2e : -INFINITY;
+            for (int ks = 0; ks < KS; ++ks) {
+                const u32x4 kop = lds[buf][ku * CH + (2 * ks + h) * 16 + kslot];
+                S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kop),
+                                                            __builtin_bit_cast(bf16x8, qb[ks]), S, 0, 0, 0);
             }
-            // V slots at or past seq_len may hold anything: zero them (their P is 0, but 0*NaN is NaN)
+            const int tok0 = st * 32 + 8 * h;            // token of register 0; register r: +16(r/8) + r%8
+            const bool need_mask = (st * 32 + 31 > w_pos_lo);   // wave-uniform
+            if (need_mask) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int tok = tok0 + 16 * (r / 8) + (r % 8);
+                    S[r] = (tok <= pos) ? S[r] * p.scale_log2e : -INFINITY;
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) S[r] *= p.scale_log2e;
+            }
+            float mloc = S[0];
+#pragma unroll
+            for (int r = 1; r < 16; ++r) mloc = fmaxf(mloc, S[r]);
+            {
+                float x, y;
+                swap32(mloc, x, y);
+                mloc = fmaxf(x, y);
+            }
+            const float m_new = fmaxf(m, mloc);
+            const float alpha = fast_exp2(m - m_new);
+            const bool grow = m_new > m;
+            m = m_new;
+            float psum = 0.f;
+            u32x4 P[2];
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
-                const int t0 = tok0 + 16 * u;            // tokens t0 .. t0+7 in this lane's V registers
-                const bool whole = (u == 1 && 2 * pr + 1 >= nblk);   // the pair's second block does not exist
+                float e[8];
 #pragma unroll
-                for (int w = 0; w < 4; ++w) {
-                    const uint32_t mk = ((!whole && t0 + 2 * w < tl.seq_len) ? 0x0000FFFFu : 0u) |
-                                        ((!whole && t0 + 2 * w + 1 < tl.seq_len) ? 0xFFFF0000u : 0u);
+                for (int r = 0; r < 8; ++r) {
+                    e[r] = fast_exp2(S[8 * u + r] - m_new);
+                    psum += e[r];
+                }
+                P[u] = u32x4{pack2_bf16(e[0], e[1]), pack2_bf16(e[2], e[3]), pack2_bf16(e[4], e[5]), pack2_bf16(e[6], e[7])};
+            }
+            lsum = lsum * alpha + psum;
+            if (__any(grow)) {
 #pragma unroll
-                    for (int mb = 0; mb < MB; ++mb) vreg[u][mb][w] &= mk;
+                for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) O[mb][r] *= alpha;
+            }
+            // V slots at or past seq_len may hold anything: zero them (their P is 0, but 0*NaN is NaN)
+            const bool vmask = (st * 32 + 32 > seq_len);   // wave-uniform
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                u32x4 mk = {0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu};
+                if (vmask) {
+                    const int t0 = tok0 + 16 * u;        // tokens t0 .. t0+7 in this lane's V operand
+                    const bool whole = (u == 1 && 2 * st + 1 >= nblk);   // the pair's second block does not exist
+#pragma unroll
+                    for (int w = 0; w < 4; ++w)
+                        mk[w] = ((!whole && t0 + 2 * w < seq_len) ? 0x0000FFFFu : 0u) |
+                                ((!whole && t0 + 2 * w + 1 < seq_len) ? 0xFFFF0000u : 0u);
+                }
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) {
+                    u32x4 vop = lds[buf][(2 + u) * CH + h * HD + 32 * mb + col];
+                    if (vmask) vop &= mk;
+                    O[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vop),
+                                                                __builtin_bit_cast(bf16x8, P[u]), O[mb], 0, 0, 0);
                 }
             }
-        } else {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) S[r] *= p.scale_log2e;
         }
-        float mloc = S[0];
-#pragma unroll
-        for (int r = 1; r < 16; ++r) mloc = fmaxf(mloc, S[r]);
-        {
-            float x, y;
-            swap32(mloc, x, y);
-            mloc = fmaxf(x, y);
-        }
-        const float m_new = fmaxf(m, mloc);
-        const float alpha = fast_exp2(m - m_new);
-        const bool grow = m_new > m;
-        m = m_new;
-        float psum = 0.f;
-        u32x4 P[2];
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            float e[8];
-#pragma unroll
-            for (int r = 0; r < 8; ++r) {
-                e[r] = fast_exp2(S[8 * u + r] - m_new);
-                psum += e[r];
-            }
-            P[u] = u32x4{pack2_bf16(e[0], e[1]), pack2_bf16(e[2], e[3]), pack2_bf16(e[4], e[5]), pack2_bf16(e[6], e[7])};
-        }
-        lsum = lsum * alpha + psum;
-        if (__any(grow)) {
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) O[mb][r] *= alpha;
-        }
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
-                O[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vreg[u][mb]),
-                                                            __builtin_bit_cast(bf16x8, P[u]), O[mb], 0, 0, 0);
+        if (st + 1 < nstep) commit(buf ^ 1);
+        __syncthreads();
     }
     float ltot;
     {
@@ -558,9 +603,9 @@ __global__ __launch_bounds__(64) void prefill_kernel(const KernArgs a)
         swap32(lsum, x, y);
         ltot = x + y;
     }
-    if (col < tl.rows) {
+    if (c_valid) {
         const float inv = 1.0f / ltot;
-        uint16_t *op = p.out + ((int64_t)(tl.q_row0 + col) * p.Hq + head) * HD + 4 * h;
+        uint16_t *op = p.out + ((int64_t)(q_row0 + row) * p.Hq + head) * HD + 4 * h;
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
@@ -626,7 +671,7 @@ hipError_t launch_decode(const KernArgs &a, hipStream_t s)
 hipError_t launch_prefill(const KernArgs &a, hipStream_t s)
 {
     if (a.p.n_tiles <= 0) return hipSuccess;
-    const dim3 grid((unsigned)((int64_t)a.p.n_tiles * a.p.Hq)), block(64);
+    const dim3 grid((unsigned)((int64_t)a.p.n_tiles * a.p.Hkv)), block(kPfThreads);
     if (a.p.hd == 128)
         hipLaunchKernelGGL((prefill_kernel<128>), grid, block, 0, s, a);
     else
