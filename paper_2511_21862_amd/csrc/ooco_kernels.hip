@@ -431,7 +431,7 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31;
     const int h = lane >> 5;
     const int g = p.g;
@@ -456,7 +456,15 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
         const int cap = p.max_blocks_per_seq * kBlockSize;
         pos0 = min(max(p.ctx_lens[seq] + t0, 0), cap - rows);
         seq_len = min(seq_len, cap);
+        // all of these are the same in every lane: keep them in scalar registers
+        q_row0 = __builtin_amdgcn_readfirstlane(q_row0);
+        rows = __builtin_amdgcn_readfirstlane(rows);
+        pos0 = __builtin_amdgcn_readfirstlane(pos0);
+        seq_len = __builtin_amdgcn_readfirstlane(seq_len);
     }
+    const uint16_t *const k_cache = p.k_cache, *const v_cache = p.v_cache;
+    const int Hkv = p.Hkv;
+    const float c_log2e = p.scale_log2e;
     // this lane's query column
     const int c = wave * 32 + col;
     const int c_row = c / g, c_head = c - c_row * g;
@@ -465,7 +473,7 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
     const int head = kvh * g + c_head;
     const int pos = pos0 + row;                          // this column's absolute position
     // the wave's columns span rows [w_row_lo, w_row_hi]
-    const int w_row_lo = min((wave * 32) / g, rows - 1), w_row_hi = min((wave * 32 + 31) / g, rows - 1);
+    const int w_row_lo = min((wave * 32) / g, rows - 1), w_row_hi = min((wave * 32 + 31) / g, rows - 1);   // scalar
     const int w_pos_lo = pos0 + w_row_lo, w_pos_hi = pos0 + w_row_hi;
     const int kv_end = pos0 + rows;                      // keys visible to the tile: [0, kv_end)
     const int nblk = (kv_end + kBlockSize - 1) / kBlockSize;
@@ -492,12 +500,12 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
         for (int n = 0; n < NCP; ++n) {
             const int cidx = tid + n * kPfThreads;
             const int which = cidx / CH, r = cidx - which * CH;   // 0: K blk0, 1: K blk1, 2: V blk0, 3: V blk1
-            const int64_t off = ((int64_t)((which & 1) ? pb1 : pb0) * p.Hkv + kvh) * tile_elems;
+            const int64_t off = ((int64_t)((which & 1) ? pb1 : pb0) * Hkv + kvh) * tile_elems;
             if (which < 2) {
-                stage[n] = reinterpret_cast<const u32x4 *>(p.k_cache + off)[r];
+                stage[n] = reinterpret_cast<const u32x4 *>(k_cache + off)[r];
             } else {   // LDS position r = half*HD + dim  <-  cache chunk 2*dim + half
                 const int dim = r % HD, half = r / HD;
-                stage[n] = reinterpret_cast<const u32x4 *>(p.v_cache + off)[2 * dim + half];
+                stage[n] = reinterpret_cast<const u32x4 *>(v_cache + off)[2 * dim + half];
             }
         }
     };
@@ -535,19 +543,18 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const int tok = tok0 + 16 * (r / 8) + (r % 8);
-                    S[r] = (tok <= pos) ? S[r] * p.scale_log2e : -INFINITY;
+                    S[r] = (tok <= pos) ? S[r] : -INFINITY;
                 }
-            } else {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) S[r] *= p.scale_log2e;
             }
+            // raw scores here; the softmax scale rides in the fma that feeds exp2 (scale > 0, so the
+            // maximum can be taken before scaling)
             float mloc = S[0];
 #pragma unroll
             for (int r = 1; r < 16; ++r) mloc = fmaxf(mloc, S[r]);
             {
                 float x, y;
                 swap32(mloc, x, y);
-                mloc = fmaxf(x, y);
+                mloc = fmaxf(x, y) * c_log2e;
             }
             const float m_new = fmaxf(m, mloc);
             const float alpha = fast_exp2(m - m_new);
@@ -560,7 +567,7 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
                 float e[8];
 #pragma unroll
                 for (int r = 0; r < 8; ++r) {
-                    e[r] = fast_exp2(S[8 * u + r] - m_new);
+                    e[r] = fast_exp2(__builtin_fmaf(S[8 * u + r], c_log2e, -m_new));
                     psum += e[r];
                 }
                 P[u] = u32x4{pack2_bf16(e[0], e[1]), pack2_bf16(e[2], e[3]), pack2_bf16(e[4], e[5]), pack2_bf16(e[6], e[7])};
