@@ -404,9 +404,9 @@ __global__ __launch_bounds__(64) void decode_kernel(const KernArgs a)
 // columns of a workgroup are the (row, head) pairs of tile_rows = 128/g consecutive query rows
 // and the g query heads that share the kv head (column c = row*g + head), 32 columns per wave,
 // so every K/V tile fetched serves the whole GQA group.  KV is walked two blocks (32 tokens) per
-// step; the workgroup stages the step's K and V tiles (16 KiB for hd 128) in LDS, double
-// buffered: the global loads of step i+1 are issued before the arithmetic of step i and written
-// to the other buffer after it, one barrier per step.  Per wave and step:
+// step; the workgroup stages the step's K and V tiles (16 KiB for hd 128) in a ring of three LDS
+// buffers filled by direct global->LDS loads issued two steps ahead, one barrier per step.
+// Per wave and step:
 //   S^T[32 tok][32 cols] = K · Q^T    (hd/16 x v_mfma_f32_32x32x16_bf16, K operand from LDS)
 //   O^T[hd][32 cols]    += V^T · P^T  (hd/32 x 2 x v_mfma_f32_32x32x16_bf16, V operand from LDS)
 // Lane l = 32*h + col.  MFMA row i of the K operand is fed with token (i with bits 2 and 3
@@ -415,9 +415,10 @@ __global__ __launch_bounds__(64) void decode_kernel(const KernArgs a)
 // LDS (16-byte units, CH = 2*hd per tile): [K blk0 | K blk1 | V blk0 | V blk1]; K tiles keep the
 // cache order [hd/8][16 slots]; V tiles are stored [token half][dim] so that the 16 lanes of a
 // quarter wave read 256 contiguous bytes (no bank conflicts).
-// Two workgroups fit a CU (<= 256 VGPRs, 32 KiB LDS each): while one wave of a SIMD runs its
+// Two workgroups fit a CU (<= 256 VGPRs, 48 KiB LDS each): while one wave of a SIMD runs its
 // softmax on the VALU the other keeps the matrix core busy.
 constexpr int kPfThreads = 256;
+constexpr int kPfRing = 3;      // LDS buffers: steps st, st+1, st+2 in flight
 
 template <int HD>
 __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a)
@@ -427,7 +428,7 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
     constexpr int MB = HD / 32;        // 32-dim groups of the output
     constexpr int CH = HD * 2;         // 16-byte chunks per (block, kv head) tile
     constexpr int NCP = 4 * CH / kPfThreads;   // chunks each thread copies per step
-    __shared__ u32x4 lds[2][4 * CH];
+    __shared__ u32x4 lds[kPfRing][4 * CH];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -465,6 +466,7 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
     const uint16_t *const k_cache = p.k_cache, *const v_cache = p.v_cache;
     const int Hkv = p.Hkv;
     const float c_log2e = p.scale_log2e;
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)&lds[0][0];
     // this lane's query column
     const int c = wave * 32 + col;
     const int c_row = c / g, c_head = c - c_row * g;
@@ -484,6 +486,11 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
         const u32x4 *qp = reinterpret_cast<const u32x4 *>(p.q + ((int64_t)(q_row0 + row) * p.Hq + head) * HD);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) qb[ks] = qp[2 * ks + h];
+        // Passing the registers through an empty asm makes the compiler wait for these loads here,
+        // before the loop, instead of counting them down inside it (which would also wait for the
+        // global->LDS loads it does not know about).
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qb[ks]));
     }
     const int32_t *table = p.block_tables + (int64_t)seq * p.max_blocks_per_seq;
     const int64_t tile_elems = (int64_t)HD * kBlockSize;
@@ -491,27 +498,37 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
     const int ku = col >> 4;
     const int kslot = (col & 3) | ((col & 4) << 1) | ((col & 8) >> 1);
 
-    // global -> register staging of one step's tiles; chunk n of thread tid is chunk tid + n*256
-    u32x4 stage[NCP];
-    auto fetch = [&](int step) {
+    // One step's tiles go from global memory straight into LDS (global_load_lds_dwordx4: every lane
+    // gives a 16-byte global address, the wave's 64 pieces land contiguously at the LDS address in
+    // M0).  Wave w moves the 64-chunk groups w, w+4, ...; chunk cidx of the buffer comes from
+    //   K: block (cidx/CH)&1 of the pair, cache chunk cidx%CH        (same order as the cache)
+    //   V: LDS position r = half*HD + dim  <-  cache chunk 2*dim + half
+    // The instruction is issued through inline asm so that the waits stay under this code's
+    // control: s_waitcnt vmcnt(NCP) before the barrier of a step leaves exactly the next step's
+    // loads in flight.
+    // (the block table is read through the constant address space: scalar loads, which the waits
+    // on the vector-memory counter below do not see)
+    typedef const __attribute__((address_space(4))) int32_t *const_i32_ptr;
+    const const_i32_ptr ctable = (const_i32_ptr)(uintptr_t)table;
+    auto issue = [&](int step, int buf) {
         const int b0 = min(2 * step, nblk - 1), b1 = min(2 * step + 1, nblk - 1);
-        const int pb0 = table[b0], pb1 = table[b1];
+        const int pb0 = ctable[b0], pb1 = ctable[b1];
 #pragma unroll
         for (int n = 0; n < NCP; ++n) {
-            const int cidx = tid + n * kPfThreads;
-            const int which = cidx / CH, r = cidx - which * CH;   // 0: K blk0, 1: K blk1, 2: V blk0, 3: V blk1
+            const int grp = wave + 4 * n;                  // wave-uniform
+            const int cidx = grp * 64 + lane;
+            const int which = (grp * 64) / CH;             // 0: K blk0, 1: K blk1, 2: V blk0, 3: V blk1 (uniform)
+            const int r = cidx - which * CH;
             const int64_t off = ((int64_t)((which & 1) ? pb1 : pb0) * Hkv + kvh) * tile_elems;
-            if (which < 2) {
-                stage[n] = reinterpret_cast<const u32x4 *>(k_cache + off)[r];
-            } else {   // LDS position r = half*HD + dim  <-  cache chunk 2*dim + half
-                const int dim = r % HD, half = r / HD;
-                stage[n] = reinterpret_cast<const u32x4 *>(v_cache + off)[2 * dim + half];
-            }
+            const u32x4 *src = which < 2 ? reinterpret_cast<const u32x4 *>(k_cache + off) + r
+                                         : reinterpret_cast<const u32x4 *>(v_cache + off) + (2 * (r % HD) + r / HD);
+            const uint32_t dst = lds_base + (uint32_t)((buf * 4 * CH + grp * 64) * 16);
+            uint32_t saved_m0;   // M0 is restored: the compiler may keep a value of its own there
+            asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\ts_mov_b32 m0, %0"
+                         : "=&s"(saved_m0)
+                         : "s"(dst), "v"(src)
+                         : "memory");
         }
-    };
-    auto commit = [&](int buf) {
-#pragma unroll
-        for (int n = 0; n < NCP; ++n) lds[buf][tid + n * kPfThreads] = stage[n];
     };
 
     f32x16 O[MB];
@@ -521,12 +538,18 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
         for (int r = 0; r < 16; ++r) O[mb][r] = 0.f;
     float m = -INFINITY, lsum = 0.f;
 
-    fetch(0);
-    commit(0);
-    __syncthreads();
+    issue(0, 0);
+    if (nstep > 1) issue(1, 1);
+    int buf = 0;
     for (int st = 0; st < nstep; ++st) {
-        const int buf = st & 1;
-        if (st + 1 < nstep) fetch(st + 1);
+        // this wave's loads of step st have landed (those of step st+1 may still fly) ...
+        if (st + 1 < nstep)
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NCP) : "memory");
+        else
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        // ... and after the barrier so have everybody's; nobody reads the buffer of step st-1 any more
+        __syncthreads();
+        if (st + 2 < nstep) issue(st + 2, buf >= 1 ? buf - 1 : kPfRing - 1);   // (buf + 2) % 3
         if (st * 32 <= w_pos_hi) {   // wave-uniform: some column of this wave sees keys of this step
             f32x16 S;
 #pragma unroll
@@ -601,8 +624,7 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
                 }
             }
         }
-        if (st + 1 < nstep) commit(buf ^ 1);
-        __syncthreads();
+        buf = buf + 1 == kPfRing ? 0 : buf + 1;
     }
     float ltot;
     {
