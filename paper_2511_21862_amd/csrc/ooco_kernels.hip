@@ -403,22 +403,26 @@ __global__ __launch_bounds__(64) void decode_kernel(const KernArgs a)
 // Prefill chunk: one workgroup of four waves per (tile of query rows, kv head).  The 128 query
 // columns of a workgroup are the (row, head) pairs of tile_rows = 128/g consecutive query rows
 // and the g query heads that share the kv head (column c = row*g + head), 32 columns per wave,
-// so every K/V tile fetched serves the whole GQA group.  KV is walked two blocks (32 tokens) per
-// step; the workgroup stages the step's K and V tiles (16 KiB for hd 128) in a ring of three LDS
-// buffers filled by direct global->LDS loads issued two steps ahead, one barrier per step.
-// Per wave and step:
+// so every K/V tile fetched serves the whole GQA group.  KV is walked four blocks (64 tokens) per
+// step; the workgroup keeps the step's K and V tiles (32 KiB for hd 128) in one of two LDS
+// buffers, filled by direct global->LDS loads issued one step ahead, one barrier per step.
+// Per wave and step, for each 32-token half:
 //   S^T[32 tok][32 cols] = K · Q^T    (hd/16 x v_mfma_f32_32x32x16_bf16, K operand from LDS)
 //   O^T[hd][32 cols]    += V^T · P^T  (hd/32 x 2 x v_mfma_f32_32x32x16_bf16, V operand from LDS)
-// Lane l = 32*h + col.  MFMA row i of the K operand is fed with token (i with bits 2 and 3
-// swapped) of its block, so that S^T register r of lane (col, h) is token 16(r/8) + 8h + r%8 of
-// the pair: eight consecutive tokens per block, which is what one 16-byte V operand holds.
-// LDS (16-byte units, CH = 2*hd per tile): [K blk0 | K blk1 | V blk0 | V blk1]; K tiles keep the
-// cache order [hd/8][16 slots]; V tiles are stored [token half][dim] so that the 16 lanes of a
-// quarter wave read 256 contiguous bytes (no bank conflicts).
-// Two workgroups fit a CU (<= 256 VGPRs, 48 KiB LDS each): while one wave of a SIMD runs its
-// softmax on the VALU the other keeps the matrix core busy.
+// with one softmax update over the 64 scores of a column.  Lane l = 32*h + col.  MFMA row i of
+// the K operand is fed with token (i with bits 2 and 3 swapped) of its block, so that S^T
+// register r of lane (col, h) is token 16(r/8) + 8h + r%8 of the half: eight consecutive tokens
+// per block, which is what one 16-byte V operand holds.
+// LDS (16-byte units, CH = 2*hd per tile): [K blk0..3 | V blk0..3]; K tiles keep the cache order
+// [hd/8][16 slots]; V tiles are stored [token half][dim] so that the 16 lanes of a quarter wave
+// read 256 contiguous bytes (no bank conflicts).
+// The SIMD's VALU issue port is shared with the matrix core (a 32x32x16 MFMA holds it for half of
+// its 32 cycles), so the kernel is tuned for few vector instructions per MFMA: 64-token steps
+// halve the per-step bookkeeping, masks run only on steps that touch the causal diagonal or
+// the end of the sequence.  Two workgroups fit a CU (<= 256 VGPRs, 64 KiB LDS each).
 constexpr int kPfThreads = 256;
-constexpr int kPfRing = 3;      // LDS buffers: steps st, st+1, st+2 in flight
+constexpr int kPfRing = 2;      // LDS buffers: step st being read, step st+1 being filled
+constexpr int kPfBlocks = 4;    // KV blocks per step
 
 template <int HD>
 __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a)
@@ -427,8 +431,9 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
     constexpr int KS = HD / 16;        // k-steps of QK
     constexpr int MB = HD / 32;        // 32-dim groups of the output
     constexpr int CH = HD * 2;         // 16-byte chunks per (block, kv head) tile
-    constexpr int NCP = 4 * CH / kPfThreads;   // chunks each thread copies per step
-    __shared__ u32x4 lds[kPfRing][4 * CH];
+    constexpr int BUF = 2 * kPfBlocks * CH;             // chunks per LDS buffer
+    constexpr int NCP = BUF / kPfThreads;               // chunks each thread moves per step
+    __shared__ u32x4 lds[kPfRing][BUF];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -474,12 +479,12 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
     const int row = min(c_row, rows - 1);
     const int head = kvh * g + c_head;
     const int pos = pos0 + row;                          // this column's absolute position
-    // the wave's columns span rows [w_row_lo, w_row_hi]
-    const int w_row_lo = min((wave * 32) / g, rows - 1), w_row_hi = min((wave * 32 + 31) / g, rows - 1);   // scalar
+    // the wave's columns span rows [w_row_lo, w_row_hi] (scalar)
+    const int w_row_lo = min((wave * 32) / g, rows - 1), w_row_hi = min((wave * 32 + 31) / g, rows - 1);
     const int w_pos_lo = pos0 + w_row_lo, w_pos_hi = pos0 + w_row_hi;
     const int kv_end = pos0 + rows;                      // keys visible to the tile: [0, kv_end)
     const int nblk = (kv_end + kBlockSize - 1) / kBlockSize;
-    const int nstep = (nblk + 1) / 2;
+    const int nstep = (nblk + kPfBlocks - 1) / kPfBlocks;
 
     u32x4 qb[KS];
     {
@@ -494,35 +499,33 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
     }
     const int32_t *table = p.block_tables + (int64_t)seq * p.max_blocks_per_seq;
     const int64_t tile_elems = (int64_t)HD * kBlockSize;
-    // K operand row col -> block (col>>4) of the pair, slot with bits 2,3 of (col&15) swapped
+    // K operand row col -> block (col>>4) of the half, slot with bits 2,3 of (col&15) swapped
     const int ku = col >> 4;
     const int kslot = (col & 3) | ((col & 4) << 1) | ((col & 8) >> 1);
 
     // One step's tiles go from global memory straight into LDS (global_load_lds_dwordx4: every lane
     // gives a 16-byte global address, the wave's 64 pieces land contiguously at the LDS address in
     // M0).  Wave w moves the 64-chunk groups w, w+4, ...; chunk cidx of the buffer comes from
-    //   K: block (cidx/CH)&1 of the pair, cache chunk cidx%CH        (same order as the cache)
-    //   V: LDS position r = half*HD + dim  <-  cache chunk 2*dim + half
+    //   K (cidx < 4*CH): block cidx/CH of the step, cache chunk cidx%CH   (same order as the cache)
+    //   V: block (cidx/CH)-4, LDS position r = half*HD + dim  <-  cache chunk 2*dim + half
     // The instruction is issued through inline asm so that the waits stay under this code's
-    // control: s_waitcnt vmcnt(NCP) before the barrier of a step leaves exactly the next step's
-    // loads in flight.
-    // (the block table is read through the constant address space: scalar loads, which the waits
-    // on the vector-memory counter below do not see)
+    // control.  (The block table is read through the constant address space: scalar loads, which
+    // the waits on the vector-memory counter do not see.)
     typedef const __attribute__((address_space(4))) int32_t *const_i32_ptr;
     const const_i32_ptr ctable = (const_i32_ptr)(uintptr_t)table;
-    auto issue = [&](int step, int buf) {
-        const int b0 = min(2 * step, nblk - 1), b1 = min(2 * step + 1, nblk - 1);
-        const int pb0 = ctable[b0], pb1 = ctable[b1];
+    auto block_id = [&](int b) -> int { return ctable[min(b, nblk - 1)]; };
+    auto issue = [&](int buf, const int (&pb)[kPfBlocks]) {   // pb: physical ids of the step's blocks
 #pragma unroll
         for (int n = 0; n < NCP; ++n) {
             const int grp = wave + 4 * n;                  // wave-uniform
             const int cidx = grp * 64 + lane;
-            const int which = (grp * 64) / CH;             // 0: K blk0, 1: K blk1, 2: V blk0, 3: V blk1 (uniform)
+            const int which = (grp * 64) / CH;             // 0..3: K blocks, 4..7: V blocks (uniform)
             const int r = cidx - which * CH;
-            const int64_t off = ((int64_t)((which & 1) ? pb1 : pb0) * Hkv + kvh) * tile_elems;
-            const u32x4 *src = which < 2 ? reinterpret_cast<const u32x4 *>(k_cache + off) + r
-                                         : reinterpret_cast<const u32x4 *>(v_cache + off) + (2 * (r % HD) + r / HD);
-            const uint32_t dst = lds_base + (uint32_t)((buf * 4 * CH + grp * 64) * 16);
+            const int64_t off = ((int64_t)pb[which & (kPfBlocks - 1)] * Hkv + kvh) * tile_elems;
+            const u32x4 *src = which < kPfBlocks
+                                   ? reinterpret_cast<const u32x4 *>(k_cache + off) + r
+                                   : reinterpret_cast<const u32x4 *>(v_cache + off) + (2 * (r % HD) + r / HD);
+            const uint32_t dst = lds_base + (uint32_t)((buf * BUF + grp * 64) * 16);
             uint32_t saved_m0;   // M0 is restored: the compiler may keep a value of its own there
             asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\ts_mov_b32 m0, %0"
                          : "=&s"(saved_m0)
@@ -538,42 +541,63 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
         for (int r = 0; r < 16; ++r) O[mb][r] = 0.f;
     float m = -INFINITY, lsum = 0.f;
 
-    issue(0, 0);
-    if (nstep > 1) issue(1, 1);
-    int buf = 0;
+    int nid[kPfBlocks];   // ids of the step issued next, fetched one iteration ahead
+#pragma unroll
+    for (int b = 0; b < kPfBlocks; ++b) nid[b] = block_id(b);
+    issue(0, nid);
+#pragma unroll
+    for (int b = 0; b < kPfBlocks; ++b) nid[b] = block_id(kPfBlocks + b);
     for (int st = 0; st < nstep; ++st) {
-        // this wave's loads of step st have landed (those of step st+1 may still fly) ...
-        if (st + 1 < nstep)
-            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NCP) : "memory");
-        else
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        // ... and after the barrier so have everybody's; nobody reads the buffer of step st-1 any more
+        const int buf = st & 1;
+        // this wave's loads of step st have landed, and after the barrier so have everybody's;
+        // nobody reads the other buffer (step st-1) any more
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        if (st + 2 < nstep) issue(st + 2, buf >= 1 ? buf - 1 : kPfRing - 1);   // (buf + 2) % 3
-        if (st * 32 <= w_pos_hi) {   // wave-uniform: some column of this wave sees keys of this step
-            f32x16 S;
+        const bool active = st * 64 <= w_pos_hi;   // wave-uniform: some column of this wave sees keys of this step
+        // the K operands of the first half are requested from LDS ...
+        u32x4 kop[KS];
+        if (active) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) S[r] = 0.f;
+            for (int ks = 0; ks < KS; ++ks) kop[ks] = lds[buf][ku * CH + (2 * ks + h) * 16 + kslot];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        // ... and while they travel the loads of step st+1 are sent off into the other buffer
+        if (st + 1 < nstep) {
+            issue(buf ^ 1, nid);
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                const u32x4 kop = lds[buf][ku * CH + (2 * ks + h) * 16 + kslot];
-                S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kop),
-                                                            __builtin_bit_cast(bf16x8, qb[ks]), S, 0, 0, 0);
-            }
-            const int tok0 = st * 32 + 8 * h;            // token of register 0; register r: +16(r/8) + r%8
-            const bool need_mask = (st * 32 + 31 > w_pos_lo);   // wave-uniform
-            if (need_mask) {
+            for (int b = 0; b < kPfBlocks; ++b) nid[b] = block_id(kPfBlocks * (st + 2) + b);
+        }
+        if (active) {
+            f32x16 S[2];
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int tok = tok0 + 16 * (r / 8) + (r % 8);
-                    S[r] = (tok <= pos) ? S[r] : -INFINITY;
+            for (int hh = 0; hh < 2; ++hh) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) S[hh][r] = 0.f;
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks)
+                    S[hh] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kop[ks]),
+                                                                __builtin_bit_cast(bf16x8, qb[ks]), S[hh], 0, 0, 0);
+                if (hh == 0) {   // second half's K operands (blocks 2, 3) into the same registers
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks)
+                        kop[ks] = lds[buf][(2 + ku) * CH + (2 * ks + h) * 16 + kslot];
                 }
+            }
+            // register r of half hh is token st*64 + 32hh + 8h + 16(r/8) + r%8
+            const int tok0 = st * 64 + 8 * h;
+            if (st * 64 + 63 > w_pos_lo) {   // wave-uniform: the step touches the causal diagonal
+                const int room = pos - tok0;             // visible iff 32hh + 16(r/8) + r%8 <= room
+#pragma unroll
+                for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        S[hh][r] = (32 * hh + 16 * (r / 8) + (r % 8) <= room) ? S[hh][r] : -INFINITY;
             }
             // raw scores here; the softmax scale rides in the fma that feeds exp2 (scale > 0, so the
             // maximum can be taken before scaling)
-            float mloc = S[0];
+            float mloc = fmaxf(S[0][0], S[1][0]);
 #pragma unroll
-            for (int r = 1; r < 16; ++r) mloc = fmaxf(mloc, S[r]);
+            for (int r = 1; r < 16; ++r) mloc = fmaxf(mloc, fmaxf(S[0][r], S[1][r]));
             {
                 float x, y;
                 swap32(mloc, x, y);
@@ -583,48 +607,54 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
             const float alpha = fast_exp2(m - m_new);
             const bool grow = m_new > m;
             m = m_new;
-            float psum = 0.f;
-            u32x4 P[2];
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                float e[8];
-#pragma unroll
-                for (int r = 0; r < 8; ++r) {
-                    e[r] = fast_exp2(__builtin_fmaf(S[8 * u + r], c_log2e, -m_new));
-                    psum += e[r];
-                }
-                P[u] = u32x4{pack2_bf16(e[0], e[1]), pack2_bf16(e[2], e[3]), pack2_bf16(e[4], e[5]), pack2_bf16(e[6], e[7])};
-            }
-            lsum = lsum * alpha + psum;
             if (__any(grow)) {
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) O[mb][r] *= alpha;
             }
-            // V slots at or past seq_len may hold anything: zero them (their P is 0, but 0*NaN is NaN)
-            const bool vmask = (st * 32 + 32 > seq_len);   // wave-uniform
+            // wave-uniform, last step of a sequence only: V slots at or past seq_len may hold anything
+            // and are zeroed (their P is 0, but 0*NaN is NaN)
+            const bool vmask = st * 64 + 64 > seq_len;
+            float psum = 0.f;
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                u32x4 mk = {0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu};
-                if (vmask) {
-                    const int t0 = tok0 + 16 * u;        // tokens t0 .. t0+7 in this lane's V operand
-                    const bool whole = (u == 1 && 2 * st + 1 >= nblk);   // the pair's second block does not exist
+            for (int hh = 0; hh < 2; ++hh) {
+                // exponentials of this half (the other half's run while this half's MFMAs execute)
+                u32x4 P[2];
 #pragma unroll
-                    for (int w = 0; w < 4; ++w)
-                        mk[w] = ((!whole && t0 + 2 * w < seq_len) ? 0x0000FFFFu : 0u) |
-                                ((!whole && t0 + 2 * w + 1 < seq_len) ? 0xFFFF0000u : 0u);
+                for (int u = 0; u < 2; ++u) {
+                    float e[8];
+#pragma unroll
+                    for (int r = 0; r < 8; ++r) {
+                        e[r] = fast_exp2(__builtin_fmaf(S[hh][8 * u + r], c_log2e, -m_new));
+                        psum += e[r];
+                    }
+                    P[u] = u32x4{pack2_bf16(e[0], e[1]), pack2_bf16(e[2], e[3]), pack2_bf16(e[4], e[5]),
+                                 pack2_bf16(e[6], e[7])};
                 }
 #pragma unroll
-                for (int mb = 0; mb < MB; ++mb) {
-                    u32x4 vop = lds[buf][(2 + u) * CH + h * HD + 32 * mb + col];
-                    if (vmask) vop &= mk;
-                    O[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vop),
-                                                                __builtin_bit_cast(bf16x8, P[u]), O[mb], 0, 0, 0);
+                for (int u = 0; u < 2; ++u) {
+                    u32x4 vop[MB];
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb)
+                        vop[mb] = lds[buf][(kPfBlocks + 2 * hh + u) * CH + h * HD + 32 * mb + col];
+                    if (vmask) {
+                        const int t0 = tok0 + 32 * hh + 16 * u;   // tokens t0 .. t0+7 in this lane's V operand
+                        u32x4 mk;
+#pragma unroll
+                        for (int w = 0; w < 4; ++w)
+                            mk[w] = (t0 + 2 * w < seq_len ? 0x0000FFFFu : 0u) | (t0 + 2 * w + 1 < seq_len ? 0xFFFF0000u : 0u);
+#pragma unroll
+                        for (int mb = 0; mb < MB; ++mb) vop[mb] &= mk;
+                    }
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb)
+                        O[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vop[mb]),
+                                                                    __builtin_bit_cast(bf16x8, P[u]), O[mb], 0, 0, 0);
                 }
             }
+            lsum = lsum * alpha + psum;
         }
-        buf = buf + 1 == kPfRing ? 0 : buf + 1;
     }
     float ltot;
     {
