@@ -37,7 +37,10 @@ struct PlanGeometry {
 // The compact plan: two cumulative arrays and a few scalars (see ooco_internal.h).
 struct HostPlan {
     std::vector<int32_t> dcum;   // [num_seqs+1] decode KV blocks before each sequence
-    std::vector<int32_t> tcum;   // [num_seqs+1] prefill query tiles before each sequence
+    // prefill chunks, heaviest (most keys) first: pf[0..P] = query tiles before chunk k of that
+    // order, pf[P+1+k] = sequence index of chunk k
+    std::vector<int32_t> pf;
+    int32_t num_pf = 0;
     int32_t dec_blocks = 0, static_blocks = 0, static_runs = 0, tail_runs = 0;
     int32_t n_tiles = 0, total_q = 0, num_seqs = 0;
     int64_t slots = 0;           // partial-result slots the decode kernel may touch
@@ -65,7 +68,6 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
         return bad(OOCO_ESHAPE, "ooco_plan: query_start_loc[0]=%d, expected 0", h_query_start_loc[0]);
     out.num_seqs = num_seqs;
     out.dcum.assign((size_t)num_seqs + 1, 0);
-    out.tcum.assign((size_t)num_seqs + 1, 0);
     int64_t dec_blocks = 0, tiles = 0;
     const int tile_rows = prefill_tile_rows(geo.Hq / geo.Hkv);
     for (int i = 0; i < num_seqs; ++i) {
@@ -85,11 +87,23 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
         if (dec_blocks > 0x7FFFFFFF / 2 || tiles > 0x7FFFFFFF / 128)
             return bad(OOCO_ESHAPE, "ooco_plan: batch too large");
         out.dcum[(size_t)i + 1] = (int32_t)dec_blocks;
-        out.tcum[(size_t)i + 1] = (int32_t)tiles;
     }
     out.total_q = num_seqs > 0 ? h_query_start_loc[num_seqs] : 0;
     out.dec_blocks = (int32_t)dec_blocks;
     out.n_tiles = (int32_t)tiles;
+    // prefill chunks in order of decreasing sequence length: workgroups are dispatched in index
+    // order, so the long ones start first and the short ones fill the end
+    std::vector<int32_t> order;
+    for (int i = 0; i < num_seqs; ++i)
+        if (h_query_start_loc[i + 1] - h_query_start_loc[i] > 1) order.push_back(i);
+    std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) { return h_seq_lens[x] > h_seq_lens[y]; });
+    out.num_pf = (int32_t)order.size();
+    out.pf.assign(2 * order.size() + 1, 0);
+    for (size_t k = 0; k < order.size(); ++k) {
+        const int64_t ql = (int64_t)h_query_start_loc[order[k] + 1] - h_query_start_loc[order[k]];
+        out.pf[k + 1] = out.pf[k] + (int32_t)((ql + tile_rows - 1) / tile_rows);
+        out.pf[order.size() + 1 + k] = order[k];
+    }
 
     // ---- run layout of the decode block line (see ooco_internal.h)
     if (dec_blocks > 0) {
@@ -391,7 +405,7 @@ ooco_status ooco_plan(ooco_ctx *ctx, int num_seqs, const int32_t *h_seq_lens, co
     geo.tail_blocks = ctx->opt_tail_blocks;
     ooco_status st = build_plan(geo, num_seqs, h_seq_lens, h_query_start_loc, h_ctx_lens, ctx->plan, ctx->err);
     if (st != OOCO_OK) return st;
-    if ((size_t)num_seqs * ctx->Hkv > kCounterInts - 1 || 2 * ((size_t)num_seqs + 1) > kPlanInts)
+    if ((size_t)num_seqs * ctx->Hkv > kCounterInts - 1 || 3 * ((size_t)num_seqs + 1) > kPlanInts)
         return fail(ctx, OOCO_ENOMEM, "ooco_plan: %d sequences exceed the context's counter/plan buffers", num_seqs);
     ctx->plan_valid = true;
     ctx->plan_dirty = true;
@@ -507,13 +521,13 @@ ooco_status ooco_attn_mixed(ooco_ctx *ctx, const void *q, const void *k_cache, c
                     pl.num_seqs, pl.total_q, num_seqs, total_q_tokens);
 
     // The cumulative arrays ride in the kernel arguments; only very large batches need a copy.
-    const bool inline_cum = num_seqs <= kInlineSeqs;
-    const size_t n_cum = (size_t)num_seqs + 1;
+    const size_t n_cum = (size_t)num_seqs + 1, n_pf = pl.pf.size();
+    const bool inline_cum = n_cum <= (size_t)kInlineSeqs + 1 && n_pf <= (size_t)kInlineSeqs + 1;
     if (!inline_cum && ctx->plan_dirty) {
         if (ctx->upload_pending) (void)hipEventSynchronize(ctx->upload_done);
         memcpy(ctx->plan_h, pl.dcum.data(), n_cum * sizeof(int32_t));
-        memcpy(ctx->plan_h + n_cum, pl.tcum.data(), n_cum * sizeof(int32_t));
-        hipError_t e = hipMemcpyAsync(ctx->plan_d, ctx->plan_h, 2 * n_cum * sizeof(int32_t), hipMemcpyHostToDevice, s);
+        memcpy(ctx->plan_h + n_cum, pl.pf.data(), n_pf * sizeof(int32_t));
+        hipError_t e = hipMemcpyAsync(ctx->plan_d, ctx->plan_h, (n_cum + n_pf) * sizeof(int32_t), hipMemcpyHostToDevice, s);
         if (e == hipSuccess) e = hipEventRecord(ctx->upload_done, s);
         if (e != hipSuccess) return fail(ctx, OOCO_EHIP, "ooco_attn_mixed: plan upload: %s", hipGetErrorString(e));
         ctx->upload_pending = true;
@@ -551,6 +565,7 @@ ooco_status ooco_attn_mixed(ooco_ctx *ctx, const void *q, const void *k_cache, c
     p.queue = reinterpret_cast<uint32_t *>(ctx->counters + kCounterInts - 1);
     p.queue_base = ctx->queue_base;
     p.n_tiles = pl.n_tiles;
+    p.num_pf = pl.num_pf;
     p.tile_rows = prefill_tile_rows(ctx->g);
     p.nbi = (int32_t)ctx->opt_nbi;
     p.rotate_heads = (int32_t)ctx->opt_rotate;
@@ -572,7 +587,7 @@ ooco_status ooco_attn_mixed(ooco_ctx *ctx, const void *q, const void *k_cache, c
     if (ev) e = hipEventRecord(ev[0], s);
     if (e == hipSuccess && pl.n_tiles > 0) {
         p.cum_dev = inline_cum ? nullptr : ctx->plan_d + n_cum;
-        if (inline_cum) memcpy(ka.cum, pl.tcum.data(), n_cum * sizeof(int32_t));
+        if (inline_cum) memcpy(ka.cum, pl.pf.data(), n_pf * sizeof(int32_t));
         e = launch_prefill(ka, s);
     }
     if (ev && e == hipSuccess) e = hipEventRecord(ev[1], s);

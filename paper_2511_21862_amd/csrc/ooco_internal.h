@@ -13,8 +13,10 @@
 //             A piece that does not cover its whole sequence writes a partial result into slot
 //             (run index) + i; the last piece of a sequence to finish merges the slots (arrival
 //             counter per sequence and kv head).
-//   prefill - cum[i] = number of query tiles (tile_rows = 128 / (Hq/Hkv) rows each, all heads of
-//             a GQA group) before sequence i; one workgroup per (tile, kv head).
+//   prefill - the P chunks (q_len > 1) are listed longest sequence first; cum[k] = number of query
+//             tiles (tile_rows = 128 / (Hq/Hkv) rows each, all heads of a GQA group) before
+//             chunk k of that list, cum[P+1+k] = its sequence index; one workgroup per
+//             (tile, kv head), heavy tiles first.
 // The cumulative array travels inside the kernel arguments (no upload, no synchronisation) when
 // the batch has at most kInlineSeqs sequences, else through a device buffer.
 #pragma once
@@ -48,6 +50,7 @@ struct AttnParams {
     int32_t num_seqs, total_q;
     int32_t dec_blocks, static_blocks, static_runs, tail_runs;   // decode run layout
     int32_t n_tiles, tile_rows; // prefill: tiles per kv head, query rows per tile
+    int32_t num_pf, pad_pf;     // prefill: number of chunks (entries of the prefill array, see below)
     int32_t nbi;                // tuning: KV blocks per softmax step of the decode kernel
     int32_t rotate_heads;       // tuning: kv head rotation across XCDs
     uint32_t queue_base;        // ticket value at which this launch's tail runs start

@@ -449,8 +449,9 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
     int seq, q_row0, rows, pos0, seq_len;
     {
         auto cum_at = [&](int idx) -> int { return p.cum_dev ? p.cum_dev[idx] : a.cum[idx]; };
-        seq = __builtin_amdgcn_readfirstlane(count_le(cum_at, p.num_seqs, tile_idx, lane));
-        const int t_end = cum_at(seq + 1);
+        const int chunk = __builtin_amdgcn_readfirstlane(count_le(cum_at, p.num_pf, tile_idx, lane));
+        const int t_end = cum_at(chunk + 1);
+        seq = min(max(cum_at(p.num_pf + 1 + chunk), 0), p.num_seqs - 1);
         const int t = (t_end - 1) - tile_idx;             // reversed order inside the sequence
         const int q0 = p.query_start_loc[seq];
         const int q_len = p.query_start_loc[seq + 1] - q0;
