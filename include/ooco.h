@@ -102,7 +102,10 @@ const char *ooco_last_error(const ooco_ctx *ctx);
  * boundary, or a sequence that spans several runs, is handled by partial results merged inside
  * the decode kernel.  These three take effect at the next ooco_plan.  "profile" (0/1, immediate): when set, every ooco_attn_mixed records HIP events
  * on its stream around its two kernels (prefill, decode) for ooco_profile_read; at most 1024
- * calls between two reads.  "trace" (0/1, immediate): see ooco_trace_read.  "decode_nbi" (1, 2 or
+ * calls between two reads.  "overlap" (0/1, default 1, immediate): in a batch that holds both
+ * prefill chunks and decode sequences, run the prefill kernel on the context's own side stream
+ * (default priority) concurrently with the decode kernel; the call still appears as one unit of
+ * work on the caller's stream (fork and join by events).  "trace" (0/1, immediate): see ooco_trace_read.  "decode_nbi" (1, 2 or
  * 4, immediate): KV blocks per softmax step of the decode kernel (0 = default).
  * Unknown name -> OOCO_EINVAL. */
 ooco_status ooco_set_option(ooco_ctx *ctx, const char *name, int64_t value);

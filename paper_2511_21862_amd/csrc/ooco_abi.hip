@@ -199,6 +199,9 @@ struct ooco_ctx {
     int64_t opt_nbi = 0;
     int64_t opt_trace = 0;
     int64_t opt_rotate = 1;
+    int64_t opt_overlap = 1;
+    hipStream_t side_stream = nullptr;   // default priority; carries the prefill kernel of mixed batches
+    hipEvent_t fork_ev = nullptr, join_ev = nullptr;
     uint64_t *trace_d = nullptr;   // [kTraceWaves][4] decode-wave time stamps
     int64_t trace_waves = 0;       // waves of the last traced call
     int64_t opt_profile = 0;
@@ -284,11 +287,17 @@ ooco_status ooco_ctx_create(ooco_ctx **out, int num_q_heads, int num_kv_heads, i
     if (e == hipSuccess) e = hipMalloc((void **)&c->counters, kCounterInts * sizeof(int32_t));
     if (e == hipSuccess) e = hipMemset(c->counters, 0, kCounterInts * sizeof(int32_t));
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->upload_done, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->side_stream, hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->fork_ev, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->join_ev, hipEventDisableTiming);
     if (e != hipSuccess) {
         fail(nullptr, e == hipErrorOutOfMemory ? OOCO_ENOMEM : OOCO_EHIP, "ooco_ctx_create: %s", hipGetErrorString(e));
         ooco_status st = e == hipErrorOutOfMemory ? OOCO_ENOMEM : OOCO_EHIP;
         (void)hipGetLastError();
         if (c->upload_done) (void)hipEventDestroy(c->upload_done);
+        if (c->fork_ev) (void)hipEventDestroy(c->fork_ev);
+        if (c->join_ev) (void)hipEventDestroy(c->join_ev);
+        if (c->side_stream) (void)hipStreamDestroy(c->side_stream);
         if (c->counters) (void)hipFree(c->counters);
         if (c->plan_d) (void)hipFree(c->plan_d);
         if (c->plan_h) (void)hipHostFree(c->plan_h);
@@ -306,6 +315,9 @@ ooco_status ooco_ctx_destroy(ooco_ctx *ctx)
     if (ctx->upload_pending) (void)hipEventSynchronize(ctx->upload_done);
     (void)hipDeviceSynchronize();
     if (ctx->upload_done) (void)hipEventDestroy(ctx->upload_done);
+    if (ctx->fork_ev) (void)hipEventDestroy(ctx->fork_ev);
+    if (ctx->join_ev) (void)hipEventDestroy(ctx->join_ev);
+    if (ctx->side_stream) (void)hipStreamDestroy(ctx->side_stream);
     for (hipEvent_t x : ctx->prof_ev)
         if (x) (void)hipEventDestroy(x);
     if (ctx->trace_d) (void)hipFree(ctx->trace_d);
@@ -369,6 +381,9 @@ ooco_status ooco_set_option(ooco_ctx *ctx, const char *name, int64_t value)
             if (e != hipSuccess) return fail(ctx, OOCO_ENOMEM, "ooco_set_option: trace buffer: %s", hipGetErrorString(e));
         }
         ctx->opt_trace = value;
+        return OOCO_OK;
+    } else if (!strcmp(name, "overlap")) {
+        ctx->opt_overlap = value;
         return OOCO_OK;
     } else if (!strcmp(name, "rotate_heads")) {
         ctx->opt_rotate = value;
@@ -584,11 +599,24 @@ ooco_status ooco_attn_mixed(ooco_ctx *ctx, const void *q, const void *k_cache, c
         }
         ev = ctx->prof_ev.data() + 3 * ctx->prof_calls++;
     }
+    // A mixed batch runs its two kernels side by side: the prefill kernel (matrix-core bound) goes to
+    // the context's side stream, forked from and joined back into the caller's stream with events,
+    // the decode kernel (HBM bound) stays on the caller's stream.  With per-kernel profiling on
+    // they run one after the other so that each gets a clean time.
+    const bool mixed = pl.n_tiles > 0 && pl.static_runs > 0;
+    const bool overlap = mixed && !ev && ctx->opt_overlap && ctx->side_stream;
     if (ev) e = hipEventRecord(ev[0], s);
     if (e == hipSuccess && pl.n_tiles > 0) {
         p.cum_dev = inline_cum ? nullptr : ctx->plan_d + n_cum;
         if (inline_cum) memcpy(ka.cum, pl.pf.data(), n_pf * sizeof(int32_t));
-        e = launch_prefill(ka, s);
+        if (overlap) {
+            e = hipEventRecord(ctx->fork_ev, s);
+            if (e == hipSuccess) e = hipStreamWaitEvent(ctx->side_stream, ctx->fork_ev, 0);
+            if (e == hipSuccess) e = launch_prefill(ka, ctx->side_stream);
+            if (e == hipSuccess) e = hipEventRecord(ctx->join_ev, ctx->side_stream);
+        } else {
+            e = launch_prefill(ka, s);
+        }
     }
     if (ev && e == hipSuccess) e = hipEventRecord(ev[1], s);
     if (e == hipSuccess && pl.static_runs > 0) {
@@ -599,6 +627,7 @@ ooco_status ooco_attn_mixed(ooco_ctx *ctx, const void *q, const void *k_cache, c
         if (e == hipSuccess && pl.tail_runs > 0)
             ctx->queue_base += (uint32_t)pl.tail_runs * (uint32_t)ctx->Hkv + (uint32_t)pl.static_runs * (uint32_t)ctx->Hkv;
     }
+    if (overlap && e == hipSuccess) e = hipStreamWaitEvent(s, ctx->join_ev, 0);
     if (ev && e == hipSuccess) e = hipEventRecord(ev[2], s);
     if (ctx->plan_one_shot) {
         ctx->plan_one_shot = false;
