@@ -114,6 +114,9 @@ def bench_block_copy(a):
               for _ in range(2)]
     src_d = torch.from_numpy(src).cuda()
     ctx = B.Context(b.Hq, b.Hkv, b.hd, b.BS, b.num_blocks, b.max_blocks_per_seq)
+    for o in a.opt:
+        k, v = o.split("=")
+        ctx.set_option(k, int(v))
     stream = torch.cuda.current_stream()
 
     def step(i):

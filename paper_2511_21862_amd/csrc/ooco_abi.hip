@@ -382,6 +382,9 @@ ooco_status ooco_set_option(ooco_ctx *ctx, const char *name, int64_t value)
         }
         ctx->opt_trace = value;
         return OOCO_OK;
+    } else if (!strcmp(name, "copy_variant")) {
+        g_copy_variant = (int)value;
+        return OOCO_OK;
     } else if (!strcmp(name, "overlap")) {
         ctx->opt_overlap = value;
         return OOCO_OK;

@@ -71,6 +71,8 @@ hipError_t launch_block_copy(const void *k_src, const void *v_src, void *k_dst, 
                              const int64_t *src_ids, const int64_t *dst_ids, int64_t num_pairs,
                              int64_t block_bytes, hipStream_t s);
 
+extern int g_copy_variant;   // tuning knob of the block-copy kernel (option "copy_variant")
+
 // Query rows of one prefill tile for a GQA group of g heads.
 __host__ __device__ inline int32_t prefill_tile_rows(int32_t g) { return kPrefillCols / g > 0 ? kPrefillCols / g : 1; }
 

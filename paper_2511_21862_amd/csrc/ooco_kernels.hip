@@ -682,8 +682,8 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
 // KV block copy: workgroup (pair, which pool, slice) moves a contiguous slice of one block with
 // 16-byte loads and stores; all loads of a thread are issued before its stores.
 constexpr int kCopyThreads = 256;
-constexpr int kCopyVecPerThread = 4;   // 256 threads x 4 x 16 B = 16 KiB per workgroup
 
+template <int VPT, bool NT>
 __global__ __launch_bounds__(kCopyThreads) void block_copy_kernel(const u32x4 *k_src, const u32x4 *v_src, u32x4 *k_dst,
                                                                   u32x4 *v_dst, const int64_t *src_ids,
                                                                   const int64_t *dst_ids, int64_t block_vecs,
@@ -696,19 +696,26 @@ __global__ __launch_bounds__(kCopyThreads) void block_copy_kernel(const u32x4 *k
     const int64_t sb = src_ids[pair], db = dst_ids[pair];
     const u32x4 *src = (which ? v_src : k_src) + sb * block_vecs;
     u32x4 *dst = (which ? v_dst : k_dst) + db * block_vecs;
-    const int64_t base = (int64_t)slice * kCopyThreads * kCopyVecPerThread + threadIdx.x;
-    u32x4 r[kCopyVecPerThread];
+    const int64_t base = (int64_t)slice * kCopyThreads * VPT + threadIdx.x;
+    u32x4 r[VPT];
 #pragma unroll
-    for (int i = 0; i < kCopyVecPerThread; ++i) {
+    for (int i = 0; i < VPT; ++i) {
         const int64_t idx = base + (int64_t)i * kCopyThreads;
-        if (idx < block_vecs) r[i] = __builtin_nontemporal_load(src + idx);
+        if (idx < block_vecs) r[i] = NT ? __builtin_nontemporal_load(src + idx) : src[idx];
     }
 #pragma unroll
-    for (int i = 0; i < kCopyVecPerThread; ++i) {
+    for (int i = 0; i < VPT; ++i) {
         const int64_t idx = base + (int64_t)i * kCopyThreads;
-        if (idx < block_vecs) __builtin_nontemporal_store(r[i], dst + idx);
+        if (idx < block_vecs) {
+            if (NT)
+                __builtin_nontemporal_store(r[i], dst + idx);
+            else
+                dst[idx] = r[i];
+        }
     }
 }
+
+int g_copy_variant = 0;   // tuning: 10*vectors per thread + non-temporal flag (0 = default)
 
 // ------------------------------------------------------------------------------------------
 hipError_t launch_decode(const KernArgs &a, hipStream_t s)
@@ -744,11 +751,25 @@ hipError_t launch_block_copy(const void *k_src, const void *v_src, void *k_dst, 
 {
     if (num_pairs == 0) return hipSuccess;
     const int64_t block_vecs = block_bytes / 16;
-    const int per_wg = kCopyThreads * kCopyVecPerThread;
+    const int variant = g_copy_variant ? g_copy_variant : 41;
+    const int vpt = variant / 10;
+    const int per_wg = kCopyThreads * vpt;
     const int slices = (int)((block_vecs + per_wg - 1) / per_wg);
     const dim3 grid((unsigned)(num_pairs * 2 * slices)), block(kCopyThreads);
-    hipLaunchKernelGGL(block_copy_kernel, grid, block, 0, s, (const u32x4 *)k_src, (const u32x4 *)v_src, (u32x4 *)k_dst,
-                       (u32x4 *)v_dst, src_ids, dst_ids, block_vecs, slices);
+#define OOCO_COPY(V, N)                                                                                              \
+    hipLaunchKernelGGL((block_copy_kernel<V, N>), grid, block, 0, s, (const u32x4 *)k_src, (const u32x4 *)v_src,      \
+                       (u32x4 *)k_dst, (u32x4 *)v_dst, src_ids, dst_ids, block_vecs, slices)
+    switch (variant) {
+    case 20: OOCO_COPY(2, false); break;
+    case 21: OOCO_COPY(2, true); break;
+    case 40: OOCO_COPY(4, false); break;
+    case 80: OOCO_COPY(8, false); break;
+    case 81: OOCO_COPY(8, true); break;
+    case 10: OOCO_COPY(1, false); break;
+    case 11: OOCO_COPY(1, true); break;
+    default: OOCO_COPY(4, true); break;
+    }
+#undef OOCO_COPY
     return hipGetLastError();
 }
 
