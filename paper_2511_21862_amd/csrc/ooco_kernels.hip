@@ -36,6 +36,22 @@ OOCO_DEV uint32_t pack2_bf16(float a, float b)
 
 OOCO_DEV float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// max of three without the NaN-quieting moves that fmaxf would add (one v_max3_f32)
+OOCO_DEV float max3(float a, float b, float c)
+{
+    float d;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+    return d;
+}
+
+// acc + lo + hi of a packed bf16 pair (one v_dot2c_f32_bf16 against the pair (1, 1))
+OOCO_DEV float sum2_bf16(uint32_t pair, float acc)
+{
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pair), __builtin_bit_cast(bf16x2, 0x3F803F80u), acc,
+                                           false);
+}
+
 // Device-scope (all XCDs) relaxed store / load of one float: the store writes through to memory,
 // the load bypasses the non-coherent cache levels.
 typedef float f32x2 __attribute__((ext_vector_type(2)));
@@ -464,6 +480,7 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
         pos0 = min(max(p.ctx_lens[seq] + t0, 0), cap - rows);
         seq_len = min(seq_len, cap);
         // all of these are the same in every lane: keep them in scalar registers
+        seq = __builtin_amdgcn_readfirstlane(seq);
         q_row0 = __builtin_amdgcn_readfirstlane(q_row0);
         rows = __builtin_amdgcn_readfirstlane(rows);
         pos0 = __builtin_amdgcn_readfirstlane(pos0);
@@ -520,7 +537,9 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
         for (int n = 0; n < NCP; ++n) {
             const int grp = wave + 4 * n;                  // wave-uniform
             const int cidx = grp * 64 + lane;
-            const int which = (grp * 64) / CH;             // 0..3: K blocks, 4..7: V blocks (uniform)
+            // 0..3: K blocks, 4..7: V blocks (wave-uniform; a compile-time constant when a tile has at
+            // least 256 chunks, which keeps pb[] in registers without select chains)
+            const int which = CH >= 256 ? (4 * n * 64) / CH : (grp * 64) / CH;
             const int r = cidx - which * CH;
             const int64_t off = ((int64_t)pb[which & (kPfBlocks - 1)] * Hkv + kvh) * tile_elems;
             const u32x4 *src = which < kPfBlocks
@@ -596,9 +615,11 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
             }
             // raw scores here; the softmax scale rides in the fma that feeds exp2 (scale > 0, so the
             // maximum can be taken before scaling)
-            float mloc = fmaxf(S[0][0], S[1][0]);
+            float mloc = max3(S[0][0], S[1][0], S[0][1]);
+            mloc = max3(mloc, S[1][1], S[0][2]);
 #pragma unroll
-            for (int r = 1; r < 16; ++r) mloc = fmaxf(mloc, fmaxf(S[0][r], S[1][r]));
+            for (int r = 2; r < 15; ++r) mloc = max3(mloc, S[1][r], S[0][r + 1]);
+            mloc = fmaxf(mloc, S[1][15]);
             {
                 float x, y;
                 swap32(mloc, x, y);
@@ -628,10 +649,12 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
 #pragma unroll
                     for (int r = 0; r < 8; ++r) {
                         e[r] = fast_exp2(__builtin_fmaf(S[hh][8 * u + r], c_log2e, -m_new));
-                        psum += e[r];
                     }
                     P[u] = u32x4{pack2_bf16(e[0], e[1]), pack2_bf16(e[2], e[3]), pack2_bf16(e[4], e[5]),
                                  pack2_bf16(e[6], e[7])};
+                    // the denominator sums the same rounded weights that enter the PV product
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) psum = sum2_bf16(P[u][w], psum);
                 }
 #pragma unroll
                 for (int u = 0; u < 2; ++u) {
