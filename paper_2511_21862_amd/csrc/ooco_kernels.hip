@@ -420,24 +420,27 @@ __global__ __launch_bounds__(64) void decode_kernel(const KernArgs a)
 // columns of a workgroup are the (row, head) pairs of tile_rows = 128/g consecutive query rows
 // and the g query heads that share the kv head (column c = row*g + head), 32 columns per wave,
 // so every K/V tile fetched serves the whole GQA group.  KV is walked four blocks (64 tokens) per
-// step; the workgroup keeps the step's K and V tiles (32 KiB for hd 128) in one of two LDS
-// buffers, filled by direct global->LDS loads issued one step ahead, one barrier per step.
-// Per wave and step, for each 32-token half:
+// step through two LDS slots for K and two for V (64 KiB for hd 128), filled by direct
+// global->LDS loads, one barrier per step.  Per wave and step, for each 32-token half:
 //   S^T[32 tok][32 cols] = K · Q^T    (hd/16 x v_mfma_f32_32x32x16_bf16, K operand from LDS)
 //   O^T[hd][32 cols]    += V^T · P^T  (hd/32 x 2 x v_mfma_f32_32x32x16_bf16, V operand from LDS)
-// with one softmax update over the 64 scores of a column.  Lane l = 32*h + col.  MFMA row i of
-// the K operand is fed with token (i with bits 2 and 3 swapped) of its block, so that S^T
-// register r of lane (col, h) is token 16(r/8) + 8h + r%8 of the half: eight consecutive tokens
-// per block, which is what one 16-byte V operand holds.
-// LDS (16-byte units, CH = 2*hd per tile): [K blk0..3 | V blk0..3]; K tiles keep the cache order
-// [hd/8][16 slots]; V tiles are stored [token half][dim] so that the 16 lanes of a quarter wave
-// read 256 contiguous bytes (no bank conflicts).
+// with one softmax update over the 64 scores of a column.  The loop is software pipelined: the
+// score MFMAs of step st+1 are issued together with the softmax arithmetic of step st (two score
+// register sets that swap roles every step), so that the matrix core works on the next scores
+// while the vector ALU exponentiates the current ones; K therefore runs one step ahead of V:
+// at the top of step st the loads of K[st+2] and V[st+1] are sent off.
+// Lane l = 32*h + col.  MFMA row i of the K operand is fed with token (i with bits 2 and 3
+// swapped) of its block, so that S^T register r of lane (col, h) is token 16(r/8) + 8h + r%8 of
+// the half: eight consecutive tokens per block, which is what one 16-byte V operand holds.
+// LDS (16-byte units, CH = 2*hd per tile): K tiles keep the cache order [hd/8][16 slots]; V tiles
+// are stored [token half][dim] so that the 16 lanes of a quarter wave read 256 contiguous bytes
+// (no bank conflicts).
 // The SIMD's VALU issue port is shared with the matrix core (a 32x32x16 MFMA holds it for half of
 // its 32 cycles), so the kernel is tuned for few vector instructions per MFMA: 64-token steps
-// halve the per-step bookkeeping, masks run only on steps that touch the causal diagonal or
-// the end of the sequence.  Two workgroups fit a CU (<= 256 VGPRs, 64 KiB LDS each).
+// halve the per-step bookkeeping, maxima use v_max3, row sums v_dot2c on the packed weights,
+// masks run only on steps that touch the causal diagonal or the end of the sequence.  Two
+// workgroups fit a CU (<= 256 VGPRs, 64 KiB LDS each).
 constexpr int kPfThreads = 256;
-constexpr int kPfRing = 2;      // LDS buffers: step st being read, step st+1 being filled
 constexpr int kPfBlocks = 4;    // KV blocks per step
 
 template <int HD>
@@ -447,9 +450,10 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
     constexpr int KS = HD / 16;        // k-steps of QK
     constexpr int MB = HD / 32;        // 32-dim groups of the output
     constexpr int CH = HD * 2;         // 16-byte chunks per (block, kv head) tile
-    constexpr int BUF = 2 * kPfBlocks * CH;             // chunks per LDS buffer
-    constexpr int NCP = BUF / kPfThreads;               // chunks each thread moves per step
-    __shared__ u32x4 lds[kPfRing][BUF];
+    constexpr int STAGE = kPfBlocks * CH;               // chunks of one step's K (or V) tiles
+    constexpr int NCP = STAGE / kPfThreads;             // chunks each thread moves per stage
+    __shared__ u32x4 ldsK[2][STAGE];
+    __shared__ u32x4 ldsV[2][STAGE];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -489,7 +493,8 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
     const uint16_t *const k_cache = p.k_cache, *const v_cache = p.v_cache;
     const int Hkv = p.Hkv;
     const float c_log2e = p.scale_log2e;
-    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)&lds[0][0];
+    const uint32_t ldsK_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)&ldsK[0][0];
+    const uint32_t ldsV_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)&ldsV[0][0];
     // this lane's query column
     const int c = wave * 32 + col;
     const int c_row = c / g, c_head = c - c_row * g;
@@ -521,35 +526,36 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
     const int ku = col >> 4;
     const int kslot = (col & 3) | ((col & 4) << 1) | ((col & 8) >> 1);
 
-    // One step's tiles go from global memory straight into LDS (global_load_lds_dwordx4: every lane
-    // gives a 16-byte global address, the wave's 64 pieces land contiguously at the LDS address in
-    // M0).  Wave w moves the 64-chunk groups w, w+4, ...; chunk cidx of the buffer comes from
-    //   K (cidx < 4*CH): block cidx/CH of the step, cache chunk cidx%CH   (same order as the cache)
-    //   V: block (cidx/CH)-4, LDS position r = half*HD + dim  <-  cache chunk 2*dim + half
+    // One stage (the K or the V tiles of a step) goes from global memory straight into LDS
+    // (global_load_lds_dwordx4: every lane gives a 16-byte global address, the wave's 64 pieces land
+    // contiguously at the LDS address in M0).  Wave w moves the 64-chunk groups w, w+4, ...; chunk
+    // cidx of the stage belongs to block cidx/CH of the step and comes from
+    //   K: cache chunk cidx%CH   (same order as the cache)
+    //   V: LDS position r = half*HD + dim  <-  cache chunk 2*dim + half
     // The instruction is issued through inline asm so that the waits stay under this code's
     // control.  (The block table is read through the constant address space: scalar loads, which
     // the waits on the vector-memory counter do not see.)
     typedef const __attribute__((address_space(4))) int32_t *const_i32_ptr;
     const const_i32_ptr ctable = (const_i32_ptr)(uintptr_t)table;
     auto block_id = [&](int b) -> int { return ctable[min(b, nblk - 1)]; };
-    auto issue = [&](int buf, const int (&pb)[kPfBlocks]) {   // pb: physical ids of the step's blocks
+    auto issue = [&](bool is_v, int slot, const int (&pb)[kPfBlocks]) {   // pb: physical ids of the step's blocks
 #pragma unroll
         for (int n = 0; n < NCP; ++n) {
             const int grp = wave + 4 * n;                  // wave-uniform
             const int cidx = grp * 64 + lane;
-            // 0..3: K blocks, 4..7: V blocks (wave-uniform; a compile-time constant when a tile has at
-            // least 256 chunks, which keeps pb[] in registers without select chains)
+            // block of the step (wave-uniform; a compile-time constant when a tile has at least 256
+            // chunks, which keeps pb[] in registers without select chains)
             const int which = CH >= 256 ? (4 * n * 64) / CH : (grp * 64) / CH;
             const int r = cidx - which * CH;
-            const int64_t off = ((int64_t)pb[which & (kPfBlocks - 1)] * Hkv + kvh) * tile_elems;
-            const u32x4 *src = which < kPfBlocks
-                                   ? reinterpret_cast<const u32x4 *>(k_cache + off) + r
-                                   : reinterpret_cast<const u32x4 *>(v_cache + off) + (2 * (r % HD) + r / HD);
-            const uint32_t dst = lds_base + (uint32_t)((buf * BUF + grp * 64) * 16);
+            const int64_t off = ((int64_t)pb[which] * Hkv + kvh) * tile_elems;
+            // scalar tile address + 32-bit lane offset (bytes)
+            const uint16_t *base = (is_v ? v_cache : k_cache) + off;
+            const uint32_t voff = (uint32_t)(is_v ? 2 * (r % HD) + r / HD : r) * 16u;
+            const uint32_t dst = (is_v ? ldsV_base : ldsK_base) + (uint32_t)((slot * STAGE + grp * 64) * 16);
             uint32_t saved_m0;   // M0 is restored: the compiler may keep a value of its own there
-            asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\ts_mov_b32 m0, %0"
+            asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3\n\ts_mov_b32 m0, %0"
                          : "=&s"(saved_m0)
-                         : "s"(dst), "v"(src)
+                         : "s"(dst), "v"(voff), "s"(base)
                          : "memory");
         }
     };
@@ -559,126 +565,160 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) O[mb][r] = 0.f;
-    float m = -INFINITY, lsum = 0.f;
 
-    int nid[kPfBlocks];   // ids of the step issued next, fetched one iteration ahead
+    // scores of one step: S[hh] register r is token st*64 + 32hh + 8h + 16(r/8) + r%8
+    auto qk = [&](f32x16 (&S)[2], int slot) {
 #pragma unroll
-    for (int b = 0; b < kPfBlocks; ++b) nid[b] = block_id(b);
-    issue(0, nid);
+        for (int hh = 0; hh < 2; ++hh) {
 #pragma unroll
-    for (int b = 0; b < kPfBlocks; ++b) nid[b] = block_id(kPfBlocks + b);
-    for (int st = 0; st < nstep; ++st) {
-        const int buf = st & 1;
-        // this wave's loads of step st have landed, and after the barrier so have everybody's;
-        // nobody reads the other buffer (step st-1) any more
+            for (int r = 0; r < 16; ++r) S[hh][r] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const u32x4 kop = ldsK[slot][(2 * hh + ku) * CH + (2 * ks + h) * 16 + kslot];
+                S[hh] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kop),
+                                                            __builtin_bit_cast(bf16x8, qb[ks]), S[hh], 0, 0, 0);
+            }
+        }
+    };
+    // causal mask of a step that touches the diagonal
+    auto mask = [&](f32x16 (&S)[2], int st) {
+        const int room = pos - (st * 64 + 8 * h);        // visible iff 32hh + 16(r/8) + r%8 <= room
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                S[hh][r] = (32 * hh + 16 * (r / 8) + (r % 8) <= room) ? S[hh][r] : -INFINITY;
+    };
+    float m = -INFINITY, lsum = 0.f;
+    // online-softmax update with the raw scores of one step; P[2hh+u] holds the packed weights of
+    // tokens 32hh + 16u + 8h + 0..7.  The softmax scale rides in the fma that feeds exp2 (scale > 0,
+    // so the maximum can be taken before scaling).
+    auto softmax = [&](const f32x16 (&S)[2], u32x4 (&P)[4], float &alpha, bool &grow) {
+        float mloc = max3(S[0][0], S[1][0], S[0][1]);
+        mloc = max3(mloc, S[1][1], S[0][2]);
+#pragma unroll
+        for (int r = 2; r < 15; ++r) mloc = max3(mloc, S[1][r], S[0][r + 1]);
+        mloc = fmaxf(mloc, S[1][15]);
+        {
+            float x, y;
+            swap32(mloc, x, y);
+            mloc = fmaxf(x, y) * c_log2e;
+        }
+        const float m_new = fmaxf(m, mloc);
+        alpha = fast_exp2(m - m_new);
+        grow = m_new > m;
+        m = m_new;
+        float psum = 0.f;
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+            float e[8];
+#pragma unroll
+            for (int r = 0; r < 8; ++r) e[r] = fast_exp2(__builtin_fmaf(S[q4 >> 1][8 * (q4 & 1) + r], c_log2e, -m_new));
+            P[q4] = u32x4{pack2_bf16(e[0], e[1]), pack2_bf16(e[2], e[3]), pack2_bf16(e[4], e[5]),
+                          pack2_bf16(e[6], e[7])};
+            // the denominator sums the same rounded weights that enter the PV product
+#pragma unroll
+            for (int w = 0; w < 4; ++w) psum = sum2_bf16(P[q4][w], psum);
+        }
+        lsum = lsum * alpha + psum;
+    };
+    auto pv = [&](const u32x4 (&P)[4], int slot, int st) {
+        // wave-uniform, last step of a sequence only: V slots at or past seq_len may hold anything
+        // and are zeroed (their P is 0, but 0*NaN is NaN)
+        const bool vmask = st * 64 + 64 > seq_len;
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+            u32x4 vop[MB];
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) vop[mb] = ldsV[slot][q4 * CH + h * HD + 32 * mb + col];
+            if (vmask) {
+                const int t0 = st * 64 + 8 * h + 16 * q4;   // tokens t0 .. t0+7 in this lane's V operand
+                u32x4 mk;
+#pragma unroll
+                for (int w = 0; w < 4; ++w)
+                    mk[w] = (t0 + 2 * w < seq_len ? 0x0000FFFFu : 0u) | (t0 + 2 * w + 1 < seq_len ? 0xFFFF0000u : 0u);
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) vop[mb] &= mk;
+            }
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+                O[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vop[mb]),
+                                                            __builtin_bit_cast(bf16x8, P[q4]), O[mb], 0, 0, 0);
+        }
+    };
+
+    int ids1[kPfBlocks], ids2[kPfBlocks];   // block ids of the steps st+1 and st+2
+    {
+        int ids0[kPfBlocks];
+#pragma unroll
+        for (int b = 0; b < kPfBlocks; ++b) {
+            ids0[b] = block_id(b);
+            ids1[b] = block_id(kPfBlocks + b);
+            ids2[b] = block_id(2 * kPfBlocks + b);
+        }
+        issue(false, 0, ids0);
+        issue(true, 0, ids0);
+        if (nstep > 1) issue(false, 1, ids1);
+    }
+    // One step.  Sc: scores of step st (computed during step st-1), Sn: receives those of step st+1.
+    auto body = [&](f32x16 (&Sc)[2], f32x16 (&Sn)[2], int st) {
+        // this wave's loads of K[st+1] and V[st] have landed, and after the barrier so have
+        // everybody's; nobody reads K[st] or V[st-1] any more
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        const bool active = st * 64 <= w_pos_hi;   // wave-uniform: some column of this wave sees keys of this step
-        // the K operands of the first half are requested from LDS ...
-        u32x4 kop[KS];
-        if (active) {
+        if (st + 2 < nstep) issue(false, st & 1, ids2);
+        if (st + 1 < nstep) issue(true, (st + 1) & 1, ids1);
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) kop[ks] = lds[buf][ku * CH + (2 * ks + h) * 16 + kslot];
+        for (int b = 0; b < kPfBlocks; ++b) {
+            ids1[b] = ids2[b];
+            ids2[b] = block_id(kPfBlocks * (st + 3) + b);
         }
-        __builtin_amdgcn_sched_barrier(0);
-        // ... and while they travel the loads of step st+1 are sent off into the other buffer
-        if (st + 1 < nstep) {
-            issue(buf ^ 1, nid);
+        // wave-uniform: some column of this wave sees keys of the step
+        if (st * 64 > w_pos_hi) return;
+        if (st * 64 + 63 > w_pos_lo) mask(Sc, st);   // the step touches the causal diagonal
+        u32x4 P[4];
+        float alpha;
+        bool grow;
+        // One straight-line region for the scheduler.  The scores of step st+1 are computed even
+        // when nothing will use them (last step of the tile, or no column of the wave sees that
+        // step): the K slot then holds an older step's tiles, and the result is dropped.
+        qk(Sn, (st + 1) & 1);
+        softmax(Sc, P, alpha, grow);
+        // the weights are due here, inside the region of the score MFMAs ...
 #pragma unroll
-            for (int b = 0; b < kPfBlocks; ++b) nid[b] = block_id(kPfBlocks * (st + 2) + b);
+        for (int q4 = 0; q4 < 4; ++q4) asm volatile("" : "+v"(P[q4]));
+        // ... and the region is laid out as 2*hd/16 x (MFMA, LDS read, a share of the vector work):
+        // the maximum is found next to the first MFMAs, the exponentials next to the others
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+#pragma unroll
+        for (int i = 0; i < KS / 2; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);
         }
-        if (active) {
-            f32x16 S[2];
 #pragma unroll
-            for (int hh = 0; hh < 2; ++hh) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) S[hh][r] = 0.f;
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks)
-                    S[hh] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kop[ks]),
-                                                                __builtin_bit_cast(bf16x8, qb[ks]), S[hh], 0, 0, 0);
-                if (hh == 0) {   // second half's K operands (blocks 2, 3) into the same registers
-#pragma unroll
-                    for (int ks = 0; ks < KS; ++ks)
-                        kop[ks] = lds[buf][(2 + ku) * CH + (2 * ks + h) * 16 + kslot];
-                }
-            }
-            // register r of half hh is token st*64 + 32hh + 8h + 16(r/8) + r%8
-            const int tok0 = st * 64 + 8 * h;
-            if (st * 64 + 63 > w_pos_lo) {   // wave-uniform: the step touches the causal diagonal
-                const int room = pos - tok0;             // visible iff 32hh + 16(r/8) + r%8 <= room
-#pragma unroll
-                for (int hh = 0; hh < 2; ++hh)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        S[hh][r] = (32 * hh + 16 * (r / 8) + (r % 8) <= room) ? S[hh][r] : -INFINITY;
-            }
-            // raw scores here; the softmax scale rides in the fma that feeds exp2 (scale > 0, so the
-            // maximum can be taken before scaling)
-            float mloc = max3(S[0][0], S[1][0], S[0][1]);
-            mloc = max3(mloc, S[1][1], S[0][2]);
-#pragma unroll
-            for (int r = 2; r < 15; ++r) mloc = max3(mloc, S[1][r], S[0][r + 1]);
-            mloc = fmaxf(mloc, S[1][15]);
-            {
-                float x, y;
-                swap32(mloc, x, y);
-                mloc = fmaxf(x, y) * c_log2e;
-            }
-            const float m_new = fmaxf(m, mloc);
-            const float alpha = fast_exp2(m - m_new);
-            const bool grow = m_new > m;
-            m = m_new;
-            if (__any(grow)) {
-#pragma unroll
-                for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) O[mb][r] *= alpha;
-            }
-            // wave-uniform, last step of a sequence only: V slots at or past seq_len may hold anything
-            // and are zeroed (their P is 0, but 0*NaN is NaN)
-            const bool vmask = st * 64 + 64 > seq_len;
-            float psum = 0.f;
-#pragma unroll
-            for (int hh = 0; hh < 2; ++hh) {
-                // exponentials of this half (the other half's run while this half's MFMAs execute)
-                u32x4 P[2];
-#pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    float e[8];
-#pragma unroll
-                    for (int r = 0; r < 8; ++r) {
-                        e[r] = fast_exp2(__builtin_fmaf(S[hh][8 * u + r], c_log2e, -m_new));
-                    }
-                    P[u] = u32x4{pack2_bf16(e[0], e[1]), pack2_bf16(e[2], e[3]), pack2_bf16(e[4], e[5]),
-                                 pack2_bf16(e[6], e[7])};
-                    // the denominator sums the same rounded weights that enter the PV product
-#pragma unroll
-                    for (int w = 0; w < 4; ++w) psum = sum2_bf16(P[u][w], psum);
-                }
-#pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    u32x4 vop[MB];
-#pragma unroll
-                    for (int mb = 0; mb < MB; ++mb)
-                        vop[mb] = lds[buf][(kPfBlocks + 2 * hh + u) * CH + h * HD + 32 * mb + col];
-                    if (vmask) {
-                        const int t0 = tok0 + 32 * hh + 16 * u;   // tokens t0 .. t0+7 in this lane's V operand
-                        u32x4 mk;
-#pragma unroll
-                        for (int w = 0; w < 4; ++w)
-                            mk[w] = (t0 + 2 * w < seq_len ? 0x0000FFFFu : 0u) | (t0 + 2 * w + 1 < seq_len ? 0xFFFF0000u : 0u);
-#pragma unroll
-                        for (int mb = 0; mb < MB; ++mb) vop[mb] &= mk;
-                    }
-#pragma unroll
-                    for (int mb = 0; mb < MB; ++mb)
-                        O[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vop[mb]),
-                                                                    __builtin_bit_cast(bf16x8, P[u]), O[mb], 0, 0, 0);
-                }
-            }
-            lsum = lsum * alpha + psum;
+        for (int i = KS / 2; i < 2 * KS; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
+            __builtin_amdgcn_sched_group_barrier(0x400, 3, 0);
         }
+        if (__any(grow)) {
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) O[mb][r] *= alpha;
+        }
+        pv(P, st & 1, st);
+    };
+
+    f32x16 SA[2], SB[2];
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    qk(SA, 0);
+    for (int st = 0; st < nstep; st += 2) {
+        body(SA, SB, st);
+        if (st + 1 < nstep) body(SB, SA, st + 1);
     }
     float ltot;
     {
