@@ -93,21 +93,36 @@ ooco_status ooco_ctx_destroy(ooco_ctx *ctx);
  * call on the same context / thread. */
 const char *ooco_last_error(const ooco_ctx *ctx);
 
-/* Options.  The KV blocks of all decode sequences, laid end to end, are streamed in runs: the
- * first part of that line is cut into "decode_segments" equal runs, one launched wave per run and
- * kv head (0 = automatic, from the device's CU count and the batch size); the last
- * "decode_tail_pct" percent (default 15; 0 = none) are cut into short runs of
- * "decode_tail_blocks" KV blocks (default 8) which the waves fetch dynamically once their own run
- * is done, evening out speed differences between compute units.  A run that crosses a sequence
- * boundary, or a sequence that spans several runs, is handled by partial results merged inside
- * the decode kernel.  These three take effect at the next ooco_plan.  "profile" (0/1, immediate): when set, every ooco_attn_mixed records HIP events
- * on its stream around its two kernels (prefill, decode) for ooco_profile_read; at most 1024
- * calls between two reads.  "overlap" (0/1, default 1, immediate): in a batch that holds both
- * prefill chunks and decode sequences, run the prefill kernel on the context's own side stream
- * (default priority) concurrently with the decode kernel; the call still appears as one unit of
- * work on the caller's stream (fork and join by events).  "trace" (0/1, immediate): see ooco_trace_read.  "decode_nbi" (1, 2 or
- * 4, immediate): KV blocks per softmax step of the decode kernel (0 = default).
- * Unknown name -> OOCO_EINVAL. */
+/* Options (name, value >= 0).  Unknown name -> OOCO_EINVAL.
+ *
+ * Decode run layout; these take effect at the next ooco_plan.  The KV blocks of all decode
+ * sequences, laid end to end, are streamed in runs, one launched wave per run and kv head.  A run
+ * that crosses a sequence boundary, or a sequence that spans several runs, is handled by partial
+ * results merged inside the decode kernel.
+ *   "decode_segments"     number of static runs (0 = automatic: three waves per compute unit,
+ *                         fewer for small batches)
+ *   "decode_tail_pct"     share (percent, default 0 = none) of the line that is cut into short
+ *                         runs which the waves fetch from a shared counter once their own run is
+ *                         done
+ *   "decode_tail_blocks"  KV blocks per such run (default 8)
+ *   "xcd_weights"         relative lengths of the static runs per XCD (the eight dies of the GPU
+ *                         differ by several percent in delivered memory bandwidth): eight bytes,
+ *                         XCD 0 in the lowest, each 1..255; static run v then goes to XCD v % 8
+ *                         and the number of static runs is rounded down to a multiple of 8.
+ *                         0 (default) = equal runs.  Weights must differ by at most 4x; they
+ *                         apply only when the static runs average at least 16 KV blocks.
+ * Immediate options:
+ *   "overlap"    0/1 (default 1): in a batch that holds both prefill chunks and decode sequences,
+ *                run the prefill kernel on the context's own side stream (default priority)
+ *                concurrently with the decode kernel; the call still appears as one unit of work
+ *                on the caller's stream (fork and join by events)
+ *   "profile"    0/1: every ooco_attn_mixed records HIP events on its stream around its two
+ *                kernels for ooco_profile_read; at most 1024 calls between two reads
+ *   "trace"      0/1: see ooco_trace_read
+ * Tuning knobs kept for experiments (defaults are the measured best): "decode_nbi" (KV blocks per
+ * softmax step of the decode kernel: 1, 2 or 4; 0 = default), "rotate_heads" (0/1: rotate the kv
+ * head of a decode wave by its run index, default 1), "copy_variant" (block copy: 10 * 16-byte
+ * vectors per thread + 1 for non-temporal accesses; 0 = default 41; process-wide). */
 ooco_status ooco_set_option(ooco_ctx *ctx, const char *name, int64_t value);
 
 /* Waits for the profiled calls made since the last read and returns the summed event-to-event
@@ -149,7 +164,9 @@ ooco_status ooco_plan(ooco_ctx *ctx, int num_seqs, const int32_t *h_seq_lens /*H
  *     holds up to 128 / (num_q_heads/num_kv_heads) query rows and runs once per kv head
  *   counts: HOST int64 [5] = (decode pieces, prefill tiles, static decode runs, partial-result
  *     slots, dynamically fetched tail runs); runs are numbered static first, then tail
- *   msg: HOST buffer of msg_cap bytes receiving the error text.  Any output pointer may be NULL. */
+ *   msg: HOST buffer of msg_cap bytes receiving the error text.  Any output pointer may be NULL.
+ *   xcd_weights: NULL for equal static runs, else the relative run lengths per XCD that option
+ *     "xcd_weights" would set (static run v then belongs to XCD v % 8). */
 ooco_status ooco_plan_dry_run(int num_q_heads, int num_kv_heads, int head_dim, int block_size,
                               int max_blocks_per_seq, int num_cus, size_t workspace_bytes,
                               int64_t decode_segments, int64_t decode_tail_pct, int64_t decode_tail_blocks,
@@ -157,7 +174,8 @@ ooco_status ooco_plan_dry_run(int num_q_heads, int num_kv_heads, int head_dim, i
                               const int32_t *h_query_start_loc /*HOST*/, const int32_t *h_ctx_lens /*HOST*/,
                               int32_t *decode_pieces_out /*HOST*/, int64_t decode_cap,
                               int32_t *prefill_tiles_out /*HOST*/, int64_t prefill_cap,
-                              int64_t *counts /*HOST*/, char *msg /*HOST*/, size_t msg_cap);
+                              int64_t *counts /*HOST*/, char *msg /*HOST*/, size_t msg_cap,
+                              const int32_t *xcd_weights /*HOST, 8 values in 1..255, or NULL*/);
 
 /* Numbers describing the current plan (any pointer may be NULL): decode runs (waves per kv head),
  * prefill tiles, KV blocks of all decode sequences, bytes of workspace the partial results use. */

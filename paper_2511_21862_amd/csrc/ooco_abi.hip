@@ -32,6 +32,7 @@ struct PlanGeometry {
     int64_t segments_opt;   // static runs; 0 = automatic
     int64_t tail_pct;       // share of the decode line handed out dynamically, in percent
     int64_t tail_blocks;    // KV blocks per dynamically fetched run
+    uint16_t xcd_cw[kXcds] = {};   // cumulative XCD weights of the static runs; zeros = equal runs
 };
 
 // The compact plan: two cumulative arrays and a few scalars (see ooco_internal.h).
@@ -42,9 +43,24 @@ struct HostPlan {
     std::vector<int32_t> pf;
     int32_t num_pf = 0;
     int32_t dec_blocks = 0, static_blocks = 0, static_runs = 0, tail_runs = 0;
+    uint16_t cw[kXcds] = {};     // XCD weights in force (RunLayout::cw)
     int32_t n_tiles = 0, total_q = 0, num_seqs = 0;
     int64_t slots = 0;           // partial-result slots the decode kernel may touch
 };
+
+// XCD weights -> cumulative form; false if a weight is outside 1..255 or they differ by more than 4x.
+bool xcd_weights_to_cw(const int32_t *w, uint16_t *cw)
+{
+    int32_t lo = 256, hi = 0, acc = 0;
+    for (int k = 0; k < kXcds; ++k) {
+        if (w[k] < 1 || w[k] > 255) return false;
+        lo = std::min(lo, w[k]);
+        hi = std::max(hi, w[k]);
+        acc += w[k];
+        cw[k] = (uint16_t)acc;
+    }
+    return hi <= 4 * lo;
+}
 
 size_t slot_bytes(const PlanGeometry &geo) { return (size_t)geo.Hq * (geo.hd + 2) * sizeof(float); }
 
@@ -114,6 +130,9 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
         int64_t runs = geo.segments_opt > 0 ? geo.segments_opt : std::min<int64_t>(wave_slots, (dec_blocks + 31) / 32);
         runs = std::max<int64_t>(1, std::min<int64_t>(runs, dec_blocks));
         for (;;) {
+            // weighted runs come in groups of one run per XCD
+            bool weighted = geo.xcd_cw[kXcds - 1] != 0 && runs >= kXcds;
+            if (weighted) runs -= runs % kXcds;
             // dynamic tail: only when a static run is much longer than a tail run
             int64_t tail_blk = 0, tails = 0;
             if (geo.tail_pct > 0 && geo.tail_blocks > 0 && dec_blocks / runs >= 4 * geo.tail_blocks) {
@@ -121,6 +140,8 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
                 tails = (tail_blk + geo.tail_blocks - 1) / geo.tail_blocks;
                 if (tails == 0) tail_blk = 0;
             }
+            // ... and only for runs long enough that no weight (they differ by at most 4x) empties one
+            if (dec_blocks - tail_blk < 16 * runs) weighted = false;
             // partial slots: (run index) + seq < runs + tails + num_seqs; one run never splits a sequence
             const int64_t slots = (runs + tails > 1) ? runs + tails + num_seqs : 0;
             if ((size_t)slots * slot_bytes(geo) <= geo.ws_bytes || runs == 1) {
@@ -128,6 +149,7 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
                     tail_blk = tails = 0;
                 }
                 out.static_runs = (int32_t)runs;
+                for (int k = 0; k < kXcds; ++k) out.cw[k] = weighted ? geo.xcd_cw[k] : 0;
                 out.static_blocks = (int32_t)(dec_blocks - tail_blk);
                 out.tail_runs = (int32_t)tails;
                 out.slots = (runs + tails > 1) ? runs + tails + num_seqs : 0;
@@ -146,7 +168,8 @@ struct Piece {
 std::vector<Piece> enumerate_pieces(const HostPlan &pl)
 {
     std::vector<Piece> v;
-    const RunLayout L = {pl.dec_blocks, pl.static_blocks, pl.static_runs, pl.tail_runs};
+    RunLayout L = {pl.dec_blocks, pl.static_blocks, pl.static_runs, pl.tail_runs, {}};
+    for (int k = 0; k < kXcds; ++k) L.cw[k] = pl.cw[k];
     for (int32_t k = 0; k < pl.static_runs + pl.tail_runs; ++k) {
         int32_t lo, hi;
         run_bounds(L, k, lo, hi);
@@ -199,6 +222,7 @@ struct ooco_ctx {
     int64_t opt_nbi = 0;
     int64_t opt_trace = 0;
     int64_t opt_rotate = 1;
+    uint16_t xcd_cw[kXcds] = {};   // option "xcd_weights"
     int64_t opt_overlap = 1;
     hipStream_t side_stream = nullptr;   // default priority; carries the prefill kernel of mixed batches
     hipEvent_t fork_ev = nullptr, join_ev = nullptr;
@@ -391,6 +415,16 @@ ooco_status ooco_set_option(ooco_ctx *ctx, const char *name, int64_t value)
     } else if (!strcmp(name, "rotate_heads")) {
         ctx->opt_rotate = value;
         return OOCO_OK;
+    } else if (!strcmp(name, "xcd_weights")) {
+        // eight relative weights, one byte each, XCD 0 in the lowest byte; 0 = equal runs
+        int32_t w[kXcds];
+        for (int k = 0; k < kXcds; ++k) w[k] = (int32_t)(((uint64_t)value >> (8 * k)) & 0xFFu);
+        if (value == 0)
+            for (int k = 0; k < kXcds; ++k) ctx->xcd_cw[k] = 0;
+        else if (!xcd_weights_to_cw(w, ctx->xcd_cw)) {
+            for (int k = 0; k < kXcds; ++k) ctx->xcd_cw[k] = 0;
+            return fail(ctx, OOCO_EINVAL, "ooco_set_option: xcd_weights needs eight bytes in 1..255 that differ by at most 4x");
+        }
     } else if (!strcmp(name, "decode_nbi")) {
         ctx->opt_nbi = value;
         return OOCO_OK;
@@ -421,6 +455,7 @@ ooco_status ooco_plan(ooco_ctx *ctx, int num_seqs, const int32_t *h_seq_lens, co
     geo.segments_opt = ctx->opt_segments;
     geo.tail_pct = ctx->opt_tail_pct;
     geo.tail_blocks = ctx->opt_tail_blocks;
+    for (int k = 0; k < kXcds; ++k) geo.xcd_cw[k] = ctx->xcd_cw[k];
     ooco_status st = build_plan(geo, num_seqs, h_seq_lens, h_query_start_loc, h_ctx_lens, ctx->plan, ctx->err);
     if (st != OOCO_OK) return st;
     if ((size_t)num_seqs * ctx->Hkv > kCounterInts - 1 || 3 * ((size_t)num_seqs + 1) > kPlanInts)
@@ -436,7 +471,8 @@ ooco_status ooco_plan_dry_run(int num_q_heads, int num_kv_heads, int head_dim, i
                               int64_t decode_tail_blocks, int num_seqs,
                               const int32_t *h_seq_lens, const int32_t *h_query_start_loc, const int32_t *h_ctx_lens,
                               int32_t *decode_pieces_out, int64_t decode_cap, int32_t *prefill_tiles_out,
-                              int64_t prefill_cap, int64_t *counts, char *msg, size_t msg_cap)
+                              int64_t prefill_cap, int64_t *counts, char *msg, size_t msg_cap,
+                              const int32_t *xcd_weights)
 {
     char err[512] = "";
     ooco_status st = OOCO_OK;
@@ -458,7 +494,12 @@ ooco_status ooco_plan_dry_run(int num_q_heads, int num_kv_heads, int head_dim, i
         geo.segments_opt = decode_segments;
         geo.tail_pct = decode_tail_pct;
         geo.tail_blocks = decode_tail_blocks;
-        st = build_plan(geo, num_seqs, h_seq_lens, h_query_start_loc, h_ctx_lens, pl, err);
+        if (xcd_weights && !xcd_weights_to_cw(xcd_weights, geo.xcd_cw)) {
+            snprintf(err, sizeof err, "ooco_plan_dry_run: xcd_weights needs eight values in 1..255 that differ by at most 4x");
+            st = OOCO_EINVAL;
+        }
+        if (st == OOCO_OK)
+            st = build_plan(geo, num_seqs, h_seq_lens, h_query_start_loc, h_ctx_lens, pl, err);
     }
     if (msg && msg_cap) snprintf(msg, msg_cap, "%s", err);
     if (st != OOCO_OK) return st;
@@ -587,6 +628,7 @@ ooco_status ooco_attn_mixed(ooco_ctx *ctx, const void *q, const void *k_cache, c
     p.tile_rows = prefill_tile_rows(ctx->g);
     p.nbi = (int32_t)ctx->opt_nbi;
     p.rotate_heads = (int32_t)ctx->opt_rotate;
+    for (int k = 0; k < kXcds; ++k) p.xcd_cw[k] = pl.cw[k];
 
     hipEvent_t *ev = nullptr;
     hipError_t e = hipSuccess;

@@ -53,6 +53,7 @@ struct AttnParams {
     int32_t num_pf, pad_pf;     // prefill: number of chunks (entries of the prefill array, see below)
     int32_t nbi;                // tuning: KV blocks per softmax step of the decode kernel
     int32_t rotate_heads;       // tuning: kv head rotation across XCDs
+    uint16_t xcd_cw[8];         // cumulative XCD weights of the static runs (RunLayout::cw); zeros = equal runs
     uint32_t queue_base;        // ticket value at which this launch's tail runs start
     uint32_t *queue;            // ticket counter for the tail runs (monotonic across launches)
 };
@@ -83,14 +84,35 @@ __host__ __device__ inline int32_t segment_of(int64_t x, int64_t s, int64_t n)
 }
 
 // The two-level run layout of the decode line (host and device use the same functions).
+// Static runs are equal by default.  With XCD weights (cw[kXcds-1] != 0; static_runs is then a
+// multiple of kXcds) every group of kXcds consecutive runs shares its blocks in proportion to the
+// weights: run 8p+k gets the share (cw[k] - cw[k-1]) / cw[7] of group p.  The decode kernel places
+// run v on XCD v % kXcds, so a slower XCD can be given shorter runs.
+constexpr int kXcds = 8;
 struct RunLayout {
     int32_t dec_blocks, static_blocks, static_runs, tail_runs;
+    uint16_t cw[kXcds];   // cumulative weights of the runs of a group; all zero = equal runs
 };
+__host__ __device__ inline int32_t group_cut(const RunLayout &L, int32_t plo, int32_t phi, int32_t k)
+{
+    // first block of run k (0..kXcds) of the group that covers blocks [plo, phi)
+    if (k <= 0) return plo;
+    if (k >= kXcds) return phi;
+    return plo + (int32_t)((int64_t)(phi - plo) * L.cw[k - 1] / L.cw[kXcds - 1]);
+}
 __host__ __device__ inline void run_bounds(const RunLayout &L, int32_t v, int32_t &lo, int32_t &hi)
 {
     if (v < L.static_runs) {
-        lo = (int32_t)((int64_t)L.static_blocks * v / L.static_runs);
-        hi = (int32_t)((int64_t)L.static_blocks * (v + 1) / L.static_runs);
+        if (L.cw[kXcds - 1] == 0) {
+            lo = (int32_t)((int64_t)L.static_blocks * v / L.static_runs);
+            hi = (int32_t)((int64_t)L.static_blocks * (v + 1) / L.static_runs);
+        } else {
+            const int32_t groups = L.static_runs / kXcds, p = v / kXcds, k = v - p * kXcds;
+            const int32_t plo = (int32_t)((int64_t)L.static_blocks * p / groups);
+            const int32_t phi = (int32_t)((int64_t)L.static_blocks * (p + 1) / groups);
+            lo = group_cut(L, plo, phi, k);
+            hi = group_cut(L, plo, phi, k + 1);
+        }
     } else {
         const int64_t t = v - L.static_runs, tb = L.dec_blocks - L.static_blocks;
         lo = L.static_blocks + (int32_t)(tb * t / L.tail_runs);
@@ -99,8 +121,16 @@ __host__ __device__ inline void run_bounds(const RunLayout &L, int32_t v, int32_
 }
 __host__ __device__ inline int32_t run_of(const RunLayout &L, int64_t x)
 {
-    if (x < L.static_blocks) return segment_of(x, L.static_runs, L.static_blocks);
-    return L.static_runs + segment_of(x - L.static_blocks, L.tail_runs, (int64_t)L.dec_blocks - L.static_blocks);
+    if (x >= L.static_blocks)
+        return L.static_runs + segment_of(x - L.static_blocks, L.tail_runs, (int64_t)L.dec_blocks - L.static_blocks);
+    if (L.cw[kXcds - 1] == 0) return segment_of(x, L.static_runs, L.static_blocks);
+    const int32_t groups = L.static_runs / kXcds;
+    const int32_t p = segment_of(x, groups, L.static_blocks);
+    const int32_t plo = (int32_t)((int64_t)L.static_blocks * p / groups);
+    const int32_t phi = (int32_t)((int64_t)L.static_blocks * (p + 1) / groups);
+    int32_t k = 0;
+    for (int32_t j = 1; j < kXcds; ++j) k += group_cut(L, plo, phi, j) <= x ? 1 : 0;
+    return p * kXcds + k;
 }
 
 }  // namespace ooco

@@ -158,10 +158,18 @@ __global__ __launch_bounds__(64) void decode_kernel(const KernArgs a)
     // in turn instead of pinning XCD x to head x.
     int run = blockIdx.x / p.Hkv;
     int kvh = p.rotate_heads ? (int)((blockIdx.x - run * p.Hkv + run) % p.Hkv) : (int)(blockIdx.x - run * p.Hkv);
+    if (p.xcd_cw[kXcds - 1]) {
+        // weighted runs: all kv heads of run v on XCD v % 8 (workgroup b runs on XCD b % 8)
+        const int x = blockIdx.x % kXcds, t = blockIdx.x / kXcds;
+        kvh = t % p.Hkv;
+        run = kXcds * (t / p.Hkv) + x;
+    }
     const int g = p.g;
     const int64_t tile_elems = (int64_t)HD * kBlockSize;   // one (block, kv head) tile
     auto cum_at = [&](int idx) -> int { return p.cum_dev ? p.cum_dev[idx] : a.cum[idx]; };
-    const RunLayout L = {p.dec_blocks, p.static_blocks, p.static_runs, p.tail_runs};
+    RunLayout L = {p.dec_blocks, p.static_blocks, p.static_runs, p.tail_runs, {}};
+#pragma unroll
+    for (int k = 0; k < kXcds; ++k) L.cw[k] = p.xcd_cw[k];
     const unsigned tail_tasks = (unsigned)p.tail_runs * (unsigned)p.Hkv;
 
     uint64_t *trace = p.trace ? p.trace + (int64_t)blockIdx.x * 4 : nullptr;   // per-wave time stamps

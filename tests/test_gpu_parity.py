@@ -64,6 +64,19 @@ def test_forced_decode_run_layouts_agree(segments, tail_pct, tail_blocks):
     assert_parity(run_gpu(b, options=opts), ref, f"segments={segments} tail={tail_pct}%x{tail_blocks}")
 
 
+@pytest.mark.parametrize("Hkv,segments,tail_pct", [(8, 8, 0), (2, 16, 0), (4, 24, 10), (8, 0, 0), (8, 10 ** 6, 0)])
+def test_xcd_weighted_decode_runs_agree(Hkv, segments, tail_pct):
+    # static runs sized per XCD (run v on XCD v % 8, all kv heads of a run on one XCD)
+    # (8, 16 and 24 runs are long enough for the weights to apply; the last two fall back to equal runs)
+    b = W.build_batch(Hq=4 * Hkv, Hkv=Hkv, hd=128, q_lens=[1, 1, 0, 1, 5, 1], ctx_lens=[6000, 130, 7, 15, 40, 900],
+                      num_blocks=520, seed=79, poison=True)
+    weights = [100, 60, 140, 95, 105, 85, 115, 100]
+    packed = sum(w << (8 * k) for k, w in enumerate(weights))
+    say(f"case: xcd weights Hkv={Hkv} decode_segments {segments} tail {tail_pct}%")
+    opts = {"decode_segments": segments, "decode_tail_pct": tail_pct, "decode_tail_blocks": 2, "xcd_weights": packed}
+    assert_parity(run_gpu(b, options=opts), oracle(b), f"xcd weights Hkv={Hkv} segments={segments}")
+
+
 def test_repeated_calls_reuse_counters_and_workspace():
     b = W.build_batch(Hq=8, Hkv=2, hd=128, q_lens=[1, 1, 1], ctx_lens=[700, 90, 300], num_blocks=80, seed=78)
     ref = oracle(b)

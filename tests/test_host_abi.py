@@ -138,6 +138,33 @@ def test_default_plan_is_equal_static_runs_plus_short_tail_runs():
     assert dry(b.seq_lens, b.query_start_loc, b.ctx_lens, decode_segments=2000)["tail_runs"] == 0
 
 
+def test_xcd_weights_shape_the_static_runs():
+    w = [100, 90, 110, 95, 105, 85, 115, 100]
+    for cfg in (W.config1, W.config2, W.config3, W.config4, W.config5):
+        b = meta_only(cfg)
+        for seg, pct in ((0, 0), (96, 0), (100, 15), (8, 0), (17, 30)):
+            plan = dry(b.seq_lens, b.query_start_loc, b.ctx_lens, num_q_heads=b.Hq, num_kv_heads=b.Hkv, head_dim=b.hd,
+                       workspace_bytes=1 << 30, decode_segments=seg, decode_tail_pct=pct, xcd_weights=w)
+            check_cover(b, plan)
+            R = plan["decode_runs"]
+            if R < 8:
+                continue                      # too few runs for one per XCD: equal runs
+            assert R % 8 == 0
+            d = plan["decode_pieces"]
+            per_run = np.bincount(d[:, 4], weights=d[:, 2] - d[:, 1], minlength=R)[:R]
+            per_xcd = per_run.reshape(-1, 8).sum(0)
+            share = per_xcd / per_xcd.sum()
+            assert np.abs(share - np.array(w) / sum(w)).max() < 0.01 + 8.0 / per_xcd.sum()
+    # fewer than 8 runs, or no weights: equal runs
+    b = meta_only(W.config2)
+    plan = dry(b.seq_lens, b.query_start_loc, b.ctx_lens, decode_segments=5, xcd_weights=w)
+    d = plan["decode_pieces"]
+    per_run = np.bincount(d[:, 4], weights=d[:, 2] - d[:, 1])
+    assert plan["decode_runs"] == 5 and per_run.max() - per_run.min() <= 1
+    with pytest.raises(B.OocoError):
+        dry(b.seq_lens, b.query_start_loc, b.ctx_lens, xcd_weights=[1, 2, 3, 0, 5, 6, 7, 8])
+
+
 def test_small_workspace_reduces_the_number_of_runs():
     b = meta_only(W.config4)
     big = dry(b.seq_lens, b.query_start_loc, b.ctx_lens, workspace_bytes=1 << 30)
