@@ -9,7 +9,8 @@
 //     one (after bf16 rounding) -- no cross-lane movement of P;
 //   * the softmax statistics (max, sum) and the accumulator rescale are per lane column;
 //   * K tiles [hd/8][16][8] and V tiles [hd][16] of the paged cache are already in A-operand
-//     order, so they go from global memory straight into MFMA source registers.
+//     order, so they go from global memory straight into MFMA source registers (decode) or are
+//     copied unchanged into LDS by direct global->LDS loads and read from there (prefill).
 // Softmax runs in base 2: scores are multiplied by scale*log2(e) and exponentiated with
 // v_exp_f32.  Masked scores are set to -inf by select; V values of slots past the end of a
 // sequence are zeroed by select (those slots may hold NaN/Inf).
