@@ -23,7 +23,7 @@ Token j of sequence i lives in physical block block_tables[i][j // BS], slot j %
 from __future__ import annotations
 
 from dataclasses import dataclass, field, replace
-from typing import Optional, Sequence
+from typing import Dict, Optional, Sequence, Tuple
 
 import numpy as np
 
@@ -268,6 +268,48 @@ def subset(b: Batch, seq_ids: Sequence[int]) -> Batch:
                  q=np.ascontiguousarray(q), k_cache=np.ascontiguousarray(k).reshape((-1,) + b.k_shape()[1:]),
                  v_cache=np.ascontiguousarray(v).reshape((-1,) + b.v_shape()[1:]),
                  name=b.name + f"[subset {len(seq_ids)}]", extra={"rows": rows})
+
+
+def row_sample(b: Batch, pairs: Sequence[Tuple[int, int]]) -> Batch:
+    """Host batch with one single-token sequence per sampled query row: (s, t) = row t of sequence s
+    of `b` becomes a sequence of ctx_len = ctx_len[s] + t that shares the KV blocks of s (copied once per
+    source sequence into a compact pool).  Pure data movement: lets the oracle check sampled rows of a
+    large device-resident batch one by one (a chunk row is a single-query decode over its visible keys)."""
+    pairs = [(int(s), int(t)) for s, t in pairs]
+    need: Dict[int, int] = {}
+    for s_, t in pairs:
+        assert 0 <= t < int(b.q_lens[s_])
+        need[s_] = max(need.get(s_, 0), (int(b.ctx_lens[s_]) + t + 1 + b.BS - 1) // b.BS)
+    base, ids, pos = {}, [], 0
+    for s_ in sorted(need):
+        base[s_] = pos
+        ids.append(b.block_tables[s_, : need[s_]])
+        pos += need[s_]
+    ids = np.concatenate(ids).astype(np.int64) if ids else np.zeros(0, np.int64)
+    maxb = max(list(need.values()) + [1])
+    bt = np.full((len(pairs), maxb), -1, dtype=np.int32)
+    ctx = np.zeros(len(pairs), dtype=np.int32)
+    rows = np.zeros(len(pairs), dtype=np.int64)
+    for r, (s_, t) in enumerate(pairs):
+        ctx[r] = int(b.ctx_lens[s_]) + t
+        n = (int(ctx[r]) + 1 + b.BS - 1) // b.BS
+        bt[r, :n] = base[s_] + np.arange(n, dtype=np.int32)
+        rows[r] = int(b.query_start_loc[s_]) + t
+    if b.on_host:
+        k, v, q = b.k_cache[ids], b.v_cache[ids], b.q[rows]
+    else:
+        import torch
+
+        idx = torch.from_numpy(ids).to(b.k_cache.device)
+        ridx = torch.from_numpy(rows).to(b.q.device)
+        k = _torch_to_bits(b.k_cache.index_select(0, idx))
+        v = _torch_to_bits(b.v_cache.index_select(0, idx))
+        q = _torch_to_bits(b.q.index_select(0, ridx))
+    return Batch(Hq=b.Hq, Hkv=b.Hkv, hd=b.hd, BS=b.BS, num_blocks=max(int(len(ids)), 1), block_tables=bt,
+                 seq_lens=ctx + 1, ctx_lens=ctx, query_start_loc=np.arange(len(pairs) + 1, dtype=np.int32),
+                 q=np.ascontiguousarray(q), k_cache=np.ascontiguousarray(k).reshape((-1,) + b.k_shape()[1:]),
+                 v_cache=np.ascontiguousarray(v).reshape((-1,) + b.v_shape()[1:]),
+                 name=b.name + f"[{len(pairs)} sampled rows]", extra={"rows": rows})
 
 
 def scatter_logical(b: Batch, seq: int, k_bits: np.ndarray, v_bits: np.ndarray) -> None:

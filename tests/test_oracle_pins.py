@@ -303,3 +303,18 @@ def test_causal_flops_count_visible_pairs():
     assert w["flops_causal"] == 4 * 256 * (32 * 33 // 2)       # 0.54 MFLOP for the tiny prefill chunk
     w = accounting.batch_work(32, 8, 128, 16, [100 + 512], [512])
     assert w["flops_causal"] == 4 * 4096 * (512 * 100 + 512 * 513 // 2)
+
+
+def test_row_sample_reproduces_rows_of_the_full_batch():
+    # the sampled-row batches handed to the oracle by the full-size GPU tests: row t of a chunk, recast as a
+    # single-query sequence over its visible keys, gives exactly the row of the whole-batch result
+    b = W.build_batch(Hq=8, Hkv=2, hd=64, q_lens=[1, 5, 33, 0, 1], ctx_lens=[40, 3, 20, 9, 0], num_blocks=40, seed=5)
+    full = ref_numpy.attn_mixed(b.q, b.k_cache, b.v_cache, b.block_tables, b.seq_lens, b.query_start_loc, b.ctx_lens)
+    pairs = [(0, 0), (1, 0), (1, 4), (2, 0), (2, 15), (2, 16), (2, 32), (4, 0)]
+    s = W.row_sample(b, pairs)
+    assert (s.q_lens == 1).all() and s.num_blocks == 3 + 1 + 4 + 1
+    got = ref_numpy.attn_mixed(s.q, s.k_cache, s.v_cache, s.block_tables, s.seq_lens, s.query_start_loc, s.ctx_lens)
+    rows = [int(b.query_start_loc[q]) + t for q, t in pairs]
+    assert (s.extra["rows"] == rows).all()
+    np.testing.assert_allclose(got, full[rows], rtol=0, atol=1e-13)
+
