@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the mixed-batch paged-attention step on ONE MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg3|cfg3-prefill|cfg4|cfg4-copy|cfg5|cfg5-prefill]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg3|cfg3-prefill|cfg4|cfg4-copy|cfg4-copy-seq|cfg5|cfg5-prefill]
 
 A step = one pass of the whole path over one synthetic batch already resident in HBM: host
 planning (ooco_plan) + ooco_attn_mixed (prefill kernel, decode kernel with its in-kernel merge).  Steps
@@ -108,7 +108,12 @@ def bench_block_copy(a):
     n = len(src)
     rng = np.random.default_rng(44)
     stage_blocks = n + 64
-    dsts = [torch.from_numpy(rng.permutation(stage_blocks)[:n].astype(np.int64)).cuda() for _ in range(2)]
+    # destination ids: a random subset of the staging pool (default: a staging pool whose free list is in
+    # no particular order), or 0..n-1 ("cfg4-copy-seq": a freshly set up staging pool)
+    if a.workload == "cfg4-copy-seq":
+        dsts = [torch.arange(n, dtype=torch.int64, device="cuda") for _ in range(2)]
+    else:
+        dsts = [torch.from_numpy(rng.permutation(stage_blocks)[:n].astype(np.int64)).cuda() for _ in range(2)]
     stages = [(torch.empty((stage_blocks,) + tuple(b.k_cache.shape[1:]), dtype=torch.bfloat16, device="cuda"),
                torch.empty((stage_blocks,) + tuple(b.v_cache.shape[1:]), dtype=torch.bfloat16, device="cuda"))
               for _ in range(2)]
@@ -195,7 +200,7 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    if a.workload == "cfg4-copy":
+    if a.workload in ("cfg4-copy", "cfg4-copy-seq"):
         return bench_block_copy(a)
     b, dominant = make_workload(a.workload)
     work = accounting.batch_work(b.Hq, b.Hkv, b.hd, b.BS, b.seq_lens, b.q_lens)
