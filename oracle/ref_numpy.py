@@ -84,3 +84,27 @@ def block_copy(k_src, v_src, k_dst, v_dst, src_ids, dst_ids):
     for s, d in zip(src_ids, dst_ids):
         k_dst[int(d)] = k_src[int(s)]
         v_dst[int(d)] = v_src[int(s)]
+
+
+def kv_append(k_new, v_new, k_cache, v_cache, block_tables, query_start_loc, ctx_lens):
+    """Writes the K and V vectors of this step's tokens into their paged slots, in place.
+
+    The paper keeps the K/V of every processed token in the KV cache so that later steps reuse them
+    (Section 2.1: the cache is what separates prefill from decode; non-contiguous pool); the token at
+    row t of sequence i sits at absolute position pos = ctx_len_i + t, i.e. in physical block
+    block_tables[i][pos // BS], slot pos % BS.  k_new, v_new: [T][Hkv][hd] bit patterns (uint16), row
+    query_start_loc[i] + t.  Nothing else of the pools changes.  Plain definition, one element at a time.
+    Pins: tests/test_oracle_pins.py (hand-evaluated offsets of a tiny example, read-back through an
+    independent gather, cache reconstruction, attention after append)."""
+    NB, Hkv, hd8, BS, eight = k_cache.shape
+    hd = hd8 * 8
+    assert eight == 8 and v_cache.shape == (NB, Hkv, hd, BS)
+    for i in range(len(ctx_lens)):
+        q0, q1 = int(query_start_loc[i]), int(query_start_loc[i + 1])
+        for t in range(q1 - q0):
+            pos = int(ctx_lens[i]) + t
+            blk, slot = int(block_tables[i][pos // BS]), pos % BS
+            for kv in range(Hkv):
+                for d in range(hd):
+                    k_cache[blk, kv, d // 8, slot, d % 8] = k_new[q0 + t, kv, d]
+                    v_cache[blk, kv, d, slot] = v_new[q0 + t, kv, d]

@@ -318,3 +318,71 @@ def test_row_sample_reproduces_rows_of_the_full_batch():
     assert (s.extra["rows"] == rows).all()
     np.testing.assert_allclose(got, full[rows], rtol=0, atol=1e-13)
 
+
+
+# ----------------------------------------------------------------------------- KV append
+def _step_kv(b):
+    """K/V vectors ([T][Hkv][hd] bit patterns) of the step's tokens, read out of a filled host batch."""
+    k_new = np.zeros((b.total_q, b.Hkv, b.hd), np.uint16)
+    v_new = np.zeros_like(k_new)
+    for i in range(b.num_seqs):
+        k, v = W.gather_logical(b, i)
+        q0, ql, c = int(b.query_start_loc[i]), int(b.q_lens[i]), int(b.ctx_lens[i])
+        k_new[q0:q0 + ql] = k[c:c + ql]
+        v_new[q0:q0 + ql] = v[c:c + ql]
+    return k_new, v_new
+
+
+def test_kv_append_offsets_of_a_hand_worked_example():
+    # Hkv=1, hd=8, BS=16: one sequence with 17 cached tokens appends 2 tokens -> positions 17, 18 live in the
+    # sequence's second block (id 5), slots 1 and 2.  K element d of slot s is word [blk][0][0][s][d] of the
+    # K pool (flat offset blk*128 + s*8 + d); V element d of slot s is [blk][0][d][s] (flat blk*128 + d*16 + s).
+    k_cache = np.zeros((8, 1, 1, 16, 8), np.uint16)
+    v_cache = np.zeros((8, 1, 8, 16), np.uint16)
+    k_new = (np.arange(16, dtype=np.uint16) + 100).reshape(2, 1, 8)
+    v_new = (np.arange(16, dtype=np.uint16) + 200).reshape(2, 1, 8)
+    ref_numpy.kv_append(k_new, v_new, k_cache, v_cache, np.array([[3, 5, -1]]), np.array([0, 2]), np.array([17]))
+    kf, vf = k_cache.reshape(-1), v_cache.reshape(-1)
+    expect_k = {5 * 128 + 1 * 8 + d: 100 + d for d in range(8)}
+    expect_k.update({5 * 128 + 2 * 8 + d: 108 + d for d in range(8)})
+    expect_v = {5 * 128 + d * 16 + 1: 200 + d for d in range(8)}
+    expect_v.update({5 * 128 + d * 16 + 2: 208 + d for d in range(8)})
+    assert {int(i): int(kf[i]) for i in np.flatnonzero(kf)} == expect_k
+    assert {int(i): int(vf[i]) for i in np.flatnonzero(vf)} == expect_v
+
+
+def test_kv_append_rebuilds_the_cache_and_touches_nothing_else():
+    for seed, (Hq, Hkv, hd, ql, cx) in enumerate([(4, 1, 64, [1, 1, 5, 0, 40], [36, 15, 16, 7, 3]),
+                                                  (8, 2, 128, [33, 1, 2], [0, 31, 47]),
+                                                  (14, 2, 64, [16, 17], [16, 15])]):
+        b = W.build_batch(Hq=Hq, Hkv=Hkv, hd=hd, q_lens=ql, ctx_lens=cx, num_blocks=24, seed=40 + seed)
+        k_new, v_new = _step_kv(b)
+        # wipe the slots of the step's tokens (and only those), then append: the pools must come back bit for bit
+        k0, v0 = b.k_cache.copy(), b.v_cache.copy()
+        hole_k, hole_v = b.k_cache.copy(), b.v_cache.copy()
+        for i in range(b.num_seqs):
+            for t in range(int(b.q_lens[i])):
+                pos = int(b.ctx_lens[i]) + t
+                blk, s = int(b.block_tables[i, pos // 16]), pos % 16
+                hole_k[blk, :, :, s, :] = 0xDEAD
+                hole_v[blk, :, :, s] = 0xDEAD
+        assert (hole_k != k0).any()
+        ref_numpy.kv_append(k_new, v_new, hole_k, hole_v, b.block_tables, b.query_start_loc, b.ctx_lens)
+        assert (hole_k == k0).all() and (hole_v == v0).all()
+        # attention over the rebuilt pools is the attention over the original ones
+        o0 = ref_numpy.attn_mixed(b.q, k0, v0, b.block_tables, b.seq_lens, b.query_start_loc, b.ctx_lens)
+        o1 = ref_numpy.attn_mixed(b.q, hole_k, hole_v, b.block_tables, b.seq_lens, b.query_start_loc, b.ctx_lens)
+        assert (o0 == o1).all()
+
+
+def test_kv_append_reads_back_through_the_independent_gather():
+    # append distinctive vectors, read the sequence back with workloads.gather_logical (separate code)
+    b = W.build_batch(Hq=4, Hkv=2, hd=64, q_lens=[3, 1], ctx_lens=[14, 0], num_blocks=8, seed=50)
+    rng = np.random.default_rng(7)
+    k_new = rng.integers(0, 65536, size=(4, 2, 64)).astype(np.uint16)
+    v_new = rng.integers(0, 65536, size=(4, 2, 64)).astype(np.uint16)
+    ref_numpy.kv_append(k_new, v_new, b.k_cache, b.v_cache, b.block_tables, b.query_start_loc, b.ctx_lens)
+    k, v = W.gather_logical(b, 0)
+    assert (k[14:17] == k_new[0:3]).all() and (v[14:17] == v_new[0:3]).all()
+    k, v = W.gather_logical(b, 1)
+    assert (k[0] == k_new[3]).all() and (v[0] == v_new[3]).all()
