@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the mixed-batch paged-attention step on ONE MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg3|cfg3-prefill|cfg4|cfg4-copy|cfg4-copy-seq|cfg5|cfg5-prefill]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg3|cfg3-prefill|cfg4|cfg4-copy|cfg4-copy-seq|cfg5|cfg5-prefill|cfg3-append|cfg5-append]
 
 A step = one pass of the whole path over one synthetic batch already resident in HBM: host
 planning (ooco_plan) + ooco_attn_mixed (prefill kernel, decode kernel with its in-kernel merge).  Steps
@@ -179,6 +179,72 @@ def bench_block_copy(a):
     print(json.dumps(line), flush=True)
 
 
+def bench_append(a):
+    """ooco_kv_append of one step's tokens of config 3 or 5 (the step that precedes the attention call);
+    steps rotate over copies of the batch dealt from disjoint physical blocks."""
+    import torch
+
+    from oracle import ref_numpy
+    from paper_2511_21862_amd import accounting
+    from paper_2511_21862_amd import binding as B
+    from paper_2511_21862_amd import workloads as W
+
+    b = (W.config3 if a.workload.startswith("cfg3") else W.config5)(device="cuda")
+    dev = lambda x: torch.from_numpy(np.ascontiguousarray(x)).cuda()
+    bts = [dev(t) for t in W.replica_tables(b, 4)]
+    qsl, cl = dev(b.query_start_loc), dev(b.ctx_lens)
+    g = torch.Generator(device="cuda").manual_seed(11)
+    k_new = torch.randn((b.total_q, b.Hkv, b.hd), generator=g, device="cuda").to(torch.bfloat16)
+    v_new = torch.randn((b.total_q, b.Hkv, b.hd), generator=g, device="cuda").to(torch.bfloat16)
+    ctx = B.Context(b.Hq, b.Hkv, b.hd, b.BS, b.num_blocks, b.max_blocks_per_seq)
+    stream = torch.cuda.current_stream()
+
+    def step(i):
+        ctx.kv_append(k_new, v_new, b.k_cache, b.v_cache, bts[i % len(bts)], qsl, cl, stream)
+
+    for i in range(a.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(a.steps):
+        step(i)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / a.steps
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(a.steps)]
+    for i, (e0, e1) in enumerate(evs):
+        e0.record(stream)
+        step(i)
+        e1.record(stream)
+    torch.cuda.synchronize()
+    kms = float(np.mean([e0.elapsed_time(e1) for e0, e1 in evs]))
+    nbytes = 2 * b.total_q * accounting.per_token_kv_bytes(b.Hkv, b.hd)      # new vectors read + slots written
+    line = {
+        "metric": "KV append tokens/s + achieved HBM GB/s (% of peak), 1 MI355X",
+        "value": b.total_q / dt, "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": dt * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u8", "data": "synthetic",
+        "config": {"workload": b.name + "-append", "bench_name": a.workload, "q_tokens": b.total_q, "num_seqs": b.num_seqs,
+                   "Hkv": b.Hkv, "head_dim": b.hd, "block_size": b.BS},
+        "roofline": {"bound": "hbm", "kernel": "kv_append_kernel", "achieved": nbytes / (kms * 1e-3) / 1e9,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": nbytes / (kms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                     "traffic": read_traffic("kv_append_kernel", a.workload), "algorithmic_bytes_per_launch": nbytes,
+                     "kernel_ms": kms},
+    }
+    if not a.no_cpu_baseline:
+        # the numpy oracle on a bounded sample: the first sequences up to about 64 tokens
+        n = int(np.searchsorted(b.query_start_loc, 64, side="right"))
+        n = max(1, min(n, b.num_seqs))
+        s = W.subset(b, list(range(n)))
+        kn = np.zeros((s.total_q, b.Hkv, b.hd), np.uint16)
+        t1 = time.perf_counter()
+        ref_numpy.kv_append(kn, kn, s.k_cache, s.v_cache, s.block_tables, s.query_start_loc, s.ctx_lens)
+        t = time.perf_counter() - t1
+        line["cpu_baseline"] = {"value": s.total_q / t, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+                                "sample": f"first {n} sequences ({s.total_q} tokens), numpy definition, {t:.2f} s"}
+    ctx.close()
+    print(json.dumps(line), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -202,6 +268,8 @@ def main():
     torch.cuda.set_device(0)
     if a.workload in ("cfg4-copy", "cfg4-copy-seq"):
         return bench_block_copy(a)
+    if a.workload in ("cfg3-append", "cfg5-append"):
+        return bench_append(a)
     b, dominant = make_workload(a.workload)
     work = accounting.batch_work(b.Hq, b.Hkv, b.hd, b.BS, b.seq_lens, b.q_lens)
     tables = W.replica_tables(b, 4)

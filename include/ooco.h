@@ -219,6 +219,22 @@ ooco_status ooco_kv_block_copy(ooco_ctx *ctx, const void *k_src /*DEVICE*/, cons
                                const int64_t *src_block_ids /*DEVICE*/,
                                const int64_t *dst_block_ids /*DEVICE*/, int64_t num_pairs, void *stream);
 
+/* KV append, the step that precedes ooco_attn_mixed: the K and V vectors of this step's tokens are
+ * written into their paged slots (the paper's KV cache keeps the K/V of every processed token for
+ * reuse by later steps, Section 2.1 and 2.3): row query_start_loc[i] + t of k_new / v_new is the
+ * token at position ctx_lens[i] + t of sequence i and goes to block
+ * block_tables[i][pos / BS], slot pos % BS.  Bit-exact; no other element of the pools changes.
+ *   k_new, v_new: DEVICE bf16 [total_q_tokens][Hkv][hd]; k_cache, v_cache: DEVICE pools of this
+ *   context's geometry (written); block_tables, query_start_loc, ctx_lens: DEVICE int32 as for
+ *   ooco_attn_mixed (seq_lens is not needed).
+ * Needs no plan, never synchronises, one kernel on `stream`.  Rows whose position lies beyond the
+ * block table, or whose block id lies outside [0, num_blocks), are skipped (ids are otherwise
+ * trusted).  num_seqs == 0 or total_q_tokens == 0 returns OOCO_OK without a launch. */
+ooco_status ooco_kv_append(ooco_ctx *ctx, const void *k_new /*DEVICE*/, const void *v_new /*DEVICE*/,
+                           void *k_cache /*DEVICE*/, void *v_cache /*DEVICE*/, const int32_t *block_tables /*DEVICE*/,
+                           const int32_t *query_start_loc /*DEVICE*/, const int32_t *ctx_lens /*DEVICE*/,
+                           int num_seqs, int total_q_tokens, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

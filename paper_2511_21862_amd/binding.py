@@ -19,7 +19,7 @@ _STATUS_NAMES = {0: "OOCO_OK", -1: "OOCO_EINVAL", -2: "OOCO_ESHAPE", -3: "OOCO_E
                  -5: "OOCO_ENOTIMPL"}
 
 EXPORTS = ["ooco_ctx_create", "ooco_ctx_destroy", "ooco_last_error", "ooco_set_option", "ooco_plan",
-           "ooco_plan_dry_run", "ooco_plan_info", "ooco_profile_read", "ooco_trace_read", "ooco_attn_mixed", "ooco_kv_block_copy"]
+           "ooco_plan_dry_run", "ooco_plan_info", "ooco_profile_read", "ooco_trace_read", "ooco_attn_mixed", "ooco_kv_block_copy", "ooco_kv_append"]
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2511_21862_amd.build` "
@@ -51,6 +51,8 @@ _lib.ooco_attn_mixed.restype = ctypes.c_int
 _lib.ooco_attn_mixed.argtypes = [_P] * 9 + [ctypes.c_int, ctypes.c_int, _P]
 _lib.ooco_kv_block_copy.restype = ctypes.c_int
 _lib.ooco_kv_block_copy.argtypes = [_P] * 7 + [ctypes.c_int64, _P]
+_lib.ooco_kv_append.restype = ctypes.c_int
+_lib.ooco_kv_append.argtypes = [_P] * 8 + [ctypes.c_int, ctypes.c_int, _P]
 
 
 class OocoError(RuntimeError):
@@ -186,6 +188,13 @@ def ooco_kv_block_copy(ctx, k_src, v_src, k_dst, v_dst, src_block_ids, dst_block
                                         _dev(dst_block_ids), num_pairs, _stream_handle(stream)))
 
 
+def ooco_kv_append(ctx, k_new, v_new, k_cache, v_cache, block_tables, query_start_loc, ctx_lens, num_seqs,
+                   total_q_tokens, stream=None) -> None:
+    _check(ctx, _lib.ooco_kv_append(ctx, _dev(k_new), _dev(v_new), _dev(k_cache), _dev(v_cache), _dev(block_tables),
+                                    _dev(query_start_loc), _dev(ctx_lens), num_seqs, total_q_tokens,
+                                    _stream_handle(stream)))
+
+
 class Context:
     """RAII holder of one ooco_ctx (no arithmetic here either)."""
 
@@ -229,6 +238,10 @@ class Context:
     def attn_mixed(self, q, k_cache, v_cache, block_tables, seq_lens, query_start_loc, ctx_lens, out, stream=None):
         ooco_attn_mixed(self.h, q, k_cache, v_cache, block_tables, seq_lens, query_start_loc, ctx_lens, out,
                         int(seq_lens.shape[0]), int(q.shape[0]), stream)
+
+    def kv_append(self, k_new, v_new, k_cache, v_cache, block_tables, query_start_loc, ctx_lens, stream=None):
+        ooco_kv_append(self.h, k_new, v_new, k_cache, v_cache, block_tables, query_start_loc, ctx_lens,
+                       int(ctx_lens.shape[0]), int(k_new.shape[0]), stream)
 
     def kv_block_copy(self, k_src, v_src, k_dst, v_dst, src_ids, dst_ids, stream=None):
         ooco_kv_block_copy(self.h, k_src, v_src, k_dst, v_dst, src_ids, dst_ids, int(src_ids.shape[0]), stream)

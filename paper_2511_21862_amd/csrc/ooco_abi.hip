@@ -700,4 +700,21 @@ ooco_status ooco_kv_block_copy(ooco_ctx *ctx, const void *k_src, const void *v_s
     return OOCO_OK;
 }
 
+ooco_status ooco_kv_append(ooco_ctx *ctx, const void *k_new, const void *v_new, void *k_cache, void *v_cache,
+                           const int32_t *block_tables, const int32_t *query_start_loc, const int32_t *ctx_lens,
+                           int num_seqs, int total_q_tokens, void *stream)
+{
+    if (!ctx) return OOCO_EINVAL;
+    if (num_seqs < 0 || total_q_tokens < 0)
+        return fail(ctx, OOCO_EINVAL, "ooco_kv_append: num_seqs=%d total_q_tokens=%d", num_seqs, total_q_tokens);
+    if (num_seqs == 0 || total_q_tokens == 0) return OOCO_OK;
+    if (!k_new || !v_new || !k_cache || !v_cache || !block_tables || !query_start_loc || !ctx_lens)
+        return fail(ctx, OOCO_EINVAL, "ooco_kv_append: NULL pointer argument");
+    hipError_t e = launch_kv_append(k_new, v_new, k_cache, v_cache, block_tables, query_start_loc, ctx_lens, num_seqs,
+                                    total_q_tokens, ctx->Hkv, ctx->hd, ctx->max_blocks_per_seq, ctx->num_blocks,
+                                    reinterpret_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(ctx, OOCO_EHIP, "ooco_kv_append: kernel launch: %s", hipGetErrorString(e));
+    return OOCO_OK;
+}
+
 }  // extern "C"

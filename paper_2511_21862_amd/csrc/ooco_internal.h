@@ -72,6 +72,10 @@ hipError_t launch_block_copy(const void *k_src, const void *v_src, void *k_dst, 
                              const int64_t *src_ids, const int64_t *dst_ids, int64_t num_pairs,
                              int64_t block_bytes, hipStream_t s);
 
+hipError_t launch_kv_append(const void *k_new, const void *v_new, void *k_cache, void *v_cache, const int32_t *block_tables,
+                            const int32_t *query_start_loc, const int32_t *ctx_lens, int num_seqs, int total_q, int Hkv,
+                            int hd, int max_blocks_per_seq, int64_t num_blocks, hipStream_t s);
+
 extern int g_copy_variant;   // tuning knob of the block-copy kernel (option "copy_variant")
 
 // Query rows of one prefill tile for a GQA group of g heads.

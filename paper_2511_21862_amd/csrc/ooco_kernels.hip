@@ -787,6 +787,77 @@ __global__ __launch_bounds__(kCopyThreads) void block_copy_kernel(const u32x4 *k
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// KV append: the K and V vectors of the step's tokens go into their paged slots.  One wave per
+// query row.  K: the wave stores its own row, one 16-byte store per group of 8 dims (the cache
+// keeps [hd/8][16 slots][8]).  V is stored [dim][16 slots], so the rows of this step that fall into
+// the same KV block are written together: each of their waves takes an equal share of the
+// (kv head, dim) elements, gathers that element from all rows of the group and writes the values
+// side by side (two 16-byte stores when the step covers the whole block, 2-byte stores otherwise).
+__global__ __launch_bounds__(64) void kv_append_kernel(const uint16_t *k_new, const uint16_t *v_new, uint16_t *k_cache,
+                                                       uint16_t *v_cache, const int32_t *block_tables,
+                                                       const int32_t *query_start_loc, const int32_t *ctx_lens,
+                                                       int num_seqs, int total_q, int Hkv, int hd, int max_blocks_per_seq,
+                                                       int64_t num_blocks)
+{
+    const int lane = threadIdx.x;
+    const int row = blockIdx.x;
+    auto qsl_at = [&](int idx) -> int { return query_start_loc[idx]; };
+    const int seq = __builtin_amdgcn_readfirstlane(min(count_le(qsl_at, num_seqs, row, lane), num_seqs - 1));
+    const int q0 = query_start_loc[seq], q_len = query_start_loc[seq + 1] - q0;
+    const int t = row - q0;
+    if (t < 0 || t >= q_len) return;                    // inconsistent query_start_loc: nothing is written
+    const int ctx = ctx_lens[seq];
+    const int pos = ctx + t;
+    const int bidx = pos / kBlockSize;
+    if (ctx < 0 || bidx >= max_blocks_per_seq) return;  // beyond the block table: nothing is written
+    const int64_t blk = block_tables[(int64_t)seq * max_blocks_per_seq + bidx];
+    if (blk < 0 || blk >= num_blocks) return;           // id outside the pool: nothing is written
+    const int slot = pos % kBlockSize;
+    const int row_elems = Hkv * hd;
+    // K: chunk c = (kv head, group of 8 dims) -> cache chunk ((blk*Hkv + kvh)*(hd/8) + d8)*16 + slot
+    {
+        const int hd8 = hd / 8;
+        const u32x4 *src = reinterpret_cast<const u32x4 *>(k_new + (int64_t)row * row_elems);
+        u32x4 *dst = reinterpret_cast<u32x4 *>(k_cache) + (int64_t)blk * Hkv * hd8 * kBlockSize + slot;
+        for (int c = lane; c < Hkv * hd8; c += 64) dst[(int64_t)c * kBlockSize] = src[c];
+    }
+    // V: the group = rows t0 .. t0+nrow-1 of this sequence that share the block; this wave is member j
+    const int t0 = max(0, t - slot);
+    const int slot0 = (ctx + t0) % kBlockSize;
+    const int nrow = min(min(kBlockSize - slot0, q_len - t0), total_q - (q0 + t0));
+    const int j = t - t0;
+    const int e_lo = (int)((int64_t)row_elems * j / nrow), e_hi = (int)((int64_t)row_elems * (j + 1) / nrow);
+    const uint16_t *src0 = v_new + (int64_t)(q0 + t0) * row_elems;
+    uint16_t *dst0 = v_cache + (int64_t)blk * row_elems * kBlockSize + slot0;
+    for (int e = e_lo + lane; e < e_hi; e += 64) {     // element e = (kv head, dim) -> cache row (blk*Hkv*hd + e)*16
+        const uint16_t *src = src0 + e;
+        uint16_t *dst = dst0 + (int64_t)e * kBlockSize;
+        if (nrow == kBlockSize) {
+            uint32_t w[8];
+#pragma unroll
+            for (int r = 0; r < 8; ++r)
+                w[r] = (uint32_t)src[(int64_t)(2 * r) * row_elems] | ((uint32_t)src[(int64_t)(2 * r + 1) * row_elems] << 16);
+            u32x4 *d4 = reinterpret_cast<u32x4 *>(dst);
+            d4[0] = u32x4{w[0], w[1], w[2], w[3]};
+            d4[1] = u32x4{w[4], w[5], w[6], w[7]};
+        } else {
+            for (int r = 0; r < nrow; ++r) dst[r] = src[(int64_t)r * row_elems];
+        }
+    }
+}
+
+hipError_t launch_kv_append(const void *k_new, const void *v_new, void *k_cache, void *v_cache, const int32_t *block_tables,
+                            const int32_t *query_start_loc, const int32_t *ctx_lens, int num_seqs, int total_q, int Hkv,
+                            int hd, int max_blocks_per_seq, int64_t num_blocks, hipStream_t s)
+{
+    if (total_q <= 0 || num_seqs <= 0) return hipSuccess;
+    hipLaunchKernelGGL(kv_append_kernel, dim3((unsigned)total_q), dim3(64), 0, s, (const uint16_t *)k_new,
+                       (const uint16_t *)v_new, (uint16_t *)k_cache, (uint16_t *)v_cache, block_tables, query_start_loc,
+                       ctx_lens, num_seqs, total_q, Hkv, hd, max_blocks_per_seq, num_blocks);
+    return hipGetLastError();
+}
+
 int g_copy_variant = 0;   // tuning: 10*vectors per thread + non-temporal flag (0 = default)
 
 // ------------------------------------------------------------------------------------------
