@@ -386,3 +386,53 @@ def test_kv_append_reads_back_through_the_independent_gather():
     assert (k[14:17] == k_new[0:3]).all() and (v[14:17] == v_new[0:3]).all()
     k, v = W.gather_logical(b, 1)
     assert (k[0] == k_new[3]).all() and (v[0] == v_new[3]).all()
+
+
+# ----------------------------------------------------------------------------- roofline latency model
+from oracle import perf_model  # noqa: E402
+
+PARAMS = dict(F_ap=1.0e15, F_ad=2.0e14, M_a=5.0e12, O_p=30e-6, O_d=20e-6)
+
+
+def test_model_operator_counts_equal_hand_evaluated_table2_rows():
+    path = os.path.join(os.path.dirname(__file__), "golden", "table2_attention.txt")
+    rows = [l.split() for l in open(path) if l.strip() and not l.startswith("#")]
+    assert len(rows) >= 5
+    for Hq, Hkv, hd, Sq, Skv, flops, nbytes in (map(int, r) for r in rows):
+        assert perf_model.attention_flops(Hq, hd, Sq, Skv) == flops
+        assert perf_model.attention_bytes(Hq, Hkv, hd, Sq, Skv) == nbytes
+
+
+def test_model_equation1_regimes_and_crossing():
+    # decode operator, Hq 32 / Hkv 8 / hd 128: FLOPs = 16384*S, bytes = 4096*S + 16384: intensity < 4 FLOP/B,
+    # far below F_ad/M_a = 40 -> memory-bound, time = bytes / M_a exactly
+    r = perf_model.predict(PARAMS, 32, 8, 128, [1], [999])
+    assert r["decode"] == (4096 * 1000 + 16384) / 5.0e12 and r["memory_bound"] == r["decode"] and r["compute_bound"] == 0
+    assert r["latency"] == r["decode"] + 20e-6 and r["prefill"] == 0
+    # prefill operator of c rows over c keys: FLOPs = 16384 c^2, bytes = 4096 c + 16384 c = 20480 c; compute-bound iff
+    # 16384 c^2 / 1e15 >= 20480 c / 5e12, i.e. c >= 250
+    lo = perf_model.predict(PARAMS, 32, 8, 128, [249], [0])
+    hi = perf_model.predict(PARAMS, 32, 8, 128, [250], [0])
+    assert lo["memory_bound"] > 0 and lo["compute_bound"] == 0 and lo["prefill"] == 20480 * 249 / 5.0e12
+    assert hi["compute_bound"] > 0 and hi["memory_bound"] == 0 and hi["prefill"] == 16384 * 250 * 250 / 1.0e15
+    assert math.isclose(hi["prefill"], 20480 * 250 / 5.0e12, rel_tol=1e-12)       # the two roofs meet at c = 250
+    # a slower decode roof turns the same decode operator compute-bound
+    slow = perf_model.predict({**PARAMS, "F_ad": 1.0e12}, 32, 8, 128, [1], [999])
+    assert slow["decode"] == 16384 * 1000 / 1.0e12 and slow["compute_bound"] == slow["decode"]
+
+
+def test_model_iteration_is_the_sum_of_operators_plus_overheads():
+    ql, cx = [1, 512, 1, 0, 2048, 1], [4095, 100, 0, 7, 4096, 70000]
+    whole = perf_model.predict(PARAMS, 64, 8, 128, ql, cx)
+    parts = [perf_model.predict(PARAMS, 64, 8, 128, [q], [c]) for q, c in zip(ql, cx)]
+    assert math.isclose(whole["prefill"], sum(p["prefill"] for p in parts), rel_tol=1e-14)
+    assert math.isclose(whole["decode"], sum(p["decode"] for p in parts), rel_tol=1e-14)
+    assert whole["overhead"] == 50e-6                                              # each kind of work once
+    assert math.isclose(whole["latency"], whole["prefill"] + whole["decode"] + 50e-6, rel_tol=1e-14)
+    assert parts[3]["latency"] == 0.0                                              # empty sequence: no operator
+    assert perf_model.predict(PARAMS, 64, 8, 128, [1, 1], [10, 20])["overhead"] == 20e-6
+    assert perf_model.predict(PARAMS, 64, 8, 128, [5], [10])["overhead"] == 30e-6
+    # decode attention latency grows in proportion to the batch's total token count (Section 3.3.3)
+    a = perf_model.predict(PARAMS, 32, 8, 128, [1] * 10, [1023] * 10)["decode"]
+    b = perf_model.predict(PARAMS, 32, 8, 128, [1] * 20, [1023] * 20)["decode"]
+    assert math.isclose(b, 2 * a, rel_tol=1e-14)
