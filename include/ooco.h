@@ -235,6 +235,29 @@ ooco_status ooco_kv_append(ooco_ctx *ctx, const void *k_new /*DEVICE*/, const vo
                            const int32_t *query_start_loc /*DEVICE*/, const int32_t *ctx_lens /*DEVICE*/,
                            int num_seqs, int total_q_tokens, void *stream);
 
+/* Roofline latency model of the attention operator (paper Section 3.3: Table 2 gives the operator's
+ * FLOPs 4*D_h*S_q*S_kv and bytes 2d*(S_q*D_h + S_kv*D_h*H_kv/H_q) with D_h = H_q*head_dim; Equation 1
+ * gives its latency max(FLOPs/F_a, bytes/M_a) with separate achievable FLOP rates for prefill and decode
+ * attention (Table 3); an iteration's latency is the sum over its operators plus a static overhead).
+ * Pure HOST function.  One operator per sequence with q_len > 0 (S_q = q_len, S_kv = ctx_len + q_len;
+ * F_ap when q_len > 1, F_ad when q_len == 1); O_p is added once if the batch holds prefill work, O_d
+ * once if it holds decode work.  causal_flops != 0 counts only the visible (row, key) pairs,
+ * 4*D_h*(S_q*ctx + S_q(S_q+1)/2), instead of Table 2's S_q*S_kv (same for decode operators).
+ *   params: environment parameters, fitted from measurements of this library on the target GPU
+ *           (FLOP/s, FLOP/s, bytes/s, seconds, seconds)
+ *   h_query_start_loc [num_seqs+1], h_ctx_lens [num_seqs]: HOST, as for ooco_plan
+ *   out: HOST double[8] = (latency s, prefill operators s, decode operators s, overhead s, FLOPs, bytes,
+ *        time of compute-bound operators s, time of memory-bound operators s)
+ *   msg: HOST buffer for the error text, may be NULL.
+ * Errors: OOCO_EINVAL (NULL pointers, non-positive rates), OOCO_ESHAPE (geometry, negative lengths). */
+typedef struct ooco_model_params {
+    double F_ap, F_ad, M_a, O_p, O_d;
+} ooco_model_params;
+ooco_status ooco_predict_latency(const ooco_model_params *params /*HOST*/, int num_q_heads, int num_kv_heads,
+                                 int head_dim, int bytes_per_value, int causal_flops, int num_seqs,
+                                 const int32_t *h_query_start_loc /*HOST*/, const int32_t *h_ctx_lens /*HOST*/,
+                                 double *out /*HOST*/, char *msg /*HOST*/, size_t msg_cap);
+
 #ifdef __cplusplus
 }
 #endif

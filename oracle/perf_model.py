@@ -17,7 +17,9 @@ sum of its operators' latencies plus a static overhead):
 Readings (the paper is silent or garbled here; the build's design notes list them too):
   * the memory term's head ratio is H_kv / H_q (printed inverted: grouped-query attention must shrink
     the KV bytes, Section 2.3);
-  * Table 2's FLOPs ignore causality; the model keeps the table's count;
+  * Table 2's FLOPs ignore causality; the model keeps the table's count by default; with causal=True the
+    count is restricted to the visible (row, key) pairs, 4 * D_h * (S_q * ctx + S_q (S_q + 1) / 2), the
+    work a causal kernel does (for a decode operator both counts coincide);
   * the paper's iterations are either prefill or decode; a mixed call is modelled as both kinds of
     work in one iteration: operator times add, and each kind present contributes its overhead once;
   * only the attention operator is modelled here (GEMM and communication operators are outside the
@@ -43,8 +45,15 @@ def op_latency(flops: float, nbytes: float, F: float, M: float) -> float:
     return max(flops / F, nbytes / M)
 
 
+def attention_flops_causal(Hq: int, hd: int, S_q: int, ctx: int) -> float:
+    pairs = 0
+    for t in range(S_q):          # row t sees the ctx cached keys and rows 0..t of the chunk
+        pairs += ctx + t + 1
+    return 4.0 * (Hq * hd) * pairs
+
+
 def predict(params: Dict[str, float], Hq: int, Hkv: int, hd: int, q_lens: Sequence[int], ctx_lens: Sequence[int],
-            d: int = 2) -> Dict[str, float]:
+            d: int = 2, causal: bool = False) -> Dict[str, float]:
     """params: F_ap, F_ad [FLOP/s], M_a [B/s], O_p, O_d [s].  Returns the iteration latency and its parts."""
     t_prefill = t_decode = flops = nbytes = t_compute = t_memory = 0.0
     any_p = any_d = False
@@ -52,7 +61,7 @@ def predict(params: Dict[str, float], Hq: int, Hkv: int, hd: int, q_lens: Sequen
         ql, ctx = int(ql), int(ctx)
         if ql <= 0:
             continue
-        f = attention_flops(Hq, hd, ql, ctx + ql)
+        f = attention_flops_causal(Hq, hd, ql, ctx) if causal else attention_flops(Hq, hd, ql, ctx + ql)
         b = attention_bytes(Hq, Hkv, hd, ql, ctx + ql, d)
         F = params["F_ap"] if ql > 1 else params["F_ad"]
         t = op_latency(f, b, F, params["M_a"])

@@ -19,7 +19,7 @@ _STATUS_NAMES = {0: "OOCO_OK", -1: "OOCO_EINVAL", -2: "OOCO_ESHAPE", -3: "OOCO_E
                  -5: "OOCO_ENOTIMPL"}
 
 EXPORTS = ["ooco_ctx_create", "ooco_ctx_destroy", "ooco_last_error", "ooco_set_option", "ooco_plan",
-           "ooco_plan_dry_run", "ooco_plan_info", "ooco_profile_read", "ooco_trace_read", "ooco_attn_mixed", "ooco_kv_block_copy", "ooco_kv_append"]
+           "ooco_plan_dry_run", "ooco_plan_info", "ooco_profile_read", "ooco_trace_read", "ooco_attn_mixed", "ooco_kv_block_copy", "ooco_kv_append", "ooco_predict_latency"]
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2511_21862_amd.build` "
@@ -53,6 +53,17 @@ _lib.ooco_kv_block_copy.restype = ctypes.c_int
 _lib.ooco_kv_block_copy.argtypes = [_P] * 7 + [ctypes.c_int64, _P]
 _lib.ooco_kv_append.restype = ctypes.c_int
 _lib.ooco_kv_append.argtypes = [_P] * 8 + [ctypes.c_int, ctypes.c_int, _P]
+
+
+
+class ModelParams(ctypes.Structure):
+    """ooco_model_params: F_ap, F_ad [FLOP/s], M_a [bytes/s], O_p, O_d [s]."""
+    _fields_ = [(n, ctypes.c_double) for n in ("F_ap", "F_ad", "M_a", "O_p", "O_d")]
+
+
+_lib.ooco_predict_latency.restype = ctypes.c_int
+_lib.ooco_predict_latency.argtypes = ([ctypes.POINTER(ModelParams)] + [ctypes.c_int] * 6 + [_P, _P, ctypes.POINTER(ctypes.c_double),
+                                      ctypes.c_char_p, ctypes.c_size_t])
 
 
 class OocoError(RuntimeError):
@@ -193,6 +204,23 @@ def ooco_kv_append(ctx, k_new, v_new, k_cache, v_cache, block_tables, query_star
     _check(ctx, _lib.ooco_kv_append(ctx, _dev(k_new), _dev(v_new), _dev(k_cache), _dev(v_cache), _dev(block_tables),
                                     _dev(query_start_loc), _dev(ctx_lens), num_seqs, total_q_tokens,
                                     _stream_handle(stream)))
+
+
+def ooco_predict_latency(params, num_q_heads, num_kv_heads, head_dim, h_query_start_loc, h_ctx_lens,
+                         bytes_per_value=2, causal_flops=False) -> dict:
+    """params: dict or ModelParams.  Returns the model's outputs by name (argument marshalling only)."""
+    p = params if isinstance(params, ModelParams) else ModelParams(**{k: float(params[k]) for k, _ in ModelParams._fields_})
+    a, pa = _host_i32(h_query_start_loc)
+    c, pc = _host_i32(h_ctx_lens)
+    out = (ctypes.c_double * 8)()
+    msg = ctypes.create_string_buffer(256)
+    st = _lib.ooco_predict_latency(ctypes.byref(p), num_q_heads, num_kv_heads, head_dim, bytes_per_value, int(bool(causal_flops)),
+                                   len(c), pa, pc,
+                                   out, msg, 256)
+    if st != OOCO_OK:
+        raise OocoError(st, msg.value.decode())
+    names = ("latency", "prefill", "decode", "overhead", "flops", "bytes", "compute_bound", "memory_bound")
+    return dict(zip(names, list(out)))
 
 
 class Context:

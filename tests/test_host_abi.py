@@ -180,3 +180,30 @@ def test_small_workspace_reduces_the_number_of_runs():
 def test_empty_batch_plans_to_nothing():
     plan = dry(np.zeros(0, np.int32), np.zeros(1, np.int32), np.zeros(0, np.int32), num_seqs=0)
     assert len(plan["decode_pieces"]) == 0 and len(plan["prefill_tiles"]) == 0
+
+
+# ----------------------------------------------------------------------------- latency model (host function)
+def test_predict_latency_equals_the_model_oracle():
+    from oracle import perf_model
+    rng = np.random.default_rng(3)
+    for trial in range(40):
+        Hkv = int(rng.choice([1, 2, 4, 8]))
+        Hq = Hkv * int(rng.choice([1, 4, 7, 8]))
+        hd = int(rng.choice([64, 128]))
+        n = int(rng.integers(1, 40))
+        ql = rng.choice([0, 1, 1, 1, 2, 17, 512, 2048], size=n)
+        cx = rng.integers(0, 100000, size=n)
+        qsl = np.concatenate([[0], np.cumsum(ql)])
+        p = dict(F_ap=10 ** rng.uniform(13, 15.5), F_ad=10 ** rng.uniform(12, 15), M_a=10 ** rng.uniform(11.5, 13),
+                 O_p=rng.uniform(0, 1e-4), O_d=rng.uniform(0, 1e-4))
+        causal = bool(trial % 2)
+        got = B.ooco_predict_latency(p, Hq, Hkv, hd, qsl, cx, causal_flops=causal)
+        want = perf_model.predict(p, Hq, Hkv, hd, ql, cx, causal=causal)
+        for k in want:
+            assert got[k] == pytest.approx(want[k], rel=1e-12, abs=1e-300), (trial, k)
+    assert B.ooco_predict_latency(p, 32, 8, 128, [0], [])["latency"] == 0.0
+    for bad in (dict(p, M_a=0.0), dict(p, F_ap=-1.0)):
+        with pytest.raises(B.OocoError):
+            B.ooco_predict_latency(bad, 32, 8, 128, [0, 1], [5])
+    with pytest.raises(B.OocoError):
+        B.ooco_predict_latency(p, 32, 7, 128, [0, 1], [5])

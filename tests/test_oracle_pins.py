@@ -436,3 +436,19 @@ def test_model_iteration_is_the_sum_of_operators_plus_overheads():
     a = perf_model.predict(PARAMS, 32, 8, 128, [1] * 10, [1023] * 10)["decode"]
     b = perf_model.predict(PARAMS, 32, 8, 128, [1] * 20, [1023] * 20)["decode"]
     assert math.isclose(b, 2 * a, rel_tol=1e-14)
+
+
+def test_model_causal_count_is_the_number_of_visible_pairs():
+    # closed forms: c rows on an empty cache see 1 + 2 + ... + c keys; on ctx cached keys c*ctx more; decode unchanged
+    assert perf_model.attention_flops_causal(32, 128, 512, 0) == 4 * 4096 * (512 * 513 // 2)
+    assert perf_model.attention_flops_causal(32, 128, 512, 1000) == 4 * 4096 * (512 * 1000 + 512 * 513 // 2)
+    assert perf_model.attention_flops_causal(32, 128, 1, 999) == perf_model.attention_flops(32, 128, 1, 1000)
+    assert perf_model.attention_flops_causal(8, 64, 3, 2) == 4 * 512 * (3 + 4 + 5)
+    a = perf_model.predict(PARAMS, 32, 8, 128, [2048, 1], [0, 500], causal=True)
+    b = perf_model.predict(PARAMS, 32, 8, 128, [2048, 1], [0, 500], causal=False)
+    assert a["decode"] == b["decode"] and a["bytes"] == b["bytes"]
+    assert math.isclose(a["prefill"] / b["prefill"], (2049 / 2) / 2048, rel_tol=1e-12)   # both compute-bound
+    # the accounting used by bench.py for MFMA utilisation counts the same pairs
+    w = accounting.batch_work(32, 8, 128, 16, [2048, 501], [2048, 1])
+    assert w["flops_causal"] == a["flops"]
+
