@@ -452,3 +452,69 @@ def test_model_causal_count_is_the_number_of_visible_pairs():
     w = accounting.batch_work(32, 8, 128, 16, [2048, 501], [2048, 1])
     assert w["flops_causal"] == a["flops"]
 
+
+# ----------------------------------------------------------------------------- Mix Decoding Selection (Algorithm 2)
+from oracle import mix_select  # noqa: E402
+
+MIXP = dict(F_ap=1e18, F_ad=1e18, M_a=4.096e9, O_p=0.0, O_d=10e-6)
+
+
+def test_mix_selection_hand_worked_example():
+    path = os.path.join(os.path.dirname(__file__), "golden", "mix_selection.txt")
+    cases = [l.split() for l in open(path) if l.startswith("S_us")]
+    assert len(cases) == 3
+    for c in cases:
+        S = float(c[1]) * 1e-6
+        order = [int(x) for x in c[c.index("order") + 1:c.index("selected")]]
+        want = [bool(int(x)) for x in c[c.index("selected") + 1:c.index("latency_us")]]
+        lat = float(c[-1]) * 1e-6
+        r = mix_select.mix_decoding_select(MIXP, 32, 8, 128, S, [100, 200], [50, 400, 30, 120, 60, 500], order)
+        assert r["selected"] == want
+        assert math.isclose(r["latency"], lat, rel_tol=1e-12)
+
+
+def test_mix_selection_equal_lengths_closed_form():
+    # every request costs (n + 4) us: with no online requests and no random looks the number admitted is
+    # floor((S - 10 us) / (n + 4) us), capped by the number of candidates
+    for n, S_us, cand in ((96, 1010.5, 20), (96, 1009.5, 20), (996, 5000.0, 3), (46, 9.0, 5), (46, 59.5, 5), (46, 60.5, 5)):
+        r = mix_select.mix_decoding_select(MIXP, 32, 8, 128, S_us * 1e-6, [], [n] * cand, [])
+        want = min(cand, int(math.floor((S_us - 10.0) / (n + 4)))) if S_us > 10.0 else 0        # (no value sits on a tie)
+        assert sum(r["selected"]) == want, (n, S_us, cand)
+
+
+def test_mix_selection_invariants_by_exhaustive_scan():
+    rng = np.random.default_rng(8)
+    p = dict(F_ap=9e14, F_ad=2e14, M_a=6e12, O_p=1e-5, O_d=9e-6)
+    L = lambda lens: mix_select.latency(p, 32, 8, 128, lens)
+    for trial in range(60):
+        on = [int(x) for x in rng.integers(16, 4000, size=rng.integers(0, 4))]
+        off = [int(x) for x in rng.integers(16, 30000, size=rng.integers(0, 12))]
+        K = int(rng.integers(0, 6))
+        order = [int(x) for x in rng.integers(0, max(1, len(off)), size=K)] if off else []
+        S = float(rng.uniform(0.5, 3.0)) * L(on + off[: len(off) // 2 + 1])
+        r = mix_select.mix_decoding_select(p, 32, 8, 128, S, on, off, order)
+        sel = [i for i, s in enumerate(r["selected"]) if s]
+        chosen = on + [off[i] for i in sel]
+        assert math.isclose(r["latency"], L(chosen), rel_tol=1e-12)
+        if L(on) <= S:
+            assert r["latency"] <= S                                     # the bound holds whenever it can
+        else:
+            assert not sel                                               # best effort: online only
+        # the random phase, replayed one look at a time
+        b, looked, acc = list(on), set(), set()
+        for i in order:
+            if i in looked:
+                continue
+            looked.add(i)
+            if L(b + [off[i]]) <= S:
+                b.append(off[i])
+                acc.add(i)
+        assert {i for i in sel if i in looked} == acc and all(r["looked"][i] for i in looked)
+        # the sorted phase: exactly the longest admissible prefix, found here by scanning every prefix
+        rest = sorted((i for i in range(len(off)) if i not in looked), key=lambda i: (off[i], i))
+        best = 0
+        if L(b) < S:
+            for m in range(1, len(rest) + 1):
+                if L(b + [off[i] for i in rest[:m]]) <= S:
+                    best = m
+        assert [i for i in sel if i not in looked] == sorted(rest[:best])
