@@ -258,6 +258,29 @@ ooco_status ooco_predict_latency(const ooco_model_params *params /*HOST*/, int n
                                  const int32_t *h_query_start_loc /*HOST*/, const int32_t *h_ctx_lens /*HOST*/,
                                  double *out /*HOST*/, char *msg /*HOST*/, size_t msg_cap);
 
+/* Mix Decoding Selection (paper Section 3.4.4, Algorithm 2): the requests of the next decode step.  All
+ * online requests are kept; offline candidates join while the predicted step latency L(batch) (the
+ * attention model above on a decode-only batch: one operator per request, S_q = 1, S_kv = its length,
+ * plus O_d) stays within the TPOT bound slo_s: first num_looks candidates are looked at in the given
+ * random order (each joins if the batch still fits, else is dropped for this step), then, if candidates
+ * remain unlooked and L(batch) < slo_s, the remaining ones are sorted by ascending length (ties by
+ * index) and the longest prefix that still fits joins, found by bisection.
+ * Pure HOST function.
+ *   h_online_lens [num_online], h_offline_lens [num_offline]: HOST int32 request lengths (KV tokens
+ *     including the token of this step, >= 1)
+ *   h_random_order [num_looks]: HOST int32 indices into the offline candidates, drawn by the caller
+ *     (the algorithm's random choice is an input so that runs can be reproduced); an index that
+ *     repeats or lies outside [0, num_offline) uses up its look and changes nothing
+ *   h_selected [num_offline]: HOST bytes, written 1 for the candidates that join
+ *   latency_out: HOST, predicted latency of the chosen batch in seconds (may be NULL)
+ * If the online requests alone exceed slo_s they are all kept and no candidate joins. */
+ooco_status ooco_mix_decoding_select(const ooco_model_params *params /*HOST*/, int num_q_heads, int num_kv_heads,
+                                     int head_dim, int bytes_per_value, double slo_s, int num_online,
+                                     const int32_t *h_online_lens /*HOST*/, int num_offline,
+                                     const int32_t *h_offline_lens /*HOST*/, int num_looks,
+                                     const int32_t *h_random_order /*HOST*/, uint8_t *h_selected /*HOST*/,
+                                     double *latency_out /*HOST*/, char *msg /*HOST*/, size_t msg_cap);
+
 #ifdef __cplusplus
 }
 #endif

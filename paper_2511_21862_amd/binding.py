@@ -19,7 +19,7 @@ _STATUS_NAMES = {0: "OOCO_OK", -1: "OOCO_EINVAL", -2: "OOCO_ESHAPE", -3: "OOCO_E
                  -5: "OOCO_ENOTIMPL"}
 
 EXPORTS = ["ooco_ctx_create", "ooco_ctx_destroy", "ooco_last_error", "ooco_set_option", "ooco_plan",
-           "ooco_plan_dry_run", "ooco_plan_info", "ooco_profile_read", "ooco_trace_read", "ooco_attn_mixed", "ooco_kv_block_copy", "ooco_kv_append", "ooco_predict_latency"]
+           "ooco_plan_dry_run", "ooco_plan_info", "ooco_profile_read", "ooco_trace_read", "ooco_attn_mixed", "ooco_kv_block_copy", "ooco_kv_append", "ooco_predict_latency", "ooco_mix_decoding_select"]
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2511_21862_amd.build` "
@@ -64,6 +64,11 @@ class ModelParams(ctypes.Structure):
 _lib.ooco_predict_latency.restype = ctypes.c_int
 _lib.ooco_predict_latency.argtypes = ([ctypes.POINTER(ModelParams)] + [ctypes.c_int] * 6 + [_P, _P, ctypes.POINTER(ctypes.c_double),
                                       ctypes.c_char_p, ctypes.c_size_t])
+
+_lib.ooco_mix_decoding_select.restype = ctypes.c_int
+_lib.ooco_mix_decoding_select.argtypes = ([ctypes.POINTER(ModelParams)] + [ctypes.c_int] * 4 + [ctypes.c_double, ctypes.c_int, _P,
+                                          ctypes.c_int, _P, ctypes.c_int, _P, _P, ctypes.POINTER(ctypes.c_double),
+                                          ctypes.c_char_p, ctypes.c_size_t])
 
 
 class OocoError(RuntimeError):
@@ -221,6 +226,24 @@ def ooco_predict_latency(params, num_q_heads, num_kv_heads, head_dim, h_query_st
         raise OocoError(st, msg.value.decode())
     names = ("latency", "prefill", "decode", "overhead", "flops", "bytes", "compute_bound", "memory_bound")
     return dict(zip(names, list(out)))
+
+
+def ooco_mix_decoding_select(params, num_q_heads, num_kv_heads, head_dim, slo_s, online_lens, offline_lens, random_order,
+                             bytes_per_value=2) -> dict:
+    """Returns dict(selected=bool array over the offline candidates, latency=predicted seconds)."""
+    p = params if isinstance(params, ModelParams) else ModelParams(**{k: float(params[k]) for k, _ in ModelParams._fields_})
+    on, pon = _host_i32(online_lens)
+    off, poff = _host_i32(offline_lens)
+    order, pord = _host_i32(random_order)
+    sel = np.zeros(max(len(off), 1), dtype=np.uint8)
+    lat = ctypes.c_double()
+    msg = ctypes.create_string_buffer(256)
+    st = _lib.ooco_mix_decoding_select(ctypes.byref(p), num_q_heads, num_kv_heads, head_dim, bytes_per_value, float(slo_s),
+                                       len(on), pon, len(off), poff, len(order), pord, sel.ctypes.data, ctypes.byref(lat),
+                                       msg, 256)
+    if st != OOCO_OK:
+        raise OocoError(st, msg.value.decode())
+    return dict(selected=sel[: len(off)].astype(bool), latency=lat.value)
 
 
 class Context:

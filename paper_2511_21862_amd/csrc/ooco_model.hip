@@ -3,7 +3,10 @@
 // = sum of operator latencies + static overhead).  No device code, no device state.
 #include "ooco.h"
 
+#include <algorithm>
 #include <cstdio>
+#include <numeric>
+#include <vector>
 
 extern "C" ooco_status ooco_predict_latency(const ooco_model_params *params, int num_q_heads, int num_kv_heads,
                                             int head_dim, int bytes_per_value, int causal_flops, int num_seqs,
@@ -55,5 +58,86 @@ extern "C" ooco_status ooco_predict_latency(const ooco_model_params *params, int
     out[5] = bytes;
     out[6] = t_c;
     out[7] = t_m;
+    return OOCO_OK;
+}
+
+namespace {
+// Latency of one decode operator over n keys (Table 2 with S_q = 1, Equation 1).
+double decode_op_time(const ooco_model_params &p, double D_h, double kv_ratio, double d, double n)
+{
+    const double f = 4.0 * D_h * n, b = 2.0 * d * (D_h + n * D_h * kv_ratio);
+    const double tf = f / p.F_ad, tb = b / p.M_a;
+    return tf >= tb ? tf : tb;
+}
+}  // namespace
+
+// Mix Decoding Selection (paper Algorithm 2).  L(B) of a decode-only batch is the sum of its operators' times
+// plus O_d, so the batch latency is kept as a running sum: one look costs O(1), the sorted phase one sort, one
+// prefix sum and a bisection.  The sums are accumulated in the same order as a from-scratch evaluation of the
+// batch (online requests, accepted looks in order, then the sorted prefix).
+extern "C" ooco_status ooco_mix_decoding_select(const ooco_model_params *params, int num_q_heads, int num_kv_heads,
+                                                int head_dim, int bytes_per_value, double slo_s, int num_online,
+                                                const int32_t *h_online_lens, int num_offline,
+                                                const int32_t *h_offline_lens, int num_looks, const int32_t *h_random_order,
+                                                uint8_t *h_selected, double *latency_out, char *msg, size_t msg_cap)
+{
+    auto bad = [&](ooco_status code, const char *text) {
+        if (msg && msg_cap) snprintf(msg, msg_cap, "ooco_mix_decoding_select: %s", text);
+        return code;
+    };
+    if (msg && msg_cap) msg[0] = 0;
+    if (!params) return bad(OOCO_EINVAL, "NULL params");
+    if (!(params->F_ad > 0) || !(params->M_a > 0) || !(params->O_d >= 0)) return bad(OOCO_EINVAL, "F_ad, M_a must be positive, O_d non-negative");
+    if (num_q_heads <= 0 || num_kv_heads <= 0 || num_q_heads % num_kv_heads || head_dim <= 0 || bytes_per_value <= 0)
+        return bad(OOCO_ESHAPE, "bad head geometry");
+    if (num_online < 0 || num_offline < 0 || num_looks < 0 || (num_online > 0 && !h_online_lens) ||
+        (num_offline > 0 && (!h_offline_lens || !h_selected)) || (num_looks > 0 && !h_random_order))
+        return bad(OOCO_EINVAL, "bad array arguments");
+    const double D_h = (double)num_q_heads * head_dim, d = bytes_per_value, kv_ratio = (double)num_kv_heads / num_q_heads;
+    auto op = [&](int32_t n) { return decode_op_time(*params, D_h, kv_ratio, d, (double)n); };
+    for (int i = 0; i < num_online; ++i)
+        if (h_online_lens[i] < 1) return bad(OOCO_ESHAPE, "request length below 1");
+    for (int i = 0; i < num_offline; ++i)
+        if (h_offline_lens[i] < 1) return bad(OOCO_ESHAPE, "request length below 1");
+    double sum = 0.0;          // operator times of the batch so far
+    int members = num_online;
+    for (int i = 0; i < num_online; ++i) sum += op(h_online_lens[i]);
+    auto L = [&](double s, int n) { return n > 0 ? s + params->O_d : 0.0; };
+    std::vector<uint8_t> looked((size_t)num_offline, 0);
+    for (int i = 0; i < num_offline; ++i) h_selected[i] = 0;
+    for (int k = 0; k < num_looks; ++k) {                      // the random looks
+        const int32_t r = h_random_order[k];
+        if (r < 0 || r >= num_offline || looked[(size_t)r]) continue;
+        looked[(size_t)r] = 1;
+        const double with = sum + op(h_offline_lens[r]);
+        if (L(with, members + 1) <= slo_s) {
+            sum = with;
+            ++members;
+            h_selected[r] = 1;
+        }
+    }
+    std::vector<int32_t> rest;
+    for (int i = 0; i < num_offline; ++i)
+        if (!looked[(size_t)i]) rest.push_back(i);
+    if (!rest.empty() && L(sum, members) < slo_s) {            // shortest first, longest admissible prefix
+        std::sort(rest.begin(), rest.end(), [&](int32_t a, int32_t b) {
+            return h_offline_lens[a] != h_offline_lens[b] ? h_offline_lens[a] < h_offline_lens[b] : a < b;
+        });
+        std::vector<double> pre(rest.size() + 1);
+        pre[0] = sum;
+        for (size_t m = 0; m < rest.size(); ++m) pre[m + 1] = pre[m] + op(h_offline_lens[rest[m]]);
+        size_t lo = 0, hi = rest.size();
+        while (lo < hi) {
+            const size_t mid = (lo + hi + 1) / 2;
+            if (L(pre[mid], members + (int)mid) <= slo_s)
+                lo = mid;
+            else
+                hi = mid - 1;
+        }
+        for (size_t m = 0; m < lo; ++m) h_selected[rest[m]] = 1;
+        sum = pre[lo];
+        members += (int)lo;
+    }
+    if (latency_out) *latency_out = L(sum, members);
     return OOCO_OK;
 }

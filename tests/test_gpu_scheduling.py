@@ -1,0 +1,65 @@
+"""Mix Decoding Selection (Algorithm 2) against the hardware: a batch admitted under a TPOT bound by
+ooco_mix_decoding_select with the parameters fitted on MI355X is run through ooco_attn_mixed and timed."""
+import json
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2511_21862_amd import binding as B
+from paper_2511_21862_amd import workloads as W
+
+from gpu_util import say
+
+pytestmark = pytest.mark.gpu
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def timed_decode(Hq, Hkv, hd, lens, num_blocks=49152, burst=8, reps=7):
+    ql = np.ones(len(lens), np.int32)
+    b = W.build_batch(Hq=Hq, Hkv=Hkv, hd=hd, q_lens=ql, ctx_lens=np.asarray(lens, np.int32) - 1, num_blocks=num_blocks,
+                      seed=90, device="cuda")
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    bt, sl, qsl, cl = t(b.block_tables), t(b.seq_lens), t(b.query_start_loc), t(b.ctx_lens)
+    out = torch.empty((b.total_q, Hq, hd), dtype=torch.bfloat16, device="cuda")
+    stream = torch.cuda.current_stream()
+    ts = []
+    with B.Context(Hq, Hkv, hd, 16, b.num_blocks, b.max_blocks_per_seq) as ctx:
+        ctx.plan(b.seq_lens, b.query_start_loc, b.ctx_lens)
+        for r in range(reps + 2):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(burst):
+                ctx.attn_mixed(b.q, b.k_cache, b.v_cache, bt, sl, qsl, cl, out, stream)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            if r >= 2:
+                ts.append(e0.elapsed_time(e1) * 1e-3 / burst)
+    assert bool(torch.isfinite(out.float()).all())
+    return float(np.median(ts))
+
+
+@pytest.mark.parametrize("slo_us", [150.0, 400.0])
+def test_admitted_batch_runs_within_the_bound(slo_us):
+    fit = json.load(open(os.path.join(HERE, "..", "paper_2511_21862_amd", "model_params_mi355x.json")))
+    p = fit["table2_flops"]["params"]
+    rng = np.random.default_rng(int(slo_us))
+    online = np.clip(np.round(np.exp(np.log(1500) + 0.5 * rng.standard_normal(16))), 64, 8192).astype(np.int32)
+    offline = np.clip(np.round(np.exp(np.log(2048) + 0.8 * rng.standard_normal(800))), 64, 16384).astype(np.int32)
+    order = rng.permutation(len(offline))[:32]
+    S = slo_us * 1e-6
+    r = B.ooco_mix_decoding_select(p, 32, 8, 128, S, online, offline, order)
+    chosen = np.concatenate([online, offline[r["selected"]]])
+    say(f"case: SLO {slo_us} us: {int(r['selected'].sum())} of {len(offline)} offline requests admitted, "
+        f"{int(chosen.sum())} KV tokens, predicted {r['latency'] * 1e6:.1f} us")
+    assert r["latency"] <= S and 0 < r["selected"].sum() < len(offline)
+    # the budget is used: the shortest candidate left out would not have fitted
+    left = offline[~r["selected"]]
+    assert B.ooco_predict_latency(p, 32, 8, 128, np.arange(len(chosen) + 2), np.concatenate([chosen, [left.min()]]) - 1)["latency"] > S \
+        or left.min() > offline[r["selected"]].max()
+    t = timed_decode(32, 8, 128, chosen)
+    say(f"  measured {t * 1e6:.1f} us per call ({t / S * 100:.0f} % of the bound, model error {(r['latency'] / t - 1) * 100:+.1f} %)")
+    assert t <= 1.25 * S, "admitted batch overran the bound by more than the model's error margin"
+    assert t >= 0.6 * S, "admitted batch leaves most of the bound unused"

@@ -207,3 +207,30 @@ def test_predict_latency_equals_the_model_oracle():
             B.ooco_predict_latency(bad, 32, 8, 128, [0, 1], [5])
     with pytest.raises(B.OocoError):
         B.ooco_predict_latency(p, 32, 7, 128, [0, 1], [5])
+
+
+# ----------------------------------------------------------------------------- Mix Decoding Selection (host function)
+def test_mix_decoding_select_equals_the_oracle():
+    from oracle import mix_select
+    rng = np.random.default_rng(12)
+    p = dict(F_ap=9e14, F_ad=2e14, M_a=6e12, O_p=1e-5, O_d=9e-6)
+    for trial in range(80):
+        Hkv = int(rng.choice([2, 4, 8]))
+        Hq = Hkv * int(rng.choice([1, 4, 7, 8]))
+        on = rng.integers(16, 6000, size=rng.integers(0, 6))
+        off = rng.integers(16, 40000, size=rng.integers(0, 40))
+        if trial % 5 == 0 and len(off):
+            off[:] = off[0]                                            # ties in the sort
+        order = rng.integers(-1, len(off) + 1, size=rng.integers(0, 12))
+        base = mix_select.latency(p, Hq, Hkv, 128, list(on) + list(off[: len(off) // 2]))
+        S = float(rng.uniform(0.3, 2.5)) * max(base, 5e-6)
+        want = mix_select.mix_decoding_select(p, Hq, Hkv, 128, S, on, off, order)
+        got = B.ooco_mix_decoding_select(p, Hq, Hkv, 128, S, on, off, order)
+        assert list(got["selected"]) == want["selected"], trial
+        assert got["latency"] == pytest.approx(want["latency"], rel=1e-12)
+    # the hand-worked example of tests/golden/mix_selection.txt through the library
+    mp = dict(F_ap=1e18, F_ad=1e18, M_a=4.096e9, O_p=0.0, O_d=10e-6)
+    got = B.ooco_mix_decoding_select(mp, 32, 8, 128, 700e-6, [100, 200], [50, 400, 30, 120, 60, 500], [1, 5, 1])
+    assert list(got["selected"]) == [True, False, True, True, True, False] and got["latency"] == pytest.approx(594e-6, rel=1e-12)
+    with pytest.raises(B.OocoError):
+        B.ooco_mix_decoding_select(mp, 32, 8, 128, 1e-3, [0], [5], [])
