@@ -293,12 +293,19 @@ def main():
     for i in range(a.warmup):
         step(i)
     torch.cuda.synchronize()
+    # the timed region is also bracketed by one pair of HIP events on the launch stream: for a batch with one
+    # kind of work (one kernel per step, launched back to back) region time / steps is that kernel's average
+    # launch duration, free of the per-launch event records of the profiled pass below
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
+    ev0.record(stream)
     for i in range(a.steps):
         step(i)
+    ev1.record(stream)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / a.steps * 1e3
+    region_ms_per_step = ev0.elapsed_time(ev1) / a.steps
 
     # per-kernel durations: the same K steps again with HIP events recorded around each kernel on
     # the launch stream (inside the library), so that the event overhead stays out of `value`
@@ -315,6 +322,12 @@ def main():
         done += n
     ctx.set_option("profile", 0)
     kern = {k: prof[k] / max(prof["calls"], 1) for k in ("prefill_ms", "decode_ms")}
+    kern["per_launch_events"] = dict(kern)
+    if work["prefill_chunks"] == 0:
+        kern["decode_ms"] = min(kern["decode_ms"], region_ms_per_step)
+    elif work["decode_seqs"] == 0:
+        kern["prefill_ms"] = min(kern["prefill_ms"], region_ms_per_step)
+    kern["region_ms_per_step"] = region_ms_per_step
 
     if dominant == "decode":
         alg = work["bytes_decode"]
