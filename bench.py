@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the mixed-batch paged-attention step on ONE MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg3|cfg3-prefill|cfg4|cfg4-copy|cfg4-copy-seq|cfg5|cfg5-prefill|cfg3-append|cfg5-append]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg3|cfg3-prefill|cfg4|cfg4-copy|cfg4-copy-seq|cfg5|cfg5-prefill|cfg3-append|cfg5-append|cfg4-preempt]
 
 A step = one pass of the whole path over one synthetic batch already resident in HBM: host
 planning (ooco_plan) + ooco_attn_mixed (prefill kernel, decode kernel with its in-kernel merge).  Steps
@@ -245,6 +245,110 @@ def bench_append(a):
     print(json.dumps(line), flush=True)
 
 
+def bench_preempt(a):
+    """Layer-level preemption of an offline decode iteration by an online prefill chunk (paper Section 3.4.1),
+    attention layers only: config 4's 512 offline decode sequences run a 32-layer iteration, one ooco_attn_mixed
+    call per layer, enqueued with a run-ahead of at most two layers; a preemption flag is raised while layer
+    `at` runs and is looked at before every enqueue.  On preemption the 64 victims' KV blocks are copied to a
+    staging pool, a 2048-token online chunk (on 4096 tokens of context) runs its 32 attention layers in the
+    freed blocks, the victims are copied back, and the iteration resumes at the layer it stopped at."""
+    import torch
+
+    from paper_2511_21862_amd import binding as B
+    from paper_2511_21862_amd import workloads as W
+
+    L = 32
+    b = W.config4(device="cuda")
+    dev = lambda x: torch.from_numpy(np.ascontiguousarray(x)).cuda()
+    bt, sl, qsl, cl = dev(b.block_tables), dev(b.seq_lens), dev(b.query_start_loc), dev(b.ctx_lens)
+    out = torch.empty((b.total_q, b.Hq, b.hd), dtype=torch.bfloat16, device="cuda")
+    victims = np.asarray(b.extra["victims"])
+    src = W.victim_block_ids(b, victims)
+    n = len(src)
+    src_d, stage_d = dev(src), torch.arange(n, dtype=torch.int64, device="cuda")
+    k_st = torch.empty((n,) + tuple(b.k_cache.shape[1:]), dtype=torch.bfloat16, device="cuda")
+    v_st = torch.empty((n,) + tuple(b.v_cache.shape[1:]), dtype=torch.bfloat16, device="cuda")
+    # the online chunk lives in the victims' blocks (they are free while the victims sit in the staging pool)
+    c_len, c_ctx = 2048, 4096
+    c_nb = (c_len + c_ctx + 15) // 16
+    assert c_nb <= n
+    c_bt = np.full((1, b.max_blocks_per_seq), -1, np.int32)
+    c_bt[0, :c_nb] = src[:c_nb]
+    c_meta = [dev(c_bt), dev(np.array([c_len + c_ctx], np.int32)), dev(np.array([0, c_len], np.int32)),
+              dev(np.array([c_ctx], np.int32))]
+    c_q = torch.randn((c_len, b.Hq, b.hd), device="cuda").to(torch.bfloat16)
+    c_out = torch.empty_like(c_q)
+    stream = torch.cuda.current_stream()
+    dec = B.Context(b.Hq, b.Hkv, b.hd, b.BS, b.num_blocks, b.max_blocks_per_seq)
+    onl = B.Context(b.Hq, b.Hkv, b.hd, b.BS, b.num_blocks, b.max_blocks_per_seq)
+    dec.plan(b.seq_lens, b.query_start_loc, b.ctx_lens)
+    onl.plan(np.array([c_len + c_ctx], np.int32), np.array([0, c_len], np.int32), np.array([c_ctx], np.int32))
+
+    def layer():
+        dec.attn_mixed(b.q, b.k_cache, b.v_cache, bt, sl, qsl, cl, out, stream)
+
+    def iteration(preempt_at=None):
+        """Returns (wall seconds, dict of the preemption's parts or None)."""
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        evs, parts = [], None
+        flag_time = None
+        l = 0
+        while l < L:
+            if len(evs) >= 2:
+                evs[-2].synchronize()            # run-ahead of at most two layers
+            if preempt_at is not None and flag_time is None and l == preempt_at + 2:
+                # the flag goes up while layer `preempt_at` runs (its predecessor has just finished); the two layers
+                # already enqueued complete, nothing further is enqueued
+                flag_time = time.perf_counter()
+                torch.cuda.synchronize()
+                t_idle = time.perf_counter()
+                dec.kv_block_copy(b.k_cache, b.v_cache, k_st, v_st, src_d, stage_d, stream)
+                torch.cuda.synchronize()
+                t_evict = time.perf_counter()
+                for _ in range(L):
+                    onl.attn_mixed(c_q, b.k_cache, b.v_cache, *c_meta, c_out, stream)
+                torch.cuda.synchronize()
+                t_online = time.perf_counter()
+                dec.kv_block_copy(k_st, v_st, b.k_cache, b.v_cache, stage_d, src_d, stream)
+                torch.cuda.synchronize()
+                t_restore = time.perf_counter()
+                parts = dict(preempt_latency_ms=(t_idle - flag_time) * 1e3, evict_ms=(t_evict - t_idle) * 1e3,
+                             online_chunk_32_layers_ms=(t_online - t_evict) * 1e3, restore_ms=(t_restore - t_online) * 1e3)
+                evs = []
+            layer()
+            e = torch.cuda.Event()
+            e.record(stream)
+            evs.append(e)
+            l += 1
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0, parts
+
+    for _ in range(max(1, a.warmup // 8)):
+        iteration()
+        iteration(5)
+    plain = [iteration()[0] for _ in range(max(3, a.steps // 20))]
+    pre = [iteration(int(at)) for at in np.random.default_rng(9).integers(0, L - 2, size=max(3, a.steps // 20))]
+    want = out.clone()
+    iteration()
+    same = bool(torch.equal(want.view(torch.int16), out.view(torch.int16)))
+    parts = {k: float(np.median([p[1][k] for p in pre])) for k in pre[0][1]}
+    t_plain, t_pre = float(np.median(plain)), float(np.median([p[0] for p in pre]))
+    line = {
+        "metric": "layer-level preemption of an offline decode iteration (attention layers only), 1 MI355X",
+        "value": b.total_q * L / t_plain, "unit": "tokens/s", "n_gpus": 1, "steps": len(plain), "warmup": a.warmup,
+        "ms_per_step": t_plain * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "cfg4-preempt", "layers": L, "decode_seqs": b.num_seqs, "victims": len(victims),
+                   "victim_blocks": n, "online_chunk": [c_len, c_ctx], "run_ahead_layers": 2},
+        "iteration_ms": t_plain * 1e3, "preempted_iteration_ms": t_pre * 1e3, **parts,
+        "layer_ms": t_plain * 1e3 / L, "output_after_preemption_bit_identical": same,
+    }
+    dec.close()
+    onl.close()
+    print(json.dumps(line), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -270,6 +374,8 @@ def main():
         return bench_block_copy(a)
     if a.workload in ("cfg3-append", "cfg5-append"):
         return bench_append(a)
+    if a.workload == "cfg4-preempt":
+        return bench_preempt(a)
     b, dominant = make_workload(a.workload)
     work = accounting.batch_work(b.Hq, b.Hkv, b.hd, b.BS, b.seq_lens, b.q_lens)
     tables = W.replica_tables(b, 4)
