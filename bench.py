@@ -6,7 +6,7 @@
 A step = one pass of the whole path over one synthetic batch already resident in HBM: host
 planning (ooco_plan) + ooco_attn_mixed (prefill kernel, decode kernel with its in-kernel merge).  Steps
 rotate over copies of the batch placed in disjoint physical blocks so that no step finds its KV
-in the 256 MB last-level cache.  Prints ONE JSON line (see the design doc for the fields).
+in the 256 MB last-level cache.  Prints ONE JSON line.
 """
 import argparse
 import json
