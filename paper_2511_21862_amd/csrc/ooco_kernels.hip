@@ -447,8 +447,9 @@ __global__ __launch_bounds__(64) void decode_kernel(const KernArgs a)
 // The SIMD's VALU issue port is shared with the matrix core (a 32x32x16 MFMA holds it for half of
 // its 32 cycles), so the kernel is tuned for few vector instructions per MFMA: 64-token steps
 // halve the per-step bookkeeping, maxima use v_max3, row sums v_dot2c on the packed weights,
-// masks run only on steps that touch the causal diagonal or the end of the sequence.  Two
-// workgroups fit a CU (<= 256 VGPRs, 64 KiB LDS each).
+// the causal mask runs only on steps that touch the diagonal; at the end of a sequence the unused V
+// slots are zeroed once in LDS instead of masking operands.  Two workgroups fit a CU (<= 256 VGPRs,
+// 64 KiB LDS each).
 constexpr int kPfThreads = 256;
 constexpr int kPfBlocks = 4;    // KV blocks per step
 
@@ -631,29 +632,39 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
         }
         lsum = lsum * alpha + psum;
     };
-    auto pv = [&](const u32x4 (&P)[4], int slot, int st) {
-        // wave-uniform, last step of a sequence only: V slots at or past seq_len may hold anything
-        // and are zeroed (their P is 0, but 0*NaN is NaN)
-        const bool vmask = st * 64 + 64 > seq_len;
+    auto pv = [&](const u32x4 (&P)[4], int slot) {
+        const u32x4 *vp = &ldsV[slot][h * HD + col];
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-            u32x4 vop[MB];
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb) vop[mb] = ldsV[slot][q4 * CH + h * HD + 32 * mb + col];
-            if (vmask) {
-                const int t0 = st * 64 + 8 * h + 16 * q4;   // tokens t0 .. t0+7 in this lane's V operand
-                u32x4 mk;
-#pragma unroll
-                for (int w = 0; w < 4; ++w)
-                    mk[w] = (t0 + 2 * w < seq_len ? 0x0000FFFFu : 0u) | (t0 + 2 * w + 1 < seq_len ? 0xFFFF0000u : 0u);
-#pragma unroll
-                for (int mb = 0; mb < MB; ++mb) vop[mb] &= mk;
-            }
-#pragma unroll
-            for (int mb = 0; mb < MB; ++mb)
-                O[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vop[mb]),
-                                                            __builtin_bit_cast(bf16x8, P[q4]), O[mb], 0, 0, 0);
+        for (int i = 0; i < 4 * MB; ++i) {
+            const u32x4 vop = vp[(i / MB) * CH + 32 * (i % MB)];
+            O[i % MB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vop),
+                                                            __builtin_bit_cast(bf16x8, P[i / MB]), O[i % MB], 0, 0, 0);
         }
+        // every operand is requested kAhead MFMAs before the MFMA that uses it
+        constexpr int kAhead = 4;
+        __builtin_amdgcn_sched_group_barrier(0x100, kAhead, 0);
+#pragma unroll
+        for (int i = 0; i < 4 * MB - kAhead; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, kAhead, 0);
+    };
+    // Last step of a sequence only (workgroup-uniform): V slots at or past seq_len may hold anything; their
+    // weights are 0, but 0*NaN is NaN, so they are zeroed in LDS before anybody multiplies with them.
+    auto scrub_v = [&](int slot, int st) {
+#pragma unroll
+        for (int n = 0; n < NCP; ++n) {
+            const int cidx = n * kPfThreads + tid;           // chunk [block][token half][dim] of the stage
+            const int blk = cidx / CH, half = (cidx % CH) / HD;
+            const int t0 = st * 64 + 16 * blk + 8 * half;    // tokens t0 .. t0+7
+            u32x4 mk;
+#pragma unroll
+            for (int w = 0; w < 4; ++w)
+                mk[w] = (t0 + 2 * w < seq_len ? 0x0000FFFFu : 0u) | (t0 + 2 * w + 1 < seq_len ? 0xFFFF0000u : 0u);
+            ldsV[slot][cidx] &= mk;
+        }
+        __syncthreads();
     };
 
     int ids1[kPfBlocks], ids2[kPfBlocks];   // block ids of the steps st+1 and st+2
@@ -677,6 +688,7 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
         __syncthreads();
         if (st + 2 < nstep) issue(false, st & 1, ids2);
         if (st + 1 < nstep) issue(true, (st + 1) & 1, ids1);
+        if (st * 64 + 64 > seq_len) scrub_v(st & 1, st);
 #pragma unroll
         for (int b = 0; b < kPfBlocks; ++b) {
             ids1[b] = ids2[b];
@@ -718,7 +730,7 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
 #pragma unroll
                 for (int r = 0; r < 16; ++r) O[mb][r] *= alpha;
         }
-        pv(P, st & 1, st);
+        pv(P, st & 1);
     };
 
     f32x16 SA[2], SB[2];
