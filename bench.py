@@ -417,18 +417,24 @@ def main():
     # the launch stream (inside the library), so that the event overhead stays out of `value`
     ctx.set_option("profile", 1)
     prof = {"prefill_ms": 0.0, "decode_ms": 0.0, "calls": 0}
+    per_call = []
     done = 0
     while done < a.steps:
         n = min(512, a.steps - done)
         for i in range(n):
             step(done + i)
-        r = ctx.profile_read()
+        r = ctx.profile_read_calls()
         for k in prof:
             prof[k] += r[k]
+        per_call.append(r["per_call"])
         done += n
     ctx.set_option("profile", 0)
     kern = {k: prof[k] / max(prof["calls"], 1) for k in ("prefill_ms", "decode_ms")}
     kern["per_launch_events"] = dict(kern)
+    pc = np.concatenate(per_call) if per_call else np.zeros((0, 2))
+    if len(pc):      # spread of the per-launch event times: p10 / median / p90
+        kern["prefill_ms_p10_p50_p90"] = [float(x) for x in np.percentile(pc[:, 0], [10, 50, 90])]
+        kern["decode_ms_p10_p50_p90"] = [float(x) for x in np.percentile(pc[:, 1], [10, 50, 90])]
     if work["prefill_chunks"] == 0:
         kern["decode_ms"] = min(kern["decode_ms"], region_ms_per_step)
     elif work["decode_seqs"] == 0:

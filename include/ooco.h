@@ -130,6 +130,12 @@ ooco_status ooco_set_option(ooco_ctx *ctx, const char *name, int64_t value);
  * and the number of calls (HOST).  Either pointer may be NULL.  Resets the sums. */
 ooco_status ooco_profile_read(ooco_ctx *ctx, double *ms_sum /*HOST*/, int64_t *calls /*HOST*/);
 
+/* The same, and also the event-to-event times of every call: per_call_ms is a HOST double
+ * [cap][2] = (prefill kernel ms, decode kernel ms) for the first cap calls since the last read
+ * (may be NULL with cap 0). */
+ooco_status ooco_profile_read_calls(ooco_ctx *ctx, double *per_call_ms /*HOST*/, int64_t cap,
+                                    double *ms_sum /*HOST double[2]*/, int64_t *calls /*HOST*/);
+
 /* Wave-level trace of the decode kernel, for tuning.  With option "trace" = 1 every decode wave of
  * the following ooco_attn_mixed calls stores four device time stamps (constant 100 MHz clock):
  * wave start, first K/V tiles arrived, end of KV streaming, wave end (after partial results and

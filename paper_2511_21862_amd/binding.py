@@ -19,7 +19,7 @@ _STATUS_NAMES = {0: "OOCO_OK", -1: "OOCO_EINVAL", -2: "OOCO_ESHAPE", -3: "OOCO_E
                  -5: "OOCO_ENOTIMPL"}
 
 EXPORTS = ["ooco_ctx_create", "ooco_ctx_destroy", "ooco_last_error", "ooco_set_option", "ooco_plan",
-           "ooco_plan_dry_run", "ooco_plan_info", "ooco_profile_read", "ooco_trace_read", "ooco_attn_mixed", "ooco_kv_block_copy", "ooco_kv_append", "ooco_predict_latency", "ooco_mix_decoding_select"]
+           "ooco_plan_dry_run", "ooco_plan_info", "ooco_profile_read", "ooco_profile_read_calls", "ooco_trace_read", "ooco_attn_mixed", "ooco_kv_block_copy", "ooco_kv_append", "ooco_predict_latency", "ooco_mix_decoding_select"]
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2511_21862_amd.build` "
@@ -45,6 +45,8 @@ _lib.ooco_plan_info.restype = ctypes.c_int
 _lib.ooco_plan_info.argtypes = [_P] + [ctypes.POINTER(ctypes.c_int64)] * 4
 _lib.ooco_profile_read.restype = ctypes.c_int
 _lib.ooco_profile_read.argtypes = [_P, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
+_lib.ooco_profile_read_calls.restype = ctypes.c_int
+_lib.ooco_profile_read_calls.argtypes = [_P, _P, ctypes.c_int64, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
 _lib.ooco_trace_read.restype = ctypes.c_int
 _lib.ooco_trace_read.argtypes = [_P, _P, ctypes.c_int64, ctypes.POINTER(ctypes.c_int64)]
 _lib.ooco_attn_mixed.restype = ctypes.c_int
@@ -185,6 +187,15 @@ def ooco_trace_read(ctx, cap_waves=1 << 16):
     return buf[: min(n.value, cap_waves)]
 
 
+def ooco_profile_read_calls(ctx, cap=1024) -> dict:
+    """Like ooco_profile_read, plus `per_call` = float64 [calls, 2] (prefill ms, decode ms) of every call."""
+    buf = np.zeros((cap, 2), dtype=np.float64)
+    ms = (ctypes.c_double * 2)()
+    n = ctypes.c_int64()
+    _check(ctx, _lib.ooco_profile_read_calls(ctx, buf.ctypes.data, cap, ms, ctypes.byref(n)))
+    return dict(prefill_ms=ms[0], decode_ms=ms[1], calls=n.value, per_call=buf[: min(n.value, cap)])
+
+
 def ooco_profile_read(ctx) -> dict:
     ms = (ctypes.c_double * 2)()
     n = ctypes.c_int64()
@@ -279,6 +290,9 @@ class Context:
 
     def plan_info(self):
         return ooco_plan_info(self.h)
+
+    def profile_read_calls(self, cap=1024):
+        return ooco_profile_read_calls(self.h, cap)
 
     def profile_read(self):
         return ooco_profile_read(self.h)

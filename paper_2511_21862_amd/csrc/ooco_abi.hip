@@ -366,9 +366,10 @@ ooco_status ooco_trace_read(ooco_ctx *ctx, uint64_t *stamps, int64_t cap_waves, 
     return OOCO_OK;
 }
 
-ooco_status ooco_profile_read(ooco_ctx *ctx, double *ms_sum, int64_t *calls)
+ooco_status ooco_profile_read_calls(ooco_ctx *ctx, double *per_call_ms, int64_t cap, double *ms_sum, int64_t *calls)
 {
     if (!ctx) return OOCO_EINVAL;
+    if (cap < 0 || (cap > 0 && !per_call_ms)) return fail(ctx, OOCO_EINVAL, "ooco_profile_read_calls: bad per-call buffer");
     double sum[2] = {0.0, 0.0};
     for (int64_t c = 0; c < ctx->prof_calls; ++c) {
         hipEvent_t *ev = ctx->prof_ev.data() + 3 * c;
@@ -377,6 +378,7 @@ ooco_status ooco_profile_read(ooco_ctx *ctx, double *ms_sum, int64_t *calls)
             float ms = 0.f;
             e = hipEventElapsedTime(&ms, ev[k], ev[k + 1]);
             sum[k] += ms;
+            if (c < cap) per_call_ms[2 * c + k] = ms;
         }
         if (e != hipSuccess) return fail(ctx, OOCO_EHIP, "ooco_profile_read: %s", hipGetErrorString(e));
     }
@@ -384,6 +386,11 @@ ooco_status ooco_profile_read(ooco_ctx *ctx, double *ms_sum, int64_t *calls)
     if (calls) *calls = ctx->prof_calls;
     ctx->prof_calls = 0;
     return OOCO_OK;
+}
+
+ooco_status ooco_profile_read(ooco_ctx *ctx, double *ms_sum, int64_t *calls)
+{
+    return ooco_profile_read_calls(ctx, nullptr, 0, ms_sum, calls);
 }
 
 const char *ooco_last_error(const ooco_ctx *ctx) { return ctx ? ctx->err : g_create_error; }
