@@ -100,6 +100,28 @@ def test_batch_above_inline_plan_limit_uses_device_plan():
     assert_parity(run_gpu(b), oracle(b), "1100 sequences")
 
 
+def test_extreme_shapes():
+    # one sequence at the maximum table length (every decode run holds a piece of it: 96-part merge), next to
+    # the smallest possible pieces of work
+    b = W.build_batch(Hq=8, Hkv=1, hd=128, q_lens=[1, 1, 2, 1], ctx_lens=[131071, 0, 0, 15], num_blocks=8200, seed=80,
+                      max_blocks_per_seq=8192)
+    say("case: 131072-token decode sequence + one-token sequences + two-row chunk")
+    assert_parity(run_gpu(b), oracle(b), "131072-token sequence")
+    # widest GQA group with the small head dim, chunks that start and end inside blocks, long prior context
+    b = W.build_batch(Hq=16, Hkv=1, hd=64, q_lens=[300, 1, 45], ctx_lens=[1003, 2500, 2], num_blocks=260, seed=81,
+                      poison=True)
+    say("case: group of 16, hd 64, ragged chunks on long context")
+    assert_parity(run_gpu(b), oracle(b), "g16 hd64 chunks")
+    # several thousand tiny sequences (device plan path, many waves with many pieces)
+    n = 3000
+    rng = np.random.default_rng(6)
+    ql = np.where(np.arange(n) % 211 == 0, 2, 1).astype(np.int32)
+    b = W.build_batch(Hq=8, Hkv=2, hd=128, q_lens=ql, ctx_lens=rng.integers(0, 33, size=n).astype(np.int32),
+                      num_blocks=9100, seed=82)
+    say("case: 3000 tiny sequences")
+    assert_parity(run_gpu(b), oracle(b), "3000 tiny sequences")
+
+
 def test_peaky_scores_give_order_one_outputs():
     # scores x8: softmax concentrates on few keys, outputs are O(1) and the relative gate bites
     b = W.build_batch(Hq=32, Hkv=8, hd=128, q_lens=[1, 1, 64], ctx_lens=[900, 3000, 500], num_blocks=300, seed=5,
