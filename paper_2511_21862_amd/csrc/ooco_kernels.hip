@@ -356,19 +356,39 @@ __global__ __launch_bounds__(64) void decode_kernel(const KernArgs a)
                                               __HIP_MEMORY_SCOPE_AGENT);
             prev = __builtin_amdgcn_readfirstlane(prev);
             if (prev == nparts - 1) {   // last piece of this (sequence, kv head): merge, in slot order
+                // The 16 lane columns hold only g heads, so 16/g (at most 4) groups of columns merge
+                // different parts side by side: column group pg takes the parts pg, pg + ngrp, ...
+                // (three at a time so that their memory round trips overlap); the groups' results
+                // are then folded into group 0 in a fixed order.  Which parts meet in which order
+                // depends only on the plan, never on which piece arrived last.
+                // (only for sequences cut into many parts: below that one group is as fast and loads less)
+                const int ngrp = nparts <= 2 * 3 ? 1 : (g <= 4 ? 4 : (g <= 8 ? 2 : 1));
+                const int pg = col / g, hc = col - pg * g;
+                const bool member = pg < ngrp;
+                const int hm = kvh * g + (member ? hc : 0);
                 float M = -INFINITY;
                 ltot = 0.f;
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) O[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
-                // parts are fetched three at a time so that their memory round trips overlap
+                auto fold = [&](float m2, float l2, const f32x4 (&o2)[NB]) {   // (M, ltot, O) <- merged with (m2, l2, o2)
+                    const float M_new = fmaxf(M, m2);
+                    const float w_old = fast_exp2(M - M_new), w_new = fast_exp2(m2 - M_new);
+                    M = M_new;
+                    ltot = ltot * w_old + l2 * w_new;
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) O[nb][r] = O[nb][r] * w_old + o2[nb][r] * w_new;
+                };
                 constexpr int MBATCH = 3;
-                for (int s0 = 0; s0 < nparts; s0 += MBATCH) {
+                const int per_grp = (nparts + ngrp - 1) / ngrp;
+                for (int k0 = 0; k0 < per_grp; k0 += MBATCH) {
                     f32x2 ml[MBATCH];
                     f32x2 t[MBATCH][NB][2];
 #pragma unroll
                     for (int b = 0; b < MBATCH; ++b) {
-                        const int sidx = min(s0 + b, nparts - 1);
-                        const int64_t row = (int64_t)(first_run + sidx + seq) * p.Hq + (col < g ? head : kvh * g);
+                        const int sidx = min((member ? pg : 0) + ngrp * (k0 + b), nparts - 1);
+                        const int64_t row = (int64_t)(first_run + sidx + seq) * p.Hq + hm;
                         ml[b] = load_dev2(p.part_ml + row * 2);
                         const float *ap = p.part_acc + row * HD + 4 * kq;
 #pragma unroll
@@ -379,20 +399,26 @@ __global__ __launch_bounds__(64) void decode_kernel(const KernArgs a)
                     }
 #pragma unroll
                     for (int b = 0; b < MBATCH; ++b) {
-                        if (s0 + b < nparts) {
-                            const float M_new = fmaxf(M, ml[b][0]);
-                            const float w_old = fast_exp2(M - M_new), w_new = fast_exp2(ml[b][0] - M_new);
-                            M = M_new;
-                            ltot = ltot * w_old + ml[b][1] * w_new;
+                        if (member && pg + ngrp * (k0 + b) < nparts) {
+                            f32x4 o2[NB];
 #pragma unroll
-                            for (int nb = 0; nb < NB; ++nb) {
-                                O[nb][0] = O[nb][0] * w_old + t[b][nb][0][0] * w_new;
-                                O[nb][1] = O[nb][1] * w_old + t[b][nb][0][1] * w_new;
-                                O[nb][2] = O[nb][2] * w_old + t[b][nb][1][0] * w_new;
-                                O[nb][3] = O[nb][3] * w_old + t[b][nb][1][1] * w_new;
-                            }
+                            for (int nb = 0; nb < NB; ++nb)
+                                o2[nb] = f32x4{t[b][nb][0][0], t[b][nb][0][1], t[b][nb][1][0], t[b][nb][1][1]};
+                            fold(ml[b][0], ml[b][1], o2);
                         }
                     }
+                }
+                // groups 1 .. ngrp-1 into group 0 (lane col < g reads lane col + j*g of its 16-lane row);
+                // a group that had no part carries (-inf, 0, 0) and changes nothing
+                for (int j = 1; j < ngrp && j < nparts; ++j) {
+                    const int src = (lane & ~15) | min(j * g + hc, 15);
+                    const float m2 = __shfl(M, src), l2 = __shfl(ltot, src);
+                    f32x4 o2[NB];
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) o2[nb][r] = __shfl(O[nb][r], src);
+                    if (pg == 0) fold(m2, l2, o2);
                 }
                 if (lane == 0)   // ready for the next call
                     __hip_atomic_store(p.counters + (int64_t)seq * p.Hkv + kvh, 0, __ATOMIC_RELAXED,
