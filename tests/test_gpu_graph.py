@@ -1,0 +1,46 @@
+"""ooco_attn_mixed under HIP graph capture: a planned call enqueues kernels and event fork/join only, so a
+serving loop can capture a run of layers once and replay it.  Every replay is checked against the eager
+result, with eager work and synchronisations between the replays."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2511_21862_amd import binding as B
+from paper_2511_21862_amd import workloads as W
+
+from gpu_util import device_meta, say
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("mixed", [False, True])
+def test_captured_calls_replay_to_the_eager_result(mixed):
+    ql = [1, 1, 96, 1, 1] if mixed else [1, 1, 1, 1, 1]
+    b = W.build_batch(Hq=32, Hkv=8, hd=128, q_lens=ql, ctx_lens=[3000, 129, 400, 64, 900], num_blocks=320, seed=91)
+    d = W.to_device(b)
+    bt, sl, qsl, cl = device_meta(b)
+    say(f"case: graph capture, {'mixed' if mixed else 'decode-only'} batch")
+    eager = torch.empty((b.total_q, b.Hq, b.hd), dtype=torch.bfloat16, device="cuda")
+    out = torch.zeros_like(eager)
+    with B.Context(b.Hq, b.Hkv, b.hd, b.BS, b.num_blocks, b.max_blocks_per_seq) as ctx:
+        ctx.plan(b.seq_lens, b.query_start_loc, b.ctx_lens)
+        ctx.attn_mixed(d.q, d.k_cache, d.v_cache, bt, sl, qsl, cl, eager)
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            ctx.attn_mixed(d.q, d.k_cache, d.v_cache, bt, sl, qsl, cl, out, side)     # warm-up on the capture stream
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                for _ in range(3):                                                    # three "layers"
+                    ctx.attn_mixed(d.q, d.k_cache, d.v_cache, bt, sl, qsl, cl, out, torch.cuda.current_stream())
+        for rep in range(4):
+            out.fill_(float("nan"))
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out.view(torch.int16), eager.view(torch.int16)), f"replay {rep} differs from the eager result"
+            # eager work of the same context between replays
+            ctx.attn_mixed(d.q, d.k_cache, d.v_cache, bt, sl, qsl, cl, out)
+            torch.cuda.synchronize()
+            assert torch.equal(out.view(torch.int16), eager.view(torch.int16))
