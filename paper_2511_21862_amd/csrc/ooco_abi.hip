@@ -32,6 +32,7 @@ struct PlanGeometry {
     int64_t segments_opt;   // static runs; 0 = automatic
     int64_t tail_pct;       // share of the decode line handed out dynamically, in percent
     int64_t tail_blocks;    // KV blocks per dynamically fetched run
+    int64_t pf_split_opt = 0;   // parts per prefill tile; 0 = automatic
     uint16_t xcd_cw[kXcds] = {};   // cumulative XCD weights of the static runs; zeros = equal runs
 };
 
@@ -45,6 +46,7 @@ struct HostPlan {
     int32_t dec_blocks = 0, static_blocks = 0, static_runs = 0, tail_runs = 0;
     uint16_t cw[kXcds] = {};     // XCD weights in force (RunLayout::cw)
     int32_t n_tiles = 0, total_q = 0, num_seqs = 0;
+    int32_t pf_split = 1;        // parts each prefill tile's keys are cut into
     int64_t slots = 0;           // partial-result slots the decode kernel may touch
 };
 
@@ -84,7 +86,7 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
         return bad(OOCO_ESHAPE, "ooco_plan: query_start_loc[0]=%d, expected 0", h_query_start_loc[0]);
     out.num_seqs = num_seqs;
     out.dcum.assign((size_t)num_seqs + 1, 0);
-    int64_t dec_blocks = 0, tiles = 0;
+    int64_t dec_blocks = 0, tiles = 0, tile_steps = 0;
     const int tile_rows = prefill_tile_rows(geo.Hq / geo.Hkv);
     for (int i = 0; i < num_seqs; ++i) {
         const int64_t ql = (int64_t)h_query_start_loc[i + 1] - h_query_start_loc[i];
@@ -99,7 +101,11 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
             return bad(OOCO_ESHAPE, "ooco_plan: sequence %d needs %lld blocks > max_blocks_per_seq %d", i,
                        (long long)nb, geo.max_blocks_per_seq);
         if (ql == 1) dec_blocks += nb;
-        if (ql > 1) tiles += (ql + tile_rows - 1) / tile_rows;
+        if (ql > 1) {
+            tiles += (ql + tile_rows - 1) / tile_rows;
+            for (int64_t t0 = 0; t0 < ql; t0 += tile_rows)      // 64-key steps of every tile
+                tile_steps += ((int64_t)h_ctx_lens[i] + std::min<int64_t>(ql, t0 + tile_rows) + 63) / 64;
+        }
         if (dec_blocks > 0x7FFFFFFF / 2 || tiles > 0x7FFFFFFF / 128)
             return bad(OOCO_ESHAPE, "ooco_plan: batch too large");
         out.dcum[(size_t)i + 1] = (int32_t)dec_blocks;
@@ -157,6 +163,36 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
             }
             runs = (runs + 1) / 2;
         }
+    }
+    // ---- prefill tiles cut along the context when there are too few of them to occupy the GPU
+    if (tiles > 0) {
+        const int64_t units = tiles * geo.Hkv;
+        int64_t split = 1;
+        if (units <= kPrefillSplitUnits) {
+            if (geo.pf_split_opt > 0)
+                split = std::min<int64_t>(geo.pf_split_opt, kMaxPrefillSplit);
+            else {
+                // Estimated time in microseconds with s parts per tile (fitted to measurements on MI355X):
+                // rounds of workgroups over the two slots per CU x steps per part x 1.3 us, plus the
+                // serial merge of s parts, 3 us each plus 1 us per 32 units (their partials share the
+                // memory system).  A split must win at least a tenth over the unsplit tile.
+                const double steps = (double)tile_steps / (double)tiles, slots = 2.0 * geo.num_cus;
+                auto est = [&](int64_t sp) {
+                    const double rounds = std::ceil((double)(units * sp) / slots);
+                    return rounds * (steps / (double)sp) * 1.3 + (sp > 1 ? (double)sp * (3.0 + (double)units / 32.0) : 0.0);
+                };
+                double best = est(1) * 0.9;
+                for (int64_t sp = 2; sp <= kMaxPrefillSplit && sp <= (int64_t)steps; ++sp)
+                    if (est(sp) < best) {
+                        best = est(sp);
+                        split = sp;
+                    }
+            }
+            const size_t part_bytes = (size_t)kPrefillCols * (geo.hd + 2) * sizeof(float);
+            const size_t left = geo.ws_bytes - std::min(geo.ws_bytes, ((size_t)out.slots * slot_bytes(geo) + 255) / 256 * 256);
+            while (split > 1 && (size_t)units * (size_t)split * part_bytes > left) --split;
+        }
+        out.pf_split = (int32_t)split;
     }
     return OOCO_OK;
 }
@@ -222,6 +258,8 @@ struct ooco_ctx {
     int64_t opt_nbi = 0;
     int64_t opt_trace = 0;
     int64_t opt_rotate = 1;
+    int64_t opt_pf_split = 0;
+    int32_t *pf_counters = nullptr;   // [kPrefillSplitUnits] arrival counters of split prefill tiles, zero between calls
     uint16_t xcd_cw[kXcds] = {};   // option "xcd_weights"
     int64_t opt_overlap = 1;
     hipStream_t side_stream = nullptr;   // default priority; carries the prefill kernel of mixed batches
@@ -310,6 +348,8 @@ ooco_status ooco_ctx_create(ooco_ctx **out, int num_q_heads, int num_kv_heads, i
     if (e == hipSuccess) e = hipMalloc((void **)&c->plan_d, kPlanInts * sizeof(int32_t));
     if (e == hipSuccess) e = hipMalloc((void **)&c->counters, kCounterInts * sizeof(int32_t));
     if (e == hipSuccess) e = hipMemset(c->counters, 0, kCounterInts * sizeof(int32_t));
+    if (e == hipSuccess) e = hipMalloc((void **)&c->pf_counters, kPrefillSplitUnits * sizeof(int32_t));
+    if (e == hipSuccess) e = hipMemset(c->pf_counters, 0, kPrefillSplitUnits * sizeof(int32_t));
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->upload_done, hipEventDisableTiming);
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->side_stream, hipStreamNonBlocking);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->fork_ev, hipEventDisableTiming);
@@ -323,6 +363,7 @@ ooco_status ooco_ctx_create(ooco_ctx **out, int num_q_heads, int num_kv_heads, i
         if (c->join_ev) (void)hipEventDestroy(c->join_ev);
         if (c->side_stream) (void)hipStreamDestroy(c->side_stream);
         if (c->counters) (void)hipFree(c->counters);
+        if (c->pf_counters) (void)hipFree(c->pf_counters);
         if (c->plan_d) (void)hipFree(c->plan_d);
         if (c->plan_h) (void)hipHostFree(c->plan_h);
         if (c->own_ws && c->ws) (void)hipFree(c->ws);
@@ -346,6 +387,7 @@ ooco_status ooco_ctx_destroy(ooco_ctx *ctx)
         if (x) (void)hipEventDestroy(x);
     if (ctx->trace_d) (void)hipFree(ctx->trace_d);
     if (ctx->counters) (void)hipFree(ctx->counters);
+    if (ctx->pf_counters) (void)hipFree(ctx->pf_counters);
     if (ctx->plan_d) (void)hipFree(ctx->plan_d);
     if (ctx->plan_h) (void)hipHostFree(ctx->plan_h);
     if (ctx->own_ws && ctx->ws) (void)hipFree(ctx->ws);
@@ -406,6 +448,8 @@ ooco_status ooco_set_option(ooco_ctx *ctx, const char *name, int64_t value)
         ctx->opt_tail_pct = value;
     else if (!strcmp(name, "decode_tail_blocks"))
         ctx->opt_tail_blocks = value;
+    else if (!strcmp(name, "prefill_split"))
+        ctx->opt_pf_split = value;
     else if (!strcmp(name, "trace")) {
         if (value && !ctx->trace_d) {
             hipError_t e = hipMalloc((void **)&ctx->trace_d, kTraceWaves * 4 * sizeof(uint64_t));
@@ -462,6 +506,7 @@ ooco_status ooco_plan(ooco_ctx *ctx, int num_seqs, const int32_t *h_seq_lens, co
     geo.segments_opt = ctx->opt_segments;
     geo.tail_pct = ctx->opt_tail_pct;
     geo.tail_blocks = ctx->opt_tail_blocks;
+    geo.pf_split_opt = ctx->opt_pf_split;
     for (int k = 0; k < kXcds; ++k) geo.xcd_cw[k] = ctx->xcd_cw[k];
     ooco_status st = build_plan(geo, num_seqs, h_seq_lens, h_query_start_loc, h_ctx_lens, ctx->plan, ctx->err);
     if (st != OOCO_OK) return st;
@@ -548,7 +593,13 @@ ooco_status ooco_plan_info(const ooco_ctx *ctx, int64_t *decode_waves, int64_t *
     if (decode_waves) *decode_waves = ctx->plan.static_runs;
     if (prefill_tiles) *prefill_tiles = ctx->plan.n_tiles;
     if (decode_blocks) *decode_blocks = ctx->plan.dec_blocks;
-    if (workspace_used) *workspace_used = (int64_t)((size_t)ctx->plan.slots * (size_t)ctx->Hq * (ctx->hd + 2) * sizeof(float));
+    if (workspace_used) {
+        size_t bytes = (size_t)ctx->plan.slots * (size_t)ctx->Hq * (ctx->hd + 2) * sizeof(float);
+        if (ctx->plan.pf_split > 1)
+            bytes = (bytes + 255) / 256 * 256 + (size_t)ctx->plan.n_tiles * ctx->Hkv * (size_t)ctx->plan.pf_split *
+                                                    kPrefillCols * (ctx->hd + 2) * sizeof(float);
+        *workspace_used = (int64_t)bytes;
+    }
     return OOCO_OK;
 }
 
@@ -613,6 +664,14 @@ ooco_status ooco_attn_mixed(ooco_ctx *ctx, const void *q, const void *k_cache, c
     p.part_acc = static_cast<float *>(ctx->ws);
     p.part_ml = p.part_acc + (size_t)pl.slots * ctx->Hq * ctx->hd;
     p.counters = ctx->counters;
+    {
+        const size_t dec_floats = ((size_t)pl.slots * ctx->Hq * (ctx->hd + 2) + 63) / 64 * 64;   // 256-byte aligned
+        const size_t parts = (size_t)pl.n_tiles * ctx->Hkv * (size_t)pl.pf_split;
+        p.pf_acc = static_cast<float *>(ctx->ws) + dec_floats;
+        p.pf_ml = p.pf_acc + parts * kPrefillCols * ctx->hd;
+        p.pf_counters = ctx->pf_counters;
+        p.pf_split = pl.pf_split;
+    }
     const bool tracing = ctx->opt_trace && ctx->trace_d && (size_t)pl.static_runs * ctx->Hkv <= kTraceWaves;
     p.trace = tracing ? ctx->trace_d : nullptr;
     if (tracing) ctx->trace_waves = (int64_t)pl.static_runs * ctx->Hkv;

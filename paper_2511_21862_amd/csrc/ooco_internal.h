@@ -17,6 +17,9 @@
 //             tiles (tile_rows = 128 / (Hq/Hkv) rows each, all heads of a GQA group) before
 //             chunk k of that list, cum[P+1+k] = its sequence index; one workgroup per
 //             (tile, kv head), heavy tiles first.
+//             When a batch has too few tiles to occupy the GPU, each (tile, kv head) is cut along
+//             its keys into pf_split parts (one workgroup each) whose partial results are merged
+//             by the part that finishes last, as for decode.
 // The cumulative array travels inside the kernel arguments (no upload, no synchronisation) when
 // the batch has at most kInlineSeqs sequences, else through a device buffer.
 #pragma once
@@ -28,7 +31,9 @@ namespace ooco {
 
 constexpr int kBlockSize = 16;      // tokens per KV block (fixed by the cache layout)
 constexpr int kPrefillCols = 128;   // (row, head) query columns per prefill workgroup
-constexpr int kInlineSeqs = 960;    // sequences whose cumulative array fits the kernel arguments
+constexpr int kInlineSeqs = 960;
+constexpr int kMaxPrefillSplit = 8; // parts a prefill tile's keys may be cut into
+constexpr int kPrefillSplitUnits = 8192;   // (tile, kv head) pairs up to which the split is available    // sequences whose cumulative array fits the kernel arguments
 
 struct AttnParams {
     const uint16_t *q;
@@ -56,6 +61,12 @@ struct AttnParams {
     uint16_t xcd_cw[8];         // cumulative XCD weights of the static runs (RunLayout::cw); zeros = equal runs
     uint32_t queue_base;        // ticket value at which this launch's tail runs start
     uint32_t *queue;            // ticket counter for the tail runs (monotonic across launches)
+    // prefill tiles split along the context (pf_split > 1): part j of unit u = (tile, kv head) writes
+    // pf_acc[(u*pf_split + j)][128 columns][hd] and pf_ml[..][128][2]; pf_counters[u] counts arrivals
+    float *pf_acc;
+    float *pf_ml;
+    int32_t *pf_counters;
+    int32_t pf_split;
 };
 
 struct KernArgs {

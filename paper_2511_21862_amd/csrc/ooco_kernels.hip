@@ -62,6 +62,45 @@ OOCO_DEV void store_dev2(float *ptr, float a, float b)   // ptr is 8-byte aligne
     __hip_atomic_store(reinterpret_cast<uint64_t *>(ptr), __builtin_bit_cast(uint64_t, v), __ATOMIC_RELAXED,
                        __HIP_MEMORY_SCOPE_AGENT);
 }
+// The same cache policy for a 16-byte store (a plain vector store with the device-scope bit: the ordering
+// against the arrival counter comes from s_waitcnt, 16-byte atomicity is not needed).  Far fewer memory
+// operations than 8-byte atomic stores, which matters for the 64 KiB partial results of a prefill part.
+// (The s_nop covers the wait states a wide store needs before its data registers may be overwritten, which
+// the compiler cannot see through the asm.)
+OOCO_DEV void store_dev4(float *ptr, f32x4 v)   // ptr is 16-byte aligned
+{
+    asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" ::"v"(ptr), "v"(v) : "memory");
+}
+// Device-scope 16-byte loads of one part of a split prefill tile as one lane sees it: four loads (1 KiB apart)
+// from each of MB pointers.  All loads and the wait for them sit in ONE asm statement, so that the compiler
+// never sees a register it believes loaded while the data is still on its way.
+#define OOCO_LD4(o, a) \
+    "global_load_dwordx4 %" #o ", %" #a ", off sc1\n\t"
+#define OOCO_LD4O(o, a, off) \
+    "global_load_dwordx4 %" #o ", %" #a ", off offset:" #off " sc1\n\t"
+OOCO_DEV void load_dev_part(f32x4 (&t)[16], const float *p0, const float *p1, const float *p2, const float *p3)
+{
+    asm volatile(OOCO_LD4(0, 16) OOCO_LD4O(1, 16, 1024) OOCO_LD4O(2, 16, 2048) OOCO_LD4O(3, 16, 3072)
+                 OOCO_LD4(4, 17) OOCO_LD4O(5, 17, 1024) OOCO_LD4O(6, 17, 2048) OOCO_LD4O(7, 17, 3072)
+                 OOCO_LD4(8, 18) OOCO_LD4O(9, 18, 1024) OOCO_LD4O(10, 18, 2048) OOCO_LD4O(11, 18, 3072)
+                 OOCO_LD4(12, 19) OOCO_LD4O(13, 19, 1024) OOCO_LD4O(14, 19, 2048) OOCO_LD4O(15, 19, 3072)
+                 "s_waitcnt vmcnt(0)"
+                 : "=&v"(t[0]), "=&v"(t[1]), "=&v"(t[2]), "=&v"(t[3]), "=&v"(t[4]), "=&v"(t[5]), "=&v"(t[6]), "=&v"(t[7]),
+                   "=&v"(t[8]), "=&v"(t[9]), "=&v"(t[10]), "=&v"(t[11]), "=&v"(t[12]), "=&v"(t[13]), "=&v"(t[14]), "=&v"(t[15])
+                 : "v"(p0), "v"(p1), "v"(p2), "v"(p3)
+                 : "memory");
+}
+OOCO_DEV void load_dev_part(f32x4 (&t)[8], const float *p0, const float *p1)
+{
+    asm volatile(OOCO_LD4(0, 8) OOCO_LD4O(1, 8, 1024) OOCO_LD4O(2, 8, 2048) OOCO_LD4O(3, 8, 3072)
+                 OOCO_LD4(4, 9) OOCO_LD4O(5, 9, 1024) OOCO_LD4O(6, 9, 2048) OOCO_LD4O(7, 9, 3072)
+                 "s_waitcnt vmcnt(0)"
+                 : "=&v"(t[0]), "=&v"(t[1]), "=&v"(t[2]), "=&v"(t[3]), "=&v"(t[4]), "=&v"(t[5]), "=&v"(t[6]), "=&v"(t[7])
+                 : "v"(p0), "v"(p1)
+                 : "memory");
+}
+#undef OOCO_LD4
+#undef OOCO_LD4O
 OOCO_DEV f32x2 load_dev2(const float *ptr)
 {
     const uint64_t u = __hip_atomic_load(reinterpret_cast<uint64_t *>(const_cast<float *>(ptr)), __ATOMIC_RELAXED,
@@ -341,10 +380,7 @@ __global__ __launch_bounds__(64) void decode_kernel(const KernArgs a)
                 const int64_t row = (int64_t)(run + seq) * p.Hq + head;
                 float *ap = p.part_acc + row * HD + 4 * kq;
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
-                    store_dev2(ap + nb * 16, O[nb][0], O[nb][1]);
-                    store_dev2(ap + nb * 16 + 2, O[nb][2], O[nb][3]);
-                }
+                for (int nb = 0; nb < NB; ++nb) store_dev4(ap + nb * 16, O[nb]);
                 if (kq == 0) store_dev2(p.part_ml + row * 2, m, ltot);
             }
             const int first_run = run_of(L, cs);
@@ -497,8 +533,12 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
     const int col = lane & 31;
     const int h = lane >> 5;
     const int g = p.g;
-    const int tile_idx = blockIdx.x / p.Hkv;
-    const int kvh = blockIdx.x - tile_idx * p.Hkv;
+    // workgroup -> (unit = (tile, kv head), part of the unit's keys)
+    const int split = p.pf_split;
+    const int unit = blockIdx.x / split;
+    const int part = blockIdx.x - unit * split;
+    const int tile_idx = unit / p.Hkv;
+    const int kvh = unit - tile_idx * p.Hkv;
 
     // tile -> (sequence, tile of the sequence); tiles of a sequence are taken last-first because
     // the later rows of a chunk see more keys and the hardware dispatches in index order
@@ -543,7 +583,12 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
     const int w_pos_lo = pos0 + w_row_lo, w_pos_hi = pos0 + w_row_hi;
     const int kv_end = pos0 + rows;                      // keys visible to the tile: [0, kv_end)
     const int nblk = (kv_end + kBlockSize - 1) / kBlockSize;
-    const int nstep = (nblk + kPfBlocks - 1) / kPfBlocks;
+    const int nstep_all = (nblk + kPfBlocks - 1) / kPfBlocks;
+    // this workgroup's share of the steps: [st_lo, nstep); a unit with fewer steps than parts has fewer parts
+    const int nparts = min(split, nstep_all);
+    if (part >= nparts) return;                          // (the whole workgroup leaves: no barrier is pending)
+    const int st_lo = nstep_all * part / nparts;
+    const int nstep = nstep_all * (part + 1) / nparts;
 
     u32x4 qb[KS];
     {
@@ -640,7 +685,9 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
             swap32(mloc, x, y);
             mloc = fmaxf(x, y) * c_log2e;
         }
-        const float m_new = fmaxf(m, mloc);
+        // (floored: a part of a split tile may start with steps that a column does not see at all; its maximum
+        // then stays at the floor, its weights and sum at 0, instead of running into inf - inf)
+        const float m_new = fmaxf(fmaxf(m, mloc), -1e30f);
         alpha = fast_exp2(m - m_new);
         grow = m_new > m;
         m = m_new;
@@ -698,13 +745,13 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
         int ids0[kPfBlocks];
 #pragma unroll
         for (int b = 0; b < kPfBlocks; ++b) {
-            ids0[b] = block_id(b);
-            ids1[b] = block_id(kPfBlocks + b);
-            ids2[b] = block_id(2 * kPfBlocks + b);
+            ids0[b] = block_id(kPfBlocks * st_lo + b);
+            ids1[b] = block_id(kPfBlocks * (st_lo + 1) + b);
+            ids2[b] = block_id(kPfBlocks * (st_lo + 2) + b);
         }
-        issue(false, 0, ids0);
-        issue(true, 0, ids0);
-        if (nstep > 1) issue(false, 1, ids1);
+        issue(false, st_lo & 1, ids0);
+        issue(true, st_lo & 1, ids0);
+        if (st_lo + 1 < nstep) issue(false, (st_lo + 1) & 1, ids1);
     }
     // One step.  Sc: scores of step st (computed during step st-1), Sn: receives those of step st+1.
     auto body = [&](f32x16 (&Sc)[2], f32x16 (&Sn)[2], int st) {
@@ -762,8 +809,8 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
     f32x16 SA[2], SB[2];
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    qk(SA, 0);
-    for (int st = 0; st < nstep; st += 2) {
+    qk(SA, st_lo & 1);
+    for (int st = st_lo; st < nstep; st += 2) {
         body(SA, SB, st);
         if (st + 1 < nstep) body(SB, SA, st + 1);
     }
@@ -772,6 +819,60 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
         float x, y;
         swap32(lsum, x, y);
         ltot = x + y;
+    }
+    if (nparts > 1) {
+        // ---- partial result of this part, arrival count, merge by the part that arrives last (same
+        // device-scope accesses as the decode kernel).  Lane (col, h) of wave w owns column c = 32w + col,
+        // dims 32mb + 8q4 + 4h + 0..3.  m is the same in both lane halves; ltot already sums them.
+        const int64_t pbase = (int64_t)unit * split;
+        // layout of a part: [wave][mb][q4][lane][4 floats], so that every store and load instruction of a wave
+        // covers 1 KiB of contiguous memory
+        auto part_ptr = [&](int64_t j, int mb) -> float * {
+            return p.pf_acc + ((((pbase + j) * 4 + wave) * MB + mb) * 4 * 64 + lane) * 4;
+        };
+        {
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4)
+                    store_dev4(part_ptr(part, mb) + q4 * 256,
+                               f32x4{O[mb][4 * q4], O[mb][4 * q4 + 1], O[mb][4 * q4 + 2], O[mb][4 * q4 + 3]});
+            if (h == 0) store_dev2(p.pf_ml + ((pbase + part) * kPrefillCols + c) * 2, m, ltot);
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's partial has reached memory ...
+        __syncthreads();                                    // ... and so have the other waves'
+        __shared__ int arrived;
+        if (tid == 0)
+            arrived = __hip_atomic_fetch_add(p.pf_counters + unit, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        if (arrived != nparts - 1) return;
+        float M = -INFINITY;
+        ltot = 0.f;
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) O[mb][r] = 0.f;
+        for (int j = 0; j < nparts; ++j) {                  // in part order: the result does not depend on who is last
+            const f32x2 ml = load_dev2(p.pf_ml + ((pbase + j) * kPrefillCols + c) * 2);
+            f32x4 t[4 * MB];   // t[4*mb + q4] = this lane's dims 32mb + 8q4 + 4h + 0..3 of part j
+            if constexpr (MB == 4)
+                load_dev_part(t, part_ptr(j, 0), part_ptr(j, 1), part_ptr(j, 2), part_ptr(j, 3));
+            else
+                load_dev_part(t, part_ptr(j, 0), part_ptr(j, 1));
+            const float M_new = fmaxf(M, ml[0]);
+            const float w_old = fast_exp2(M - M_new), w_new = fast_exp2(ml[0] - M_new);
+            M = M_new;
+            ltot = ltot * w_old + ml[1] * w_new;
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) O[mb][4 * q4 + r] = O[mb][4 * q4 + r] * w_old + t[4 * mb + q4][r] * w_new;
+                }
+        }
+        if (tid == 0)   // ready for the next call
+            __hip_atomic_store(p.pf_counters + unit, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     if (c_valid) {
         const float inv = 1.0f / ltot;
@@ -919,7 +1020,7 @@ hipError_t launch_decode(const KernArgs &a, hipStream_t s)
 hipError_t launch_prefill(const KernArgs &a, hipStream_t s)
 {
     if (a.p.n_tiles <= 0) return hipSuccess;
-    const dim3 grid((unsigned)((int64_t)a.p.n_tiles * a.p.Hkv)), block(kPfThreads);
+    const dim3 grid((unsigned)((int64_t)a.p.n_tiles * a.p.Hkv * (a.p.pf_split > 0 ? a.p.pf_split : 1))), block(kPfThreads);
     if (a.p.hd == 128)
         hipLaunchKernelGGL((prefill_kernel<128>), grid, block, 0, s, a);
     else

@@ -77,6 +77,25 @@ def test_xcd_weighted_decode_runs_agree(Hkv, segments, tail_pct):
     assert_parity(run_gpu(b, options=opts), oracle(b), f"xcd weights Hkv={Hkv} segments={segments}")
 
 
+@pytest.mark.parametrize("split", [0, 2, 3, 8])
+def test_prefill_tiles_split_along_the_context_agree(split):
+    # each (tile, kv head) cut into `split` parts along its keys, partial results merged by the last part
+    # (0 = the planner's own choice, which splits here: few tiles, long context)
+    say(f"case: prefill_split {split}")
+    b = W.build_batch(Hq=8, Hkv=2, hd=128, q_lens=[2, 31, 33, 65, 1, 200], ctx_lens=[0, 5, 100, 47, 300, 1500],
+                      num_blocks=200, seed=83, poison=True)
+    assert_parity(run_gpu(b, options={"prefill_split": split}), oracle(b), f"split {split}, ragged chunks")
+    # MHA, small head dim: the 32 columns of a wave are 32 different rows, so a part can start beyond what
+    # some of them see
+    b = W.build_batch(Hq=4, Hkv=4, hd=64, q_lens=[100, 40], ctx_lens=[700, 3], num_blocks=80, seed=84, poison=True)
+    assert_parity(run_gpu(b, options={"prefill_split": split}), oracle(b), f"split {split}, MHA hd 64")
+    # twice on one context (counters are back at zero), bit-identical
+    with B.Context(b.Hq, b.Hkv, b.hd, b.BS, b.num_blocks, b.max_blocks_per_seq) as ctx:
+        first = run_gpu(b, ctx=ctx, options={"prefill_split": split})
+        again = run_gpu(b, ctx=ctx)
+        assert np.array_equal(first, again)
+
+
 def test_repeated_calls_reuse_counters_and_workspace():
     b = W.build_batch(Hq=8, Hkv=2, hd=128, q_lens=[1, 1, 1], ctx_lens=[700, 90, 300], num_blocks=80, seed=78)
     ref = oracle(b)
