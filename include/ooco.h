@@ -111,6 +111,13 @@ const char *ooco_last_error(const ooco_ctx *ctx);
  *                         and the number of static runs is rounded down to a multiple of 8.
  *                         0 (default) = equal runs.  Weights must differ by at most 4x; they
  *                         apply only when the static runs average at least 16 KV blocks.
+ * Prefill tiles (takes effect at the next ooco_plan):
+ *   "prefill_split"       parts a prefill tile's key range is cut into, 1..8 (more is taken as 8); every part is a
+ *                         workgroup of its own and the last one to finish merges their partial
+ *                         results (held in the workspace).  0 (default) = automatic: split only
+ *                         when the batch has too few tiles to occupy the compute units and an
+ *                         estimate of the kernel time improves by at least 7 %.  A tile
+ *                         never gets more parts than it has 64-key steps.
  * Immediate options:
  *   "overlap"    0/1 (default 1): in a batch that holds both prefill chunks and decode sequences,
  *                run the prefill kernel on the context's own side stream (default priority)
@@ -168,11 +175,13 @@ ooco_status ooco_plan(ooco_ctx *ctx, int num_seqs, const int32_t *h_seq_lens /*H
  *     -1 when the piece covers the whole sequence and writes the output directly
  *   prefill_tiles_out: HOST int32 [prefill_cap][5] = (seq, q_row0, rows, pos0, seq_len); a tile
  *     holds up to 128 / (num_q_heads/num_kv_heads) query rows and runs once per kv head
- *   counts: HOST int64 [5] = (decode pieces, prefill tiles, static decode runs, partial-result
- *     slots, dynamically fetched tail runs); runs are numbered static first, then tail
+ *   counts: HOST int64 [6] = (decode pieces, prefill tiles, static decode runs, partial-result
+ *     slots, dynamically fetched tail runs, parts each prefill tile's key range is cut into);
+ *     runs are numbered static first, then tail
  *   msg: HOST buffer of msg_cap bytes receiving the error text.  Any output pointer may be NULL.
  *   xcd_weights: NULL for equal static runs, else the relative run lengths per XCD that option
- *     "xcd_weights" would set (static run v then belongs to XCD v % 8). */
+ *     "xcd_weights" would set (static run v then belongs to XCD v % 8).
+ *   prefill_split: what option "prefill_split" would set (0 = automatic). */
 ooco_status ooco_plan_dry_run(int num_q_heads, int num_kv_heads, int head_dim, int block_size,
                               int max_blocks_per_seq, int num_cus, size_t workspace_bytes,
                               int64_t decode_segments, int64_t decode_tail_pct, int64_t decode_tail_blocks,
@@ -181,12 +190,14 @@ ooco_status ooco_plan_dry_run(int num_q_heads, int num_kv_heads, int head_dim, i
                               int32_t *decode_pieces_out /*HOST*/, int64_t decode_cap,
                               int32_t *prefill_tiles_out /*HOST*/, int64_t prefill_cap,
                               int64_t *counts /*HOST*/, char *msg /*HOST*/, size_t msg_cap,
-                              const int32_t *xcd_weights /*HOST, 8 values in 1..255, or NULL*/);
+                              const int32_t *xcd_weights /*HOST, 8 values in 1..255, or NULL*/,
+                              int64_t prefill_split);
 
 /* Numbers describing the current plan (any pointer may be NULL): decode runs (waves per kv head),
- * prefill tiles, KV blocks of all decode sequences, bytes of workspace the partial results use. */
+ * prefill tiles, KV blocks of all decode sequences, bytes of workspace the partial results use,
+ * parts each prefill tile's key range is cut into (1 = not split). */
 ooco_status ooco_plan_info(const ooco_ctx *ctx, int64_t *decode_waves, int64_t *prefill_tiles,
-                           int64_t *decode_blocks, int64_t *workspace_used);
+                           int64_t *decode_blocks, int64_t *workspace_used, int64_t *prefill_parts);
 
 /* The mixed-batch attention step (operation defined at the top of this file).
  *   q, out: DEVICE bf16 [total_q_tokens][Hq][hd]; k_cache, v_cache: DEVICE, read-only here;

@@ -40,9 +40,9 @@ _lib.ooco_plan.restype = ctypes.c_int
 _lib.ooco_plan.argtypes = [_P, ctypes.c_int, _P, _P, _P]
 _lib.ooco_plan_dry_run.restype = ctypes.c_int
 _lib.ooco_plan_dry_run.argtypes = ([ctypes.c_int] * 6 + [ctypes.c_size_t] + [ctypes.c_int64] * 3 + [ctypes.c_int, _P, _P, _P]
-                                   + [_P, ctypes.c_int64, _P, ctypes.c_int64, _P, ctypes.c_char_p, ctypes.c_size_t, _P])
+                                   + [_P, ctypes.c_int64, _P, ctypes.c_int64, _P, ctypes.c_char_p, ctypes.c_size_t, _P, ctypes.c_int64])
 _lib.ooco_plan_info.restype = ctypes.c_int
-_lib.ooco_plan_info.argtypes = [_P] + [ctypes.POINTER(ctypes.c_int64)] * 4
+_lib.ooco_plan_info.argtypes = [_P] + [ctypes.POINTER(ctypes.c_int64)] * 5
 _lib.ooco_profile_read.restype = ctypes.c_int
 _lib.ooco_profile_read.argtypes = [_P, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
 _lib.ooco_profile_read_calls.restype = ctypes.c_int
@@ -144,13 +144,13 @@ def ooco_plan(ctx, num_seqs, h_seq_lens, h_query_start_loc, h_ctx_lens) -> None:
 
 def ooco_plan_dry_run(num_q_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, num_cus, workspace_bytes,
                       h_seq_lens, h_query_start_loc, h_ctx_lens, decode_segments=0, decode_tail_pct=0,
-                      decode_tail_blocks=8, num_seqs=None, xcd_weights=None) -> dict:
+                      decode_tail_blocks=8, num_seqs=None, xcd_weights=None, prefill_split=0) -> dict:
     """Host-only planner run; returns the work the kernels derive from the plan as numpy arrays."""
     a, pa = _host_i32(h_seq_lens)
     b, pb = _host_i32(h_query_start_loc)
     c, pc = _host_i32(h_ctx_lens)
     n = len(a) if num_seqs is None else num_seqs
-    counts = np.zeros(5, dtype=np.int64)
+    counts = np.zeros(6, dtype=np.int64)
     msg = ctypes.create_string_buffer(512)
     xw, pxw = _host_i32(xcd_weights) if xcd_weights is not None else (None, 0)
 
@@ -158,7 +158,7 @@ def ooco_plan_dry_run(num_q_heads, num_kv_heads, head_dim, block_size, max_block
         return _lib.ooco_plan_dry_run(num_q_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, num_cus,
                                       workspace_bytes, decode_segments, decode_tail_pct, decode_tail_blocks, n, pa, pb, pc,
                                       dptr, dcap, pptr, pcap,
-                                      counts.ctypes.data, msg, 512, pxw)
+                                      counts.ctypes.data, msg, 512, pxw, prefill_split)
 
     st = call(0, 0, 0, 0)
     if st != OOCO_OK:
@@ -169,14 +169,14 @@ def ooco_plan_dry_run(num_q_heads, num_kv_heads, head_dim, block_size, max_block
     if st != OOCO_OK:
         raise OocoError(st, msg.value.decode())
     return dict(decode_pieces=d, prefill_tiles=p, decode_runs=int(counts[2]), slots=int(counts[3]),
-                tail_runs=int(counts[4]))
+                tail_runs=int(counts[4]), prefill_parts=int(counts[5]))
 
 
 def ooco_plan_info(ctx) -> dict:
-    v = [ctypes.c_int64() for _ in range(4)]
+    v = [ctypes.c_int64() for _ in range(5)]
     _check(ctx, _lib.ooco_plan_info(ctx, *[ctypes.byref(x) for x in v]))
     return dict(decode_waves=v[0].value, prefill_tiles=v[1].value, decode_blocks=v[2].value,
-                workspace_used=v[3].value)
+                workspace_used=v[3].value, prefill_parts=v[4].value)
 
 
 def ooco_trace_read(ctx, cap_waves=1 << 16):

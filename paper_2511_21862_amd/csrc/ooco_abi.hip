@@ -86,7 +86,7 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
         return bad(OOCO_ESHAPE, "ooco_plan: query_start_loc[0]=%d, expected 0", h_query_start_loc[0]);
     out.num_seqs = num_seqs;
     out.dcum.assign((size_t)num_seqs + 1, 0);
-    int64_t dec_blocks = 0, tiles = 0, tile_steps = 0;
+    int64_t dec_blocks = 0, tiles = 0, tile_steps = 0, max_tile_steps = 1;
     const int tile_rows = prefill_tile_rows(geo.Hq / geo.Hkv);
     for (int i = 0; i < num_seqs; ++i) {
         const int64_t ql = (int64_t)h_query_start_loc[i + 1] - h_query_start_loc[i];
@@ -103,8 +103,11 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
         if (ql == 1) dec_blocks += nb;
         if (ql > 1) {
             tiles += (ql + tile_rows - 1) / tile_rows;
-            for (int64_t t0 = 0; t0 < ql; t0 += tile_rows)      // 64-key steps of every tile
-                tile_steps += ((int64_t)h_ctx_lens[i] + std::min<int64_t>(ql, t0 + tile_rows) + 63) / 64;
+            for (int64_t t0 = 0; t0 < ql; t0 += tile_rows) {    // 64-key steps of every tile
+                const int64_t nstep = ((int64_t)h_ctx_lens[i] + std::min<int64_t>(ql, t0 + tile_rows) + 63) / 64;
+                tile_steps += nstep;
+                max_tile_steps = std::max(max_tile_steps, nstep);
+            }
         }
         if (dec_blocks > 0x7FFFFFFF / 2 || tiles > 0x7FFFFFFF / 128)
             return bad(OOCO_ESHAPE, "ooco_plan: batch too large");
@@ -170,18 +173,24 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
         int64_t split = 1;
         if (units <= kPrefillSplitUnits) {
             if (geo.pf_split_opt > 0)
-                split = std::min<int64_t>(geo.pf_split_opt, kMaxPrefillSplit);
+                split = std::min<int64_t>(std::min<int64_t>(geo.pf_split_opt, kMaxPrefillSplit), max_tile_steps);
             else {
-                // Estimated time in microseconds with s parts per tile (fitted to measurements on MI355X):
-                // rounds of workgroups over the two slots per CU x steps per part x 1.3 us, plus the
-                // serial merge of s parts, 3 us each plus 1 us per 32 units (their partials share the
-                // memory system).  A split must win at least a tenth over the unsplit tile.
-                const double steps = (double)tile_steps / (double)tiles, slots = 2.0 * geo.num_cus;
+                // Estimated time in microseconds with sp parts per tile, from measurements on MI355X.  A compute
+                // unit finishes a 64-key step of one workgroup in about 1.2 us whether one or two workgroups
+                // share it, so what counts is how many workgroups each unit gets: W = units x sp workgroups
+                // take W / CUs rounds (a started round counted half), a launch that just fills the units
+                // spreads unevenly (up to 1.4 us per step), and the last workgroup of a tile merges the sp
+                // partial results one after the other, slower when many tiles do so at once.  A split must
+                // win 7 % over the unsplit tile.
+                const double steps = (double)tile_steps / (double)tiles, cus = (double)geo.num_cus;
                 auto est = [&](int64_t sp) {
-                    const double rounds = std::ceil((double)(units * sp) / slots);
-                    return rounds * (steps / (double)sp) * 1.3 + (sp > 1 ? (double)sp * (3.0 + (double)units / 32.0) : 0.0);
+                    const double w = (double)(units * sp), r = w / cus;
+                    const double rounds = w <= cus ? 1.0 : 0.5 * (r + std::ceil(r));
+                    const double t_step = w <= cus ? 1.2 + 0.2 * std::max(0.0, 2.0 * r - 1.0) : 1.2;
+                    const double merge = sp > 1 ? 2.0 + (double)sp * (1.2 + (double)units / 64.0) : 0.0;
+                    return rounds * (steps / (double)sp) * t_step + merge;
                 };
-                double best = est(1) * 0.9;
+                double best = est(1) * 0.93;
                 for (int64_t sp = 2; sp <= kMaxPrefillSplit && sp <= (int64_t)steps; ++sp)
                     if (est(sp) < best) {
                         best = est(sp);
@@ -524,14 +533,14 @@ ooco_status ooco_plan_dry_run(int num_q_heads, int num_kv_heads, int head_dim, i
                               const int32_t *h_seq_lens, const int32_t *h_query_start_loc, const int32_t *h_ctx_lens,
                               int32_t *decode_pieces_out, int64_t decode_cap, int32_t *prefill_tiles_out,
                               int64_t prefill_cap, int64_t *counts, char *msg, size_t msg_cap,
-                              const int32_t *xcd_weights)
+                              const int32_t *xcd_weights, int64_t prefill_split)
 {
     char err[512] = "";
     ooco_status st = OOCO_OK;
     HostPlan pl;
     if (num_q_heads <= 0 || num_kv_heads <= 0 || num_q_heads % num_kv_heads || (head_dim != 64 && head_dim != 128) ||
         block_size != kBlockSize || max_blocks_per_seq <= 0 || num_cus <= 0 || decode_segments < 0 ||
-        decode_tail_pct < 0 || decode_tail_blocks < 0) {
+        decode_tail_pct < 0 || decode_tail_blocks < 0 || prefill_split < 0) {
         snprintf(err, sizeof err, "ooco_plan_dry_run: bad geometry");
         st = OOCO_ESHAPE;
     } else {
@@ -546,6 +555,7 @@ ooco_status ooco_plan_dry_run(int num_q_heads, int num_kv_heads, int head_dim, i
         geo.segments_opt = decode_segments;
         geo.tail_pct = decode_tail_pct;
         geo.tail_blocks = decode_tail_blocks;
+        geo.pf_split_opt = prefill_split;
         if (xcd_weights && !xcd_weights_to_cw(xcd_weights, geo.xcd_cw)) {
             snprintf(err, sizeof err, "ooco_plan_dry_run: xcd_weights needs eight values in 1..255 that differ by at most 4x");
             st = OOCO_EINVAL;
@@ -562,6 +572,7 @@ ooco_status ooco_plan_dry_run(int num_q_heads, int num_kv_heads, int head_dim, i
         counts[2] = pl.static_runs;
         counts[3] = pl.slots;
         counts[4] = pl.tail_runs;
+        counts[5] = pl.pf_split;
     }
     if (decode_pieces_out)
         for (int64_t i = 0; i < std::min<int64_t>(decode_cap, (int64_t)pieces.size()); ++i) {
@@ -586,7 +597,7 @@ ooco_status ooco_plan_dry_run(int num_q_heads, int num_kv_heads, int head_dim, i
 }
 
 ooco_status ooco_plan_info(const ooco_ctx *ctx, int64_t *decode_waves, int64_t *prefill_tiles, int64_t *decode_blocks,
-                           int64_t *workspace_used)
+                           int64_t *workspace_used, int64_t *prefill_parts)
 {
     if (!ctx) return OOCO_EINVAL;
     if (!ctx->plan_valid) return fail(ctx, OOCO_EINVAL, "ooco_plan_info: no current plan");
@@ -600,6 +611,7 @@ ooco_status ooco_plan_info(const ooco_ctx *ctx, int64_t *decode_waves, int64_t *
                                                     kPrefillCols * (ctx->hd + 2) * sizeof(float);
         *workspace_used = (int64_t)bytes;
     }
+    if (prefill_parts) *prefill_parts = ctx->plan.n_tiles > 0 ? ctx->plan.pf_split : 1;
     return OOCO_OK;
 }
 

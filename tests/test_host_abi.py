@@ -177,6 +177,29 @@ def test_small_workspace_reduces_the_number_of_runs():
     assert (tiny["decode_pieces"][:, 3] == -1).all()
 
 
+def prefill_parts(n, c, prior, **kw):
+    return dry([prior + c] * n, [i * c for i in range(n + 1)], [prior] * n, **kw)["prefill_parts"]
+
+
+def test_prefill_tiles_are_split_only_when_the_batch_cannot_occupy_the_gpu():
+    # the benchmark configurations' prefill parts and other batches with a workgroup or more per CU stay whole
+    for n, c, prior in ((2, 2048, 4096), (8, 512, 1024), (1, 2048, 8192), (4, 512, 2048), (1, 2048, 0)):
+        assert prefill_parts(n, c, prior) == 1, (n, c, prior)
+    # a few tiles walking a long context alone are cut up; fewer parts the more tiles there are
+    p1, p4, p8 = (prefill_parts(n, 128, 8192) for n in (1, 4, 8))
+    assert 8 >= p1 > p4 >= p8 >= 1 and p4 >= 2
+    # no context to cut: one 64-key step per part at least
+    assert prefill_parts(1, 128, 0) == 1
+    assert prefill_parts(1, 32, 100, prefill_split=8) <= 3
+    # forced values are honoured up to 8; the workspace bounds the parts (66,560 bytes each here)
+    assert prefill_parts(1, 128, 8192, prefill_split=3) == 3
+    assert prefill_parts(1, 128, 8192, prefill_split=50) == 8
+    assert prefill_parts(1, 128, 8192, prefill_split=8, workspace_bytes=32 * 5 * 66560) == 5
+    assert prefill_parts(1, 128, 8192, workspace_bytes=0) == 1
+    # decode-only batches report 1
+    assert dry([100, 200], [0, 1, 2], [99, 199])["prefill_parts"] == 1
+
+
 def test_empty_batch_plans_to_nothing():
     plan = dry(np.zeros(0, np.int32), np.zeros(1, np.int32), np.zeros(0, np.int32), num_seqs=0)
     assert len(plan["decode_pieces"]) == 0 and len(plan["prefill_tiles"]) == 0
