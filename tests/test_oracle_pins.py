@@ -518,3 +518,109 @@ def test_mix_selection_invariants_by_exhaustive_scan():
                 if L(b + [off[i] for i in rest[:m]]) <= S:
                     best = m
         assert [i for i in sel if i not in looked] == sorted(rest[:best])
+
+
+# ---------------------------------------------------------------- migration decision and eviction rule
+from oracle import migration  # noqa: E402
+
+
+def golden_lines(name, tag):
+    path = os.path.join(os.path.dirname(__file__), "golden", name)
+    return [l.split() for l in open(path) if l.startswith(tag + " ")]
+
+
+def test_migration_hand_worked_examples():
+    B = [100, 200]
+    prefs = golden_lines("migration.txt", "pref")
+    assert len(prefs) == 8
+    for c in prefs:
+        S, inc, sat, cap, lo, hi = float(c[1]) * 1e-6, bool(int(c[2])), int(c[3]), int(c[4]), int(c[5]), int(c[6])
+        r = migration.migration_preference(MIXP, 32, 8, 128, S, B, inc, sat, 16, cap, lo, hi)
+        assert (r["branch"], -1 if r["pref"] is None else r["pref"]) == (c[8], int(c[9])), c
+    sels = golden_lines("migration.txt", "select")
+    assert len(sels) == 3
+    for c in sels:
+        lens = [int(x) for x in c[c.index(":") + 1:c.index("->")]]
+        want = [int(x) for x in c[c.index("->") + 1:]]
+        got = migration.migration_select(MIXP, 32, 8, 128, float(c[1]) * 1e-6, B, lens, int(c[2]), 16, 10 ** 6, int(c[3]))
+        assert got == want, c
+    evs = golden_lines("migration.txt", "evict")
+    assert len(evs) == 4
+    for c in evs:
+        lens = [int(x) for x in c[c.index(":") + 1:c.index("->")]]
+        want = [int(x) for x in c[c.index("->") + 1:]]
+        r = migration.eviction_victims(lens, int(c[1]), 16, int(c[2]), int(c[3]))
+        assert [int(r["enough"])] + r["victims"] == want, c
+
+
+def test_migration_preference_closed_forms_in_the_memory_bound_regime():
+    # k requests of length n0 cost 10 + k (n0 + 4) us; S is chosen off every tie
+    for k, n0, S_us, sat in ((4, 96, 1000.5, 4), (4, 96, 1000.5, 3), (4, 96, 1000.5, 9), (1, 500, 9000.5, 40),
+                             (6, 30, 400.5, 8), (3, 1000, 3100.5, 2)):
+        room = S_us - (10 + k * (n0 + 4))
+        r = migration.migration_preference(MIXP, 32, 8, 128, S_us * 1e-6, [n0] * k, True, sat, 16, 10 ** 9, 8, 3000)
+        if room <= 0:
+            assert r["pref"] is None
+        elif k >= sat:
+            want = min(3000, int(math.floor(room - 4)))
+            assert (r["pref"], r["branch"]) == ((want, "saturated") if want >= 8 else (None, "none"))
+        else:
+            n = sat - k
+            if n * (8 + 4) <= room:
+                assert (r["pref"], r["branch"]) == (min(3000, int(math.floor(room / n - 4))), "reach")
+            else:
+                assert (r["pref"], r["branch"]) == (8, "shortest")
+
+
+def test_migration_preference_is_the_maximum_by_direct_evaluation():
+    # compute-bound decode operators too (small F_ad): the preferred length fits, the next one does not
+    rng = np.random.default_rng(21)
+    p = dict(F_ap=9e14, F_ad=3e12, M_a=6e12, O_p=1e-5, O_d=9e-6)
+    L = lambda lens: mix_select.latency(p, 32, 8, 128, lens)
+    seen = set()
+    for trial in range(80):
+        B = [int(x) for x in rng.integers(16, 3000, size=rng.integers(1, 7))]
+        sat = int(rng.integers(1, 16))
+        S = L(B) * float(rng.uniform(0.9, 1.5) if trial % 2 else rng.uniform(1.0, 2.5))
+        cap = int(rng.integers(50, 1500))
+        lo = 16 if trial % 3 else 1200
+        r = migration.migration_preference(p, 32, 8, 128, S, B, True, sat, 16, cap, lo, 2048)
+        seen.add(r["branch"])
+        n = max(1, sat - len(B))
+        if r["branch"] == "none":
+            ok = L(B) < S and len(B) >= sat
+            assert not ok or L(B + [lo]) > S or migration.u_mem(B + [lo], 16, cap) > 1
+        elif r["branch"] == "shortest":
+            assert r["pref"] == lo and L(B + [lo] * n) > S
+        else:
+            l = r["pref"]
+            mem = (lambda x: migration.u_mem(B + [x], 16, cap) <= 1) if r["branch"] == "saturated" else (lambda x: True)
+            assert L(B + [l] * n) <= S and mem(l)
+            assert l == 2048 or L(B + [l + 1] * n) > S or not mem(l + 1)
+    assert seen == {"none", "saturated", "reach", "shortest"}
+
+
+def test_eviction_victims_against_every_subset():
+    rng = np.random.default_rng(5)
+    for trial in range(80):
+        lens = [int(x) for x in rng.integers(1, 400, size=rng.integers(1, 9))]
+        blk = [migration.blocks(n, 16) for n in lens]
+        need = int(rng.integers(0, sum(blk) + 8))
+        for compute_bound in (False, True):
+            r = migration.eviction_victims(lens, need, 16, 10 if compute_bound else 3, 10)
+            v = r["victims"]
+            assert r["compute_bound"] == compute_bound and len(set(v)) == len(v)
+            assert r["enough"] == (sum(blk) >= need)
+            if not r["enough"]:
+                assert sorted(v) == list(range(len(lens)))
+                continue
+            freed = sum(blk[i] for i in v)
+            assert freed >= need
+            assert all(freed - blk[i] < need for i in v)                      # nobody is evicted needlessly
+            order = sorted(range(len(lens)), key=lambda i: (-lens[i], i) if compute_bound else (lens[i], i))
+            k = next(k for k in range(len(lens) + 1) if sum(blk[i] for i in order[:k]) >= need)
+            assert set(v) <= set(order[:k])                                   # only from the preferred end
+            if compute_bound:                                                 # fewest victims of all feasible subsets
+                best = min(bin(m).count("1") for m in range(1 << len(lens))
+                           if sum(blk[i] for i in range(len(lens)) if m >> i & 1) >= need)
+                assert len(v) == best
