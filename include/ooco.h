@@ -301,6 +301,55 @@ ooco_status ooco_mix_decoding_select(const ooco_model_params *params /*HOST*/, i
                                      const int32_t *h_random_order /*HOST*/, uint8_t *h_selected /*HOST*/,
                                      double *latency_out /*HOST*/, char *msg /*HOST*/, size_t msg_cap);
 
+/* Offline Request Migration Decision (paper Section 3.4.3, Algorithm 1), the latency-strict node's side:
+ * the request length it prefers to pull from a latency-relaxed node.  L is the predictor of
+ * ooco_mix_decoding_select; lengths on offer range over [len_min, len_max]; the cache holds
+ * capacity_blocks blocks of block_size tokens and a request of length n occupies ceil(n / block_size).
+ *   L(batch) >= slo_s, or all_included == 0 (the last mix decoding selection left a request of the
+ *     node out): no migration, *pref_out = -1, *branch_out = 0;
+ *   batch_size >= bs_sat (compute-saturated; fill the memory): the largest length whose request keeps
+ *     L <= slo_s and fits the cache (branch 1; none fits: -1, branch 0);
+ *   else, with n = bs_sat - batch_size requests missing to saturation: if n requests of len_min keep
+ *     L <= slo_s, the largest length such that n requests of that length do (branch 2; the cache
+ *     condition is stated for the saturated case only and applied only there), otherwise len_min,
+ *     to make the batch as large as possible (branch 3).
+ * Pure HOST function.  h_batch_lens [batch_size]: HOST int32, >= 1.  branch_out may be NULL.
+ * Errors: OOCO_EINVAL (NULL pointers, sizes out of range), OOCO_ESHAPE (a length below 1). */
+ooco_status ooco_migration_preference(const ooco_model_params *params /*HOST*/, int num_q_heads, int num_kv_heads,
+                                      int head_dim, int bytes_per_value, double slo_s, int batch_size,
+                                      const int32_t *h_batch_lens /*HOST*/, int all_included, int bs_sat,
+                                      int block_size, int64_t capacity_blocks, int32_t len_min, int32_t len_max,
+                                      int32_t *pref_out /*HOST*/, int32_t *branch_out /*HOST*/, char *msg /*HOST*/,
+                                      size_t msg_cap);
+
+/* The latency-relaxed node's side of the same algorithm: which of its ongoing offline requests
+ * (h_relaxed_lens [num_relaxed]) go to the strict node whose batch is h_batch_lens.  They are visited
+ * by ascending distance of their length from pref (ties: shorter first, then lower index); a request
+ * goes if the strict node's batch with it keeps L <= slo_s and fits its cache, otherwise it is passed
+ * over; at most max_migrate go.  h_chosen: HOST int32 [min(max_migrate, num_relaxed)], the indices in
+ * the order taken; *num_chosen their number.  Pure HOST function. */
+ooco_status ooco_migration_select(const ooco_model_params *params /*HOST*/, int num_q_heads, int num_kv_heads,
+                                  int head_dim, int bytes_per_value, double slo_s, int batch_size,
+                                  const int32_t *h_batch_lens /*HOST*/, int num_relaxed,
+                                  const int32_t *h_relaxed_lens /*HOST*/, int32_t pref, int block_size,
+                                  int64_t capacity_blocks, int max_migrate, int32_t *h_chosen /*HOST*/,
+                                  int32_t *num_chosen /*HOST*/, char *msg /*HOST*/, size_t msg_cap);
+
+/* Which offline requests a latency-strict node evicts to free need_blocks KV blocks for an online
+ * request arriving from its prefill (paper Section 3.4.1): when the node is compute-bound
+ * (batch_size >= bs_sat) long requests go first, so that the decode batch stays large; otherwise
+ * short ones go first, which keeps the recomputation small.  Requests are taken in that order (ties
+ * by index) until their blocks cover the need; then, in the order taken, a request whose blocks the
+ * others make unnecessary stays after all.  The blocks of the victims are what a caller hands to
+ * ooco_kv_block_copy.
+ *   h_victims: HOST int32 [num_offline], indices in the order taken; *num_victims their number;
+ *   *enough (may be NULL): 0 when all requests together do not cover the need (then all are listed).
+ * Pure HOST function. */
+ooco_status ooco_eviction_victims(int num_offline, const int32_t *h_offline_lens /*HOST*/, int64_t need_blocks,
+                                  int block_size, int batch_size, int bs_sat, int32_t *h_victims /*HOST*/,
+                                  int32_t *num_victims /*HOST*/, int32_t *enough /*HOST*/, char *msg /*HOST*/,
+                                  size_t msg_cap);
+
 #ifdef __cplusplus
 }
 #endif

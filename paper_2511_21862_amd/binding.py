@@ -19,7 +19,8 @@ _STATUS_NAMES = {0: "OOCO_OK", -1: "OOCO_EINVAL", -2: "OOCO_ESHAPE", -3: "OOCO_E
                  -5: "OOCO_ENOTIMPL"}
 
 EXPORTS = ["ooco_ctx_create", "ooco_ctx_destroy", "ooco_last_error", "ooco_set_option", "ooco_plan",
-           "ooco_plan_dry_run", "ooco_plan_info", "ooco_profile_read", "ooco_profile_read_calls", "ooco_trace_read", "ooco_attn_mixed", "ooco_kv_block_copy", "ooco_kv_append", "ooco_predict_latency", "ooco_mix_decoding_select"]
+           "ooco_plan_dry_run", "ooco_plan_info", "ooco_profile_read", "ooco_profile_read_calls", "ooco_trace_read", "ooco_attn_mixed", "ooco_kv_block_copy", "ooco_kv_append", "ooco_predict_latency", "ooco_mix_decoding_select",
+           "ooco_migration_preference", "ooco_migration_select", "ooco_eviction_victims"]
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2511_21862_amd.build` "
@@ -255,6 +256,72 @@ def ooco_mix_decoding_select(params, num_q_heads, num_kv_heads, head_dim, slo_s,
     if st != OOCO_OK:
         raise OocoError(st, msg.value.decode())
     return dict(selected=sel[: len(off)].astype(bool), latency=lat.value)
+
+
+_lib.ooco_migration_preference.restype = ctypes.c_int
+_lib.ooco_migration_preference.argtypes = ([ctypes.POINTER(ModelParams)] + [ctypes.c_int] * 4 + [ctypes.c_double, ctypes.c_int, _P]
+                                           + [ctypes.c_int] * 3 + [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, _P, _P,
+                                                                   ctypes.c_char_p, ctypes.c_size_t])
+_lib.ooco_migration_select.restype = ctypes.c_int
+_lib.ooco_migration_select.argtypes = ([ctypes.POINTER(ModelParams)] + [ctypes.c_int] * 4 + [ctypes.c_double, ctypes.c_int, _P,
+                                                                                            ctypes.c_int, _P, ctypes.c_int32,
+                                                                                            ctypes.c_int, ctypes.c_int64,
+                                                                                            ctypes.c_int, _P, _P,
+                                                                                            ctypes.c_char_p, ctypes.c_size_t])
+_lib.ooco_eviction_victims.restype = ctypes.c_int
+_lib.ooco_eviction_victims.argtypes = [ctypes.c_int, _P, ctypes.c_int64, ctypes.c_int, ctypes.c_int, ctypes.c_int, _P, _P, _P,
+                                       ctypes.c_char_p, ctypes.c_size_t]
+
+MIGRATION_BRANCHES = ("none", "saturated", "reach", "shortest")
+
+
+def _model_params(params):
+    return params if isinstance(params, ModelParams) else ModelParams(**{k: float(params[k]) for k, _ in ModelParams._fields_})
+
+
+def ooco_migration_preference(params, num_q_heads, num_kv_heads, head_dim, slo_s, batch_lens, all_included, bs_sat,
+                              block_size, capacity_blocks, len_min, len_max, bytes_per_value=2) -> dict:
+    """Returns dict(pref=length or None, branch=one of MIGRATION_BRANCHES)."""
+    p = _model_params(params)
+    b, pb = _host_i32(batch_lens)
+    pref, branch = ctypes.c_int32(), ctypes.c_int32()
+    msg = ctypes.create_string_buffer(256)
+    st = _lib.ooco_migration_preference(ctypes.byref(p), num_q_heads, num_kv_heads, head_dim, bytes_per_value, float(slo_s),
+                                        len(b), pb, int(bool(all_included)), bs_sat, block_size, capacity_blocks, len_min,
+                                        len_max, ctypes.addressof(pref), ctypes.addressof(branch), msg, 256)
+    if st != OOCO_OK:
+        raise OocoError(st, msg.value.decode())
+    return dict(pref=None if pref.value < 0 else pref.value, branch=MIGRATION_BRANCHES[branch.value])
+
+
+def ooco_migration_select(params, num_q_heads, num_kv_heads, head_dim, slo_s, batch_lens, relaxed_lens, pref, block_size,
+                          capacity_blocks, max_migrate, bytes_per_value=2) -> list:
+    """Indices into relaxed_lens of the requests to migrate, in the order taken."""
+    p = _model_params(params)
+    b, pb = _host_i32(batch_lens)
+    r, pr = _host_i32(relaxed_lens)
+    chosen = np.zeros(max(1, min(max_migrate, len(r))), dtype=np.int32)
+    n = ctypes.c_int32()
+    msg = ctypes.create_string_buffer(256)
+    st = _lib.ooco_migration_select(ctypes.byref(p), num_q_heads, num_kv_heads, head_dim, bytes_per_value, float(slo_s),
+                                    len(b), pb, len(r), pr, pref, block_size, capacity_blocks, max_migrate,
+                                    chosen.ctypes.data, ctypes.addressof(n), msg, 256)
+    if st != OOCO_OK:
+        raise OocoError(st, msg.value.decode())
+    return [int(x) for x in chosen[: n.value]]
+
+
+def ooco_eviction_victims(offline_lens, need_blocks, block_size, batch_size, bs_sat) -> dict:
+    """Returns dict(victims=[indices in the order taken], enough=bool)."""
+    o, po = _host_i32(offline_lens)
+    victims = np.zeros(max(1, len(o)), dtype=np.int32)
+    n, enough = ctypes.c_int32(), ctypes.c_int32()
+    msg = ctypes.create_string_buffer(256)
+    st = _lib.ooco_eviction_victims(len(o), po, need_blocks, block_size, batch_size, bs_sat, victims.ctypes.data,
+                                    ctypes.addressof(n), ctypes.addressof(enough), msg, 256)
+    if st != OOCO_OK:
+        raise OocoError(st, msg.value.decode())
+    return dict(victims=[int(x) for x in victims[: n.value]], enough=bool(enough.value))
 
 
 class Context:

@@ -1,10 +1,12 @@
 // Host-only part of libooco: the roofline latency model of the attention operator
 // (paper Section 3.3: operator model of Table 2, operator latency of Equation 1, iteration latency
-// = sum of operator latencies + static overhead).  No device code, no device state.
+// = sum of operator latencies + static overhead) and the scheduling rules that consume it (Algorithm 2,
+// Algorithm 1, the eviction rule of Section 3.4.1).  No device code, no device state.
 #include "ooco.h"
 
 #include <algorithm>
 #include <cstdio>
+#include <cstdlib>
 #include <numeric>
 #include <vector>
 
@@ -139,5 +141,180 @@ extern "C" ooco_status ooco_mix_decoding_select(const ooco_model_params *params,
         members += (int)lo;
     }
     if (latency_out) *latency_out = L(sum, members);
+    return OOCO_OK;
+}
+
+namespace {
+bool model_args_ok(const ooco_model_params *p, int Hq, int Hkv, int hd, int bpv)
+{
+    return p && p->F_ad > 0 && p->M_a > 0 && p->O_d >= 0 && Hq > 0 && Hkv > 0 && Hq % Hkv == 0 && hd > 0 && bpv > 0;
+}
+int64_t blocks_of(int64_t len, int block_size) { return (len + block_size - 1) / block_size; }
+}  // namespace
+
+// Offline Request Migration Decision (paper Algorithm 1).  The batch's operator times are summed once; a
+// hypothetical group of n requests of length l adds n times the same operator time, accumulated one by one as a
+// from-scratch evaluation of the enlarged batch would; both L and the block count grow with l, so the largest
+// admissible length is found by bisection over [len_min, len_max].
+extern "C" ooco_status ooco_migration_preference(const ooco_model_params *params, int num_q_heads, int num_kv_heads,
+                                                 int head_dim, int bytes_per_value, double slo_s, int batch_size,
+                                                 const int32_t *h_batch_lens, int all_included, int bs_sat, int block_size,
+                                                 int64_t capacity_blocks, int32_t len_min, int32_t len_max,
+                                                 int32_t *pref_out, int32_t *branch_out, char *msg, size_t msg_cap)
+{
+    auto bad = [&](ooco_status code, const char *text) {
+        if (msg && msg_cap) snprintf(msg, msg_cap, "ooco_migration_preference: %s", text);
+        return code;
+    };
+    if (msg && msg_cap) msg[0] = 0;
+    if (!pref_out) return bad(OOCO_EINVAL, "NULL pref_out");
+    if (!model_args_ok(params, num_q_heads, num_kv_heads, head_dim, bytes_per_value))
+        return bad(OOCO_EINVAL, "bad model parameters or head geometry");
+    if (batch_size < 0 || (batch_size > 0 && !h_batch_lens) || bs_sat < 1 || block_size < 1 || capacity_blocks < 0 ||
+        len_min < 1 || len_max < len_min)
+        return bad(OOCO_EINVAL, "bad sizes (batch_size >= 0, bs_sat >= 1, block_size >= 1, 1 <= len_min <= len_max)");
+    const double D_h = (double)num_q_heads * head_dim, d = bytes_per_value, kv_ratio = (double)num_kv_heads / num_q_heads;
+    double base = 0.0;
+    int64_t used = 0;
+    for (int i = 0; i < batch_size; ++i) {
+        if (h_batch_lens[i] < 1) return bad(OOCO_ESHAPE, "request length below 1");
+        base += decode_op_time(*params, D_h, kv_ratio, d, (double)h_batch_lens[i]);
+        used += blocks_of(h_batch_lens[i], block_size);
+    }
+    auto L_with = [&](int32_t len, int n) {        // L(B + n requests of length len)
+        double s = base;
+        const double t = decode_op_time(*params, D_h, kv_ratio, d, (double)len);
+        for (int k = 0; k < n; ++k) s += t;
+        return batch_size + n > 0 ? s + params->O_d : 0.0;
+    };
+    auto largest = [&](int n, bool memory) -> int32_t {     // largest admissible length, or -1
+        auto fits = [&](int32_t len) {
+            return L_with(len, n) <= slo_s && (!memory || used + (int64_t)n * blocks_of(len, block_size) <= capacity_blocks);
+        };
+        if (!fits(len_min)) return -1;
+        int32_t lo = len_min, hi = len_max;
+        while (lo < hi) {
+            const int32_t mid = (int32_t)(((int64_t)lo + hi + 1) / 2);
+            if (fits(mid))
+                lo = mid;
+            else
+                hi = mid - 1;
+        }
+        return lo;
+    };
+    int32_t pref = -1, branch = 0;
+    if (L_with(len_min, 0) < slo_s && all_included) {
+        if (batch_size >= bs_sat) {
+            pref = largest(1, true);
+            branch = pref >= 0 ? 1 : 0;
+        } else {
+            const int n = bs_sat - batch_size;
+            pref = largest(n, false);
+            branch = 2;
+            if (pref < 0) {
+                pref = len_min;
+                branch = 3;
+            }
+        }
+    }
+    *pref_out = pref;
+    if (branch_out) *branch_out = branch;
+    return OOCO_OK;
+}
+
+// The latency-relaxed node's side of Algorithm 1: its ongoing offline requests nearest to the preferred length
+// first; a request goes if the strict node's batch with it keeps L <= S and fits the cache.
+extern "C" ooco_status ooco_migration_select(const ooco_model_params *params, int num_q_heads, int num_kv_heads,
+                                             int head_dim, int bytes_per_value, double slo_s, int batch_size,
+                                             const int32_t *h_batch_lens, int num_relaxed, const int32_t *h_relaxed_lens,
+                                             int32_t pref, int block_size, int64_t capacity_blocks, int max_migrate,
+                                             int32_t *h_chosen, int32_t *num_chosen, char *msg, size_t msg_cap)
+{
+    auto bad = [&](ooco_status code, const char *text) {
+        if (msg && msg_cap) snprintf(msg, msg_cap, "ooco_migration_select: %s", text);
+        return code;
+    };
+    if (msg && msg_cap) msg[0] = 0;
+    if (!num_chosen) return bad(OOCO_EINVAL, "NULL num_chosen");
+    *num_chosen = 0;
+    if (!model_args_ok(params, num_q_heads, num_kv_heads, head_dim, bytes_per_value))
+        return bad(OOCO_EINVAL, "bad model parameters or head geometry");
+    if (batch_size < 0 || (batch_size > 0 && !h_batch_lens) || num_relaxed < 0 || (num_relaxed > 0 && !h_relaxed_lens) ||
+        block_size < 1 || capacity_blocks < 0 || max_migrate < 0 || pref < 1 || (max_migrate > 0 && num_relaxed > 0 && !h_chosen))
+        return bad(OOCO_EINVAL, "bad sizes or NULL arrays (pref >= 1, block_size >= 1)");
+    const double D_h = (double)num_q_heads * head_dim, d = bytes_per_value, kv_ratio = (double)num_kv_heads / num_q_heads;
+    double sum = 0.0;
+    int64_t used = 0;
+    for (int i = 0; i < batch_size; ++i) {
+        if (h_batch_lens[i] < 1) return bad(OOCO_ESHAPE, "request length below 1");
+        sum += decode_op_time(*params, D_h, kv_ratio, d, (double)h_batch_lens[i]);
+        used += blocks_of(h_batch_lens[i], block_size);
+    }
+    for (int i = 0; i < num_relaxed; ++i)
+        if (h_relaxed_lens[i] < 1) return bad(OOCO_ESHAPE, "request length below 1");
+    std::vector<int32_t> order((size_t)num_relaxed);
+    std::iota(order.begin(), order.end(), 0);
+    auto dist = [&](int32_t i) { return std::abs((int64_t)h_relaxed_lens[i] - (int64_t)pref); };
+    std::sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
+        if (dist(a) != dist(b)) return dist(a) < dist(b);
+        if (h_relaxed_lens[a] != h_relaxed_lens[b]) return h_relaxed_lens[a] < h_relaxed_lens[b];
+        return a < b;
+    });
+    int taken = 0;
+    for (int32_t i : order) {
+        if (taken >= max_migrate) break;
+        const double with = sum + decode_op_time(*params, D_h, kv_ratio, d, (double)h_relaxed_lens[i]);
+        const int64_t blk = blocks_of(h_relaxed_lens[i], block_size);
+        if (with + params->O_d <= slo_s && used + blk <= capacity_blocks) {
+            sum = with;
+            used += blk;
+            h_chosen[taken++] = i;
+        }
+    }
+    *num_chosen = taken;
+    return OOCO_OK;
+}
+
+// Which offline requests leave a latency-strict node to free need_blocks KV blocks (paper Section 3.4.1):
+// long ones first when the node is compute-bound (batch_size >= bs_sat), short ones first otherwise; then, in
+// the order taken, whoever is not needed for the total any more stays.
+extern "C" ooco_status ooco_eviction_victims(int num_offline, const int32_t *h_offline_lens, int64_t need_blocks,
+                                             int block_size, int batch_size, int bs_sat, int32_t *h_victims,
+                                             int32_t *num_victims, int32_t *enough, char *msg, size_t msg_cap)
+{
+    auto bad = [&](ooco_status code, const char *text) {
+        if (msg && msg_cap) snprintf(msg, msg_cap, "ooco_eviction_victims: %s", text);
+        return code;
+    };
+    if (msg && msg_cap) msg[0] = 0;
+    if (!num_victims) return bad(OOCO_EINVAL, "NULL num_victims");
+    *num_victims = 0;
+    if (num_offline < 0 || (num_offline > 0 && (!h_offline_lens || !h_victims)) || need_blocks < 0 || block_size < 1 ||
+        batch_size < 0 || bs_sat < 1)
+        return bad(OOCO_EINVAL, "bad sizes or NULL arrays");
+    for (int i = 0; i < num_offline; ++i)
+        if (h_offline_lens[i] < 1) return bad(OOCO_ESHAPE, "request length below 1");
+    const bool compute_bound = batch_size >= bs_sat;
+    std::vector<int32_t> order((size_t)num_offline);
+    std::iota(order.begin(), order.end(), 0);
+    std::sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
+        if (h_offline_lens[a] != h_offline_lens[b])
+            return compute_bound ? h_offline_lens[a] > h_offline_lens[b] : h_offline_lens[a] < h_offline_lens[b];
+        return a < b;
+    });
+    int64_t freed = 0;
+    size_t k = 0;
+    while (k < order.size() && freed < need_blocks) freed += blocks_of(h_offline_lens[order[k++]], block_size);
+    const bool ok = freed >= need_blocks;
+    int n = 0;
+    for (size_t j = 0; j < k; ++j) {
+        const int64_t b = blocks_of(h_offline_lens[order[j]], block_size);
+        if (ok && freed - b >= need_blocks)
+            freed -= b;                      // not needed after all
+        else
+            h_victims[n++] = order[j];
+    }
+    *num_victims = n;
+    if (enough) *enough = ok ? 1 : 0;
     return OOCO_OK;
 }

@@ -1,5 +1,6 @@
-"""Mix Decoding Selection (Algorithm 2) against the hardware: a batch admitted under a TPOT bound by
-ooco_mix_decoding_select with the parameters fitted on MI355X is run through ooco_attn_mixed and timed."""
+"""The scheduling rules against the hardware: a batch admitted under a TPOT bound by ooco_mix_decoding_select
+(Algorithm 2), or enlarged by what ooco_migration_preference / ooco_migration_select pull in (Algorithm 1),
+with the parameters fitted on MI355X, is run through ooco_attn_mixed and timed."""
 import json
 import os
 
@@ -63,3 +64,36 @@ def test_admitted_batch_runs_within_the_bound(slo_us):
     say(f"  measured {t * 1e6:.1f} us per call ({t / S * 100:.0f} % of the bound, model error {(r['latency'] / t - 1) * 100:+.1f} %)")
     assert t <= 1.35 * S, "admitted batch overran the bound by more than the model's error margin"
     assert t >= 0.5 * S, "admitted batch leaves most of the bound unused"
+
+
+@pytest.mark.parametrize("bs_sat,label", [(32, "saturated"), (96, "reach")])
+def test_batch_after_migration_runs_within_the_bound(bs_sat, label):
+    fit = json.load(open(os.path.join(HERE, "..", "paper_2511_21862_amd", "model_params_mi355x.json")))
+    p = fit["table2_flops"]["params"]
+    rng = np.random.default_rng(bs_sat)
+    strict = np.clip(np.round(np.exp(np.log(1500) + 0.5 * rng.standard_normal(48))), 64, 8192).astype(np.int32)
+    relaxed = np.clip(np.round(np.exp(np.log(2048) + 0.8 * rng.standard_normal(400))), 64, 16384).astype(np.int32)
+    relaxed[:8] = rng.integers(20000, 60000, size=8)                      # a few long ones on offer
+    # saturated case: 2000 free KV blocks bound the preference; other case: the latency bound does
+    S, cap = 250e-6, (int(sum(-(-int(x) // 16) for x in strict)) + 2000 if label == "saturated" else 49152 - 1024)
+    d = B.ooco_migration_preference(p, 32, 8, 128, S, strict, True, bs_sat, 16, cap, 64, 65536)
+    assert d["branch"] == label and d["pref"] is not None
+    n = max(1, bs_sat - len(strict))
+    # the preferred length is the largest that fits: n requests of that length are predicted within the bound,
+    # n requests one token longer are not (or the cache is full, or the offer ends there)
+    with_pref = np.concatenate([strict, np.full(n, d["pref"], np.int32)])
+    L = lambda lens: B.ooco_predict_latency(p, 32, 8, 128, np.arange(len(lens) + 1), np.asarray(lens) - 1)["latency"]
+    assert L(with_pref) <= S
+    if d["pref"] < 65536:
+        longer = np.concatenate([strict, np.full(n, d["pref"] + 1, np.int32)])
+        assert L(longer) > S or (label == "saturated" and sum(-(-int(x) // 16) for x in longer) > cap)
+    chosen = B.ooco_migration_select(p, 32, 8, 128, S, strict, relaxed, d["pref"], 16, cap, 64)
+    batch = np.concatenate([strict, relaxed[chosen]])
+    say(f"case: {label}: preference {d['pref']} tokens, {len(chosen)} requests migrated "
+        f"(lengths {relaxed[chosen].min() if chosen else 0}..{relaxed[chosen].max() if chosen else 0}), "
+        f"batch {len(strict)} -> {len(batch)}, predicted {L(batch) * 1e6:.1f} us of {S * 1e6:.0f}")
+    assert chosen and L(batch) <= S
+    t0 = timed_decode(32, 8, 128, strict)
+    t = timed_decode(32, 8, 128, batch)
+    say(f"  measured {t0 * 1e6:.1f} us before, {t * 1e6:.1f} us after ({t / S * 100:.0f} % of the bound)")
+    assert t0 < S and t <= 1.35 * S

@@ -257,3 +257,75 @@ def test_mix_decoding_select_equals_the_oracle():
     assert list(got["selected"]) == [True, False, True, True, True, False] and got["latency"] == pytest.approx(594e-6, rel=1e-12)
     with pytest.raises(B.OocoError):
         B.ooco_mix_decoding_select(mp, 32, 8, 128, 1e-3, [0], [5], [])
+
+
+# ----------------------------------------------------------------------------- migration decision, eviction rule
+def test_migration_and_eviction_equal_the_oracle():
+    from oracle import migration, mix_select
+    rng = np.random.default_rng(31)
+    branches = set()
+    for trial in range(120):
+        p = dict(F_ap=9e14, F_ad=float(rng.choice([3e12, 2e14])), M_a=6e12, O_p=1e-5, O_d=9e-6)
+        Hkv = int(rng.choice([2, 4, 8]))
+        Hq = Hkv * int(rng.choice([1, 4, 7]))
+        Bl = [int(x) for x in rng.integers(1, 3000, size=rng.integers(0, 8))]
+        sat = int(rng.integers(1, 16))
+        S = max(mix_select.latency(p, Hq, Hkv, 128, Bl), 5e-6) * float(rng.uniform(0.9, 1.6) if trial % 2 else rng.uniform(1.0, 3.0))
+        cap = int(rng.integers(20, 1500))
+        lo = int(rng.choice([1, 16, 1200]))
+        hi = lo + int(rng.integers(0, 1500))
+        inc = bool(trial % 7)
+        want = migration.migration_preference(p, Hq, Hkv, 128, S, Bl, inc, sat, 16, cap, lo, hi)
+        got = B.ooco_migration_preference(p, Hq, Hkv, 128, S, Bl, inc, sat, 16, cap, lo, hi)
+        assert got == want, (trial, got, want)
+        branches.add(got["branch"])
+        rel = [int(x) for x in rng.integers(1, 4000, size=rng.integers(0, 20))]
+        if trial % 4 == 0 and rel:
+            rel = [rel[0]] * len(rel)                                  # ties in the order
+        pref = got["pref"] or int(rng.integers(1, 3000))
+        mm = int(rng.integers(0, 8))
+        assert (B.ooco_migration_select(p, Hq, Hkv, 128, S, Bl, rel, pref, 16, cap, mm)
+                == migration.migration_select(p, Hq, Hkv, 128, S, Bl, rel, pref, 16, cap, mm)), trial
+        need = int(rng.integers(0, 300))
+        bs = int(rng.integers(0, 20))
+        w = migration.eviction_victims(rel, need, 16, bs, sat)
+        g = B.ooco_eviction_victims(rel, need, 16, bs, sat)
+        assert g["victims"] == w["victims"] and g["enough"] == w["enough"], trial
+    assert branches == {"none", "saturated", "reach", "shortest"}
+
+
+def test_migration_golden_cases_through_the_library():
+    mp = dict(F_ap=1e18, F_ad=1e18, M_a=4.096e9, O_p=0.0, O_d=10e-6)
+    path = os.path.join(ROOT, "tests", "golden", "migration.txt")
+    rows = [l.split() for l in open(path) if l[:1].isalpha()]
+    assert len(rows) == 15
+    for c in rows:
+        if c[0] == "pref":
+            r = B.ooco_migration_preference(mp, 32, 8, 128, float(c[1]) * 1e-6, [100, 200], int(c[2]), int(c[3]), 16,
+                                            int(c[4]), int(c[5]), int(c[6]))
+            assert (r["branch"], -1 if r["pref"] is None else r["pref"]) == (c[8], int(c[9])), c
+            continue
+        lens = [int(x) for x in c[c.index(":") + 1:c.index("->")]]
+        want = [int(x) for x in c[c.index("->") + 1:]]
+        if c[0] == "select":
+            assert B.ooco_migration_select(mp, 32, 8, 128, float(c[1]) * 1e-6, [100, 200], lens, int(c[2]), 16, 10 ** 6,
+                                           int(c[3])) == want, c
+        else:
+            r = B.ooco_eviction_victims(lens, int(c[1]), 16, int(c[2]), int(c[3]))
+            assert [int(r["enough"])] + r["victims"] == want, c
+
+
+def test_migration_functions_reject_bad_arguments():
+    mp = dict(F_ap=1e18, F_ad=1e18, M_a=4.096e9, O_p=0.0, O_d=10e-6)
+    for kw in (dict(len_min=0), dict(len_min=10, len_max=9), dict(bs_sat=0), dict(block_size=0), dict(batch_lens=[5, 0])):
+        args = dict(batch_lens=[100], all_included=True, bs_sat=2, block_size=16, capacity_blocks=100, len_min=1, len_max=100)
+        args.update(kw)
+        with pytest.raises(B.OocoError) as e:
+            B.ooco_migration_preference(mp, 32, 8, 128, 1e-3, **args)
+        assert "ooco_migration_preference" in e.value.message
+    with pytest.raises(B.OocoError):
+        B.ooco_migration_select(mp, 32, 8, 128, 1e-3, [100], [50, -3], 60, 16, 100, 4)
+    with pytest.raises(B.OocoError):
+        B.ooco_eviction_victims([10, 0], 5, 16, 3, 8)
+    assert B.ooco_eviction_victims([], 5, 16, 3, 8) == dict(victims=[], enough=False)
+    assert B.ooco_eviction_victims([40], 0, 16, 3, 8) == dict(victims=[], enough=True)
