@@ -687,9 +687,13 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
         }
         // (floored: a part of a split tile may start with steps that a column does not see at all; its maximum
         // then stays at the floor, its weights and sum at 0, instead of running into inf - inf)
-        const float m_new = fmaxf(fmaxf(m, mloc), -1e30f);
+        // The reference point m only has to stay within 2^8 of the true running maximum (weights up to 256 are
+        // exact enough in bf16 and harmless in the fp32 sums; the final division cancels the reference), so it
+        // moves, and the accumulators are rescaled, only when a step's maximum exceeds it by more than 8.
+        const float m_cand = fmaxf(mloc, -1e30f);
+        grow = m_cand > m + 8.0f;
+        const float m_new = grow ? m_cand : m;
         alpha = fast_exp2(m - m_new);
-        grow = m_new > m;
         m = m_new;
         float psum = 0.f;
 #pragma unroll
