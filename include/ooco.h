@@ -20,6 +20,11 @@
  * nothing aborts or throws across this boundary.  Calls that launch GPU work are asynchronous
  * on the given HIP stream: inputs must stay alive and unmodified, and outputs must not be
  * read, until the stream has passed the work of the call.
+ * A context is not thread-safe, and the GPU work of two calls on one context must not overlap
+ * in time: they share the context's workspace (partial results) and arrival counters.  Calls
+ * issued to one stream are ordered by it; callers that drive several streams at once use one
+ * context per stream.  The host-only functions (ooco_plan_dry_run, ooco_predict_latency and the
+ * scheduling rules at the end of this file) keep no state and may be called from any thread.
  *
  * ---------------------------------------------------------------------------------------
  * Data layout (bf16 = upper 16 bits of IEEE binary32; all tensors contiguous)
