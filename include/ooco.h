@@ -116,6 +116,12 @@ const char *ooco_last_error(const ooco_ctx *ctx);
  *                         and the number of static runs is rounded down to a multiple of 8.
  *                         0 (default) = equal runs.  Weights must differ by at most 4x; they
  *                         apply only when the static runs average at least 16 KV blocks.
+ *   "decode_piece_pad"    what starting a piece is charged when the line is cut into runs, in KV
+ *                         blocks: a run that holds the beginnings of n sequences streams n times
+ *                         this many blocks less than a run that holds none, so that all waves
+ *                         finish together.  Default 3 * 128 / head_dim (a wave needs about 3 us
+ *                         from one piece to the first tile of the next); 0 = runs of equal
+ *                         block counts; at most 64.
  * Prefill tiles (takes effect at the next ooco_plan):
  *   "prefill_split"       parts a prefill tile's key range is cut into, 1..8 (more is taken as 8); every part is a
  *                         workgroup of its own and the last one to finish merges their partial
@@ -186,7 +192,8 @@ ooco_status ooco_plan(ooco_ctx *ctx, int num_seqs, const int32_t *h_seq_lens /*H
  *   msg: HOST buffer of msg_cap bytes receiving the error text.  Any output pointer may be NULL.
  *   xcd_weights: NULL for equal static runs, else the relative run lengths per XCD that option
  *     "xcd_weights" would set (static run v then belongs to XCD v % 8).
- *   prefill_split: what option "prefill_split" would set (0 = automatic). */
+ *   prefill_split: what option "prefill_split" would set (0 = automatic).
+ *   decode_piece_pad: what option "decode_piece_pad" would set; negative = the default. */
 ooco_status ooco_plan_dry_run(int num_q_heads, int num_kv_heads, int head_dim, int block_size,
                               int max_blocks_per_seq, int num_cus, size_t workspace_bytes,
                               int64_t decode_segments, int64_t decode_tail_pct, int64_t decode_tail_blocks,
@@ -196,7 +203,7 @@ ooco_status ooco_plan_dry_run(int num_q_heads, int num_kv_heads, int head_dim, i
                               int32_t *prefill_tiles_out /*HOST*/, int64_t prefill_cap,
                               int64_t *counts /*HOST*/, char *msg /*HOST*/, size_t msg_cap,
                               const int32_t *xcd_weights /*HOST, 8 values in 1..255, or NULL*/,
-                              int64_t prefill_split);
+                              int64_t prefill_split, int64_t decode_piece_pad);
 
 /* Numbers describing the current plan (any pointer may be NULL): decode runs (waves per kv head),
  * prefill tiles, KV blocks of all decode sequences, bytes of workspace the partial results use,

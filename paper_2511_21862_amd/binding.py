@@ -41,7 +41,7 @@ _lib.ooco_plan.restype = ctypes.c_int
 _lib.ooco_plan.argtypes = [_P, ctypes.c_int, _P, _P, _P]
 _lib.ooco_plan_dry_run.restype = ctypes.c_int
 _lib.ooco_plan_dry_run.argtypes = ([ctypes.c_int] * 6 + [ctypes.c_size_t] + [ctypes.c_int64] * 3 + [ctypes.c_int, _P, _P, _P]
-                                   + [_P, ctypes.c_int64, _P, ctypes.c_int64, _P, ctypes.c_char_p, ctypes.c_size_t, _P, ctypes.c_int64])
+                                   + [_P, ctypes.c_int64, _P, ctypes.c_int64, _P, ctypes.c_char_p, ctypes.c_size_t, _P, ctypes.c_int64, ctypes.c_int64])
 _lib.ooco_plan_info.restype = ctypes.c_int
 _lib.ooco_plan_info.argtypes = [_P] + [ctypes.POINTER(ctypes.c_int64)] * 5
 _lib.ooco_profile_read.restype = ctypes.c_int
@@ -145,7 +145,7 @@ def ooco_plan(ctx, num_seqs, h_seq_lens, h_query_start_loc, h_ctx_lens) -> None:
 
 def ooco_plan_dry_run(num_q_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, num_cus, workspace_bytes,
                       h_seq_lens, h_query_start_loc, h_ctx_lens, decode_segments=0, decode_tail_pct=0,
-                      decode_tail_blocks=8, num_seqs=None, xcd_weights=None, prefill_split=0) -> dict:
+                      decode_tail_blocks=8, num_seqs=None, xcd_weights=None, prefill_split=0, decode_piece_pad=-1) -> dict:
     """Host-only planner run; returns the work the kernels derive from the plan as numpy arrays."""
     a, pa = _host_i32(h_seq_lens)
     b, pb = _host_i32(h_query_start_loc)
@@ -159,7 +159,7 @@ def ooco_plan_dry_run(num_q_heads, num_kv_heads, head_dim, block_size, max_block
         return _lib.ooco_plan_dry_run(num_q_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, num_cus,
                                       workspace_bytes, decode_segments, decode_tail_pct, decode_tail_blocks, n, pa, pb, pc,
                                       dptr, dcap, pptr, pcap,
-                                      counts.ctypes.data, msg, 512, pxw, prefill_split)
+                                      counts.ctypes.data, msg, 512, pxw, prefill_split, decode_piece_pad)
 
     st = call(0, 0, 0, 0)
     if st != OOCO_OK:

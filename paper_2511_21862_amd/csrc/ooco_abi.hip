@@ -33,17 +33,20 @@ struct PlanGeometry {
     int64_t tail_pct;       // share of the decode line handed out dynamically, in percent
     int64_t tail_blocks;    // KV blocks per dynamically fetched run
     int64_t pf_split_opt = 0;   // parts per prefill tile; 0 = automatic
+    int64_t piece_pad = 0;      // line units charged for starting a piece (see build_plan)
     uint16_t xcd_cw[kXcds] = {};   // cumulative XCD weights of the static runs; zeros = equal runs
 };
 
 // The compact plan: two cumulative arrays and a few scalars (see ooco_internal.h).
 struct HostPlan {
-    std::vector<int32_t> dcum;   // [num_seqs+1] decode KV blocks before each sequence
+    std::vector<int32_t> dcum;   // [num_seqs+1] units of the decode line before each sequence (blocks + piece_pad per decode sequence)
     // prefill chunks, heaviest (most keys) first: pf[0..P] = query tiles before chunk k of that
     // order, pf[P+1+k] = sequence index of chunk k
     std::vector<int32_t> pf;
     int32_t num_pf = 0;
-    int32_t dec_blocks = 0, static_blocks = 0, static_runs = 0, tail_runs = 0;
+    int32_t dec_blocks = 0, static_blocks = 0, static_runs = 0, tail_runs = 0;   // in line units
+    int32_t piece_pad = 0;
+    int64_t kv_blocks = 0;       // KV blocks of all decode sequences
     uint16_t cw[kXcds] = {};     // XCD weights in force (RunLayout::cw)
     int32_t n_tiles = 0, total_q = 0, num_seqs = 0;
     int32_t pf_split = 1;        // parts each prefill tile's keys are cut into
@@ -86,7 +89,11 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
         return bad(OOCO_ESHAPE, "ooco_plan: query_start_loc[0]=%d, expected 0", h_query_start_loc[0]);
     out.num_seqs = num_seqs;
     out.dcum.assign((size_t)num_seqs + 1, 0);
-    int64_t dec_blocks = 0, tiles = 0, tile_steps = 0, max_tile_steps = 1;
+    // The decode line: every decode sequence contributes piece_pad units followed by one unit per KV block.  The
+    // runs cut the line into equal lengths, so a run that starts several pieces streams correspondingly fewer
+    // blocks (starting a piece costs a wave about as long as streaming three 8 KiB tiles).
+    int64_t dec_blocks = 0, kv_blocks = 0, tiles = 0, tile_steps = 0, max_tile_steps = 1;
+    const int64_t pad = geo.piece_pad;
     const int tile_rows = prefill_tile_rows(geo.Hq / geo.Hkv);
     for (int i = 0; i < num_seqs; ++i) {
         const int64_t ql = (int64_t)h_query_start_loc[i + 1] - h_query_start_loc[i];
@@ -100,7 +107,10 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
         if (nb > geo.max_blocks_per_seq)
             return bad(OOCO_ESHAPE, "ooco_plan: sequence %d needs %lld blocks > max_blocks_per_seq %d", i,
                        (long long)nb, geo.max_blocks_per_seq);
-        if (ql == 1) dec_blocks += nb;
+        if (ql == 1) {
+            dec_blocks += nb + pad;
+            kv_blocks += nb;
+        }
         if (ql > 1) {
             tiles += (ql + tile_rows - 1) / tile_rows;
             for (int64_t t0 = 0; t0 < ql; t0 += tile_rows) {    // 64-key steps of every tile
@@ -115,6 +125,8 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
     }
     out.total_q = num_seqs > 0 ? h_query_start_loc[num_seqs] : 0;
     out.dec_blocks = (int32_t)dec_blocks;
+    out.kv_blocks = kv_blocks;
+    out.piece_pad = (int32_t)pad;
     out.n_tiles = (int32_t)tiles;
     // prefill chunks in order of decreasing sequence length: workgroups are dispatched in index
     // order, so the long ones start first and the short ones fill the end
@@ -136,7 +148,7 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
         // flight to saturate HBM, few enough waves that start-up and partial results stay small)
         // and at least ~32 blocks per wave
         const int64_t wave_slots = std::max<int64_t>(1, (int64_t)geo.num_cus * 3 / geo.Hkv);
-        int64_t runs = geo.segments_opt > 0 ? geo.segments_opt : std::min<int64_t>(wave_slots, (dec_blocks + 31) / 32);
+        int64_t runs = geo.segments_opt > 0 ? geo.segments_opt : std::min<int64_t>(wave_slots, (kv_blocks + 31) / 32);
         runs = std::max<int64_t>(1, std::min<int64_t>(runs, dec_blocks));
         for (;;) {
             // weighted runs come in groups of one run per XCD
@@ -225,8 +237,12 @@ std::vector<Piece> enumerate_pieces(const HostPlan &pl)
             while (pl.dcum[(size_t)seq + 1] <= pos) ++seq;
             const int64_t cs = pl.dcum[(size_t)seq], ce = pl.dcum[(size_t)seq + 1];
             const int64_t stop = std::min<int64_t>(hi, ce);
-            const bool whole = pos == cs && stop == ce;
-            v.push_back(Piece{seq, (int32_t)(pos - cs), (int32_t)(stop - cs), whole ? -1 : (int32_t)(k + seq), (int32_t)k});
+            const int64_t first = cs + pl.piece_pad, begin = std::max(pos, first);   // the blocks start at `first`
+            if (begin < stop) {
+                const bool whole = begin == first && stop == ce;
+                v.push_back(Piece{seq, (int32_t)(begin - first), (int32_t)(stop - first), whole ? -1 : (int32_t)(k + seq),
+                                  (int32_t)k});
+            }
             pos = stop;
             ++seq;
         }
@@ -268,6 +284,7 @@ struct ooco_ctx {
     int64_t opt_trace = 0;
     int64_t opt_rotate = 1;
     int64_t opt_pf_split = 0;
+    int64_t opt_piece_pad = 0;   // set at creation: 3 tiles of head_dim 128
     int32_t *pf_counters = nullptr;   // [kPrefillSplitUnits] arrival counters of split prefill tiles, zero between calls
     uint16_t xcd_cw[kXcds] = {};   // option "xcd_weights"
     int64_t opt_overlap = 1;
@@ -343,6 +360,7 @@ ooco_status ooco_ctx_create(ooco_ctx **out, int num_q_heads, int num_kv_heads, i
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device) == hipSuccess && cus > 0)
             c->num_cus = cus;
     }
+    c->opt_piece_pad = default_piece_pad(head_dim);
     if (e == hipSuccess) {
         if (workspace) {
             c->ws = workspace;
@@ -459,6 +477,10 @@ ooco_status ooco_set_option(ooco_ctx *ctx, const char *name, int64_t value)
         ctx->opt_tail_blocks = value;
     else if (!strcmp(name, "prefill_split"))
         ctx->opt_pf_split = value;
+    else if (!strcmp(name, "decode_piece_pad")) {
+        if (value > 64) return fail(ctx, OOCO_EINVAL, "ooco_set_option: decode_piece_pad must be 0..64");
+        ctx->opt_piece_pad = value;
+    }
     else if (!strcmp(name, "trace")) {
         if (value && !ctx->trace_d) {
             hipError_t e = hipMalloc((void **)&ctx->trace_d, kTraceWaves * 4 * sizeof(uint64_t));
@@ -516,6 +538,7 @@ ooco_status ooco_plan(ooco_ctx *ctx, int num_seqs, const int32_t *h_seq_lens, co
     geo.tail_pct = ctx->opt_tail_pct;
     geo.tail_blocks = ctx->opt_tail_blocks;
     geo.pf_split_opt = ctx->opt_pf_split;
+    geo.piece_pad = ctx->opt_piece_pad;
     for (int k = 0; k < kXcds; ++k) geo.xcd_cw[k] = ctx->xcd_cw[k];
     ooco_status st = build_plan(geo, num_seqs, h_seq_lens, h_query_start_loc, h_ctx_lens, ctx->plan, ctx->err);
     if (st != OOCO_OK) return st;
@@ -533,14 +556,14 @@ ooco_status ooco_plan_dry_run(int num_q_heads, int num_kv_heads, int head_dim, i
                               const int32_t *h_seq_lens, const int32_t *h_query_start_loc, const int32_t *h_ctx_lens,
                               int32_t *decode_pieces_out, int64_t decode_cap, int32_t *prefill_tiles_out,
                               int64_t prefill_cap, int64_t *counts, char *msg, size_t msg_cap,
-                              const int32_t *xcd_weights, int64_t prefill_split)
+                              const int32_t *xcd_weights, int64_t prefill_split, int64_t decode_piece_pad)
 {
     char err[512] = "";
     ooco_status st = OOCO_OK;
     HostPlan pl;
     if (num_q_heads <= 0 || num_kv_heads <= 0 || num_q_heads % num_kv_heads || (head_dim != 64 && head_dim != 128) ||
         block_size != kBlockSize || max_blocks_per_seq <= 0 || num_cus <= 0 || decode_segments < 0 ||
-        decode_tail_pct < 0 || decode_tail_blocks < 0 || prefill_split < 0) {
+        decode_tail_pct < 0 || decode_tail_blocks < 0 || prefill_split < 0 || decode_piece_pad > 64) {
         snprintf(err, sizeof err, "ooco_plan_dry_run: bad geometry");
         st = OOCO_ESHAPE;
     } else {
@@ -556,6 +579,7 @@ ooco_status ooco_plan_dry_run(int num_q_heads, int num_kv_heads, int head_dim, i
         geo.tail_pct = decode_tail_pct;
         geo.tail_blocks = decode_tail_blocks;
         geo.pf_split_opt = prefill_split;
+        geo.piece_pad = decode_piece_pad < 0 ? default_piece_pad(head_dim) : decode_piece_pad;
         if (xcd_weights && !xcd_weights_to_cw(xcd_weights, geo.xcd_cw)) {
             snprintf(err, sizeof err, "ooco_plan_dry_run: xcd_weights needs eight values in 1..255 that differ by at most 4x");
             st = OOCO_EINVAL;
@@ -603,7 +627,7 @@ ooco_status ooco_plan_info(const ooco_ctx *ctx, int64_t *decode_waves, int64_t *
     if (!ctx->plan_valid) return fail(ctx, OOCO_EINVAL, "ooco_plan_info: no current plan");
     if (decode_waves) *decode_waves = ctx->plan.static_runs;
     if (prefill_tiles) *prefill_tiles = ctx->plan.n_tiles;
-    if (decode_blocks) *decode_blocks = ctx->plan.dec_blocks;
+    if (decode_blocks) *decode_blocks = ctx->plan.kv_blocks;
     if (workspace_used) {
         size_t bytes = (size_t)ctx->plan.slots * (size_t)ctx->Hq * (ctx->hd + 2) * sizeof(float);
         if (ctx->plan.pf_split > 1)
@@ -696,6 +720,7 @@ ooco_status ooco_attn_mixed(ooco_ctx *ctx, const void *q, const void *k_cache, c
     p.num_seqs = num_seqs;
     p.total_q = total_q_tokens;
     p.dec_blocks = pl.dec_blocks;
+    p.piece_pad = pl.piece_pad;
     p.static_blocks = pl.static_blocks;
     p.static_runs = pl.static_runs;
     p.tail_runs = pl.tail_runs;

@@ -54,6 +54,7 @@ struct AttnParams {
     float scale_log2e;          // softmax scale * log2(e)
     int32_t num_seqs, total_q;
     int32_t dec_blocks, static_blocks, static_runs, tail_runs;   // decode run layout
+    int32_t piece_pad;   // line units in front of every decode sequence's blocks (the cost of starting a piece)
     int32_t n_tiles, tile_rows; // prefill: tiles per kv head, query rows per tile
     int32_t num_pf, pad_pf;     // prefill: number of chunks (entries of the prefill array, see below)
     int32_t nbi;                // tuning: KV blocks per softmax step of the decode kernel
@@ -104,6 +105,9 @@ __host__ __device__ inline int32_t segment_of(int64_t x, int64_t s, int64_t n)
 // weights: run 8p+k gets the share (cw[k] - cw[k-1]) / cw[7] of group p.  The decode kernel places
 // run v on XCD v % kXcds, so a slower XCD can be given shorter runs.
 constexpr int kXcds = 8;
+// Default cost of starting a piece, in line units (= KV tiles of one kv head): measured on MI355X a wave
+// needs about 3 us from one piece to the first tile of the next, the time it streams three 8 KiB tiles.
+inline int default_piece_pad(int head_dim) { return 3 * 128 / head_dim; }
 struct RunLayout {
     int32_t dec_blocks, static_blocks, static_runs, tail_runs;
     uint16_t cw[kXcds];   // cumulative weights of the runs of a group; all zero = equal runs

@@ -236,9 +236,17 @@ __global__ __launch_bounds__(64) void decode_kernel(const KernArgs a)
             ce = cum_at(seq + 1);
         }
         const int stop = min(hi, ce);
-        const int blk_begin = pos - cs;
-        const int nblk = stop - pos;
-        const bool whole = (pos == cs) && (stop == ce);
+        // the sequence's blocks start piece_pad units into its stretch of the line
+        const int first = cs + p.piece_pad;
+        const int begin = max(pos, first);
+        if (begin >= stop) {   // the run ends before the first block of this sequence
+            if (trace && lane == 0) trace[2] = wall_clock64();
+            pos = stop;
+            continue;
+        }
+        const int blk_begin = begin - first;
+        const int nblk = stop - begin;
+        const bool whole = (begin == first) && (stop == ce);
         const int seq_len = p.seq_lens[seq];
         const int q_row = min(max(p.query_start_loc[seq], 0), p.total_q - 1);
 
@@ -383,7 +391,7 @@ __global__ __launch_bounds__(64) void decode_kernel(const KernArgs a)
                 for (int nb = 0; nb < NB; ++nb) store_dev4(ap + nb * 16, O[nb]);
                 if (kq == 0) store_dev2(p.part_ml + row * 2, m, ltot);
             }
-            const int first_run = run_of(L, cs);
+            const int first_run = run_of(L, first);
             const int nparts = run_of(L, (int64_t)ce - 1) - first_run + 1;
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the partial has reached memory before the count
             int prev = 0;

@@ -122,7 +122,7 @@ def test_default_plan_is_equal_static_runs_plus_short_tail_runs():
     for cfg in (W.config2, W.config4, W.config5):
         b = meta_only(cfg)
         plan = dry(b.seq_lens, b.query_start_loc, b.ctx_lens, num_q_heads=b.Hq, num_kv_heads=b.Hkv,
-                   workspace_bytes=1 << 30, decode_tail_pct=15)
+                   workspace_bytes=1 << 30, decode_tail_pct=15, decode_piece_pad=0)
         d = plan["decode_pieces"]
         R, T = plan["decode_runs"], plan["tail_runs"]
         per_run = np.bincount(d[:, 4], weights=d[:, 2] - d[:, 1], minlength=R + T)
@@ -138,16 +138,39 @@ def test_default_plan_is_equal_static_runs_plus_short_tail_runs():
     assert dry(b.seq_lens, b.query_start_loc, b.ctx_lens, decode_segments=2000)["tail_runs"] == 0
 
 
+def test_runs_that_start_more_pieces_stream_fewer_blocks():
+    for cfg in (W.config2, W.config3, W.config4):
+        b = meta_only(cfg)
+        for pad in (3, 6, 1):
+            plan = dry(b.seq_lens, b.query_start_loc, b.ctx_lens, num_q_heads=b.Hq, num_kv_heads=b.Hkv,
+                       workspace_bytes=1 << 30, decode_piece_pad=pad)
+            check_cover(b, plan)
+            d = plan["decode_pieces"]
+            R = plan["decode_runs"]
+            blocks = np.bincount(d[:, 4], weights=d[:, 2] - d[:, 1], minlength=R)
+            starts = np.bincount(d[:, 4], weights=(d[:, 1] == 0), minlength=R)
+            cost = blocks + pad * starts
+            # equal up to the rounding of the cuts and a piece start that a cut may split between two runs
+            assert cost.max() - cost.min() <= 2 * pad + 1, (pad, cost.min(), cost.max())
+            assert np.percentile(cost, 90) - np.percentile(cost, 10) <= 1
+            assert blocks.max() - blocks.min() >= pad                       # and the block counts do differ
+        default = dry(b.seq_lens, b.query_start_loc, b.ctx_lens, num_q_heads=b.Hq, num_kv_heads=b.Hkv, workspace_bytes=1 << 30)
+        three = dry(b.seq_lens, b.query_start_loc, b.ctx_lens, num_q_heads=b.Hq, num_kv_heads=b.Hkv, workspace_bytes=1 << 30,
+                    decode_piece_pad=3)
+        assert (default["decode_pieces"] == three["decode_pieces"]).all()   # head_dim 128: three blocks
+
+
 def test_xcd_weights_shape_the_static_runs():
     w = [100, 90, 110, 95, 105, 85, 115, 100]
     for cfg in (W.config1, W.config2, W.config3, W.config4, W.config5):
         b = meta_only(cfg)
-        for seg, pct in ((0, 0), (96, 0), (100, 15), (8, 0), (17, 30)):
+        for seg, pct, trial_pad in ((0, 0, 0), (96, 0, 0), (100, 15, 0), (8, 0, 0), (17, 30, 0), (0, 0, 3), (100, 15, 5)):
             plan = dry(b.seq_lens, b.query_start_loc, b.ctx_lens, num_q_heads=b.Hq, num_kv_heads=b.Hkv, head_dim=b.hd,
-                       workspace_bytes=1 << 30, decode_segments=seg, decode_tail_pct=pct, xcd_weights=w)
+                       workspace_bytes=1 << 30, decode_segments=seg, decode_tail_pct=pct, xcd_weights=w,
+                       decode_piece_pad=trial_pad)
             check_cover(b, plan)
             R = plan["decode_runs"]
-            if R < 8:
+            if R < 8 or trial_pad:
                 continue                      # too few runs for one per XCD: equal runs
             assert R % 8 == 0
             d = plan["decode_pieces"]
@@ -157,7 +180,7 @@ def test_xcd_weights_shape_the_static_runs():
             assert np.abs(share - np.array(w) / sum(w)).max() < 0.01 + 8.0 / per_xcd.sum()
     # fewer than 8 runs, or no weights: equal runs
     b = meta_only(W.config2)
-    plan = dry(b.seq_lens, b.query_start_loc, b.ctx_lens, decode_segments=5, xcd_weights=w)
+    plan = dry(b.seq_lens, b.query_start_loc, b.ctx_lens, decode_segments=5, xcd_weights=w, decode_piece_pad=0)
     d = plan["decode_pieces"]
     per_run = np.bincount(d[:, 4], weights=d[:, 2] - d[:, 1])
     assert plan["decode_runs"] == 5 and per_run.max() - per_run.min() <= 1
