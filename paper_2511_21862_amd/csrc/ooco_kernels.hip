@@ -45,6 +45,49 @@ OOCO_DEV float max3(float a, float b, float c)
     return d;
 }
 
+// max of two / with a floor of -1e30, as single instructions (no NaN-quieting moves)
+OOCO_DEV float max2(float a, float b)
+{
+    float d;
+    asm("v_max_f32_e32 %0, %1, %2" : "=v"(d) : "v"(a), "v"(b));
+    return d;
+}
+OOCO_DEV float floor_m1e30(float a)
+{
+    float d;
+    asm("v_max_f32_e32 %0, 0xf149f2ca, %1" : "=v"(d) : "v"(a));   // 0xf149f2ca = -1e30f
+    return d;
+}
+// max of the 32 scores a lane holds for one step (two 16-register MFMA results), as one dependent chain of
+// v_max3_f32 in two asm statements (an asm statement takes at most 30 operands)
+OOCO_DEV float max32(const f32x16 &a, const f32x16 &b)
+{
+    float d, e;
+    asm("v_max3_f32 %0, %1, %2, %3\n\t"
+        "v_max3_f32 %0, %0, %4, %5\n\t"
+        "v_max3_f32 %0, %0, %6, %7\n\t"
+        "v_max3_f32 %0, %0, %8, %9\n\t"
+        "v_max3_f32 %0, %0, %10, %11\n\t"
+        "v_max3_f32 %0, %0, %12, %13\n\t"
+        "v_max3_f32 %0, %0, %14, %15\n\t"
+        "v_max3_f32 %0, %0, %16, %17"
+        : "=&v"(d)
+        : "v"(a[0]), "v"(b[0]), "v"(a[1]), "v"(b[1]), "v"(a[2]), "v"(b[2]), "v"(a[3]), "v"(b[3]), "v"(a[4]), "v"(b[4]),
+          "v"(a[5]), "v"(b[5]), "v"(a[6]), "v"(b[6]), "v"(a[7]), "v"(b[7]), "v"(a[8]));
+    asm("v_max3_f32 %0, %1, %2, %3\n\t"
+        "v_max3_f32 %0, %0, %4, %5\n\t"
+        "v_max3_f32 %0, %0, %6, %7\n\t"
+        "v_max3_f32 %0, %0, %8, %9\n\t"
+        "v_max3_f32 %0, %0, %10, %11\n\t"
+        "v_max3_f32 %0, %0, %12, %13\n\t"
+        "v_max3_f32 %0, %0, %14, %15\n\t"
+        "v_max_f32_e32 %0, %0, %16"
+        : "=&v"(e)
+        : "v"(d), "v"(b[8]), "v"(a[9]), "v"(b[9]), "v"(a[10]), "v"(b[10]), "v"(a[11]), "v"(b[11]), "v"(a[12]), "v"(b[12]),
+          "v"(a[13]), "v"(b[13]), "v"(a[14]), "v"(b[14]), "v"(a[15]), "v"(b[15]));
+    return e;
+}
+
 // acc + lo + hi of a packed bf16 pair (one v_dot2c_f32_bf16 against the pair (1, 1))
 OOCO_DEV float sum2_bf16(uint32_t pair, float acc)
 {
@@ -683,22 +726,18 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
     // tokens 32hh + 16u + 8h + 0..7.  The softmax scale rides in the fma that feeds exp2 (scale > 0,
     // so the maximum can be taken before scaling).
     auto softmax = [&](const f32x16 (&S)[2], u32x4 (&P)[4], float &alpha, bool &grow) {
-        float mloc = max3(S[0][0], S[1][0], S[0][1]);
-        mloc = max3(mloc, S[1][1], S[0][2]);
-#pragma unroll
-        for (int r = 2; r < 15; ++r) mloc = max3(mloc, S[1][r], S[0][r + 1]);
-        mloc = fmaxf(mloc, S[1][15]);
+        float mloc = max32(S[0], S[1]);
         {
             float x, y;
             swap32(mloc, x, y);
-            mloc = fmaxf(x, y) * c_log2e;
+            mloc = max2(x, y) * c_log2e;
         }
         // (floored: a part of a split tile may start with steps that a column does not see at all; its maximum
         // then stays at the floor, its weights and sum at 0, instead of running into inf - inf)
         // The reference point m only has to stay within 2^8 of the true running maximum (weights up to 256 are
         // exact enough in bf16 and harmless in the fp32 sums; the final division cancels the reference), so it
         // moves, and the accumulators are rescaled, only when a step's maximum exceeds it by more than 8.
-        const float m_cand = fmaxf(mloc, -1e30f);
+        const float m_cand = floor_m1e30(mloc);
         grow = m_cand > m + 8.0f;
         const float m_new = grow ? m_cand : m;
         alpha = fast_exp2(m - m_new);
