@@ -725,7 +725,18 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
     // online-softmax update with the raw scores of one step; P[2hh+u] holds the packed weights of
     // tokens 32hh + 16u + 8h + 0..7.  The softmax scale rides in the fma that feeds exp2 (scale > 0,
     // so the maximum can be taken before scaling).
-    auto softmax = [&](const f32x16 (&S)[2], u32x4 (&P)[4], float &alpha, bool &grow) {
+    // The update comes in two halves so that the PV products of the first 32 tokens can run beside the
+    // exponentials of the last 32: weights(S, P, q4, ...) turns the scores of tokens 16*q4 + 8h + 0..7 into P[q4].
+    auto weights = [&](const f32x16 (&S)[2], u32x4 (&P)[4], int q4, float m_ref, float &psum) {
+        float e[8];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) e[r] = fast_exp2(__builtin_fmaf(S[q4 >> 1][8 * (q4 & 1) + r], c_log2e, -m_ref));
+        P[q4] = u32x4{pack2_bf16(e[0], e[1]), pack2_bf16(e[2], e[3]), pack2_bf16(e[4], e[5]), pack2_bf16(e[6], e[7])};
+        // the denominator sums the same rounded weights that enter the PV product
+#pragma unroll
+        for (int w = 0; w < 4; ++w) psum = sum2_bf16(P[q4][w], psum);
+    };
+    auto softmax_first = [&](const f32x16 (&S)[2], u32x4 (&P)[4], float &alpha, bool &grow, float &psum) {
         float mloc = max32(S[0], S[1]);
         {
             float x, y;
@@ -742,20 +753,17 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
         const float m_new = grow ? m_cand : m;
         alpha = fast_exp2(m - m_new);
         m = m_new;
-        float psum = 0.f;
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-            float e[8];
-#pragma unroll
-            for (int r = 0; r < 8; ++r) e[r] = fast_exp2(__builtin_fmaf(S[q4 >> 1][8 * (q4 & 1) + r], c_log2e, -m_new));
-            P[q4] = u32x4{pack2_bf16(e[0], e[1]), pack2_bf16(e[2], e[3]), pack2_bf16(e[4], e[5]),
-                          pack2_bf16(e[6], e[7])};
-            // the denominator sums the same rounded weights that enter the PV product
-#pragma unroll
-            for (int w = 0; w < 4; ++w) psum = sum2_bf16(P[q4][w], psum);
-        }
+        psum = 0.f;
+        weights(S, P, 0, m, psum);
+        weights(S, P, 1, m, psum);
+    };
+    auto softmax_second = [&](const f32x16 (&S)[2], u32x4 (&P)[4], float alpha, float psum) {
+        weights(S, P, 2, m, psum);
+        weights(S, P, 3, m, psum);
         lsum = lsum * alpha + psum;
     };
+    // The MFMAs of tokens 0..31 (P[0], P[1]) are laid out beside the vector work that is still due when pv
+    // starts (the second half of the softmax update), those of tokens 32..63 follow.
     auto pv = [&](const u32x4 (&P)[4], int slot) {
         const u32x4 *vp = &ldsV[slot][h * HD + col];
 #pragma unroll
@@ -771,6 +779,10 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
         for (int i = 0; i < 4 * MB - kAhead; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            if (i < 2 * MB) {
+                __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+                __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
+            }
         }
         __builtin_amdgcn_sched_group_barrier(0x008, kAhead, 0);
     };
@@ -822,16 +834,16 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
         if (st * 64 > w_pos_hi) return;
         if (st * 64 + 63 > w_pos_lo) mask(Sc, st);   // the step touches the causal diagonal
         u32x4 P[4];
-        float alpha;
+        float alpha, psum;
         bool grow;
         // One straight-line region for the scheduler.  The scores of step st+1 are computed even
         // when nothing will use them (last step of the tile, or no column of the wave sees that
         // step): the K slot then holds an older step's tiles, and the result is dropped.
         qk(Sn, (st + 1) & 1);
-        softmax(Sc, P, alpha, grow);
-        // the weights are due here, inside the region of the score MFMAs ...
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) asm volatile("" : "+v"(P[q4]));
+        softmax_first(Sc, P, alpha, grow, psum);
+        // the weights of the first 32 tokens are due here, inside the region of the score MFMAs ...
+        asm volatile("" : "+v"(P[0]));
+        asm volatile("" : "+v"(P[1]));
         // ... and the region is laid out as 2*hd/16 x (MFMA, LDS read, a share of the vector work):
         // the maximum is found next to the first MFMAs, the exponentials next to the others
         __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
@@ -839,14 +851,14 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
         for (int i = 0; i < KS / 2; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
         }
 #pragma unroll
         for (int i = KS / 2; i < 2 * KS; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
-            __builtin_amdgcn_sched_group_barrier(0x400, 3, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+            __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
         }
         if (__any(grow)) {
 #pragma unroll
@@ -854,6 +866,10 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
 #pragma unroll
                 for (int r = 0; r < 16; ++r) O[mb][r] *= alpha;
         }
+        // the second half of the update belongs to the region of the PV MFMAs: its scores pass through an empty
+        // asm here so that nothing of it is moved up
+        asm volatile("" : "+v"(Sc[1]));
+        softmax_second(Sc, P, alpha, psum);
         pv(P, st & 1);
     };
 
