@@ -701,16 +701,18 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
     // scores of one step: S[hh] register r is token st*64 + 32hh + 8h + 16(r/8) + r%8
     auto qk = [&](f32x16 (&S)[2], int slot) {
 #pragma unroll
-        for (int hh = 0; hh < 2; ++hh) {
+        for (int hh = 0; hh < 2; ++hh)
 #pragma unroll
             for (int r = 0; r < 16; ++r) S[hh][r] = 0.f;
+        // the two token halves alternate, so that consecutive MFMAs never wait for each other's result
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh) {
                 const u32x4 kop = ldsK[slot][(2 * hh + ku) * CH + (2 * ks + h) * 16 + kslot];
                 S[hh] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kop),
                                                             __builtin_bit_cast(bf16x8, qb[ks]), S[hh], 0, 0, 0);
             }
-        }
     };
     // causal mask of a step that touches the diagonal
     auto mask = [&](f32x16 (&S)[2], int st) {
