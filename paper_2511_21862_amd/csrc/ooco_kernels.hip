@@ -781,10 +781,7 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
         for (int i = 0; i < 4 * MB - kAhead; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            if (i < 2 * MB) {
-                __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
-                __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
-            }
+            if (i < 2 * MB) __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);   // (exponentials count as VALU here)
         }
         __builtin_amdgcn_sched_group_barrier(0x008, kAhead, 0);
     };
