@@ -670,7 +670,13 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
     typedef const __attribute__((address_space(4))) int32_t *const_i32_ptr;
     const const_i32_ptr ctable = (const_i32_ptr)(uintptr_t)table;
     auto block_id = [&](int b) -> int { return ctable[min(b, nblk - 1)]; };
+    // (tile of kv head kvh of physical block pb) = cache + pb * blk_stride + kvh * tile_elems, in elements
+    const uint16_t *const k_head = k_cache + (int64_t)kvh * tile_elems, *const v_head = v_cache + (int64_t)kvh * tile_elems;
+    const uint32_t blk_stride = (uint32_t)Hkv * (uint32_t)tile_elems;
     auto issue = [&](bool is_v, int slot, const int (&pb)[kPfBlocks]) {   // pb: physical ids of the step's blocks
+        static_assert(NCP == 4 || NCP == 2, "one asm statement per stage");
+        const uint16_t *base[NCP];
+        uint32_t voff[NCP], dst[NCP];
 #pragma unroll
         for (int n = 0; n < NCP; ++n) {
             const int grp = wave + 4 * n;                  // wave-uniform
@@ -679,17 +685,31 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
             // chunks, which keeps pb[] in registers without select chains)
             const int which = CH >= 256 ? (4 * n * 64) / CH : (grp * 64) / CH;
             const int r = cidx - which * CH;
-            const int64_t off = ((int64_t)pb[which] * Hkv + kvh) * tile_elems;
             // scalar tile address + 32-bit lane offset (bytes)
-            const uint16_t *base = (is_v ? v_cache : k_cache) + off;
-            const uint32_t voff = (uint32_t)(is_v ? 2 * (r % HD) + r / HD : r) * 16u;
-            const uint32_t dst = (is_v ? ldsV_base : ldsK_base) + (uint32_t)((slot * STAGE + grp * 64) * 16);
-            uint32_t saved_m0;   // M0 is restored: the compiler may keep a value of its own there
-            asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3\n\ts_mov_b32 m0, %0"
-                         : "=&s"(saved_m0)
-                         : "s"(dst), "v"(voff), "s"(base)
-                         : "memory");
+            base[n] = (is_v ? v_head : k_head) + (uint64_t)(uint32_t)pb[which] * blk_stride;
+            voff[n] = (uint32_t)(is_v ? 2 * (r % HD) + r / HD : r) * 16u;
+            dst[n] = (is_v ? ldsV_base : ldsK_base) + (uint32_t)((slot * STAGE + grp * 64) * 16);
         }
+        uint32_t saved_m0;   // M0 is restored: the compiler may keep a value of its own there
+        if constexpr (NCP == 4)
+            asm volatile("s_mov_b32 %0, m0\n\t"
+                         "s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %5, %9\n\t"
+                         "s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %6, %10\n\t"
+                         "s_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %7, %11\n\t"
+                         "s_mov_b32 m0, %4\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %8, %12\n\t"
+                         "s_mov_b32 m0, %0"
+                         : "=&s"(saved_m0)
+                         : "s"(dst[0]), "s"(dst[1]), "s"(dst[2]), "s"(dst[3]), "v"(voff[0]), "v"(voff[1]), "v"(voff[2]),
+                           "v"(voff[3]), "s"(base[0]), "s"(base[1]), "s"(base[2]), "s"(base[3])
+                         : "memory");
+        else
+            asm volatile("s_mov_b32 %0, m0\n\t"
+                         "s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %3, %5\n\t"
+                         "s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %4, %6\n\t"
+                         "s_mov_b32 m0, %0"
+                         : "=&s"(saved_m0)
+                         : "s"(dst[0]), "s"(dst[1]), "v"(voff[0]), "v"(voff[1]), "s"(base[0]), "s"(base[1])
+                         : "memory");
     };
 
     f32x16 O[MB];
