@@ -13,10 +13,13 @@ from gpu_util import device_meta, say
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("mixed", [False, True])
+@pytest.mark.parametrize("mixed", [False, True, "split"])
 def test_captured_calls_replay_to_the_eager_result(mixed):
+    # "split": the chunk sits on a long prefix, so its tiles are cut along the context and merged through the
+    # workspace and the arrival counters, which every replay must find reset
     ql = [1, 1, 96, 1, 1] if mixed else [1, 1, 1, 1, 1]
-    b = W.build_batch(Hq=32, Hkv=8, hd=128, q_lens=ql, ctx_lens=[3000, 129, 400, 64, 900], num_blocks=320, seed=91)
+    ctx_lens = [3000, 129, 4000 if mixed == "split" else 400, 64, 900]
+    b = W.build_batch(Hq=32, Hkv=8, hd=128, q_lens=ql, ctx_lens=ctx_lens, num_blocks=560, seed=91)
     d = W.to_device(b)
     bt, sl, qsl, cl = device_meta(b)
     say(f"case: graph capture, {'mixed' if mixed else 'decode-only'} batch")
@@ -24,6 +27,7 @@ def test_captured_calls_replay_to_the_eager_result(mixed):
     out = torch.zeros_like(eager)
     with B.Context(b.Hq, b.Hkv, b.hd, b.BS, b.num_blocks, b.max_blocks_per_seq) as ctx:
         ctx.plan(b.seq_lens, b.query_start_loc, b.ctx_lens)
+        assert (ctx.plan_info()["prefill_parts"] > 1) == (mixed == "split")
         ctx.attn_mixed(d.q, d.k_cache, d.v_cache, bt, sl, qsl, cl, eager)
         torch.cuda.synchronize()
         side = torch.cuda.Stream()

@@ -64,6 +64,16 @@ def test_forced_decode_run_layouts_agree(segments, tail_pct, tail_blocks):
     assert_parity(run_gpu(b, options=opts), ref, f"segments={segments} tail={tail_pct}%x{tail_blocks}")
 
 
+@pytest.mark.parametrize("pad,segments,tail_pct", [(0, 0, 0), (1, 5, 0), (7, 40, 0), (64, 3, 0), (64, 10 ** 6, 0), (5, 6, 40)])
+def test_piece_pad_values_agree(pad, segments, tail_pct):
+    # the run cuts charge `pad` blocks for every piece a run starts; with 64 some runs hold no block at all
+    b = W.build_batch(Hq=32, Hkv=8, hd=128, q_lens=[1, 1, 0, 1, 5, 1, 1], ctx_lens=[2000, 130, 7, 15, 40, 0, 300],
+                      num_blocks=200, seed=78, poison=True)
+    say(f"case: decode_piece_pad {pad}, decode_segments {segments}, tail {tail_pct}%")
+    opts = {"decode_piece_pad": pad, "decode_segments": segments, "decode_tail_pct": tail_pct, "decode_tail_blocks": 2}
+    assert_parity(run_gpu(b, options=opts), oracle(b), f"piece pad {pad} segments {segments}")
+
+
 @pytest.mark.parametrize("Hkv,segments,tail_pct", [(8, 8, 0), (2, 16, 0), (4, 24, 10), (8, 0, 0), (8, 10 ** 6, 0)])
 def test_xcd_weighted_decode_runs_agree(Hkv, segments, tail_pct):
     # static runs sized per XCD (run v on XCD v % 8, all kv heads of a run on one XCD)
