@@ -228,7 +228,7 @@ OOCO_DEV int count_le(CumAt cum_at, int n, int x, int lane)
 // (seq, kv head); the piece that arrives last merges all slots of the sequence in slot order
 // (so the result does not depend on which piece is last) and resets the counter.
 template <int HD, int NBI>
-__global__ __launch_bounds__(64) void decode_kernel(const KernArgs a)
+__global__ __launch_bounds__(64, 2) void decode_kernel(const KernArgs a)
 {
     constexpr int KC = HD / 32;
     constexpr int NB = HD / 16;
