@@ -225,8 +225,7 @@ struct Piece {
 std::vector<Piece> enumerate_pieces(const HostPlan &pl)
 {
     std::vector<Piece> v;
-    RunLayout L = {pl.dec_blocks, pl.static_blocks, pl.static_runs, pl.tail_runs, {}};
-    for (int k = 0; k < kXcds; ++k) L.cw[k] = pl.cw[k];
+    const RunLayout L = {pl.dec_blocks, pl.static_blocks, pl.static_runs, pl.tail_runs, pl.cw};
     for (int32_t k = 0; k < pl.static_runs + pl.tail_runs; ++k) {
         int32_t lo, hi;
         run_bounds(L, k, lo, hi);

@@ -110,7 +110,10 @@ constexpr int kXcds = 8;
 inline int default_piece_pad(int head_dim) { return 3 * 128 / head_dim; }
 struct RunLayout {
     int32_t dec_blocks, static_blocks, static_runs, tail_runs;
-    uint16_t cw[kXcds];   // cumulative weights of the runs of a group; all zero = equal runs
+    // cumulative weights of the runs of a group, kXcds values; all zero = equal runs.  (A pointer, not a copy: the
+    // device reads the weights straight from the kernel arguments; a local copy indexed by a run-time value would
+    // live in scratch memory.)
+    const uint16_t *cw;
 };
 __host__ __device__ inline int32_t group_cut(const RunLayout &L, int32_t plo, int32_t phi, int32_t k)
 {

@@ -250,9 +250,7 @@ __global__ __launch_bounds__(64, 2) void decode_kernel(const KernArgs a)
     const int g = p.g;
     const int64_t tile_elems = (int64_t)HD * kBlockSize;   // one (block, kv head) tile
     auto cum_at = [&](int idx) -> int { return p.cum_dev ? p.cum_dev[idx] : a.cum[idx]; };
-    RunLayout L = {p.dec_blocks, p.static_blocks, p.static_runs, p.tail_runs, {}};
-#pragma unroll
-    for (int k = 0; k < kXcds; ++k) L.cw[k] = p.xcd_cw[k];
+    const RunLayout L = {p.dec_blocks, p.static_blocks, p.static_runs, p.tail_runs, p.xcd_cw};
     const unsigned tail_tasks = (unsigned)p.tail_runs * (unsigned)p.Hkv;
 
     uint64_t *trace = p.trace ? p.trace + (int64_t)blockIdx.x * 4 : nullptr;   // per-wave time stamps
