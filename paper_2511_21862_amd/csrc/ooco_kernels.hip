@@ -233,6 +233,15 @@ __global__ __launch_bounds__(64, 2) void decode_kernel(const KernArgs a)
     constexpr int KC = HD / 32;
     constexpr int NB = HD / 16;
     const AttnParams &p = a.p;
+    // What a wave needs before its first KV tile is on its way comes from a dozen places of the kernel
+    // arguments; asked for one after the other, each at its point of use, they cost a wave ten dependent
+    // round trips to the scalar cache.  Naming them here makes the compiler fetch them together.
+    asm volatile("" ::"s"(p.q), "s"(p.k_cache), "s"(p.v_cache), "s"(p.block_tables), "s"(p.seq_lens),
+                 "s"(p.query_start_loc), "s"(p.cum_dev), "s"(p.trace), "s"(p.queue), "s"(p.Hq), "s"(p.Hkv), "s"(p.g),
+                 "s"(p.max_blocks_per_seq), "s"(p.num_seqs), "s"(p.total_q), "s"(p.dec_blocks), "s"(p.static_blocks),
+                 "s"(p.static_runs), "s"(p.tail_runs), "s"(p.piece_pad), "s"(p.rotate_heads), "s"(p.scale_log2e),
+                 "s"(p.queue_base), "s"(*reinterpret_cast<const uint64_t *>(&p.xcd_cw[0])),
+                 "s"(*reinterpret_cast<const uint64_t *>(&p.xcd_cw[4])));
     const int lane = threadIdx.x;
     const int col = lane & 15;
     const int kq = lane >> 4;
