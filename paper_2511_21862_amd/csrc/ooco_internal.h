@@ -2,14 +2,15 @@
 // libooco.  Not part of the public ABI.
 //
 // Work decomposition (computed by every wave from a small cumulative array, no work lists):
-//   decode  - the KV blocks of all decode sequences, laid end to end in sequence order, form one
-//             line of `dec_blocks` blocks.  Its first `static_blocks` blocks are cut into
+//   decode  - the KV blocks of all decode sequences, laid end to end in sequence order, each
+//             preceded by `piece_pad` empty units (the cost of starting a piece, in blocks), form one
+//             line of `dec_blocks` units.  Its first `static_blocks` units are cut into
 //             `static_runs` equal runs, one per launched wave and kv head; the rest into
 //             `tail_runs` short runs that the waves fetch from a shared ticket counter when they
 //             are done with their own run, so that faster waves (XCDs differ by several percent
 //             in delivered bandwidth) end up streaming more blocks.  Where a run crosses sequence
 //             boundaries it has several pieces.
-//             cum[i] = number of decode blocks before sequence i (cum[num_seqs] = dec_blocks).
+//             cum[i] = number of line units before sequence i (cum[num_seqs] = dec_blocks).
 //             A piece that does not cover its whole sequence writes a partial result into slot
 //             (run index) + i; the last piece of a sequence to finish merges the slots (arrival
 //             counter per sequence and kv head).
@@ -31,9 +32,9 @@ namespace ooco {
 
 constexpr int kBlockSize = 16;      // tokens per KV block (fixed by the cache layout)
 constexpr int kPrefillCols = 128;   // (row, head) query columns per prefill workgroup
-constexpr int kInlineSeqs = 960;
+constexpr int kInlineSeqs = 960;    // sequences whose cumulative array fits the kernel arguments
 constexpr int kMaxPrefillSplit = 8; // parts a prefill tile's keys may be cut into
-constexpr int kPrefillSplitUnits = 8192;   // (tile, kv head) pairs up to which the split is available    // sequences whose cumulative array fits the kernel arguments
+constexpr int kPrefillSplitUnits = 8192;   // (tile, kv head) pairs up to which the split is available
 
 struct AttnParams {
     const uint16_t *q;
