@@ -134,6 +134,8 @@ const char *ooco_last_error(const ooco_ctx *ctx);
  *                run the prefill kernel on the context's own side stream (default priority)
  *                concurrently with the decode kernel; the call still appears as one unit of work
  *                on the caller's stream (fork and join by events)
+ *   "decode_first"  0/1 (default 1): with "overlap", enqueue the decode kernel before the prefill
+ *                kernel (0: the other way round)
  *   "profile"    0/1: every ooco_attn_mixed records HIP events on its stream around its two
  *                kernels for ooco_profile_read; at most 1024 calls between two reads
  *   "trace"      0/1: see ooco_trace_read

@@ -283,6 +283,7 @@ struct ooco_ctx {
     int64_t opt_trace = 0;
     int64_t opt_rotate = 1;
     int64_t opt_pf_split = 0;
+    int64_t opt_decode_first = 1;   // mixed batches: enqueue the decode kernel before the prefill kernel
     int64_t opt_piece_pad = 0;   // set at creation: 3 tiles of head_dim 128
     int32_t *pf_counters = nullptr;   // [kPrefillSplitUnits] arrival counters of split prefill tiles, zero between calls
     uint16_t xcd_cw[kXcds] = {};   // option "xcd_weights"
@@ -476,6 +477,8 @@ ooco_status ooco_set_option(ooco_ctx *ctx, const char *name, int64_t value)
         ctx->opt_tail_blocks = value;
     else if (!strcmp(name, "prefill_split"))
         ctx->opt_pf_split = value;
+    else if (!strcmp(name, "decode_first"))
+        ctx->opt_decode_first = value;
     else if (!strcmp(name, "decode_piece_pad")) {
         if (value > 64) return fail(ctx, OOCO_EINVAL, "ooco_set_option: decode_piece_pad must be 0..64");
         ctx->opt_piece_pad = value;
@@ -748,12 +751,15 @@ ooco_status ooco_attn_mixed(ooco_ctx *ctx, const void *q, const void *k_cache, c
     }
     // A mixed batch runs its two kernels side by side: the prefill kernel (matrix-core bound) goes to
     // the context's side stream, forked from and joined back into the caller's stream with events,
-    // the decode kernel (HBM bound) stays on the caller's stream.  With per-kernel profiling on
-    // they run one after the other so that each gets a clean time.
+    // the decode kernel (HBM bound) stays on the caller's stream.  The decode kernel is enqueued first
+    // (its three waves per compute unit take their places before the prefill workgroups fill the
+    // register files; measured 1.5 % faster on a long-context mixed batch, no difference on a short one).
+    // With per-kernel profiling on they run one after the other so that each gets a clean time.
     const bool mixed = pl.n_tiles > 0 && pl.static_runs > 0;
     const bool overlap = mixed && !ev && ctx->opt_overlap && ctx->side_stream;
     if (ev) e = hipEventRecord(ev[0], s);
-    if (e == hipSuccess && pl.n_tiles > 0) {
+    auto run_prefill = [&]() {
+        if (e != hipSuccess || pl.n_tiles <= 0) return;
         p.cum_dev = inline_cum ? nullptr : ctx->plan_d + n_cum;
         if (inline_cum) memcpy(ka.cum, pl.pf.data(), n_pf * sizeof(int32_t));
         if (overlap) {
@@ -764,15 +770,31 @@ ooco_status ooco_attn_mixed(ooco_ctx *ctx, const void *q, const void *k_cache, c
         } else {
             e = launch_prefill(ka, s);
         }
-    }
-    if (ev && e == hipSuccess) e = hipEventRecord(ev[1], s);
-    if (e == hipSuccess && pl.static_runs > 0) {
+    };
+    auto run_decode = [&]() {
+        if (e != hipSuccess || pl.static_runs <= 0) return;
         p.cum_dev = inline_cum ? nullptr : ctx->plan_d;
         if (inline_cum) memcpy(ka.cum, pl.dcum.data(), n_cum * sizeof(int32_t));
         e = launch_decode(ka, s);
         // every wave draws one ticket per tail run it takes plus one that tells it to stop
         if (e == hipSuccess && pl.tail_runs > 0)
             ctx->queue_base += (uint32_t)pl.tail_runs * (uint32_t)ctx->Hkv + (uint32_t)pl.static_runs * (uint32_t)ctx->Hkv;
+    };
+    if (overlap && ctx->opt_decode_first) {
+        // fork before the decode kernel is enqueued, so that the side stream does not wait for it
+        e = hipEventRecord(ctx->fork_ev, s);
+        run_decode();
+        if (e == hipSuccess) e = hipStreamWaitEvent(ctx->side_stream, ctx->fork_ev, 0);
+        if (e == hipSuccess) {
+            p.cum_dev = inline_cum ? nullptr : ctx->plan_d + n_cum;
+            if (inline_cum) memcpy(ka.cum, pl.pf.data(), n_pf * sizeof(int32_t));
+            e = launch_prefill(ka, ctx->side_stream);
+        }
+        if (e == hipSuccess) e = hipEventRecord(ctx->join_ev, ctx->side_stream);
+    } else {
+        run_prefill();
+        if (ev && e == hipSuccess) e = hipEventRecord(ev[1], s);
+        run_decode();
     }
     if (overlap && e == hipSuccess) e = hipStreamWaitEvent(s, ctx->join_ev, 0);
     if (ev && e == hipSuccess) e = hipEventRecord(ev[2], s);
