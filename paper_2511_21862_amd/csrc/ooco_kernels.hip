@@ -267,11 +267,18 @@ __global__ __launch_bounds__(64, 2) void decode_kernel(const KernArgs a)
     bool first_piece = true;
 
   for (;;) {   // the wave's own run first, then tail runs by ticket
-    // The ticket for the next tail run is drawn now and looked at after this run, so that the
-    // round trip of the atomic overlaps the streaming.
+    // The ticket for the next tail run is drawn when the last piece of this run has been streamed (whoever
+    // is done first gets the next run) and looked at after that piece's epilogue, which covers the round
+    // trip of the atomic.  (Every wave ends by drawing a ticket that tells it to stop; atomics on one address
+    // are served one after the other, about 13 ns each on MI355X, which is why the tail only pays on long
+    // kernels.)
     unsigned ticket = 0xFFFFFFFFu;
-    if (tail_tasks && lane == 0)
-        ticket = __hip_atomic_fetch_add(p.queue, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - p.queue_base;
+    bool drawn = false;
+    auto draw = [&]() {
+        if (lane == 0)
+            ticket = __hip_atomic_fetch_add(p.queue, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - p.queue_base;
+        drawn = true;
+    };
     const int head = kvh * g + col;
     int lo, hi;
     run_bounds(L, run, lo, hi);
@@ -428,6 +435,7 @@ __global__ __launch_bounds__(64, 2) void decode_kernel(const KernArgs a)
         }
 
         if (trace && stop == hi && lane == 0) trace[2] = wall_clock64();   // end of streaming
+        if (tail_tasks && stop == hi) draw();
         float ltot = rows_sum(lsum);
         bool store_out = whole;
         if (!whole) {
@@ -533,6 +541,7 @@ __global__ __launch_bounds__(64, 2) void decode_kernel(const KernArgs a)
         ++seq;
     }
     if (!tail_tasks) break;
+    if (!drawn) draw();   // (a run that held no block)
     ticket = __builtin_amdgcn_readfirstlane(ticket);
     if (ticket >= tail_tasks) break;
     run = p.static_runs + (int)(ticket / (unsigned)p.Hkv);
