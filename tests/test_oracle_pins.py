@@ -14,7 +14,8 @@ from paper_2511_21862_amd import workloads as W
 GOLD = os.path.join(os.path.dirname(__file__), "golden")
 
 
-def run(b, fn=ref_numpy.attn_mixed, **kw):
+def run(b, fn=None, **kw):
+    fn = fn or ref_numpy.attn_mixed   # (looked up at call time: tests/test_oracle_mutants.py swaps it)
     return fn(b.q, b.k_cache, b.v_cache, b.block_tables, b.seq_lens, b.query_start_loc, b.ctx_lens, **kw)
 
 
@@ -59,6 +60,16 @@ def test_random_tiny_cases_match_dense_bruteforce(seed):
 
 
 # --------------------------------------------------------------------------- library special cases
+@pytest.mark.parametrize("Hq,Hkv", [(8, 2), (8, 4), (6, 3), (12, 4), (14, 2)])
+def test_grouped_head_shapes_match_dense_bruteforce(Hq, Hkv):
+    """1 < Hkv < Hq, where a contiguous and an interleaved head-to-kv-head mapping differ."""
+    b = W.build_batch(Hq=Hq, Hkv=Hkv, hd=16, q_lens=[1, 7, 1], ctx_lens=[21, 18, 0], num_blocks=12, seed=Hq * 31 + Hkv,
+                      poison=True)
+    o = run(b)
+    assert np.abs(o - run(b, dense_bruteforce.attn_mixed_dense)).max() <= 1e-12
+    assert np.abs(o - run(b, ref_c.attn_mixed)).max() <= 1e-12
+
+
 def test_prefill_without_context_equals_torch_sdpa_causal():
     b = tiny(1, Hq=2, Hkv=2, hd=16, q_lens=(23,), ctx_lens=(0,))
     k, v = W.gather_logical(b, 0)
