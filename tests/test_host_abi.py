@@ -280,6 +280,13 @@ def test_mix_decoding_select_equals_the_oracle():
     assert list(got["selected"]) == [True, False, True, True, True, False] and got["latency"] == pytest.approx(594e-6, rel=1e-12)
     with pytest.raises(B.OocoError):
         B.ooco_mix_decoding_select(mp, 32, 8, 128, 1e-3, [0], [5], [])
+    # the bound is inclusive in both phases (Algorithm 2 admits on L <= S): bounds that equal a predicted latency
+    on, off = [700, 1500], [900, 300, 5000, 1200, 650]
+    S = B.ooco_predict_latency(p, 32, 8, 128, np.arange(4), np.array(on + [off[2]]) - 1)["latency"]
+    assert S == mix_select.latency(p, 32, 8, 128, on + [off[2]])
+    assert list(B.ooco_mix_decoding_select(p, 32, 8, 128, S, on, off, [2])["selected"]) == [False, False, True, False, False]
+    S = mix_select.latency(p, 32, 8, 128, on + [300, 650, 900])
+    assert list(B.ooco_mix_decoding_select(p, 32, 8, 128, S, on, off, [])["selected"]) == [True, True, False, False, True]
 
 
 # ----------------------------------------------------------------------------- migration decision, eviction rule

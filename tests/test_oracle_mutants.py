@@ -101,3 +101,89 @@ def test_a_planted_mistake_is_rejected(monkeypatch, case):
         assert any(rejects(pin) for pin in BRUTE), f"'{name}' passes the brute-force comparison"
     caught = [pin.__name__ for pin in OTHER if rejects(pin)]
     assert caught, f"'{name}' passes every pin that does not use the brute force"
+
+
+# ------------------------------------------------------------------------------------------------------------
+# The same for the other oracles: KV append, the latency model (Table 2, Equation 1), Mix Decoding Selection
+# (Algorithm 2), the migration decision (Algorithm 1) and the eviction rule.  A mutant must be rejected by at
+# least one of the module's pins.
+from oracle import migration, mix_select, perf_model  # noqa: E402
+
+APPEND_PINS = [P.test_kv_append_offsets_of_a_hand_worked_example, P.test_kv_append_rebuilds_the_cache_and_touches_nothing_else,
+               P.test_kv_append_reads_back_through_the_independent_gather]
+MODEL_PINS = [P.test_model_operator_counts_equal_hand_evaluated_table2_rows, P.test_model_equation1_regimes_and_crossing,
+              P.test_model_iteration_is_the_sum_of_operators_plus_overheads,
+              P.test_model_causal_count_is_the_number_of_visible_pairs]
+MIX_PINS = [P.test_mix_selection_hand_worked_example, P.test_mix_selection_equal_lengths_closed_form,
+            P.test_mix_selection_invariants_by_exhaustive_scan, P.test_mix_selection_bounds_are_inclusive]
+MIG_PINS = [P.test_migration_hand_worked_examples, P.test_migration_preference_closed_forms_in_the_memory_bound_regime,
+            P.test_migration_preference_is_the_maximum_by_direct_evaluation, P.test_eviction_victims_against_every_subset]
+
+# (module, function, pins, name, text of the oracle, text of the mistake)
+OTHER_MUTANTS = [
+    (ref_numpy, "kv_append", APPEND_PINS, "slot from the row index instead of the position", "), pos % BS", "), t % BS"),
+    (ref_numpy, "kv_append", APPEND_PINS, "position ignores the cached prefix", "pos = int(ctx_lens[i]) + t", "pos = t"),
+    (ref_numpy, "kv_append", APPEND_PINS, "K written in V's layout", "k_cache[blk, kv, d // 8, slot, d % 8]",
+     "k_cache[blk, kv, d % (hd // 8), slot, d // (hd // 8)]"),
+    (ref_numpy, "kv_append", APPEND_PINS, "row of the wrong sequence", "k_new[q0 + t, kv, d]", "k_new[t, kv, d]"),
+    (ref_numpy, "kv_append", APPEND_PINS, "V of the neighbouring kv head", "v_new[q0 + t, kv, d]", "v_new[q0 + t, (kv + 1) % Hkv, d]"),
+    (perf_model, "attention_flops", MODEL_PINS, "one of the two matrix products forgotten", "4.0 *", "2.0 *"),
+    (perf_model, "attention_bytes", MODEL_PINS, "K/V bytes per query head instead of per kv head", "S_kv * D_h * Hkv / Hq", "S_kv * D_h"),
+    (perf_model, "attention_bytes", MODEL_PINS, "only K counted", "2.0 * d * (S_q * D_h + S_kv * D_h * Hkv / Hq)",
+     "d * (2.0 * S_q * D_h + S_kv * D_h * Hkv / Hq)"),
+    (perf_model, "attention_bytes", MODEL_PINS, "group ratio upside down", "Hkv / Hq", "Hq / Hkv"),
+    (perf_model, "op_latency", MODEL_PINS, "sum instead of maximum", "max(flops / F, nbytes / M)", "flops / F + nbytes / M"),
+    (perf_model, "op_latency", MODEL_PINS, "minimum instead of maximum", "max(flops / F, nbytes / M)", "min(flops / F, nbytes / M)"),
+    (perf_model, "attention_flops_causal", MODEL_PINS, "own key not counted", "pairs += ctx + t + 1", "pairs += ctx + t"),
+    (perf_model, "predict", MODEL_PINS, "decode rate used for prefill", 'F = params["F_ap"] if ql > 1 else params["F_ad"]',
+     'F = params["F_ad"]'),
+    (perf_model, "predict", MODEL_PINS, "overheads charged whether or not the kind of work is there",
+     '(params["O_p"] if any_p else 0.0) + (params["O_d"] if any_d else 0.0)', 'params["O_p"] + params["O_d"]'),
+    (perf_model, "predict", MODEL_PINS, "overhead left out", "latency=t_prefill + t_decode + overhead", "latency=t_prefill + t_decode"),
+    (perf_model, "predict", MODEL_PINS, "S_kv without the new tokens", "attention_bytes(Hq, Hkv, hd, ql, ctx + ql, d)",
+     "attention_bytes(Hq, Hkv, hd, ql, ctx, d)"),
+    (mix_select, "mix_decoding_select", MIX_PINS, "a request that reaches the bound exactly is refused",
+     "batch + [int(offline_lens[r])]) <= S", "batch + [int(offline_lens[r])]) < S"),
+    # (not planted: letting refused requests back into the sorted phase changes nothing, because the predictor
+    # grows with a request's length: whatever was refused once stops the prefix exactly where the oracle stops)
+    (mix_select, "mix_decoding_select", MIX_PINS, "sorted by descending length", "key=lambda i: (int(offline_lens[i]), i))",
+     "key=lambda i: (-int(offline_lens[i]), i))"),
+    (mix_select, "mix_decoding_select", MIX_PINS, "prefix one short", "for i in rest[:lo]:", "for i in rest[:max(lo - 1, 0)]:"),
+    (mix_select, "mix_decoding_select", MIX_PINS, "admitted request not added to the batch", "            batch.append(int(offline_lens[r]))\n",
+     "            pass\n"),
+    (mix_select, "mix_decoding_select", MIX_PINS, "bisection keeps the first admissible prefix", "                lo = mid\n",
+     "                lo = mid\n                break\n"),
+    (mix_select, "latency", MIX_PINS, "length counted without the new token twice", "[int(n) - 1 for n in lens]", "[int(n) - 2 for n in lens]"),
+    (migration, "migration_preference", MIG_PINS, "headroom test inverted", "if not (L(B) < S and all_included):", "if L(B) < S and all_included:"),
+    (migration, "migration_preference", MIG_PINS, "node not required to be drained", "L(B) < S and all_included", "L(B) < S"),
+    (migration, "migration_preference", MIG_PINS, "memory not checked when saturated",
+     "if L(B + [l]) <= S and u_mem(B + [l], block_size, capacity_blocks) <= 1.0]", "if L(B + [l]) <= S]"),
+    (migration, "migration_preference", MIG_PINS, "shortest that fits instead of longest (saturated)",
+     'pref=max(fits) if fits else None, branch="saturated"', 'pref=min(fits) if fits else None, branch="saturated"'),
+    (migration, "migration_preference", MIG_PINS, "one request assumed instead of the missing n", "if L(B + [l] * n) <= S]", "if L(B + [l]) <= S]"),
+    (migration, "migration_preference", MIG_PINS, "saturation test off by one", "if len(B) >= bs_sat:", "if len(B) > bs_sat:"),
+    (migration, "migration_preference", MIG_PINS, "longest instead of shortest when saturation is out of reach",
+     'return dict(pref=len_min, branch="shortest")', 'return dict(pref=len_max, branch="shortest")'),
+    (migration, "migration_select", MIG_PINS, "longest first instead of closest to the preference",
+     "key=lambda i: (abs(int(relaxed_lens[i]) - pref), int(relaxed_lens[i]), i))", "key=lambda i: (-int(relaxed_lens[i]), i))"),
+    (migration, "migration_select", MIG_PINS, "batch not grown by what was taken", "            B = cand\n", ""),
+    (migration, "eviction_victims", MIG_PINS, "long requests evicted when memory-bound", "compute_bound = batch_size >= bs_sat",
+     "compute_bound = batch_size < bs_sat"),
+    (migration, "eviction_victims", MIG_PINS, "victims that are not needed are kept", "            if freed - b >= need_blocks:",
+     "            if False:"),
+    (migration, "eviction_victims", MIG_PINS, "stops one victim early", "        if freed >= need_blocks:\n            break",
+     "        if freed + blocks(offline_lens[i], block_size) >= need_blocks:\n            break"),
+    (migration, "blocks", MIG_PINS, "blocks rounded down", "(int(length) + block_size - 1) // block_size", "int(length) // block_size"),
+]
+
+
+@pytest.mark.parametrize("case", OTHER_MUTANTS, ids=[f"{m[1]}__" + re.sub(r"\W+", "_", m[3]) for m in OTHER_MUTANTS])
+def test_a_planted_mistake_in_the_other_oracles_is_rejected(monkeypatch, case):
+    module, func, pins, name, old, new = case
+    src = inspect.getsource(getattr(module, func))
+    assert src.count(old) == 1, f"{func} no longer contains {old!r} exactly once"
+    ns = dict(vars(module))
+    exec(compile(src.replace(old, new), "<mutant>", "exec"), ns)
+    monkeypatch.setattr(module, func, ns[func])
+    caught = [pin.__name__ for pin in pins if rejects(pin)]
+    assert caught, f"'{name}' in {func} passes every pin of its module"

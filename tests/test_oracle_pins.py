@@ -493,6 +493,21 @@ def test_mix_selection_equal_lengths_closed_form():
         assert sum(r["selected"]) == want, (n, S_us, cand)
 
 
+def test_mix_selection_bounds_are_inclusive():
+    """Algorithm 2 admits on L <= S in both phases: a bound that equals a predicted latency bit for bit admits
+    that batch and nothing beyond it."""
+    p = dict(F_ap=9e14, F_ad=2e14, M_a=6e12, O_p=1e-5, O_d=9e-6)
+    L = lambda lens: mix_select.latency(p, 32, 8, 128, lens)
+    on, off = [700, 1500], [900, 300, 5000, 1200, 650]
+    # random phase: the first request looked at lands exactly on the bound
+    r = mix_select.mix_decoding_select(p, 32, 8, 128, L(on + [off[2]]), on, off, [2])
+    assert r["selected"] == [False, False, True, False, False] and r["latency"] == L(on + [off[2]])
+    # sorted phase: the bound is the latency of the three shortest candidates
+    S = L(on + [300, 650, 900])
+    r = mix_select.mix_decoding_select(p, 32, 8, 128, S, on, off, [])
+    assert r["selected"] == [True, True, False, False, True] and r["latency"] == S
+
+
 def test_mix_selection_invariants_by_exhaustive_scan():
     rng = np.random.default_rng(8)
     p = dict(F_ap=9e14, F_ad=2e14, M_a=6e12, O_p=1e-5, O_d=9e-6)
