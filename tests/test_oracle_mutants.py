@@ -187,3 +187,43 @@ def test_a_planted_mistake_in_the_other_oracles_is_rejected(monkeypatch, case):
     monkeypatch.setattr(module, func, ns[func])
     caught = [pin.__name__ for pin in pins if rejects(pin)]
     assert caught, f"'{name}' in {func} passes every pin of its module"
+
+
+# ------------------------------------------------------------------------------------------------------------
+# Would the GPU parity tests notice?  The kernels are held to max-abs 2e-2 / mean-abs 2e-3 / relative L2 1e-2
+# against the oracle.  On the inputs of the GPU parity cases (tests/test_gpu_parity.py, the smaller ones) every
+# planted mistake, with its output rounded to bf16 like a kernel's, must break those gates: the tolerance is
+# wide enough for bf16 rounding and not wide enough to hide a wrong kernel.
+def test_the_parity_gates_on_the_gpu_cases_reject_every_planted_mistake():
+    import gpu_util
+    import test_gpu_parity as G
+    from paper_2511_21862_amd import workloads as W
+
+    cases = []
+    for case in (0, 9, 6, 5, 4, 7, 1):
+        Hq, Hkv, hd, ql, ctx = G.RAGGED[case]
+        nblk = int(sum((c + q + 15) // 16 for c, q in zip(ctx, ql))) + 7
+        b = W.build_batch(Hq=Hq, Hkv=Hkv, hd=hd, q_lens=ql, ctx_lens=ctx, num_blocks=nblk, seed=1000 + case, poison=True)
+        cases.append((case, b, P.run(b)))
+    # the oracle itself, rounded to bf16, passes
+    for case, b, ref in cases:
+        e = gpu_util.errors(W.f32_to_bf16_bits(ref.astype(np.float32)), ref)
+        assert e["max_abs"] <= gpu_util.MAX_ABS / 2 and e["mean_abs"] <= gpu_util.MEAN_ABS / 2 and e["rel_l2"] <= gpu_util.REL_L2 / 2
+    for m in MUTANTS:
+        if len(m) > 3:
+            continue
+        fn = mutant_of(m[1], m[2])
+        broke = None
+        for case, b, ref in cases:
+            with np.errstate(all="ignore"):
+                try:
+                    out = P.run(b, fn)
+                except (ValueError, IndexError):
+                    broke = case
+                    break
+            e = gpu_util.errors(W.f32_to_bf16_bits(np.nan_to_num(out, nan=np.inf).astype(np.float32)), ref)
+            if not (e["finite"] and e["max_abs"] <= gpu_util.MAX_ABS and e["mean_abs"] <= gpu_util.MEAN_ABS
+                    and e["rel_l2"] <= gpu_util.REL_L2):
+                broke = case
+                break
+        assert broke is not None, f"'{m[0]}' stays within the parity gates on every case"
