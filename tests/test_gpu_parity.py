@@ -223,6 +223,43 @@ def test_block_copy_bit_exact_round_trip():
                           torch.zeros(0, dtype=torch.int64, device="cuda"))
 
 
+@pytest.mark.parametrize("variant", [10, 11, 20, 21, 40, 41, 80, 81])
+def test_block_copy_variants_are_bit_exact(variant):
+    # option "copy_variant": 16-byte vectors per thread x 10 + (1 = non-temporal accesses)
+    b = W.build_batch(Hq=32, Hkv=8, hd=128, q_lens=[1, 1], ctx_lens=[700, 45], num_blocks=80, seed=19)
+    say(f"case: block copy variant {variant}")
+    d = W.to_device(b)
+    src = W.victim_block_ids(b, [0, 1])
+    n = len(src)
+    dst = np.random.default_rng(variant).permutation(n + 3)[:n].astype(np.int64)
+    ks = torch.full((n + 3,) + tuple(d.k_cache.shape[1:]), 3.0, dtype=torch.bfloat16, device="cuda")
+    vs = torch.full((n + 3,) + tuple(d.v_cache.shape[1:]), 3.0, dtype=torch.bfloat16, device="cuda")
+    with B.Context(b.Hq, b.Hkv, b.hd, b.BS, b.num_blocks, b.max_blocks_per_seq) as ctx:
+        ctx.set_option("copy_variant", variant)
+        ctx.kv_block_copy(d.k_cache, d.v_cache, ks, vs, torch.from_numpy(src).cuda(), torch.from_numpy(dst).cuda())
+        torch.cuda.synchronize()
+        ctx.set_option("copy_variant", 0)
+    kh = np.full(ks.shape, W.f32_to_bf16_bits(np.float32([3.0]))[0], np.uint16)
+    vh = kh.reshape(-1)[: vs.numel()].reshape(vs.shape).copy()
+    ref_c.block_copy(b.k_cache, b.v_cache, kh, vh, src, dst)
+    assert np.array_equal(ks.view(torch.int16).cpu().numpy().view(np.uint16), kh)
+    assert np.array_equal(vs.view(torch.int16).cpu().numpy().view(np.uint16), vh)
+
+
+@pytest.mark.parametrize("opts", [{"decode_nbi": 2}, {"decode_nbi": 4}, {"rotate_heads": 0}, {"decode_first": 0},
+                                  {"overlap": 0}, {"decode_nbi": 2, "decode_segments": 9, "decode_tail_pct": 20,
+                                                   "decode_tail_blocks": 3}],
+                         ids=lambda o: "-".join(f"{k}{v}" for k, v in o.items()))
+def test_tuning_knobs_agree(opts):
+    # the knobs kept for experiments select other kernel instantiations or launch orders: same results
+    b = W.build_batch(Hq=32, Hkv=8, hd=128, q_lens=[1, 1, 70, 1, 1, 0, 1], ctx_lens=[1500, 31, 200, 0, 16, 9, 333],
+                      num_blocks=160, seed=91, poison=True)
+    say(f"case: knobs {opts}")
+    assert_parity(run_gpu(b, options=opts), oracle(b), f"knobs {opts}")
+    b64 = W.build_batch(Hq=8, Hkv=2, hd=64, q_lens=[1, 1, 1], ctx_lens=[900, 17, 64], num_blocks=70, seed=92, poison=True)
+    assert_parity(run_gpu(b64, options=opts), oracle(b64), f"knobs {opts}, head_dim 64")
+
+
 def test_errors_surface_through_the_abi():
     b = W.config1()
     d = W.to_device(b)
