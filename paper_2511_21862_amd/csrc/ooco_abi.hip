@@ -283,6 +283,7 @@ struct ooco_ctx {
     int64_t opt_trace = 0;
     int64_t opt_rotate = 1;
     int64_t opt_pf_split = 0;
+    int opt_copy_variant = 0;       // block copy: 10 x vectors per thread + non-temporal flag, 0 = default
     int64_t opt_decode_first = 1;   // mixed batches: enqueue the decode kernel before the prefill kernel
     int64_t opt_piece_pad = 0;   // set at creation: 3 tiles of head_dim 128
     int32_t *pf_counters = nullptr;   // [kPrefillSplitUnits] arrival counters of split prefill tiles, zero between calls
@@ -491,7 +492,7 @@ ooco_status ooco_set_option(ooco_ctx *ctx, const char *name, int64_t value)
         ctx->opt_trace = value;
         return OOCO_OK;
     } else if (!strcmp(name, "copy_variant")) {
-        g_copy_variant = (int)value;
+        ctx->opt_copy_variant = (int)value;
         return OOCO_OK;
     } else if (!strcmp(name, "overlap")) {
         ctx->opt_overlap = value;
@@ -819,7 +820,7 @@ ooco_status ooco_kv_block_copy(ooco_ctx *ctx, const void *k_src, const void *v_s
         return fail(ctx, OOCO_EINVAL, "ooco_kv_block_copy: num_pairs=%lld too large", (long long)num_pairs);
     const int64_t block_bytes = (int64_t)ctx->Hkv * ctx->BS * ctx->hd * 2;
     hipError_t e = launch_block_copy(k_src, v_src, k_dst, v_dst, src_block_ids, dst_block_ids, num_pairs, block_bytes,
-                                     reinterpret_cast<hipStream_t>(stream));
+                                     ctx->opt_copy_variant, reinterpret_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail(ctx, OOCO_EHIP, "ooco_kv_block_copy: kernel launch: %s", hipGetErrorString(e));
     return OOCO_OK;
 }

@@ -81,15 +81,15 @@ static_assert(sizeof(KernArgs) <= 4096, "kernel arguments must stay within 4 KiB
 // unless a.p.cum_dev is set.  Each returns the hipError_t of its launch.
 hipError_t launch_decode(const KernArgs &a, hipStream_t s);
 hipError_t launch_prefill(const KernArgs &a, hipStream_t s);
+// variant: tuning knob of the block-copy kernel (option "copy_variant"): 10 x 16-byte vectors per thread
+// + 1 for non-temporal accesses; 0 = default
 hipError_t launch_block_copy(const void *k_src, const void *v_src, void *k_dst, void *v_dst,
                              const int64_t *src_ids, const int64_t *dst_ids, int64_t num_pairs,
-                             int64_t block_bytes, hipStream_t s);
+                             int64_t block_bytes, int variant, hipStream_t s);
 
 hipError_t launch_kv_append(const void *k_new, const void *v_new, void *k_cache, void *v_cache, const int32_t *block_tables,
                             const int32_t *query_start_loc, const int32_t *ctx_lens, int num_seqs, int total_q, int Hkv,
                             int hd, int max_blocks_per_seq, int64_t num_blocks, hipStream_t s);
-
-extern int g_copy_variant;   // tuning knob of the block-copy kernel (option "copy_variant")
 
 // Query rows of one prefill tile for a GQA group of g heads.
 __host__ __device__ inline int32_t prefill_tile_rows(int32_t g) { return kPrefillCols / g > 0 ? kPrefillCols / g : 1; }

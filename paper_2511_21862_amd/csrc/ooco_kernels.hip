@@ -1099,7 +1099,6 @@ hipError_t launch_kv_append(const void *k_new, const void *v_new, void *k_cache,
     return hipGetLastError();
 }
 
-int g_copy_variant = 0;   // tuning: 10*vectors per thread + non-temporal flag (0 = default)
 
 // ------------------------------------------------------------------------------------------
 hipError_t launch_decode(const KernArgs &a, hipStream_t s)
@@ -1131,11 +1130,11 @@ hipError_t launch_prefill(const KernArgs &a, hipStream_t s)
 }
 
 hipError_t launch_block_copy(const void *k_src, const void *v_src, void *k_dst, void *v_dst, const int64_t *src_ids,
-                             const int64_t *dst_ids, int64_t num_pairs, int64_t block_bytes, hipStream_t s)
+                             const int64_t *dst_ids, int64_t num_pairs, int64_t block_bytes, int variant, hipStream_t s)
 {
     if (num_pairs == 0) return hipSuccess;
     const int64_t block_vecs = block_bytes / 16;
-    const int variant = g_copy_variant ? g_copy_variant : 41;
+    if (variant == 0) variant = 41;
     const int vpt = variant / 10;
     const int per_wg = kCopyThreads * vpt;
     const int slices = (int)((block_vecs + per_wg - 1) / per_wg);

@@ -238,7 +238,6 @@ def test_block_copy_variants_are_bit_exact(variant):
         ctx.set_option("copy_variant", variant)
         ctx.kv_block_copy(d.k_cache, d.v_cache, ks, vs, torch.from_numpy(src).cuda(), torch.from_numpy(dst).cuda())
         torch.cuda.synchronize()
-        ctx.set_option("copy_variant", 0)
     kh = np.full(ks.shape, W.f32_to_bf16_bits(np.float32([3.0]))[0], np.uint16)
     vh = kh.reshape(-1)[: vs.numel()].reshape(vs.shape).copy()
     ref_c.block_copy(b.k_cache, b.v_cache, kh, vh, src, dst)
