@@ -228,8 +228,9 @@ ooco_status ooco_plan_info(const ooco_ctx *ctx, int64_t *decode_waves, int64_t *
  * Same context + same plan + same inputs give bit-identical output on every call (no
  * floating-point atomics).  One context serves one stream at a time.
  * A planned call enqueues only kernels and event records / waits, so it can be recorded into a HIP
- * graph (stream capture) and replayed; keep "profile", "trace" and "decode_tail_pct" off for
- * captured calls (the dynamic tail's ticket base is fixed at enqueue time).
+ * graph (stream capture) and replayed; keep "profile" and "trace" off for captured calls.  A plan
+ * with a dynamic tail ("decode_tail_pct") is refused on a capturing stream with OOCO_EINVAL (the
+ * tail's ticket base is fixed at enqueue time).
  * Errors: OOCO_EINVAL for null pointers / negative sizes, OOCO_ESHAPE when sizes contradict
  * the plan, OOCO_EHIP when a launch fails (message holds hipGetErrorString). */
 ooco_status ooco_attn_mixed(ooco_ctx *ctx, const void *q /*DEVICE*/, const void *k_cache /*DEVICE*/,

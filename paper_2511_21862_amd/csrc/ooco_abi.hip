@@ -672,9 +672,14 @@ ooco_status ooco_attn_mixed(ooco_ctx *ctx, const void *q, const void *k_cache, c
         ctx->plan_one_shot = true;
     }
     const HostPlan &pl = ctx->plan;
-    if (pl.num_seqs != num_seqs || pl.total_q != total_q_tokens)
+    if (pl.num_seqs != num_seqs || pl.total_q != total_q_tokens) {
+        if (ctx->plan_one_shot) {   // the plan made above from the device's lengths does not outlive this call
+            ctx->plan_one_shot = false;
+            ctx->plan_valid = false;
+        }
         return fail(ctx, OOCO_ESHAPE, "ooco_attn_mixed: plan was made for %d sequences / %d query tokens, call has %d / %d",
                     pl.num_seqs, pl.total_q, num_seqs, total_q_tokens);
+    }
 
     // The cumulative arrays ride in the kernel arguments; only very large batches need a copy.
     const size_t n_cum = (size_t)num_seqs + 1, n_pf = pl.pf.size();
@@ -736,6 +741,13 @@ ooco_status ooco_attn_mixed(ooco_ctx *ctx, const void *q, const void *k_cache, c
     p.rotate_heads = (int32_t)ctx->opt_rotate;
     for (int k = 0; k < kXcds; ++k) p.xcd_cw[k] = pl.cw[k];
 
+    if (pl.tail_runs > 0) {
+        // the ticket base of the dynamic tail is fixed when the call is enqueued: a replayed graph would hand out
+        // tickets that lie beyond it and leave the tail runs undone
+        hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(s, &cs) == hipSuccess && cs != hipStreamCaptureStatusNone)
+            return fail(ctx, OOCO_EINVAL, "ooco_attn_mixed: a plan with a dynamic tail (decode_tail_pct) cannot be captured into a graph");
+    }
     hipEvent_t *ev = nullptr;
     hipError_t e = hipSuccess;
     if (ctx->opt_profile) {
