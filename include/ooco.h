@@ -140,7 +140,7 @@ const char *ooco_last_error(const ooco_ctx *ctx);
  *                kernels for ooco_profile_read; at most 1024 calls between two reads
  *   "trace"      0/1: see ooco_trace_read
  * Tuning knobs kept for experiments (defaults are the measured best): "decode_nbi" (KV blocks per
- * softmax step of the decode kernel: 1, 2 or 4; 0 = default), "rotate_heads" (0/1: rotate the kv
+ * softmax step of the decode kernel: 1, 2 or 4; 0 = default: 1 for head_dim 128, 2 for head_dim 64), "rotate_heads" (0/1: rotate the kv
  * head of a decode wave by its run index, default 1), "copy_variant" (block copy: 10 * 16-byte
  * vectors per thread + 1 for non-temporal accesses; 0 = default 41; process-wide). */
 ooco_status ooco_set_option(ooco_ctx *ctx, const char *name, int64_t value);

@@ -1105,15 +1105,24 @@ hipError_t launch_decode(const KernArgs &a, hipStream_t s)
 {
     if (a.p.static_runs <= 0 || a.p.dec_blocks <= 0) return hipSuccess;
     const dim3 grid((unsigned)((int64_t)a.p.static_runs * a.p.Hkv)), block(64);
+    // KV blocks per softmax step: a wave keeps one step's tiles in flight, and 8 KiB per wave is what it takes
+    // to saturate HBM with three waves per compute unit: one block for head_dim 128, two for head_dim 64
+    // (measured: 56.9 % -> 72.2 % of the HBM peak on 256 sequences with head_dim 64; four blocks: 69.8 %)
+    const int nbi = a.p.nbi ? a.p.nbi : (a.p.hd == 64 ? 2 : 1);
     if (a.p.hd == 128) {
-        if (a.p.nbi == 2)
+        if (nbi == 2)
             hipLaunchKernelGGL((decode_kernel<128, 2>), grid, block, 0, s, a);
-        else if (a.p.nbi == 4)
+        else if (nbi == 4)
             hipLaunchKernelGGL((decode_kernel<128, 4>), grid, block, 0, s, a);
         else
             hipLaunchKernelGGL((decode_kernel<128, 1>), grid, block, 0, s, a);
     } else {
-        hipLaunchKernelGGL((decode_kernel<64, 1>), grid, block, 0, s, a);
+        if (nbi == 2)
+            hipLaunchKernelGGL((decode_kernel<64, 2>), grid, block, 0, s, a);
+        else if (nbi == 4)
+            hipLaunchKernelGGL((decode_kernel<64, 4>), grid, block, 0, s, a);
+        else
+            hipLaunchKernelGGL((decode_kernel<64, 1>), grid, block, 0, s, a);
     }
     return hipGetLastError();
 }

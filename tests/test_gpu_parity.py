@@ -245,7 +245,7 @@ def test_block_copy_variants_are_bit_exact(variant):
     assert np.array_equal(vs.view(torch.int16).cpu().numpy().view(np.uint16), vh)
 
 
-@pytest.mark.parametrize("opts", [{"decode_nbi": 2}, {"decode_nbi": 4}, {"rotate_heads": 0}, {"decode_first": 0},
+@pytest.mark.parametrize("opts", [{"decode_nbi": 1}, {"decode_nbi": 2}, {"decode_nbi": 4}, {"rotate_heads": 0}, {"decode_first": 0},
                                   {"overlap": 0}, {"decode_nbi": 2, "decode_segments": 9, "decode_tail_pct": 20,
                                                    "decode_tail_blocks": 3}],
                          ids=lambda o: "-".join(f"{k}{v}" for k, v in o.items()))
