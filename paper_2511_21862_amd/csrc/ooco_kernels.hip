@@ -335,6 +335,10 @@ __global__ __launch_bounds__(64, 2) void decode_kernel(const KernArgs a)
             const int pb = __builtin_amdgcn_readlane(idv, j - wbase);
             return ((int64_t)pb * p.Hkv + kvh) * tile_elems;
         };
+        // K and V tiles are read once per kv head and never again in this launch: they are loaded with the
+        // non-temporal policy (`nt`), so that the stream does not push other data out of the caches on its way
+        // through them.  Measured on MI355X: 64 sequences 115.7 -> 103.3 us, 512 sequences 1.149 -> 1.030 ms
+        // (6.1 -> 6.8 TB/s).
         // Loads are issued unconditionally (steps past the end re-read the last block, an L2 hit)
         // so that every step has the same number of loads in flight and the waits before the
         // MFMAs can leave the younger loads outstanding.
@@ -344,7 +348,7 @@ __global__ __launch_bounds__(64, 2) void decode_kernel(const KernArgs a)
                 offs[u] = tile_off(min(step * NBI + u, nblk - 1));
                 const u32x4 *kp = reinterpret_cast<const u32x4 *>(p.k_cache + offs[u]);
 #pragma unroll
-                for (int c = 0; c < KC; ++c) kreg[u][c] = kp[c * 64 + lane];
+                for (int c = 0; c < KC; ++c) kreg[u][c] = __builtin_nontemporal_load(&kp[c * 64 + lane]);
             }
         };
         auto issue_v = [&]() {
@@ -352,7 +356,7 @@ __global__ __launch_bounds__(64, 2) void decode_kernel(const KernArgs a)
             for (int u = 0; u < NBI; ++u) {
                 const u32x2 *vp = reinterpret_cast<const u32x2 *>(p.v_cache + offs[u]);
 #pragma unroll
-                for (int nb = 0; nb < NB; ++nb) vreg[u][nb] = vp[(nb * 16 + col) * 4 + kq];
+                for (int nb = 0; nb < NB; ++nb) vreg[u][nb] = __builtin_nontemporal_load(&vp[(nb * 16 + col) * 4 + kq]);
             }
         };
 
