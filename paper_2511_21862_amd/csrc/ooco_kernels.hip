@@ -1060,12 +1060,18 @@ __global__ __launch_bounds__(64) void kv_append_kernel(const uint16_t *k_new, co
     if (blk < 0 || blk >= num_blocks) return;           // id outside the pool: nothing is written
     const int slot = pos % kBlockSize;
     const int row_elems = Hkv * hd;
-    // K: chunk c = (kv head, group of 8 dims) -> cache chunk ((blk*Hkv + kvh)*(hd/8) + d8)*16 + slot
-    {
-        const int hd8 = hd / 8;
-        const u32x4 *src = reinterpret_cast<const u32x4 *>(k_new + (int64_t)row * row_elems);
-        u32x4 *dst = reinterpret_cast<u32x4 *>(k_cache) + (int64_t)blk * Hkv * hd8 * kBlockSize + slot;
-        for (int c = lane; c < Hkv * hd8; c += 64) dst[(int64_t)c * kBlockSize] = src[c];
+    // K: chunk c = (kv head, group of 8 dims) -> cache chunk ((blk*Hkv + kvh)*(hd/8) + d8)*16 + slot.  Four
+    // consecutive slots of a chunk row are one 64-byte line: the rows of this sequence that fall into one line
+    // are written together by the wave of the first of them (lane = 4 * chunk + row), so that whole lines
+    // leave the compute unit instead of 16-byte pieces 256 bytes apart.
+    if ((slot & 3) == 0 || t == 0) {
+        const int chunks = Hkv * (hd / 8);
+        const int nr = min(min(4 - (slot & 3), q_len - t), total_q - row);   // rows row .. row+nr-1 share the line
+        const int r = lane & 3;
+        const u32x4 *src = reinterpret_cast<const u32x4 *>(k_new + (int64_t)(row + min(r, nr - 1)) * row_elems);
+        u32x4 *dst = reinterpret_cast<u32x4 *>(k_cache) + (int64_t)blk * chunks * kBlockSize + slot + r;
+        if (r < nr)
+            for (int c = lane >> 2; c < chunks; c += 16) dst[(int64_t)c * kBlockSize] = src[c];
     }
     // V: the group = rows t0 .. t0+nrow-1 of this sequence that share the block; this wave is member j
     const int t0 = max(0, t - slot);
