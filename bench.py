@@ -1,7 +1,10 @@
 #!/usr/bin/env python3
 """Benchmark of the mixed-batch paged-attention step on ONE MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2|cfg3|cfg3-prefill|cfg4|cfg4-copy|cfg4-copy-seq|cfg5|cfg5-prefill|cfg3-append|cfg5-append|cfg4-preempt]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5|cfg3|cfg2|cfg4|cfg3-prefill|cfg5-prefill|cfg4-copy|cfg4-copy-seq|cfg3-append|cfg5-append|cfg4-preempt]
+
+The default workload is the largest mixed configuration (cfg5: 2 online prefill chunks of 2048 tokens + 32 offline
+decode sequences of 32K-131K tokens, 64/8 heads).
 
 A step = one pass of the whole path over one synthetic batch already resident in HBM: host
 planning (ooco_plan) + ooco_attn_mixed (prefill kernel, decode kernel with its in-kernel merge).  Steps
@@ -55,41 +58,49 @@ def make_workload(name):
     raise SystemExit(f"unknown workload {name}")
 
 
-def cpu_baseline(b, max_seconds=25.0):
-    """The oracle as it stands, timed on this machine's host cores on (a sample of) the same batch."""
+def cpu_baseline(b, budget_units=45.0e6):
+    """The oracle as it stands, timed on this machine's host cores on a bounded sample of the same batch: every
+    prefill chunk (while they fit the budget) plus every k-th decode sequence, k the smallest stride that keeps
+    the sample within the budget.  One unit = one (query row, key) pair over 32 query heads; the C oracle does
+    about two million of them per second on 16 cores, so the default budget is 20-25 s of CPU work."""
     from oracle import ref_c
     from paper_2511_21862_amd import workloads as W
 
-    # ~0.6 M KV-token*rows per second on 8 cores was seen for 32 heads; bound the sample by work
-    work = b.seq_lens.astype(np.float64) * np.maximum(b.q_lens, 1) * (b.Hq / 32.0)
-    order = np.arange(b.num_seqs)
-    budget = 4.0e6
+    ql, ctx = b.q_lens.astype(np.float64), b.ctx_lens.astype(np.float64)
+    units = (ql * ctx + ql * (ql + 1) / 2.0) * (b.Hq / 32.0)
+    chunks = [int(i) for i in np.flatnonzero(b.q_lens > 1)]
+    dec = [int(i) for i in np.flatnonzero(b.q_lens == 1)]
     keep, acc = [], 0.0
-    for i in order:
-        if b.q_lens[i] == 0:
-            continue
-        w = work[i] if b.q_lens[i] == 1 else b.q_lens[i] * (b.ctx_lens[i] + b.q_lens[i] / 2.0) * (b.Hq / 32.0)
-        if keep and acc + w > budget:
-            continue
-        keep.append(int(i))
-        acc += w
+    for i in chunks:
+        if acc + units[i] <= budget_units or not keep:
+            keep.append(i)
+            acc += units[i]
+    n_chunks = len(keep)
+    stride = 0
+    if dec:
+        stride = 1
+        while units[dec[::stride]].sum() > max(budget_units - acc, 0.0) and stride < len(dec):
+            stride += 1
+        if units[dec[::stride]].sum() <= max(budget_units - acc, 0.0) or not keep:
+            keep += dec[::stride]
+            acc += float(units[dec[::stride]].sum())
+        else:
+            stride = 0
     sub = W.subset(b, keep)
     args = (sub.q, sub.k_cache, sub.v_cache, sub.block_tables, sub.seq_lens, sub.query_start_loc, sub.ctx_lens)
     times = []
     threads = 0
-    t_all = time.perf_counter()
-    for _ in range(3):
+    for _ in range(3 if acc < 8.0e6 else 1):
         t0 = time.perf_counter()
         _, threads = ref_c.attn_mixed(*args, return_threads=True)
         times.append(time.perf_counter() - t0)
-        if time.perf_counter() - t_all > max_seconds:
-            break
     t = float(np.median(times))
+    what = f"{n_chunks} of {len(chunks)} prefill chunks"
+    what += f" + every {stride}. decode sequence ({len(keep) - n_chunks} of {len(dec)})" if stride else " + no decode sequence"
     return {
         "value": sub.total_q / t, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-        "sample": f"{len(keep)} of {b.num_seqs} sequences ({sub.total_q} of {b.total_q} query tokens, "
-                  f"{int(sub.seq_lens.sum())} KV tokens), float64 C/OpenMP oracle, median of {len(times)} runs, "
-                  f"{t:.3f} s each",
+        "sample": f"{what}: {sub.total_q} of {b.total_q} query tokens, {int(sub.seq_lens.sum())} KV tokens, "
+                  f"float64 C/OpenMP oracle, {'median of 3 runs' if len(times) > 1 else 'one run'}, {t:.3f} s",
     }
 
 
@@ -354,7 +365,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--workload", default="cfg5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--replan-every-step", type=int, default=1)
     ap.add_argument("--opt", action="append", default=[], help="name=value passed to ooco_set_option")
@@ -378,6 +389,7 @@ def main():
         return bench_preempt(a)
     b, dominant = make_workload(a.workload)
     work = accounting.batch_work(b.Hq, b.Hkv, b.hd, b.BS, b.seq_lens, b.q_lens)
+    mixed = work["prefill_chunks"] > 0 and work["decode_seqs"] > 0
     tables = W.replica_tables(b, 4)
     dev = lambda x: torch.from_numpy(np.ascontiguousarray(x)).cuda()
     bts = [dev(t) for t in tables]
@@ -388,20 +400,27 @@ def main():
         k, v = o.split("=")
         ctx.set_option(k, int(v))
     stream = torch.cuda.current_stream()
+    host_us = {"plan": 0.0, "launch": 0.0}
 
-    def step(i):
+    def step(i, clock=False):
+        t0 = time.perf_counter() if clock else 0.0
         if a.replan_every_step or i == 0:
             ctx.plan(b.seq_lens, b.query_start_loc, b.ctx_lens)
+        t1 = time.perf_counter() if clock else 0.0
         ctx.attn_mixed(b.q, b.k_cache, b.v_cache, bts[i % len(bts)], sl, qsl, cl, out, stream)
+        if clock:
+            host_us["plan"] += (t1 - t0) * 1e6
+            host_us["launch"] += (time.perf_counter() - t1) * 1e6
 
     step(0)
     info = ctx.plan_info()
     for i in range(a.warmup):
         step(i)
     torch.cuda.synchronize()
-    # the timed region is also bracketed by one pair of HIP events on the launch stream: for a batch with one
-    # kind of work (one kernel per step, launched back to back) region time / steps is that kernel's average
-    # launch duration, free of the per-launch event records of the profiled pass below
+    # The timed region is also bracketed by one pair of HIP events on the launch stream (every kernel of a step
+    # is ordered inside it: the side stream is forked from and joined into this stream), so region time / steps
+    # is the GPU time of one step with its kernels running exactly as in the product path; for a batch with one
+    # kind of work it is that one kernel's average launch duration.
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     ev0.record(stream)
@@ -412,11 +431,17 @@ def main():
     dt = time.perf_counter() - t0
     ms_per_step = dt / a.steps * 1e3
     region_ms_per_step = ev0.elapsed_time(ev1) / a.steps
+    # host cost of planning and of enqueueing, one step at a time with the GPU idle in between
+    n_host = min(a.steps, 50)
+    for i in range(n_host):
+        step(i, clock=True)
+        torch.cuda.synchronize()
+    host_us = {k: v / n_host for k, v in host_us.items()}
 
-    # per-kernel durations: the same K steps again with HIP events recorded around each kernel on
-    # the launch stream (inside the library), so that the event overhead stays out of `value`
+    # per-kernel durations: the same K steps again with HIP events recorded inside the library around each kernel
+    # on the stream it runs on (launch order and overlap unchanged), so that the event records stay out of `value`
     ctx.set_option("profile", 1)
-    prof = {"prefill_ms": 0.0, "decode_ms": 0.0, "calls": 0}
+    prof = {"prefill_ms": 0.0, "decode_ms": 0.0, "call_ms": 0.0, "calls": 0}
     per_call = []
     done = 0
     while done < a.steps:
@@ -429,25 +454,31 @@ def main():
         per_call.append(r["per_call"])
         done += n
     ctx.set_option("profile", 0)
-    kern = {k: prof[k] / max(prof["calls"], 1) for k in ("prefill_ms", "decode_ms")}
+    kern = {k: prof[k] / max(prof["calls"], 1) for k in ("prefill_ms", "decode_ms", "call_ms")}
     kern["per_launch_events"] = dict(kern)
-    pc = np.concatenate(per_call) if per_call else np.zeros((0, 2))
+    pc = np.concatenate(per_call) if per_call else np.zeros((0, 3))
     if len(pc):      # spread of the per-launch event times: p10 / median / p90
         kern["prefill_ms_p10_p50_p90"] = [float(x) for x in np.percentile(pc[:, 0], [10, 50, 90])]
         kern["decode_ms_p10_p50_p90"] = [float(x) for x in np.percentile(pc[:, 1], [10, 50, 90])]
+        kern["call_ms_p10_p50_p90"] = [float(x) for x in np.percentile(pc[:, 2], [10, 50, 90])]
     if work["prefill_chunks"] == 0:
         kern["decode_ms"] = min(kern["decode_ms"], region_ms_per_step)
     elif work["decode_seqs"] == 0:
         kern["prefill_ms"] = min(kern["prefill_ms"], region_ms_per_step)
     kern["region_ms_per_step"] = region_ms_per_step
+    kern["overlapped"] = bool(mixed)
 
+    whole_step_frac = work["bytes_total"] / (region_ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS
     if dominant == "decode":
+        # the dominant kernel as it runs in the step (beside the prefill kernel when the batch holds both kinds)
         alg = work["bytes_decode"]
         dur = kern["decode_ms"] * 1e-3
         achieved = alg / dur / 1e9 if dur > 0 else 0.0
         roofline = {"bound": "hbm", "kernel": "decode_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                    "algorithmic_bytes_per_launch": alg, "kernel_ms": kern["decode_ms"]}
+                    "algorithmic_bytes_per_launch": alg, "kernel_ms": kern["decode_ms"],
+                    "whole_step_frac": whole_step_frac, "whole_step_bytes": work["bytes_total"],
+                    "whole_step_ms": region_ms_per_step}
     else:
         alg = work["flops_causal_prefill"]
         dur = kern["prefill_ms"] * 1e-3
@@ -472,6 +503,7 @@ def main():
         "hbm_frac_whole_step": work["bytes_total"] / (dt / a.steps) / 1e9 / HBM_PEAK_GBS,
         "kv_tokens_per_s": work["kv_tokens"] / (dt / a.steps),
         "tflops_causal_whole_step": work["flops_causal"] / (dt / a.steps) / 1e12,
+        "plan_host_us": host_us["plan"], "launch_host_us": host_us["launch"],
         "kernel_ms": kern,
         "roofline": roofline,
     }

@@ -136,25 +136,30 @@ const char *ooco_last_error(const ooco_ctx *ctx);
  *                on the caller's stream (fork and join by events)
  *   "decode_first"  0/1 (default 1): with "overlap", enqueue the decode kernel before the prefill
  *                kernel (0: the other way round)
- *   "profile"    0/1: every ooco_attn_mixed records HIP events on its stream around its two
- *                kernels for ooco_profile_read; at most 1024 calls between two reads
+ *   "profile"    0/1: every ooco_attn_mixed records HIP events around its two kernels (each on the
+ *                stream the kernel runs on) and around the whole call for ooco_profile_read; at most
+ *                1024 calls between two reads
  *   "trace"      0/1: see ooco_trace_read
  * Tuning knobs kept for experiments (defaults are the measured best): "decode_nbi" (KV blocks per
  * softmax step of the decode kernel: 1, 2 or 4; 0 = default: 1 for head_dim 128, 2 for head_dim 64), "rotate_heads" (0/1: rotate the kv
- * head of a decode wave by its run index, default 1), "copy_variant" (block copy: 10 * 16-byte
- * vectors per thread + 1 for non-temporal accesses; 0 = default 41; process-wide). */
+ * head of a decode wave by its run index, default 1), "copy_variant" (block copy of this context: 10 * 16-byte
+ * vectors per thread + 1 for non-temporal accesses, one of 10, 11, 20, 21, 40, 41, 80, 81; 0 = default 41;
+ * any other value -> OOCO_EINVAL). */
 ooco_status ooco_set_option(ooco_ctx *ctx, const char *name, int64_t value);
 
 /* Waits for the profiled calls made since the last read and returns the summed event-to-event
- * times in milliseconds: ms_sum[0] = prefill kernel, ms_sum[1] = decode kernel (HOST double[2]),
- * and the number of calls (HOST).  Either pointer may be NULL.  Resets the sums. */
+ * times in milliseconds: ms_sum[0] = prefill kernel, ms_sum[1] = decode kernel, ms_sum[2] = whole call
+ * (HOST double[3]), and the number of calls (HOST).  Either pointer may be NULL.  Resets the sums.
+ * Profiling changes neither the launch order nor the streams: in a batch with both kinds of work the two
+ * kernels still run side by side, each bracketed by events on its own stream, so the times are those of
+ * the kernels as they run in the step (they overlap; the whole-call time is not their sum). */
 ooco_status ooco_profile_read(ooco_ctx *ctx, double *ms_sum /*HOST*/, int64_t *calls /*HOST*/);
 
 /* The same, and also the event-to-event times of every call: per_call_ms is a HOST double
- * [cap][2] = (prefill kernel ms, decode kernel ms) for the first cap calls since the last read
- * (may be NULL with cap 0). */
+ * [cap][3] = (prefill kernel ms, decode kernel ms, whole call ms) for the first cap calls since the
+ * last read (may be NULL with cap 0). */
 ooco_status ooco_profile_read_calls(ooco_ctx *ctx, double *per_call_ms /*HOST*/, int64_t cap,
-                                    double *ms_sum /*HOST double[2]*/, int64_t *calls /*HOST*/);
+                                    double *ms_sum /*HOST double[3]*/, int64_t *calls /*HOST*/);
 
 /* Wave-level trace of the decode kernel, for tuning.  With option "trace" = 1 every decode wave of
  * the following ooco_attn_mixed calls stores four device time stamps (constant 100 MHz clock):
@@ -221,8 +226,9 @@ ooco_status ooco_plan_info(const ooco_ctx *ctx, int64_t *decode_waves, int64_t *
  * used and the three DEVICE length arrays are trusted to equal the planned HOST copies.
  * Without a current plan the call copies the length arrays to the host, waits for that copy
  * (one stream synchronisation) and plans by itself.
- * Launches at most two kernels (prefill chunks, then decode with its in-kernel merge) and no
- * copies (batches above 960 sequences: one small copy).
+ * Launches at most two kernels (decode with its in-kernel merge, and prefill chunks on the context's
+ * side stream when the batch holds both kinds of work) and no copies (batches above 960 sequences:
+ * one small copy).
  * Writes every row of out (and the context's workspace), nothing else.  num_seqs == 0 or
  * total_q_tokens == 0 returns OOCO_OK without launching anything.
  * Same context + same plan + same inputs give bit-identical output on every call (no
@@ -271,7 +277,10 @@ ooco_status ooco_kv_append(ooco_ctx *ctx, const void *k_new /*DEVICE*/, const vo
                            int num_seqs, int total_q_tokens, void *stream);
 
 /* Roofline latency model of the attention operator (paper Section 3.3: Table 2 gives the operator's
- * FLOPs 4*D_h*S_q*S_kv and bytes 2d*(S_q*D_h + S_kv*D_h*H_kv/H_q) with D_h = H_q*head_dim; Equation 1
+ * FLOPs 4*D_h*S_q*S_kv and bytes 2d*(S_q*D_h + S_kv*D_h*H_kv/H_q) with D_h = H_q*head_dim.  Table 2 as
+ * printed shows the head ratio of the KV term as H_q/H_kv; the library uses H_kv/H_q, because the KV
+ * tensors have H_kv heads of head_dim values per token, i.e. D_h*H_kv/H_q values (grouped-query attention
+ * shrinks the KV cache, Section 2.3).  Equation 1
  * gives its latency max(FLOPs/F_a, bytes/M_a) with separate achievable FLOP rates for prefill and decode
  * attention (Table 3); an iteration's latency is the sum over its operators plus a static overhead).
  * Pure HOST function.  One operator per sequence with q_len > 0 (S_q = q_len, S_kv = ctx_len + q_len;

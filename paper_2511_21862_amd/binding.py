@@ -189,19 +189,19 @@ def ooco_trace_read(ctx, cap_waves=1 << 16):
 
 
 def ooco_profile_read_calls(ctx, cap=1024) -> dict:
-    """Like ooco_profile_read, plus `per_call` = float64 [calls, 2] (prefill ms, decode ms) of every call."""
-    buf = np.zeros((cap, 2), dtype=np.float64)
-    ms = (ctypes.c_double * 2)()
+    """Like ooco_profile_read, plus `per_call` = float64 [calls, 3] (prefill ms, decode ms, whole call ms)."""
+    buf = np.zeros((cap, 3), dtype=np.float64)
+    ms = (ctypes.c_double * 3)()
     n = ctypes.c_int64()
     _check(ctx, _lib.ooco_profile_read_calls(ctx, buf.ctypes.data, cap, ms, ctypes.byref(n)))
-    return dict(prefill_ms=ms[0], decode_ms=ms[1], calls=n.value, per_call=buf[: min(n.value, cap)])
+    return dict(prefill_ms=ms[0], decode_ms=ms[1], call_ms=ms[2], calls=n.value, per_call=buf[: min(n.value, cap)])
 
 
 def ooco_profile_read(ctx) -> dict:
-    ms = (ctypes.c_double * 2)()
+    ms = (ctypes.c_double * 3)()
     n = ctypes.c_int64()
     _check(ctx, _lib.ooco_profile_read(ctx, ms, ctypes.byref(n)))
-    return dict(prefill_ms=ms[0], decode_ms=ms[1], calls=n.value)
+    return dict(prefill_ms=ms[0], decode_ms=ms[1], call_ms=ms[2], calls=n.value)
 
 
 def ooco_attn_mixed(ctx, q, k_cache, v_cache, block_tables, seq_lens, query_start_loc, ctx_lens, out, num_seqs,

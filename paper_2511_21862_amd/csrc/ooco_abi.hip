@@ -21,6 +21,7 @@ constexpr size_t kPlanInts = 1u << 21;       // staging for cumulative arrays of
 constexpr size_t kCounterInts = 1u << 20;    // arrival counters: num_seqs * num_kv_heads must fit
 constexpr size_t kTraceWaves = 1u << 16;     // decode waves the trace buffer can hold
 constexpr int kProfSlots = 1024;             // profiled calls between two ooco_profile_read
+constexpr int kProfEvents = 6;               // events per profiled call
 
 }  // namespace
 
@@ -39,10 +40,12 @@ struct PlanGeometry {
 
 // The compact plan: two cumulative arrays and a few scalars (see ooco_internal.h).
 struct HostPlan {
-    std::vector<int32_t> dcum;   // [num_seqs+1] units of the decode line before each sequence (blocks + piece_pad per decode sequence)
+    // (the two arrays live in storage the caller of build_plan provides, see PlanStorage)
+    const int32_t *dcum = nullptr;   // [num_seqs+1] units of the decode line before each sequence (blocks + piece_pad per decode sequence)
     // prefill chunks, heaviest (most keys) first: pf[0..P] = query tiles before chunk k of that
     // order, pf[P+1+k] = sequence index of chunk k
-    std::vector<int32_t> pf;
+    const int32_t *pf = nullptr;
+    size_t pf_size = 0;              // 2 * num_pf + 1
     int32_t num_pf = 0;
     int32_t dec_blocks = 0, static_blocks = 0, static_runs = 0, tail_runs = 0;   // in line units
     int32_t piece_pad = 0;
@@ -69,9 +72,22 @@ bool xcd_weights_to_cw(const int32_t *w, uint16_t *cw)
 
 size_t slot_bytes(const PlanGeometry &geo) { return (size_t)geo.Hq * (geo.hd + 2) * sizeof(float); }
 
-// Validates the length arrays and builds the plan.  Pure host code.
+// Where build_plan puts the plan's arrays: room for `seqs_cap` sequences, i.e. dcum [seqs_cap + 1],
+// pf [2 * seqs_cap + 1] and a work array order [seqs_cap].  build_plan itself allocates nothing.
+struct PlanStorage {
+    int32_t *dcum, *pf, *order;
+    size_t seqs_cap;
+};
+PlanStorage carve_storage(int32_t *base, size_t seqs_cap)
+{
+    return PlanStorage{base, base + (seqs_cap + 1), base + (seqs_cap + 1) + (2 * seqs_cap + 1), seqs_cap};
+}
+size_t storage_ints(size_t seqs_cap) { return (seqs_cap + 1) + (2 * seqs_cap + 1) + seqs_cap; }
+
+// Validates the length arrays and builds the plan.  Pure host code, no allocation.
 ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_seq_lens,
-                       const int32_t *h_query_start_loc, const int32_t *h_ctx_lens, HostPlan &out, char *err)
+                       const int32_t *h_query_start_loc, const int32_t *h_ctx_lens, const PlanStorage &store,
+                       HostPlan &out, char *err)
 {
     auto bad = [&](ooco_status code, const char *fmt, ...) __attribute__((format(printf, 3, 4))) {
         va_list ap;
@@ -87,8 +103,13 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
     const int BS = geo.BS;
     if (num_seqs > 0 && h_query_start_loc[0] != 0)
         return bad(OOCO_ESHAPE, "ooco_plan: query_start_loc[0]=%d, expected 0", h_query_start_loc[0]);
+    if ((size_t)num_seqs > store.seqs_cap)
+        return bad(OOCO_ENOMEM, "ooco_plan: %d sequences exceed the plan storage (%zu)", num_seqs, store.seqs_cap);
     out.num_seqs = num_seqs;
-    out.dcum.assign((size_t)num_seqs + 1, 0);
+    int32_t *const dcum = store.dcum, *const pf = store.pf, *const order = store.order;
+    out.dcum = dcum;
+    out.pf = pf;
+    std::fill(dcum, dcum + num_seqs + 1, 0);
     // The decode line: every decode sequence contributes piece_pad units followed by one unit per KV block.  The
     // runs cut the line into equal lengths, so a run that starts several pieces streams correspondingly fewer
     // blocks (starting a piece costs a wave about as long as streaming three 8 KiB tiles).
@@ -121,7 +142,7 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
         }
         if (dec_blocks > 0x7FFFFFFF / 2 || tiles > 0x7FFFFFFF / 128)
             return bad(OOCO_ESHAPE, "ooco_plan: batch too large");
-        out.dcum[(size_t)i + 1] = (int32_t)dec_blocks;
+        dcum[(size_t)i + 1] = (int32_t)dec_blocks;
     }
     out.total_q = num_seqs > 0 ? h_query_start_loc[num_seqs] : 0;
     out.dec_blocks = (int32_t)dec_blocks;
@@ -130,16 +151,20 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
     out.n_tiles = (int32_t)tiles;
     // prefill chunks in order of decreasing sequence length: workgroups are dispatched in index
     // order, so the long ones start first and the short ones fill the end
-    std::vector<int32_t> order;
+    size_t n_order = 0;
     for (int i = 0; i < num_seqs; ++i)
-        if (h_query_start_loc[i + 1] - h_query_start_loc[i] > 1) order.push_back(i);
-    std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) { return h_seq_lens[x] > h_seq_lens[y]; });
-    out.num_pf = (int32_t)order.size();
-    out.pf.assign(2 * order.size() + 1, 0);
-    for (size_t k = 0; k < order.size(); ++k) {
+        if (h_query_start_loc[i + 1] - h_query_start_loc[i] > 1) order[n_order++] = i;
+    // (equal lengths keep their batch order; std::sort with the index as tie-break needs no temporary buffer)
+    std::sort(order, order + n_order, [&](int32_t x, int32_t y) {
+        return h_seq_lens[x] != h_seq_lens[y] ? h_seq_lens[x] > h_seq_lens[y] : x < y;
+    });
+    out.num_pf = (int32_t)n_order;
+    out.pf_size = 2 * n_order + 1;
+    std::fill(pf, pf + out.pf_size, 0);
+    for (size_t k = 0; k < n_order; ++k) {
         const int64_t ql = (int64_t)h_query_start_loc[order[k] + 1] - h_query_start_loc[order[k]];
-        out.pf[k + 1] = out.pf[k] + (int32_t)((ql + tile_rows - 1) / tile_rows);
-        out.pf[order.size() + 1 + k] = order[k];
+        pf[k + 1] = pf[k] + (int32_t)((ql + tile_rows - 1) / tile_rows);
+        pf[n_order + 1 + k] = order[k];
     }
 
     // ---- run layout of the decode block line (see ooco_internal.h)
@@ -268,7 +293,8 @@ struct ooco_ctx {
     hipEvent_t upload_done = nullptr;
     bool upload_pending = false;
 
-    // current plan
+    // current plan (its arrays live in plan_store)
+    std::vector<int32_t> plan_store;
     HostPlan plan;
     bool plan_valid = false;
     bool plan_dirty = false;
@@ -295,7 +321,8 @@ struct ooco_ctx {
     int64_t trace_waves = 0;       // waves of the last traced call
     int64_t opt_profile = 0;
 
-    // per-kernel timing (option "profile"): 3 events per call
+    // per-kernel timing (option "profile"): kProfEvents events per call (decode start/end, prefill start/end,
+    // call start/end), each pair recorded on the stream its kernel runs on
     std::vector<hipEvent_t> prof_ev;
     int64_t prof_calls = 0;
 
@@ -440,19 +467,24 @@ ooco_status ooco_profile_read_calls(ooco_ctx *ctx, double *per_call_ms, int64_t 
 {
     if (!ctx) return OOCO_EINVAL;
     if (cap < 0 || (cap > 0 && !per_call_ms)) return fail(ctx, OOCO_EINVAL, "ooco_profile_read_calls: bad per-call buffer");
-    double sum[2] = {0.0, 0.0};
+    double sum[3] = {0.0, 0.0, 0.0};
     for (int64_t c = 0; c < ctx->prof_calls; ++c) {
-        hipEvent_t *ev = ctx->prof_ev.data() + 3 * c;
-        hipError_t e = hipEventSynchronize(ev[2]);
-        for (int k = 0; k < 2 && e == hipSuccess; ++k) {
+        hipEvent_t *ev = ctx->prof_ev.data() + kProfEvents * c;
+        // wait for the call's last record on either stream
+        hipError_t e = hipEventSynchronize(ev[5]);
+        if (e == hipSuccess) e = hipEventSynchronize(ev[3]);
+        if (e == hipSuccess) e = hipEventSynchronize(ev[1]);
+        // (prefill start, prefill end), (decode start, decode end), (call start, call end)
+        static const int pairs[3][2] = {{2, 3}, {0, 1}, {4, 5}};
+        for (int k = 0; k < 3 && e == hipSuccess; ++k) {
             float ms = 0.f;
-            e = hipEventElapsedTime(&ms, ev[k], ev[k + 1]);
+            e = hipEventElapsedTime(&ms, ev[pairs[k][0]], ev[pairs[k][1]]);
             sum[k] += ms;
-            if (c < cap) per_call_ms[2 * c + k] = ms;
+            if (c < cap) per_call_ms[3 * c + k] = ms;
         }
         if (e != hipSuccess) return fail(ctx, OOCO_EHIP, "ooco_profile_read: %s", hipGetErrorString(e));
     }
-    if (ms_sum) ms_sum[0] = sum[0], ms_sum[1] = sum[1];
+    if (ms_sum) ms_sum[0] = sum[0], ms_sum[1] = sum[1], ms_sum[2] = sum[2];
     if (calls) *calls = ctx->prof_calls;
     ctx->prof_calls = 0;
     return OOCO_OK;
@@ -492,6 +524,9 @@ ooco_status ooco_set_option(ooco_ctx *ctx, const char *name, int64_t value)
         ctx->opt_trace = value;
         return OOCO_OK;
     } else if (!strcmp(name, "copy_variant")) {
+        static const int64_t known[] = {0, 10, 11, 20, 21, 40, 41, 80, 81};
+        if (std::find(std::begin(known), std::end(known), value) == std::end(known))
+            return fail(ctx, OOCO_EINVAL, "ooco_set_option: copy_variant must be one of 0, 10, 11, 20, 21, 40, 41, 80, 81");
         ctx->opt_copy_variant = (int)value;
         return OOCO_OK;
     } else if (!strcmp(name, "overlap")) {
@@ -543,7 +578,10 @@ ooco_status ooco_plan(ooco_ctx *ctx, int num_seqs, const int32_t *h_seq_lens, co
     geo.pf_split_opt = ctx->opt_pf_split;
     geo.piece_pad = ctx->opt_piece_pad;
     for (int k = 0; k < kXcds; ++k) geo.xcd_cw[k] = ctx->xcd_cw[k];
-    ooco_status st = build_plan(geo, num_seqs, h_seq_lens, h_query_start_loc, h_ctx_lens, ctx->plan, ctx->err);
+    const size_t cap = (size_t)std::max(num_seqs, 0);
+    if (ctx->plan_store.size() < storage_ints(cap)) ctx->plan_store.resize(storage_ints(cap));
+    ooco_status st = build_plan(geo, num_seqs, h_seq_lens, h_query_start_loc, h_ctx_lens,
+                                carve_storage(ctx->plan_store.data(), cap), ctx->plan, ctx->err);
     if (st != OOCO_OK) return st;
     if ((size_t)num_seqs * ctx->Hkv > kCounterInts - 1 || 3 * ((size_t)num_seqs + 1) > kPlanInts)
         return fail(ctx, OOCO_ENOMEM, "ooco_plan: %d sequences exceed the context's counter/plan buffers", num_seqs);
@@ -564,6 +602,7 @@ ooco_status ooco_plan_dry_run(int num_q_heads, int num_kv_heads, int head_dim, i
     char err[512] = "";
     ooco_status st = OOCO_OK;
     HostPlan pl;
+    std::vector<int32_t> store;
     if (num_q_heads <= 0 || num_kv_heads <= 0 || num_q_heads % num_kv_heads || (head_dim != 64 && head_dim != 128) ||
         block_size != kBlockSize || max_blocks_per_seq <= 0 || num_cus <= 0 || decode_segments < 0 ||
         decode_tail_pct < 0 || decode_tail_blocks < 0 || prefill_split < 0 || decode_piece_pad > 64) {
@@ -587,8 +626,11 @@ ooco_status ooco_plan_dry_run(int num_q_heads, int num_kv_heads, int head_dim, i
             snprintf(err, sizeof err, "ooco_plan_dry_run: xcd_weights needs eight values in 1..255 that differ by at most 4x");
             st = OOCO_EINVAL;
         }
-        if (st == OOCO_OK)
-            st = build_plan(geo, num_seqs, h_seq_lens, h_query_start_loc, h_ctx_lens, pl, err);
+        if (st == OOCO_OK) {
+            const size_t cap = (size_t)std::max(num_seqs, 0);
+            store.resize(storage_ints(cap));
+            st = build_plan(geo, num_seqs, h_seq_lens, h_query_start_loc, h_ctx_lens, carve_storage(store.data(), cap), pl, err);
+        }
     }
     if (msg && msg_cap) snprintf(msg, msg_cap, "%s", err);
     if (st != OOCO_OK) return st;
@@ -682,12 +724,12 @@ ooco_status ooco_attn_mixed(ooco_ctx *ctx, const void *q, const void *k_cache, c
     }
 
     // The cumulative arrays ride in the kernel arguments; only very large batches need a copy.
-    const size_t n_cum = (size_t)num_seqs + 1, n_pf = pl.pf.size();
+    const size_t n_cum = (size_t)num_seqs + 1, n_pf = pl.pf_size;
     const bool inline_cum = n_cum <= (size_t)kInlineSeqs + 1 && n_pf <= (size_t)kInlineSeqs + 1;
     if (!inline_cum && ctx->plan_dirty) {
         if (ctx->upload_pending) (void)hipEventSynchronize(ctx->upload_done);
-        memcpy(ctx->plan_h, pl.dcum.data(), n_cum * sizeof(int32_t));
-        memcpy(ctx->plan_h + n_cum, pl.pf.data(), n_pf * sizeof(int32_t));
+        memcpy(ctx->plan_h, pl.dcum, n_cum * sizeof(int32_t));
+        memcpy(ctx->plan_h + n_cum, pl.pf, n_pf * sizeof(int32_t));
         hipError_t e = hipMemcpyAsync(ctx->plan_d, ctx->plan_h, (n_cum + n_pf) * sizeof(int32_t), hipMemcpyHostToDevice, s);
         if (e == hipSuccess) e = hipEventRecord(ctx->upload_done, s);
         if (e != hipSuccess) return fail(ctx, OOCO_EHIP, "ooco_attn_mixed: plan upload: %s", hipGetErrorString(e));
@@ -755,62 +797,70 @@ ooco_status ooco_attn_mixed(ooco_ctx *ctx, const void *q, const void *k_cache, c
             return fail(ctx, OOCO_EINVAL, "ooco_attn_mixed: more than %d profiled calls without ooco_profile_read",
                         kProfSlots);
         if (ctx->prof_ev.empty()) {
-            ctx->prof_ev.assign((size_t)3 * kProfSlots, nullptr);
+            ctx->prof_ev.assign((size_t)kProfEvents * kProfSlots, nullptr);
             for (auto &x : ctx->prof_ev)
                 if (e == hipSuccess) e = hipEventCreate(&x);
             if (e != hipSuccess) return fail(ctx, OOCO_EHIP, "ooco_attn_mixed: %s", hipGetErrorString(e));
         }
-        ev = ctx->prof_ev.data() + 3 * ctx->prof_calls++;
+        ev = ctx->prof_ev.data() + kProfEvents * ctx->prof_calls++;
     }
     // A mixed batch runs its two kernels side by side: the prefill kernel (matrix-core bound) goes to
     // the context's side stream, forked from and joined back into the caller's stream with events,
     // the decode kernel (HBM bound) stays on the caller's stream.  The decode kernel is enqueued first
     // (its three waves per compute unit take their places before the prefill workgroups fill the
     // register files; measured 1.5 % faster on a long-context mixed batch, no difference on a short one).
-    // With per-kernel profiling on they run one after the other so that each gets a clean time.
+    // With per-kernel profiling on, the launch order and the streams stay exactly as they are without it:
+    // every kernel is bracketed by two events on the stream it runs on (ev[0..1] decode, ev[2..3] prefill)
+    // and the whole call by two on the caller's stream (ev[4..5]), so the times are those of the kernels
+    // as they run in the step.
     const bool mixed = pl.n_tiles > 0 && pl.static_runs > 0;
-    const bool overlap = mixed && !ev && ctx->opt_overlap && ctx->side_stream;
-    if (ev) e = hipEventRecord(ev[0], s);
+    const bool overlap = mixed && ctx->opt_overlap && ctx->side_stream;
+    hipStream_t ps = overlap ? ctx->side_stream : s;   // the stream of the prefill kernel
+    auto mark = [&](int k, hipStream_t st) {
+        if (ev && e == hipSuccess) e = hipEventRecord(ev[k], st);
+    };
     auto run_prefill = [&]() {
-        if (e != hipSuccess || pl.n_tiles <= 0) return;
-        p.cum_dev = inline_cum ? nullptr : ctx->plan_d + n_cum;
-        if (inline_cum) memcpy(ka.cum, pl.pf.data(), n_pf * sizeof(int32_t));
-        if (overlap) {
-            e = hipEventRecord(ctx->fork_ev, s);
-            if (e == hipSuccess) e = hipStreamWaitEvent(ctx->side_stream, ctx->fork_ev, 0);
-            if (e == hipSuccess) e = launch_prefill(ka, ctx->side_stream);
-            if (e == hipSuccess) e = hipEventRecord(ctx->join_ev, ctx->side_stream);
-        } else {
-            e = launch_prefill(ka, s);
+        if (e == hipSuccess && pl.n_tiles > 0) {
+            p.cum_dev = inline_cum ? nullptr : ctx->plan_d + n_cum;
+            if (inline_cum) memcpy(ka.cum, pl.pf, n_pf * sizeof(int32_t));
         }
+        mark(2, ps);
+        if (e == hipSuccess && pl.n_tiles > 0) e = launch_prefill(ka, ps);
+        mark(3, ps);
     };
     auto run_decode = [&]() {
-        if (e != hipSuccess || pl.static_runs <= 0) return;
-        p.cum_dev = inline_cum ? nullptr : ctx->plan_d;
-        if (inline_cum) memcpy(ka.cum, pl.dcum.data(), n_cum * sizeof(int32_t));
-        e = launch_decode(ka, s);
-        // every wave draws one ticket per tail run it takes plus one that tells it to stop
-        if (e == hipSuccess && pl.tail_runs > 0)
-            ctx->queue_base += (uint32_t)pl.tail_runs * (uint32_t)ctx->Hkv + (uint32_t)pl.static_runs * (uint32_t)ctx->Hkv;
+        if (e == hipSuccess && pl.static_runs > 0) {
+            p.cum_dev = inline_cum ? nullptr : ctx->plan_d;
+            if (inline_cum) memcpy(ka.cum, pl.dcum, n_cum * sizeof(int32_t));
+        }
+        mark(0, s);
+        if (e == hipSuccess && pl.static_runs > 0) {
+            e = launch_decode(ka, s);
+            // every wave draws one ticket per tail run it takes plus one that tells it to stop
+            if (e == hipSuccess && pl.tail_runs > 0)
+                ctx->queue_base += (uint32_t)pl.tail_runs * (uint32_t)ctx->Hkv + (uint32_t)pl.static_runs * (uint32_t)ctx->Hkv;
+        }
+        mark(1, s);
     };
-    if (overlap && ctx->opt_decode_first) {
-        // fork before the decode kernel is enqueued, so that the side stream does not wait for it
-        e = hipEventRecord(ctx->fork_ev, s);
-        run_decode();
+    mark(4, s);
+    if (overlap) {
+        // fork before anything else is enqueued, so that the side stream waits for nothing of this call
+        if (e == hipSuccess) e = hipEventRecord(ctx->fork_ev, s);
         if (e == hipSuccess) e = hipStreamWaitEvent(ctx->side_stream, ctx->fork_ev, 0);
-        if (e == hipSuccess) {
-            p.cum_dev = inline_cum ? nullptr : ctx->plan_d + n_cum;
-            if (inline_cum) memcpy(ka.cum, pl.pf.data(), n_pf * sizeof(int32_t));
-            e = launch_prefill(ka, ctx->side_stream);
+        if (ctx->opt_decode_first) {
+            run_decode();
+            run_prefill();
+        } else {
+            run_prefill();
+            run_decode();
         }
         if (e == hipSuccess) e = hipEventRecord(ctx->join_ev, ctx->side_stream);
+        if (e == hipSuccess) e = hipStreamWaitEvent(s, ctx->join_ev, 0);
     } else {
         run_prefill();
-        if (ev && e == hipSuccess) e = hipEventRecord(ev[1], s);
         run_decode();
     }
-    if (overlap && e == hipSuccess) e = hipStreamWaitEvent(s, ctx->join_ev, 0);
-    if (ev && e == hipSuccess) e = hipEventRecord(ev[2], s);
+    mark(5, s);
     if (ctx->plan_one_shot) {
         ctx->plan_one_shot = false;
         ctx->plan_valid = false;

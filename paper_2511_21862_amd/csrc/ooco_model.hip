@@ -35,7 +35,8 @@ extern "C" ooco_status ooco_predict_latency(const ooco_model_params *params, int
         if (ql < 0 || h_ctx_lens[i] < 0) return bad(OOCO_ESHAPE, "negative length");
         if (ql == 0) continue;
         const double S_q = (double)ql, S_kv = (double)h_ctx_lens[i] + (double)ql;
-        // Table 2, attention row; optionally only the (row, key) pairs a causal kernel visits
+        // Table 2, attention row; optionally only the (row, key) pairs a causal kernel visits.  The table prints
+        // the head ratio of the KV term as H_q/H_kv; H_kv/H_q is used, since the KV tensors have H_kv heads.
         const double f = causal_flops ? 4.0 * D_h * (S_q * (double)h_ctx_lens[i] + S_q * (S_q + 1.0) / 2.0) : 4.0 * D_h * S_q * S_kv;
         const double b = 2.0 * d * (S_q * D_h + S_kv * D_h * kv_ratio);
         const double tf = f / (ql > 1 ? params->F_ap : params->F_ad), tb = b / params->M_a;

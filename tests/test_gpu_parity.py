@@ -274,4 +274,39 @@ def test_errors_surface_through_the_abi():
         assert e.value.status == B.OOCO_ESHAPE
         with pytest.raises(B.OocoError):
             ctx.set_option("no_such_option", 1)
+        for bad in (5, 42, 90):   # block-copy variants that no kernel instantiation stands behind
+            with pytest.raises(B.OocoError) as e:
+                ctx.set_option("copy_variant", bad)
+            assert e.value.status == B.OOCO_EINVAL
         B.ooco_attn_mixed(ctx.h, d.q, d.k_cache, d.v_cache, bt, sl, qsl, cl, out, 0, 0)     # empty: OK
+
+
+def test_profiled_calls_keep_the_overlap_and_the_results():
+    # option "profile" brackets every kernel with events on the stream it runs on: same launch order, same
+    # streams, same output bits; the whole-call time covers both kernels
+    b = W.build_batch(Hq=32, Hkv=8, hd=128, q_lens=[1, 300, 1, 1, 1], ctx_lens=[2500, 900, 64, 4000, 700],
+                      num_blocks=700, seed=93, poison=True)
+    say("case: profiled mixed calls")
+    d = W.to_device(b)
+    bt, sl, qsl, cl = device_meta(b)
+    out = torch.empty((b.total_q, b.Hq, b.hd), dtype=torch.bfloat16, device="cuda")
+    with B.Context(b.Hq, b.Hkv, b.hd, b.BS, b.num_blocks, b.max_blocks_per_seq) as ctx:
+        ctx.plan(b.seq_lens, b.query_start_loc, b.ctx_lens)
+        ctx.attn_mixed(d.q, d.k_cache, d.v_cache, bt, sl, qsl, cl, out)
+        torch.cuda.synchronize()
+        plain = out.clone()
+        ctx.set_option("profile", 1)
+        for _ in range(5):
+            out.zero_()
+            ctx.attn_mixed(d.q, d.k_cache, d.v_cache, bt, sl, qsl, cl, out)
+        r = ctx.profile_read_calls()
+        ctx.set_option("profile", 0)
+        torch.cuda.synchronize()
+    assert r["calls"] == 5 and r["per_call"].shape == (5, 3)
+    pc = r["per_call"]
+    say(f"  per call (prefill, decode, whole call) ms: {pc.tolist()}")
+    assert (pc > 0).all()
+    # the two kernels lie inside the call; they overlap, so the call is shorter than their sum would need
+    assert (pc[:, 2] >= pc[:, :2].max(axis=1) * 0.9).all()
+    assert torch.equal(out.view(torch.int16), plain.view(torch.int16))
+    assert_parity(out.view(torch.int16).cpu().numpy().view(np.uint16), oracle(b), "profiled mixed call")
