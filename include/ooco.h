@@ -245,6 +245,32 @@ ooco_status ooco_attn_mixed(ooco_ctx *ctx, const void *q /*DEVICE*/, const void 
                             const int32_t *ctx_lens /*DEVICE*/, void *out /*DEVICE*/, int num_seqs,
                             int total_q_tokens, void *stream);
 
+/* ooco_attn_mixed for callers that cannot allocate: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  No context: the geometry (as for ooco_ctx_create) and the HOST copies of the
+ * length arrays (as for ooco_plan) come with the call, the plan is made on the stack, and everything the kernels
+ * need beyond the caller's tensors -- arrival counters and the partial results of split sequences -- lives in one
+ * 16 MiB array that is part of the library's device code (every GPU the library runs on holds its own copy until the
+ * process ends).  The call allocates nothing on host or device, creates no stream or event, never synchronises
+ * and enqueues at most three kernels on `stream` (a small fill that zeroes the counters it will use, the prefill
+ * kernel, the decode kernel; the two attention kernels run one after the other).
+ *   Device arguments, shapes and results as for ooco_attn_mixed; default run layout; prefill tiles are never
+ *   split along the context.  Limits: num_seqs <= 960, num_seqs * num_kv_heads <= 65536 (-> OOCO_ENOMEM with a
+ *   message beyond them); a partial-result area too small for the usual number of decode runs lowers that number.
+ *   All calls on one GPU share the array, which keeps the contents of the last call: calls whose GPU work
+ *   overlaps in time on one GPU (two streams, two threads) race and give unspecified results.
+ *   msg: HOST buffer of msg_cap bytes for the error text (may be NULL).
+ * Errors: OOCO_EINVAL (NULL pointers, negative sizes), OOCO_ESHAPE (geometry, inconsistent lengths), OOCO_ENOMEM
+ * (limits above), OOCO_EHIP (symbol lookup or launch failed). */
+ooco_status ooco_attn_mixed_static(int num_q_heads, int num_kv_heads, int head_dim, int block_size,
+                                   int max_blocks_per_seq, float softmax_scale,
+                                   const int32_t *h_seq_lens /*HOST*/, const int32_t *h_query_start_loc /*HOST*/,
+                                   const int32_t *h_ctx_lens /*HOST*/, const void *q /*DEVICE*/,
+                                   const void *k_cache /*DEVICE*/, const void *v_cache /*DEVICE*/,
+                                   const int32_t *block_tables /*DEVICE*/, const int32_t *seq_lens /*DEVICE*/,
+                                   const int32_t *query_start_loc /*DEVICE*/, const int32_t *ctx_lens /*DEVICE*/,
+                                   void *out /*DEVICE*/, int num_seqs, int total_q_tokens, void *stream,
+                                   char *msg /*HOST*/, size_t msg_cap);
+
 /* Whole-block copy for preemption eviction / restore:
  *   for p in [0, num_pairs):  k_dst[dst_block_ids[p]] <- k_src[src_block_ids[p]]  (one block =
  *   Hkv*BS*hd bf16, all slots, garbage tail included) and the same for V.  Bit-exact.

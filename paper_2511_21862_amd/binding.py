@@ -19,7 +19,7 @@ _STATUS_NAMES = {0: "OOCO_OK", -1: "OOCO_EINVAL", -2: "OOCO_ESHAPE", -3: "OOCO_E
                  -5: "OOCO_ENOTIMPL"}
 
 EXPORTS = ["ooco_ctx_create", "ooco_ctx_destroy", "ooco_last_error", "ooco_set_option", "ooco_plan",
-           "ooco_plan_dry_run", "ooco_plan_info", "ooco_profile_read", "ooco_profile_read_calls", "ooco_trace_read", "ooco_attn_mixed", "ooco_kv_block_copy", "ooco_kv_append", "ooco_predict_latency", "ooco_mix_decoding_select",
+           "ooco_plan_dry_run", "ooco_plan_info", "ooco_profile_read", "ooco_profile_read_calls", "ooco_trace_read", "ooco_attn_mixed", "ooco_attn_mixed_static", "ooco_kv_block_copy", "ooco_kv_append", "ooco_predict_latency", "ooco_mix_decoding_select",
            "ooco_migration_preference", "ooco_migration_select", "ooco_eviction_victims"]
 
 if not os.path.exists(LIB_PATH):
@@ -52,6 +52,9 @@ _lib.ooco_trace_read.restype = ctypes.c_int
 _lib.ooco_trace_read.argtypes = [_P, _P, ctypes.c_int64, ctypes.POINTER(ctypes.c_int64)]
 _lib.ooco_attn_mixed.restype = ctypes.c_int
 _lib.ooco_attn_mixed.argtypes = [_P] * 9 + [ctypes.c_int, ctypes.c_int, _P]
+_lib.ooco_attn_mixed_static.restype = ctypes.c_int
+_lib.ooco_attn_mixed_static.argtypes = ([ctypes.c_int] * 5 + [ctypes.c_float] + [_P] * 11 + [ctypes.c_int, ctypes.c_int, _P,
+                                        ctypes.c_char_p, ctypes.c_size_t])
 _lib.ooco_kv_block_copy.restype = ctypes.c_int
 _lib.ooco_kv_block_copy.argtypes = [_P] * 7 + [ctypes.c_int64, _P]
 _lib.ooco_kv_append.restype = ctypes.c_int
@@ -209,6 +212,21 @@ def ooco_attn_mixed(ctx, q, k_cache, v_cache, block_tables, seq_lens, query_star
     _check(ctx, _lib.ooco_attn_mixed(ctx, _dev(q), _dev(k_cache), _dev(v_cache), _dev(block_tables), _dev(seq_lens),
                                      _dev(query_start_loc), _dev(ctx_lens), _dev(out), num_seqs, total_q_tokens,
                                      _stream_handle(stream)))
+
+
+def ooco_attn_mixed_static(num_q_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, softmax_scale, h_seq_lens,
+                           h_query_start_loc, h_ctx_lens, q, k_cache, v_cache, block_tables, seq_lens, query_start_loc,
+                           ctx_lens, out, num_seqs, total_q_tokens, stream=None) -> None:
+    a, pa = _host_i32(h_seq_lens)
+    b, pb = _host_i32(h_query_start_loc)
+    c, pc = _host_i32(h_ctx_lens)
+    msg = ctypes.create_string_buffer(512)
+    st = _lib.ooco_attn_mixed_static(num_q_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq, softmax_scale,
+                                     pa, pb, pc, _dev(q), _dev(k_cache), _dev(v_cache), _dev(block_tables), _dev(seq_lens),
+                                     _dev(query_start_loc), _dev(ctx_lens), _dev(out), num_seqs, total_q_tokens,
+                                     _stream_handle(stream), msg, 512)
+    if st != OOCO_OK:
+        raise OocoError(st, msg.value.decode())
 
 
 def ooco_kv_block_copy(ctx, k_src, v_src, k_dst, v_dst, src_block_ids, dst_block_ids, num_pairs, stream=None) -> None:

@@ -7,6 +7,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -23,6 +24,50 @@ constexpr size_t kTraceWaves = 1u << 16;     // decode waves the trace buffer ca
 constexpr int kProfSlots = 1024;             // profiled calls between two ooco_profile_read
 constexpr int kProfEvents = 6;               // events per profiled call
 
+// ooco_attn_mixed_static: everything the kernels need beyond the caller's tensors lives in one fixed device array
+// (arrival counters at the front, partial results behind them); see include/ooco.h
+constexpr size_t kStaticScratchBytes = 16u << 20;
+constexpr size_t kStaticCounterInts = 1u << 16;
+constexpr int kStaticMaxDevices = 64;
+
+}  // namespace
+
+// One copy per GPU, at an address of its own on each; zero when the code object is loaded.  In host code the
+// name below is only a handle for hipGetSymbolAddress, never a device address.  (No `used` attribute: the
+// compiler gives a static device variable that host code refers to an externally visible symbol, which is what
+// the runtime looks up; marked `used` it stays a local symbol and the lookup aborts.)
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+struct StaticDevice {
+    void *ptr = nullptr;   // device address of `scratch` on this GPU
+    int num_cus = 0;
+};
+std::mutex g_static_mu;
+StaticDevice g_static_dev[kStaticMaxDevices];
+
+// Address of this device's scratch array and its CU count, looked up once per device with that device current.
+hipError_t static_device(StaticDevice &out, int &device)
+{
+    hipError_t e = hipGetDevice(&device);
+    if (e != hipSuccess) return e;
+    if (device < 0 || device >= kStaticMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    StaticDevice &d = g_static_dev[device];
+    if (!d.ptr) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        int cus = 0;
+        e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device);
+        if (e != hipSuccess) return e;
+        d.num_cus = cus > 0 ? cus : 256;
+        d.ptr = ptr;
+    }
+    out = d;
+    return hipSuccess;
+}
 }  // namespace
 
 namespace {
@@ -866,6 +911,130 @@ ooco_status ooco_attn_mixed(ooco_ctx *ctx, const void *q, const void *k_cache, c
         ctx->plan_valid = false;
     }
     if (e != hipSuccess) return fail(ctx, OOCO_EHIP, "ooco_attn_mixed: kernel launch: %s", hipGetErrorString(e));
+    return OOCO_OK;
+}
+
+ooco_status ooco_attn_mixed_static(int num_q_heads, int num_kv_heads, int head_dim, int block_size, int max_blocks_per_seq,
+                                   float softmax_scale, const int32_t *h_seq_lens, const int32_t *h_query_start_loc,
+                                   const int32_t *h_ctx_lens, const void *q, const void *k_cache, const void *v_cache,
+                                   const int32_t *block_tables, const int32_t *seq_lens, const int32_t *query_start_loc,
+                                   const int32_t *ctx_lens, void *out, int num_seqs, int total_q_tokens, void *stream,
+                                   char *msg, size_t msg_cap)
+{
+    char err[512] = "";
+    auto bad = [&](ooco_status code, const char *fmt, ...) __attribute__((format(printf, 3, 4))) {
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(err, sizeof err, fmt, ap);
+        va_end(ap);
+        if (msg && msg_cap) snprintf(msg, msg_cap, "%s", err);
+        return code;
+    };
+    if (msg && msg_cap) msg[0] = 0;
+    if (num_seqs < 0 || total_q_tokens < 0)
+        return bad(OOCO_EINVAL, "ooco_attn_mixed_static: negative size (num_seqs=%d, total_q_tokens=%d)", num_seqs, total_q_tokens);
+    if (num_q_heads <= 0 || num_kv_heads <= 0 || num_q_heads % num_kv_heads != 0 || num_q_heads / num_kv_heads > 16 ||
+        (head_dim != 64 && head_dim != 128) || block_size != kBlockSize || max_blocks_per_seq <= 0)
+        return bad(OOCO_ESHAPE, "ooco_attn_mixed_static: unsupported geometry (heads %d/%d, head_dim %d, block_size %d, "
+                                "max_blocks_per_seq %d)", num_q_heads, num_kv_heads, head_dim, block_size, max_blocks_per_seq);
+    if (num_seqs == 0 || total_q_tokens == 0) return OOCO_OK;
+    if (!q || !k_cache || !v_cache || !block_tables || !seq_lens || !query_start_loc || !ctx_lens || !out || !h_seq_lens ||
+        !h_query_start_loc || !h_ctx_lens)
+        return bad(OOCO_EINVAL, "ooco_attn_mixed_static: NULL pointer argument");
+    if (num_seqs > kInlineSeqs)
+        return bad(OOCO_ENOMEM, "ooco_attn_mixed_static: %d sequences exceed the maximum of %d", num_seqs, kInlineSeqs);
+    if ((size_t)num_seqs * (size_t)num_kv_heads > kStaticCounterInts)
+        return bad(OOCO_ENOMEM, "ooco_attn_mixed_static: %d sequences x %d kv heads exceed the %zu arrival counters", num_seqs,
+                   num_kv_heads, kStaticCounterInts);
+    StaticDevice dev;
+    int device = 0;
+    hipError_t e = static_device(dev, device);
+    if (e != hipSuccess) return bad(OOCO_EHIP, "ooco_attn_mixed_static: scratch array: %s", hipGetErrorString(e));
+
+    // plan on the stack: default run layout, no dynamic tail, prefill tiles never split (their partial results
+    // would not fit the fixed array); a partial-result area too small for the wanted runs lowers their number
+    PlanGeometry geo;
+    geo.Hq = num_q_heads;
+    geo.Hkv = num_kv_heads;
+    geo.hd = head_dim;
+    geo.BS = block_size;
+    geo.max_blocks_per_seq = max_blocks_per_seq;
+    geo.num_cus = dev.num_cus;
+    geo.ws_bytes = kStaticScratchBytes - kStaticCounterInts * sizeof(int32_t);
+    geo.segments_opt = 0;
+    geo.tail_pct = 0;
+    geo.tail_blocks = 0;
+    geo.pf_split_opt = 1;
+    geo.piece_pad = default_piece_pad(head_dim);
+    int32_t store[(kInlineSeqs + 1) + (2 * kInlineSeqs + 1) + kInlineSeqs];
+    HostPlan pl;
+    ooco_status st = build_plan(geo, num_seqs, h_seq_lens, h_query_start_loc, h_ctx_lens, carve_storage(store, kInlineSeqs), pl, err);
+    if (st != OOCO_OK) {
+        if (msg && msg_cap) snprintf(msg, msg_cap, "%s", err);
+        return st;
+    }
+    if (pl.total_q != total_q_tokens)
+        return bad(OOCO_ESHAPE, "ooco_attn_mixed_static: query_start_loc ends at %d, call has %d query tokens", pl.total_q,
+                   total_q_tokens);
+    if ((size_t)pl.slots * slot_bytes(geo) > geo.ws_bytes)
+        return bad(OOCO_ENOMEM, "ooco_attn_mixed_static: partial results of %lld slots exceed the scratch array", (long long)pl.slots);
+
+    KernArgs ka;
+    memset(&ka, 0, sizeof ka);
+    AttnParams &p = ka.p;
+    int32_t *const counters = static_cast<int32_t *>(dev.ptr);
+    float *const partials = reinterpret_cast<float *>(static_cast<unsigned char *>(dev.ptr) + kStaticCounterInts * sizeof(int32_t));
+    p.q = static_cast<const uint16_t *>(q);
+    p.k_cache = static_cast<const uint16_t *>(k_cache);
+    p.v_cache = static_cast<const uint16_t *>(v_cache);
+    p.block_tables = block_tables;
+    p.seq_lens = seq_lens;
+    p.query_start_loc = query_start_loc;
+    p.ctx_lens = ctx_lens;
+    p.out = static_cast<uint16_t *>(out);
+    p.part_acc = partials;
+    p.part_ml = partials + (size_t)pl.slots * num_q_heads * head_dim;
+    p.counters = counters;
+    p.cum_dev = nullptr;
+    p.trace = nullptr;
+    p.Hq = num_q_heads;
+    p.Hkv = num_kv_heads;
+    p.g = num_q_heads / num_kv_heads;
+    p.hd = head_dim;
+    p.max_blocks_per_seq = max_blocks_per_seq;
+    p.scale_log2e = (softmax_scale > 0.f ? softmax_scale : 1.0f / std::sqrt((float)head_dim)) * 1.4426950408889634f;
+    p.num_seqs = num_seqs;
+    p.total_q = total_q_tokens;
+    p.dec_blocks = pl.dec_blocks;
+    p.piece_pad = pl.piece_pad;
+    p.static_blocks = pl.static_blocks;
+    p.static_runs = pl.static_runs;
+    p.tail_runs = 0;
+    p.queue = reinterpret_cast<uint32_t *>(counters + kStaticCounterInts - 1);   // (no tail runs: never touched)
+    p.queue_base = 0;
+    p.n_tiles = pl.n_tiles;
+    p.num_pf = pl.num_pf;
+    p.tile_rows = prefill_tile_rows(p.g);
+    p.nbi = 0;
+    p.rotate_heads = 1;
+    p.pf_acc = nullptr;
+    p.pf_ml = nullptr;
+    p.pf_counters = nullptr;
+    p.pf_split = 1;
+
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    // The array keeps whatever the last call on this GPU left: the arrival counters this call will count in
+    // start at zero (a small fill kernel, not a memset node, so that the call can be captured into a graph).
+    if (pl.static_runs > 1) e = launch_fill_zero(counters, (int64_t)num_seqs * num_kv_heads, s);
+    if (e == hipSuccess && pl.n_tiles > 0) {
+        memcpy(ka.cum, pl.pf, pl.pf_size * sizeof(int32_t));
+        e = launch_prefill(ka, s);
+    }
+    if (e == hipSuccess && pl.static_runs > 0) {
+        memcpy(ka.cum, pl.dcum, ((size_t)num_seqs + 1) * sizeof(int32_t));
+        e = launch_decode(ka, s);
+    }
+    if (e != hipSuccess) return bad(OOCO_EHIP, "ooco_attn_mixed_static: kernel launch: %s", hipGetErrorString(e));
     return OOCO_OK;
 }
 

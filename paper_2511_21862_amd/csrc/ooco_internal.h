@@ -91,6 +91,9 @@ hipError_t launch_kv_append(const void *k_new, const void *v_new, void *k_cache,
                             const int32_t *query_start_loc, const int32_t *ctx_lens, int num_seqs, int total_q, int Hkv,
                             int hd, int max_blocks_per_seq, int64_t num_blocks, hipStream_t s);
 
+// n int32 values at p become zero (a kernel, so that callers under stream capture record no memset node).
+hipError_t launch_fill_zero(int32_t *p, int64_t n, hipStream_t s);
+
 // Query rows of one prefill tile for a GQA group of g heads.
 __host__ __device__ inline int32_t prefill_tile_rows(int32_t g) { return kPrefillCols / g > 0 ? kPrefillCols / g : 1; }
 

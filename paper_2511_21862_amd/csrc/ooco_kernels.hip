@@ -1111,6 +1111,19 @@ hipError_t launch_kv_append(const void *k_new, const void *v_new, void *k_cache,
 
 
 // ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void fill_zero_kernel(int32_t *p, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+
+hipError_t launch_fill_zero(int32_t *p, int64_t n, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p, n);
+    return hipGetLastError();
+}
+
 hipError_t launch_decode(const KernArgs &a, hipStream_t s)
 {
     if (a.p.static_runs <= 0 || a.p.dec_blocks <= 0) return hipSuccess;
