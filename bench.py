@@ -258,14 +258,20 @@ def bench_append(a):
 
 def bench_preempt(a):
     """Layer-level preemption of an offline decode iteration by an online prefill chunk (paper Section 3.4.1),
-    attention layers only: config 4's 512 offline decode sequences run a 32-layer iteration, one ooco_attn_mixed
-    call per layer, enqueued with a run-ahead of at most two layers; a preemption flag is raised while layer
-    `at` runs and is looked at before every enqueue.  On preemption the 64 victims' KV blocks are copied to a
-    staging pool, a 2048-token online chunk (on 4096 tokens of context) runs its 32 attention layers in the
-    freed blocks, the victims are copied back, and the iteration resumes at the layer it stopped at."""
+    attention layers only, through the package's preemption driver (paper_2511_21862_amd/preempt.py): config 4's
+    512 offline decode sequences run a 32-layer iteration, one ooco_attn_mixed per layer, enqueued with a run-ahead
+    of at most two layers; a timer thread raises the preemption flag somewhere inside the iteration and the loop
+    sees it before its next enqueue.  The online request (2048 new tokens on 4096 tokens of context = 384 KV
+    blocks, none free) names its victims through ooco_eviction_victims, once on a compute-bound node (long
+    requests first) and once on a memory-bound one (short first); their blocks go to a staging pool through
+    ooco_kv_block_copy, the chunk runs its 32 attention layers in the freed blocks, the victims come back, and the
+    iteration resumes at the layer it stopped at."""
+    import threading
+
     import torch
 
     from paper_2511_21862_amd import binding as B
+    from paper_2511_21862_amd import preempt as P
     from paper_2511_21862_amd import workloads as W
 
     L = 32
@@ -273,87 +279,86 @@ def bench_preempt(a):
     dev = lambda x: torch.from_numpy(np.ascontiguousarray(x)).cuda()
     bt, sl, qsl, cl = dev(b.block_tables), dev(b.seq_lens), dev(b.query_start_loc), dev(b.ctx_lens)
     out = torch.empty((b.total_q, b.Hq, b.hd), dtype=torch.bfloat16, device="cuda")
-    victims = np.asarray(b.extra["victims"])
-    src = W.victim_block_ids(b, victims)
-    n = len(src)
-    src_d, stage_d = dev(src), torch.arange(n, dtype=torch.int64, device="cuda")
-    k_st = torch.empty((n,) + tuple(b.k_cache.shape[1:]), dtype=torch.bfloat16, device="cuda")
-    v_st = torch.empty((n,) + tuple(b.v_cache.shape[1:]), dtype=torch.bfloat16, device="cuda")
-    # the online chunk lives in the victims' blocks (they are free while the victims sit in the staging pool)
     c_len, c_ctx = 2048, 4096
     c_nb = (c_len + c_ctx + 15) // 16
-    assert c_nb <= n
-    c_bt = np.full((1, b.max_blocks_per_seq), -1, np.int32)
-    c_bt[0, :c_nb] = src[:c_nb]
-    c_meta = [dev(c_bt), dev(np.array([c_len + c_ctx], np.int32)), dev(np.array([0, c_len], np.int32)),
-              dev(np.array([c_ctx], np.int32))]
     c_q = torch.randn((c_len, b.Hq, b.hd), device="cuda").to(torch.bfloat16)
     c_out = torch.empty_like(c_q)
     stream = torch.cuda.current_stream()
     dec = B.Context(b.Hq, b.Hkv, b.hd, b.BS, b.num_blocks, b.max_blocks_per_seq)
     onl = B.Context(b.Hq, b.Hkv, b.hd, b.BS, b.num_blocks, b.max_blocks_per_seq)
+    dec.set_option("plan_persistent", 1)
+    onl.set_option("plan_persistent", 1)
     dec.plan(b.seq_lens, b.query_start_loc, b.ctx_lens)
-    onl.plan(np.array([c_len + c_ctx], np.int32), np.array([0, c_len], np.int32), np.array([c_ctx], np.int32))
+    c_seq, c_qsl, c_cx = np.array([c_len + c_ctx], np.int32), np.array([0, c_len], np.int32), np.array([c_ctx], np.int32)
+    onl.plan(c_seq, c_qsl, c_cx)
 
-    def layer():
+    def layer(_l):
         dec.attn_mixed(b.q, b.k_cache, b.v_cache, bt, sl, qsl, cl, out, stream)
 
-    def iteration(preempt_at=None):
-        """Returns (wall seconds, dict of the preemption's parts or None)."""
+    def iteration(bs_sat=None, delay=None):
+        """One iteration; with bs_sat a timer raises the flag `delay` seconds after the start."""
         torch.cuda.synchronize()
+        flag = P.PreemptFlag() if bs_sat is not None else None
+        timer = None
+
+        def on_preempt(_next_layer):
+            t0 = time.perf_counter()
+            ev = P.Eviction(dec, b.seq_lens, b.block_tables, c_nb, bs_sat)
+            k_st, v_st = P.staging_pools(b, ev.num_blocks)
+            t1 = time.perf_counter()
+            ev.evict(b.k_cache, b.v_cache, k_st, v_st, stream)
+            stream.synchronize()
+            t2 = time.perf_counter()
+            c_bt = np.full((1, b.max_blocks_per_seq), -1, np.int32)
+            c_bt[0, :c_nb] = ev.block_ids[:c_nb]
+            meta = [dev(c_bt), dev(c_seq), dev(c_qsl), dev(c_cx)]
+            for _ in range(L):
+                onl.attn_mixed(c_q, b.k_cache, b.v_cache, *meta, c_out, stream)
+            stream.synchronize()
+            t3 = time.perf_counter()
+            ev.restore(b.k_cache, b.v_cache, k_st, v_st, stream)
+            stream.synchronize()
+            t4 = time.perf_counter()
+            return dict(victims=len(ev.victims), victim_blocks=ev.num_blocks, select_ms=(t1 - t0) * 1e3,
+                        evict_ms=(t2 - t1) * 1e3, online_chunk_layers_ms=(t3 - t2) * 1e3, restore_ms=(t4 - t3) * 1e3)
+
+        if flag is not None:
+            timer = threading.Timer(delay, flag.raise_now)
+            timer.start()
         t0 = time.perf_counter()
-        evs, parts = [], None
-        flag_time = None
-        l = 0
-        while l < L:
-            if len(evs) >= 2:
-                evs[-2].synchronize()            # run-ahead of at most two layers
-            if preempt_at is not None and flag_time is None and l == preempt_at + 2:
-                # the flag goes up while layer `preempt_at` runs (its predecessor has just finished); the two layers
-                # already enqueued complete, nothing further is enqueued
-                flag_time = time.perf_counter()
-                torch.cuda.synchronize()
-                t_idle = time.perf_counter()
-                dec.kv_block_copy(b.k_cache, b.v_cache, k_st, v_st, src_d, stage_d, stream)
-                torch.cuda.synchronize()
-                t_evict = time.perf_counter()
-                for _ in range(L):
-                    onl.attn_mixed(c_q, b.k_cache, b.v_cache, *c_meta, c_out, stream)
-                torch.cuda.synchronize()
-                t_online = time.perf_counter()
-                dec.kv_block_copy(k_st, v_st, b.k_cache, b.v_cache, stage_d, src_d, stream)
-                torch.cuda.synchronize()
-                t_restore = time.perf_counter()
-                parts = dict(preempt_latency_ms=(t_idle - flag_time) * 1e3, evict_ms=(t_evict - t_idle) * 1e3,
-                             online_chunk_32_layers_ms=(t_online - t_evict) * 1e3, restore_ms=(t_restore - t_online) * 1e3)
-                evs = []
-            layer()
-            e = torch.cuda.Event()
-            e.record(stream)
-            evs.append(e)
-            l += 1
-        torch.cuda.synchronize()
-        return time.perf_counter() - t0, parts
+        rep = P.run_layers(L, layer, stream, flag=flag, on_preempt=on_preempt)
+        dt = time.perf_counter() - t0
+        if timer is not None:
+            timer.join()
+        return dt, rep
 
     for _ in range(max(1, a.warmup // 8)):
         iteration()
-        iteration(5)
-    plain = [iteration()[0] for _ in range(max(3, a.steps // 20))]
-    pre = [iteration(int(at)) for at in np.random.default_rng(9).integers(0, L - 2, size=max(3, a.steps // 20))]
+    n_it = max(3, a.steps // 20)
+    plain = [iteration()[0] for _ in range(n_it)]
+    t_plain = float(np.median(plain))
     want = out.clone()
-    iteration()
+    regimes = {}
+    rng = np.random.default_rng(9)
+    for name, bs_sat in (("compute_bound", 256), ("memory_bound", 4096)):
+        runs = [iteration(bs_sat, float(rng.uniform(0.1, 0.8)) * t_plain) for _ in range(n_it)]
+        runs = [(t, r) for t, r in runs if r is not None]
+        keys = [k for k in runs[0][1] if k != "resumed_at_layer"]
+        regimes[name] = {k: float(np.median([r[k] for _, r in runs])) for k in keys}
+        regimes[name]["preempted_iteration_ms"] = float(np.median([t for t, _ in runs])) * 1e3
+        regimes[name]["preemptions"] = len(runs)
+        regimes[name]["bs_sat"] = bs_sat
     same = bool(torch.equal(want.view(torch.int16), out.view(torch.int16)))
-    parts = {k: float(np.median([p[1][k] for p in pre])) for k in pre[0][1]}
-    t_plain, t_pre = float(np.median(plain)), float(np.median([p[0] for p in pre]))
     line = {
         "metric": "layer-level preemption of an offline decode iteration (attention layers only), 1 MI355X",
         "value": b.total_q * L / t_plain, "unit": "tokens/s", "n_gpus": 1, "steps": len(plain), "warmup": a.warmup,
         "ms_per_step": t_plain * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": "cfg4-preempt", "layers": L, "decode_seqs": b.num_seqs, "victims": len(victims),
-                   "victim_blocks": n, "online_chunk": [c_len, c_ctx], "run_ahead_layers": 2},
-        "iteration_ms": t_plain * 1e3, "preempted_iteration_ms": t_pre * 1e3, **parts,
-        "layer_ms": t_plain * 1e3 / L, "output_after_preemption_bit_identical": same,
+        "config": {"workload": "cfg4-preempt", "layers": L, "decode_seqs": b.num_seqs, "online_chunk": [c_len, c_ctx],
+                   "online_chunk_blocks": c_nb, "run_ahead_layers": 2},
+        "iteration_ms": t_plain * 1e3, "layer_ms": t_plain * 1e3 / L,
+        "preempt_latency_ms": {k: v["preempt_latency_ms"] for k, v in regimes.items()},
+        "preemption": regimes, "output_after_preemption_bit_identical": same,
     }
     dec.close()
     onl.close()
@@ -399,6 +404,8 @@ def main():
     for o in a.opt:
         k, v = o.split("=")
         ctx.set_option(k, int(v))
+    if not a.replan_every_step:
+        ctx.set_option("plan_persistent", 1)
     stream = torch.cuda.current_stream()
     host_us = {"plan": 0.0, "launch": 0.0}
 

@@ -130,6 +130,13 @@ const char *ooco_last_error(const ooco_ctx *ctx);
  *                         estimate of the kernel time improves by at least 7 %.  A tile
  *                         never gets more parts than it has 64-key steps.
  * Immediate options:
+ *   "plan_persistent"  0/1 (default 0): 0 = a plan made by ooco_plan serves exactly one ooco_attn_mixed and is
+ *                then used up (a later call without a new plan plans by itself from the device arrays), so that
+ *                a caller that advances the lengths on the device between steps can never run on a stale
+ *                plan; 1 = the plan stays current for every following call with the same num_seqs and
+ *                total_q_tokens until the next ooco_plan -- for callers that repeat one batch (benchmarks,
+ *                the layers of one iteration, graph replay), who then answer for the device arrays still
+ *                matching it
  *   "overlap"    0/1 (default 1): in a batch that holds both prefill chunks and decode sequences,
  *                run the prefill kernel on the context's own side stream (default priority)
  *                concurrently with the decode kernel; the call still appears as one unit of work
@@ -212,7 +219,7 @@ ooco_status ooco_plan_dry_run(int num_q_heads, int num_kv_heads, int head_dim, i
                               const int32_t *xcd_weights /*HOST, 8 values in 1..255, or NULL*/,
                               int64_t prefill_split, int64_t decode_piece_pad);
 
-/* Numbers describing the current plan (any pointer may be NULL): decode runs (waves per kv head),
+/* Numbers describing the last plan made, current or used up (any pointer may be NULL): decode runs (waves per kv head),
  * prefill tiles, KV blocks of all decode sequences, bytes of workspace the partial results use,
  * parts each prefill tile's key range is cut into (1 = not split). */
 ooco_status ooco_plan_info(const ooco_ctx *ctx, int64_t *decode_waves, int64_t *prefill_tiles,
@@ -223,7 +230,8 @@ ooco_status ooco_plan_info(const ooco_ctx *ctx, int64_t *decode_waves, int64_t *
  *   block_tables, seq_lens, query_start_loc, ctx_lens: DEVICE int32 (shapes above).
  *   stream: a hipStream_t (NULL = the default stream).
  * If ooco_plan was called for this batch (same num_seqs and total_q_tokens) its work lists are
- * used and the three DEVICE length arrays are trusted to equal the planned HOST copies.
+ * used and the three DEVICE length arrays are trusted to equal the planned HOST copies; the plan is
+ * used up by the call unless option "plan_persistent" is set.
  * Without a current plan the call copies the length arrays to the host, waits for that copy
  * (one stream synchronisation) and plans by itself.
  * Launches at most two kernels (decode with its in-kernel merge, and prefill chunks on the context's

@@ -344,6 +344,8 @@ struct ooco_ctx {
     bool plan_valid = false;
     bool plan_dirty = false;
     bool plan_one_shot = false;   // planned inside ooco_attn_mixed from device lengths
+    bool plan_made = false;       // ctx->plan holds the numbers of the last plan made (current or used up)
+    int64_t opt_plan_persistent = 0;   // an explicit plan serves every following call of the same shape
 
     // options
     int64_t opt_segments = 0;
@@ -574,6 +576,9 @@ ooco_status ooco_set_option(ooco_ctx *ctx, const char *name, int64_t value)
             return fail(ctx, OOCO_EINVAL, "ooco_set_option: copy_variant must be one of 0, 10, 11, 20, 21, 40, 41, 80, 81");
         ctx->opt_copy_variant = (int)value;
         return OOCO_OK;
+    } else if (!strcmp(name, "plan_persistent")) {
+        ctx->opt_plan_persistent = value;
+        return OOCO_OK;
     } else if (!strcmp(name, "overlap")) {
         ctx->opt_overlap = value;
         return OOCO_OK;
@@ -631,6 +636,7 @@ ooco_status ooco_plan(ooco_ctx *ctx, int num_seqs, const int32_t *h_seq_lens, co
     if ((size_t)num_seqs * ctx->Hkv > kCounterInts - 1 || 3 * ((size_t)num_seqs + 1) > kPlanInts)
         return fail(ctx, OOCO_ENOMEM, "ooco_plan: %d sequences exceed the context's counter/plan buffers", num_seqs);
     ctx->plan_valid = true;
+    ctx->plan_made = true;
     ctx->plan_dirty = true;
     ctx->plan_one_shot = false;
     return OOCO_OK;
@@ -714,7 +720,7 @@ ooco_status ooco_plan_info(const ooco_ctx *ctx, int64_t *decode_waves, int64_t *
                            int64_t *workspace_used, int64_t *prefill_parts)
 {
     if (!ctx) return OOCO_EINVAL;
-    if (!ctx->plan_valid) return fail(ctx, OOCO_EINVAL, "ooco_plan_info: no current plan");
+    if (!ctx->plan_made) return fail(ctx, OOCO_EINVAL, "ooco_plan_info: no plan has been made");
     if (decode_waves) *decode_waves = ctx->plan.static_runs;
     if (prefill_tiles) *prefill_tiles = ctx->plan.n_tiles;
     if (decode_blocks) *decode_blocks = ctx->plan.kv_blocks;
@@ -906,7 +912,9 @@ ooco_status ooco_attn_mixed(ooco_ctx *ctx, const void *q, const void *k_cache, c
         run_decode();
     }
     mark(5, s);
-    if (ctx->plan_one_shot) {
+    // A plan serves one call: the device length arrays are trusted to equal the planned host copies, and a caller
+    // that advances the lengths between steps must plan again (option "plan_persistent" keeps an explicit plan).
+    if (ctx->plan_one_shot || !ctx->opt_plan_persistent) {
         ctx->plan_one_shot = false;
         ctx->plan_valid = false;
     }

@@ -39,6 +39,7 @@ def _measure(torch, B, ctx, pool, Hq, Hkv, hd, q_lens, ctx_lens, perm, reps, ove
     q = torch.randn((T, Hq, hd), device="cuda").to(torch.bfloat16)
     out = torch.empty_like(q)
     ctx.set_option("overlap", overlap)
+    ctx.set_option("plan_persistent", 1)
     ctx.plan(seq, qsl, cx)
     stream = torch.cuda.current_stream()
     ts = []

@@ -1,7 +1,7 @@
 """GPU parity at the full sizes of the benchmark configurations, in the launch configuration
-bench.py times (default plan, default options, device-resident pools): sampled query rows are
-checked one by one against the float64 C oracle (a chunk row is a single-query decode over its
-visible keys, see workloads.row_sample), plus properties that hold at any size."""
+bench.py times (default plan, default options, device-resident pools): EVERY query row of
+configurations 2-5 is checked against the float64 C oracle (the sequences travel to the host in
+groups), plus properties that hold at any size."""
 import numpy as np
 import pytest
 import torch
@@ -29,57 +29,68 @@ def run_device_batch(b, options=None):
     return out, info
 
 
-def sampled_pairs(b, rng, n_decode, rows_per_chunk):
-    """(sequence, row) pairs: the longest and shortest decode sequences plus random ones; for every
-    chunk its first and last rows, the rows around the query-tile boundaries and random rows."""
-    ql = b.q_lens
-    dec = np.flatnonzero(ql == 1)
-    pairs = []
-    if len(dec):
-        order = dec[np.argsort(b.seq_lens[dec], kind="stable")]
-        pick = {int(order[0]), int(order[-1])}
-        pick.update(int(x) for x in rng.choice(dec, size=min(n_decode, len(dec)), replace=False))
-        pairs += [(s, 0) for s in sorted(pick)]
-    tile_rows = max(1, 128 // (b.Hq // b.Hkv))
-    for s in np.flatnonzero(ql > 1):
-        n = int(ql[s])
-        rows = {0, 1, n - 1, n - 2}
-        for t in (tile_rows, (n // tile_rows // 2) * tile_rows, ((n - 1) // tile_rows) * tile_rows):
-            rows.update((t - 1, t, t + 1))
-        rows.update(int(x) for x in rng.integers(0, n, size=rows_per_chunk))
-        pairs += [(int(s), t) for t in sorted(r for r in rows if 0 <= r < n)]
-    return pairs
+def oracle_all_rows(b, kv_tokens_per_batch=600_000):
+    """The float64 C oracle on EVERY query row of a device-resident batch: the sequences go to the host in groups
+    (workloads.subset: a compact copy of their blocks) of at most `kv_tokens_per_batch` KV tokens, so that host
+    memory stays bounded; returns float64 [total_q, Hq, hd]."""
+    ref = np.full((b.total_q, b.Hq, b.hd), np.nan, dtype=np.float64)
+    order = [int(i) for i in np.flatnonzero(b.q_lens > 0)]
+    group, tokens, n_groups = [], 0, 0
+    def flush():
+        nonlocal group, tokens, n_groups
+        if not group:
+            return
+        s = W.subset(b, group)
+        r = ref_c.attn_mixed(s.q, s.k_cache, s.v_cache, s.block_tables, s.seq_lens, s.query_start_loc, s.ctx_lens)
+        ref[s.extra["rows"]] = r
+        n_groups += 1
+        group, tokens = [], 0
+    for i in order:
+        if group and tokens + int(b.seq_lens[i]) > kv_tokens_per_batch:
+            flush()
+        group.append(i)
+        tokens += int(b.seq_lens[i])
+    flush()
+    assert not np.isnan(ref).any()
+    return ref, n_groups
 
 
-CASES = [
-    # name, n_decode samples, random rows per chunk
-    ("config2", 64, 0),
-    ("config3", 24, 24),
-    ("config4", 24, 0),
-    ("config5", 4, 16),
-]
+def worst_rows(got_bits, ref, b):
+    """(row, sequence, max-abs error) of the worst query row, and the worst per-row relative L2 error."""
+    g = W.bf16_bits_to_f32(got_bits).astype(np.float64)
+    d = np.abs(g - ref).reshape(ref.shape[0], -1)
+    row_max = d.max(axis=1)
+    row_rel = np.sqrt((d ** 2).sum(axis=1)) / np.maximum(np.sqrt((ref.reshape(ref.shape[0], -1) ** 2).sum(axis=1)), 1e-30)
+    r = int(row_max.argmax())
+    seq = int(np.searchsorted(b.query_start_loc, r, side="right") - 1)
+    return dict(row=r, seq=seq, seq_len=int(b.seq_lens[seq]), max_abs=float(row_max[r]), worst_row_rel_l2=float(row_rel.max()),
+                worst_rel_row=int(row_rel.argmax()))
 
 
-@pytest.mark.parametrize("name,n_decode,rows_per_chunk", CASES)
-def test_full_size_sampled_rows(name, n_decode, rows_per_chunk):
+CASES = ["config2", "config3", "config4", "config5"]
+
+
+@pytest.mark.parametrize("name", CASES)
+def test_full_size_every_row(name):
     b = getattr(W, name)(device="cuda")
     say(f"case: {name} full size: {b.num_seqs} sequences, {b.total_q} query tokens, pool {b.num_blocks} blocks")
     out, info = run_device_batch(b)
     say(f"  plan: {info}")
-    # property at any size: every output element was written and is finite
     assert bool(torch.isfinite(out.float()).all()), f"{name}: non-finite or unwritten output"
-    pairs = sampled_pairs(b, np.random.default_rng(1234), n_decode, rows_per_chunk)
-    s = W.row_sample(b, pairs)
-    say(f"  oracle on {len(pairs)} sampled rows ({int(s.seq_lens.sum())} keys)")
-    ref = ref_c.attn_mixed(s.q, s.k_cache, s.v_cache, s.block_tables, s.seq_lens, s.query_start_loc, s.ctx_lens)
-    rows = torch.from_numpy(s.extra["rows"]).cuda()
-    got = out.index_select(0, rows).view(torch.int16).cpu().numpy().view(np.uint16)
-    assert_parity(got, ref, f"{name} sampled")
-    # property at any size: a second call with the dynamic tail and other run counts changes nothing
-    # beyond rounding (the same rows still pass the gate)
+    ref, n_groups = oracle_all_rows(b)
+    say(f"  oracle on all {b.total_q} rows ({int(b.seq_lens[b.q_lens > 0].sum())} KV tokens) in {n_groups} groups")
+    got = out.view(torch.int16).cpu().numpy().view(np.uint16)
+    assert_parity(got, ref, f"{name}, every row")
+    w = worst_rows(got, ref, b)
+    say(f"  worst row: {w}")
+    # no single row hides behind the batch-wide averages: each row alone is within the absolute gate, and within a
+    # relative error that bf16 rounding of output and weights explains
+    assert w["max_abs"] <= 2e-2 and w["worst_row_rel_l2"] <= 2.5e-2
+    # a second call with the dynamic tail and other run counts changes nothing beyond rounding: every row again
     out2, _ = run_device_batch(b, options={"decode_segments": 64, "decode_tail_pct": 10})
-    got2 = out2.index_select(0, rows).view(torch.int16).cpu().numpy().view(np.uint16)
-    assert_parity(got2, ref, f"{name} sampled, other run layout")
+    got2 = out2.view(torch.int16).cpu().numpy().view(np.uint16)
+    assert_parity(got2, ref, f"{name}, every row, other run layout")
+    say(f"  worst row, other run layout: {worst_rows(got2, ref, b)}")
 
 
 def test_config4_preemption_sequence():

@@ -26,6 +26,7 @@ def test_captured_calls_replay_to_the_eager_result(mixed):
     eager = torch.empty((b.total_q, b.Hq, b.hd), dtype=torch.bfloat16, device="cuda")
     out = torch.zeros_like(eager)
     with B.Context(b.Hq, b.Hkv, b.hd, b.BS, b.num_blocks, b.max_blocks_per_seq) as ctx:
+        ctx.set_option("plan_persistent", 1)     # one plan serves the eager calls, the capture and nothing changes in between
         ctx.plan(b.seq_lens, b.query_start_loc, b.ctx_lens)
         assert (ctx.plan_info()["prefill_parts"] > 1) == (mixed == "split")
         ctx.attn_mixed(d.q, d.k_cache, d.v_cache, bt, sl, qsl, cl, eager)
@@ -59,6 +60,7 @@ def test_a_plan_with_a_dynamic_tail_is_refused_on_a_capturing_stream():
     say("case: graph capture of a plan with a dynamic tail")
     out = torch.zeros((b.total_q, b.Hq, b.hd), dtype=torch.bfloat16, device="cuda")
     with B.Context(b.Hq, b.Hkv, b.hd, b.BS, b.num_blocks, b.max_blocks_per_seq) as ctx:
+        ctx.set_option("plan_persistent", 1)
         ctx.set_option("decode_segments", 4)
         ctx.set_option("decode_tail_pct", 20)
         ctx.set_option("decode_tail_blocks", 4)

@@ -291,6 +291,7 @@ def test_profiled_calls_keep_the_overlap_and_the_results():
     bt, sl, qsl, cl = device_meta(b)
     out = torch.empty((b.total_q, b.Hq, b.hd), dtype=torch.bfloat16, device="cuda")
     with B.Context(b.Hq, b.Hkv, b.hd, b.BS, b.num_blocks, b.max_blocks_per_seq) as ctx:
+        ctx.set_option("plan_persistent", 1)
         ctx.plan(b.seq_lens, b.query_start_loc, b.ctx_lens)
         ctx.attn_mixed(d.q, d.k_cache, d.v_cache, bt, sl, qsl, cl, out)
         torch.cuda.synchronize()
@@ -310,3 +311,23 @@ def test_profiled_calls_keep_the_overlap_and_the_results():
     assert (pc[:, 2] >= pc[:, :2].max(axis=1) * 0.9).all()
     assert torch.equal(out.view(torch.int16), plain.view(torch.int16))
     assert_parity(out.view(torch.int16).cpu().numpy().view(np.uint16), oracle(b), "profiled mixed call")
+
+
+def test_a_plan_serves_one_call_only():
+    # decode loop: the caller plans once and then advances the lengths on the device only.  The plan is used up by
+    # its call, so the later calls plan by themselves from the device arrays and see every new token, also when a
+    # sequence crosses a block boundary.
+    base = np.array([15, 31, 700, 1024], np.int32)
+    say("case: plan used up by its call, lengths advance on the device")
+    with B.Context(32, 8, 128, 16, 200, 80) as ctx:
+        full = W.build_batch(Hq=32, Hkv=8, hd=128, q_lens=[1, 1, 1, 1], ctx_lens=base + 2, num_blocks=200, seed=95,
+                             max_blocks_per_seq=80)
+        for step in range(3):
+            # the same pools and tables, lengths one token longer every step
+            b = W.Batch(Hq=32, Hkv=8, hd=128, BS=16, num_blocks=200, block_tables=full.block_tables,
+                        seq_lens=base + 1 + step, ctx_lens=base + step, query_start_loc=full.query_start_loc, q=full.q,
+                        k_cache=full.k_cache, v_cache=full.v_cache)
+            if step == 0:
+                ctx.plan(b.seq_lens, b.query_start_loc, b.ctx_lens)
+            got = run_gpu(b, plan=False, ctx=ctx)
+            assert_parity(got, oracle(b), f"decode step {step}")

@@ -8,6 +8,7 @@ import numpy as np
 import pytest
 import torch
 
+from oracle import migration, mix_select
 from paper_2511_21862_amd import binding as B
 from paper_2511_21862_amd import workloads as W
 
@@ -16,6 +17,12 @@ from gpu_util import say
 pytestmark = pytest.mark.gpu
 
 HERE = os.path.dirname(os.path.abspath(__file__))
+
+# How far a measured decode step may lie from the latency model's prediction.  The fit report
+# (profiles/perf_model_mi355x.md) lists every decode batch large enough to occupy the GPU within 7.4 % of the
+# model (worst row: 512 sequences of ~256 tokens); the same kernel on the same batch differs by up to 5 % from one
+# MI355X machine to another.  The two together, rounded up:
+MODEL_ERR = 0.15
 
 
 def timed_decode(Hq, Hkv, hd, lens, num_blocks=49152, burst=8, reps=7):
@@ -28,6 +35,7 @@ def timed_decode(Hq, Hkv, hd, lens, num_blocks=49152, burst=8, reps=7):
     stream = torch.cuda.current_stream()
     ts = []
     with B.Context(Hq, Hkv, hd, 16, b.num_blocks, b.max_blocks_per_seq) as ctx:
+        ctx.set_option("plan_persistent", 1)
         ctx.plan(b.seq_lens, b.query_start_loc, b.ctx_lens)
         for r in range(reps + 2):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -52,6 +60,10 @@ def test_admitted_batch_runs_within_the_bound(slo_us):
     order = rng.permutation(len(offline))[:32]
     S = slo_us * 1e-6
     r = B.ooco_mix_decoding_select(p, 32, 8, 128, S, online, offline, order)
+    # the library's decision is Algorithm 2's: the same selection and latency as the oracle, request by request
+    want = mix_select.mix_decoding_select(p, 32, 8, 128, S, online, offline, order)
+    assert list(r["selected"]) == want["selected"]
+    assert r["latency"] == pytest.approx(want["latency"], rel=1e-12)
     chosen = np.concatenate([online, offline[r["selected"]]])
     say(f"case: SLO {slo_us} us: {int(r['selected'].sum())} of {len(offline)} offline requests admitted, "
         f"{int(chosen.sum())} KV tokens, predicted {r['latency'] * 1e6:.1f} us")
@@ -62,8 +74,10 @@ def test_admitted_batch_runs_within_the_bound(slo_us):
         or left.min() > offline[r["selected"]].max()
     t = timed_decode(32, 8, 128, chosen)
     say(f"  measured {t * 1e6:.1f} us per call ({t / S * 100:.0f} % of the bound, model error {(r['latency'] / t - 1) * 100:+.1f} %)")
-    assert t <= 1.35 * S, "admitted batch overran the bound by more than the model's error margin"
-    assert t >= 0.5 * S, "admitted batch leaves most of the bound unused"
+    # the bound holds on the hardware as far as the model is accurate: the step takes what was predicted, within
+    # the model's error (the prediction itself is within the bound, and the budget is used, both asserted above)
+    assert abs(t / r["latency"] - 1.0) <= MODEL_ERR, "measured step differs from the prediction by more than the model's error"
+    assert t <= (1.0 + MODEL_ERR) * S
 
 
 @pytest.mark.parametrize("bs_sat,label", [(32, "saturated"), (96, "reach")])
@@ -77,6 +91,9 @@ def test_batch_after_migration_runs_within_the_bound(bs_sat, label):
     # saturated case: 2000 free KV blocks bound the preference; other case: the latency bound does
     S, cap = 250e-6, (int(sum(-(-int(x) // 16) for x in strict)) + 2000 if label == "saturated" else 49152 - 1024)
     d = B.ooco_migration_preference(p, 32, 8, 128, S, strict, True, bs_sat, 16, cap, 64, 65536)
+    # the library's decision is Algorithm 1's: the oracle scans every length on offer and finds the same preference
+    want = migration.migration_preference(p, 32, 8, 128, S, strict, True, bs_sat, 16, cap, 64, 65536)
+    assert d["pref"] == want["pref"] and d["branch"] == want["branch"]
     assert d["branch"] == label and d["pref"] is not None
     n = max(1, bs_sat - len(strict))
     # the preferred length is the largest that fits: n requests of that length are predicted within the bound,
@@ -88,6 +105,7 @@ def test_batch_after_migration_runs_within_the_bound(bs_sat, label):
         longer = np.concatenate([strict, np.full(n, d["pref"] + 1, np.int32)])
         assert L(longer) > S or (label == "saturated" and sum(-(-int(x) // 16) for x in longer) > cap)
     chosen = B.ooco_migration_select(p, 32, 8, 128, S, strict, relaxed, d["pref"], 16, cap, 64)
+    assert chosen == migration.migration_select(p, 32, 8, 128, S, strict, relaxed, d["pref"], 16, cap, 64)
     batch = np.concatenate([strict, relaxed[chosen]])
     say(f"case: {label}: preference {d['pref']} tokens, {len(chosen)} requests migrated "
         f"(lengths {relaxed[chosen].min() if chosen else 0}..{relaxed[chosen].max() if chosen else 0}), "
@@ -96,4 +114,4 @@ def test_batch_after_migration_runs_within_the_bound(bs_sat, label):
     t0 = timed_decode(32, 8, 128, strict)
     t = timed_decode(32, 8, 128, batch)
     say(f"  measured {t0 * 1e6:.1f} us before, {t * 1e6:.1f} us after ({t / S * 100:.0f} % of the bound)")
-    assert t0 < S and t <= 1.35 * S
+    assert t0 < S and abs(t / L(batch) - 1.0) <= MODEL_ERR and t <= (1.0 + MODEL_ERR) * S

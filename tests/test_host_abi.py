@@ -19,6 +19,12 @@ def declared_symbols():
     return sorted(set(re.findall(r"\b(ooco_[a-z_]+)\s*\(", text)))
 
 
+# The comparisons of the host functions with their oracles need no GPU; they run in the CPU suite and, under the
+# second parameter, once more in the GPU suite, so that the record of the GPU run shows them against the library
+# that runs there.
+BOTH_RECORDS = pytest.mark.parametrize("record", ["cpu", pytest.param("gpu-box", marks=pytest.mark.gpu)])
+
+
 def test_library_exports_every_declared_symbol():
     lib = ctypes.CDLL(B.LIB_PATH)
     names = declared_symbols()
@@ -229,7 +235,8 @@ def test_empty_batch_plans_to_nothing():
 
 
 # ----------------------------------------------------------------------------- latency model (host function)
-def test_predict_latency_equals_the_model_oracle():
+@BOTH_RECORDS
+def test_predict_latency_equals_the_model_oracle(record):
     from oracle import perf_model
     rng = np.random.default_rng(3)
     for trial in range(40):
@@ -256,7 +263,8 @@ def test_predict_latency_equals_the_model_oracle():
 
 
 # ----------------------------------------------------------------------------- Mix Decoding Selection (host function)
-def test_mix_decoding_select_equals_the_oracle():
+@BOTH_RECORDS
+def test_mix_decoding_select_equals_the_oracle(record):
     from oracle import mix_select
     rng = np.random.default_rng(12)
     p = dict(F_ap=9e14, F_ad=2e14, M_a=6e12, O_p=1e-5, O_d=9e-6)
@@ -290,7 +298,8 @@ def test_mix_decoding_select_equals_the_oracle():
 
 
 # ----------------------------------------------------------------------------- migration decision, eviction rule
-def test_migration_and_eviction_equal_the_oracle():
+@BOTH_RECORDS
+def test_migration_and_eviction_equal_the_oracle(record):
     from oracle import migration, mix_select
     rng = np.random.default_rng(31)
     branches = set()
@@ -324,7 +333,8 @@ def test_migration_and_eviction_equal_the_oracle():
     assert branches == {"none", "saturated", "reach", "shortest"}
 
 
-def test_migration_golden_cases_through_the_library():
+@BOTH_RECORDS
+def test_migration_golden_cases_through_the_library(record):
     mp = dict(F_ap=1e18, F_ad=1e18, M_a=4.096e9, O_p=0.0, O_d=10e-6)
     path = os.path.join(ROOT, "tests", "golden", "migration.txt")
     rows = [l.split() for l in open(path) if l[:1].isalpha()]
