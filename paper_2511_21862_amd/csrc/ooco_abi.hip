@@ -80,6 +80,8 @@ struct PlanGeometry {
     int64_t tail_blocks;    // KV blocks per dynamically fetched run
     int64_t pf_split_opt = 0;   // parts per prefill tile; 0 = automatic
     int64_t piece_pad = 0;      // line units charged for starting a piece (see build_plan)
+    int64_t fused = 0;          // batches with both kinds of work run in the one-launch mixed kernel
+    int64_t dec_cus_opt = 0;    // mixed kernel: compute units per XCD that decode; 0 = automatic
     uint16_t xcd_cw[kXcds] = {};   // cumulative XCD weights of the static runs; zeros = equal runs
 };
 
@@ -98,6 +100,7 @@ struct HostPlan {
     uint16_t cw[kXcds] = {};     // XCD weights in force (RunLayout::cw)
     int32_t n_tiles = 0, total_q = 0, num_seqs = 0;
     int32_t pf_split = 1;        // parts each prefill tile's keys are cut into
+    int32_t dec_cus = 0;         // > 0: the batch runs in the mixed kernel with this many decoding compute units per XCD
     int64_t slots = 0;           // partial-result slots the decode kernel may touch
 };
 
@@ -159,6 +162,7 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
     // runs cut the line into equal lengths, so a run that starts several pieces streams correspondingly fewer
     // blocks (starting a piece costs a wave about as long as streaming three 8 KiB tiles).
     int64_t dec_blocks = 0, kv_blocks = 0, tiles = 0, tile_steps = 0, max_tile_steps = 1;
+    double pf_pairs = 0.0;   // visible (query row, key) pairs of all prefill chunks
     const int64_t pad = geo.piece_pad;
     const int tile_rows = prefill_tile_rows(geo.Hq / geo.Hkv);
     for (int i = 0; i < num_seqs; ++i) {
@@ -178,6 +182,7 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
             kv_blocks += nb;
         }
         if (ql > 1) {
+            pf_pairs += (double)ql * (double)h_ctx_lens[i] + (double)ql * (double)(ql + 1) / 2.0;
             tiles += (ql + tile_rows - 1) / tile_rows;
             for (int64_t t0 = 0; t0 < ql; t0 += tile_rows) {    // 64-key steps of every tile
                 const int64_t nstep = ((int64_t)h_ctx_lens[i] + std::min<int64_t>(ql, t0 + tile_rows) + 63) / 64;
@@ -212,21 +217,39 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
         pf[n_order + 1 + k] = order[k];
     }
 
+    // ---- one launch for both kinds of work: how many compute units of every XCD decode.  The decode part is
+    // bound by HBM and reaches its bandwidth from a part of the units; the prefill part is bound by the matrix
+    // cores and takes as long as its share of the units makes it.  The prefill units are sized so that they
+    // finish with the decode stream (estimated from rates measured on MI355X: 6.8 TB/s, and 1.05 PFLOP/s on all
+    // units), leaving the decode side at least kMinDecCus units per XCD; whoever finishes first helps the other.
+    const int cus_per_xcd = std::max(1, geo.num_cus / kXcds);
+    if (geo.fused && dec_blocks > 0 && tiles > 0 && cus_per_xcd >= 4 && geo.num_cus % kXcds == 0) {
+        constexpr int kMinDecCus = 10;
+        const double t_dec = (double)kv_blocks * BS * 2.0 * geo.Hkv * geo.hd * 2.0 / 6.8e12;
+        const double t_pf = 4.0 * geo.Hq * geo.hd * pf_pairs / 1.05e15;
+        int pf_cus = (int)std::ceil(cus_per_xcd * t_pf / std::max(t_dec, 1e-9));
+        pf_cus = std::max(1, std::min(pf_cus, cus_per_xcd - std::min(kMinDecCus, cus_per_xcd / 2)));
+        int dec = cus_per_xcd - pf_cus;
+        if (geo.dec_cus_opt > 0) dec = (int)std::min<int64_t>(geo.dec_cus_opt, cus_per_xcd - 1);
+        out.dec_cus = dec;
+    }
     // ---- run layout of the decode block line (see ooco_internal.h)
     if (dec_blocks > 0) {
         // static runs: by default three waves per CU (measured best on MI355X: enough loads in
         // flight to saturate HBM, few enough waves that start-up and partial results stay small)
         // and at least ~32 blocks per wave
-        const int64_t wave_slots = std::max<int64_t>(1, (int64_t)geo.num_cus * 3 / geo.Hkv);
+        // (mixed kernel: eight decode waves on every decoding unit, one run each)
+        const int64_t wave_slots = out.dec_cus > 0 ? std::max<int64_t>(1, (int64_t)out.dec_cus * kXcds * 8 / geo.Hkv)
+                                                   : std::max<int64_t>(1, (int64_t)geo.num_cus * 3 / geo.Hkv);
         int64_t runs = geo.segments_opt > 0 ? geo.segments_opt : std::min<int64_t>(wave_slots, (kv_blocks + 31) / 32);
         runs = std::max<int64_t>(1, std::min<int64_t>(runs, dec_blocks));
         for (;;) {
             // weighted runs come in groups of one run per XCD
-            bool weighted = geo.xcd_cw[kXcds - 1] != 0 && runs >= kXcds;
+            bool weighted = geo.xcd_cw[kXcds - 1] != 0 && runs >= kXcds && out.dec_cus == 0;
             if (weighted) runs -= runs % kXcds;
             // dynamic tail: only when a static run is much longer than a tail run
             int64_t tail_blk = 0, tails = 0;
-            if (geo.tail_pct > 0 && geo.tail_blocks > 0 && dec_blocks / runs >= 4 * geo.tail_blocks) {
+            if (geo.tail_pct > 0 && geo.tail_blocks > 0 && dec_blocks / runs >= 4 * geo.tail_blocks && out.dec_cus == 0) {
                 tail_blk = std::min<int64_t>(dec_blocks - runs, dec_blocks * std::min<int64_t>(geo.tail_pct, 90) / 100);
                 tails = (tail_blk + geo.tail_blocks - 1) / geo.tail_blocks;
                 if (tails == 0) tail_blk = 0;
@@ -362,6 +385,8 @@ struct ooco_ctx {
     int32_t *pf_counters = nullptr;   // [kPrefillSplitUnits] arrival counters of split prefill tiles, zero between calls
     uint16_t xcd_cw[kXcds] = {};   // option "xcd_weights"
     int64_t opt_overlap = 1;
+    int64_t opt_fused = 0;          // mixed batches in one launch (mixed kernel) instead of two kernels on two streams
+    int64_t opt_dec_cus = 0;        // mixed kernel: decoding compute units per XCD, 0 = automatic
     hipStream_t side_stream = nullptr;   // default priority; carries the prefill kernel of mixed batches
     hipEvent_t fork_ev = nullptr, join_ev = nullptr;
     uint64_t *trace_d = nullptr;   // [kTraceWaves][4] decode-wave time stamps
@@ -559,6 +584,10 @@ ooco_status ooco_set_option(ooco_ctx *ctx, const char *name, int64_t value)
         ctx->opt_pf_split = value;
     else if (!strcmp(name, "decode_first"))
         ctx->opt_decode_first = value;
+    else if (!strcmp(name, "mixed_fused"))
+        ctx->opt_fused = value;
+    else if (!strcmp(name, "mixed_dec_cus"))
+        ctx->opt_dec_cus = value;
     else if (!strcmp(name, "decode_piece_pad")) {
         if (value > 64) return fail(ctx, OOCO_EINVAL, "ooco_set_option: decode_piece_pad must be 0..64");
         ctx->opt_piece_pad = value;
@@ -627,13 +656,15 @@ ooco_status ooco_plan(ooco_ctx *ctx, int num_seqs, const int32_t *h_seq_lens, co
     geo.tail_blocks = ctx->opt_tail_blocks;
     geo.pf_split_opt = ctx->opt_pf_split;
     geo.piece_pad = ctx->opt_piece_pad;
+    geo.fused = ctx->opt_fused && ctx->opt_overlap;
+    geo.dec_cus_opt = ctx->opt_dec_cus;
     for (int k = 0; k < kXcds; ++k) geo.xcd_cw[k] = ctx->xcd_cw[k];
     const size_t cap = (size_t)std::max(num_seqs, 0);
     if (ctx->plan_store.size() < storage_ints(cap)) ctx->plan_store.resize(storage_ints(cap));
     ooco_status st = build_plan(geo, num_seqs, h_seq_lens, h_query_start_loc, h_ctx_lens,
                                 carve_storage(ctx->plan_store.data(), cap), ctx->plan, ctx->err);
     if (st != OOCO_OK) return st;
-    if ((size_t)num_seqs * ctx->Hkv > kCounterInts - 1 || 3 * ((size_t)num_seqs + 1) > kPlanInts)
+    if ((size_t)num_seqs * ctx->Hkv > kCounterInts - kMixedStateInts || 3 * ((size_t)num_seqs + 1) > kPlanInts)
         return fail(ctx, OOCO_ENOMEM, "ooco_plan: %d sequences exceed the context's counter/plan buffers", num_seqs);
     ctx->plan_valid = true;
     ctx->plan_made = true;
@@ -776,7 +807,9 @@ ooco_status ooco_attn_mixed(ooco_ctx *ctx, const void *q, const void *k_cache, c
 
     // The cumulative arrays ride in the kernel arguments; only very large batches need a copy.
     const size_t n_cum = (size_t)num_seqs + 1, n_pf = pl.pf_size;
-    const bool inline_cum = n_cum <= (size_t)kInlineSeqs + 1 && n_pf <= (size_t)kInlineSeqs + 1;
+    // (the mixed kernel, pl.dec_cus > 0, takes both arrays at once; the two separate kernels one each)
+    const bool inline_cum = pl.dec_cus > 0 ? n_cum + n_pf <= (size_t)kInlineSeqs + 1
+                                           : n_cum <= (size_t)kInlineSeqs + 1 && n_pf <= (size_t)kInlineSeqs + 1;
     if (!inline_cum && ctx->plan_dirty) {
         if (ctx->upload_pending) (void)hipEventSynchronize(ctx->upload_done);
         memcpy(ctx->plan_h, pl.dcum, n_cum * sizeof(int32_t));
@@ -809,9 +842,11 @@ ooco_status ooco_attn_mixed(ooco_ctx *ctx, const void *q, const void *k_cache, c
         p.pf_counters = ctx->pf_counters;
         p.pf_split = pl.pf_split;
     }
-    const bool tracing = ctx->opt_trace && ctx->trace_d && (size_t)pl.static_runs * ctx->Hkv <= kTraceWaves;
+    // (the mixed kernel stamps once per workgroup, the decode kernel once per wave)
+    const int64_t trace_rows = pl.dec_cus > 0 && pl.n_tiles > 0 ? 2 * (int64_t)ctx->num_cus : (int64_t)pl.static_runs * ctx->Hkv;
+    const bool tracing = ctx->opt_trace && ctx->trace_d && (size_t)trace_rows <= kTraceWaves;
     p.trace = tracing ? ctx->trace_d : nullptr;
-    if (tracing) ctx->trace_waves = (int64_t)pl.static_runs * ctx->Hkv;
+    if (tracing) ctx->trace_waves = trace_rows;
     p.Hq = ctx->Hq;
     p.Hkv = ctx->Hkv;
     p.g = ctx->g;
@@ -829,6 +864,7 @@ ooco_status ooco_attn_mixed(ooco_ctx *ctx, const void *q, const void *k_cache, c
     p.queue_base = ctx->queue_base;
     p.n_tiles = pl.n_tiles;
     p.num_pf = pl.num_pf;
+    p.dec_cus = pl.dec_cus;
     p.tile_rows = prefill_tile_rows(ctx->g);
     p.nbi = (int32_t)ctx->opt_nbi;
     p.rotate_heads = (int32_t)ctx->opt_rotate;
@@ -865,7 +901,10 @@ ooco_status ooco_attn_mixed(ooco_ctx *ctx, const void *q, const void *k_cache, c
     // and the whole call by two on the caller's stream (ev[4..5]), so the times are those of the kernels
     // as they run in the step.
     const bool mixed = pl.n_tiles > 0 && pl.static_runs > 0;
-    const bool overlap = mixed && ctx->opt_overlap && ctx->side_stream;
+    // ... or, by default, in ONE launch: the mixed kernel, whose compute units either decode or prefill (the plan
+    // says how many do which).  Both arrays of the plan travel together (in the kernel arguments if they fit).
+    const bool fused = mixed && pl.dec_cus > 0;
+    const bool overlap = mixed && !fused && ctx->opt_overlap && ctx->side_stream;
     hipStream_t ps = overlap ? ctx->side_stream : s;   // the stream of the prefill kernel
     auto mark = [&](int k, hipStream_t st) {
         if (ev && e == hipSuccess) e = hipEventRecord(ev[k], st);
@@ -894,7 +933,18 @@ ooco_status ooco_attn_mixed(ooco_ctx *ctx, const void *q, const void *k_cache, c
         mark(1, s);
     };
     mark(4, s);
-    if (overlap) {
+    if (fused) {
+        p.cum_dev = inline_cum ? nullptr : ctx->plan_d;
+        if (inline_cum) {
+            memcpy(ka.cum, pl.dcum, n_cum * sizeof(int32_t));
+            memcpy(ka.cum + n_cum, pl.pf, n_pf * sizeof(int32_t));
+        }
+        mark(0, s);
+        mark(2, s);
+        if (e == hipSuccess) e = launch_mixed(ka, ctx->num_cus, s);
+        mark(1, s);
+        mark(3, s);
+    } else if (overlap) {
         // fork before anything else is enqueued, so that the side stream waits for nothing of this call
         if (e == hipSuccess) e = hipEventRecord(ctx->fork_ev, s);
         if (e == hipSuccess) e = hipStreamWaitEvent(ctx->side_stream, ctx->fork_ev, 0);

@@ -35,6 +35,7 @@ constexpr int kPrefillCols = 128;   // (row, head) query columns per prefill wor
 constexpr int kInlineSeqs = 960;    // sequences whose cumulative array fits the kernel arguments
 constexpr int kMaxPrefillSplit = 8; // parts a prefill tile's keys may be cut into
 constexpr int kPrefillSplitUnits = 8192;   // (tile, kv head) pairs up to which the split is available
+constexpr int kMixedStateInts = 4096;      // ints in front of (and including) the ticket counter that the mixed kernel keeps its claims and counters in
 
 struct AttnParams {
     const uint16_t *q;
@@ -57,7 +58,8 @@ struct AttnParams {
     int32_t dec_blocks, static_blocks, static_runs, tail_runs;   // decode run layout
     int32_t piece_pad;   // line units in front of every decode sequence's blocks (the cost of starting a piece)
     int32_t n_tiles, tile_rows; // prefill: tiles per kv head, query rows per tile
-    int32_t num_pf, pad_pf;     // prefill: number of chunks (entries of the prefill array, see below)
+    int32_t num_pf;             // prefill: number of chunks (entries of the prefill array, see below)
+    int32_t dec_cus;            // mixed kernel: compute units per XCD that run decode waves (the others run prefill tiles)
     int32_t nbi;                // tuning: KV blocks per softmax step of the decode kernel
     int32_t rotate_heads;       // tuning: kv head rotation across XCDs
     uint16_t xcd_cw[8];         // cumulative XCD weights of the static runs (RunLayout::cw); zeros = equal runs
@@ -81,6 +83,9 @@ static_assert(sizeof(KernArgs) <= 4096, "kernel arguments must stay within 4 KiB
 // unless a.p.cum_dev is set.  Each returns the hipError_t of its launch.
 hipError_t launch_decode(const KernArgs &a, hipStream_t s);
 hipError_t launch_prefill(const KernArgs &a, hipStream_t s);
+// One launch for a batch with both kinds of work: a.cum holds the decode array (num_seqs + 1 entries) followed by
+// the prefill array (or a.p.cum_dev both, in that order); 2 * num_cus persistent workgroups.
+hipError_t launch_mixed(const KernArgs &a, int num_cus, hipStream_t s);
 // variant: tuning knob of the block-copy kernel (option "copy_variant"): 10 x 16-byte vectors per thread
 // + 1 for non-temporal accesses; 0 = default
 hipError_t launch_block_copy(const void *k_src, const void *v_src, void *k_dst, void *v_dst,

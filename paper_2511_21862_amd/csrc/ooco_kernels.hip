@@ -227,58 +227,18 @@ OOCO_DEV int count_le(CumAt cum_at, int n, int x, int lane)
 // stores (acc, m, l) in fp32 into partial slot k + seq, then bumps the arrival counter of
 // (seq, kv head); the piece that arrives last merges all slots of the sequence in slot order
 // (so the result does not depend on which piece is last) and resets the counter.
-template <int HD, int NBI>
-__global__ __launch_bounds__(64, 2) void decode_kernel(const KernArgs a)
+// One run of the decode line for one kv head, all its pieces, executed by one wave (see above).
+// `at_stream_end()` is called once the last piece of the run has been streamed, before its epilogue.
+template <int HD, int NBI, class CumAt, class AtStreamEnd>
+OOCO_DEV void decode_run(const AttnParams &p, CumAt cum_at, const RunLayout &L, int run, int kvh, int lane, uint64_t *trace,
+                         bool &first_piece, AtStreamEnd at_stream_end)
 {
     constexpr int KC = HD / 32;
     constexpr int NB = HD / 16;
-    const AttnParams &p = a.p;
-    // What a wave needs before its first KV tile is on its way comes from a dozen places of the kernel
-    // arguments; asked for one after the other, each at its point of use, they cost a wave ten dependent
-    // round trips to the scalar cache.  Naming them here makes the compiler fetch them together.
-    asm volatile("" ::"s"(p.q), "s"(p.k_cache), "s"(p.v_cache), "s"(p.block_tables), "s"(p.seq_lens),
-                 "s"(p.query_start_loc), "s"(p.cum_dev), "s"(p.trace), "s"(p.queue), "s"(p.Hq), "s"(p.Hkv), "s"(p.g),
-                 "s"(p.max_blocks_per_seq), "s"(p.num_seqs), "s"(p.total_q), "s"(p.dec_blocks), "s"(p.static_blocks),
-                 "s"(p.static_runs), "s"(p.tail_runs), "s"(p.piece_pad), "s"(p.rotate_heads), "s"(p.scale_log2e),
-                 "s"(p.queue_base), "s"(*reinterpret_cast<const uint64_t *>(&p.xcd_cw[0])),
-                 "s"(*reinterpret_cast<const uint64_t *>(&p.xcd_cw[4])));
-    const int lane = threadIdx.x;
     const int col = lane & 15;
     const int kq = lane >> 4;
-    // Workgroups are handed to the XCDs round-robin and the kv heads of a block lie in adjacent
-    // 4 KiB pieces of memory: rotating the head by the run index gives every XCD every kv head
-    // in turn instead of pinning XCD x to head x.
-    int run = blockIdx.x / p.Hkv;
-    int kvh = p.rotate_heads ? (int)((blockIdx.x - run * p.Hkv + run) % p.Hkv) : (int)(blockIdx.x - run * p.Hkv);
-    if (p.xcd_cw[kXcds - 1]) {
-        // weighted runs: all kv heads of run v on XCD v % 8 (workgroup b runs on XCD b % 8)
-        const int x = blockIdx.x % kXcds, t = blockIdx.x / kXcds;
-        kvh = t % p.Hkv;
-        run = kXcds * (t / p.Hkv) + x;
-    }
     const int g = p.g;
     const int64_t tile_elems = (int64_t)HD * kBlockSize;   // one (block, kv head) tile
-    auto cum_at = [&](int idx) -> int { return p.cum_dev ? p.cum_dev[idx] : a.cum[idx]; };
-    const RunLayout L = {p.dec_blocks, p.static_blocks, p.static_runs, p.tail_runs, p.xcd_cw};
-    const unsigned tail_tasks = (unsigned)p.tail_runs * (unsigned)p.Hkv;
-
-    uint64_t *trace = p.trace ? p.trace + (int64_t)blockIdx.x * 4 : nullptr;   // per-wave time stamps
-    if (trace && lane == 0) trace[0] = wall_clock64();
-    bool first_piece = true;
-
-  for (;;) {   // the wave's own run first, then tail runs by ticket
-    // The ticket for the next tail run is drawn when the last piece of this run has been streamed (whoever
-    // is done first gets the next run) and looked at after that piece's epilogue, which covers the round
-    // trip of the atomic.  (Every wave ends by drawing a ticket that tells it to stop; atomics on one address
-    // are served one after the other, about 13 ns each on MI355X, which is why the tail only pays on long
-    // kernels.)
-    unsigned ticket = 0xFFFFFFFFu;
-    bool drawn = false;
-    auto draw = [&]() {
-        if (lane == 0)
-            ticket = __hip_atomic_fetch_add(p.queue, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - p.queue_base;
-        drawn = true;
-    };
     const int head = kvh * g + col;
     int lo, hi;
     run_bounds(L, run, lo, hi);
@@ -439,7 +399,7 @@ __global__ __launch_bounds__(64, 2) void decode_kernel(const KernArgs a)
         }
 
         if (trace && stop == hi && lane == 0) trace[2] = wall_clock64();   // end of streaming
-        if (tail_tasks && stop == hi) draw();
+        if (stop == hi) at_stream_end();
         float ltot = rows_sum(lsum);
         bool store_out = whole;
         if (!whole) {
@@ -544,6 +504,57 @@ __global__ __launch_bounds__(64, 2) void decode_kernel(const KernArgs a)
         pos = stop;
         ++seq;
     }
+}
+
+template <int HD, int NBI>
+__global__ __launch_bounds__(64, 2) void decode_kernel(const KernArgs a)
+{
+    const AttnParams &p = a.p;
+    // What a wave needs before its first KV tile is on its way comes from a dozen places of the kernel
+    // arguments; asked for one after the other, each at its point of use, they cost a wave ten dependent
+    // round trips to the scalar cache.  Naming them here makes the compiler fetch them together.
+    asm volatile("" ::"s"(p.q), "s"(p.k_cache), "s"(p.v_cache), "s"(p.block_tables), "s"(p.seq_lens),
+                 "s"(p.query_start_loc), "s"(p.cum_dev), "s"(p.trace), "s"(p.queue), "s"(p.Hq), "s"(p.Hkv), "s"(p.g),
+                 "s"(p.max_blocks_per_seq), "s"(p.num_seqs), "s"(p.total_q), "s"(p.dec_blocks), "s"(p.static_blocks),
+                 "s"(p.static_runs), "s"(p.tail_runs), "s"(p.piece_pad), "s"(p.rotate_heads), "s"(p.scale_log2e),
+                 "s"(p.queue_base), "s"(*reinterpret_cast<const uint64_t *>(&p.xcd_cw[0])),
+                 "s"(*reinterpret_cast<const uint64_t *>(&p.xcd_cw[4])));
+    const int lane = threadIdx.x;
+    // Workgroups are handed to the XCDs round-robin and the kv heads of a block lie in adjacent
+    // 4 KiB pieces of memory: rotating the head by the run index gives every XCD every kv head
+    // in turn instead of pinning XCD x to head x.
+    int run = blockIdx.x / p.Hkv;
+    int kvh = p.rotate_heads ? (int)((blockIdx.x - run * p.Hkv + run) % p.Hkv) : (int)(blockIdx.x - run * p.Hkv);
+    if (p.xcd_cw[kXcds - 1]) {
+        // weighted runs: all kv heads of run v on XCD v % 8 (workgroup b runs on XCD b % 8)
+        const int x = blockIdx.x % kXcds, t = blockIdx.x / kXcds;
+        kvh = t % p.Hkv;
+        run = kXcds * (t / p.Hkv) + x;
+    }
+    auto cum_at = [&](int idx) -> int { return p.cum_dev ? p.cum_dev[idx] : a.cum[idx]; };
+    const RunLayout L = {p.dec_blocks, p.static_blocks, p.static_runs, p.tail_runs, p.xcd_cw};
+    const unsigned tail_tasks = (unsigned)p.tail_runs * (unsigned)p.Hkv;
+
+    uint64_t *trace = p.trace ? p.trace + (int64_t)blockIdx.x * 4 : nullptr;   // per-wave time stamps
+    if (trace && lane == 0) trace[0] = wall_clock64();
+    bool first_piece = true;
+
+  for (;;) {   // the wave's own run first, then tail runs by ticket
+    // The ticket for the next tail run is drawn when the last piece of this run has been streamed (whoever
+    // is done first gets the next run) and looked at after that piece's epilogue, which covers the round
+    // trip of the atomic.  (Every wave ends by drawing a ticket that tells it to stop; atomics on one address
+    // are served one after the other, about 13 ns each on MI355X, which is why the tail only pays on long
+    // kernels.)
+    unsigned ticket = 0xFFFFFFFFu;
+    bool drawn = false;
+    auto draw = [&]() {
+        if (lane == 0)
+            ticket = __hip_atomic_fetch_add(p.queue, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - p.queue_base;
+        drawn = true;
+    };
+    decode_run<HD, NBI>(p, cum_at, L, run, kvh, lane, trace, first_piece, [&]() {
+        if (tail_tasks) draw();
+    });
     if (!tail_tasks) break;
     if (!drawn) draw();   // (a run that held no block)
     ticket = __builtin_amdgcn_readfirstlane(ticket);
@@ -586,10 +597,12 @@ __global__ __launch_bounds__(64, 2) void decode_kernel(const KernArgs a)
 constexpr int kPfThreads = 256;
 constexpr int kPfBlocks = 4;    // KV blocks per step
 
-template <int HD>
-__global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a)
+// One workgroup's work on virtual block index `vb` (what blockIdx.x is in the stand-alone kernel): unit vb / split
+// = (tile, kv head), part vb % split of its keys.  `cum_at(i)` reads the prefill array of the plan.  All 256
+// threads of the workgroup call it together; every return is workgroup-uniform.
+template <int HD, class CumAt>
+OOCO_DEV void prefill_unit(const AttnParams &p, CumAt cum_at, const int vb)
 {
-    const AttnParams &p = a.p;
     constexpr int KS = HD / 16;        // k-steps of QK
     constexpr int MB = HD / 32;        // 32-dim groups of the output
     constexpr int CH = HD * 2;         // 16-byte chunks per (block, kv head) tile
@@ -606,8 +619,8 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
     const int g = p.g;
     // workgroup -> (unit = (tile, kv head), part of the unit's keys)
     const int split = p.pf_split;
-    const int unit = blockIdx.x / split;
-    const int part = blockIdx.x - unit * split;
+    const int unit = vb / split;
+    const int part = vb - unit * split;
     const int tile_idx = unit / p.Hkv;
     const int kvh = unit - tile_idx * p.Hkv;
 
@@ -615,7 +628,6 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
     // the later rows of a chunk see more keys and the hardware dispatches in index order
     int seq, q_row0, rows, pos0, seq_len;
     {
-        auto cum_at = [&](int idx) -> int { return p.cum_dev ? p.cum_dev[idx] : a.cum[idx]; };
         const int chunk = __builtin_amdgcn_readfirstlane(count_le(cum_at, p.num_pf, tile_idx, lane));
         const int t_end = cum_at(chunk + 1);
         seq = min(max(cum_at(p.num_pf + 1 + chunk), 0), p.num_seqs - 1);
@@ -995,6 +1007,133 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
     }
 }
 
+template <int HD>
+__global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a)
+{
+    const AttnParams &p = a.p;
+    prefill_unit<HD>(p, [&](int idx) -> int { return p.cum_dev ? p.cum_dev[idx] : a.cum[idx]; }, (int)blockIdx.x);
+}
+
+// ------------------------------------------------------------------------------------------
+// Mixed batches in ONE launch: a persistent grid of two 256-thread workgroups per compute unit in which a compute
+// unit runs EITHER decode waves (eight per unit, each streaming runs of the decode line exactly as the decode
+// kernel's waves do) OR prefill workgroups (two per unit, each working through (tile, kv head) units exactly as
+// the prefill kernel's workgroups do).  Side by side on one unit the two kinds get into each other's way -- the
+// decode waves lose their issue slots and the matrix pipe to prefill waves that keep both busy, the prefill
+// workgroups lose half their register file -- and both kernels stretch; apart, the decode units keep HBM busy
+// while the prefill units keep the matrix cores busy.
+//   * Which unit does what: the first workgroup to arrive on a compute unit (identified by the hardware's XCD,
+//     shader-engine and CU ids) claims it and draws the unit's rank within its XCD from a counter; the other
+//     workgroup of the unit reads that rank.  Ranks below p.dec_cus decode, the others prefill, so every XCD (and
+//     its L2) gets the same mix.
+//   * Work is pulled from counters: decode waves draw (run, kv head) items, prefill workgroups draw units from
+//     the list of their own XCD first (unit index = XCD mod 8, so the tiles that share keys meet in one L2, as
+//     in the stand-alone kernel) and from the other XCDs' lists after that.
+//   * A workgroup whose own kind of work has run out takes up the other kind once, then leaves: the split of the
+//     units only has to be roughly right.
+// Nothing waits for another workgroup except the bounded look at a claim in progress, so the grid drains whatever
+// the placement.  The last workgroup to leave resets the claims and counters for the next launch (or replay).
+// State (int32, zero between launches), at p.queue - kMixedStateInts + 1:
+//   [0, 2048) claims: 0 free, 1 being claimed, rank + 2;  [2048, 2056) arrivals per XCD;
+//   [2056, 2064) prefill units drawn per XCD;  [2064] decode items drawn;  [2065] workgroups that have left
+constexpr int kMixedClaims = 2048;
+template <int HD>
+__global__ __launch_bounds__(kPfThreads, 2) void mixed_kernel(const KernArgs a)
+{
+    const AttnParams &p = a.p;
+    __shared__ int sh_role, sh_item;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    int32_t *const state = reinterpret_cast<int32_t *>(p.queue) - (kMixedStateInts - 1);
+    int32_t *const claims = state, *const xcd_arrivals = state + kMixedClaims, *const pf_drawn = state + kMixedClaims + 8;
+    int32_t *const dec_drawn = state + kMixedClaims + 16, *const left = state + kMixedClaims + 17;
+    const int n_cum = p.num_seqs + 1;   // the prefill array follows the decode array
+    auto dcum_at = [&](int idx) -> int { return p.cum_dev ? p.cum_dev[idx] : a.cum[idx]; };
+    auto pf_at = [&](int idx) -> int { return p.cum_dev ? p.cum_dev[n_cum + idx] : a.cum[n_cum + idx]; };
+    const unsigned xcc = __builtin_amdgcn_s_getreg((31 << 11) | 20) & 7u;              // XCC_ID
+    if (tid == 0) {
+        const unsigned hw = __builtin_amdgcn_s_getreg((31 << 11) | 4);                 // HW_ID: CU, SH, SE ids in bits 8..15
+        int32_t *const claim = claims + (xcc * 256u + ((hw >> 8) & 255u));
+        int expected = 0, rank;
+        if (__hip_atomic_compare_exchange_strong(claim, &expected, 1, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                                 __HIP_MEMORY_SCOPE_AGENT)) {
+            rank = __hip_atomic_fetch_add(xcd_arrivals + xcc, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(claim, rank + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        } else {
+            // the claimant runs on this very compute unit and needs two more memory operations: a bounded look
+            int v = expected;
+            for (int spin = 0; v < 2 && spin < (1 << 16); ++spin) {
+                __builtin_amdgcn_s_sleep(8);
+                v = __hip_atomic_load(claim, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            rank = v >= 2 ? v - 2 : 0;   // (never seen: decode)
+        }
+        sh_role = rank < p.dec_cus ? 0 : 1;
+    }
+    __syncthreads();
+    int role = sh_role;   // 0 = decode, 1 = prefill
+    // option "trace": per workgroup (start, end of its first kind of work, end of its second kind, first role +
+    // 256 * items of wave 0 in the first kind + 2^32 * items in the second) on the 100 MHz clock
+    uint64_t *const trace = p.trace ? p.trace + (int64_t)blockIdx.x * 4 : nullptr;
+    uint64_t n_items[2] = {0, 0};
+    if (trace && tid == 0) {
+        trace[0] = wall_clock64();
+        trace[3] = (uint64_t)role;
+    }
+    const int n_dec_items = p.static_runs * p.Hkv;
+    const int n_vb = p.n_tiles * p.Hkv * p.pf_split;
+    const RunLayout L = {p.dec_blocks, p.static_blocks, p.static_runs, 0, p.xcd_cw};
+    for (int pass = 0; pass < 2; ++pass, role ^= 1) {
+        if (role == 0) {
+            bool first_piece = false;
+            for (;;) {
+                int item = 0;
+                if (lane == 0) item = __hip_atomic_fetch_add(dec_drawn, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                item = __builtin_amdgcn_readfirstlane(item);
+                if (item >= n_dec_items) break;
+                const int run = item / p.Hkv;
+                const int kvh = (item - run * p.Hkv + run) % p.Hkv;   // kv heads rotate over the runs
+                decode_run<HD, (HD == 64 ? 2 : 1)>(p, dcum_at, L, run, kvh, lane, nullptr, first_piece, []() {});
+                ++n_items[pass];
+            }
+        } else {
+            for (;;) {
+                __syncthreads();   // everybody is done with the last unit's LDS tiles and has read sh_item
+                if (tid == 0) {
+                    int vb = -1;
+                    for (unsigned k = 0; k < 8 && vb < 0; ++k) {
+                        const unsigned x = (xcc + k) & 7u;
+                        const int count = (n_vb - (int)x + 7) / 8;   // units x, x + 8, ... below n_vb
+                        // (a look before the draw keeps the counters of exhausted lists from running on)
+                        if (__hip_atomic_load(pf_drawn + x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= count) continue;
+                        const int j = __hip_atomic_fetch_add(pf_drawn + x, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        if (j < count) vb = 8 * j + (int)x;
+                    }
+                    sh_item = vb;
+                }
+                __syncthreads();
+                const int vb = sh_item;
+                if (vb < 0) break;
+                prefill_unit<HD>(p, pf_at, vb);
+                ++n_items[pass];
+            }
+        }
+        __syncthreads();   // the whole workgroup changes its kind of work together
+        if (trace && tid == 0) trace[1 + pass] = wall_clock64();
+    }
+    if (trace && tid == 0) trace[3] += (n_items[0] << 8) + (n_items[1] << 32);
+    // leave; the last workgroup out clears the state
+    if (tid == 0) {
+        const int gone = __hip_atomic_fetch_add(left, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sh_item = gone == (int)gridDim.x - 1;
+    }
+    __syncthreads();
+    if (sh_item) {
+        for (int i = tid; i < kMixedStateInts - 1; i += kPfThreads)
+            __hip_atomic_store(state + i, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
 // ------------------------------------------------------------------------------------------
 // KV block copy: workgroup (pair, which pool, slice) moves a contiguous slice of one block with
 // 16-byte loads and stores; all loads of a thread are issued before its stores.
@@ -1158,6 +1297,17 @@ hipError_t launch_prefill(const KernArgs &a, hipStream_t s)
         hipLaunchKernelGGL((prefill_kernel<128>), grid, block, 0, s, a);
     else
         hipLaunchKernelGGL((prefill_kernel<64>), grid, block, 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_mixed(const KernArgs &a, int num_cus, hipStream_t s)
+{
+    if (a.p.n_tiles <= 0 || a.p.static_runs <= 0) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)(2 * num_cus)), block(kPfThreads);
+    if (a.p.hd == 128)
+        hipLaunchKernelGGL((mixed_kernel<128>), grid, block, 0, s, a);
+    else
+        hipLaunchKernelGGL((mixed_kernel<64>), grid, block, 0, s, a);
     return hipGetLastError();
 }
 
