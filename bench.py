@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the mixed-batch paged-attention step on ONE MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5|cfg3|cfg2|cfg4|cfg3-prefill|cfg5-prefill|cfg4-copy|cfg4-copy-seq|cfg3-append|cfg5-append|cfg4-preempt]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5|cfg3|cfg2|cfg4|cfg3-prefill|cfg5-prefill|cfg4-copy|cfg4-copy-seq|cfg3-append|cfg5-append|cfg4-preempt|shape-<Hq>-<Hkv>-<hd>]
 
 The default workload is the largest mixed configuration (cfg5: 2 online prefill chunks of 2048 tokens + 32 offline
 decode sequences of 32K-131K tokens, 64/8 heads).
@@ -55,6 +55,12 @@ def make_workload(name):
         return W.config5(device="cuda"), "decode"
     if name == "cfg5-prefill":
         return W.config5(device="cuda", n_decode=0, num_blocks=4096), "prefill"
+    if name.startswith("shape-"):   # shape-<Hq>-<Hkv>-<hd>: 256 decode sequences of 512-4096 tokens with another head shape
+        Hq, Hkv, hd = (int(x) for x in name.split("-")[1:4])
+        rng = np.random.default_rng(77)
+        seq = W.uniform_lengths(rng, 256, 512, 4096)
+        return W.build_batch(Hq=Hq, Hkv=Hkv, hd=hd, q_lens=np.ones(256, np.int32), ctx_lens=seq - 1, num_blocks=98304,
+                             seed=77, device="cuda", rng=rng, name=f"decode256-{Hq}-{Hkv}-{hd}"), "decode"
     raise SystemExit(f"unknown workload {name}")
 
 

@@ -80,6 +80,7 @@ struct PlanGeometry {
     int64_t tail_blocks;    // KV blocks per dynamically fetched run
     int64_t pf_split_opt = 0;   // parts per prefill tile; 0 = automatic
     int64_t piece_pad = 0;      // line units charged for starting a piece (see build_plan)
+    int64_t pf_waves_opt = 0;   // waves per prefill workgroup: 4, 8, or 0 = automatic
     int64_t fused = 0;          // batches with both kinds of work run in the one-launch mixed kernel
     int64_t dec_cus_opt = 0;    // mixed kernel: compute units per XCD that decode; 0 = automatic
     uint16_t xcd_cw[kXcds] = {};   // cumulative XCD weights of the static runs; zeros = equal runs
@@ -100,6 +101,7 @@ struct HostPlan {
     uint16_t cw[kXcds] = {};     // XCD weights in force (RunLayout::cw)
     int32_t n_tiles = 0, total_q = 0, num_seqs = 0;
     int32_t pf_split = 1;        // parts each prefill tile's keys are cut into
+    int32_t pf_waves = 4;        // waves per prefill workgroup (32 query columns each)
     int32_t dec_cus = 0;         // > 0: the batch runs in the mixed kernel with this many decoding compute units per XCD
     int64_t slots = 0;           // partial-result slots the decode kernel may touch
 };
@@ -164,7 +166,13 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
     int64_t dec_blocks = 0, kv_blocks = 0, tiles = 0, tile_steps = 0, max_tile_steps = 1;
     double pf_pairs = 0.0;   // visible (query row, key) pairs of all prefill chunks
     const int64_t pad = geo.piece_pad;
-    const int tile_rows = prefill_tile_rows(geo.Hq / geo.Hkv);
+    // Waves per prefill workgroup.  Eight waves share every K/V tile staged in LDS among 256 query columns instead
+    // of 128, which halves the traffic from L2 into the compute units.  Measured on MI355X it is no faster (that
+    // traffic is not what bounds the kernel) and its 220-register waves leave no room for decode waves beside
+    // them, so four waves are the default; eight (head_dim 128 only) stay selectable.
+    const int pf_waves = geo.hd == 128 && geo.pf_waves_opt == 8 ? 8 : 4;
+    out.pf_waves = pf_waves;
+    const int tile_rows = prefill_tile_rows(geo.Hq / geo.Hkv, pf_waves);
     for (int i = 0; i < num_seqs; ++i) {
         const int64_t ql = (int64_t)h_query_start_loc[i + 1] - h_query_start_loc[i];
         if (ql < 0) return bad(OOCO_ESHAPE, "ooco_plan: query_start_loc decreases at sequence %d", i);
@@ -223,7 +231,7 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
     // finish with the decode stream (estimated from rates measured on MI355X: 6.8 TB/s, and 1.05 PFLOP/s on all
     // units), leaving the decode side at least kMinDecCus units per XCD; whoever finishes first helps the other.
     const int cus_per_xcd = std::max(1, geo.num_cus / kXcds);
-    if (geo.fused && dec_blocks > 0 && tiles > 0 && cus_per_xcd >= 4 && geo.num_cus % kXcds == 0) {
+    if (geo.fused && pf_waves == 4 && dec_blocks > 0 && tiles > 0 && cus_per_xcd >= 4 && geo.num_cus % kXcds == 0) {
         constexpr int kMinDecCus = 10;
         const double t_dec = (double)kv_blocks * BS * 2.0 * geo.Hkv * geo.hd * 2.0 / 6.8e12;
         const double t_pf = 4.0 * geo.Hq * geo.hd * pf_pairs / 1.05e15;
@@ -231,6 +239,7 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
         pf_cus = std::max(1, std::min(pf_cus, cus_per_xcd - std::min(kMinDecCus, cus_per_xcd / 2)));
         int dec = cus_per_xcd - pf_cus;
         if (geo.dec_cus_opt > 0) dec = (int)std::min<int64_t>(geo.dec_cus_opt, cus_per_xcd - 1);
+        if (geo.dec_cus_opt == 99) dec = 99;   // every unit runs both kinds (one workgroup each): for measurements
         out.dec_cus = dec;
     }
     // ---- run layout of the decode block line (see ooco_internal.h)
@@ -239,7 +248,8 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
         // flight to saturate HBM, few enough waves that start-up and partial results stay small)
         // and at least ~32 blocks per wave
         // (mixed kernel: eight decode waves on every decoding unit, one run each)
-        const int64_t wave_slots = out.dec_cus > 0 ? std::max<int64_t>(1, (int64_t)out.dec_cus * kXcds * 8 / geo.Hkv)
+        const int64_t wave_slots = out.dec_cus == 99 ? std::max<int64_t>(1, (int64_t)geo.num_cus * 4 / geo.Hkv)
+                                   : out.dec_cus > 0 ? std::max<int64_t>(1, (int64_t)out.dec_cus * kXcds * 8 / geo.Hkv)
                                                    : std::max<int64_t>(1, (int64_t)geo.num_cus * 3 / geo.Hkv);
         int64_t runs = geo.segments_opt > 0 ? geo.segments_opt : std::min<int64_t>(wave_slots, (kv_blocks + 31) / 32);
         runs = std::max<int64_t>(1, std::min<int64_t>(runs, dec_blocks));
@@ -302,7 +312,7 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
                         split = sp;
                     }
             }
-            const size_t part_bytes = (size_t)kPrefillCols * (geo.hd + 2) * sizeof(float);
+            const size_t part_bytes = (size_t)(32 * pf_waves) * (geo.hd + 2) * sizeof(float);
             const size_t left = geo.ws_bytes - std::min(geo.ws_bytes, ((size_t)out.slots * slot_bytes(geo) + 255) / 256 * 256);
             while (split > 1 && (size_t)units * (size_t)split * part_bytes > left) --split;
         }
@@ -385,6 +395,7 @@ struct ooco_ctx {
     int32_t *pf_counters = nullptr;   // [kPrefillSplitUnits] arrival counters of split prefill tiles, zero between calls
     uint16_t xcd_cw[kXcds] = {};   // option "xcd_weights"
     int64_t opt_overlap = 1;
+    int64_t opt_pf_waves = 0;       // waves per prefill workgroup: 0 = automatic, 4, 8
     int64_t opt_fused = 0;          // mixed batches in one launch (mixed kernel) instead of two kernels on two streams
     int64_t opt_dec_cus = 0;        // mixed kernel: decoding compute units per XCD, 0 = automatic
     hipStream_t side_stream = nullptr;   // default priority; carries the prefill kernel of mixed batches
@@ -584,6 +595,11 @@ ooco_status ooco_set_option(ooco_ctx *ctx, const char *name, int64_t value)
         ctx->opt_pf_split = value;
     else if (!strcmp(name, "decode_first"))
         ctx->opt_decode_first = value;
+    else if (!strcmp(name, "prefill_waves")) {
+        if (value != 0 && value != 4 && value != 8)
+            return fail(ctx, OOCO_EINVAL, "ooco_set_option: prefill_waves must be 0 (automatic), 4 or 8");
+        ctx->opt_pf_waves = value;
+    }
     else if (!strcmp(name, "mixed_fused"))
         ctx->opt_fused = value;
     else if (!strcmp(name, "mixed_dec_cus"))
@@ -656,6 +672,7 @@ ooco_status ooco_plan(ooco_ctx *ctx, int num_seqs, const int32_t *h_seq_lens, co
     geo.tail_blocks = ctx->opt_tail_blocks;
     geo.pf_split_opt = ctx->opt_pf_split;
     geo.piece_pad = ctx->opt_piece_pad;
+    geo.pf_waves_opt = ctx->opt_pf_waves;
     geo.fused = ctx->opt_fused && ctx->opt_overlap;
     geo.dec_cus_opt = ctx->opt_dec_cus;
     for (int k = 0; k < kXcds; ++k) geo.xcd_cw[k] = ctx->xcd_cw[k];
@@ -736,7 +753,7 @@ ooco_status ooco_plan_dry_run(int num_q_heads, int num_kv_heads, int head_dim, i
         for (int i = 0; i < num_seqs && n < prefill_cap; ++i) {
             const int q0 = h_query_start_loc[i], ql = h_query_start_loc[i + 1] - q0;
             if (ql <= 1) continue;
-            const int tile_rows = prefill_tile_rows(num_q_heads / num_kv_heads);
+            const int tile_rows = prefill_tile_rows(num_q_heads / num_kv_heads, pl.pf_waves);
             for (int t0 = 0; t0 < ql && n < prefill_cap; t0 += tile_rows, ++n) {
                 int32_t *o = prefill_tiles_out + 5 * n;
                 o[0] = i, o[1] = q0 + t0, o[2] = std::min(tile_rows, ql - t0), o[3] = h_ctx_lens[i] + t0;
@@ -759,7 +776,7 @@ ooco_status ooco_plan_info(const ooco_ctx *ctx, int64_t *decode_waves, int64_t *
         size_t bytes = (size_t)ctx->plan.slots * (size_t)ctx->Hq * (ctx->hd + 2) * sizeof(float);
         if (ctx->plan.pf_split > 1)
             bytes = (bytes + 255) / 256 * 256 + (size_t)ctx->plan.n_tiles * ctx->Hkv * (size_t)ctx->plan.pf_split *
-                                                    kPrefillCols * (ctx->hd + 2) * sizeof(float);
+                                                    (size_t)(32 * ctx->plan.pf_waves) * (ctx->hd + 2) * sizeof(float);
         *workspace_used = (int64_t)bytes;
     }
     if (prefill_parts) *prefill_parts = ctx->plan.n_tiles > 0 ? ctx->plan.pf_split : 1;
@@ -838,7 +855,7 @@ ooco_status ooco_attn_mixed(ooco_ctx *ctx, const void *q, const void *k_cache, c
         const size_t dec_floats = ((size_t)pl.slots * ctx->Hq * (ctx->hd + 2) + 63) / 64 * 64;   // 256-byte aligned
         const size_t parts = (size_t)pl.n_tiles * ctx->Hkv * (size_t)pl.pf_split;
         p.pf_acc = static_cast<float *>(ctx->ws) + dec_floats;
-        p.pf_ml = p.pf_acc + parts * kPrefillCols * ctx->hd;
+        p.pf_ml = p.pf_acc + parts * (size_t)(32 * pl.pf_waves) * ctx->hd;
         p.pf_counters = ctx->pf_counters;
         p.pf_split = pl.pf_split;
     }
@@ -865,7 +882,7 @@ ooco_status ooco_attn_mixed(ooco_ctx *ctx, const void *q, const void *k_cache, c
     p.n_tiles = pl.n_tiles;
     p.num_pf = pl.num_pf;
     p.dec_cus = pl.dec_cus;
-    p.tile_rows = prefill_tile_rows(ctx->g);
+    p.pf_waves = pl.pf_waves;
     p.nbi = (int32_t)ctx->opt_nbi;
     p.rotate_heads = (int32_t)ctx->opt_rotate;
     for (int k = 0; k < kXcds; ++k) p.xcd_cw[k] = pl.cw[k];
@@ -1072,7 +1089,7 @@ ooco_status ooco_attn_mixed_static(int num_q_heads, int num_kv_heads, int head_d
     p.queue_base = 0;
     p.n_tiles = pl.n_tiles;
     p.num_pf = pl.num_pf;
-    p.tile_rows = prefill_tile_rows(p.g);
+    p.pf_waves = pl.pf_waves;
     p.nbi = 0;
     p.rotate_heads = 1;
     p.pf_acc = nullptr;

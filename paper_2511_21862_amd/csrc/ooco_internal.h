@@ -31,7 +31,7 @@
 namespace ooco {
 
 constexpr int kBlockSize = 16;      // tokens per KV block (fixed by the cache layout)
-constexpr int kPrefillCols = 128;   // (row, head) query columns per prefill workgroup
+constexpr int kPrefillCols = 128;   // (row, head) query columns per four-wave prefill workgroup (eight waves: 256)
 constexpr int kInlineSeqs = 960;    // sequences whose cumulative array fits the kernel arguments
 constexpr int kMaxPrefillSplit = 8; // parts a prefill tile's keys may be cut into
 constexpr int kPrefillSplitUnits = 8192;   // (tile, kv head) pairs up to which the split is available
@@ -57,7 +57,8 @@ struct AttnParams {
     int32_t num_seqs, total_q;
     int32_t dec_blocks, static_blocks, static_runs, tail_runs;   // decode run layout
     int32_t piece_pad;   // line units in front of every decode sequence's blocks (the cost of starting a piece)
-    int32_t n_tiles, tile_rows; // prefill: tiles per kv head, query rows per tile
+    int32_t n_tiles;            // prefill: tiles per kv head
+    int32_t pf_waves;           // prefill: waves per workgroup, 4 or 8 (a tile has 32 query columns per wave)
     int32_t num_pf;             // prefill: number of chunks (entries of the prefill array, see below)
     int32_t dec_cus;            // mixed kernel: compute units per XCD that run decode waves (the others run prefill tiles)
     int32_t nbi;                // tuning: KV blocks per softmax step of the decode kernel
@@ -100,7 +101,10 @@ hipError_t launch_kv_append(const void *k_new, const void *v_new, void *k_cache,
 hipError_t launch_fill_zero(int32_t *p, int64_t n, hipStream_t s);
 
 // Query rows of one prefill tile for a GQA group of g heads.
-__host__ __device__ inline int32_t prefill_tile_rows(int32_t g) { return kPrefillCols / g > 0 ? kPrefillCols / g : 1; }
+__host__ __device__ inline int32_t prefill_tile_rows(int32_t g, int32_t waves = 4)
+{
+    return 32 * waves / g > 0 ? 32 * waves / g : 1;
+}
 
 // n blocks cut into s equal runs, run k = [n*k/s, n*(k+1)/s): index of the run holding block x.
 __host__ __device__ inline int32_t segment_of(int64_t x, int64_t s, int64_t n)

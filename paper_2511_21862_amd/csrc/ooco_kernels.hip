@@ -594,20 +594,24 @@ __global__ __launch_bounds__(64, 2) void decode_kernel(const KernArgs a)
 // the causal mask runs only on steps that touch the diagonal; at the end of a sequence the unused V
 // slots are zeroed once in LDS instead of masking operands.  Two workgroups fit a CU (<= 256 VGPRs,
 // 64 KiB LDS each).
-constexpr int kPfThreads = 256;
+constexpr int kPfThreads = 256;   // threads of the four-wave workgroup (the eight-wave one has 512)
 constexpr int kPfBlocks = 4;    // KV blocks per step
 
 // One workgroup's work on virtual block index `vb` (what blockIdx.x is in the stand-alone kernel): unit vb / split
 // = (tile, kv head), part vb % split of its keys.  `cum_at(i)` reads the prefill array of the plan.  All 256
 // threads of the workgroup call it together; every return is workgroup-uniform.
-template <int HD, class CumAt>
+// NW = waves per workgroup: 4 (128 query columns) or 8 (256 columns: the same K/V tiles in LDS serve twice as many
+// columns, which halves the traffic from L2 into the compute unit per unit of matrix work).
+template <int HD, int NW, class CumAt>
 OOCO_DEV void prefill_unit(const AttnParams &p, CumAt cum_at, const int vb)
 {
+    constexpr int THREADS = NW * 64;
+    constexpr int COLS = NW * 32;      // query columns per workgroup
     constexpr int KS = HD / 16;        // k-steps of QK
     constexpr int MB = HD / 32;        // 32-dim groups of the output
     constexpr int CH = HD * 2;         // 16-byte chunks per (block, kv head) tile
     constexpr int STAGE = kPfBlocks * CH;               // chunks of one step's K (or V) tiles
-    constexpr int NCP = STAGE / kPfThreads;             // chunks each thread moves per stage
+    constexpr int NCP = STAGE / THREADS;                // chunks each thread moves per stage
     __shared__ u32x4 ldsK[2][STAGE];
     __shared__ u32x4 ldsV[2][STAGE];
 
@@ -634,9 +638,10 @@ OOCO_DEV void prefill_unit(const AttnParams &p, CumAt cum_at, const int vb)
         const int t = (t_end - 1) - tile_idx;             // reversed order inside the sequence
         const int q0 = p.query_start_loc[seq];
         const int q_len = p.query_start_loc[seq + 1] - q0;
-        const int t0 = t * p.tile_rows;
+        const int tile_rows = max(1, COLS / g);
+        const int t0 = t * tile_rows;
         q_row0 = min(max(q0 + t0, 0), p.total_q - 1);
-        rows = max(1, min(min(p.tile_rows, q_len - t0), p.total_q - q_row0));
+        rows = max(1, min(min(tile_rows, q_len - t0), p.total_q - q_row0));
         seq_len = p.seq_lens[seq];
         // keys beyond what the plan allotted to this sequence are never touched
         const int cap = p.max_blocks_per_seq * kBlockSize;
@@ -711,14 +716,23 @@ OOCO_DEV void prefill_unit(const AttnParams &p, CumAt cum_at, const int vb)
         uint32_t voff[NCP], dst[NCP];
 #pragma unroll
         for (int n = 0; n < NCP; ++n) {
-            const int grp = wave + 4 * n;                  // wave-uniform
+            const int grp = wave + NW * n;                 // wave-uniform
             const int cidx = grp * 64 + lane;
-            // block of the step (wave-uniform; a compile-time constant when a tile has at least 256
-            // chunks, which keeps pb[] in registers without select chains)
-            const int which = CH >= 256 ? (4 * n * 64) / CH : (grp * 64) / CH;
+            // block of the step (wave-uniform).  Four waves and at least 256 chunks per tile: a compile-time
+            // constant, which keeps pb[] in registers without select chains.  Eight waves (256 chunks per tile):
+            // waves 0..3 move the even blocks' tiles, waves 4..7 the odd ones (one select, no indexed array).
+            int which, pbw;
+            if constexpr (NW == 4) {
+                which = CH >= 256 ? (4 * n * 64) / CH : (grp * 64) / CH;
+                pbw = pb[which];
+            } else {
+                static_assert(NW != 8 || CH == 256, "eight-wave workgroups: head_dim 128");
+                which = 2 * n + (wave >> 2);
+                pbw = (wave >> 2) ? pb[2 * n + 1] : pb[2 * n];
+            }
             const int r = cidx - which * CH;
             // scalar tile address + 32-bit lane offset (bytes)
-            base[n] = (is_v ? v_head : k_head) + (uint64_t)(uint32_t)pb[which] * blk_stride;
+            base[n] = (is_v ? v_head : k_head) + (uint64_t)(uint32_t)pbw * blk_stride;
             voff[n] = (uint32_t)(is_v ? 2 * (r % HD) + r / HD : r) * 16u;
             dst[n] = (is_v ? ldsV_base : ldsK_base) + (uint32_t)((slot * STAGE + grp * 64) * 16);
         }
@@ -842,7 +856,7 @@ OOCO_DEV void prefill_unit(const AttnParams &p, CumAt cum_at, const int vb)
     auto scrub_v = [&](int slot, int st) {
 #pragma unroll
         for (int n = 0; n < NCP; ++n) {
-            const int cidx = n * kPfThreads + tid;           // chunk [block][token half][dim] of the stage
+            const int cidx = n * THREADS + tid;              // chunk [block][token half][dim] of the stage
             const int blk = cidx / CH, half = (cidx % CH) / HD;
             const int t0 = st * 64 + 16 * blk + 8 * half;    // tokens t0 .. t0+7
             u32x4 mk;
@@ -946,7 +960,7 @@ OOCO_DEV void prefill_unit(const AttnParams &p, CumAt cum_at, const int vb)
         // layout of a part: [wave][mb][q4][lane][4 floats], so that every store and load instruction of a wave
         // covers 1 KiB of contiguous memory
         auto part_ptr = [&](int64_t j, int mb) -> float * {
-            return p.pf_acc + ((((pbase + j) * 4 + wave) * MB + mb) * 4 * 64 + lane) * 4;
+            return p.pf_acc + ((((pbase + j) * NW + wave) * MB + mb) * 4 * 64 + lane) * 4;
         };
         {
 #pragma unroll
@@ -955,7 +969,7 @@ OOCO_DEV void prefill_unit(const AttnParams &p, CumAt cum_at, const int vb)
                 for (int q4 = 0; q4 < 4; ++q4)
                     store_dev4(part_ptr(part, mb) + q4 * 256,
                                f32x4{O[mb][4 * q4], O[mb][4 * q4 + 1], O[mb][4 * q4 + 2], O[mb][4 * q4 + 3]});
-            if (h == 0) store_dev2(p.pf_ml + ((pbase + part) * kPrefillCols + c) * 2, m, ltot);
+            if (h == 0) store_dev2(p.pf_ml + ((pbase + part) * COLS + c) * 2, m, ltot);
         }
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's partial has reached memory ...
         __syncthreads();                                    // ... and so have the other waves'
@@ -971,7 +985,7 @@ OOCO_DEV void prefill_unit(const AttnParams &p, CumAt cum_at, const int vb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) O[mb][r] = 0.f;
         for (int j = 0; j < nparts; ++j) {                  // in part order: the result does not depend on who is last
-            const f32x2 ml = load_dev2(p.pf_ml + ((pbase + j) * kPrefillCols + c) * 2);
+            const f32x2 ml = load_dev2(p.pf_ml + ((pbase + j) * COLS + c) * 2);
             f32x4 t[4 * MB];   // t[4*mb + q4] = this lane's dims 32mb + 8q4 + 4h + 0..3 of part j
             if constexpr (MB == 4)
                 load_dev_part(t, part_ptr(j, 0), part_ptr(j, 1), part_ptr(j, 2), part_ptr(j, 3));
@@ -1007,11 +1021,11 @@ OOCO_DEV void prefill_unit(const AttnParams &p, CumAt cum_at, const int vb)
     }
 }
 
-template <int HD>
-__global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a)
+template <int HD, int NW>
+__global__ __launch_bounds__(NW * 64, 8 / NW) void prefill_kernel(const KernArgs a)
 {
     const AttnParams &p = a.p;
-    prefill_unit<HD>(p, [&](int idx) -> int { return p.cum_dev ? p.cum_dev[idx] : a.cum[idx]; }, (int)blockIdx.x);
+    prefill_unit<HD, NW>(p, [&](int idx) -> int { return p.cum_dev ? p.cum_dev[idx] : a.cum[idx]; }, (int)blockIdx.x);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1037,6 +1051,7 @@ __global__ __launch_bounds__(kPfThreads, 2) void prefill_kernel(const KernArgs a
 //   [0, 2048) claims: 0 free, 1 being claimed, rank + 2;  [2048, 2056) arrivals per XCD;
 //   [2056, 2064) prefill units drawn per XCD;  [2064] decode items drawn;  [2065] workgroups that have left
 constexpr int kMixedClaims = 2048;
+constexpr int kMixedShareCus = 99;
 template <int HD>
 __global__ __launch_bounds__(kPfThreads, 2) void mixed_kernel(const KernArgs a)
 {
@@ -1055,8 +1070,9 @@ __global__ __launch_bounds__(kPfThreads, 2) void mixed_kernel(const KernArgs a)
         const unsigned hw = __builtin_amdgcn_s_getreg((31 << 11) | 4);                 // HW_ID: CU, SH, SE ids in bits 8..15
         int32_t *const claim = claims + (xcc * 256u + ((hw >> 8) & 255u));
         int expected = 0, rank;
-        if (__hip_atomic_compare_exchange_strong(claim, &expected, 1, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
-                                                 __HIP_MEMORY_SCOPE_AGENT)) {
+        const bool won = __hip_atomic_compare_exchange_strong(claim, &expected, 1, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                                              __HIP_MEMORY_SCOPE_AGENT);
+        if (won) {
             rank = __hip_atomic_fetch_add(xcd_arrivals + xcc, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __hip_atomic_store(claim, rank + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         } else {
@@ -1068,14 +1084,16 @@ __global__ __launch_bounds__(kPfThreads, 2) void mixed_kernel(const KernArgs a)
             }
             rank = v >= 2 ? v - 2 : 0;   // (never seen: decode)
         }
-        sh_role = rank < p.dec_cus ? 0 : 1;
+        // p.dec_cus == kMixedShareCus: every unit runs both kinds side by side (its first workgroup decodes, its
+        // second prefills) -- the arrangement of the two separate kernels, inside one launch, kept for measurements
+        sh_role = p.dec_cus == kMixedShareCus ? (won ? 0 : 1) : (rank < p.dec_cus ? 0 : 1);
     }
     __syncthreads();
     int role = sh_role;   // 0 = decode, 1 = prefill
     // option "trace": per workgroup (start, end of its first kind of work, end of its second kind, first role +
     // 256 * items of wave 0 in the first kind + 2^32 * items in the second) on the 100 MHz clock
     uint64_t *const trace = p.trace ? p.trace + (int64_t)blockIdx.x * 4 : nullptr;
-    uint64_t n_items[2] = {0, 0};
+    uint64_t n_first = 0, n_second = 0;   // (two scalars: an array indexed by the pass would live in scratch memory)
     if (trace && tid == 0) {
         trace[0] = wall_clock64();
         trace[3] = (uint64_t)role;
@@ -1094,7 +1112,7 @@ __global__ __launch_bounds__(kPfThreads, 2) void mixed_kernel(const KernArgs a)
                 const int run = item / p.Hkv;
                 const int kvh = (item - run * p.Hkv + run) % p.Hkv;   // kv heads rotate over the runs
                 decode_run<HD, (HD == 64 ? 2 : 1)>(p, dcum_at, L, run, kvh, lane, nullptr, first_piece, []() {});
-                ++n_items[pass];
+                if (pass == 0) ++n_first; else ++n_second;
             }
         } else {
             for (;;) {
@@ -1114,14 +1132,14 @@ __global__ __launch_bounds__(kPfThreads, 2) void mixed_kernel(const KernArgs a)
                 __syncthreads();
                 const int vb = sh_item;
                 if (vb < 0) break;
-                prefill_unit<HD>(p, pf_at, vb);
-                ++n_items[pass];
+                prefill_unit<HD, 4>(p, pf_at, vb);
+                if (pass == 0) ++n_first; else ++n_second;
             }
         }
         __syncthreads();   // the whole workgroup changes its kind of work together
         if (trace && tid == 0) trace[1 + pass] = wall_clock64();
     }
-    if (trace && tid == 0) trace[3] += (n_items[0] << 8) + (n_items[1] << 32);
+    if (trace && tid == 0) trace[3] += (n_first << 8) + (n_second << 32);
     // leave; the last workgroup out clears the state
     if (tid == 0) {
         const int gone = __hip_atomic_fetch_add(left, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -1292,11 +1310,13 @@ hipError_t launch_decode(const KernArgs &a, hipStream_t s)
 hipError_t launch_prefill(const KernArgs &a, hipStream_t s)
 {
     if (a.p.n_tiles <= 0) return hipSuccess;
-    const dim3 grid((unsigned)((int64_t)a.p.n_tiles * a.p.Hkv * (a.p.pf_split > 0 ? a.p.pf_split : 1))), block(kPfThreads);
-    if (a.p.hd == 128)
-        hipLaunchKernelGGL((prefill_kernel<128>), grid, block, 0, s, a);
+    const dim3 grid((unsigned)((int64_t)a.p.n_tiles * a.p.Hkv * (a.p.pf_split > 0 ? a.p.pf_split : 1)));
+    if (a.p.hd == 128 && a.p.pf_waves == 8)
+        hipLaunchKernelGGL((prefill_kernel<128, 8>), grid, dim3(512), 0, s, a);
+    else if (a.p.hd == 128)
+        hipLaunchKernelGGL((prefill_kernel<128, 4>), grid, dim3(kPfThreads), 0, s, a);
     else
-        hipLaunchKernelGGL((prefill_kernel<64>), grid, block, 0, s, a);
+        hipLaunchKernelGGL((prefill_kernel<64, 4>), grid, dim3(kPfThreads), 0, s, a);
     return hipGetLastError();
 }
 
