@@ -148,19 +148,17 @@ def bench_block_copy(a):
     for i in range(a.warmup):
         step(i)
     torch.cuda.synchronize()
+    # one kernel per step, launched back to back: the timed region is bracketed by one pair of HIP events on the
+    # launch stream (torch's current stream here), region time / steps = the kernel's average launch duration
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
+    ev0.record(stream)
     for i in range(a.steps):
         step(i)
+    ev1.record(stream)
     torch.cuda.synchronize()
     dt = (time.perf_counter() - t0) / a.steps
-    # kernel duration by HIP events on the launch stream (torch's current stream here)
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(a.steps)]
-    for i, (e0, e1) in enumerate(evs):
-        e0.record(stream)
-        step(i)
-        e1.record(stream)
-    torch.cuda.synchronize()
-    kms = float(np.mean([e0.elapsed_time(e1) for e0, e1 in evs]))
+    kms = ev0.elapsed_time(ev1) / a.steps
     nbytes = accounting.block_copy_bytes(n, b.Hkv, b.hd, b.BS)
     tokens = int(b.seq_lens[b.extra["victims"]].sum())
     line = {
@@ -222,18 +220,17 @@ def bench_append(a):
     for i in range(a.warmup):
         step(i)
     torch.cuda.synchronize()
+    # one kernel per step, launched back to back: the timed region is bracketed by one pair of HIP events on the
+    # launch stream (torch's current stream here), region time / steps = the kernel's average launch duration
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
+    ev0.record(stream)
     for i in range(a.steps):
         step(i)
+    ev1.record(stream)
     torch.cuda.synchronize()
     dt = (time.perf_counter() - t0) / a.steps
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(a.steps)]
-    for i, (e0, e1) in enumerate(evs):
-        e0.record(stream)
-        step(i)
-        e1.record(stream)
-    torch.cuda.synchronize()
-    kms = float(np.mean([e0.elapsed_time(e1) for e0, e1 in evs]))
+    kms = ev0.elapsed_time(ev1) / a.steps
     nbytes = 2 * b.total_q * accounting.per_token_kv_bytes(b.Hkv, b.hd)      # new vectors read + slots written
     line = {
         "metric": "KV append tokens/s + achieved HBM GB/s (% of peak), 1 MI355X",
