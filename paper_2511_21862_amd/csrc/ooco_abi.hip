@@ -81,6 +81,7 @@ struct PlanGeometry {
     int64_t pf_split_opt = 0;   // parts per prefill tile; 0 = automatic
     int64_t piece_pad = 0;      // line units charged for starting a piece (see build_plan)
     int64_t pf_waves_opt = 0;   // waves per prefill workgroup: 4, 8, or 0 = automatic
+    int64_t lean_opt = 0;       // mixed batches: register-lean kernels (see HostPlan::lean)
     int64_t fused = 0;          // batches with both kinds of work run in the one-launch mixed kernel
     int64_t dec_cus_opt = 0;    // mixed kernel: compute units per XCD that decode; 0 = automatic
     uint16_t xcd_cw[kXcds] = {};   // cumulative XCD weights of the static runs; zeros = equal runs
@@ -102,6 +103,10 @@ struct HostPlan {
     int32_t n_tiles = 0, total_q = 0, num_seqs = 0;
     int32_t pf_split = 1;        // parts each prefill tile's keys are cut into
     int32_t pf_waves = 4;        // waves per prefill workgroup (32 query columns each)
+    // mixed batches (head_dim 128): the register-lean pair of kernels -- prefill workgroups of eight waves (176
+    // registers, no software pipeline) and decode waves of 144 registers, four per compute unit -- so that a SIMD
+    // holds two prefill waves and a decode wave at once
+    int32_t lean = 0;
     int32_t dec_cus = 0;         // > 0: the batch runs in the mixed kernel with this many decoding compute units per XCD
     int64_t slots = 0;           // partial-result slots the decode kernel may touch
 };
@@ -170,7 +175,22 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
     // of 128, which halves the traffic from L2 into the compute units.  Measured on MI355X it is no faster (that
     // traffic is not what bounds the kernel) and its 220-register waves leave no room for decode waves beside
     // them, so four waves are the default; eight (head_dim 128 only) stay selectable.
-    const int pf_waves = geo.hd == 128 && geo.pf_waves_opt == 8 ? 8 : 4;
+    // The register-lean pair for batches with both kinds of work (lean_opt 1 = when every compute unit gets at
+    // least one eight-wave prefill workgroup, 2 = whenever the batch is mixed).  Measured on MI355X: the long-context
+    // mixed batch 1.75 -> 1.63 ms, the short one 0.288 -> 0.274 ms.
+    bool lean = false;
+    if (geo.lean_opt && geo.hd == 128 && !geo.fused && num_seqs > 0) {
+        const int rows8 = prefill_tile_rows(geo.Hq / geo.Hkv, 8);
+        int64_t n_dec = 0, tiles8 = 0;
+        for (int i = 0; i < num_seqs; ++i) {
+            const int64_t ql = (int64_t)h_query_start_loc[i + 1] - h_query_start_loc[i];
+            n_dec += ql == 1;
+            if (ql > 1) tiles8 += (ql + rows8 - 1) / rows8;
+        }
+        lean = n_dec > 0 && tiles8 > 0 && (geo.lean_opt >= 2 || tiles8 * geo.Hkv >= (int64_t)geo.num_cus);
+    }
+    out.lean = lean;
+    const int pf_waves = geo.hd == 128 && (geo.pf_waves_opt == 8 || lean) ? 8 : 4;
     out.pf_waves = pf_waves;
     const int tile_rows = prefill_tile_rows(geo.Hq / geo.Hkv, pf_waves);
     for (int i = 0; i < num_seqs; ++i) {
@@ -248,7 +268,7 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
         // flight to saturate HBM, few enough waves that start-up and partial results stay small)
         // and at least ~32 blocks per wave
         // (mixed kernel: eight decode waves on every decoding unit, one run each)
-        const int64_t wave_slots = out.dec_cus == 99 ? std::max<int64_t>(1, (int64_t)geo.num_cus * 4 / geo.Hkv)
+        const int64_t wave_slots = lean ? std::max<int64_t>(1, (int64_t)geo.num_cus * 4 / geo.Hkv) : out.dec_cus == 99 ? std::max<int64_t>(1, (int64_t)geo.num_cus * 4 / geo.Hkv)
                                    : out.dec_cus > 0 ? std::max<int64_t>(1, (int64_t)out.dec_cus * kXcds * 8 / geo.Hkv)
                                                    : std::max<int64_t>(1, (int64_t)geo.num_cus * 3 / geo.Hkv);
         int64_t runs = geo.segments_opt > 0 ? geo.segments_opt : std::min<int64_t>(wave_slots, (kv_blocks + 31) / 32);
@@ -395,6 +415,7 @@ struct ooco_ctx {
     int32_t *pf_counters = nullptr;   // [kPrefillSplitUnits] arrival counters of split prefill tiles, zero between calls
     uint16_t xcd_cw[kXcds] = {};   // option "xcd_weights"
     int64_t opt_overlap = 1;
+    int64_t opt_lean = 1;           // mixed batches: the register-lean kernels (0 never, 1 automatic, 2 always)
     int64_t opt_pf_waves = 0;       // waves per prefill workgroup: 0 = automatic, 4, 8
     int64_t opt_fused = 0;          // mixed batches in one launch (mixed kernel) instead of two kernels on two streams
     int64_t opt_dec_cus = 0;        // mixed kernel: decoding compute units per XCD, 0 = automatic
@@ -600,6 +621,8 @@ ooco_status ooco_set_option(ooco_ctx *ctx, const char *name, int64_t value)
             return fail(ctx, OOCO_EINVAL, "ooco_set_option: prefill_waves must be 0 (automatic), 4 or 8");
         ctx->opt_pf_waves = value;
     }
+    else if (!strcmp(name, "mixed_lean"))
+        ctx->opt_lean = value;
     else if (!strcmp(name, "mixed_fused"))
         ctx->opt_fused = value;
     else if (!strcmp(name, "mixed_dec_cus"))
@@ -673,6 +696,7 @@ ooco_status ooco_plan(ooco_ctx *ctx, int num_seqs, const int32_t *h_seq_lens, co
     geo.pf_split_opt = ctx->opt_pf_split;
     geo.piece_pad = ctx->opt_piece_pad;
     geo.pf_waves_opt = ctx->opt_pf_waves;
+    geo.lean_opt = ctx->opt_lean;
     geo.fused = ctx->opt_fused && ctx->opt_overlap;
     geo.dec_cus_opt = ctx->opt_dec_cus;
     for (int k = 0; k < kXcds; ++k) geo.xcd_cw[k] = ctx->xcd_cw[k];
@@ -884,7 +908,8 @@ ooco_status ooco_attn_mixed(ooco_ctx *ctx, const void *q, const void *k_cache, c
     p.dec_cus = pl.dec_cus;
     p.pf_waves = pl.pf_waves;
     p.nbi = (int32_t)ctx->opt_nbi;
-    p.rotate_heads = (int32_t)ctx->opt_rotate;
+    p.rotate_heads = (int16_t)(ctx->opt_rotate != 0);
+    p.lean = (int16_t)pl.lean;
     for (int k = 0; k < kXcds; ++k) p.xcd_cw[k] = pl.cw[k];
 
     if (pl.tail_runs > 0) {

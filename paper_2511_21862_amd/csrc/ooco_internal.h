@@ -62,7 +62,8 @@ struct AttnParams {
     int32_t num_pf;             // prefill: number of chunks (entries of the prefill array, see below)
     int32_t dec_cus;            // mixed kernel: compute units per XCD that run decode waves (the others run prefill tiles)
     int32_t nbi;                // tuning: KV blocks per softmax step of the decode kernel
-    int32_t rotate_heads;       // tuning: kv head rotation across XCDs
+    int16_t rotate_heads;       // tuning: kv head rotation across XCDs
+    int16_t lean;               // mixed batches: the register-lean kernels (decode 128, prefill 8 waves x 192 registers)
     uint16_t xcd_cw[8];         // cumulative XCD weights of the static runs (RunLayout::cw); zeros = equal runs
     uint32_t queue_base;        // ticket value at which this launch's tail runs start
     uint32_t *queue;            // ticket counter for the tail runs (monotonic across launches)

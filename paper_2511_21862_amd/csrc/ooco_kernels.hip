@@ -229,7 +229,7 @@ OOCO_DEV int count_le(CumAt cum_at, int n, int x, int lane)
 // (so the result does not depend on which piece is last) and resets the counter.
 // One run of the decode line for one kv head, all its pieces, executed by one wave (see above).
 // `at_stream_end()` is called once the last piece of the run has been streamed, before its epilogue.
-template <int HD, int NBI, class CumAt, class AtStreamEnd>
+template <int HD, int NBI, int MBATCH, class CumAt, class AtStreamEnd>
 OOCO_DEV void decode_run(const AttnParams &p, CumAt cum_at, const RunLayout &L, int run, int kvh, int lane, uint64_t *trace,
                          bool &first_piece, AtStreamEnd at_stream_end)
 {
@@ -446,7 +446,7 @@ OOCO_DEV void decode_run(const AttnParams &p, CumAt cum_at, const RunLayout &L, 
 #pragma unroll
                         for (int r = 0; r < 4; ++r) O[nb][r] = O[nb][r] * w_old + o2[nb][r] * w_new;
                 };
-                constexpr int MBATCH = 3;
+                // (MBATCH parts per round trip: three by default; one in the register-lean instantiation)
                 const int per_grp = (nparts + ngrp - 1) / ngrp;
                 for (int k0 = 0; k0 < per_grp; k0 += MBATCH) {
                     f32x2 ml[MBATCH];
@@ -506,8 +506,8 @@ OOCO_DEV void decode_run(const AttnParams &p, CumAt cum_at, const RunLayout &L, 
     }
 }
 
-template <int HD, int NBI>
-__global__ __launch_bounds__(64, 2) void decode_kernel(const KernArgs a)
+template <int HD, int NBI, int MBATCH>
+OOCO_DEV void decode_kernel_body(const KernArgs &a)
 {
     const AttnParams &p = a.p;
     // What a wave needs before its first KV tile is on its way comes from a dozen places of the kernel
@@ -552,7 +552,7 @@ __global__ __launch_bounds__(64, 2) void decode_kernel(const KernArgs a)
             ticket = __hip_atomic_fetch_add(p.queue, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - p.queue_base;
         drawn = true;
     };
-    decode_run<HD, NBI>(p, cum_at, L, run, kvh, lane, trace, first_piece, [&]() {
+    decode_run<HD, NBI, MBATCH>(p, cum_at, L, run, kvh, lane, trace, first_piece, [&]() {
         if (tail_tasks) draw();
     });
     if (!tail_tasks) break;
@@ -566,6 +566,21 @@ __global__ __launch_bounds__(64, 2) void decode_kernel(const KernArgs a)
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         if (lane == 0) trace[3] = wall_clock64();
     }
+}
+
+template <int HD, int NBI>
+__global__ __launch_bounds__(64, 2) void decode_kernel(const KernArgs a)
+{
+    decode_kernel_body<HD, NBI, 3>(a);
+}
+
+// The same kernel within 160 registers per wave (one KV block per step, one part per merge round trip), for
+// batches whose prefill workgroups need the rest of the register file: a SIMD then holds one decode wave beside
+// two prefill waves of 176 registers.
+template <int HD>
+__global__ __launch_bounds__(64, 3) void decode_kernel_lean(const KernArgs a)
+{
+    decode_kernel_body<HD, 1, 1>(a);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -602,7 +617,10 @@ constexpr int kPfBlocks = 4;    // KV blocks per step
 // threads of the workgroup call it together; every return is workgroup-uniform.
 // NW = waves per workgroup: 4 (128 query columns) or 8 (256 columns: the same K/V tiles in LDS serve twice as many
 // columns, which halves the traffic from L2 into the compute unit per unit of matrix work).
-template <int HD, int NW, class CumAt>
+// PIPE = false: no software pipeline across steps (the scores of a step are computed in that step, one score
+// register set): fewer registers, so that two such waves and a decode wave share a SIMD; the overlap of matrix and
+// vector work then comes from the two waves of a SIMD rather than from within one wave.
+template <int HD, int NW, bool PIPE, class CumAt>
 OOCO_DEV void prefill_unit(const AttnParams &p, CumAt cum_at, const int vb)
 {
     constexpr int THREADS = NW * 64;
@@ -879,7 +897,7 @@ OOCO_DEV void prefill_unit(const AttnParams &p, CumAt cum_at, const int vb)
         }
         issue(false, st_lo & 1, ids0);
         issue(true, st_lo & 1, ids0);
-        if (st_lo + 1 < nstep) issue(false, (st_lo + 1) & 1, ids1);
+        if (PIPE && st_lo + 1 < nstep) issue(false, (st_lo + 1) & 1, ids1);
     }
     // One step.  Sc: scores of step st (computed during step st-1), Sn: receives those of step st+1.
     auto body = [&](f32x16 (&Sc)[2], f32x16 (&Sn)[2], int st) {
@@ -938,13 +956,51 @@ OOCO_DEV void prefill_unit(const AttnParams &p, CumAt cum_at, const int vb)
         pv(P, st & 1);
     };
 
-    f32x16 SA[2], SB[2];
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    qk(SA, st_lo & 1);
-    for (int st = st_lo; st < nstep; st += 2) {
-        body(SA, SB, st);
-        if (st + 1 < nstep) body(SB, SA, st + 1);
+    if constexpr (PIPE) {
+        f32x16 SA[2], SB[2];
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        qk(SA, st_lo & 1);
+        for (int st = st_lo; st < nstep; st += 2) {
+            body(SA, SB, st);
+            if (st + 1 < nstep) body(SB, SA, st + 1);
+        }
+    } else {
+        for (int st = st_lo; st < nstep; ++st) {
+            // the loads of K[st] and V[st] have landed (everybody's, after the barrier); nobody reads the tiles of
+            // step st-1 any more, so the loads of step st+1 may overwrite them
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            if (st + 1 < nstep) {
+                issue(false, (st + 1) & 1, ids1);
+                issue(true, (st + 1) & 1, ids1);
+            }
+            if (st * 64 + 64 > seq_len) scrub_v(st & 1, st);
+#pragma unroll
+            for (int b = 0; b < kPfBlocks; ++b) ids1[b] = block_id(kPfBlocks * (st + 2) + b);
+            if (st * 64 > w_pos_hi) continue;   // wave-uniform: no column of this wave sees keys of the step
+            f32x16 S[2];
+            qk(S, st & 1);
+            if (st * 64 + 63 > w_pos_lo) mask(S, st);
+            u32x4 P[4];
+            float alpha, psum;
+            bool grow;
+            softmax_first(S, P, alpha, grow, psum);
+            if (__any(grow)) {
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) O[mb][r] *= alpha;
+            }
+            softmax_second(S, P, alpha, psum);
+            const u32x4 *vp = &ldsV[st & 1][h * HD + col];
+#pragma unroll
+            for (int i = 0; i < 4 * MB; ++i) {
+                const u32x4 vop = vp[(i / MB) * CH + 32 * (i % MB)];
+                O[i % MB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vop),
+                                                                __builtin_bit_cast(bf16x8, P[i / MB]), O[i % MB], 0, 0, 0);
+            }
+        }
     }
     float ltot;
     {
@@ -1025,7 +1081,16 @@ template <int HD, int NW>
 __global__ __launch_bounds__(NW * 64, 8 / NW) void prefill_kernel(const KernArgs a)
 {
     const AttnParams &p = a.p;
-    prefill_unit<HD, NW>(p, [&](int idx) -> int { return p.cum_dev ? p.cum_dev[idx] : a.cum[idx]; }, (int)blockIdx.x);
+    prefill_unit<HD, NW, true>(p, [&](int idx) -> int { return p.cum_dev ? p.cum_dev[idx] : a.cum[idx]; }, (int)blockIdx.x);
+}
+
+// Eight waves, 256 query columns, no software pipeline, at most 176 registers per wave: the prefill kernel of
+// batches that also hold decode work (see decode_kernel_lean).
+template <int HD>
+__global__ __launch_bounds__(512, 1) __attribute__((amdgpu_num_vgpr(168))) void prefill_kernel_lean(const KernArgs a)
+{
+    const AttnParams &p = a.p;
+    prefill_unit<HD, 8, false>(p, [&](int idx) -> int { return p.cum_dev ? p.cum_dev[idx] : a.cum[idx]; }, (int)blockIdx.x);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1111,7 +1176,7 @@ __global__ __launch_bounds__(kPfThreads, 2) void mixed_kernel(const KernArgs a)
                 if (item >= n_dec_items) break;
                 const int run = item / p.Hkv;
                 const int kvh = (item - run * p.Hkv + run) % p.Hkv;   // kv heads rotate over the runs
-                decode_run<HD, (HD == 64 ? 2 : 1)>(p, dcum_at, L, run, kvh, lane, nullptr, first_piece, []() {});
+                decode_run<HD, (HD == 64 ? 2 : 1), 3>(p, dcum_at, L, run, kvh, lane, nullptr, first_piece, []() {});
                 if (pass == 0) ++n_first; else ++n_second;
             }
         } else {
@@ -1132,7 +1197,7 @@ __global__ __launch_bounds__(kPfThreads, 2) void mixed_kernel(const KernArgs a)
                 __syncthreads();
                 const int vb = sh_item;
                 if (vb < 0) break;
-                prefill_unit<HD, 4>(p, pf_at, vb);
+                prefill_unit<HD, 4, true>(p, pf_at, vb);
                 if (pass == 0) ++n_first; else ++n_second;
             }
         }
@@ -1285,6 +1350,10 @@ hipError_t launch_decode(const KernArgs &a, hipStream_t s)
 {
     if (a.p.static_runs <= 0 || a.p.dec_blocks <= 0) return hipSuccess;
     const dim3 grid((unsigned)((int64_t)a.p.static_runs * a.p.Hkv)), block(64);
+    if (a.p.lean && a.p.hd == 128) {
+        hipLaunchKernelGGL((decode_kernel_lean<128>), grid, block, 0, s, a);
+        return hipGetLastError();
+    }
     // KV blocks per softmax step: a wave keeps one step's tiles in flight, and 8 KiB per wave is what it takes
     // to saturate HBM with three waves per compute unit: one block for head_dim 128, two for head_dim 64
     // (measured: 56.9 % -> 72.2 % of the HBM peak on 256 sequences with head_dim 64; four blocks: 69.8 %)
@@ -1311,7 +1380,9 @@ hipError_t launch_prefill(const KernArgs &a, hipStream_t s)
 {
     if (a.p.n_tiles <= 0) return hipSuccess;
     const dim3 grid((unsigned)((int64_t)a.p.n_tiles * a.p.Hkv * (a.p.pf_split > 0 ? a.p.pf_split : 1)));
-    if (a.p.hd == 128 && a.p.pf_waves == 8)
+    if (a.p.hd == 128 && a.p.pf_waves == 8 && a.p.lean)
+        hipLaunchKernelGGL((prefill_kernel_lean<128>), grid, dim3(512), 0, s, a);
+    else if (a.p.hd == 128 && a.p.pf_waves == 8)
         hipLaunchKernelGGL((prefill_kernel<128, 8>), grid, dim3(512), 0, s, a);
     else if (a.p.hd == 128)
         hipLaunchKernelGGL((prefill_kernel<128, 4>), grid, dim3(kPfThreads), 0, s, a);
