@@ -212,6 +212,9 @@ def bench_append(a):
     k_new = torch.randn((b.total_q, b.Hkv, b.hd), generator=g, device="cuda").to(torch.bfloat16)
     v_new = torch.randn((b.total_q, b.Hkv, b.hd), generator=g, device="cuda").to(torch.bfloat16)
     ctx = B.Context(b.Hq, b.Hkv, b.hd, b.BS, b.num_blocks, b.max_blocks_per_seq)
+    for o in a.opt:
+        k, v = o.split("=")
+        ctx.set_option(k, int(v))
     stream = torch.cuda.current_stream()
 
     def step(i):
@@ -424,6 +427,7 @@ def main():
 
     step(0)
     info = ctx.plan_info()
+    kernels = ctx.plan_kernels()            # as rocprofv3 names them, decode first
     for i in range(a.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -484,7 +488,7 @@ def main():
         alg = work["bytes_decode"]
         dur = kern["decode_ms"] * 1e-3
         achieved = alg / dur / 1e9 if dur > 0 else 0.0
-        roofline = {"bound": "hbm", "kernel": "decode_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
+        roofline = {"bound": "hbm", "kernel": kernels[0], "achieved": achieved, "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
                     "algorithmic_bytes_per_launch": alg, "kernel_ms": kern["decode_ms"],
                     "whole_step_frac": whole_step_frac, "whole_step_bytes": work["bytes_total"],
@@ -493,10 +497,10 @@ def main():
         alg = work["flops_causal_prefill"]
         dur = kern["prefill_ms"] * 1e-3
         achieved = alg / dur / 1e12 if dur > 0 else 0.0
-        roofline = {"bound": "mfma", "kernel": "prefill_kernel", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
+        roofline = {"bound": "mfma", "kernel": kernels[-1], "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
                     "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
                     "algorithmic_flops_per_launch": alg, "kernel_ms": kern["prefill_ms"]}
-    roofline["traffic"] = read_traffic(roofline["kernel"], a.workload)
+    roofline["traffic"] = read_traffic(roofline["kernel"].split("<")[0], a.workload)
 
     line = {
         "metric": "mixed-batch attention tokens/s + achieved HBM GB/s (% of peak), 1 MI355X",
@@ -508,7 +512,7 @@ def main():
         "config": {"workload": b.name, "bench_name": a.workload, "num_seqs": b.num_seqs, "decode_seqs": work["decode_seqs"],
                    "prefill_chunks": work["prefill_chunks"], "q_tokens": work["q_tokens"], "kv_tokens": work["kv_tokens"],
                    "Hq": b.Hq, "Hkv": b.Hkv, "head_dim": b.hd, "block_size": b.BS, "replicas": len(bts),
-                   "plan": info, "replan_every_step": bool(a.replan_every_step)},
+                   "plan": info, "kernels": kernels, "replan_every_step": bool(a.replan_every_step)},
         "hbm_gbs_whole_step": work["bytes_total"] / (dt / a.steps) / 1e9,
         "hbm_frac_whole_step": work["bytes_total"] / (dt / a.steps) / 1e9 / HBM_PEAK_GBS,
         "kv_tokens_per_s": work["kv_tokens"] / (dt / a.steps),

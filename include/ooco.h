@@ -148,7 +148,8 @@ const char *ooco_last_error(const ooco_ctx *ctx);
  *                1024 calls between two reads
  *   "trace"      0/1: see ooco_trace_read
  * Tuning knobs kept for experiments (defaults are the measured best): "decode_nbi" (KV blocks per
- * softmax step of the decode kernel: 1, 2 or 4; 0 = default: 1 for head_dim 128, 2 for head_dim 64), "rotate_heads" (0/1: rotate the kv
+ * softmax step of the decode kernel: 1, 2 or 4; 0 = default: 1 for head_dim 128, 2 for head_dim 64), "append_parts" (KV append: workgroups that share one (sequence, KV block) pair,
+ * 1..8; 0 = default), "rotate_heads" (0/1: rotate the kv
  * head of a decode wave by its run index, default 1), "copy_variant" (block copy of this context: 10 * 16-byte
  * vectors per thread + 1 for non-temporal accesses, one of 10, 11, 20, 21, 40, 41, 80, 81; 0 = default 41;
  * any other value -> OOCO_EINVAL). */
@@ -224,6 +225,11 @@ ooco_status ooco_plan_dry_run(int num_q_heads, int num_kv_heads, int head_dim, i
  * parts each prefill tile's key range is cut into (1 = not split). */
 ooco_status ooco_plan_info(const ooco_ctx *ctx, int64_t *decode_waves, int64_t *prefill_tiles,
                            int64_t *decode_blocks, int64_t *workspace_used, int64_t *prefill_parts);
+
+/* Names of the kernels the last plan made launches, as rocprofv3 shows them without the argument list, separated
+ * by ';' (decode first), e.g. "decode_kernel_lean<128>;prefill_kernel_lean<128>": for matching profiler output
+ * with a batch.  names: HOST buffer of cap bytes. */
+ooco_status ooco_plan_kernels(const ooco_ctx *ctx, char *names /*HOST*/, size_t cap);
 
 /* The mixed-batch attention step (operation defined at the top of this file).
  *   q, out: DEVICE bf16 [total_q_tokens][Hq][hd]; k_cache, v_cache: DEVICE, read-only here;

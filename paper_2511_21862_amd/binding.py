@@ -19,7 +19,7 @@ _STATUS_NAMES = {0: "OOCO_OK", -1: "OOCO_EINVAL", -2: "OOCO_ESHAPE", -3: "OOCO_E
                  -5: "OOCO_ENOTIMPL"}
 
 EXPORTS = ["ooco_ctx_create", "ooco_ctx_destroy", "ooco_last_error", "ooco_set_option", "ooco_plan",
-           "ooco_plan_dry_run", "ooco_plan_info", "ooco_profile_read", "ooco_profile_read_calls", "ooco_trace_read", "ooco_attn_mixed", "ooco_attn_mixed_static", "ooco_kv_block_copy", "ooco_kv_append", "ooco_predict_latency", "ooco_mix_decoding_select",
+           "ooco_plan_dry_run", "ooco_plan_info", "ooco_plan_kernels", "ooco_profile_read", "ooco_profile_read_calls", "ooco_trace_read", "ooco_attn_mixed", "ooco_attn_mixed_static", "ooco_kv_block_copy", "ooco_kv_append", "ooco_predict_latency", "ooco_mix_decoding_select",
            "ooco_migration_preference", "ooco_migration_select", "ooco_eviction_victims"]
 
 if not os.path.exists(LIB_PATH):
@@ -44,6 +44,8 @@ _lib.ooco_plan_dry_run.argtypes = ([ctypes.c_int] * 6 + [ctypes.c_size_t] + [cty
                                    + [_P, ctypes.c_int64, _P, ctypes.c_int64, _P, ctypes.c_char_p, ctypes.c_size_t, _P, ctypes.c_int64, ctypes.c_int64])
 _lib.ooco_plan_info.restype = ctypes.c_int
 _lib.ooco_plan_info.argtypes = [_P] + [ctypes.POINTER(ctypes.c_int64)] * 5
+_lib.ooco_plan_kernels.restype = ctypes.c_int
+_lib.ooco_plan_kernels.argtypes = [_P, ctypes.c_char_p, ctypes.c_size_t]
 _lib.ooco_profile_read.restype = ctypes.c_int
 _lib.ooco_profile_read.argtypes = [_P, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
 _lib.ooco_profile_read_calls.restype = ctypes.c_int
@@ -181,6 +183,12 @@ def ooco_plan_info(ctx) -> dict:
     _check(ctx, _lib.ooco_plan_info(ctx, *[ctypes.byref(x) for x in v]))
     return dict(decode_waves=v[0].value, prefill_tiles=v[1].value, decode_blocks=v[2].value,
                 workspace_used=v[3].value, prefill_parts=v[4].value)
+
+
+def ooco_plan_kernels(ctx) -> list:
+    buf = ctypes.create_string_buffer(256)
+    _check(ctx, _lib.ooco_plan_kernels(ctx, buf, 256))
+    return [k for k in buf.value.decode().split(";") if k]
 
 
 def ooco_trace_read(ctx, cap_waves=1 << 16):
@@ -375,6 +383,9 @@ class Context:
 
     def plan_info(self):
         return ooco_plan_info(self.h)
+
+    def plan_kernels(self):
+        return ooco_plan_kernels(self.h)
 
     def profile_read_calls(self, cap=1024):
         return ooco_profile_read_calls(self.h, cap)

@@ -415,6 +415,7 @@ struct ooco_ctx {
     int32_t *pf_counters = nullptr;   // [kPrefillSplitUnits] arrival counters of split prefill tiles, zero between calls
     uint16_t xcd_cw[kXcds] = {};   // option "xcd_weights"
     int64_t opt_overlap = 1;
+    int64_t opt_append_parts = 0;   // KV append: workgroups per (sequence, block) pair, 0 = automatic
     int64_t opt_lean = 1;           // mixed batches: the register-lean kernels (0 never, 1 automatic, 2 always)
     int64_t opt_pf_waves = 0;       // waves per prefill workgroup: 0 = automatic, 4, 8
     int64_t opt_fused = 0;          // mixed batches in one launch (mixed kernel) instead of two kernels on two streams
@@ -644,6 +645,9 @@ ooco_status ooco_set_option(ooco_ctx *ctx, const char *name, int64_t value)
             return fail(ctx, OOCO_EINVAL, "ooco_set_option: copy_variant must be one of 0, 10, 11, 20, 21, 40, 41, 80, 81");
         ctx->opt_copy_variant = (int)value;
         return OOCO_OK;
+    } else if (!strcmp(name, "append_parts")) {
+        ctx->opt_append_parts = value;
+        return OOCO_OK;
     } else if (!strcmp(name, "plan_persistent")) {
         ctx->opt_plan_persistent = value;
         return OOCO_OK;
@@ -804,6 +808,31 @@ ooco_status ooco_plan_info(const ooco_ctx *ctx, int64_t *decode_waves, int64_t *
         *workspace_used = (int64_t)bytes;
     }
     if (prefill_parts) *prefill_parts = ctx->plan.n_tiles > 0 ? ctx->plan.pf_split : 1;
+    return OOCO_OK;
+}
+
+ooco_status ooco_plan_kernels(const ooco_ctx *ctx, char *names, size_t cap)
+{
+    if (!ctx) return OOCO_EINVAL;
+    if (!ctx->plan_made) return fail(ctx, OOCO_EINVAL, "ooco_plan_kernels: no plan has been made");
+    if (!names || cap == 0) return fail(ctx, OOCO_EINVAL, "ooco_plan_kernels: no buffer");
+    const HostPlan &pl = ctx->plan;
+    const bool dec = pl.static_runs > 0, pf = pl.n_tiles > 0;
+    const int nbi = ctx->opt_nbi ? (int)ctx->opt_nbi : (ctx->hd == 64 ? 2 : 1);
+    char d[64] = "", f[64] = "";
+    if (dec && pf && pl.dec_cus > 0)
+        snprintf(d, sizeof d, "mixed_kernel<%d>", ctx->hd);
+    else {
+        if (dec && pl.lean)
+            snprintf(d, sizeof d, "decode_kernel_lean<%d>", ctx->hd);
+        else if (dec)
+            snprintf(d, sizeof d, "decode_kernel<%d, %d>", ctx->hd, nbi);
+        if (pf && pl.lean && pl.pf_waves == 8)
+            snprintf(f, sizeof f, "prefill_kernel_lean<%d>", ctx->hd);
+        else if (pf)
+            snprintf(f, sizeof f, "prefill_kernel<%d, %d>", ctx->hd, pl.pf_waves);
+    }
+    snprintf(names, cap, "%s%s%s", d, d[0] && f[0] ? ";" : "", f);
     return OOCO_OK;
 }
 
@@ -1168,7 +1197,7 @@ ooco_status ooco_kv_append(ooco_ctx *ctx, const void *k_new, const void *v_new, 
         return fail(ctx, OOCO_EINVAL, "ooco_kv_append: NULL pointer argument");
     hipError_t e = launch_kv_append(k_new, v_new, k_cache, v_cache, block_tables, query_start_loc, ctx_lens, num_seqs,
                                     total_q_tokens, ctx->Hkv, ctx->hd, ctx->max_blocks_per_seq, ctx->num_blocks,
-                                    reinterpret_cast<hipStream_t>(stream));
+                                    (int)ctx->opt_append_parts, reinterpret_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail(ctx, OOCO_EHIP, "ooco_kv_append: kernel launch: %s", hipGetErrorString(e));
     return OOCO_OK;
 }

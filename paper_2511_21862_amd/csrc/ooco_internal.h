@@ -96,7 +96,7 @@ hipError_t launch_block_copy(const void *k_src, const void *v_src, void *k_dst, 
 
 hipError_t launch_kv_append(const void *k_new, const void *v_new, void *k_cache, void *v_cache, const int32_t *block_tables,
                             const int32_t *query_start_loc, const int32_t *ctx_lens, int num_seqs, int total_q, int Hkv,
-                            int hd, int max_blocks_per_seq, int64_t num_blocks, hipStream_t s);
+                            int hd, int max_blocks_per_seq, int64_t num_blocks, int parts_opt, hipStream_t s);
 
 // n int32 values at p become zero (a kernel, so that callers under stream capture record no memset node).
 hipError_t launch_fill_zero(int32_t *p, int64_t n, hipStream_t s);

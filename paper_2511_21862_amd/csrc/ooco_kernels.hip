@@ -16,6 +16,8 @@
 // sequence are zeroed by select (those slots may hold NaN/Inf).
 #include "ooco_internal.h"
 
+#include <algorithm>
+
 namespace ooco {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -1255,79 +1257,145 @@ __global__ __launch_bounds__(kCopyThreads) void block_copy_kernel(const u32x4 *k
 }
 
 // ------------------------------------------------------------------------------------------
-// KV append: the K and V vectors of the step's tokens go into their paged slots.  One wave per
-// query row.  K: the wave stores its own row, one 16-byte store per group of 8 dims (the cache
-// keeps [hd/8][16 slots][8]).  V is stored [dim][16 slots], so the rows of this step that fall into
-// the same KV block are written together: each of their waves takes an equal share of the
-// (kv head, dim) elements, gathers that element from all rows of the group and writes the values
-// side by side (two 16-byte stores when the step covers the whole block, 2-byte stores otherwise).
-__global__ __launch_bounds__(64) void kv_append_kernel(const uint16_t *k_new, const uint16_t *v_new, uint16_t *k_cache,
-                                                       uint16_t *v_cache, const int32_t *block_tables,
-                                                       const int32_t *query_start_loc, const int32_t *ctx_lens,
-                                                       int num_seqs, int total_q, int Hkv, int hd, int max_blocks_per_seq,
-                                                       int64_t num_blocks)
+// KV append: the K and V vectors of the step's tokens go into their paged slots.  One workgroup of 256 threads per
+// (sequence, KV block that the step's rows of that sequence touch): the rows of a block are written together, so
+// that whole lines leave the compute unit -- K keeps [hd/8][16 slots][8]: the 16-byte pieces of up to 16 rows are
+// contiguous per group of 8 dims; V keeps [dim][16 slots]: a thread gathers one (kv head, dim) element from all
+// rows of the block and writes them side by side (two 16-byte stores when the step covers the whole block, 2-byte
+// stores otherwise).
+// Workgroup w -> (sequence, block) without a plan: sequence i owns the workgroup indices [G(i), G(i+1)) with
+// G(i) = query_start_loc[i] / 16 + 2 i, which is at least as many as the blocks its q_len rows can touch
+// (q_len / 16 + 2); the grid has total_q / 16 + 2 num_seqs + 1 workgroups and those beyond a sequence's last
+// block leave at once.  Every workgroup finds its sequence with one 64-lane look at query_start_loc.
+constexpr int kAppendThreads = 256;
+__global__ __launch_bounds__(kAppendThreads) void kv_append_kernel(const uint16_t *k_new, const uint16_t *v_new,
+                                                                   uint16_t *k_cache, uint16_t *v_cache,
+                                                                   const int32_t *block_tables,
+                                                                   const int32_t *query_start_loc, const int32_t *ctx_lens,
+                                                                   int num_seqs, int total_q, int Hkv, int hd,
+                                                                   int max_blocks_per_seq, int64_t num_blocks, int parts)
 {
-    const int lane = threadIdx.x;
-    const int row = blockIdx.x;
-    auto qsl_at = [&](int idx) -> int { return query_start_loc[idx]; };
-    const int seq = __builtin_amdgcn_readfirstlane(min(count_le(qsl_at, num_seqs, row, lane), num_seqs - 1));
-    const int q0 = query_start_loc[seq], q_len = query_start_loc[seq + 1] - q0;
-    const int t = row - q0;
-    if (t < 0 || t >= q_len) return;                    // inconsistent query_start_loc: nothing is written
-    const int ctx = ctx_lens[seq];
-    const int pos = ctx + t;
-    const int bidx = pos / kBlockSize;
-    if (ctx < 0 || bidx >= max_blocks_per_seq) return;  // beyond the block table: nothing is written
-    const int64_t blk = block_tables[(int64_t)seq * max_blocks_per_seq + bidx];
-    if (blk < 0 || blk >= num_blocks) return;           // id outside the pool: nothing is written
-    const int slot = pos % kBlockSize;
-    const int row_elems = Hkv * hd;
-    // K: chunk c = (kv head, group of 8 dims) -> cache chunk ((blk*Hkv + kvh)*(hd/8) + d8)*16 + slot.  Four
-    // consecutive slots of a chunk row are one 64-byte line: the rows of this sequence that fall into one line
-    // are written together by the wave of the first of them (lane = 4 * chunk + row), so that whole lines
-    // leave the compute unit instead of 16-byte pieces 256 bytes apart.
-    if ((slot & 3) == 0 || t == 0) {
-        const int chunks = Hkv * (hd / 8);
-        const int nr = min(min(4 - (slot & 3), q_len - t), total_q - row);   // rows row .. row+nr-1 share the line
-        const int r = lane & 3;
-        const u32x4 *src = reinterpret_cast<const u32x4 *>(k_new + (int64_t)(row + min(r, nr - 1)) * row_elems);
-        u32x4 *dst = reinterpret_cast<u32x4 *>(k_cache) + (int64_t)blk * chunks * kBlockSize + slot + r;
-        if (r < nr)
-            for (int c = lane >> 2; c < chunks; c += 16) dst[(int64_t)c * kBlockSize] = src[c];
-    }
-    // V: the group = rows t0 .. t0+nrow-1 of this sequence that share the block; this wave is member j
-    const int t0 = max(0, t - slot);
-    const int slot0 = (ctx + t0) % kBlockSize;
-    const int nrow = min(min(kBlockSize - slot0, q_len - t0), total_q - (q0 + t0));
-    const int j = t - t0;
-    const int e_lo = (int)((int64_t)row_elems * j / nrow), e_hi = (int)((int64_t)row_elems * (j + 1) / nrow);
-    const uint16_t *src0 = v_new + (int64_t)(q0 + t0) * row_elems;
-    uint16_t *dst0 = v_cache + (int64_t)blk * row_elems * kBlockSize + slot0;
-    for (int e = e_lo + lane; e < e_hi; e += 64) {     // element e = (kv head, dim) -> cache row (blk*Hkv*hd + e)*16
-        const uint16_t *src = src0 + e;
-        uint16_t *dst = dst0 + (int64_t)e * kBlockSize;
-        if (nrow == kBlockSize) {
-            uint32_t w[8];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    // `parts` workgroups share a (sequence, block) pair: each takes every parts-th slice of the K chunks and of the
+    // V elements, so that a pair whose rows cover its block only partly (many narrow stores) does not end last
+    const int w = blockIdx.x / parts;
+    const int part = blockIdx.x - w * parts;
+    auto g_at = [&](int idx) -> int { return query_start_loc[idx] / kBlockSize + 2 * idx; };
+    int seq;
+    if (num_seqs <= 4 * 64) {
+        // up to 256 sequences: the four 64-lane looks are independent loads (one memory round trip), where
+        // count_le would wait for each before starting the next
+        int cnt = 0;
 #pragma unroll
-            for (int r = 0; r < 8; ++r)
-                w[r] = (uint32_t)src[(int64_t)(2 * r) * row_elems] | ((uint32_t)src[(int64_t)(2 * r + 1) * row_elems] << 16);
-            u32x4 *d4 = reinterpret_cast<u32x4 *>(dst);
-            d4[0] = u32x4{w[0], w[1], w[2], w[3]};
-            d4[1] = u32x4{w[4], w[5], w[6], w[7]};
-        } else {
-            for (int r = 0; r < nrow; ++r) dst[r] = src[(int64_t)r * row_elems];
+        for (int pass = 0; pass < 4; ++pass) {
+            const int idx = 1 + 64 * pass + lane;
+            const int v = idx <= num_seqs ? g_at(idx) : 0x7FFFFFFF;
+            cnt += __popcll(__ballot(v <= w));
+        }
+        seq = cnt;
+    } else {
+        seq = count_le(g_at, num_seqs, w, lane);
+    }
+    seq = __builtin_amdgcn_readfirstlane(min(seq, num_seqs - 1));
+    const int q0 = query_start_loc[seq], q_len = query_start_loc[seq + 1] - q0;
+    const int ctx = ctx_lens[seq];
+    if (q_len <= 0 || ctx < 0 || q0 < 0 || q0 + q_len > total_q) return;   // nothing to write / inconsistent arrays
+    const int j = w - (q0 / kBlockSize + 2 * seq);          // which of the touched blocks
+    const int bidx = ctx / kBlockSize + j;
+    if (j < 0 || bidx > (ctx + q_len - 1) / kBlockSize) return;   // beyond the sequence's last touched block
+    if (bidx >= max_blocks_per_seq) return;                 // beyond the block table: nothing is written
+    // (the id is checked where the stores are, so that the loads of the new vectors do not wait for it)
+    const int64_t blk_raw = block_tables[(int64_t)seq * max_blocks_per_seq + bidx];
+    const bool blk_ok = blk_raw >= 0 && blk_raw < num_blocks;   // id outside the pool: nothing is written
+    const int64_t blk = blk_ok ? blk_raw : 0;
+    // rows t_lo .. t_lo + nrow - 1 of the sequence fall into this block, starting at slot slot0
+    const int t_lo = max(0, bidx * kBlockSize - ctx);
+    const int slot0 = ctx + t_lo - bidx * kBlockSize;
+    const int nrow = min(kBlockSize - slot0, q_len - t_lo);
+    const int row_elems = Hkv * hd;
+    const int64_t row0 = (int64_t)(q0 + t_lo);
+    // K: thread -> (row r = tid % 16, 16-byte chunk c = tid / 16 + 16 i): the 16 rows of a chunk are adjacent in
+    // the cache, so a wave's stores cover 4 chunks x 256 contiguous bytes
+    {
+        const int chunks = row_elems / 8;
+        const int r = tid & 15;
+        if (r < nrow) {
+            const u32x4 *src = reinterpret_cast<const u32x4 *>(k_new + (row0 + r) * row_elems);
+            u32x4 *dst = reinterpret_cast<u32x4 *>(k_cache) + (int64_t)blk * chunks * kBlockSize + slot0 + r;
+            constexpr int kSlice = kAppendThreads / 16;   // chunks a workgroup moves per pass
+            for (int c0 = (tid >> 4) + kSlice * part; c0 < chunks; c0 += 2 * kSlice * parts) {
+                u32x4 v[2];
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    const int c = c0 + i * kSlice * parts;
+                    if (c < chunks) v[i] = src[c];
+                }
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    const int c = c0 + i * kSlice * parts;
+                    if (c < chunks && blk_ok) dst[(int64_t)c * kBlockSize] = v[i];
+                }
+            }
+        }
+    }
+    // V: thread -> element e = (kv head, dim); cache row (blk * Hkv * hd + e) * 16, slots slot0 .. slot0 + nrow - 1
+    {
+        const uint16_t *src0 = v_new + row0 * row_elems;
+        uint16_t *dst0 = v_cache + (int64_t)blk * row_elems * kBlockSize + slot0;
+        for (int e = tid + kAppendThreads * part; e < row_elems; e += kAppendThreads * parts) {
+            const uint16_t *src = src0 + e;
+            uint16_t *dst = dst0 + (int64_t)e * kBlockSize;
+            if (nrow == kBlockSize) {
+                uint32_t x[8];
+#pragma unroll
+                for (int r = 0; r < 8; ++r)
+                    x[r] = (uint32_t)src[(int64_t)(2 * r) * row_elems] | ((uint32_t)src[(int64_t)(2 * r + 1) * row_elems] << 16);
+                u32x4 *d4 = reinterpret_cast<u32x4 *>(dst);
+                if (blk_ok) {
+                    d4[0] = u32x4{x[0], x[1], x[2], x[3]};
+                    d4[1] = u32x4{x[4], x[5], x[6], x[7]};
+                }
+            } else {
+                // all loads before the first store (one memory round trip instead of one per row); x[s] = value of
+                // slot s of the block.  Quarters of the cache row (4 slots = 8 bytes) that the step covers whole are
+                // written with one store each, the ragged ends slot by slot.
+                uint16_t x[kBlockSize];
+#pragma unroll
+                for (int sl = 0; sl < kBlockSize; ++sl) {
+                    const int r = sl - slot0;
+                    x[sl] = (r >= 0 && r < nrow) ? src[(int64_t)r * row_elems] : (uint16_t)0;
+                }
+                uint16_t *row = dst - slot0;   // slot 0 of the cache row (32-byte aligned)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    if (!blk_ok) {
+                    } else if (4 * q >= slot0 && 4 * q + 4 <= slot0 + nrow) {
+                        *reinterpret_cast<u32x2 *>(row + 4 * q) =
+                            u32x2{(uint32_t)x[4 * q] | ((uint32_t)x[4 * q + 1] << 16), (uint32_t)x[4 * q + 2] | ((uint32_t)x[4 * q + 3] << 16)};
+                    } else {
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) {
+                            const int sl = 4 * q + k;
+                            if (sl >= slot0 && sl < slot0 + nrow) row[sl] = x[sl];
+                        }
+                    }
+                }
+            }
         }
     }
 }
 
 hipError_t launch_kv_append(const void *k_new, const void *v_new, void *k_cache, void *v_cache, const int32_t *block_tables,
                             const int32_t *query_start_loc, const int32_t *ctx_lens, int num_seqs, int total_q, int Hkv,
-                            int hd, int max_blocks_per_seq, int64_t num_blocks, hipStream_t s)
+                            int hd, int max_blocks_per_seq, int64_t num_blocks, int parts_opt, hipStream_t s)
 {
     if (total_q <= 0 || num_seqs <= 0) return hipSuccess;
-    hipLaunchKernelGGL(kv_append_kernel, dim3((unsigned)total_q), dim3(64), 0, s, (const uint16_t *)k_new,
+    const int parts = parts_opt > 0 ? std::min(parts_opt, 8) : std::max(1, std::min(2, Hkv * hd / (2 * kAppendThreads)));   // two for 8 kv heads x 128: measured best (1: 13.6 us, 2: 11.2, 4: 14.6 on 4,224 tokens)
+    const unsigned grid = (unsigned)((total_q / kBlockSize + 2 * (int64_t)num_seqs + 1) * parts);
+    hipLaunchKernelGGL(kv_append_kernel, dim3(grid), dim3(kAppendThreads), 0, s, (const uint16_t *)k_new,
                        (const uint16_t *)v_new, (uint16_t *)k_cache, (uint16_t *)v_cache, block_tables, query_start_loc,
-                       ctx_lens, num_seqs, total_q, Hkv, hd, max_blocks_per_seq, num_blocks);
+                       ctx_lens, num_seqs, total_q, Hkv, hd, max_blocks_per_seq, num_blocks, parts);
     return hipGetLastError();
 }
 
