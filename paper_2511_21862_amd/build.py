@@ -11,7 +11,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libooco.so")
-SOURCES = ["ooco_abi.hip", "ooco_kernels.hip", "ooco_model.hip"]
+SOURCES = ["ooco_abi.hip", "ooco_kernels.hip", "ooco_model.hip", "ooco_sort.hip"]
 HEADERS = [os.path.join(CSRC, "ooco_internal.h"), os.path.join(HERE, "..", "include", "ooco.h")]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -415,6 +415,10 @@ struct ooco_ctx {
     int32_t *pf_counters = nullptr;   // [kPrefillSplitUnits] arrival counters of split prefill tiles, zero between calls
     uint16_t xcd_cw[kXcds] = {};   // option "xcd_weights"
     int64_t opt_overlap = 1;
+    int64_t opt_copy_sort = 1;      // block copy: order the pairs by destination id on the device (0 never, 1 from kCopySortMin pairs, 2 always)
+    void *sort_buf = nullptr;       // [2 * sort_cap int64 (sorted dst, sorted src)] + temporary storage of the sort
+    int64_t sort_cap = 0;           // pairs the buffer holds
+    size_t sort_temp_bytes = 0;
     int64_t opt_append_parts = 0;   // KV append: workgroups per (sequence, block) pair, 0 = automatic
     int64_t opt_lean = 1;           // mixed batches: the register-lean kernels (0 never, 1 automatic, 2 always)
     int64_t opt_pf_waves = 0;       // waves per prefill workgroup: 0 = automatic, 4, 8
@@ -546,6 +550,7 @@ ooco_status ooco_ctx_destroy(ooco_ctx *ctx)
     for (hipEvent_t x : ctx->prof_ev)
         if (x) (void)hipEventDestroy(x);
     if (ctx->trace_d) (void)hipFree(ctx->trace_d);
+    if (ctx->sort_buf) (void)hipFree(ctx->sort_buf);
     if (ctx->counters) (void)hipFree(ctx->counters);
     if (ctx->pf_counters) (void)hipFree(ctx->pf_counters);
     if (ctx->plan_d) (void)hipFree(ctx->plan_d);
@@ -644,6 +649,9 @@ ooco_status ooco_set_option(ooco_ctx *ctx, const char *name, int64_t value)
         if (std::find(std::begin(known), std::end(known), value) == std::end(known))
             return fail(ctx, OOCO_EINVAL, "ooco_set_option: copy_variant must be one of 0, 10, 11, 20, 21, 40, 41, 80, 81");
         ctx->opt_copy_variant = (int)value;
+        return OOCO_OK;
+    } else if (!strcmp(name, "copy_sort")) {
+        ctx->opt_copy_sort = value;
         return OOCO_OK;
     } else if (!strcmp(name, "append_parts")) {
         ctx->opt_append_parts = value;
@@ -1179,8 +1187,57 @@ ooco_status ooco_kv_block_copy(ooco_ctx *ctx, const void *k_src, const void *v_s
     if (num_pairs > (int64_t)1 << 26)
         return fail(ctx, OOCO_EINVAL, "ooco_kv_block_copy: num_pairs=%lld too large", (long long)num_pairs);
     const int64_t block_bytes = (int64_t)ctx->Hkv * ctx->BS * ctx->hd * 2;
-    hipError_t e = launch_block_copy(k_src, v_src, k_dst, v_dst, src_block_ids, dst_block_ids, num_pairs, block_bytes,
-                                     ctx->opt_copy_variant, reinterpret_cast<hipStream_t>(stream));
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    hipError_t e = hipSuccess;
+    // Large copies take their pairs in order of destination id (sorted on the device into a buffer of the context,
+    // which grows on demand -- never while the stream is being captured, a captured copy keeps the caller's order).
+    constexpr int64_t kCopySortMin = 2048;
+    if (ctx->opt_copy_sort >= 2 || (ctx->opt_copy_sort == 1 && num_pairs >= kCopySortMin)) {
+        bool ready = num_pairs <= ctx->sort_cap;
+        if (!ready) {
+            hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+            const bool capturing = hipStreamIsCapturing(s, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone;
+            size_t temp = 0;
+            if (!capturing && sort_pairs_temp_bytes(num_pairs, &temp) == hipSuccess) {
+                // (work of earlier calls may still read the old buffer: wait for it before freeing)
+                if (ctx->sort_buf) {
+                    (void)hipStreamSynchronize(s);
+                    (void)hipFree(ctx->sort_buf);
+                    ctx->sort_buf = nullptr;
+                    ctx->sort_cap = 0;
+                }
+                const size_t ids = ((size_t)num_pairs * 2 * sizeof(int64_t) + 255) / 256 * 256;
+                if (hipMalloc(&ctx->sort_buf, ids + temp) == hipSuccess) {
+                    ctx->sort_cap = num_pairs;
+                    ctx->sort_temp_bytes = temp;
+                    ready = true;
+                } else {
+                    (void)hipGetLastError();
+                    ctx->sort_buf = nullptr;
+                }
+            }
+        }
+        if (ready) {
+            int64_t *dst_sorted = static_cast<int64_t *>(ctx->sort_buf), *src_sorted = dst_sorted + ctx->sort_cap;
+            void *temp = static_cast<unsigned char *>(ctx->sort_buf) + ((size_t)ctx->sort_cap * 2 * sizeof(int64_t) + 255) / 256 * 256;
+            // (key = the low bits that number the blocks of this context's pool; the destination pool is that pool or
+            // a smaller one)
+            int bits = 1;
+            while (bits < 32 && ((int64_t)1 << bits) < ctx->num_blocks) ++bits;
+            e = launch_sort_pairs(temp, ctx->sort_temp_bytes, dst_block_ids, dst_sorted, src_block_ids, src_sorted, num_pairs,
+                                  bits, s);
+            if (e == hipSuccess) {
+                src_block_ids = src_sorted;
+                dst_block_ids = dst_sorted;
+            } else {
+                (void)hipGetLastError();   // the sort did not start: copy in the caller's order
+                e = hipSuccess;
+            }
+        }
+    }
+    if (e == hipSuccess)
+        e = launch_block_copy(k_src, v_src, k_dst, v_dst, src_block_ids, dst_block_ids, num_pairs, block_bytes,
+                              ctx->opt_copy_variant, s);
     if (e != hipSuccess) return fail(ctx, OOCO_EHIP, "ooco_kv_block_copy: kernel launch: %s", hipGetErrorString(e));
     return OOCO_OK;
 }

@@ -94,6 +94,12 @@ hipError_t launch_block_copy(const void *k_src, const void *v_src, void *k_dst, 
                              const int64_t *src_ids, const int64_t *dst_ids, int64_t num_pairs,
                              int64_t block_bytes, int variant, hipStream_t s);
 
+// Pairs ordered by destination id (ooco_sort.hip): bytes of temporary storage for num_pairs, and the sort itself
+// (dst_sorted / src_sorted: num_pairs int64 each; the low `bits` bits of the destination ids are the sort key).
+hipError_t sort_pairs_temp_bytes(int64_t num_pairs, size_t *bytes);
+hipError_t launch_sort_pairs(void *temp, size_t temp_bytes, const int64_t *dst_ids, int64_t *dst_sorted,
+                             const int64_t *src_ids, int64_t *src_sorted, int64_t num_pairs, int bits, hipStream_t s);
+
 hipError_t launch_kv_append(const void *k_new, const void *v_new, void *k_cache, void *v_cache, const int32_t *block_tables,
                             const int32_t *query_start_loc, const int32_t *ctx_lens, int num_seqs, int total_q, int Hkv,
                             int hd, int max_blocks_per_seq, int64_t num_blocks, int parts_opt, hipStream_t s);

@@ -223,11 +223,13 @@ def test_block_copy_bit_exact_round_trip():
                           torch.zeros(0, dtype=torch.int64, device="cuda"))
 
 
-@pytest.mark.parametrize("variant", [10, 11, 20, 21, 40, 41, 80, 81])
+@pytest.mark.parametrize("variant", [10, 11, 20, 21, 40, 41, 80, 81, 1041])
 def test_block_copy_variants_are_bit_exact(variant):
-    # option "copy_variant": 16-byte vectors per thread x 10 + (1 = non-temporal accesses)
+    # option "copy_variant": 16-byte vectors per thread x 10 + (1 = non-temporal accesses); +1000 here = with the
+    # pairs ordered by destination id on the device first (option "copy_sort", which large copies use by themselves)
+    sort, variant = variant >= 1000, variant % 1000
     b = W.build_batch(Hq=32, Hkv=8, hd=128, q_lens=[1, 1], ctx_lens=[700, 45], num_blocks=80, seed=19)
-    say(f"case: block copy variant {variant}")
+    say(f"case: block copy variant {variant}, sorted {sort}")
     d = W.to_device(b)
     src = W.victim_block_ids(b, [0, 1])
     n = len(src)
@@ -236,8 +238,13 @@ def test_block_copy_variants_are_bit_exact(variant):
     vs = torch.full((n + 3,) + tuple(d.v_cache.shape[1:]), 3.0, dtype=torch.bfloat16, device="cuda")
     with B.Context(b.Hq, b.Hkv, b.hd, b.BS, b.num_blocks, b.max_blocks_per_seq) as ctx:
         ctx.set_option("copy_variant", variant)
-        ctx.kv_block_copy(d.k_cache, d.v_cache, ks, vs, torch.from_numpy(src).cuda(), torch.from_numpy(dst).cuda())
+        ctx.set_option("copy_sort", 2 if sort else 0)
+        src_d, dst_d = torch.from_numpy(src).cuda(), torch.from_numpy(dst).cuda()
+        ctx.kv_block_copy(d.k_cache, d.v_cache, ks, vs, src_d, dst_d)
+        if sort:   # again with fewer pairs (the context's sort buffer is reused), same blocks, same result
+            ctx.kv_block_copy(d.k_cache, d.v_cache, ks, vs, src_d[: n // 2], dst_d[: n // 2])
         torch.cuda.synchronize()
+        assert torch.equal(src_d.cpu(), torch.from_numpy(src)) and torch.equal(dst_d.cpu(), torch.from_numpy(dst))   # the caller's lists are not touched
     kh = np.full(ks.shape, W.f32_to_bf16_bits(np.float32([3.0]))[0], np.uint16)
     vh = kh.reshape(-1)[: vs.numel()].reshape(vs.shape).copy()
     ref_c.block_copy(b.k_cache, b.v_cache, kh, vh, src, dst)
