@@ -371,6 +371,49 @@ def bench_preempt(a):
     print(json.dumps(line), flush=True)
 
 
+def wg_timeline(ctx, b, run_step, torch, reps=5):
+    """One traced launch of a prefill-only batch: when every workgroup started and ended (option "trace"; the
+    kernel's own 100 MHz time stamps), summed up per eighth of the dispatch order and per compute unit.  Median
+    over `reps` launches of every figure, in microseconds from the first workgroup's start."""
+    from paper_2511_21862_amd import binding as B
+
+    tiles = B.ooco_plan_dry_run(b.Hq, b.Hkv, b.hd, b.BS, b.max_blocks_per_seq, torch.cuda.get_device_properties(0).multi_processor_count,
+                                512 << 20, h_seq_lens=b.seq_lens, h_query_start_loc=b.query_start_loc,
+                                h_ctx_lens=b.ctx_lens)["prefill_tiles"]
+    steps_tile = (tiles[:, 3] + tiles[:, 2] + 63) // 64
+    ctx.set_option("trace", 1)
+    rows = []
+    for _ in range(reps):
+        run_step()
+        torch.cuda.synchronize()
+        raw = ctx.trace_read()
+        t0 = raw[:, 0].astype(np.float64) / 100.0
+        t1 = raw[:, 3].astype(np.float64) / 100.0
+        cu = raw[:, 1].astype(np.int64)
+        base = t0.min()
+        t0, t1 = t0 - base, t1 - base
+        n = len(t0)
+        steps = np.repeat(steps_tile, n // len(steps_tile))
+        r = {"workgroups": n, "compute_units": int(len(np.unique(cu))), "span_us": float(t1.max()),
+             "all_first_round_started_by_us": float(np.sort(t0)[min(n, 2 * len(np.unique(cu))) - 1]),
+             "slot_busy_us_mean": float((t1 - t0).sum() / (2 * len(np.unique(cu)))),
+             "steps_total": int(steps.sum())}
+        ends = np.array([t1[cu == c].max() for c in np.unique(cu)])
+        r["cu_last_end_us_min_mean_max"] = [float(ends.min()), float(ends.mean()), float(ends.max())]
+        eighth = []
+        for k in range(8):
+            sel = slice(k * n // 8, (k + 1) * n // 8)
+            eighth.append([float(steps[sel].mean()), float(t0[sel].min()), float(t0[sel].max()), float(t1[sel].min()),
+                           float(t1[sel].max()), float((t1 - t0)[sel].mean())])
+        r["eighths_steps_start_min_max_end_min_max_duration_mean"] = eighth
+        rows.append(r)
+    ctx.set_option("trace", 0)
+    med = lambda key: np.median(np.array([r[key] for r in rows], dtype=np.float64), axis=0)
+    outd = {k: (med(k).tolist() if isinstance(rows[0][k], list) else float(med(k))) for k in rows[0]}
+    outd["launches"] = reps
+    return outd
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -380,6 +423,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--replan-every-step", type=int, default=1)
     ap.add_argument("--opt", action="append", default=[], help="name=value passed to ooco_set_option")
+    ap.add_argument("--wg-timeline", action="store_true",
+                    help="prefill-only workloads: add the workgroups' start and end times of one traced launch to the line")
     a = ap.parse_args()
     if a.gpus != 1:
         raise SystemExit("bench.py: this build measures one GPU only (no collectives, no sharding); run with --gpus 1")
@@ -521,6 +566,8 @@ def main():
         "kernel_ms": kern,
         "roofline": roofline,
     }
+    if a.wg_timeline and work["decode_seqs"] == 0:
+        line["wg_timeline"] = wg_timeline(ctx, b, lambda: step(0), torch)
     if not a.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(b)
     ctx.close()

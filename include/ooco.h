@@ -129,6 +129,11 @@ const char *ooco_last_error(const ooco_ctx *ctx);
  *                         when the batch has too few tiles to occupy the compute units and an
  *                         estimate of the kernel time improves by at least 7 %.  A tile
  *                         never gets more parts than it has 64-key steps.
+ *   "prefill_sorted"      0/1 (default 1): a batch of at most 512 prefill tiles dispatches the tiles of ALL its
+ *                         chunks by decreasing number of 64-key steps (one list entry per tile, in the kernel
+ *                         arguments); 0 or more tiles: chunk by chunk, longest sequence first, the later tiles of
+ *                         a chunk first.  Measured on MI355X, 8 chunks of 512 rows on 175..1781 cached tokens:
+ *                         the span of the workgroups 94..98 -> 89..92 us.
  * Immediate options:
  *   "plan_persistent"  0/1 (default 0): 0 = a plan made by ooco_plan serves exactly one ooco_attn_mixed and is
  *                then used up (a later call without a new plan plans by itself from the device arrays), so that
@@ -179,6 +184,9 @@ ooco_status ooco_profile_read_calls(ooco_ctx *ctx, double *per_call_ms /*HOST*/,
  * merge).  ooco_trace_read synchronises the device and copies the stamps of the last traced call:
  *   stamps: HOST uint64 [cap_waves][4], wave index = run * num_kv_heads + kv head;
  *   waves: HOST, receives the number of decode waves of that call.
+ * A traced batch WITHOUT decode sequences stores per prefill workgroup instead (workgroup index = (tile in
+ * dispatch order * num_kv_heads + kv head) * parts + part): start, XCD * 256 + compute-unit id, 0, end; `waves`
+ * then receives the number of prefill workgroups.
  * Tracing adds waits to the kernel; never leave it on when measuring throughput. */
 ooco_status ooco_trace_read(ooco_ctx *ctx, uint64_t *stamps /*HOST*/, int64_t cap_waves, int64_t *waves /*HOST*/);
 
@@ -203,8 +211,9 @@ ooco_status ooco_plan(ooco_ctx *ctx, int num_seqs, const int32_t *h_seq_lens /*H
  *   decode_pieces_out: HOST int32 [decode_cap][5] = (seq, blk_begin, blk_end, slot, run): the KV
  *     block range of sequence seq that decode run `run` streams; slot = partial-result slot, or
  *     -1 when the piece covers the whole sequence and writes the output directly
- *   prefill_tiles_out: HOST int32 [prefill_cap][5] = (seq, q_row0, rows, pos0, seq_len); a tile
- *     holds up to 128 / (num_q_heads/num_kv_heads) query rows and runs once per kv head
+ *   prefill_tiles_out: HOST int32 [prefill_cap][5] = (seq, q_row0, rows, pos0, seq_len), in the order in which
+ *     the tiles are dispatched; a tile holds up to 128 / (num_q_heads/num_kv_heads) query rows (256 / ... in
+ *     the eight-wave kernel) and runs once per kv head
  *   counts: HOST int64 [6] = (decode pieces, prefill tiles, static decode runs, partial-result
  *     slots, dynamically fetched tail runs, parts each prefill tile's key range is cut into);
  *     runs are numbered static first, then tail

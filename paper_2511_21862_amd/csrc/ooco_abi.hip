@@ -84,6 +84,7 @@ struct PlanGeometry {
     int64_t lean_opt = 0;       // mixed batches: register-lean kernels (see HostPlan::lean)
     int64_t fused = 0;          // batches with both kinds of work run in the one-launch mixed kernel
     int64_t dec_cus_opt = 0;    // mixed kernel: compute units per XCD that decode; 0 = automatic
+    int64_t pf_table_opt = 1;   // batches of at most kSortedTiles prefill tiles: tiles dispatched longest first across chunks
     uint16_t xcd_cw[kXcds] = {};   // cumulative XCD weights of the static runs; zeros = equal runs
 };
 
@@ -94,7 +95,8 @@ struct HostPlan {
     // prefill chunks, heaviest (most keys) first: pf[0..P] = query tiles before chunk k of that
     // order, pf[P+1+k] = sequence index of chunk k
     const int32_t *pf = nullptr;
-    size_t pf_size = 0;              // 2 * num_pf + 1
+    size_t pf_size = 0;              // 2 * num_pf + 1, + n_tiles with the tile list (pf_table)
+    int32_t pf_table = 0;            // pf goes on with one entry per tile in dispatch order: (k << 20) | tile of chunk k
     int32_t num_pf = 0;
     int32_t dec_blocks = 0, static_blocks = 0, static_runs = 0, tail_runs = 0;   // in line units
     int32_t piece_pad = 0;
@@ -128,16 +130,16 @@ bool xcd_weights_to_cw(const int32_t *w, uint16_t *cw)
 size_t slot_bytes(const PlanGeometry &geo) { return (size_t)geo.Hq * (geo.hd + 2) * sizeof(float); }
 
 // Where build_plan puts the plan's arrays: room for `seqs_cap` sequences, i.e. dcum [seqs_cap + 1],
-// pf [2 * seqs_cap + 1] and a work array order [seqs_cap].  build_plan itself allocates nothing.
+// pf [2 * seqs_cap + 1 + kSortedTiles] and a work array order [seqs_cap].  build_plan itself allocates nothing.
 struct PlanStorage {
     int32_t *dcum, *pf, *order;
     size_t seqs_cap;
 };
 PlanStorage carve_storage(int32_t *base, size_t seqs_cap)
 {
-    return PlanStorage{base, base + (seqs_cap + 1), base + (seqs_cap + 1) + (2 * seqs_cap + 1), seqs_cap};
+    return PlanStorage{base, base + (seqs_cap + 1), base + (seqs_cap + 1) + (2 * seqs_cap + 1 + kSortedTiles), seqs_cap};
 }
-size_t storage_ints(size_t seqs_cap) { return (seqs_cap + 1) + (2 * seqs_cap + 1) + seqs_cap; }
+constexpr size_t storage_ints(size_t seqs_cap) { return (seqs_cap + 1) + (2 * seqs_cap + 1 + kSortedTiles) + seqs_cap; }
 
 // Validates the length arrays and builds the plan.  Pure host code, no allocation.
 ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_seq_lens,
@@ -243,6 +245,28 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
         const int64_t ql = (int64_t)h_query_start_loc[order[k] + 1] - h_query_start_loc[order[k]];
         pf[k + 1] = pf[k] + (int32_t)((ql + tile_rows - 1) / tile_rows);
         pf[n_order + 1 + k] = order[k];
+    }
+    // A launch of few tiles is as long as its unluckiest compute unit is busy, and the hardware hands workgroups out
+    // in index order to whichever unit has room: the tiles of ALL chunks go out by decreasing number of 64-key
+    // steps (a chunk on a short context has fewer steps in its last tile than one on a long context in its first).
+    // (only while the longer array still travels in the kernel arguments)
+    if (geo.pf_table_opt && tiles > 0 && tiles <= kSortedTiles && 2 * n_order + 1 + (size_t)tiles <= (size_t)kInlineSeqs + 1) {
+        int32_t *const tab = pf + out.pf_size;
+        auto steps_of = [&](int32_t e) -> int64_t {
+            const int i = order[e >> 20];
+            const int64_t ql = (int64_t)h_query_start_loc[i + 1] - h_query_start_loc[i], t0 = (int64_t)(e & 0xFFFFF) * tile_rows;
+            return ((int64_t)h_ctx_lens[i] + std::min<int64_t>(ql, t0 + tile_rows) + 63) / 64;
+        };
+        size_t n = 0;
+        for (size_t k = 0; k < n_order; ++k)
+            for (int32_t t = pf[k + 1] - pf[k] - 1; t >= 0; --t) tab[n++] = (int32_t)(k << 20) | t;
+        // (ties keep the chunk order and, inside a chunk, the later tile first: entries compare as numbers)
+        std::sort(tab, tab + n, [&](int32_t x, int32_t y) {
+            const int64_t sx = steps_of(x), sy = steps_of(y);
+            return sx != sy ? sx > sy : (x >> 20) != (y >> 20) ? (x >> 20) < (y >> 20) : x > y;
+        });
+        out.pf_size += n;
+        out.pf_table = 1;
     }
 
     // ---- one launch for both kinds of work: how many compute units of every XCD decode.  The decode part is
@@ -409,6 +433,7 @@ struct ooco_ctx {
     int64_t opt_trace = 0;
     int64_t opt_rotate = 1;
     int64_t opt_pf_split = 0;
+    int64_t opt_pf_table = 1;       // few prefill tiles: dispatched by decreasing number of steps across chunks
     int opt_copy_variant = 0;       // block copy: 10 x vectors per thread + non-temporal flag, 0 = default
     int64_t opt_decode_first = 1;   // mixed batches: enqueue the decode kernel before the prefill kernel
     int64_t opt_piece_pad = 0;   // set at creation: 3 tiles of head_dim 128
@@ -620,6 +645,8 @@ ooco_status ooco_set_option(ooco_ctx *ctx, const char *name, int64_t value)
         ctx->opt_tail_blocks = value;
     else if (!strcmp(name, "prefill_split"))
         ctx->opt_pf_split = value;
+    else if (!strcmp(name, "prefill_sorted"))
+        ctx->opt_pf_table = value;
     else if (!strcmp(name, "decode_first"))
         ctx->opt_decode_first = value;
     else if (!strcmp(name, "prefill_waves")) {
@@ -711,13 +738,14 @@ ooco_status ooco_plan(ooco_ctx *ctx, int num_seqs, const int32_t *h_seq_lens, co
     geo.lean_opt = ctx->opt_lean;
     geo.fused = ctx->opt_fused && ctx->opt_overlap;
     geo.dec_cus_opt = ctx->opt_dec_cus;
+    geo.pf_table_opt = ctx->opt_pf_table;
     for (int k = 0; k < kXcds; ++k) geo.xcd_cw[k] = ctx->xcd_cw[k];
     const size_t cap = (size_t)std::max(num_seqs, 0);
     if (ctx->plan_store.size() < storage_ints(cap)) ctx->plan_store.resize(storage_ints(cap));
     ooco_status st = build_plan(geo, num_seqs, h_seq_lens, h_query_start_loc, h_ctx_lens,
                                 carve_storage(ctx->plan_store.data(), cap), ctx->plan, ctx->err);
     if (st != OOCO_OK) return st;
-    if ((size_t)num_seqs * ctx->Hkv > kCounterInts - kMixedStateInts || 3 * ((size_t)num_seqs + 1) > kPlanInts)
+    if ((size_t)num_seqs * ctx->Hkv > kCounterInts - kMixedStateInts || 3 * ((size_t)num_seqs + 1) + kSortedTiles > kPlanInts)
         return fail(ctx, OOCO_ENOMEM, "ooco_plan: %d sequences exceed the context's counter/plan buffers", num_seqs);
     ctx->plan_valid = true;
     ctx->plan_made = true;
@@ -785,16 +813,25 @@ ooco_status ooco_plan_dry_run(int num_q_heads, int num_kv_heads, int head_dim, i
             o[0] = d.seq, o[1] = d.blk_begin, o[2] = d.blk_end, o[3] = d.slot, o[4] = d.run;
         }
     if (prefill_tiles_out) {
-        int64_t n = 0;
-        for (int i = 0; i < num_seqs && n < prefill_cap; ++i) {
-            const int q0 = h_query_start_loc[i], ql = h_query_start_loc[i + 1] - q0;
-            if (ql <= 1) continue;
-            const int tile_rows = prefill_tile_rows(num_q_heads / num_kv_heads, pl.pf_waves);
-            for (int t0 = 0; t0 < ql && n < prefill_cap; t0 += tile_rows, ++n) {
-                int32_t *o = prefill_tiles_out + 5 * n;
-                o[0] = i, o[1] = q0 + t0, o[2] = std::min(tile_rows, ql - t0), o[3] = h_ctx_lens[i] + t0;
-                o[4] = h_seq_lens[i];
+        // in dispatch order, derived from the plan's arrays the way the prefill kernel derives them
+        const int tile_rows = prefill_tile_rows(num_q_heads / num_kv_heads, pl.pf_waves);
+        const int32_t *const pf = pl.pf;
+        const int P = pl.num_pf;
+        for (int64_t idx = 0; idx < pl.n_tiles && idx < prefill_cap; ++idx) {
+            int k, t;
+            if (pl.pf_table) {
+                const int32_t e = pf[2 * P + 1 + idx];
+                k = e >> 20;
+                t = e & 0xFFFFF;
+            } else {
+                k = (int)(std::upper_bound(pf, pf + P + 1, (int32_t)idx) - pf) - 1;
+                t = (pf[k + 1] - 1) - (int)idx;
             }
+            const int i = pf[P + 1 + k];
+            const int q0 = h_query_start_loc[i], ql = h_query_start_loc[i + 1] - q0, t0 = t * tile_rows;
+            int32_t *o = prefill_tiles_out + 5 * idx;
+            o[0] = i, o[1] = q0 + t0, o[2] = std::min(tile_rows, ql - t0), o[3] = h_ctx_lens[i] + t0;
+            o[4] = h_seq_lens[i];
         }
     }
     return OOCO_OK;
@@ -919,9 +956,13 @@ ooco_status ooco_attn_mixed(ooco_ctx *ctx, const void *q, const void *k_cache, c
         p.pf_ml = p.pf_acc + parts * (size_t)(32 * pl.pf_waves) * ctx->hd;
         p.pf_counters = ctx->pf_counters;
         p.pf_split = pl.pf_split;
+        p.pf_table = pl.pf_table;
     }
     // (the mixed kernel stamps once per workgroup, the decode kernel once per wave)
-    const int64_t trace_rows = pl.dec_cus > 0 && pl.n_tiles > 0 ? 2 * (int64_t)ctx->num_cus : (int64_t)pl.static_runs * ctx->Hkv;
+    // (a batch without decode work: once per prefill workgroup)
+    const int64_t trace_rows = pl.dec_cus > 0 && pl.n_tiles > 0 ? 2 * (int64_t)ctx->num_cus
+                               : pl.static_runs > 0           ? (int64_t)pl.static_runs * ctx->Hkv
+                                                              : (int64_t)pl.n_tiles * ctx->Hkv * pl.pf_split;
     const bool tracing = ctx->opt_trace && ctx->trace_d && (size_t)trace_rows <= kTraceWaves;
     p.trace = tracing ? ctx->trace_d : nullptr;
     if (tracing) ctx->trace_waves = trace_rows;
@@ -1103,7 +1144,7 @@ ooco_status ooco_attn_mixed_static(int num_q_heads, int num_kv_heads, int head_d
     geo.tail_blocks = 0;
     geo.pf_split_opt = 1;
     geo.piece_pad = default_piece_pad(head_dim);
-    int32_t store[(kInlineSeqs + 1) + (2 * kInlineSeqs + 1) + kInlineSeqs];
+    int32_t store[storage_ints(kInlineSeqs)];
     HostPlan pl;
     ooco_status st = build_plan(geo, num_seqs, h_seq_lens, h_query_start_loc, h_ctx_lens, carve_storage(store, kInlineSeqs), pl, err);
     if (st != OOCO_OK) {
@@ -1158,6 +1199,7 @@ ooco_status ooco_attn_mixed_static(int num_q_heads, int num_kv_heads, int head_d
     p.pf_ml = nullptr;
     p.pf_counters = nullptr;
     p.pf_split = 1;
+    p.pf_table = pl.pf_table;
 
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     // The array keeps whatever the last call on this GPU left: the arrival counters this call will count in

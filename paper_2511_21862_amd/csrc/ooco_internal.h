@@ -35,6 +35,7 @@ constexpr int kPrefillCols = 128;   // (row, head) query columns per four-wave p
 constexpr int kInlineSeqs = 960;    // sequences whose cumulative array fits the kernel arguments
 constexpr int kMaxPrefillSplit = 8; // parts a prefill tile's keys may be cut into
 constexpr int kPrefillSplitUnits = 8192;   // (tile, kv head) pairs up to which the split is available
+constexpr int kSortedTiles = 512;    // prefill tiles up to which the plan lists them one by one, most 64-key steps first
 constexpr int kMixedStateInts = 4096;      // ints in front of (and including) the ticket counter that the mixed kernel keeps its claims and counters in
 
 struct AttnParams {
@@ -73,6 +74,9 @@ struct AttnParams {
     float *pf_ml;
     int32_t *pf_counters;
     int32_t pf_split;
+    // 1: the prefill array continues with one entry per tile in dispatch order, (chunk of the array << 20) | tile of
+    // the chunk: tiles of all chunks ordered by their number of 64-key steps, the longest first
+    int32_t pf_table;
 };
 
 struct KernArgs {

@@ -652,10 +652,16 @@ OOCO_DEV void prefill_unit(const AttnParams &p, CumAt cum_at, const int vb)
     // the later rows of a chunk see more keys and the hardware dispatches in index order
     int seq, q_row0, rows, pos0, seq_len;
     {
-        const int chunk = __builtin_amdgcn_readfirstlane(count_le(cum_at, p.num_pf, tile_idx, lane));
-        const int t_end = cum_at(chunk + 1);
+        int chunk, t;
+        if (p.pf_table) {   // the plan lists the tiles one by one: (chunk << 20) | tile of the chunk
+            const int e = cum_at(2 * p.num_pf + 1 + min(tile_idx, p.n_tiles - 1));
+            chunk = min(max(e >> 20, 0), p.num_pf - 1);
+            t = e & 0xFFFFF;
+        } else {
+            chunk = __builtin_amdgcn_readfirstlane(count_le(cum_at, p.num_pf, tile_idx, lane));
+            t = (cum_at(chunk + 1) - 1) - tile_idx;       // reversed order inside the sequence
+        }
         seq = min(max(cum_at(p.num_pf + 1 + chunk), 0), p.num_seqs - 1);
-        const int t = (t_end - 1) - tile_idx;             // reversed order inside the sequence
         const int q0 = p.query_start_loc[seq];
         const int q_len = p.query_start_loc[seq + 1] - q0;
         const int tile_rows = max(1, COLS / g);
@@ -1083,7 +1089,18 @@ template <int HD, int NW>
 __global__ __launch_bounds__(NW * 64, 8 / NW) void prefill_kernel(const KernArgs a)
 {
     const AttnParams &p = a.p;
+    // option "trace" on a batch without decode work: per workgroup (start, XCD * 256 + compute unit id, 0, end)
+    uint64_t *const trace = (p.trace && p.static_runs == 0) ? p.trace + (int64_t)blockIdx.x * 4 : nullptr;
+    if (trace && threadIdx.x == 0) {
+        trace[0] = wall_clock64();
+        trace[1] = (__builtin_amdgcn_s_getreg((31 << 11) | 20) & 7u) * 256u + ((__builtin_amdgcn_s_getreg((31 << 11) | 4) >> 8) & 255u);
+        trace[2] = 0;
+    }
     prefill_unit<HD, NW, true>(p, [&](int idx) -> int { return p.cum_dev ? p.cum_dev[idx] : a.cum[idx]; }, (int)blockIdx.x);
+    if (trace) {
+        __syncthreads();
+        if (threadIdx.x == 0) trace[3] = wall_clock64();
+    }
 }
 
 // Eight waves, 256 query columns, no software pipeline, at most 176 registers per wave: the prefill kernel of

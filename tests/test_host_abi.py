@@ -229,6 +229,35 @@ def test_prefill_tiles_are_split_only_when_the_batch_cannot_occupy_the_gpu():
     assert dry([100, 200], [0, 1, 2], [99, 199])["prefill_parts"] == 1
 
 
+def test_few_prefill_tiles_are_dispatched_longest_first_across_chunks():
+    # up to 512 tiles: one list entry per tile, by decreasing number of 64-key steps whatever the chunk; ties keep
+    # the chunk order (longest sequence first) and the later tile of a chunk first
+    ql = np.array([512, 1, 300, 512, 33, 1, 512, 64, 2], np.int32)
+    cx = np.array([1662, 4000, 0, 175, 90, 17, 1781, 700, 5], np.int32)
+    qsl = np.zeros(len(ql) + 1, np.int32)
+    qsl[1:] = np.cumsum(ql)
+    t = dry(cx + ql, qsl, cx)["prefill_tiles"]
+    want = sum(-(-int(q) // 32) for q in ql if q > 1)
+    assert len(t) == want and len({(int(r[0]), int(r[1])) for r in t}) == want          # every tile once
+    steps = (t[:, 3] + t[:, 2] + 63) // 64
+    assert (np.diff(steps) <= 0).all() and steps[0] == (1781 + 512 + 63) // 64
+    assert len(np.unique(t[:len(t) // 2, 0])) > 1                                          # chunks interleave
+    for a, b2, sa, sb in zip(t[:-1], t[1:], steps[:-1], steps[1:]):
+        if sa == sb and a[0] != b2[0]:
+            assert (cx + ql)[a[0]] >= (cx + ql)[b2[0]]
+        if sa == sb and a[0] == b2[0]:
+            assert a[1] > b2[1]
+    # more than 512 tiles: chunk by chunk, longest sequence first, later tiles first
+    ql2, cx2 = np.array([8192, 8192, 512], np.int32), np.array([100, 5000, 70000], np.int32)
+    qsl2 = np.zeros(4, np.int32)
+    qsl2[1:] = np.cumsum(ql2)
+    t2 = dry(cx2 + ql2, qsl2, cx2)["prefill_tiles"]
+    assert len(t2) == 256 + 256 + 16
+    assert (t2[:16, 0] == 2).all() and (t2[16:272, 0] == 1).all() and (t2[272:, 0] == 0).all()
+    for i in (0, 1, 2):
+        assert (np.diff(t2[t2[:, 0] == i][:, 1]) < 0).all()
+
+
 def test_empty_batch_plans_to_nothing():
     plan = dry(np.zeros(0, np.int32), np.zeros(1, np.int32), np.zeros(0, np.int32), num_seqs=0)
     assert len(plan["decode_pieces"]) == 0 and len(plan["prefill_tiles"]) == 0
