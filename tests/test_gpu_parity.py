@@ -106,6 +106,20 @@ def test_prefill_tiles_split_along_the_context_agree(split):
         assert np.array_equal(first, again)
 
 
+@pytest.mark.parametrize("opts", [{}, {"prefill_sorted": 0}, {"prefill_split": 3}, {"prefill_waves": 8}, {"mixed_lean": 2},
+                                  {"mixed_fused": 1}, {"overlap": 0}],
+                         ids=lambda o: "-".join(f"{k}{v}" for k, v in o.items()) or "default")
+def test_tiles_of_several_chunks_interleave(opts):
+    # few tiles: the plan lists them one by one, longest first across chunks (the tiles of the chunk on the long
+    # context, then alternately the others'); same results whatever the order and the kernel
+    say(f"case: several chunks, tile list, {opts}")
+    b = W.build_batch(Hq=32, Hkv=8, hd=128, q_lens=[100, 1, 257, 1, 64, 33, 1, 2], ctx_lens=[900, 700, 10, 64, 411, 0, 2000, 77],
+                      num_blocks=420, seed=85, poison=True)
+    assert_parity(run_gpu(b, options=opts), oracle(b), f"several chunks {opts}")
+    b = W.build_batch(Hq=8, Hkv=2, hd=64, q_lens=[70, 90, 1, 200], ctx_lens=[300, 0, 100, 150], num_blocks=90, seed=86, poison=True)
+    assert_parity(run_gpu(b, options=opts), oracle(b), f"several chunks {opts}, head_dim 64")
+
+
 def test_repeated_calls_reuse_counters_and_workspace():
     b = W.build_batch(Hq=8, Hkv=2, hd=128, q_lens=[1, 1, 1], ctx_lens=[700, 90, 300], num_blocks=80, seed=78)
     ref = oracle(b)
