@@ -72,8 +72,7 @@ typedef enum {
     OOCO_EINVAL = -1,   /* bad argument value (null pointer, negative size, bad option) */
     OOCO_ESHAPE = -2,   /* inconsistent shapes / lengths / unsupported head geometry    */
     OOCO_ENOMEM = -3,   /* allocation failed or workspace too small                     */
-    OOCO_EHIP = -4,     /* a HIP runtime call or kernel launch failed                   */
-    OOCO_ENOTIMPL = -5
+    OOCO_EHIP = -4      /* a HIP runtime call or kernel launch failed                   */
 } ooco_status;
 
 /* Creates a context for one attention-layer geometry on the current HIP device.
@@ -89,8 +88,9 @@ ooco_status ooco_ctx_create(ooco_ctx **out, int num_q_heads, int num_kv_heads, i
                             float softmax_scale, void *workspace /*DEVICE or NULL*/,
                             size_t workspace_bytes);
 
-/* Frees the context and whatever it allocated (never the caller's buffers).  Synchronises with
- * the work the context has enqueued.  NULL is accepted. */
+/* Frees the context and whatever it allocated (never the caller's buffers).  Waits for the work the
+ * context has enqueued: the streams its calls were given (up to four different ones are remembered,
+ * beyond that the whole device) and its own side stream; those streams must still exist.  NULL is accepted. */
 ooco_status ooco_ctx_destroy(ooco_ctx *ctx);
 
 /* Message of the last failure on this context (or, with ctx == NULL, of the calling thread's
@@ -181,7 +181,8 @@ ooco_status ooco_profile_read_calls(ooco_ctx *ctx, double *per_call_ms /*HOST*/,
 /* Wave-level trace of the decode kernel, for tuning.  With option "trace" = 1 every decode wave of
  * the following ooco_attn_mixed calls stores four device time stamps (constant 100 MHz clock):
  * wave start, first K/V tiles arrived, end of KV streaming, wave end (after partial results and
- * merge).  ooco_trace_read synchronises the device and copies the stamps of the last traced call:
+ * merge).  ooco_trace_read waits for the streams the context's calls were given and copies the stamps of the last
+ * traced call:
  *   stamps: HOST uint64 [cap_waves][4], wave index = run * num_kv_heads + kv head;
  *   waves: HOST, receives the number of decode waves of that call.
  * A traced batch WITHOUT decode sequences stores per prefill workgroup instead (workgroup index = (tile in

@@ -14,9 +14,8 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libooco.so")
 
-OOCO_OK, OOCO_EINVAL, OOCO_ESHAPE, OOCO_ENOMEM, OOCO_EHIP, OOCO_ENOTIMPL = 0, -1, -2, -3, -4, -5
-_STATUS_NAMES = {0: "OOCO_OK", -1: "OOCO_EINVAL", -2: "OOCO_ESHAPE", -3: "OOCO_ENOMEM", -4: "OOCO_EHIP",
-                 -5: "OOCO_ENOTIMPL"}
+OOCO_OK, OOCO_EINVAL, OOCO_ESHAPE, OOCO_ENOMEM, OOCO_EHIP = 0, -1, -2, -3, -4
+_STATUS_NAMES = {0: "OOCO_OK", -1: "OOCO_EINVAL", -2: "OOCO_ESHAPE", -3: "OOCO_ENOMEM", -4: "OOCO_EHIP"}
 
 EXPORTS = ["ooco_ctx_create", "ooco_ctx_destroy", "ooco_last_error", "ooco_set_option", "ooco_plan",
            "ooco_plan_dry_run", "ooco_plan_info", "ooco_plan_kernels", "ooco_profile_read", "ooco_profile_read_calls", "ooco_trace_read", "ooco_attn_mixed", "ooco_attn_mixed_static", "ooco_kv_block_copy", "ooco_kv_append", "ooco_predict_latency", "ooco_mix_decoding_select",

@@ -409,6 +409,35 @@ struct ooco_ctx {
     size_t ws_bytes = 0;
     bool own_ws = false;
 
+    // streams that calls have put work on which uses the context's memory (workspace, counters, plan, sort buffer):
+    // what ooco_ctx_destroy and ooco_trace_read wait for.  More than kMaxStreams different ones: the whole device.
+    static constexpr int kMaxStreams = 4;
+    hipStream_t used_streams[kMaxStreams] = {};
+    int n_used_streams = 0;
+    bool many_streams = false;
+    hipStream_t last_stream = nullptr;
+    void note_stream(hipStream_t st)
+    {
+        last_stream = st;
+        for (int i = 0; i < n_used_streams; ++i)
+            if (used_streams[i] == st) return;
+        if (n_used_streams < kMaxStreams)
+            used_streams[n_used_streams++] = st;
+        else
+            many_streams = true;
+    }
+    // Waits for everything the context has enqueued (its side stream is joined into the caller's stream by every call).
+    hipError_t wait_for_own_work()
+    {
+        if (many_streams) return hipDeviceSynchronize();
+        hipError_t first = hipSuccess;
+        for (int i = 0; i < n_used_streams; ++i) {
+            const hipError_t e = hipStreamSynchronize(used_streams[i]);
+            if (first == hipSuccess) first = e;
+        }
+        return first;
+    }
+
     int32_t *plan_h = nullptr;   // pinned host staging for batches beyond kInlineSeqs sequences
     int32_t *plan_d = nullptr;   // device copy of the two cumulative arrays
     int32_t *counters = nullptr; // arrival counters [kCounterInts], zero between calls
@@ -567,7 +596,8 @@ ooco_status ooco_ctx_destroy(ooco_ctx *ctx)
 {
     if (!ctx) return OOCO_OK;
     if (ctx->upload_pending) (void)hipEventSynchronize(ctx->upload_done);
-    (void)hipDeviceSynchronize();
+    (void)ctx->wait_for_own_work();
+    if (ctx->side_stream) (void)hipStreamSynchronize(ctx->side_stream);
     if (ctx->upload_done) (void)hipEventDestroy(ctx->upload_done);
     if (ctx->fork_ev) (void)hipEventDestroy(ctx->fork_ev);
     if (ctx->join_ev) (void)hipEventDestroy(ctx->join_ev);
@@ -589,7 +619,7 @@ ooco_status ooco_trace_read(ooco_ctx *ctx, uint64_t *stamps, int64_t cap_waves, 
 {
     if (!ctx) return OOCO_EINVAL;
     if (!ctx->trace_d) return fail(ctx, OOCO_EINVAL, "ooco_trace_read: option \"trace\" was never enabled");
-    hipError_t e = hipDeviceSynchronize();
+    hipError_t e = ctx->wait_for_own_work();
     const int64_t n = std::min<int64_t>(cap_waves, ctx->trace_waves);
     if (e == hipSuccess && stamps && n > 0)
         e = hipMemcpy(stamps, ctx->trace_d, (size_t)n * 4 * sizeof(uint64_t), hipMemcpyDeviceToHost);
@@ -893,6 +923,7 @@ ooco_status ooco_attn_mixed(ooco_ctx *ctx, const void *q, const void *k_cache, c
     if (!q || !k_cache || !v_cache || !block_tables || !seq_lens || !query_start_loc || !ctx_lens || !out)
         return fail(ctx, OOCO_EINVAL, "ooco_attn_mixed: NULL pointer argument");
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    ctx->note_stream(s);
 
     if (!ctx->plan_valid) {
         // No host plan for this batch: fetch the lengths and plan here (costs one stream sync).
@@ -1230,6 +1261,7 @@ ooco_status ooco_kv_block_copy(ooco_ctx *ctx, const void *k_src, const void *v_s
         return fail(ctx, OOCO_EINVAL, "ooco_kv_block_copy: num_pairs=%lld too large", (long long)num_pairs);
     const int64_t block_bytes = (int64_t)ctx->Hkv * ctx->BS * ctx->hd * 2;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    ctx->note_stream(s);
     hipError_t e = hipSuccess;
     // Large copies take their pairs in order of destination id (sorted on the device into a buffer of the context,
     // which grows on demand -- never while the stream is being captured, a captured copy keeps the caller's order).

@@ -221,9 +221,9 @@ OOCO_DEV int count_le(CumAt cum_at, int n, int x, int lane)
 //   V operand, group nb: 8 B at tile offset ((16nb + col)*16 + 4kq)*2   (dim 16nb+col, tokens 4kq..+4)
 //   O^T result reg r:    dim 16nb + 4kq + r, head col
 // One K and one V register set: the K loads of block j+1 are issued right after the QK MFMAs of
-// block j have consumed the K registers, the V loads of block j+1 right after the PV MFMAs;
-// memory latency is covered by several resident waves per SIMD (the kernel stays under 128
-// VGPRs) rather than by a second register set.
+// block j have consumed the K registers, the V loads of block j+1 right after the PV MFMAs, so a
+// wave always has one block's tiles (8 KiB with head_dim 128) on their way; a few such waves per
+// compute unit keep HBM busy, and no second register set is needed.
 //
 // A piece that covers its whole sequence normalises and stores bf16 output.  Any other piece
 // stores (acc, m, l) in fp32 into partial slot k + seq, then bumps the arrival counter of
