@@ -26,8 +26,9 @@ def run_static(b):
 
 def check(b, what):
     got = run_static(b)
-    # the existing entry point with the same planning choices (prefill tiles not split): same run layout, same bits
-    want = run_gpu(b, options={"prefill_split": 1})
+    # the existing entry point with the same planning choices (prefill tiles not split, the stand-alone pair of
+    # kernels): same run layout, same bits
+    want = run_gpu(b, options={"prefill_split": 1, "mixed_lean": 0})
     g, w = W.bf16_bits_to_f32(got).astype(np.float64), W.bf16_bits_to_f32(want).astype(np.float64)
     d = np.abs(g - w)
     say(f"  {what}: vs ooco_attn_mixed max-abs {d.max():.3g} mean-abs {d.mean():.3g}, bit-identical {np.array_equal(got, want)}")
