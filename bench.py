@@ -49,6 +49,10 @@ def make_workload(name):
         return W.config3(device="cuda"), "decode"
     if name == "cfg3-prefill":
         return W.config3(device="cuda", n_decode=0), "prefill"
+    if name == "cfg3-decode":       # the decode sequences of config 3 without its chunks
+        return W.config3(device="cuda", decode_only=True), "decode"
+    if name == "cfg5-decode":       # the decode sequences of config 5 without its chunks
+        return W.config5(device="cuda", n_prefill=0), "decode"
     if name == "cfg4":
         return W.config4(device="cuda"), "decode"
     if name == "cfg5":

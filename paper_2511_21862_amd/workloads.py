@@ -379,18 +379,21 @@ def config2(device: str = "cuda", value_std: float = 1.0 / np.sqrt(128.0), num_s
 
 
 def config3(device: str = "cuda", n_prefill: int = 8, n_decode: int = 128, chunk: int = 512, seed: int = 3,
-            Hq: int = 32, Hkv: int = 8) -> Batch:
+            Hq: int = 32, Hkv: int = 8, decode_only: bool = False) -> Batch:
     """Co-located mixed batch: prefill chunks on prior context U[0,2048] first, then
-    decode sequences with lognormal lengths (median 2048, sigma 0.8, clipped to [128, 8192])."""
+    decode sequences with lognormal lengths (median 2048, sigma 0.8, clipped to [128, 8192]).
+    `decode_only`: the same decode sequences without the chunks (the lengths are drawn as for the mixed batch)."""
     rng = np.random.default_rng(seed)
     pctx = uniform_lengths(rng, n_prefill, 0, 2048)
     dseq = lognormal_lengths(rng, n_decode, 2048, 0.8, 128, 8192)
+    if decode_only:
+        n_prefill, pctx = 0, pctx[:0]
     ql = np.concatenate([np.full(n_prefill, chunk, np.int32), np.ones(n_decode, np.int32)])
     ctx = np.concatenate([pctx, dseq - 1]).astype(np.int32)
     need = int(_blocks_needed(ctx + ql, 16).sum())
     nblk = max(32768, int(1.25 * need))
     return build_batch(Hq=Hq, Hkv=Hkv, hd=128, q_lens=ql, ctx_lens=ctx, num_blocks=nblk, seed=seed,
-                       device=device, rng=rng, name="cfg3-mixed")
+                       device=device, rng=rng, name="cfg3-decode-part" if decode_only else "cfg3-mixed")
 
 
 def config4(device: str = "cuda", n_decode: int = 512, n_victims: int = 64, seed: int = 4,
