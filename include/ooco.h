@@ -134,6 +134,20 @@ const char *ooco_last_error(const ooco_ctx *ctx);
  *                         arguments); 0 or more tiles: chunk by chunk, longest sequence first, the later tiles of
  *                         a chunk first.  Measured on MI355X, 8 chunks of 512 rows on 175..1781 cached tokens:
  *                         the span of the workgroups 94..98 -> 89..92 us.
+ * Batches that hold both prefill chunks and decode sequences (take effect at the next ooco_plan):
+ *   "mixed_lean"          the register-lean pair of kernels (head_dim 128): prefill workgroups of eight waves
+ *                         (256 query columns, at most 176 registers per wave) beside decode waves of 144 registers,
+ *                         four per compute unit, so that a SIMD holds two prefill waves and a decode wave at once.
+ *                         1 (default) = automatic: when the prefill part gives every compute unit at least one
+ *                         eight-wave workgroup; 0 = never (the stand-alone kernels side by side); 2 = whenever the
+ *                         batch holds both kinds of work.
+ *   "prefill_waves"       waves per prefill workgroup: 4 (128 query columns per staged K/V tile), 8 (256), or
+ *                         0 (default) = 4, and 8 where "mixed_lean" applies.  Other values -> OOCO_EINVAL.
+ *   "mixed_fused"         0 (default) / 1: 1 = both kinds of work in ONE launch of a persistent kernel in which a
+ *                         compute unit runs either decode waves or prefill workgroups (with "overlap" on).  Slower
+ *                         than the two kernels side by side at every split measured; kept for measurements.
+ *   "mixed_dec_cus"       with "mixed_fused": compute units per XCD that decode (the others prefill); 0 (default) =
+ *                         from the batch's bytes and FLOPs; 99 = every unit runs both kinds.
  * Immediate options:
  *   "plan_persistent"  0/1 (default 0): 0 = a plan made by ooco_plan serves exactly one ooco_attn_mixed and is
  *                then used up (a later call without a new plan plans by itself from the device arrays), so that
