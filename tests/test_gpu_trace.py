@@ -1,0 +1,64 @@
+"""Option "trace" on the GPU: the decode waves' and the prefill workgroups' own time stamps (ooco_trace_read) are
+complete and ordered, and tracing changes no output bit."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2511_21862_amd import binding as B
+from paper_2511_21862_amd import workloads as W
+
+from gpu_util import device_meta, run_gpu, say
+
+pytestmark = pytest.mark.gpu
+
+
+def traced(b, options=None):
+    """(output bits of a traced call, stamps, plan info) of one batch."""
+    d = W.to_device(b)
+    bt, sl, qsl, cl = device_meta(b)
+    out = torch.full((b.total_q, b.Hq, b.hd), float("nan"), dtype=torch.bfloat16, device="cuda")
+    with B.Context(b.Hq, b.Hkv, b.hd, b.BS, b.num_blocks, b.max_blocks_per_seq) as ctx:
+        for k, v in (options or {}).items():
+            ctx.set_option(k, v)
+        ctx.set_option("trace", 1)
+        ctx.plan(b.seq_lens, b.query_start_loc, b.ctx_lens)
+        info = ctx.plan_info()
+        ctx.attn_mixed(d.q, d.k_cache, d.v_cache, bt, sl, qsl, cl, out)
+        stamps = ctx.trace_read()
+    return out.view(torch.int16).cpu().numpy().view(np.uint16), stamps, info
+
+
+def test_decode_waves_leave_ordered_stamps_and_the_output_is_unchanged():
+    rng = np.random.default_rng(11)
+    lens = rng.integers(200, 6000, size=24).astype(np.int32)
+    b = W.build_batch(Hq=32, Hkv=8, hd=128, q_lens=np.ones(24, np.int32), ctx_lens=lens - 1,
+                      num_blocks=int(((lens + 15) // 16).sum()) + 9, seed=11, poison=True)
+    say("case: trace of a decode batch")
+    got, t, info = traced(b)
+    assert np.array_equal(got, run_gpu(b))
+    assert len(t) == info["decode_waves"] * b.Hkv and len(t) > 0
+    t = t.astype(np.int64)
+    # wave start <= first tiles arrived <= end of streaming <= wave end, all within a few milliseconds (100 MHz clock)
+    assert (t[:, 0] > 0).all()
+    assert (t[:, 0] <= t[:, 1]).all() and (t[:, 1] <= t[:, 2]).all() and (t[:, 2] <= t[:, 3]).all()
+    assert t[:, 3].max() - t[:, 0].min() < 100 * 5000
+    say(f"  {len(t)} waves, kernel span {(t[:, 3].max() - t[:, 0].min()) / 100:.1f} us")
+
+
+@pytest.mark.parametrize("opts", [{}, {"prefill_split": 2}, {"prefill_waves": 8}], ids=["default", "split2", "8waves"])
+def test_prefill_workgroups_leave_stamps_and_the_output_is_unchanged(opts):
+    b = W.build_batch(Hq=32, Hkv=8, hd=128, q_lens=[300, 64, 513], ctx_lens=[900, 0, 2000], num_blocks=260, seed=12,
+                      poison=True)
+    say(f"case: trace of a prefill-only batch, {opts}")
+    got, t, info = traced(b, opts)
+    assert np.array_equal(got, run_gpu(b, options=opts))
+    assert len(t) == info["prefill_tiles"] * b.Hkv * info["prefill_parts"] and len(t) > 0
+    t = t.astype(np.int64)
+    assert (t[:, 0] > 0).all() and (t[:, 0] <= t[:, 3]).all()
+    assert t[:, 3].max() - t[:, 0].min() < 100 * 5000
+    xcd, cu = t[:, 1] >> 8, t[:, 1] & 255
+    assert ((xcd >= 0) & (xcd < 8)).all() and (t[:, 2] == 0).all()
+    # the hardware deals a launch's workgroups to the XCDs in turn (starting wherever the last launch stopped), so
+    # with eight kv heads all tiles of a kv head meet in one L2
+    assert len(np.unique((xcd - np.arange(len(t))) % 8)) == 1
+    say(f"  {len(t)} workgroups on {len(np.unique(t[:, 1]))} compute units, span {(t[:, 3].max() - t[:, 0].min()) / 100:.1f} us")
