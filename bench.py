@@ -59,6 +59,12 @@ def make_workload(name):
         return W.config5(device="cuda"), "decode"
     if name == "cfg5-prefill":
         return W.config5(device="cuda", n_decode=0, num_blocks=4096), "prefill"
+    if name.startswith("mix-"):     # mix-<chunks>x<rows>+<decodes>: config 3's recipe with other proportions
+        chunks, rest = name[4:].split("x")
+        rows, ndec = rest.split("+")
+        b = W.config3(device="cuda", n_prefill=int(chunks), chunk=int(rows), n_decode=int(ndec))
+        b.name = name
+        return b, "decode"
     if name.startswith("shape-"):   # shape-<Hq>-<Hkv>-<hd>: 256 decode sequences of 512-4096 tokens with another head shape
         Hq, Hkv, hd = (int(x) for x in name.split("-")[1:4])
         rng = np.random.default_rng(77)

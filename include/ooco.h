@@ -139,8 +139,10 @@ const char *ooco_last_error(const ooco_ctx *ctx);
  *                         (256 query columns, at most 176 registers per wave) beside decode waves of 144 registers,
  *                         four per compute unit, so that a SIMD holds two prefill waves and a decode wave at once.
  *                         1 (default) = automatic: when the prefill part gives every compute unit at least one
- *                         eight-wave workgroup; 0 = never (the stand-alone kernels side by side); 2 = whenever the
- *                         batch holds both kinds of work.
+ *                         eight-wave workgroup and, by the batch's FLOPs and bytes, would by itself take between
+ *                         0.35 and 4 times as long as the decode part (a shorter one does not repay the lean
+ *                         decode kernel's 3 %, a longer one not the lean prefill kernel's 5 %); 0 = never (the
+ *                         stand-alone kernels side by side); 2 = whenever the batch holds both kinds of work.
  *   "prefill_waves"       waves per prefill workgroup: 4 (128 query columns per staged K/V tile), 8 (256), or
  *                         0 (default) = 4, and 8 where "mixed_lean" applies.  Other values -> OOCO_EINVAL.
  *   "mixed_fused"         0 (default) / 1: 1 = both kinds of work in ONE launch of a persistent kernel in which a
@@ -221,7 +223,8 @@ ooco_status ooco_plan(ooco_ctx *ctx, int num_seqs, const int32_t *h_seq_lens /*H
 
 /* The planner of ooco_plan as a pure HOST function (no context, no device): validates the length
  * arrays exactly as ooco_plan does and lists the work the kernels will derive from the plan for
- * the given geometry, CU count, workspace size and decode run options.  For schedulers that
+ * the given geometry, CU count, workspace size and decode run options (every other option at a context's
+ * default).  For schedulers that
  * want to know the split of a batch in advance, and for testing the planner without a GPU.
  *   decode_pieces_out: HOST int32 [decode_cap][5] = (seq, blk_begin, blk_end, slot, run): the KV
  *     block range of sequence seq that decode run `run` streams; slot = partial-result slot, or

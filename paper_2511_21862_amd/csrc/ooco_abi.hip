@@ -177,19 +177,32 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
     // of 128, which halves the traffic from L2 into the compute units.  Measured on MI355X it is no faster (that
     // traffic is not what bounds the kernel) and its 220-register waves leave no room for decode waves beside
     // them, so four waves are the default; eight (head_dim 128 only) stay selectable.
-    // The register-lean pair for batches with both kinds of work (lean_opt 1 = when every compute unit gets at
-    // least one eight-wave prefill workgroup, 2 = whenever the batch is mixed).  Measured on MI355X: the long-context
-    // mixed batch 1.75 -> 1.63 ms, the short one 0.288 -> 0.274 ms.
+    // The register-lean pair for batches with both kinds of work (lean_opt 2 = whenever the batch is mixed; 1 = when
+    // it pays: every compute unit gets at least one eight-wave prefill workgroup, and the prefill part, by itself,
+    // would take between 0.35 and 4 times as long as the decode part -- estimated from the batch's FLOPs and bytes
+    // at 1.05 PFLOP/s and 6.8 TB/s).  Measured on MI355X, 32/8 heads, 128 decode sequences of 1.4 GB in all: beside
+    // 2 x 2048 rows 319 -> 291 us, beside 8 x 512 rows 286 -> 270 us, but beside 4 x 512 rows 257 -> 263 us and beside
+    // 1 x 512 rows 242 -> 266 us (alone the lean decode kernel is 3 % slower than the stand-alone one, which a short
+    // prefill part does not repay; alone the lean prefill kernel is 5 % slower, so a batch that is nearly all prefill
+    // keeps the stand-alone pair too); the long-context batch of 64/8 heads 1.75 -> 1.62 ms.
     bool lean = false;
     if (geo.lean_opt && geo.hd == 128 && !geo.fused && num_seqs > 0) {
         const int rows8 = prefill_tile_rows(geo.Hq / geo.Hkv, 8);
-        int64_t n_dec = 0, tiles8 = 0;
+        int64_t n_dec = 0, tiles8 = 0, dec_blk = 0;
+        double pairs = 0.0;
         for (int i = 0; i < num_seqs; ++i) {
             const int64_t ql = (int64_t)h_query_start_loc[i + 1] - h_query_start_loc[i];
             n_dec += ql == 1;
-            if (ql > 1) tiles8 += (ql + rows8 - 1) / rows8;
+            if (ql == 1) dec_blk += ((int64_t)h_seq_lens[i] + BS - 1) / BS;
+            if (ql > 1) {
+                tiles8 += (ql + rows8 - 1) / rows8;
+                pairs += (double)ql * (double)h_ctx_lens[i] + (double)ql * (double)(ql + 1) / 2.0;
+            }
         }
-        lean = n_dec > 0 && tiles8 > 0 && (geo.lean_opt >= 2 || tiles8 * geo.Hkv >= (int64_t)geo.num_cus);
+        const double t_pf = 4.0 * geo.Hq * geo.hd * pairs / 1.05e15;
+        const double t_dec = (double)dec_blk * BS * 2.0 * geo.Hkv * geo.hd * 2.0 / 6.8e12;
+        const bool pays = tiles8 * geo.Hkv >= (int64_t)geo.num_cus && t_pf >= 0.35 * t_dec && t_pf <= 4.0 * t_dec;
+        lean = n_dec > 0 && tiles8 > 0 && (geo.lean_opt >= 2 || pays);
     }
     out.lean = lean;
     const int pf_waves = geo.hd == 128 && (geo.pf_waves_opt == 8 || lean) ? 8 : 4;
@@ -814,6 +827,7 @@ ooco_status ooco_plan_dry_run(int num_q_heads, int num_kv_heads, int head_dim, i
         geo.tail_pct = decode_tail_pct;
         geo.tail_blocks = decode_tail_blocks;
         geo.pf_split_opt = prefill_split;
+        geo.lean_opt = 1;   // (the default of a context)
         geo.piece_pad = decode_piece_pad < 0 ? default_piece_pad(head_dim) : decode_piece_pad;
         if (xcd_weights && !xcd_weights_to_cw(xcd_weights, geo.xcd_cw)) {
             snprintf(err, sizeof err, "ooco_plan_dry_run: xcd_weights needs eight values in 1..255 that differ by at most 4x");

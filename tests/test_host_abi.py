@@ -258,6 +258,28 @@ def test_few_prefill_tiles_are_dispatched_longest_first_across_chunks():
         assert (np.diff(t2[t2[:, 0] == i][:, 1]) < 0).all()
 
 
+def test_lean_pair_is_planned_only_where_the_prefill_part_weighs_enough():
+    # the eight-wave prefill workgroups of the register-lean pair show in the dry run as tiles of 256 / g query rows
+    # (g = 4: 64) instead of 128 / g; the pair is planned when every compute unit gets such a workgroup and the prefill
+    # part's estimated time is 0.35 .. 4 times the decode part's
+    rng = np.random.default_rng(3)
+    dec = rng.integers(1500, 4000, size=128).astype(np.int32)          # about 1.4 GB of K/V
+
+    def tile_rows(n_chunks, chunk, n_dec):
+        ql = np.r_[np.full(n_chunks, chunk), np.ones(n_dec, int)].astype(np.int32)
+        cx = np.r_[np.full(n_chunks, 1000), dec[:n_dec] - 1].astype(np.int32)
+        qsl = np.zeros(len(ql) + 1, np.int32)
+        qsl[1:] = np.cumsum(ql)
+        return int(dry(cx + ql, qsl, cx)["prefill_tiles"][:, 2].max())
+
+    assert tile_rows(8, 512, 128) == 64            # config 3's proportions
+    assert tile_rows(2, 2048, 128) == 64
+    assert tile_rows(4, 512, 128) == 32            # too little prefill work beside this much decode
+    assert tile_rows(16, 128, 128) == 32
+    assert tile_rows(8, 2048, 16) == 32            # prefill-dominated: the stand-alone kernels
+    assert tile_rows(8, 512, 0) == 32 and tile_rows(1, 512, 128) == 32
+
+
 def test_empty_batch_plans_to_nothing():
     plan = dry(np.zeros(0, np.int32), np.zeros(1, np.int32), np.zeros(0, np.int32), num_seqs=0)
     assert len(plan["decode_pieces"]) == 0 and len(plan["prefill_tiles"]) == 0
