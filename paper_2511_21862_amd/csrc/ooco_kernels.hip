@@ -1299,24 +1299,45 @@ __global__ __launch_bounds__(kAppendThreads) void kv_append_kernel(const uint16_
     const int w = blockIdx.x / parts;
     const int part = blockIdx.x - w * parts;
     auto g_at = [&](int idx) -> int { return query_start_loc[idx] / kBlockSize + 2 * idx; };
-    int seq;
+    int seq, q0, q_len, ctx;
     if (num_seqs <= 4 * 64) {
         // up to 256 sequences: the four 64-lane looks are independent loads (one memory round trip), where
-        // count_le would wait for each before starting the next
-        int cnt = 0;
+        // count_le would wait for each before starting the next; the same round trip brings the lengths of all
+        // sequences (lane l of look p holds query_start_loc[64p + l + 1] and ctx_lens[64p + l]), so that the found
+        // sequence's own values are a lane read away instead of a second round trip
+        int cnt = 0, qv[4], cv[4];
+        const int qs0 = query_start_loc[0];   // (0 by the arrays' contract; read in the same round trip all the same)
 #pragma unroll
         for (int pass = 0; pass < 4; ++pass) {
             const int idx = 1 + 64 * pass + lane;
-            const int v = idx <= num_seqs ? g_at(idx) : 0x7FFFFFFF;
+            qv[pass] = idx <= num_seqs ? query_start_loc[idx] : 0x7FFFFFFF;
+            cv[pass] = idx <= num_seqs ? ctx_lens[idx - 1] : 0;
+        }
+#pragma unroll
+        for (int pass = 0; pass < 4; ++pass) {
+            const int idx = 1 + 64 * pass + lane;
+            const int v = idx <= num_seqs ? qv[pass] / kBlockSize + 2 * idx : 0x7FFFFFFF;
             cnt += __popcll(__ballot(v <= w));
         }
-        seq = cnt;
+        seq = __builtin_amdgcn_readfirstlane(min(cnt, num_seqs - 1));
+        // query_start_loc[seq + 1] and ctx_lens[seq] sit in lane seq % 64 of look seq / 64, query_start_loc[seq] in
+        // the lane before
+        auto pick = [&](const int (&r)[4], int i) -> int {   // value of flat index i (wave-uniform) of a 4 x 64 array
+            const int p4 = i >> 6, l = i & 63;
+            const int x = p4 == 0 ? r[0] : p4 == 1 ? r[1] : p4 == 2 ? r[2] : r[3];
+            return __builtin_amdgcn_readlane(x, l);
+        };
+        const int q1 = pick(qv, seq);
+        q0 = seq > 0 ? pick(qv, seq - 1) : qs0;
+        q_len = q1 - q0;
+        ctx = pick(cv, seq);
     } else {
         seq = count_le(g_at, num_seqs, w, lane);
+        seq = __builtin_amdgcn_readfirstlane(min(seq, num_seqs - 1));
+        q0 = query_start_loc[seq];
+        q_len = query_start_loc[seq + 1] - q0;
+        ctx = ctx_lens[seq];
     }
-    seq = __builtin_amdgcn_readfirstlane(min(seq, num_seqs - 1));
-    const int q0 = query_start_loc[seq], q_len = query_start_loc[seq + 1] - q0;
-    const int ctx = ctx_lens[seq];
     if (q_len <= 0 || ctx < 0 || q0 < 0 || q0 + q_len > total_q) return;   // nothing to write / inconsistent arrays
     const int j = w - (q0 / kBlockSize + 2 * seq);          // which of the touched blocks
     const int bidx = ctx / kBlockSize + j;
