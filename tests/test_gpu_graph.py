@@ -1,7 +1,6 @@
 """ooco_attn_mixed under HIP graph capture: a planned call enqueues kernels and event fork/join only, so a
 serving loop can capture a run of layers once and replay it.  Every replay is checked against the eager
 result, with eager work and synchronisations between the replays."""
-import numpy as np
 import pytest
 import torch
 

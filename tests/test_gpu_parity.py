@@ -9,7 +9,7 @@ from oracle import ref_c, ref_numpy
 from paper_2511_21862_amd import binding as B
 from paper_2511_21862_amd import workloads as W
 
-from gpu_util import assert_parity, device_meta, errors, run_gpu, say
+from gpu_util import assert_parity, device_meta, run_gpu, say
 
 pytestmark = pytest.mark.gpu
 
