@@ -158,10 +158,13 @@ const char *ooco_last_error(const ooco_ctx *ctx);
  *                total_q_tokens until the next ooco_plan -- for callers that repeat one batch (benchmarks,
  *                the layers of one iteration, graph replay), who then answer for the device arrays still
  *                matching it
- *   "overlap"    0/1 (default 1): in a batch that holds both prefill chunks and decode sequences,
+ *   "overlap"    0/1/2 (default 1): in a batch that holds both prefill chunks and decode sequences,
  *                run the prefill kernel on the context's own side stream (default priority)
  *                concurrently with the decode kernel; the call still appears as one unit of work
- *                on the caller's stream (fork and join by events)
+ *                on the caller's stream (fork and join by events).  1 = unless the plan estimates the two
+ *                kernels at under 80 us together (they then run one after the other on the caller's stream:
+ *                measured faster there, and the host enqueues the call in 8 us instead of 41); 2 = always;
+ *                0 = never
  *   "decode_first"  0/1 (default 1): with "overlap", enqueue the decode kernel before the prefill
  *                kernel (0: the other way round)
  *   "profile"    0/1: every ooco_attn_mixed records HIP events around its two kernels (each on the

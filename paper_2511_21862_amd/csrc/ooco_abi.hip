@@ -111,6 +111,9 @@ struct HostPlan {
     int32_t lean = 0;
     int32_t dec_cus = 0;         // > 0: the batch runs in the mixed kernel with this many decoding compute units per XCD
     int64_t slots = 0;           // partial-result slots the decode kernel may touch
+    // a batch with both kinds of work whose two kernels, one after the other, are estimated to take under 80 us: they
+    // then run in sequence on the caller's stream (the fork and join of the second stream cost more than they gain)
+    bool brief = false;
 };
 
 // XCD weights -> cumulative form; false if a weight is outside 1..255 or they differ by more than 4x.
@@ -282,6 +285,15 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
         out.pf_table = 1;
     }
 
+    // ---- short mixed batches.  Measured on MI355X (32/8 heads): 1 x 64 rows + 4 decode sequences 50.7 us side by
+    // side, 44.9 us in sequence; 1 x 128 + 8: 49.0 / 46.9; 2 x 128 + 32: 84.9 / 81.3; 4 x 128 + 64: 129.8 / 139.7 -- and
+    // enqueueing the forked call costs the host 41 us against 8 us.  Estimate: each kernel's roofline time plus its
+    // fixed cost (15 us decode, 12 us prefill).
+    if (dec_blocks > 0 && tiles > 0) {
+        const double t_dec = (double)kv_blocks * BS * 2.0 * geo.Hkv * geo.hd * 2.0 / 6.8e12 + 15e-6;
+        const double t_pf = 4.0 * geo.Hq * geo.hd * pf_pairs / 1.05e15 + 12e-6;
+        out.brief = t_dec + t_pf < 80e-6;
+    }
     // ---- one launch for both kinds of work: how many compute units of every XCD decode.  The decode part is
     // bound by HBM and reaches its bandwidth from a part of the units; the prefill part is bound by the matrix
     // cores and takes as long as its share of the units makes it.  The prefill units are sized so that they
@@ -1069,7 +1081,7 @@ ooco_status ooco_attn_mixed(ooco_ctx *ctx, const void *q, const void *k_cache, c
     // ... or, by default, in ONE launch: the mixed kernel, whose compute units either decode or prefill (the plan
     // says how many do which).  Both arrays of the plan travel together (in the kernel arguments if they fit).
     const bool fused = mixed && pl.dec_cus > 0;
-    const bool overlap = mixed && !fused && ctx->opt_overlap && ctx->side_stream;
+    const bool overlap = mixed && !fused && ctx->side_stream && (ctx->opt_overlap >= 2 || (ctx->opt_overlap == 1 && !pl.brief));
     hipStream_t ps = overlap ? ctx->side_stream : s;   // the stream of the prefill kernel
     auto mark = [&](int k, hipStream_t st) {
         if (ev && e == hipSuccess) e = hipEventRecord(ev[k], st);

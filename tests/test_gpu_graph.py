@@ -13,7 +13,7 @@ from gpu_util import device_meta, say
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("mixed", [False, True, "split", "lean"])
+@pytest.mark.parametrize("mixed", [False, True, "split", "lean", "in sequence"])
 def test_captured_calls_replay_to_the_eager_result(mixed):
     # "split": the chunk sits on a long prefix, so its tiles are cut along the context and merged through the
     # workspace and the arrival counters, which every replay must find reset
@@ -27,10 +27,14 @@ def test_captured_calls_replay_to_the_eager_result(mixed):
     out = torch.zeros_like(eager)
     with B.Context(b.Hq, b.Hkv, b.hd, b.BS, b.num_blocks, b.max_blocks_per_seq) as ctx:
         ctx.set_option("plan_persistent", 1)     # one plan serves the eager calls, the capture and nothing changes in between
+        # a batch this short runs its two kernels one after the other by default ("in sequence"); the other mixed
+        # variants force the fork onto the context's second stream and the join, which is what a capture must record
+        if mixed and mixed != "in sequence":
+            ctx.set_option("overlap", 2)
         if mixed == "lean":                      # the register-lean pair of kernels of large mixed batches, forced here
             ctx.set_option("mixed_lean", 2)
         ctx.plan(b.seq_lens, b.query_start_loc, b.ctx_lens)
-        if mixed != "lean":
+        if mixed not in ("lean", "in sequence"):
             assert (ctx.plan_info()["prefill_parts"] > 1) == (mixed == "split")
         ctx.attn_mixed(d.q, d.k_cache, d.v_cache, bt, sl, qsl, cl, eager)
         torch.cuda.synchronize()

@@ -107,7 +107,7 @@ def test_prefill_tiles_split_along_the_context_agree(split):
 
 
 @pytest.mark.parametrize("opts", [{}, {"prefill_sorted": 0}, {"prefill_split": 3}, {"prefill_waves": 8}, {"mixed_lean": 2},
-                                  {"mixed_fused": 1}, {"overlap": 0}],
+                                  {"mixed_fused": 1}, {"overlap": 0}, {"overlap": 2}, {"overlap": 2, "mixed_lean": 2}],
                          ids=lambda o: "-".join(f"{k}{v}" for k, v in o.items()) or "default")
 def test_tiles_of_several_chunks_interleave(opts):
     # few tiles: the plan lists them one by one, longest first across chunks (the tiles of the chunk on the long
@@ -267,7 +267,7 @@ def test_block_copy_variants_are_bit_exact(variant):
 
 
 @pytest.mark.parametrize("opts", [{"decode_nbi": 1}, {"decode_nbi": 2}, {"decode_nbi": 4}, {"rotate_heads": 0}, {"decode_first": 0}, {"prefill_sorted": 0},
-                                  {"overlap": 0}, {"mixed_lean": 2}, {"mixed_lean": 2, "prefill_split": 2}, {"mixed_lean": 2, "decode_segments": 5}, {"mixed_lean": 0}, {"prefill_waves": 8}, {"prefill_waves": 8, "prefill_split": 3}, {"prefill_waves": 4}, {"mixed_fused": 1}, {"mixed_fused": 1, "mixed_dec_cus": 1},
+                                  {"overlap": 0}, {"overlap": 2}, {"overlap": 2, "decode_first": 0}, {"overlap": 2, "mixed_lean": 2}, {"mixed_lean": 2}, {"mixed_lean": 2, "prefill_split": 2}, {"mixed_lean": 2, "decode_segments": 5}, {"mixed_lean": 0}, {"prefill_waves": 8}, {"prefill_waves": 8, "prefill_split": 3}, {"prefill_waves": 4}, {"mixed_fused": 1}, {"mixed_fused": 1, "mixed_dec_cus": 1},
                                   {"mixed_fused": 1, "mixed_dec_cus": 31}, {"mixed_fused": 1, "mixed_dec_cus": 16, "prefill_split": 3}, {"decode_nbi": 2, "decode_segments": 9, "decode_tail_pct": 20,
                                                    "decode_tail_blocks": 3}],
                          ids=lambda o: "-".join(f"{k}{v}" for k, v in o.items()))
@@ -314,6 +314,7 @@ def test_profiled_calls_keep_the_overlap_and_the_results():
     out = torch.empty((b.total_q, b.Hq, b.hd), dtype=torch.bfloat16, device="cuda")
     with B.Context(b.Hq, b.Hkv, b.hd, b.BS, b.num_blocks, b.max_blocks_per_seq) as ctx:
         ctx.set_option("plan_persistent", 1)
+        ctx.set_option("overlap", 2)             # (a batch this short would otherwise run its kernels in sequence)
         ctx.plan(b.seq_lens, b.query_start_loc, b.ctx_lens)
         ctx.attn_mixed(d.q, d.k_cache, d.v_cache, bt, sl, qsl, cl, out)
         torch.cuda.synchronize()
