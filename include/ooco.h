@@ -274,9 +274,9 @@ ooco_status ooco_plan_kernels(const ooco_ctx *ctx, char *names /*HOST*/, size_t 
  * used up by the call unless option "plan_persistent" is set.
  * Without a current plan the call copies the length arrays to the host, waits for that copy
  * (one stream synchronisation) and plans by itself.
- * Launches at most two kernels (decode with its in-kernel merge, and prefill chunks on the context's
- * side stream when the batch holds both kinds of work) and no copies (batches above 960 sequences:
- * one small copy).
+ * Launches at most two kernels (decode with its in-kernel merge, and prefill chunks -- on the context's
+ * side stream when the batch holds both kinds of work and is not a short one, see option "overlap") and no
+ * copies (batches above 960 sequences: one small copy).
  * Writes every row of out (and the context's workspace), nothing else.  num_seqs == 0 or
  * total_q_tokens == 0 returns OOCO_OK without launching anything.
  * Same context + same plan + same inputs give bit-identical output on every call (no
