@@ -315,12 +315,15 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
     if (dec_blocks > 0) {
         // static runs: by default three waves per CU (measured best on MI355X: enough loads in
         // flight to saturate HBM, few enough waves that start-up and partial results stay small)
-        // and at least ~32 blocks per wave
+        // and at least ~16 blocks of head_dim 128 per wave (a small batch is a chain of dependent blocks per wave:
+        // one sequence of 512 blocks takes 27 us in 16 runs, 21 us in 32, 26 us in 64; eight sequences of 1121 blocks
+        // 30 us in 36 runs, 25 us in 64)
         // (mixed kernel: eight decode waves on every decoding unit, one run each)
         const int64_t wave_slots = lean ? std::max<int64_t>(1, (int64_t)geo.num_cus * 4 / geo.Hkv) : out.dec_cus == 99 ? std::max<int64_t>(1, (int64_t)geo.num_cus * 4 / geo.Hkv)
                                    : out.dec_cus > 0 ? std::max<int64_t>(1, (int64_t)out.dec_cus * kXcds * 8 / geo.Hkv)
                                                    : std::max<int64_t>(1, (int64_t)geo.num_cus * 3 / geo.Hkv);
-        int64_t runs = geo.segments_opt > 0 ? geo.segments_opt : std::min<int64_t>(wave_slots, (kv_blocks + 31) / 32);
+        const int64_t min_blocks = 16 * 128 / geo.hd;
+        int64_t runs = geo.segments_opt > 0 ? geo.segments_opt : std::min<int64_t>(wave_slots, (kv_blocks + min_blocks - 1) / min_blocks);
         runs = std::max<int64_t>(1, std::min<int64_t>(runs, dec_blocks));
         for (;;) {
             // weighted runs come in groups of one run per XCD
