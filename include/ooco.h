@@ -172,7 +172,8 @@ const char *ooco_last_error(const ooco_ctx *ctx);
  *                1024 calls between two reads
  *   "trace"      0/1: see ooco_trace_read
  * Tuning knobs kept for experiments (defaults are the measured best): "decode_nbi" (KV blocks per
- * softmax step of the decode kernel: 1, 2 or 4; 0 = default: 1 for head_dim 128, 2 for head_dim 64), "copy_sort" (block copy: 0 = pairs in the caller's order, 1 = default: copies of 2048 pairs or more are first
+ * softmax step of the decode kernel: 1, 2 or 4; 0 = the plan's choice: 1 for head_dim 128 -- 2 for small batches, whose
+ * waves are chains of dependent steps --, 2 for head_dim 64), "copy_sort" (block copy: 0 = pairs in the caller's order, 1 = default: copies of 2048 pairs or more are first
  * ordered by destination id on the device, into a buffer of the context that grows on demand -- measured on MI355X,
  * 13,044 blocks into random slots of a staging pool: 332 -> 314 us including the sort, which costs about 30 us and
  * does not pay when the slots are handed out in ascending order anyway (283 us) -- 2 = always),

@@ -114,6 +114,7 @@ struct HostPlan {
     // a batch with both kinds of work whose two kernels, one after the other, are estimated to take under 80 us: they
     // then run in sequence on the caller's stream (the fork and join of the second stream cost more than they gain)
     bool brief = false;
+    int32_t nbi = 0;             // KV blocks per softmax step of the decode kernel that the plan asks for (0 = the kernel's default)
 };
 
 // XCD weights -> cumulative form; false if a weight is outside 1..255 or they differ by more than 4x.
@@ -319,10 +320,17 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
         // one sequence of 512 blocks takes 27 us in 16 runs, 21 us in 32, 26 us in 64; eight sequences of 1121 blocks
         // 30 us in 36 runs, 25 us in 64)
         // (mixed kernel: eight decode waves on every decoding unit, one run each)
-        const int64_t wave_slots = lean ? std::max<int64_t>(1, (int64_t)geo.num_cus * 4 / geo.Hkv) : out.dec_cus == 99 ? std::max<int64_t>(1, (int64_t)geo.num_cus * 4 / geo.Hkv)
+        int64_t wave_slots = lean ? std::max<int64_t>(1, (int64_t)geo.num_cus * 4 / geo.Hkv) : out.dec_cus == 99 ? std::max<int64_t>(1, (int64_t)geo.num_cus * 4 / geo.Hkv)
                                    : out.dec_cus > 0 ? std::max<int64_t>(1, (int64_t)out.dec_cus * kXcds * 8 / geo.Hkv)
                                                    : std::max<int64_t>(1, (int64_t)geo.num_cus * 3 / geo.Hkv);
         const int64_t min_blocks = 16 * 128 / geo.hd;
+        // A small batch (at most 24,576 (block, kv head) tiles of head_dim 128) cannot keep HBM busy anyway: what
+        // counts is the length of every wave's chain of dependent steps.  Two blocks per step and at most half the
+        // usual number of runs: one 8K-token sequence 21.0 -> 18.3 us, eight sequences (1121 blocks) 25.9 -> 21.4 us,
+        // sixteen (2277 blocks) 35.2 -> 31.9 us; from 32 sequences (5296 blocks) on the usual layout is faster.
+        const bool small = geo.hd == 128 && !lean && out.dec_cus == 0 && kv_blocks * geo.Hkv <= 24576;
+        if (small) out.nbi = 2;
+        if (small && geo.segments_opt == 0) wave_slots = std::max<int64_t>(1, wave_slots / 2);
         int64_t runs = geo.segments_opt > 0 ? geo.segments_opt : std::min<int64_t>(wave_slots, (kv_blocks + min_blocks - 1) / min_blocks);
         runs = std::max<int64_t>(1, std::min<int64_t>(runs, dec_blocks));
         for (;;) {
@@ -922,7 +930,7 @@ ooco_status ooco_plan_kernels(const ooco_ctx *ctx, char *names, size_t cap)
     if (!names || cap == 0) return fail(ctx, OOCO_EINVAL, "ooco_plan_kernels: no buffer");
     const HostPlan &pl = ctx->plan;
     const bool dec = pl.static_runs > 0, pf = pl.n_tiles > 0;
-    const int nbi = ctx->opt_nbi ? (int)ctx->opt_nbi : (ctx->hd == 64 ? 2 : 1);
+    const int nbi = ctx->opt_nbi ? (int)ctx->opt_nbi : pl.nbi ? pl.nbi : (ctx->hd == 64 ? 2 : 1);
     char d[64] = "", f[64] = "";
     if (dec && pf && pl.dec_cus > 0)
         snprintf(d, sizeof d, "mixed_kernel<%d>", ctx->hd);
@@ -1045,7 +1053,7 @@ ooco_status ooco_attn_mixed(ooco_ctx *ctx, const void *q, const void *k_cache, c
     p.num_pf = pl.num_pf;
     p.dec_cus = pl.dec_cus;
     p.pf_waves = pl.pf_waves;
-    p.nbi = (int32_t)ctx->opt_nbi;
+    p.nbi = ctx->opt_nbi ? (int32_t)ctx->opt_nbi : pl.nbi;
     p.rotate_heads = (int16_t)(ctx->opt_rotate != 0);
     p.lean = (int16_t)pl.lean;
     for (int k = 0; k < kXcds; ++k) p.xcd_cw[k] = pl.cw[k];
@@ -1253,7 +1261,7 @@ ooco_status ooco_attn_mixed_static(int num_q_heads, int num_kv_heads, int head_d
     p.n_tiles = pl.n_tiles;
     p.num_pf = pl.num_pf;
     p.pf_waves = pl.pf_waves;
-    p.nbi = 0;
+    p.nbi = pl.nbi;
     p.rotate_heads = 1;
     p.pf_acc = nullptr;
     p.pf_ml = nullptr;
