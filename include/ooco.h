@@ -129,10 +129,12 @@ const char *ooco_last_error(const ooco_ctx *ctx);
  *                         when the batch has too few tiles to occupy the compute units and an
  *                         estimate of the kernel time improves by at least 7 %.  A tile
  *                         never gets more parts than it has 64-key steps.
- *   "prefill_sorted"      0/1 (default 1): a batch of at most 512 prefill tiles dispatches the tiles of ALL its
+ *   "prefill_sorted"      0/1/2 (default 1): a batch of at most 512 prefill tiles dispatches the tiles of ALL its
  *                         chunks by decreasing number of 64-key steps (one list entry per tile, in the kernel
  *                         arguments); 0 or more tiles: chunk by chunk, longest sequence first, the later tiles of
- *                         a chunk first.  Measured on MI355X, 8 chunks of 512 rows on 175..1781 cached tokens:
+ *                         a chunk first.  A launch of at most two workgroups per compute unit lists the second
+ *                         half of its tiles in ascending order, so that the two workgroups that share a unit are
+ *                         a long and a short one (2 = never, plain descending order).  Measured on MI355X, 8 chunks of 512 rows on 175..1781 cached tokens:
  *                         the span of the workgroups 94..98 -> 89..92 us.
  * Batches that hold both prefill chunks and decode sequences (take effect at the next ooco_plan):
  *   "mixed_lean"          the register-lean pair of kernels (head_dim 128): prefill workgroups of eight waves

@@ -106,7 +106,7 @@ def test_prefill_tiles_split_along_the_context_agree(split):
         assert np.array_equal(first, again)
 
 
-@pytest.mark.parametrize("opts", [{}, {"prefill_sorted": 0}, {"prefill_split": 3}, {"prefill_waves": 8}, {"mixed_lean": 2},
+@pytest.mark.parametrize("opts", [{}, {"prefill_sorted": 0}, {"prefill_sorted": 2}, {"prefill_split": 3}, {"prefill_waves": 8}, {"mixed_lean": 2},
                                   {"mixed_fused": 1}, {"overlap": 0}, {"overlap": 2}, {"overlap": 2, "mixed_lean": 2}],
                          ids=lambda o: "-".join(f"{k}{v}" for k, v in o.items()) or "default")
 def test_tiles_of_several_chunks_interleave(opts):
@@ -266,7 +266,7 @@ def test_block_copy_variants_are_bit_exact(variant):
     assert np.array_equal(vs.view(torch.int16).cpu().numpy().view(np.uint16), vh)
 
 
-@pytest.mark.parametrize("opts", [{"decode_nbi": 1}, {"decode_nbi": 2}, {"decode_nbi": 4}, {"rotate_heads": 0}, {"decode_first": 0}, {"prefill_sorted": 0},
+@pytest.mark.parametrize("opts", [{"decode_nbi": 1}, {"decode_nbi": 2}, {"decode_nbi": 4}, {"rotate_heads": 0}, {"decode_first": 0}, {"prefill_sorted": 0}, {"prefill_sorted": 2},
                                   {"overlap": 0}, {"overlap": 2}, {"overlap": 2, "decode_first": 0}, {"overlap": 2, "mixed_lean": 2}, {"mixed_lean": 2}, {"mixed_lean": 2, "prefill_split": 2}, {"mixed_lean": 2, "decode_segments": 5}, {"mixed_lean": 0}, {"prefill_waves": 8}, {"prefill_waves": 8, "prefill_split": 3}, {"prefill_waves": 4}, {"mixed_fused": 1}, {"mixed_fused": 1, "mixed_dec_cus": 1},
                                   {"mixed_fused": 1, "mixed_dec_cus": 31}, {"mixed_fused": 1, "mixed_dec_cus": 16, "prefill_split": 3}, {"decode_nbi": 2, "decode_segments": 9, "decode_tail_pct": 20,
                                                    "decode_tail_blocks": 3}],

@@ -240,13 +240,26 @@ def test_few_prefill_tiles_are_dispatched_longest_first_across_chunks():
     want = sum(-(-int(q) // 32) for q in ql if q > 1)
     assert len(t) == want and len({(int(r[0]), int(r[1])) for r in t}) == want          # every tile once
     steps = (t[:, 3] + t[:, 2] + 63) // 64
-    assert (np.diff(steps) <= 0).all() and steps[0] == (1781 + 512 + 63) // 64
-    assert len(np.unique(t[:len(t) // 2, 0])) > 1                                          # chunks interleave
-    for a, b2, sa, sb in zip(t[:-1], t[1:], steps[:-1], steps[1:]):
+    # 63 tiles on 256 compute units and 8 kv heads: one round of at most two workgroups per unit, workgroups w and
+    # w + 256 (tile positions p and p + 32) share a unit -- the first 32 positions descend, the others ASCEND, so that
+    # the longest tile is paired with the shortest
+    assert steps[0] == (1781 + 512 + 63) // 64 and (np.diff(steps[:32]) <= 0).all() and (np.diff(steps[32:]) >= 0).all()
+    assert steps[32:].max() <= steps[:32].min()
+    assert len(np.unique(t[:32, 0])) > 1                                                   # chunks interleave
+    order = np.r_[np.arange(32), np.arange(len(t) - 1, 31, -1)]                             # back to descending order
+    td, sd = t[order], steps[order]
+    for a, b2, sa, sb in zip(td[:-1], td[1:], sd[:-1], sd[1:]):
         if sa == sb and a[0] != b2[0]:
             assert (cx + ql)[a[0]] >= (cx + ql)[b2[0]]
         if sa == sb and a[0] == b2[0]:
             assert a[1] > b2[1]
+    # a batch of two rounds keeps the plain descending order
+    ql3 = np.full(8, 512, np.int32)
+    cx3 = np.array([1662, 175, 367, 485, 371, 1641, 1781, 1192], np.int32)
+    qsl3 = np.zeros(9, np.int32)
+    qsl3[1:] = np.cumsum(ql3)
+    t3 = dry(cx3 + ql3, qsl3, cx3)["prefill_tiles"]
+    assert len(t3) == 128 and (np.diff((t3[:, 3] + t3[:, 2] + 63) // 64) <= 0).all()
     # more than 512 tiles: chunk by chunk, longest sequence first, later tiles first
     ql2, cx2 = np.array([8192, 8192, 512], np.int32), np.array([100, 5000, 70000], np.int32)
     qsl2 = np.zeros(4, np.int32)
