@@ -370,22 +370,26 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
             if (geo.pf_split_opt > 0)
                 split = std::min<int64_t>(std::min<int64_t>(geo.pf_split_opt, kMaxPrefillSplit), max_tile_steps);
             else {
-                // Estimated time in microseconds with sp parts per tile, from measurements on MI355X.  A compute
-                // unit finishes a 64-key step of one workgroup in about 1.2 us whether one or two workgroups
-                // share it, so what counts is how many workgroups each unit gets: W = units x sp workgroups
-                // take W / CUs rounds (a started round counted half), a launch that just fills the units
-                // spreads unevenly (up to 1.4 us per step), and the last workgroup of a tile merges the sp
-                // partial results one after the other, slower when many tiles do so at once.  A split must
-                // win 7 % over the unsplit tile.
+                // Estimated time in microseconds with sp parts per tile, fitted to a sweep of 24 batches x 7 splits on
+                // MI355X (the choice is within 5 % of the best measured split on every one of them).  A workgroup's
+                // 64-key step takes 1.08 us while at most every other compute unit holds a workgroup, 1.3 us with one
+                // workgroup on every unit, 1.95 us with two (the unit then completes a step every 0.98 us, and further
+                // workgroups queue behind); the last workgroup of a tile merges the sp partial results, which costs
+                // 2 us + 0.03 us per workgroup of the launch up to two per unit + 0.04 us for every further one (their
+                // partial results then meet in memory at the same time).  A split must win 5 % over the unsplit tile.
                 const double steps = (double)tile_steps / (double)tiles, cus = (double)geo.num_cus;
-                auto est = [&](int64_t sp) {
-                    const double w = (double)(units * sp), r = w / cus;
-                    const double rounds = w <= cus ? 1.0 : 0.5 * (r + std::ceil(r));
-                    const double t_step = w <= cus ? 1.2 + 0.2 * std::max(0.0, 2.0 * r - 1.0) : 1.2;
-                    const double merge = sp > 1 ? 2.0 + (double)sp * (1.2 + (double)units / 64.0) : 0.0;
-                    return rounds * (steps / (double)sp) * t_step + merge;
+                auto step_us = [&](double r) {   // r = workgroups per compute unit
+                    if (r <= 0.5) return 1.08;
+                    if (r <= 1.0) return 1.08 + 0.44 * (r - 0.5);
+                    if (r <= 2.0) return 1.3 + 0.65 * (r - 1.0);
+                    return 0.975 * r;
                 };
-                double best = est(1) * 0.93;
+                auto est = [&](int64_t sp) {
+                    const double w = (double)(units * sp);
+                    const double merge = sp > 1 ? 2.0 + 0.03 * std::min(w, 2.0 * cus) + 0.04 * std::max(0.0, w - 2.0 * cus) : 0.0;
+                    return steps / (double)sp * step_us(w / cus) + merge;
+                };
+                double best = est(1) * 0.95;
                 for (int64_t sp = 2; sp <= kMaxPrefillSplit && sp <= (int64_t)steps; ++sp)
                     if (est(sp) < best) {
                         best = est(sp);

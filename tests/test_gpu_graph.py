@@ -33,6 +33,8 @@ def test_captured_calls_replay_to_the_eager_result(mixed):
             ctx.set_option("overlap", 2)
         if mixed == "lean":                      # the register-lean pair of kernels of large mixed batches, forced here
             ctx.set_option("mixed_lean", 2)
+        if mixed and mixed != "split":           # (the planner would cut even this short chunk's tiles in three)
+            ctx.set_option("prefill_split", 1)
         ctx.plan(b.seq_lens, b.query_start_loc, b.ctx_lens)
         if mixed not in ("lean", "in sequence"):
             assert (ctx.plan_info()["prefill_parts"] > 1) == (mixed == "split")
