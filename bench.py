@@ -65,6 +65,14 @@ def make_workload(name):
         b = W.config3(device="cuda", n_prefill=int(chunks), chunk=int(rows), n_decode=int(ndec))
         b.name = name
         return b, "decode"
+    if name.startswith("pf-"):      # pf-<chunks>x<rows>@<ctx>: prefill chunks of equal length on equal prior context
+        chunks, rest = name[3:].split("x")
+        rows, ctx = rest.split("@")
+        n, c, pc = int(chunks), int(rows), int(ctx)
+        need = n * ((c + pc + 15) // 16)
+        b = W.build_batch(Hq=32, Hkv=8, hd=128, q_lens=[c] * n, ctx_lens=[pc] * n, num_blocks=max(4096, 5 * need), seed=3,
+                          device="cuda", name=name)
+        return b, "prefill"
     if name.startswith("shape-"):   # shape-<Hq>-<Hkv>-<hd>: 256 decode sequences of 512-4096 tokens with another head shape
         Hq, Hkv, hd = (int(x) for x in name.split("-")[1:4])
         rng = np.random.default_rng(77)
