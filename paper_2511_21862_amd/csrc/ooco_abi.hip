@@ -324,13 +324,16 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
                                    : out.dec_cus > 0 ? std::max<int64_t>(1, (int64_t)out.dec_cus * kXcds * 8 / geo.Hkv)
                                                    : std::max<int64_t>(1, (int64_t)geo.num_cus * 3 / geo.Hkv);
         const int64_t min_blocks = 16 * 128 / geo.hd;
-        // A small batch (at most 24,576 (block, kv head) tiles of head_dim 128) cannot keep HBM busy anyway: what
+        // A small batch (at most 36,864 (block, kv head) tiles of head_dim 128) cannot keep HBM busy anyway: what
         // counts is the length of every wave's chain of dependent steps.  Two blocks per step and at most half the
         // usual number of runs: one 8K-token sequence 21.0 -> 18.3 us, eight sequences (1121 blocks) 25.9 -> 21.4 us,
         // sixteen (2277 blocks) 35.2 -> 31.9 us; from 32 sequences (5296 blocks) on the usual layout is faster.
-        const bool small = geo.hd == 128 && !lean && out.dec_cus == 0 && kv_blocks * geo.Hkv <= 24576;
+        // (between 24,576 and 36,864 tiles two thirds of the usual runs: 3814 blocks 49.2 -> 46.6 us; at 4739 blocks the
+        // two layouts are level)
+        const bool small = geo.hd == 128 && !lean && out.dec_cus == 0 && kv_blocks * geo.Hkv <= 36864;
         if (small) out.nbi = 2;
-        if (small && geo.segments_opt == 0) wave_slots = std::max<int64_t>(1, wave_slots / 2);
+        if (small && geo.segments_opt == 0)
+            wave_slots = std::max<int64_t>(1, kv_blocks * geo.Hkv <= 24576 ? wave_slots / 2 : wave_slots * 2 / 3);
         int64_t runs = geo.segments_opt > 0 ? geo.segments_opt : std::min<int64_t>(wave_slots, (kv_blocks + min_blocks - 1) / min_blocks);
         runs = std::max<int64_t>(1, std::min<int64_t>(runs, dec_blocks));
         for (;;) {
