@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the mixed-batch paged-attention step on ONE MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5|cfg3|cfg2|cfg4|cfg3-prefill|cfg5-prefill|cfg4-copy|cfg4-copy-seq|cfg3-append|cfg5-append|cfg4-preempt|shape-<Hq>-<Hkv>-<hd>]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5|cfg3|cfg2|cfg4|cfg3-prefill|cfg5-prefill|cfg3-decode|cfg5-decode|cfg4-copy|cfg4-copy-seq|cfg3-append|cfg5-append|cfg4-preempt|shape-<Hq>-<Hkv>-<hd>|mix-<c>x<r>+<d>[:<Hq>-<Hkv>]|pf-<c>x<r>@<ctx>[:<Hq>-<Hkv>]]
 
 The default workload is the largest mixed configuration (cfg5: 2 online prefill chunks of 2048 tokens + 32 offline
 decode sequences of 32K-131K tokens, 64/8 heads).
@@ -59,19 +59,26 @@ def make_workload(name):
         return W.config5(device="cuda"), "decode"
     if name == "cfg5-prefill":
         return W.config5(device="cuda", n_decode=0, num_blocks=4096), "prefill"
+    heads = (32, 8)
+    if name.startswith(("mix-", "pf-")) and ":" in name:   # ...:<Hq>-<Hkv>: the same batch with other head counts
+        name, shape = name.split(":")
+        heads = tuple(int(x) for x in shape.split("-"))
+        full = f"{name}:{shape}"
+    else:
+        full = name
     if name.startswith("mix-"):     # mix-<chunks>x<rows>+<decodes>: config 3's recipe with other proportions
         chunks, rest = name[4:].split("x")
         rows, ndec = rest.split("+")
-        b = W.config3(device="cuda", n_prefill=int(chunks), chunk=int(rows), n_decode=int(ndec))
-        b.name = name
-        return b, "decode"
+        b = W.config3(device="cuda", n_prefill=int(chunks), chunk=int(rows), n_decode=int(ndec), Hq=heads[0], Hkv=heads[1])
+        b.name = full
+        return b, ("decode" if int(ndec) else "prefill")
     if name.startswith("pf-"):      # pf-<chunks>x<rows>@<ctx>: prefill chunks of equal length on equal prior context
         chunks, rest = name[3:].split("x")
         rows, ctx = rest.split("@")
         n, c, pc = int(chunks), int(rows), int(ctx)
         need = n * ((c + pc + 15) // 16)
-        b = W.build_batch(Hq=32, Hkv=8, hd=128, q_lens=[c] * n, ctx_lens=[pc] * n, num_blocks=max(4096, 5 * need), seed=3,
-                          device="cuda", name=name)
+        b = W.build_batch(Hq=heads[0], Hkv=heads[1], hd=128, q_lens=[c] * n, ctx_lens=[pc] * n, num_blocks=max(4096, 5 * need),
+                          seed=3, device="cuda", name=full)
         return b, "prefill"
     if name.startswith("shape-"):   # shape-<Hq>-<Hkv>-<hd>: 256 decode sequences of 512-4096 tokens with another head shape
         Hq, Hkv, hd = (int(x) for x in name.split("-")[1:4])

@@ -142,7 +142,7 @@ const char *ooco_last_error(const ooco_ctx *ctx);
  *                         four per compute unit, so that a SIMD holds two prefill waves and a decode wave at once.
  *                         1 (default) = automatic: when the prefill part gives every compute unit at least one
  *                         eight-wave workgroup and, by the batch's FLOPs and bytes, would by itself take between
- *                         0.35 and 4 times as long as the decode part (a shorter one does not repay the lean
+ *                         0.30 and 4 times as long as the decode part (a shorter one does not repay the lean
  *                         decode kernel's 3 %, a longer one not the lean prefill kernel's 5 %); 0 = never (the
  *                         stand-alone kernels side by side); 2 = whenever the batch holds both kinds of work.
  *   "prefill_waves"       waves per prefill workgroup: 4 (128 query columns per staged K/V tile), 8 (256), or

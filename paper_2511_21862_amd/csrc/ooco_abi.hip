@@ -183,7 +183,7 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
     // them, so four waves are the default; eight (head_dim 128 only) stay selectable.
     // The register-lean pair for batches with both kinds of work (lean_opt 2 = whenever the batch is mixed; 1 = when
     // it pays: every compute unit gets at least one eight-wave prefill workgroup, and the prefill part, by itself,
-    // would take between 0.35 and 4 times as long as the decode part -- estimated from the batch's FLOPs and bytes
+    // would take between 0.30 and 4 times as long as the decode part -- estimated from the batch's FLOPs and bytes
     // at 1.05 PFLOP/s and 6.8 TB/s).  Measured on MI355X, 32/8 heads, 128 decode sequences of 1.4 GB in all: beside
     // 2 x 2048 rows 319 -> 291 us, beside 8 x 512 rows 286 -> 270 us, but beside 4 x 512 rows 257 -> 263 us and beside
     // 1 x 512 rows 242 -> 266 us (alone the lean decode kernel is 3 % slower than the stand-alone one, which a short
@@ -205,7 +205,7 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
         }
         const double t_pf = 4.0 * geo.Hq * geo.hd * pairs / 1.05e15;
         const double t_dec = (double)dec_blk * BS * 2.0 * geo.Hkv * geo.hd * 2.0 / 6.8e12;
-        const bool pays = tiles8 * geo.Hkv >= (int64_t)geo.num_cus && t_pf >= 0.35 * t_dec && t_pf <= 4.0 * t_dec;
+        const bool pays = tiles8 * geo.Hkv >= (int64_t)geo.num_cus && t_pf >= 0.30 * t_dec && t_pf <= 4.0 * t_dec;
         lean = n_dec > 0 && tiles8 > 0 && (geo.lean_opt >= 2 || pays);
     }
     out.lean = lean;

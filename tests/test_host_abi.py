@@ -274,7 +274,7 @@ def test_few_prefill_tiles_are_dispatched_longest_first_across_chunks():
 def test_lean_pair_is_planned_only_where_the_prefill_part_weighs_enough():
     # the eight-wave prefill workgroups of the register-lean pair show in the dry run as tiles of 256 / g query rows
     # (g = 4: 64) instead of 128 / g; the pair is planned when every compute unit gets such a workgroup and the prefill
-    # part's estimated time is 0.35 .. 4 times the decode part's
+    # part's estimated time is 0.30 .. 4 times the decode part's
     rng = np.random.default_rng(3)
     dec = rng.integers(1500, 4000, size=128).astype(np.int32)          # about 1.4 GB of K/V
 
