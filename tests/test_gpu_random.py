@@ -4,6 +4,8 @@ the unused cache slots and a random choice of planner options are all drawn per 
   * ooco_attn_mixed against the float64 C oracle (the parity gates),
   * ooco_attn_mixed_static against ooco_attn_mixed with the same kernels (bit-identical),
   * ooco_kv_append and ooco_kv_block_copy against the numpy oracle (bit-exact)."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -23,6 +25,7 @@ OPTIONS = [{}, {}, {"prefill_split": 2}, {"prefill_split": 5}, {"prefill_sorted"
            {"decode_tail_pct": 30, "decode_tail_blocks": 2}, {"mixed_lean": 2}, {"mixed_lean": 2, "overlap": 2},
            {"prefill_waves": 8}, {"mixed_fused": 1}, {"rotate_heads": 0}, {"decode_piece_pad": 5}, {"xcd_weights": sum(w << (8 * k) for k, w in enumerate([100, 60, 140, 95, 105, 85, 115, 100])), "decode_segments": 16}, {"decode_first": 0}]
 bits = lambda t: t.view(torch.int16).cpu().numpy().view(np.uint16)
+N_CASES = int(os.environ.get("OOCO_RANDOM_CASES", "24"))      # set higher for a longer run (400 cases take 90 s)
 
 
 def draw(case):
@@ -44,7 +47,7 @@ def draw(case):
     return rng, b, opts
 
 
-@pytest.mark.parametrize("case", range(24))
+@pytest.mark.parametrize("case", range(N_CASES))
 def test_random_batch_attention(case):
     rng, b, opts = draw(case)
     say(f"case: random {case}: {b.Hq}/{b.Hkv}/{b.hd} q_lens={b.q_lens.tolist()} ctx={b.ctx_lens.tolist()} options={opts}")
@@ -87,7 +90,7 @@ def test_random_larger_batch_attention(case):
     assert_parity(run_gpu(b, options=opts), ref, f"larger random {case}")
 
 
-@pytest.mark.parametrize("case", range(24))
+@pytest.mark.parametrize("case", range(N_CASES))
 def test_random_batch_append_and_copy(case):
     rng, b, _ = draw(case)
     say(f"case: random {case} append + copy: {b.Hq}/{b.Hkv}/{b.hd} q_lens={b.q_lens.tolist()} ctx={b.ctx_lens.tolist()}")
