@@ -124,6 +124,33 @@ def test_plan_covers_every_block_and_row_once(cfg):
         check_cover(b, plan)
 
 
+def test_plans_of_random_batches_cover_every_block_and_row_once():
+    # 300 seeded batches: 1-400 sequences, a random mix of empty / decode / chunk sequences, lengths over four orders of
+    # magnitude, head shapes, compute-unit counts, workspace sizes and every planner option that shapes the work lists
+    rng = np.random.default_rng(20251)
+    for case in range(300):
+        n = int(rng.choice([1, 2, 5, 30, 120, 400]))
+        kinds = rng.choice(3, size=n, p=[0.1, 0.6, 0.3])
+        ql = np.where(kinds == 0, 0, np.where(kinds == 1, 1, rng.integers(2, 3000, size=n))).astype(np.int32)
+        cx = np.where(rng.random(n) < 0.15, 0, (2.0 ** rng.uniform(0, 16, size=n)).astype(np.int64)).astype(np.int32)
+        qsl = np.zeros(n + 1, np.int32)
+        qsl[1:] = np.cumsum(ql)
+        Hq, Hkv, hd = [(32, 8, 128), (28, 4, 128), (64, 8, 128), (8, 1, 128), (16, 16, 64), (4, 1, 64)][rng.integers(6)]
+        kw = dict(num_q_heads=Hq, num_kv_heads=Hkv, head_dim=hd, num_cus=int(rng.choice([256, 304, 64, 8])),
+                  workspace_bytes=int(rng.choice([1 << 20, 64 << 20, 1 << 30])),
+                  decode_segments=int(rng.choice([0, 0, 1, 5, 77, 10 ** 9])), decode_tail_pct=int(rng.choice([0, 0, 15, 60])),
+                  decode_tail_blocks=int(rng.choice([1, 3, 8])), prefill_split=int(rng.choice([0, 0, 1, 2, 7])),
+                  decode_piece_pad=int(rng.choice([-1, -1, 0, 3, 64])))
+        if rng.random() < 0.2:
+            kw["xcd_weights"] = rng.integers(60, 140, size=8).astype(np.int32)
+        b = W.Batch(Hq=Hq, Hkv=Hkv, hd=hd, BS=16, num_blocks=1, block_tables=np.zeros((n, 1), np.int32), seq_lens=cx + ql,
+                    ctx_lens=cx, query_start_loc=qsl, q=None, k_cache=None, v_cache=None)
+        try:
+            check_cover(b, dry(b.seq_lens, b.query_start_loc, b.ctx_lens, **kw))
+        except Exception as e:
+            raise AssertionError(f"case {case}: q_lens {ql.tolist()} ctx {cx.tolist()} {kw}") from e
+
+
 def test_default_plan_is_equal_static_runs_plus_short_tail_runs():
     for cfg in (W.config2, W.config4, W.config5):
         b = meta_only(cfg)
