@@ -431,6 +431,19 @@ def wg_timeline(ctx, b, run_step, torch, reps=5):
             eighth.append([float(steps[sel].mean()), float(t0[sel].min()), float(t0[sel].max()), float(t1[sel].min()),
                            float(t1[sel].max()), float((t1 - t0)[sel].mean())])
         r["eighths_steps_start_min_max_end_min_max_duration_mean"] = eighth
+        # phases of a workgroup (16 bits each in the third stamp, 10 ns since its start): tile looked up, first loads
+        # sent off, first tiles arrived, last step done; the epilogue is what remains until its end.  Medians over
+        # the first round (the workgroups that start on an idle GPU) and over the later ones.
+        x = raw[:, 2].astype(np.uint64)
+        ph = np.stack([((x >> np.uint64(16 * k)) & np.uint64(0xFFFF)).astype(np.float64) / 100.0 for k in range(4)], axis=1)
+        order = np.argsort(t0, kind="stable")
+        first = order[: min(n, 2 * len(np.unique(cu)))]
+        later = order[min(n, 2 * len(np.unique(cu))):]
+        for name, idx in (("first_round", first), ("later_rounds", later)):
+            idx = idx[x[idx] != 0]
+            if len(idx):
+                r[f"phases_us_{name}_lookup_issued_landed_loopend_epilogue"] = (
+                    np.median(ph[idx], axis=0).tolist() + [float(np.median((t1 - t0)[idx] - ph[idx, 3]))])
         rows.append(r)
     ctx.set_option("trace", 0)
     med = lambda key: np.median(np.array([r[key] for r in rows], dtype=np.float64), axis=0)

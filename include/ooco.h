@@ -208,8 +208,10 @@ ooco_status ooco_profile_read_calls(ooco_ctx *ctx, double *per_call_ms /*HOST*/,
  *   stamps: HOST uint64 [cap_waves][4], wave index = run * num_kv_heads + kv head;
  *   waves: HOST, receives the number of decode waves of that call.
  * A traced batch WITHOUT decode sequences stores per prefill workgroup instead (workgroup index = (tile in
- * dispatch order * num_kv_heads + kv head) * parts + part): start, XCD * 256 + compute-unit id, 0, end; `waves`
- * then receives the number of prefill workgroups.
+ * dispatch order * num_kv_heads + kv head) * parts + part): start, XCD * 256 + compute-unit id, phases, end; `waves`
+ * then receives the number of prefill workgroups.  `phases` packs four times since the workgroup's start, 16 bits
+ * each (units of 10 ns, saturating at 65535), lowest first: tile looked up, first K/V loads sent off, first tiles
+ * arrived in LDS, last step done; 0 for a part of a split tile that had no step to work on.
  * Tracing adds waits to the kernel; never leave it on when measuring throughput. */
 ooco_status ooco_trace_read(ooco_ctx *ctx, uint64_t *stamps /*HOST*/, int64_t cap_waves, int64_t *waves /*HOST*/);
 

@@ -622,8 +622,11 @@ constexpr int kPfBlocks = 4;    // KV blocks per step
 // PIPE = false: no software pipeline across steps (the scores of a step are computed in that step, one score
 // register set): fewer registers, so that two such waves and a decode wave share a SIMD; the overlap of matrix and
 // vector work then comes from the two waves of a SIMD rather than from within one wave.
+// `phases` (option "trace", prefill-only batches): receives four 16-bit times in units of 10 ns since `t_start`
+// (saturating), lowest first: tile looked up, first K/V loads sent off, first tiles arrived, last step done.
 template <int HD, int NW, bool PIPE, class CumAt>
-OOCO_DEV void prefill_unit(const AttnParams &p, CumAt cum_at, const int vb)
+OOCO_DEV void prefill_unit(const AttnParams &p, CumAt cum_at, const int vb, uint64_t *phases = nullptr,
+                           const uint64_t t_start = 0)
 {
     constexpr int THREADS = NW * 64;
     constexpr int COLS = NW * 32;      // query columns per workgroup
@@ -641,6 +644,13 @@ OOCO_DEV void prefill_unit(const AttnParams &p, CumAt cum_at, const int vb)
     const int col = lane & 31;
     const int h = lane >> 5;
     const int g = p.g;
+    uint64_t phase_bits = 0;   // (scalar; touched only when tracing)
+    auto phase = [&](int k) {
+        if (phases) {
+            const uint64_t dt = (uint64_t)wall_clock64() - t_start;
+            phase_bits |= (dt < 0xFFFFu ? dt : (uint64_t)0xFFFFu) << (16 * k);
+        }
+    };
     // workgroup -> (unit = (tile, kv head), part of the unit's keys)
     const int split = p.pf_split;
     const int unit = vb / split;
@@ -704,6 +714,7 @@ OOCO_DEV void prefill_unit(const AttnParams &p, CumAt cum_at, const int vb)
     const int st_lo = nstep_all * part / nparts;
     const int nstep = nstep_all * (part + 1) / nparts;
 
+    phase(0);
     u32x4 qb[KS];
     {
         const u32x4 *qp = reinterpret_cast<const u32x4 *>(p.q + ((int64_t)(q_row0 + row) * p.Hq + head) * HD);
@@ -907,6 +918,7 @@ OOCO_DEV void prefill_unit(const AttnParams &p, CumAt cum_at, const int vb)
         issue(true, st_lo & 1, ids0);
         if (PIPE && st_lo + 1 < nstep) issue(false, (st_lo + 1) & 1, ids1);
     }
+    phase(1);
     // One step.  Sc: scores of step st (computed during step st-1), Sn: receives those of step st+1.
     auto body = [&](f32x16 (&Sc)[2], f32x16 (&Sn)[2], int st) {
         // this wave's loads of K[st+1] and V[st] have landed, and after the barrier so have
@@ -968,6 +980,7 @@ OOCO_DEV void prefill_unit(const AttnParams &p, CumAt cum_at, const int vb)
         f32x16 SA[2], SB[2];
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
+        phase(2);
         qk(SA, st_lo & 1);
         for (int st = st_lo; st < nstep; st += 2) {
             body(SA, SB, st);
@@ -1010,6 +1023,8 @@ OOCO_DEV void prefill_unit(const AttnParams &p, CumAt cum_at, const int vb)
             }
         }
     }
+    phase(3);
+    if (phases && tid == 0) *phases = phase_bits;
     float ltot;
     {
         float x, y;
@@ -1089,14 +1104,17 @@ template <int HD, int NW>
 __global__ __launch_bounds__(NW * 64, 8 / NW) void prefill_kernel(const KernArgs a)
 {
     const AttnParams &p = a.p;
-    // option "trace" on a batch without decode work: per workgroup (start, XCD * 256 + compute unit id, 0, end)
+    // option "trace" on a batch without decode work: per workgroup (start, XCD * 256 + compute unit id, times of
+    // four phases since the start, end)
     uint64_t *const trace = (p.trace && p.static_runs == 0) ? p.trace + (int64_t)blockIdx.x * 4 : nullptr;
+    const uint64_t t_start = trace ? wall_clock64() : 0;
     if (trace && threadIdx.x == 0) {
-        trace[0] = wall_clock64();
+        trace[0] = t_start;
         trace[1] = (__builtin_amdgcn_s_getreg((31 << 11) | 20) & 7u) * 256u + ((__builtin_amdgcn_s_getreg((31 << 11) | 4) >> 8) & 255u);
-        trace[2] = 0;
+        trace[2] = 0;   // (a workgroup that leaves before its first step stores no phases)
     }
-    prefill_unit<HD, NW, true>(p, [&](int idx) -> int { return p.cum_dev ? p.cum_dev[idx] : a.cum[idx]; }, (int)blockIdx.x);
+    prefill_unit<HD, NW, true>(p, [&](int idx) -> int { return p.cum_dev ? p.cum_dev[idx] : a.cum[idx]; }, (int)blockIdx.x,
+                               trace ? trace + 2 : nullptr, t_start);
     if (trace) {
         __syncthreads();
         if (threadIdx.x == 0) trace[3] = wall_clock64();
