@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the mixed-batch paged-attention step on ONE MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5|cfg3|cfg2|cfg4|cfg3-prefill|cfg5-prefill|cfg3-decode|cfg5-decode|cfg4-copy|cfg4-copy-seq|cfg3-append|cfg5-append|cfg4-preempt|shape-<Hq>-<Hkv>-<hd>|mix-<c>x<r>+<d>[:<Hq>-<Hkv>]|pf-<c>x<r>@<ctx>[:<Hq>-<Hkv>]]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5|cfg3|cfg2|cfg4|cfg3-prefill|cfg5-prefill|cfg3-decode|cfg5-decode|cfg4-copy|cfg4-copy-seq|cfg3-append|cfg5-append|cfg4-preempt|shape-<Hq>-<Hkv>-<hd>|mix-<c>x<r>+<d>[:<Hq>-<Hkv>]|pf-<c>x<r>@<ctx>[:<Hq>-<Hkv>]|pfx-[<n>x]<r>@<ctx>+...]
 
 The default workload is the largest mixed configuration (cfg5: 2 online prefill chunks of 2048 tokens + 32 offline
 decode sequences of 32K-131K tokens, 64/8 heads).
@@ -79,6 +79,17 @@ def make_workload(name):
         need = n * ((c + pc + 15) // 16)
         b = W.build_batch(Hq=heads[0], Hkv=heads[1], hd=128, q_lens=[c] * n, ctx_lens=[pc] * n, num_blocks=max(4096, 5 * need),
                           seed=3, device="cuda", name=full)
+        return b, "prefill"
+    if name.startswith("pfx-"):     # pfx-[<n>x]<rows>@<ctx>+[<n>x]<rows>@<ctx>+...: prefill chunks of several lengths and prior contexts
+        ql, cx = [], []
+        for item in name[4:].split("+"):
+            n, rest = item.split("x") if "x" in item else ("1", item)
+            rows, ctx = rest.split("@")
+            ql += [int(rows)] * int(n)
+            cx += [int(ctx)] * int(n)
+        need = sum((c + q + 15) // 16 for q, c in zip(ql, cx))
+        b = W.build_batch(Hq=32, Hkv=8, hd=128, q_lens=ql, ctx_lens=cx, num_blocks=max(4096, 5 * need), seed=3, device="cuda",
+                          name=name)
         return b, "prefill"
     if name.startswith("shape-"):   # shape-<Hq>-<Hkv>-<hd>: 256 decode sequences of 512-4096 tokens with another head shape
         Hq, Hkv, hd = (int(x) for x in name.split("-")[1:4])

@@ -123,16 +123,20 @@ const char *ooco_last_error(const ooco_ctx *ctx);
  *                         from one piece to the first tile of the next); 0 = runs of equal
  *                         block counts; at most 64.
  * Prefill tiles (takes effect at the next ooco_plan):
- *   "prefill_split"       parts a prefill tile's key range is cut into, 1..8 (more is taken as 8); every part is a
- *                         workgroup of its own and the last one to finish merges their partial
+ *   "prefill_split"       parts a prefill tile's key range is cut into, 1..16 (more is taken as 16); every part is
+ *                         a workgroup of its own and the last one to finish merges their partial
  *                         results (held in the workspace).  0 (default) = automatic: split only
- *                         when the batch has too few tiles to occupy the compute units and an
- *                         estimate of the kernel time improves by at least 7 %.  A tile
- *                         never gets more parts than it has 64-key steps.
+ *                         when the batch cannot occupy the compute units, or when a few tiles on a long context
+ *                         would run on long after all others, and an estimate of the kernel time improves by at
+ *                         least 5 %; in a batch of at most 512 tiles every tile then gets parts by its own number of
+ *                         steps (the tile with the most steps k parts, the others as many as keep their parts no
+ *                         longer than that tile's), so that a chunk on a short context stays whole beside one on a
+ *                         long context.  A tile never gets more parts than it has 64-key steps.
  *   "prefill_sorted"      0/1/2 (default 1): a batch of at most 512 prefill tiles dispatches the tiles of ALL its
- *                         chunks by decreasing number of 64-key steps (one list entry per tile, in the kernel
- *                         arguments); 0 or more tiles: chunk by chunk, longest sequence first, the later tiles of
- *                         a chunk first.  A launch of at most two workgroups per compute unit lists the second
+ *                         chunks -- the parts of its tiles, if they are split -- by decreasing number of 64-key
+ *                         steps (one list entry per tile or part, in the kernel arguments; at most 896 entries);
+ *                         0 or more tiles: chunk by chunk, longest sequence first, the later tiles of
+ *                         a chunk first, every tile the same number of parts.  A launch of at most two workgroups per compute unit lists the second
  *                         half of its tiles in ascending order, so that the two workgroups that share a unit are
  *                         a long and a short one (2 = never, plain descending order).  Measured on MI355X, 8 chunks of 512 rows on 175..1781 cached tokens:
  *                         the span of the workgroups 94..98 -> 89..92 us.
@@ -237,11 +241,11 @@ ooco_status ooco_plan(ooco_ctx *ctx, int num_seqs, const int32_t *h_seq_lens /*H
  *   decode_pieces_out: HOST int32 [decode_cap][5] = (seq, blk_begin, blk_end, slot, run): the KV
  *     block range of sequence seq that decode run `run` streams; slot = partial-result slot, or
  *     -1 when the piece covers the whole sequence and writes the output directly
- *   prefill_tiles_out: HOST int32 [prefill_cap][5] = (seq, q_row0, rows, pos0, seq_len), in the order in which
- *     the tiles are dispatched; a tile holds up to 128 / (num_q_heads/num_kv_heads) query rows (256 / ... in
- *     the eight-wave kernel) and runs once per kv head
+ *   prefill_tiles_out: HOST int32 [prefill_cap][5] = (seq, q_row0, rows, pos0, parts), in the order in which
+ *     the tiles (their first parts) are dispatched; a tile holds up to 128 / (num_q_heads/num_kv_heads) query rows
+ *     (256 / ... in the eight-wave kernel) and runs once per kv head; parts = workgroups its key range is cut into
  *   counts: HOST int64 [6] = (decode pieces, prefill tiles, static decode runs, partial-result
- *     slots, dynamically fetched tail runs, parts each prefill tile's key range is cut into);
+ *     slots, dynamically fetched tail runs, the most parts a prefill tile's key range is cut into);
  *     runs are numbered static first, then tail
  *   msg: HOST buffer of msg_cap bytes receiving the error text.  Any output pointer may be NULL.
  *   xcd_weights: NULL for equal static runs, else the relative run lengths per XCD that option
@@ -261,7 +265,7 @@ ooco_status ooco_plan_dry_run(int num_q_heads, int num_kv_heads, int head_dim, i
 
 /* Numbers describing the last plan made, current or used up (any pointer may be NULL): decode runs (waves per kv head),
  * prefill tiles, KV blocks of all decode sequences, bytes of workspace the partial results use,
- * parts each prefill tile's key range is cut into (1 = not split). */
+ * the most parts a prefill tile's key range is cut into (1 = no tile is split). */
 ooco_status ooco_plan_info(const ooco_ctx *ctx, int64_t *decode_waves, int64_t *prefill_tiles,
                            int64_t *decode_blocks, int64_t *workspace_used, int64_t *prefill_parts);
 

@@ -95,15 +95,15 @@ struct HostPlan {
     // prefill chunks, heaviest (most keys) first: pf[0..P] = query tiles before chunk k of that
     // order, pf[P+1+k] = sequence index of chunk k
     const int32_t *pf = nullptr;
-    size_t pf_size = 0;              // 2 * num_pf + 1, + n_tiles with the tile list (pf_table)
-    int32_t pf_table = 0;            // pf goes on with one entry per tile in dispatch order: (k << 20) | tile of chunk k
+    size_t pf_size = 0;              // 2 * num_pf + 1, + pf_table with the tile list
+    int32_t pf_table = 0;            // > 0: pf goes on with that many (tile, part) entries in dispatch order (list_entry)
     int32_t num_pf = 0;
     int32_t dec_blocks = 0, static_blocks = 0, static_runs = 0, tail_runs = 0;   // in line units
     int32_t piece_pad = 0;
     int64_t kv_blocks = 0;       // KV blocks of all decode sequences
     uint16_t cw[kXcds] = {};     // XCD weights in force (RunLayout::cw)
     int32_t n_tiles = 0, total_q = 0, num_seqs = 0;
-    int32_t pf_split = 1;        // parts each prefill tile's keys are cut into
+    int32_t pf_split = 1;        // parts a prefill tile's keys are cut into (with the tile list: the most any tile has)
     int32_t pf_waves = 4;        // waves per prefill workgroup (32 query columns each)
     // mixed batches (head_dim 128): the register-lean pair of kernels -- prefill workgroups of eight waves (176
     // registers, no software pipeline) and decode waves of 144 registers, four per compute unit -- so that a SIMD
@@ -134,16 +134,16 @@ bool xcd_weights_to_cw(const int32_t *w, uint16_t *cw)
 size_t slot_bytes(const PlanGeometry &geo) { return (size_t)geo.Hq * (geo.hd + 2) * sizeof(float); }
 
 // Where build_plan puts the plan's arrays: room for `seqs_cap` sequences, i.e. dcum [seqs_cap + 1],
-// pf [2 * seqs_cap + 1 + kSortedTiles] and a work array order [seqs_cap].  build_plan itself allocates nothing.
+// pf [2 * seqs_cap + 1 + kListEntries] and a work array order [seqs_cap].  build_plan itself allocates nothing.
 struct PlanStorage {
     int32_t *dcum, *pf, *order;
     size_t seqs_cap;
 };
 PlanStorage carve_storage(int32_t *base, size_t seqs_cap)
 {
-    return PlanStorage{base, base + (seqs_cap + 1), base + (seqs_cap + 1) + (2 * seqs_cap + 1 + kSortedTiles), seqs_cap};
+    return PlanStorage{base, base + (seqs_cap + 1), base + (seqs_cap + 1) + (2 * seqs_cap + 1 + kListEntries), seqs_cap};
 }
-constexpr size_t storage_ints(size_t seqs_cap) { return (seqs_cap + 1) + (2 * seqs_cap + 1 + kSortedTiles) + seqs_cap; }
+constexpr size_t storage_ints(size_t seqs_cap) { return (seqs_cap + 1) + (2 * seqs_cap + 1 + kListEntries) + seqs_cap; }
 
 // Validates the length arrays and builds the plan.  Pure host code, no allocation.
 ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_seq_lens,
@@ -263,27 +263,27 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
         pf[k + 1] = pf[k] + (int32_t)((ql + tile_rows - 1) / tile_rows);
         pf[n_order + 1 + k] = order[k];
     }
+    auto steps_of = [&](int32_t e) -> int64_t {   // 64-key steps of the tile a list entry names
+        const int i = order[entry_chunk(e)];
+        const int64_t ql = (int64_t)h_query_start_loc[i + 1] - h_query_start_loc[i], t0 = (int64_t)entry_tile(e) * tile_rows;
+        return ((int64_t)h_ctx_lens[i] + std::min<int64_t>(ql, t0 + tile_rows) + 63) / 64;
+    };
     // A launch of few tiles is as long as its unluckiest compute unit is busy, and the hardware hands workgroups out
     // in index order to whichever unit has room: the tiles of ALL chunks go out by decreasing number of 64-key
     // steps (a chunk on a short context has fewer steps in its last tile than one on a long context in its first).
     // (only while the longer array still travels in the kernel arguments)
     if (geo.pf_table_opt && tiles > 0 && tiles <= kSortedTiles && 2 * n_order + 1 + (size_t)tiles <= (size_t)kInlineSeqs + 1) {
         int32_t *const tab = pf + out.pf_size;
-        auto steps_of = [&](int32_t e) -> int64_t {
-            const int i = order[e >> 20];
-            const int64_t ql = (int64_t)h_query_start_loc[i + 1] - h_query_start_loc[i], t0 = (int64_t)(e & 0xFFFFF) * tile_rows;
-            return ((int64_t)h_ctx_lens[i] + std::min<int64_t>(ql, t0 + tile_rows) + 63) / 64;
-        };
         size_t n = 0;
         for (size_t k = 0; k < n_order; ++k)
-            for (int32_t t = pf[k + 1] - pf[k] - 1; t >= 0; --t) tab[n++] = (int32_t)(k << 20) | t;
-        // (ties keep the chunk order and, inside a chunk, the later tile first: entries compare as numbers)
+            for (int32_t t = pf[k + 1] - pf[k] - 1; t >= 0; --t) tab[n++] = list_entry((int)k, t, 0, 1);
+        // (ties keep the chunk order and, inside a chunk, the later tile first)
         std::sort(tab, tab + n, [&](int32_t x, int32_t y) {
             const int64_t sx = steps_of(x), sy = steps_of(y);
-            return sx != sy ? sx > sy : (x >> 20) != (y >> 20) ? (x >> 20) < (y >> 20) : x > y;
+            return sx != sy ? sx > sy : entry_chunk(x) != entry_chunk(y) ? entry_chunk(x) < entry_chunk(y) : entry_tile(x) > entry_tile(y);
         });
         out.pf_size += n;
-        out.pf_table = 1;
+        out.pf_table = (int32_t)n;
     }
 
     // ---- short mixed batches.  Measured on MI355X (32/8 heads): 1 x 64 rows + 4 decode sequences 50.7 us side by
@@ -369,39 +369,115 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
     if (tiles > 0) {
         const int64_t units = tiles * geo.Hkv;
         int64_t split = 1;
+        int32_t *const tab = store.pf + (2 * (size_t)out.num_pf + 1);
+        const size_t part_bytes = (size_t)(32 * pf_waves) * (geo.hd + 2) * sizeof(float);
+        const size_t left = geo.ws_bytes - std::min(geo.ws_bytes, ((size_t)out.slots * slot_bytes(geo) + 255) / 256 * 256);
+        const double cus = (double)geo.num_cus;
+        // Estimated time in microseconds of a launch of w workgroups in all, the longest of them `longest` 64-key steps,
+        // fitted to a sweep of 24 batches of equal chunks x 7 splits on MI355X (the choice is within 5 % of the best
+        // measured split on every one of them).  A workgroup's step takes 1.08 us while at most every other compute unit
+        // holds a workgroup, 1.3 us with one workgroup on every unit, 1.95 us with two (the unit then completes a step
+        // every 0.98 us, and further workgroups queue behind); the last workgroup of a tile merges the partial results
+        // of its parts, which costs 2 us + 0.03 us per workgroup of the launch up to two per unit + 0.04 us for every
+        // further one (their partial results then meet in memory at the same time).  The launch takes as long as its
+        // average workgroup at the launch's occupancy or as its longest one beside what the others leave of a unit
+        // (a chunk on a long context among chunks on short ones), whichever is more.
+        auto step_us = [&](double r) {   // r = workgroups per compute unit
+            if (r <= 0.5) return 1.08;
+            if (r <= 1.0) return 1.08 + 0.44 * (r - 0.5);
+            if (r <= 2.0) return 1.3 + 0.65 * (r - 1.0);
+            return 0.975 * r;
+        };
+        // (the longest workgroup shares its unit with as many others as the launch has per unit, but no more than the
+        // launch's work provides over its lifetime; a workgroup's start-up and epilogue, 2.5 us, come once per
+        // workgroup that a unit holds at a time)
+        const double all_steps = (double)tile_steps * geo.Hkv;   // 64-key steps of all workgroups together
+        auto est = [&](double w, double longest, bool merges) {
+            const double r = w / cus;
+            const double beside = std::min(std::min(r, 2.0), all_steps / (longest * cus));
+            const double merge = merges ? 2.0 + 0.03 * std::min(w, 2.0 * cus) + 0.04 * std::max(0.0, w - 2.0 * cus) : 0.0;
+            return std::max(all_steps / w * step_us(r), longest * step_us(beside)) + merge + 2.5 * std::ceil(std::min(r, 2.0));
+        };
+        // With the tile list every tile gets parts by its own number of steps: the longest tile k parts, the others as
+        // many as keep their parts no longer than that tile's (a tile of a short chunk stays whole beside a long one).
+        // Without it (more than kSortedTiles tiles, or a forced value) every tile gets the same number.
+        auto parts_of = [&](int64_t s, int64_t k, bool by_steps) -> int64_t {
+            if (!by_steps) return std::min(k, s);
+            const int64_t longest = (max_tile_steps + k - 1) / k;
+            return std::min((s + longest - 1) / longest, s);
+        };
+        int32_t st[kSortedTiles];   // steps of the listed tiles, in list order
+        if (out.pf_table)
+            for (int64_t i = 0; i < tiles; ++i) st[i] = (int32_t)steps_of(tab[i]);
+        auto entries_of = [&](int64_t k, bool by_steps) -> int64_t {
+            int64_t e = 0;
+            for (int64_t i = 0; i < tiles; ++i) e += parts_of(st[i], k, by_steps);
+            return e;
+        };
+        // what a list of e entries, some of them parts, must fit: the kernel arguments, the counters, the workspace
+        auto list_fits = [&](int64_t e) {
+            return e <= kListEntries && 2 * n_order + 1 + (size_t)e <= (size_t)kInlineSeqs + 1 &&
+                   e * geo.Hkv <= kPrefillSplitUnits && (size_t)e * geo.Hkv * part_bytes <= left;
+        };
+        bool by_steps = false;
         if (units <= kPrefillSplitUnits) {
-            if (geo.pf_split_opt > 0)
+            if (geo.pf_split_opt > 0) {
                 split = std::min<int64_t>(std::min<int64_t>(geo.pf_split_opt, kMaxPrefillSplit), max_tile_steps);
-            else {
-                // Estimated time in microseconds with sp parts per tile, fitted to a sweep of 24 batches x 7 splits on
-                // MI355X (the choice is within 5 % of the best measured split on every one of them).  A workgroup's
-                // 64-key step takes 1.08 us while at most every other compute unit holds a workgroup, 1.3 us with one
-                // workgroup on every unit, 1.95 us with two (the unit then completes a step every 0.98 us, and further
-                // workgroups queue behind); the last workgroup of a tile merges the sp partial results, which costs
-                // 2 us + 0.03 us per workgroup of the launch up to two per unit + 0.04 us for every further one (their
-                // partial results then meet in memory at the same time).  A split must win 5 % over the unsplit tile.
-                const double steps = (double)tile_steps / (double)tiles, cus = (double)geo.num_cus;
-                auto step_us = [&](double r) {   // r = workgroups per compute unit
-                    if (r <= 0.5) return 1.08;
-                    if (r <= 1.0) return 1.08 + 0.44 * (r - 0.5);
-                    if (r <= 2.0) return 1.3 + 0.65 * (r - 1.0);
-                    return 0.975 * r;
-                };
-                auto est = [&](int64_t sp) {
-                    const double w = (double)(units * sp);
-                    const double merge = sp > 1 ? 2.0 + 0.03 * std::min(w, 2.0 * cus) + 0.04 * std::max(0.0, w - 2.0 * cus) : 0.0;
-                    return steps / (double)sp * step_us(w / cus) + merge;
-                };
-                double best = est(1) * 0.95;
-                for (int64_t sp = 2; sp <= kMaxPrefillSplit && sp <= (int64_t)steps; ++sp)
-                    if (est(sp) < best) {
-                        best = est(sp);
+            } else if (out.pf_table) {
+                by_steps = true;
+                double best = est((double)units, (double)max_tile_steps, false) * 0.95;   // a split must win 5 %
+                // (a launch of two or more workgroups per unit whose longest tile is no longer than the units' average
+                // load cannot gain from more workgroups)
+                const bool full = (double)units >= 2.0 * cus && all_steps / cus * 0.975 >= (double)max_tile_steps * 1.95;
+                for (int64_t k = 2; !full && k <= kMaxPrefillSplit && k <= max_tile_steps; ++k) {
+                    const int64_t e = entries_of(k, true);
+                    if (!list_fits(e)) break;
+                    const double t = est((double)(e * geo.Hkv), (double)((max_tile_steps + k - 1) / k), true);
+                    if (t < best) {
+                        best = t;
+                        split = k;
+                    }
+                }
+            } else {
+                const double steps = (double)tile_steps / (double)tiles;   // (every tile the same number of parts)
+                double best = est((double)units, (double)max_tile_steps, false) * 0.95;
+                for (int64_t sp = 2; sp <= kMaxPrefillSplit && sp <= (int64_t)steps; ++sp) {
+                    const double t = est((double)(units * sp), (double)((max_tile_steps + sp - 1) / sp), true);
+                    if (t < best) {
+                        best = t;
                         split = sp;
                     }
+                }
             }
-            const size_t part_bytes = (size_t)(32 * pf_waves) * (geo.hd + 2) * sizeof(float);
-            const size_t left = geo.ws_bytes - std::min(geo.ws_bytes, ((size_t)out.slots * slot_bytes(geo) + 255) / 256 * 256);
+        }
+        if (out.pf_table && split > 1 && !by_steps && !list_fits(entries_of(split, false))) {
+            // a forced number of parts whose list would not fit: the same parts without the list (chunk by chunk)
+            out.pf_size -= (size_t)out.pf_table;
+            out.pf_table = 0;
+        }
+        if (!out.pf_table)
             while (split > 1 && (size_t)units * (size_t)split * part_bytes > left) --split;
+        if (out.pf_table && split > 1) {
+            // (tile, part) entries, by decreasing number of steps of a part; the parts of a tile stay together, in part
+            // order; ties keep the chunk order and, inside a chunk, the later tile first.  Sorted as plain numbers.
+            uint64_t keys[kListEntries];
+            size_t e = 0;
+            int64_t most = 1;
+            for (int64_t i = 0; i < tiles; ++i) {
+                const int64_t s_i = st[i], parts = parts_of(s_i, split, by_steps), per = (s_i + parts - 1) / parts;
+                most = std::max(most, parts);
+                for (int64_t j = 0; j < parts; ++j)
+                    keys[e++] = ((uint64_t)(0xFFFFF - per) << 32) |
+                                (uint32_t)((entry_chunk(tab[i]) << 21) | ((511 - entry_tile(tab[i])) << 12) | (int)(j << 6) | (int)(parts - 1));
+            }
+            std::sort(keys, keys + e);
+            for (size_t i = 0; i < e; ++i) {
+                const uint32_t k = (uint32_t)keys[i];
+                tab[i] = list_entry((int)(k >> 21), 511 - (int)((k >> 12) & 511), (int)((k >> 6) & 63), (int)(k & 63) + 1);
+            }
+            out.pf_size += e - (size_t)out.pf_table;
+            out.pf_table = (int32_t)e;
+            split = most;
         }
         out.pf_split = (int32_t)split;
         // A launch of at most two four-wave workgroups per compute unit is one round: the hardware gives workgroups w
@@ -412,10 +488,7 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
         // keeps the plain descending order).
         if (out.pf_table && geo.pf_table_opt == 1 && split == 1 && out.pf_waves == 4 && geo.num_cus % geo.Hkv == 0) {
             const int64_t half = geo.num_cus / geo.Hkv;   // tile positions whose workgroups arrive first on their unit
-            if (tiles > half && tiles <= 2 * half) {
-                int32_t *const tab = store.pf + (2 * (size_t)out.num_pf + 1);
-                std::reverse(tab + half, tab + tiles);
-            }
+            if (tiles > half && tiles <= 2 * half) std::reverse(tab + half, tab + tiles);
         }
     }
     return OOCO_OK;
@@ -831,7 +904,7 @@ ooco_status ooco_plan(ooco_ctx *ctx, int num_seqs, const int32_t *h_seq_lens, co
     ooco_status st = build_plan(geo, num_seqs, h_seq_lens, h_query_start_loc, h_ctx_lens,
                                 carve_storage(ctx->plan_store.data(), cap), ctx->plan, ctx->err);
     if (st != OOCO_OK) return st;
-    if ((size_t)num_seqs * ctx->Hkv > kCounterInts - kMixedStateInts || 3 * ((size_t)num_seqs + 1) + kSortedTiles > kPlanInts)
+    if ((size_t)num_seqs * ctx->Hkv > kCounterInts - kMixedStateInts || 3 * ((size_t)num_seqs + 1) + kListEntries > kPlanInts)
         return fail(ctx, OOCO_ENOMEM, "ooco_plan: %d sequences exceed the context's counter/plan buffers", num_seqs);
     ctx->plan_valid = true;
     ctx->plan_made = true;
@@ -904,21 +977,27 @@ ooco_status ooco_plan_dry_run(int num_q_heads, int num_kv_heads, int head_dim, i
         const int tile_rows = prefill_tile_rows(num_q_heads / num_kv_heads, pl.pf_waves);
         const int32_t *const pf = pl.pf;
         const int P = pl.num_pf;
-        for (int64_t idx = 0; idx < pl.n_tiles && idx < prefill_cap; ++idx) {
-            int k, t;
+        // (with the tile list a tile is listed where its first part is dispatched)
+        const int64_t n_list = pl.pf_table ? pl.pf_table : pl.n_tiles;
+        int64_t idx = 0;
+        for (int64_t pos = 0; pos < n_list && idx < prefill_cap; ++pos) {
+            int k, t, parts;
             if (pl.pf_table) {
-                const int32_t e = pf[2 * P + 1 + idx];
-                k = e >> 20;
-                t = e & 0xFFFFF;
+                const int32_t e = pf[2 * P + 1 + pos];
+                if (entry_part(e) != 0) continue;
+                k = entry_chunk(e);
+                t = entry_tile(e);
+                parts = entry_parts(e);
             } else {
-                k = (int)(std::upper_bound(pf, pf + P + 1, (int32_t)idx) - pf) - 1;
-                t = (pf[k + 1] - 1) - (int)idx;
+                k = (int)(std::upper_bound(pf, pf + P + 1, (int32_t)pos) - pf) - 1;
+                t = (pf[k + 1] - 1) - (int)pos;
+                parts = pl.pf_split;
             }
             const int i = pf[P + 1 + k];
             const int q0 = h_query_start_loc[i], ql = h_query_start_loc[i + 1] - q0, t0 = t * tile_rows;
-            int32_t *o = prefill_tiles_out + 5 * idx;
+            int32_t *o = prefill_tiles_out + 5 * idx++;
             o[0] = i, o[1] = q0 + t0, o[2] = std::min(tile_rows, ql - t0), o[3] = h_ctx_lens[i] + t0;
-            o[4] = h_seq_lens[i];
+            o[4] = (int32_t)std::min<int64_t>(parts, ((int64_t)o[3] + o[2] + 63) / 64);
         }
     }
     return OOCO_OK;
@@ -935,8 +1014,10 @@ ooco_status ooco_plan_info(const ooco_ctx *ctx, int64_t *decode_waves, int64_t *
     if (workspace_used) {
         size_t bytes = (size_t)ctx->plan.slots * (size_t)ctx->Hq * (ctx->hd + 2) * sizeof(float);
         if (ctx->plan.pf_split > 1)
-            bytes = (bytes + 255) / 256 * 256 + (size_t)ctx->plan.n_tiles * ctx->Hkv * (size_t)ctx->plan.pf_split *
-                                                    (size_t)(32 * ctx->plan.pf_waves) * (ctx->hd + 2) * sizeof(float);
+            bytes = (bytes + 255) / 256 * 256 +
+                    (ctx->plan.pf_table ? (size_t)ctx->plan.pf_table * ctx->Hkv
+                                        : (size_t)ctx->plan.n_tiles * ctx->Hkv * (size_t)ctx->plan.pf_split) *
+                        (size_t)(32 * ctx->plan.pf_waves) * (ctx->hd + 2) * sizeof(float);
         *workspace_used = (int64_t)bytes;
     }
     if (prefill_parts) *prefill_parts = ctx->plan.n_tiles > 0 ? ctx->plan.pf_split : 1;
@@ -1039,7 +1120,7 @@ ooco_status ooco_attn_mixed(ooco_ctx *ctx, const void *q, const void *k_cache, c
     p.counters = ctx->counters;
     {
         const size_t dec_floats = ((size_t)pl.slots * ctx->Hq * (ctx->hd + 2) + 63) / 64 * 64;   // 256-byte aligned
-        const size_t parts = (size_t)pl.n_tiles * ctx->Hkv * (size_t)pl.pf_split;
+        const size_t parts = pl.pf_table ? (size_t)pl.pf_table * ctx->Hkv : (size_t)pl.n_tiles * ctx->Hkv * (size_t)pl.pf_split;
         p.pf_acc = static_cast<float *>(ctx->ws) + dec_floats;
         p.pf_ml = p.pf_acc + parts * (size_t)(32 * pl.pf_waves) * ctx->hd;
         p.pf_counters = ctx->pf_counters;
@@ -1050,6 +1131,7 @@ ooco_status ooco_attn_mixed(ooco_ctx *ctx, const void *q, const void *k_cache, c
     // (a batch without decode work: once per prefill workgroup)
     const int64_t trace_rows = pl.dec_cus > 0 && pl.n_tiles > 0 ? 2 * (int64_t)ctx->num_cus
                                : pl.static_runs > 0           ? (int64_t)pl.static_runs * ctx->Hkv
+                               : pl.pf_table                  ? (int64_t)pl.pf_table * ctx->Hkv
                                                               : (int64_t)pl.n_tiles * ctx->Hkv * pl.pf_split;
     const bool tracing = ctx->opt_trace && ctx->trace_d && (size_t)trace_rows <= kTraceWaves;
     p.trace = tracing ? ctx->trace_d : nullptr;

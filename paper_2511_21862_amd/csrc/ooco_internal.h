@@ -33,9 +33,10 @@ namespace ooco {
 constexpr int kBlockSize = 16;      // tokens per KV block (fixed by the cache layout)
 constexpr int kPrefillCols = 128;   // (row, head) query columns per four-wave prefill workgroup (eight waves: 256)
 constexpr int kInlineSeqs = 960;    // sequences whose cumulative array fits the kernel arguments
-constexpr int kMaxPrefillSplit = 8; // parts a prefill tile's keys may be cut into
+constexpr int kMaxPrefillSplit = 16; // parts a prefill tile's keys may be cut into
 constexpr int kPrefillSplitUnits = 8192;   // (tile, kv head) pairs up to which the split is available
 constexpr int kSortedTiles = 512;    // prefill tiles up to which the plan lists them one by one, most 64-key steps first
+constexpr int kListEntries = 896;    // ... and the most (tile, part) entries that list may have
 constexpr int kMixedStateInts = 4096;      // ints in front of (and including) the ticket counter that the mixed kernel keeps its claims and counters in
 
 struct AttnParams {
@@ -74,10 +75,24 @@ struct AttnParams {
     float *pf_ml;
     int32_t *pf_counters;
     int32_t pf_split;
-    // 1: the prefill array continues with one entry per tile in dispatch order, (chunk of the array << 20) | tile of
-    // the chunk: tiles of all chunks ordered by their number of 64-key steps, the longest first
+    // > 0: the prefill array continues with that many entries, one per (tile, part of its keys) in dispatch order
+    // (see list_entry): the parts of all tiles ordered by their number of 64-key steps, the longest first, the parts
+    // of one tile next to each other in part order.  Workgroup b works on entry b / Hkv for kv head b % Hkv; part j
+    // of the tile whose part 0 is entry e0 writes partial slot (e0 + j) * Hkv + kv head, and pf_counters[e0 * Hkv +
+    // kv head] counts the arrivals.  Every tile has its own number of parts (pf_split is the largest).
     int32_t pf_table;
 };
+
+// Entry of the tile list: chunk of the prefill array (9 bits), tile of the chunk (9 bits), part (6 bits), parts of the
+// tile - 1 (6 bits).  A list exists only for batches of at most kSortedTiles tiles, so both indices fit.
+__host__ __device__ inline int32_t list_entry(int chunk, int tile, int part, int parts)
+{
+    return chunk | (tile << 9) | (part << 18) | ((parts - 1) << 24);
+}
+__host__ __device__ inline int entry_chunk(int32_t e) { return e & 511; }
+__host__ __device__ inline int entry_tile(int32_t e) { return (e >> 9) & 511; }
+__host__ __device__ inline int entry_part(int32_t e) { return (e >> 18) & 63; }
+__host__ __device__ inline int entry_parts(int32_t e) { return ((e >> 24) & 63) + 1; }
 
 struct KernArgs {
     AttnParams p;

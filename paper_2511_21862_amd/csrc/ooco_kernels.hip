@@ -614,6 +614,18 @@ __global__ __launch_bounds__(64, 3) void decode_kernel_lean(const KernArgs a)
 constexpr int kPfThreads = 256;   // threads of the four-wave workgroup (the eight-wave one has 512)
 constexpr int kPfBlocks = 4;    // KV blocks per step
 
+// Entry idx of the plan's array: from device memory if the plan did not fit the kernel arguments, else from the
+// argument block.  The two loads must stay two loads: merged into one load through a selected pointer, the argument
+// block would have to be addressable like memory, and the compiler would copy all 4 KiB of it into every lane's
+// private memory (the empty asm keeps the arms of the branch apart).
+OOCO_DEV int plan_entry(const KernArgs &a, int idx)
+{
+    if (a.p.cum_dev) return a.p.cum_dev[idx];
+    int v = a.cum[idx];
+    asm volatile("" : "+v"(v));
+    return v;
+}
+
 // One workgroup's work on virtual block index `vb` (what blockIdx.x is in the stand-alone kernel): unit vb / split
 // = (tile, kv head), part vb % split of its keys.  `cum_at(i)` reads the prefill array of the plan.  All 256
 // threads of the workgroup call it together; every return is workgroup-uniform.
@@ -651,22 +663,39 @@ OOCO_DEV void prefill_unit(const AttnParams &p, CumAt cum_at, const int vb, uint
             phase_bits |= (dt < 0xFFFFu ? dt : (uint64_t)0xFFFFu) << (16 * k);
         }
     };
-    // workgroup -> (unit = (tile, kv head), part of the unit's keys)
-    const int split = p.pf_split;
-    const int unit = vb / split;
-    const int part = vb - unit * split;
-    const int tile_idx = unit / p.Hkv;
-    const int kvh = unit - tile_idx * p.Hkv;
+    // workgroup -> (tile, kv head, part of the tile's keys, parts the tile has), and the partial-result slot of
+    // part 0 of that (tile, kv head) with the distance between the slots of consecutive parts.  With the tile list
+    // every tile has its own number of parts; without it vb = ((tile * Hkv) + kv head) * pf_split + part.
+    int split, part, tile_idx, kvh, list_raw = 0;
+    int slot0, slot_step;   // (at most kPrefillSplitUnits * kMaxPrefillSplit slots)
+    if (p.pf_table) {
+        const int entry = min(vb / p.Hkv, p.pf_table - 1);
+        kvh = vb - (vb / p.Hkv) * p.Hkv;
+        list_raw = cum_at(2 * p.num_pf + 1 + entry);
+        const int list_e = __builtin_amdgcn_readfirstlane(list_raw);   // (the same in every lane)
+        part = entry_part(list_e);
+        split = entry_parts(list_e);
+        tile_idx = 0;   // (looked up from the entry below)
+        slot0 = (entry - part) * p.Hkv + kvh;
+        slot_step = p.Hkv;
+    } else {
+        split = p.pf_split;
+        const int unit = vb / split;
+        part = vb - unit * split;
+        tile_idx = unit / p.Hkv;
+        kvh = unit - tile_idx * p.Hkv;
+        slot0 = unit * split;
+        slot_step = 1;
+    }
 
     // tile -> (sequence, tile of the sequence); tiles of a sequence are taken last-first because
     // the later rows of a chunk see more keys and the hardware dispatches in index order
     int seq, q_row0, rows, pos0, seq_len;
     {
         int chunk, t;
-        if (p.pf_table) {   // the plan lists the tiles one by one: (chunk << 20) | tile of the chunk
-            const int e = cum_at(2 * p.num_pf + 1 + min(tile_idx, p.n_tiles - 1));
-            chunk = min(max(e >> 20, 0), p.num_pf - 1);
-            t = e & 0xFFFFF;
+        if (p.pf_table) {   // the plan lists the (tile, part) pairs one by one
+            chunk = min(entry_chunk(list_raw), p.num_pf - 1);
+            t = entry_tile(list_raw);
         } else {
             chunk = __builtin_amdgcn_readfirstlane(count_le(cum_at, p.num_pf, tile_idx, lane));
             t = (cum_at(chunk + 1) - 1) - tile_idx;       // reversed order inside the sequence
@@ -1032,14 +1061,15 @@ OOCO_DEV void prefill_unit(const AttnParams &p, CumAt cum_at, const int vb, uint
         ltot = x + y;
     }
     if (nparts > 1) {
+        // (one counter per (tile, kv head): the slot of its part 0 with the list, the unit's index without)
+        const int counter_idx = p.pf_table ? slot0 : slot0 / split;
         // ---- partial result of this part, arrival count, merge by the part that arrives last (same
         // device-scope accesses as the decode kernel).  Lane (col, h) of wave w owns column c = 32w + col,
         // dims 32mb + 8q4 + 4h + 0..3.  m is the same in both lane halves; ltot already sums them.
-        const int64_t pbase = (int64_t)unit * split;
         // layout of a part: [wave][mb][q4][lane][4 floats], so that every store and load instruction of a wave
         // covers 1 KiB of contiguous memory
         auto part_ptr = [&](int64_t j, int mb) -> float * {
-            return p.pf_acc + ((((pbase + j) * NW + wave) * MB + mb) * 4 * 64 + lane) * 4;
+            return p.pf_acc + ((((int64_t)(slot0 + (int)j * slot_step) * NW + wave) * MB + mb) * 4 * 64 + lane) * 4;
         };
         {
 #pragma unroll
@@ -1048,13 +1078,13 @@ OOCO_DEV void prefill_unit(const AttnParams &p, CumAt cum_at, const int vb, uint
                 for (int q4 = 0; q4 < 4; ++q4)
                     store_dev4(part_ptr(part, mb) + q4 * 256,
                                f32x4{O[mb][4 * q4], O[mb][4 * q4 + 1], O[mb][4 * q4 + 2], O[mb][4 * q4 + 3]});
-            if (h == 0) store_dev2(p.pf_ml + ((pbase + part) * COLS + c) * 2, m, ltot);
+            if (h == 0) store_dev2(p.pf_ml + ((int64_t)(slot0 + part * slot_step) * COLS + c) * 2, m, ltot);
         }
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's partial has reached memory ...
         __syncthreads();                                    // ... and so have the other waves'
         __shared__ int arrived;
         if (tid == 0)
-            arrived = __hip_atomic_fetch_add(p.pf_counters + unit, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            arrived = __hip_atomic_fetch_add(p.pf_counters + counter_idx, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __syncthreads();
         if (arrived != nparts - 1) return;
         float M = -INFINITY;
@@ -1064,7 +1094,7 @@ OOCO_DEV void prefill_unit(const AttnParams &p, CumAt cum_at, const int vb, uint
 #pragma unroll
             for (int r = 0; r < 16; ++r) O[mb][r] = 0.f;
         for (int j = 0; j < nparts; ++j) {                  // in part order: the result does not depend on who is last
-            const f32x2 ml = load_dev2(p.pf_ml + ((pbase + j) * COLS + c) * 2);
+            const f32x2 ml = load_dev2(p.pf_ml + ((int64_t)(slot0 + j * slot_step) * COLS + c) * 2);
             f32x4 t[4 * MB];   // t[4*mb + q4] = this lane's dims 32mb + 8q4 + 4h + 0..3 of part j
             if constexpr (MB == 4)
                 load_dev_part(t, part_ptr(j, 0), part_ptr(j, 1), part_ptr(j, 2), part_ptr(j, 3));
@@ -1083,7 +1113,7 @@ OOCO_DEV void prefill_unit(const AttnParams &p, CumAt cum_at, const int vb, uint
                 }
         }
         if (tid == 0)   // ready for the next call
-            __hip_atomic_store(p.pf_counters + unit, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(p.pf_counters + counter_idx, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     if (c_valid) {
         const float inv = 1.0f / ltot;
@@ -1113,7 +1143,7 @@ __global__ __launch_bounds__(NW * 64, 8 / NW) void prefill_kernel(const KernArgs
         trace[1] = (__builtin_amdgcn_s_getreg((31 << 11) | 20) & 7u) * 256u + ((__builtin_amdgcn_s_getreg((31 << 11) | 4) >> 8) & 255u);
         trace[2] = 0;   // (a workgroup that leaves before its first step stores no phases)
     }
-    prefill_unit<HD, NW, true>(p, [&](int idx) -> int { return p.cum_dev ? p.cum_dev[idx] : a.cum[idx]; }, (int)blockIdx.x,
+    prefill_unit<HD, NW, true>(p, [&](int idx) -> int { return plan_entry(a, idx); }, (int)blockIdx.x,
                                trace ? trace + 2 : nullptr, t_start);
     if (trace) {
         __syncthreads();
@@ -1127,7 +1157,7 @@ template <int HD>
 __global__ __launch_bounds__(512, 1) __attribute__((amdgpu_num_vgpr(168))) void prefill_kernel_lean(const KernArgs a)
 {
     const AttnParams &p = a.p;
-    prefill_unit<HD, 8, false>(p, [&](int idx) -> int { return p.cum_dev ? p.cum_dev[idx] : a.cum[idx]; }, (int)blockIdx.x);
+    prefill_unit<HD, 8, false>(p, [&](int idx) -> int { return plan_entry(a, idx); }, (int)blockIdx.x);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1166,7 +1196,7 @@ __global__ __launch_bounds__(kPfThreads, 2) void mixed_kernel(const KernArgs a)
     int32_t *const dec_drawn = state + kMixedClaims + 16, *const left = state + kMixedClaims + 17;
     const int n_cum = p.num_seqs + 1;   // the prefill array follows the decode array
     auto dcum_at = [&](int idx) -> int { return p.cum_dev ? p.cum_dev[idx] : a.cum[idx]; };
-    auto pf_at = [&](int idx) -> int { return p.cum_dev ? p.cum_dev[n_cum + idx] : a.cum[n_cum + idx]; };
+    auto pf_at = [&](int idx) -> int { return plan_entry(a, n_cum + idx); };
     const unsigned xcc = __builtin_amdgcn_s_getreg((31 << 11) | 20) & 7u;              // XCC_ID
     if (tid == 0) {
         const unsigned hw = __builtin_amdgcn_s_getreg((31 << 11) | 4);                 // HW_ID: CU, SH, SE ids in bits 8..15
@@ -1201,7 +1231,7 @@ __global__ __launch_bounds__(kPfThreads, 2) void mixed_kernel(const KernArgs a)
         trace[3] = (uint64_t)role;
     }
     const int n_dec_items = p.static_runs * p.Hkv;
-    const int n_vb = p.n_tiles * p.Hkv * p.pf_split;
+    const int n_vb = p.pf_table ? p.pf_table * p.Hkv : p.n_tiles * p.Hkv * p.pf_split;
     const RunLayout L = {p.dec_blocks, p.static_blocks, p.static_runs, 0, p.xcd_cw};
     for (int pass = 0; pass < 2; ++pass, role ^= 1) {
         if (role == 0) {
@@ -1503,7 +1533,8 @@ hipError_t launch_decode(const KernArgs &a, hipStream_t s)
 hipError_t launch_prefill(const KernArgs &a, hipStream_t s)
 {
     if (a.p.n_tiles <= 0) return hipSuccess;
-    const dim3 grid((unsigned)((int64_t)a.p.n_tiles * a.p.Hkv * (a.p.pf_split > 0 ? a.p.pf_split : 1)));
+    const dim3 grid((unsigned)(a.p.pf_table ? (int64_t)a.p.pf_table * a.p.Hkv
+                                            : (int64_t)a.p.n_tiles * a.p.Hkv * (a.p.pf_split > 0 ? a.p.pf_split : 1)));
     if (a.p.hd == 128 && a.p.pf_waves == 8 && a.p.lean)
         hipLaunchKernelGGL((prefill_kernel_lean<128>), grid, dim3(512), 0, s, a);
     else if (a.p.hd == 128 && a.p.pf_waves == 8)

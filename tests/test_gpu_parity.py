@@ -87,7 +87,7 @@ def test_xcd_weighted_decode_runs_agree(Hkv, segments, tail_pct):
     assert_parity(run_gpu(b, options=opts), oracle(b), f"xcd weights Hkv={Hkv} segments={segments}")
 
 
-@pytest.mark.parametrize("split", [0, 2, 3, 8])
+@pytest.mark.parametrize("split", [0, 2, 3, 8, 16])
 def test_prefill_tiles_split_along_the_context_agree(split):
     # each (tile, kv head) cut into `split` parts along its keys, partial results merged by the last part
     # (0 = the planner's own choice, which splits here: few tiles, long context)
@@ -104,6 +104,29 @@ def test_prefill_tiles_split_along_the_context_agree(split):
         first = run_gpu(b, ctx=ctx, options={"prefill_split": split})
         again = run_gpu(b, ctx=ctx)
         assert np.array_equal(first, again)
+
+
+@pytest.mark.parametrize("opts", [{}, {"prefill_sorted": 0}, {"prefill_waves": 8}, {"prefill_sorted": 0, "prefill_split": 5},
+                                  {"mixed_fused": 1, "mixed_dec_cus": 16}])
+def test_chunks_on_long_and_short_contexts_split_by_their_own_steps(opts):
+    # one chunk on a long context among chunks on short ones (and a few decode sequences): by default the long chunk's
+    # tiles are cut into parts and the others stay whole; without the tile list every tile gets the same parts
+    b = W.build_batch(Hq=32, Hkv=8, hd=128, q_lens=[96, 1, 128, 40, 1, 64], ctx_lens=[300, 900, 9000, 0, 64, 2500],
+                      num_blocks=900, seed=87, poison=True)
+    say(f"case: chunks on 0 .. 9000 cached tokens, {opts}")
+    if not opts:
+        plan = B.ooco_plan_dry_run(32, 8, 128, 16, b.max_blocks_per_seq, 256, 128 << 20, b.seq_lens, b.query_start_loc, b.ctx_lens)
+        parts = dict(zip(plan["prefill_tiles"][:, 1].tolist(), plan["prefill_tiles"][:, 4].tolist()))
+        assert max(parts.values()) > 2 and min(parts.values()) == 1
+    ref = oracle(b)
+    assert_parity(run_gpu(b, options=opts), ref, f"long and short contexts {opts}")
+    # prefill chunks only, twice on one context: the counters are back at zero, the bits the same
+    c = W.build_batch(Hq=28, Hkv=4, hd=128, q_lens=[96, 130, 40], ctx_lens=[300, 7000, 0], num_blocks=600, seed=88, poison=True)
+    with B.Context(c.Hq, c.Hkv, c.hd, c.BS, c.num_blocks, c.max_blocks_per_seq) as ctx:
+        first = run_gpu(c, ctx=ctx, options={k: v for k, v in opts.items() if not k.startswith("mixed")})
+        again = run_gpu(c, ctx=ctx)
+        assert np.array_equal(first, again)
+    assert_parity(first, oracle(c), f"prefill-only, long and short contexts {opts}")
 
 
 @pytest.mark.parametrize("opts", [{}, {"prefill_sorted": 0}, {"prefill_sorted": 2}, {"prefill_split": 3}, {"prefill_waves": 8}, {"mixed_lean": 2},

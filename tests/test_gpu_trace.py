@@ -52,7 +52,10 @@ def test_prefill_workgroups_leave_stamps_and_the_output_is_unchanged(opts):
     say(f"case: trace of a prefill-only batch, {opts}")
     got, t, info = traced(b, opts)
     assert np.array_equal(got, run_gpu(b, options=opts))
-    assert len(t) == info["prefill_tiles"] * b.Hkv * info["prefill_parts"] and len(t) > 0
+    # one workgroup per (tile, part, kv head); a tile never has more parts than 64-key steps
+    assert info["prefill_tiles"] * b.Hkv <= len(t) <= info["prefill_tiles"] * b.Hkv * info["prefill_parts"]
+    if "prefill_split" in opts:
+        assert len(t) > info["prefill_tiles"] * b.Hkv
     t = t.astype(np.int64)
     assert (t[:, 0] > 0).all() and (t[:, 0] <= t[:, 3]).all()
     assert t[:, 3].max() - t[:, 0].min() < 100 * 5000

@@ -243,17 +243,43 @@ def test_prefill_tiles_are_split_only_when_the_batch_cannot_occupy_the_gpu():
         assert prefill_parts(n, c, prior) == 1, (n, c, prior)
     # a few tiles walking a long context alone are cut up; fewer parts the more tiles there are
     p1, p4, p8 = (prefill_parts(n, 128, 8192) for n in (1, 4, 8))
-    assert 8 >= p1 > p4 >= p8 >= 1 and p4 >= 2
+    assert 16 >= p1 > p4 >= p8 >= 1 and p4 >= 2
     # no context to cut: one 64-key step per part at least
     assert prefill_parts(1, 128, 0) == 1
     assert prefill_parts(1, 32, 100, prefill_split=8) <= 3
-    # forced values are honoured up to 8; the workspace bounds the parts (66,560 bytes each here)
+    # forced values are honoured up to 16; the workspace bounds the parts (66,560 bytes each here)
     assert prefill_parts(1, 128, 8192, prefill_split=3) == 3
-    assert prefill_parts(1, 128, 8192, prefill_split=50) == 8
+    assert prefill_parts(1, 128, 8192, prefill_split=50) == 16
     assert prefill_parts(1, 128, 8192, prefill_split=8, workspace_bytes=32 * 5 * 66560) == 5
     assert prefill_parts(1, 128, 8192, workspace_bytes=0) == 1
     # decode-only batches report 1
     assert dry([100, 200], [0, 1, 2], [99, 199])["prefill_parts"] == 1
+
+
+def test_tiles_get_parts_by_their_own_number_of_steps():
+    # a chunk on a long context among chunks on short ones: its tiles are cut up, the others stay whole, and no part is
+    # longer than the longest tile's parts; forced values give every tile the same number of parts
+    ql = np.array([128, 128, 128, 128, 1], np.int32)
+    cx = np.array([256, 16384, 300, 256, 77], np.int32)
+    qsl = np.zeros(len(ql) + 1, np.int32)
+    qsl[1:] = np.cumsum(ql)
+    plan = dry(cx + ql, qsl, cx)
+    t = plan["prefill_tiles"]
+    steps = (t[:, 3] + t[:, 2] + 63) // 64
+    k = plan["prefill_parts"]
+    assert 4 <= k <= 16 and (t[t[:, 0] == 1, 4] == k).all() and (t[t[:, 0] != 1, 4] == 1).all()
+    longest = -(-steps.max() // k)
+    assert (-(-steps // t[:, 4]) <= longest).all()
+    check_cover(W.Batch(Hq=32, Hkv=8, hd=128, BS=16, num_blocks=1, block_tables=np.zeros((5, 1), np.int32), seq_lens=cx + ql,
+                        ctx_lens=cx, query_start_loc=qsl, q=None, k_cache=None, v_cache=None), plan)
+    # the first parts go out by decreasing length of a part
+    per = -(-steps // t[:, 4])
+    assert (np.diff(per) <= 0).all()
+    forced = dry(cx + ql, qsl, cx, prefill_split=4)["prefill_tiles"]
+    assert (forced[:, 4] == np.minimum(4, (forced[:, 3] + forced[:, 2] + 63) // 64)).all()
+    # a batch of equal chunks gets equal parts
+    eq = dry([8192 + 128] * 2, [0, 128, 256], [8192] * 2)
+    assert len(set(eq["prefill_tiles"][:, 4].tolist())) == 1 and eq["prefill_parts"] > 1
 
 
 def test_few_prefill_tiles_are_dispatched_longest_first_across_chunks():
