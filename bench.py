@@ -90,7 +90,7 @@ def make_workload(name):
         need = sum((c + q + 15) // 16 for q, c in zip(ql, cx))
         b = W.build_batch(Hq=32, Hkv=8, hd=128, q_lens=ql, ctx_lens=cx, num_blocks=max(4096, 5 * need), seed=3, device="cuda",
                           name=name)
-        return b, "prefill"
+        return b, ("decode" if 1 in ql else "prefill")     # (items of one row are decode sequences)
     if name.startswith("shape-"):   # shape-<Hq>-<Hkv>-<hd>: 256 decode sequences of 512-4096 tokens with another head shape
         Hq, Hkv, hd = (int(x) for x in name.split("-")[1:4])
         rng = np.random.default_rng(77)

@@ -182,7 +182,8 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
     // traffic is not what bounds the kernel) and its 220-register waves leave no room for decode waves beside
     // them, so four waves are the default; eight (head_dim 128 only) stay selectable.
     // The register-lean pair for batches with both kinds of work (lean_opt 2 = whenever the batch is mixed; 1 = when
-    // it pays: every compute unit gets at least one eight-wave prefill workgroup, and the prefill part, by itself,
+    // it pays: every compute unit gets at least one eight-wave prefill workgroup -- counting the parts of 16 or more
+    // 64-key steps that tiles on a long context can be cut into --, and the prefill part, by itself,
     // would take between 0.30 and 4 times as long as the decode part -- estimated from the batch's FLOPs and bytes
     // at 1.05 PFLOP/s and 6.8 TB/s).  Measured on MI355X, 32/8 heads, 128 decode sequences of 1.4 GB in all: beside
     // 2 x 2048 rows 319 -> 291 us, beside 8 x 512 rows 286 -> 270 us, but beside 4 x 512 rows 257 -> 263 us and beside
@@ -192,20 +193,22 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
     bool lean = false;
     if (geo.lean_opt && geo.hd == 128 && !geo.fused && num_seqs > 0) {
         const int rows8 = prefill_tile_rows(geo.Hq / geo.Hkv, 8);
-        int64_t n_dec = 0, tiles8 = 0, dec_blk = 0;
+        int64_t n_dec = 0, tiles8 = 0, wgs8 = 0, dec_blk = 0;
         double pairs = 0.0;
         for (int i = 0; i < num_seqs; ++i) {
             const int64_t ql = (int64_t)h_query_start_loc[i + 1] - h_query_start_loc[i];
             n_dec += ql == 1;
             if (ql == 1) dec_blk += ((int64_t)h_seq_lens[i] + BS - 1) / BS;
             if (ql > 1) {
-                tiles8 += (ql + rows8 - 1) / rows8;
+                const int64_t t8 = (ql + rows8 - 1) / rows8, parts = ((int64_t)h_seq_lens[i] + 63) / 64 / 16;
+                tiles8 += t8;
+                wgs8 += t8 * std::min<int64_t>(std::max<int64_t>(parts, 1), kMaxPrefillSplit);
                 pairs += (double)ql * (double)h_ctx_lens[i] + (double)ql * (double)(ql + 1) / 2.0;
             }
         }
         const double t_pf = 4.0 * geo.Hq * geo.hd * pairs / 1.05e15;
         const double t_dec = (double)dec_blk * BS * 2.0 * geo.Hkv * geo.hd * 2.0 / 6.8e12;
-        const bool pays = tiles8 * geo.Hkv >= (int64_t)geo.num_cus && t_pf >= 0.30 * t_dec && t_pf <= 4.0 * t_dec;
+        const bool pays = wgs8 * geo.Hkv >= (int64_t)geo.num_cus && t_pf >= 0.30 * t_dec && t_pf <= 4.0 * t_dec;
         lean = n_dec > 0 && tiles8 > 0 && (geo.lean_opt >= 2 || pays);
     }
     out.lean = lean;
@@ -391,12 +394,29 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
         // (the longest workgroup shares its unit with as many others as the launch has per unit, but no more than the
         // launch's work provides over its lifetime; a workgroup's start-up and epilogue, 2.5 us, come once per
         // workgroup that a unit holds at a time)
+        // A compute unit holds ONE prefill workgroup, not two, when the workgroups have eight waves or when decode waves
+        // share its registers (a batch with both kinds of work): such a workgroup counts as two, and beside decode
+        // waves it never has a unit to itself.
+        // (... a decode part, that is, which by its bytes lasts at least half as long as the prefill part by its FLOPs)
+        const bool beside_decode = dec_blocks > 0 && !geo.fused &&
+                                   (double)kv_blocks * BS * 2.0 * geo.Hkv * geo.hd * 2.0 / 6.8e12 >= 0.5 * 4.0 * geo.Hq * geo.hd * pf_pairs / 1.05e15;
+        const double wg_weight = beside_decode || pf_waves == 8 ? 2.0 : 1.0;
         const double all_steps = (double)tile_steps * geo.Hkv;   // 64-key steps of all workgroups together
-        auto est = [&](double w, double longest, bool merges) {
-            const double r = w / cus;
-            const double beside = std::min(std::min(r, 2.0), all_steps / (longest * cus));
+        // w workgroups, w_big of them at least half as long as the longest one (`longest` steps)
+        auto est = [&](double w, double w_big, double longest, bool merges) {
+            const double r = wg_weight * w / cus;
+            const double beside = beside_decode ? 2.0 : std::min(std::min(r, 2.0), wg_weight * all_steps / (longest * cus));
             const double merge = merges ? 2.0 + 0.03 * std::min(w, 2.0 * cus) + 0.04 * std::max(0.0, w - 2.0 * cus) : 0.0;
-            return std::max(all_steps / w * step_us(r), longest * step_us(beside)) + merge + 2.5 * std::ceil(std::min(r, 2.0));
+            double average = all_steps / w * step_us(r);
+            if (r > 2.0 && merges) {
+                // more workgroups than fit at a time: the units work through them at full occupancy, and the long ones
+                // go in rounds (up to four rounds count whole: the parts of a split tile are equally long, and 2.5
+                // rounds of them take as long as 3; whole tiles of many lengths pack better than that)
+                double rounds = wg_weight * w_big / (2.0 * cus);
+                if (rounds <= 4.0) rounds = std::ceil(rounds - 1e-9);
+                average = std::max(average, rounds * longest * 1.95);
+            }
+            return std::max(average, longest * step_us(beside)) + merge + 2.5 * std::ceil(std::min(r, 2.0));
         };
         // With the tile list every tile gets parts by its own number of steps: the longest tile k parts, the others as
         // many as keep their parts no longer than that tile's (a tile of a short chunk stays whole beside a long one).
@@ -409,9 +429,15 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
         int32_t st[kSortedTiles];   // steps of the listed tiles, in list order
         if (out.pf_table)
             for (int64_t i = 0; i < tiles; ++i) st[i] = (int32_t)steps_of(tab[i]);
-        auto entries_of = [&](int64_t k, bool by_steps) -> int64_t {
-            int64_t e = 0;
-            for (int64_t i = 0; i < tiles; ++i) e += parts_of(st[i], k, by_steps);
+        auto entries_of = [&](int64_t k, bool by_steps, int64_t *big = nullptr) -> int64_t {
+            const int64_t longest = (max_tile_steps + k - 1) / k;
+            int64_t e = 0, b = 0;
+            for (int64_t i = 0; i < tiles; ++i) {
+                const int64_t parts = parts_of(st[i], k, by_steps);
+                e += parts;
+                if (2 * ((st[i] + parts - 1) / parts) >= longest) b += parts;
+            }
+            if (big) *big = b;
             return e;
         };
         // what a list of e entries, some of them parts, must fit: the kernel arguments, the counters, the workspace
@@ -425,14 +451,16 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
                 split = std::min<int64_t>(std::min<int64_t>(geo.pf_split_opt, kMaxPrefillSplit), max_tile_steps);
             } else if (out.pf_table) {
                 by_steps = true;
-                double best = est((double)units, (double)max_tile_steps, false) * 0.95;   // a split must win 5 %
+                int64_t big = 0;
+                (void)entries_of(1, true, &big);
+                double best = est((double)units, (double)(big * geo.Hkv), (double)max_tile_steps, false) * 0.95;   // a split must win 5 %
                 // (a launch of two or more workgroups per unit whose longest tile is no longer than the units' average
                 // load cannot gain from more workgroups)
-                const bool full = (double)units >= 2.0 * cus && all_steps / cus * 0.975 >= (double)max_tile_steps * 1.95;
+                const bool full = wg_weight * (double)units >= 2.0 * cus && wg_weight * all_steps / cus * 0.975 >= (double)max_tile_steps * 1.95;
                 for (int64_t k = 2; !full && k <= kMaxPrefillSplit && k <= max_tile_steps; ++k) {
-                    const int64_t e = entries_of(k, true);
+                    const int64_t e = entries_of(k, true, &big);
                     if (!list_fits(e)) break;
-                    const double t = est((double)(e * geo.Hkv), (double)((max_tile_steps + k - 1) / k), true);
+                    const double t = est((double)(e * geo.Hkv), (double)(big * geo.Hkv), (double)((max_tile_steps + k - 1) / k), true);
                     if (t < best) {
                         best = t;
                         split = k;
@@ -440,9 +468,9 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
                 }
             } else {
                 const double steps = (double)tile_steps / (double)tiles;   // (every tile the same number of parts)
-                double best = est((double)units, (double)max_tile_steps, false) * 0.95;
+                double best = est((double)units, (double)units, (double)max_tile_steps, false) * 0.95;
                 for (int64_t sp = 2; sp <= kMaxPrefillSplit && sp <= (int64_t)steps; ++sp) {
-                    const double t = est((double)(units * sp), (double)((max_tile_steps + sp - 1) / sp), true);
+                    const double t = est((double)(units * sp), (double)(units * sp), (double)((max_tile_steps + sp - 1) / sp), true);
                     if (t < best) {
                         best = t;
                         split = sp;
