@@ -128,7 +128,7 @@ const char *ooco_last_error(const ooco_ctx *ctx);
  *                         results (held in the workspace).  0 (default) = automatic: split only
  *                         when the batch cannot occupy the compute units, or when a few tiles on a long context
  *                         would run on long after all others, and an estimate of the kernel time improves by at
- *                         least 5 %; in a batch of at most 512 tiles every tile then gets parts by its own number of
+ *                         least 3 %; in a batch of at most 512 tiles every tile then gets parts by its own number of
  *                         steps (the tile with the most steps k parts, the others as many as keep their parts no
  *                         longer than that tile's), so that a chunk on a short context stays whole beside one on a
  *                         long context.  A tile never gets more parts than it has 64-key steps.

@@ -453,7 +453,7 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
                 by_steps = true;
                 int64_t big = 0;
                 (void)entries_of(1, true, &big);
-                double best = est((double)units, (double)(big * geo.Hkv), (double)max_tile_steps, false) * 0.95;   // a split must win 5 %
+                double best = est((double)units, (double)(big * geo.Hkv), (double)max_tile_steps, false) * 0.97;   // a split must win 3 %
                 // (a launch of two or more workgroups per unit whose longest tile is no longer than the units' average
                 // load cannot gain from more workgroups)
                 const bool full = wg_weight * (double)units >= 2.0 * cus && wg_weight * all_steps / cus * 0.975 >= (double)max_tile_steps * 1.95;
@@ -468,7 +468,7 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
                 }
             } else {
                 const double steps = (double)tile_steps / (double)tiles;   // (every tile the same number of parts)
-                double best = est((double)units, (double)units, (double)max_tile_steps, false) * 0.95;
+                double best = est((double)units, (double)units, (double)max_tile_steps, false) * 0.97;
                 for (int64_t sp = 2; sp <= kMaxPrefillSplit && sp <= (int64_t)steps; ++sp) {
                     const double t = est((double)(units * sp), (double)(units * sp), (double)((max_tile_steps + sp - 1) / sp), true);
                     if (t < best) {
