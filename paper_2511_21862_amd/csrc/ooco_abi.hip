@@ -104,6 +104,7 @@ struct HostPlan {
     uint16_t cw[kXcds] = {};     // XCD weights in force (RunLayout::cw)
     int32_t n_tiles = 0, total_q = 0, num_seqs = 0;
     int32_t pf_split = 1;        // parts a prefill tile's keys are cut into (with the tile list: the most any tile has)
+    int64_t pf_slots = 0;        // partial-result slots of the split tiles per kv head (with the list: its leading entries that are parts)
     int32_t pf_waves = 4;        // waves per prefill workgroup (32 query columns each)
     // mixed batches (head_dim 128): the register-lean pair of kernels -- prefill workgroups of eight waves (176
     // registers, no software pipeline) and decode waves of 144 registers, four per compute unit -- so that a SIMD
@@ -266,6 +267,7 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
         pf[k + 1] = pf[k] + (int32_t)((ql + tile_rows - 1) / tile_rows);
         pf[n_order + 1 + k] = order[k];
     }
+    int32_t st[kSortedTiles];   // with the tile list: 64-key steps of the listed tiles, in list order
     auto steps_of = [&](int32_t e) -> int64_t {   // 64-key steps of the tile a list entry names
         const int i = order[entry_chunk(e)];
         const int64_t ql = (int64_t)h_query_start_loc[i + 1] - h_query_start_loc[i], t0 = (int64_t)entry_tile(e) * tile_rows;
@@ -276,15 +278,19 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
     // steps (a chunk on a short context has fewer steps in its last tile than one on a long context in its first).
     // (only while the longer array still travels in the kernel arguments)
     if (geo.pf_table_opt && tiles > 0 && tiles <= kSortedTiles && 2 * n_order + 1 + (size_t)tiles <= (size_t)kInlineSeqs + 1) {
+        // (ties keep the chunk order and, inside a chunk, the later tile first; sorted as plain numbers: steps
+        // descending in the high half, chunk and descending tile below)
         int32_t *const tab = pf + out.pf_size;
+        uint64_t keys[kSortedTiles];
         size_t n = 0;
         for (size_t k = 0; k < n_order; ++k)
-            for (int32_t t = pf[k + 1] - pf[k] - 1; t >= 0; --t) tab[n++] = list_entry((int)k, t, 0, 1);
-        // (ties keep the chunk order and, inside a chunk, the later tile first)
-        std::sort(tab, tab + n, [&](int32_t x, int32_t y) {
-            const int64_t sx = steps_of(x), sy = steps_of(y);
-            return sx != sy ? sx > sy : entry_chunk(x) != entry_chunk(y) ? entry_chunk(x) < entry_chunk(y) : entry_tile(x) > entry_tile(y);
-        });
+            for (int32_t t = pf[k + 1] - pf[k] - 1; t >= 0; --t)
+                keys[n++] = ((uint64_t)(0xFFFFF - steps_of(list_entry((int)k, t, 0, 1))) << 32) | (uint32_t)((k << 10) | (uint32_t)(1023 - t));
+        std::sort(keys, keys + n);
+        for (size_t i = 0; i < n; ++i) {
+            tab[i] = list_entry((int)((uint32_t)keys[i] >> 10), 1023 - (int)((uint32_t)keys[i] & 1023u), 0, 1);
+            st[i] = (int32_t)(0xFFFFF - (keys[i] >> 32));
+        }
         out.pf_size += n;
         out.pf_table = (int32_t)n;
     }
@@ -402,11 +408,13 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
                                    (double)kv_blocks * BS * 2.0 * geo.Hkv * geo.hd * 2.0 / 6.8e12 >= 0.5 * 4.0 * geo.Hq * geo.hd * pf_pairs / 1.05e15;
         const double wg_weight = beside_decode || pf_waves == 8 ? 2.0 : 1.0;
         const double all_steps = (double)tile_steps * geo.Hkv;   // 64-key steps of all workgroups together
-        // w workgroups, w_big of them at least half as long as the longest one (`longest` steps)
-        auto est = [&](double w, double w_big, double longest, bool merges) {
+        // w workgroups, w_big of them at least half as long as the longest one (`longest` steps), w_parts of them parts
+        // of split tiles (which write partial results that the last of them merges)
+        auto est = [&](double w, double w_big, double w_parts, double longest) {
+            const bool merges = w_parts > 0.0;
             const double r = wg_weight * w / cus;
             const double beside = beside_decode ? 2.0 : std::min(std::min(r, 2.0), wg_weight * all_steps / (longest * cus));
-            const double merge = merges ? 2.0 + 0.03 * std::min(w, 2.0 * cus) + 0.04 * std::max(0.0, w - 2.0 * cus) : 0.0;
+            const double merge = merges ? 2.0 + 0.03 * std::min(w_parts, 2.0 * cus) + 0.04 * std::max(0.0, w_parts - 2.0 * cus) : 0.0;
             double average = all_steps / w * step_us(r);
             if (r > 2.0 && merges) {
                 // more workgroups than fit at a time: the units work through them at full occupancy, and the long ones
@@ -426,24 +434,24 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
             const int64_t longest = (max_tile_steps + k - 1) / k;
             return std::min((s + longest - 1) / longest, s);
         };
-        int32_t st[kSortedTiles];   // steps of the listed tiles, in list order
-        if (out.pf_table)
-            for (int64_t i = 0; i < tiles; ++i) st[i] = (int32_t)steps_of(tab[i]);
-        auto entries_of = [&](int64_t k, bool by_steps, int64_t *big = nullptr) -> int64_t {
+        auto entries_of = [&](int64_t k, bool by_steps, int64_t *big = nullptr, int64_t *split_ones = nullptr) -> int64_t {
             const int64_t longest = (max_tile_steps + k - 1) / k;
-            int64_t e = 0, b = 0;
+            int64_t e = 0, b = 0, sp = 0;
             for (int64_t i = 0; i < tiles; ++i) {
                 const int64_t parts = parts_of(st[i], k, by_steps);
                 e += parts;
                 if (2 * ((st[i] + parts - 1) / parts) >= longest) b += parts;
+                if (parts > 1) sp += parts;
             }
             if (big) *big = b;
+            if (split_ones) *split_ones = sp;
             return e;
         };
-        // what a list of e entries, some of them parts, must fit: the kernel arguments, the counters, the workspace
-        auto list_fits = [&](int64_t e) {
+        // what a list of e entries, e_parts of them parts of split tiles, must fit: the kernel arguments; the counters
+        // and the workspace (the parts come first in the list, and an entry's index is its partial-result slot)
+        auto list_fits = [&](int64_t e, int64_t e_parts) {
             return e <= kListEntries && 2 * n_order + 1 + (size_t)e <= (size_t)kInlineSeqs + 1 &&
-                   e * geo.Hkv <= kPrefillSplitUnits && (size_t)e * geo.Hkv * part_bytes <= left;
+                   e_parts * geo.Hkv <= kPrefillSplitUnits && (size_t)e_parts * geo.Hkv * part_bytes <= left;
         };
         bool by_steps = false;
         if (units <= kPrefillSplitUnits) {
@@ -451,16 +459,17 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
                 split = std::min<int64_t>(std::min<int64_t>(geo.pf_split_opt, kMaxPrefillSplit), max_tile_steps);
             } else if (out.pf_table) {
                 by_steps = true;
-                int64_t big = 0;
+                int64_t big = 0, split_ones = 0;
                 (void)entries_of(1, true, &big);
-                double best = est((double)units, (double)(big * geo.Hkv), (double)max_tile_steps, false) * 0.97;   // a split must win 3 %
+                double best = est((double)units, (double)(big * geo.Hkv), 0.0, (double)max_tile_steps) * 0.97;   // a split must win 3 %
                 // (a launch of two or more workgroups per unit whose longest tile is no longer than the units' average
                 // load cannot gain from more workgroups)
                 const bool full = wg_weight * (double)units >= 2.0 * cus && wg_weight * all_steps / cus * 0.975 >= (double)max_tile_steps * 1.95;
                 for (int64_t k = 2; !full && k <= kMaxPrefillSplit && k <= max_tile_steps; ++k) {
-                    const int64_t e = entries_of(k, true, &big);
-                    if (!list_fits(e)) break;
-                    const double t = est((double)(e * geo.Hkv), (double)(big * geo.Hkv), (double)((max_tile_steps + k - 1) / k), true);
+                    const int64_t e = entries_of(k, true, &big, &split_ones);
+                    if (!list_fits(e, split_ones)) break;
+                    const double t = est((double)(e * geo.Hkv), (double)(big * geo.Hkv), (double)(split_ones * geo.Hkv),
+                                         (double)((max_tile_steps + k - 1) / k));
                     if (t < best) {
                         best = t;
                         split = k;
@@ -468,9 +477,9 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
                 }
             } else {
                 const double steps = (double)tile_steps / (double)tiles;   // (every tile the same number of parts)
-                double best = est((double)units, (double)units, (double)max_tile_steps, false) * 0.97;
+                double best = est((double)units, (double)units, 0.0, (double)max_tile_steps) * 0.97;
                 for (int64_t sp = 2; sp <= kMaxPrefillSplit && sp <= (int64_t)steps; ++sp) {
-                    const double t = est((double)(units * sp), (double)(units * sp), (double)((max_tile_steps + sp - 1) / sp), true);
+                    const double t = est((double)(units * sp), (double)(units * sp), (double)(units * sp), (double)((max_tile_steps + sp - 1) / sp));
                     if (t < best) {
                         best = t;
                         split = sp;
@@ -478,7 +487,8 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
                 }
             }
         }
-        if (out.pf_table && split > 1 && !by_steps && !list_fits(entries_of(split, false))) {
+        int64_t forced_parts = 0;
+        if (out.pf_table && split > 1 && !by_steps && !list_fits(entries_of(split, false, nullptr, &forced_parts), forced_parts)) {
             // a forced number of parts whose list would not fit: the same parts without the list (chunk by chunk)
             out.pf_size -= (size_t)out.pf_table;
             out.pf_table = 0;
@@ -486,8 +496,9 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
         if (!out.pf_table)
             while (split > 1 && (size_t)units * (size_t)split * part_bytes > left) --split;
         if (out.pf_table && split > 1) {
-            // (tile, part) entries, by decreasing number of steps of a part; the parts of a tile stay together, in part
-            // order; ties keep the chunk order and, inside a chunk, the later tile first.  Sorted as plain numbers.
+            // (tile, part) entries: first the parts of the split tiles, then the whole tiles, each by decreasing number of
+            // steps; the parts of a tile stay together, in part order; ties keep the chunk order and, inside a chunk,
+            // the later tile first.  Sorted as plain numbers.
             uint64_t keys[kListEntries];
             size_t e = 0;
             int64_t most = 1;
@@ -495,17 +506,20 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
                 const int64_t s_i = st[i], parts = parts_of(s_i, split, by_steps), per = (s_i + parts - 1) / parts;
                 most = std::max(most, parts);
                 for (int64_t j = 0; j < parts; ++j)
-                    keys[e++] = ((uint64_t)(0xFFFFF - per) << 32) |
-                                (uint32_t)((entry_chunk(tab[i]) << 21) | ((511 - entry_tile(tab[i])) << 12) | (int)(j << 6) | (int)(parts - 1));
+                    keys[e++] = ((uint64_t)(parts == 1) << 52) | ((uint64_t)(0xFFFFF - per) << 32) | ((uint32_t)entry_chunk(tab[i]) << 22) |
+                                ((uint32_t)(1023 - entry_tile(tab[i])) << 12) | ((uint32_t)j << 6) | (uint32_t)(parts - 1);
             }
             std::sort(keys, keys + e);
             for (size_t i = 0; i < e; ++i) {
                 const uint32_t k = (uint32_t)keys[i];
-                tab[i] = list_entry((int)(k >> 21), 511 - (int)((k >> 12) & 511), (int)((k >> 6) & 63), (int)(k & 63) + 1);
+                tab[i] = list_entry((int)(k >> 22), 1023 - (int)((k >> 12) & 1023u), (int)((k >> 6) & 63u), (int)(k & 63u) + 1);
             }
             out.pf_size += e - (size_t)out.pf_table;
             out.pf_table = (int32_t)e;
             split = most;
+            for (size_t i = 0; i < e && entry_parts(tab[i]) > 1; ++i) ++out.pf_slots;   // (the parts come first)
+        } else if (split > 1) {
+            out.pf_slots = tiles * split;
         }
         out.pf_split = (int32_t)split;
         // A launch of at most two four-wave workgroups per compute unit is one round: the hardware gives workgroups w
@@ -1042,10 +1056,8 @@ ooco_status ooco_plan_info(const ooco_ctx *ctx, int64_t *decode_waves, int64_t *
     if (workspace_used) {
         size_t bytes = (size_t)ctx->plan.slots * (size_t)ctx->Hq * (ctx->hd + 2) * sizeof(float);
         if (ctx->plan.pf_split > 1)
-            bytes = (bytes + 255) / 256 * 256 +
-                    (ctx->plan.pf_table ? (size_t)ctx->plan.pf_table * ctx->Hkv
-                                        : (size_t)ctx->plan.n_tiles * ctx->Hkv * (size_t)ctx->plan.pf_split) *
-                        (size_t)(32 * ctx->plan.pf_waves) * (ctx->hd + 2) * sizeof(float);
+            bytes = (bytes + 255) / 256 * 256 + (size_t)ctx->plan.pf_slots * ctx->Hkv * (size_t)(32 * ctx->plan.pf_waves) *
+                                                    (ctx->hd + 2) * sizeof(float);
         *workspace_used = (int64_t)bytes;
     }
     if (prefill_parts) *prefill_parts = ctx->plan.n_tiles > 0 ? ctx->plan.pf_split : 1;
@@ -1148,12 +1160,19 @@ ooco_status ooco_attn_mixed(ooco_ctx *ctx, const void *q, const void *k_cache, c
     p.counters = ctx->counters;
     {
         const size_t dec_floats = ((size_t)pl.slots * ctx->Hq * (ctx->hd + 2) + 63) / 64 * 64;   // 256-byte aligned
-        const size_t parts = pl.pf_table ? (size_t)pl.pf_table * ctx->Hkv : (size_t)pl.n_tiles * ctx->Hkv * (size_t)pl.pf_split;
+        const size_t parts = (size_t)pl.pf_slots * ctx->Hkv;   // (what the planner checked against the workspace)
         p.pf_acc = static_cast<float *>(ctx->ws) + dec_floats;
         p.pf_ml = p.pf_acc + parts * (size_t)(32 * pl.pf_waves) * ctx->hd;
         p.pf_counters = ctx->pf_counters;
         p.pf_split = pl.pf_split;
         p.pf_table = pl.pf_table;
+        // (what the kernels will address, once more against what the context owns: a plan that does not fit is an error of
+        // this library, reported instead of launched)
+        const size_t pf_end = (dec_floats + parts * (size_t)(32 * pl.pf_waves) * (ctx->hd + 2)) * sizeof(float);
+        if ((pl.pf_split > 1 && (pf_end > ctx->ws_bytes || parts > (size_t)kPrefillSplitUnits)) ||
+            (size_t)pl.slots * ctx->Hq * (ctx->hd + 2) * sizeof(float) > ctx->ws_bytes)
+            return fail(ctx, OOCO_EINVAL, "ooco_attn_mixed: internal error: the plan's partial results (%zu bytes) do not fit the workspace (%zu bytes)",
+                        pf_end, ctx->ws_bytes);
     }
     // (the mixed kernel stamps once per workgroup, the decode kernel once per wave)
     // (a batch without decode work: once per prefill workgroup)

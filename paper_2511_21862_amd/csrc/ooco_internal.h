@@ -35,8 +35,8 @@ constexpr int kPrefillCols = 128;   // (row, head) query columns per four-wave p
 constexpr int kInlineSeqs = 960;    // sequences whose cumulative array fits the kernel arguments
 constexpr int kMaxPrefillSplit = 16; // parts a prefill tile's keys may be cut into
 constexpr int kPrefillSplitUnits = 8192;   // (tile, kv head) pairs up to which the split is available
-constexpr int kSortedTiles = 512;    // prefill tiles up to which the plan lists them one by one, most 64-key steps first
-constexpr int kListEntries = 896;    // ... and the most (tile, part) entries that list may have
+constexpr int kListEntries = 896;    // (tile, part) entries the plan's tile list may have (it lives in the kernel arguments)
+constexpr int kSortedTiles = kListEntries;   // prefill tiles up to which the plan lists them one by one, most 64-key steps first
 constexpr int kMixedStateInts = 4096;      // ints in front of (and including) the ticket counter that the mixed kernel keeps its claims and counters in
 
 struct AttnParams {
@@ -83,16 +83,17 @@ struct AttnParams {
     int32_t pf_table;
 };
 
-// Entry of the tile list: chunk of the prefill array (9 bits), tile of the chunk (9 bits), part (6 bits), parts of the
-// tile - 1 (6 bits).  A list exists only for batches of at most kSortedTiles tiles, so both indices fit.
+// Entry of the tile list: chunk of the prefill array (10 bits), tile of the chunk (10 bits), part (6 bits), parts of
+// the tile - 1 (6 bits).  A list exists only for batches of at most kSortedTiles tiles, so both indices fit.
 __host__ __device__ inline int32_t list_entry(int chunk, int tile, int part, int parts)
 {
-    return chunk | (tile << 9) | (part << 18) | ((parts - 1) << 24);
+    return (int32_t)((uint32_t)chunk | ((uint32_t)tile << 10) | ((uint32_t)part << 20) | ((uint32_t)(parts - 1) << 26));
 }
-__host__ __device__ inline int entry_chunk(int32_t e) { return e & 511; }
-__host__ __device__ inline int entry_tile(int32_t e) { return (e >> 9) & 511; }
-__host__ __device__ inline int entry_part(int32_t e) { return (e >> 18) & 63; }
-__host__ __device__ inline int entry_parts(int32_t e) { return ((e >> 24) & 63) + 1; }
+__host__ __device__ inline int entry_chunk(int32_t e) { return (int)((uint32_t)e & 1023u); }
+__host__ __device__ inline int entry_tile(int32_t e) { return (int)(((uint32_t)e >> 10) & 1023u); }
+__host__ __device__ inline int entry_part(int32_t e) { return (int)(((uint32_t)e >> 20) & 63u); }
+__host__ __device__ inline int entry_parts(int32_t e) { return (int)(((uint32_t)e >> 26) & 63u) + 1; }
+static_assert(kSortedTiles <= 1024, "tile and chunk indices of a list entry have 10 bits");
 
 struct KernArgs {
     AttnParams p;

@@ -283,7 +283,7 @@ def test_tiles_get_parts_by_their_own_number_of_steps():
 
 
 def test_few_prefill_tiles_are_dispatched_longest_first_across_chunks():
-    # up to 512 tiles: one list entry per tile, by decreasing number of 64-key steps whatever the chunk; ties keep
+    # up to 896 tiles: one list entry per tile, by decreasing number of 64-key steps whatever the chunk; ties keep
     # the chunk order (longest sequence first) and the later tile of a chunk first
     ql = np.array([512, 1, 300, 512, 33, 1, 512, 64, 2], np.int32)
     cx = np.array([1662, 4000, 0, 175, 90, 17, 1781, 700, 5], np.int32)
@@ -313,15 +313,23 @@ def test_few_prefill_tiles_are_dispatched_longest_first_across_chunks():
     qsl3[1:] = np.cumsum(ql3)
     t3 = dry(cx3 + ql3, qsl3, cx3)["prefill_tiles"]
     assert len(t3) == 128 and (np.diff((t3[:, 3] + t3[:, 2] + 63) // 64) <= 0).all()
-    # more than 512 tiles: chunk by chunk, longest sequence first, later tiles first
-    ql2, cx2 = np.array([8192, 8192, 512], np.int32), np.array([100, 5000, 70000], np.int32)
+    # 528 tiles still have a list; the 16 tiles of the chunk on 70,000 cached tokens are cut up and come first
+    ql2, cx2 = np.array([8192, 8192, 512], np.int32), np.array([100, 100, 70000], np.int32)
     qsl2 = np.zeros(4, np.int32)
     qsl2[1:] = np.cumsum(ql2)
     t2 = dry(cx2 + ql2, qsl2, cx2)["prefill_tiles"]
     assert len(t2) == 256 + 256 + 16
-    assert (t2[:16, 0] == 2).all() and (t2[16:272, 0] == 1).all() and (t2[272:, 0] == 0).all()
+    assert (t2[:16, 0] == 2).all() and (t2[:16, 4] > 1).all() and (t2[16:, 4] == 1).all()
+    assert (np.diff((t2[16:, 3] + t2[16:, 2] + 63) // 64) <= 0).all()
+    # more than 896 tiles: chunk by chunk, longest sequence first, later tiles first
+    ql4, cx4 = np.array([16384, 16384, 512], np.int32), np.array([100, 5000, 70000], np.int32)
+    qsl4 = np.zeros(4, np.int32)
+    qsl4[1:] = np.cumsum(ql4)
+    t4 = dry(cx4 + ql4, qsl4, cx4)["prefill_tiles"]
+    assert len(t4) == 512 + 512 + 16
+    assert (t4[:16, 0] == 2).all() and (t4[16:528, 0] == 1).all() and (t4[528:, 0] == 0).all()
     for i in (0, 1, 2):
-        assert (np.diff(t2[t2[:, 0] == i][:, 1]) < 0).all()
+        assert (np.diff(t4[t4[:, 0] == i][:, 1]) < 0).all()
 
 
 def test_lean_pair_is_planned_only_where_the_prefill_part_weighs_enough():
