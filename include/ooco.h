@@ -128,11 +128,11 @@ const char *ooco_last_error(const ooco_ctx *ctx);
  *                         results (held in the workspace).  0 (default) = automatic: split only
  *                         when the batch cannot occupy the compute units, or when a few tiles on a long context
  *                         would run on long after all others, and an estimate of the kernel time improves by at
- *                         least 3 %; in a batch of at most 512 tiles every tile then gets parts by its own number of
+ *                         least 3 %; in a batch of at most 896 tiles every tile then gets parts by its own number of
  *                         steps (the tile with the most steps k parts, the others as many as keep their parts no
  *                         longer than that tile's), so that a chunk on a short context stays whole beside one on a
  *                         long context.  A tile never gets more parts than it has 64-key steps.
- *   "prefill_sorted"      0/1/2 (default 1): a batch of at most 512 prefill tiles dispatches the tiles of ALL its
+ *   "prefill_sorted"      0/1/2 (default 1): a batch of at most 896 prefill tiles dispatches the tiles of ALL its
  *                         chunks -- the parts of its tiles, if they are split -- by decreasing number of 64-key
  *                         steps (one list entry per tile or part, in the kernel arguments; at most 896 entries);
  *                         0 or more tiles: chunk by chunk, longest sequence first, the later tiles of

@@ -473,6 +473,8 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
                     if (t < best) {
                         best = t;
                         split = k;
+                    } else if (k >= split + 4) {
+                        break;   // (four values in a row without a gain: the estimate only grows from here)
                     }
                 }
             } else {
