@@ -90,6 +90,35 @@ def test_random_larger_batch_attention(case):
     assert_parity(run_gpu(b, options=opts), ref, f"larger random {case}")
 
 
+@pytest.mark.parametrize("case", range(10))
+def test_random_long_and_short_contexts(case):
+    # one to three chunks on 4K-40K cached tokens among chunks on short contexts and decode sequences: the planner
+    # cuts the long chunks' tiles into parts by their own number of steps (parts first in its list, whole tiles after)
+    rng = np.random.default_rng(54000 + case)
+    Hq, Hkv, hd = [(32, 8, 128), (28, 4, 128), (64, 8, 128), (8, 1, 128), (16, 2, 64)][case % 5]
+    n_long, n_short, n_dec = int(rng.integers(1, 4)), int(rng.integers(0, 12)), int(rng.choice([0, 0, 3, 40]))
+    ql = np.r_[rng.integers(8, 200, size=n_long), rng.integers(2, 400, size=n_short), np.ones(n_dec, np.int64)]
+    cx = np.r_[(2.0 ** rng.uniform(12, 15.3, size=n_long)).astype(np.int64), rng.integers(0, 600, size=n_short),
+               rng.integers(1, 3000, size=n_dec)]
+    perm = rng.permutation(len(ql))
+    ql, cx = ql[perm].astype(np.int32), cx[perm].astype(np.int32)
+    nblk = int(((cx + ql + 15) // 16).sum()) + 32
+    opts = [{}, {}, {"overlap": 2}, {"prefill_waves": 8}, {}, {"mixed_lean": 2}, {"prefill_sorted": 0}, {}, {"prefill_split": 7}, {}][case]
+    if hd != 128:
+        opts = {k: v for k, v in opts.items() if k not in ("prefill_waves", "mixed_lean")}
+    b = W.build_batch(Hq=Hq, Hkv=Hkv, hd=hd, q_lens=ql, ctx_lens=cx, num_blocks=nblk, seed=7200 + case, poison=True)
+    plan = B.ooco_plan_dry_run(Hq, Hkv, hd, 16, b.max_blocks_per_seq, 256, 128 << 20, b.seq_lens, b.query_start_loc, b.ctx_lens,
+                               prefill_split=opts.get("prefill_split", 0))
+    say(f"case: long and short contexts {case}: {Hq}/{Hkv}/{hd} q_lens={ql.tolist()} ctx={cx.tolist()} options={opts}; "
+        f"parts per tile {sorted(set(plan['prefill_tiles'][:, 4].tolist()))}")
+    ref = ref_c.attn_mixed(b.q, b.k_cache, b.v_cache, b.block_tables, b.seq_lens, b.query_start_loc, b.ctx_lens)
+    with B.Context(b.Hq, b.Hkv, b.hd, b.BS, b.num_blocks, b.max_blocks_per_seq) as ctx:
+        first = run_gpu(b, ctx=ctx, options=opts)
+        again = run_gpu(b, ctx=ctx)                 # (the arrival counters are back at zero)
+    assert_parity(first, ref, f"long and short contexts {case}")
+    assert np.array_equal(first, again)
+
+
 @pytest.mark.parametrize("case", range(N_CASES))
 def test_random_batch_append_and_copy(case):
     rng, b, _ = draw(case)
