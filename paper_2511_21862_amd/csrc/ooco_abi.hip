@@ -1375,6 +1375,8 @@ ooco_status ooco_attn_mixed_static(int num_q_heads, int num_kv_heads, int head_d
                    total_q_tokens);
     if ((size_t)pl.slots * slot_bytes(geo) > geo.ws_bytes)
         return bad(OOCO_ENOMEM, "ooco_attn_mixed_static: partial results of %lld slots exceed the scratch array", (long long)pl.slots);
+    if (pl.pf_split != 1 || pl.pf_slots != 0)   // (this entry point has no area for parts of prefill tiles)
+        return bad(OOCO_EINVAL, "ooco_attn_mixed_static: internal error: the plan splits prefill tiles");
 
     KernArgs ka;
     memset(&ka, 0, sizeof ka);
