@@ -176,6 +176,7 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
     // runs cut the line into equal lengths, so a run that starts several pieces streams correspondingly fewer
     // blocks (starting a piece costs a wave about as long as streaming three 8 KiB tiles).
     int64_t dec_blocks = 0, kv_blocks = 0, tiles = 0, tile_steps = 0, max_tile_steps = 1;
+    int64_t dec_seqs = 0;    // decode sequences that hold at least one block
     double pf_pairs = 0.0;   // visible (query row, key) pairs of all prefill chunks
     const int64_t pad = geo.piece_pad;
     // Waves per prefill workgroup.  Eight waves share every K/V tile staged in LDS among 256 query columns instead
@@ -231,6 +232,7 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
         if (ql == 1) {
             dec_blocks += nb + pad;
             kv_blocks += nb;
+            dec_seqs += nb > 0;
         }
         if (ql > 1) {
             pf_pairs += (double)ql * (double)h_ctx_lens[i] + (double)ql * (double)(ql + 1) / 2.0;
@@ -332,18 +334,29 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
         int64_t wave_slots = lean ? std::max<int64_t>(1, (int64_t)geo.num_cus * 4 / geo.Hkv) : out.dec_cus == 99 ? std::max<int64_t>(1, (int64_t)geo.num_cus * 4 / geo.Hkv)
                                    : out.dec_cus > 0 ? std::max<int64_t>(1, (int64_t)out.dec_cus * kXcds * 8 / geo.Hkv)
                                                    : std::max<int64_t>(1, (int64_t)geo.num_cus * 3 / geo.Hkv);
-        const int64_t min_blocks = 16 * 128 / geo.hd;
         // A small batch (at most 36,864 (block, kv head) tiles of head_dim 128) cannot keep HBM busy anyway: what
         // counts is the length of every wave's chain of dependent steps.  Two blocks per step and at most half the
         // usual number of runs: one 8K-token sequence 21.0 -> 18.3 us, eight sequences (1121 blocks) 25.9 -> 21.4 us,
         // sixteen (2277 blocks) 35.2 -> 31.9 us; from 32 sequences (5296 blocks) on the usual layout is faster.
         // (between 24,576 and 36,864 tiles two thirds of the usual runs: 3814 blocks 49.2 -> 46.6 us; at 4739 blocks the
         // two layouts are level)
-        const bool small = geo.hd == 128 && !lean && out.dec_cus == 0 && kv_blocks * geo.Hkv <= 36864;
+        // A batch of SHORT sequences (24 blocks = 384 tokens on average, or fewer) is a line of many short pieces, each
+        // with its own start (query vectors, first tiles): four waves per compute unit hide those better than three, and
+        // one block per step wastes no padded step.  512 sequences of 128 tokens 58.5 -> 50.9 us, 900 of 64 71.9 -> 62.0,
+        // 2048 of 256 403 -> 382, 1024 of 384 285 -> 275; 4096 of 512 tokens are faster with three waves (1430 / 1449 us).
+        const bool short_seqs = geo.hd == 128 && !lean && out.dec_cus == 0 && dec_seqs > 0 && kv_blocks <= 24 * dec_seqs;
+        const bool small = geo.hd == 128 && !lean && out.dec_cus == 0 && !short_seqs && kv_blocks * geo.Hkv <= 36864;
+        // (up to 16,384 tiles of them two blocks per step, and as many runs as sequences even if those hold fewer than 16
+        // blocks: 32 sequences of 128 tokens 13.0 -> 10.2 us, 64 of 256 15.2 -> 13.2, 128 of 128 17.7 -> 14.8; 128 of 384
+        // tokens, 24,576 tiles: 34.5 / 33.7 us)
         if (small) out.nbi = 2;
+        if (short_seqs) out.nbi = kv_blocks * geo.Hkv <= 16384 ? 2 : 1;
+        if (short_seqs && geo.segments_opt == 0) wave_slots = std::max<int64_t>(1, (int64_t)geo.num_cus * 4 / geo.Hkv);
+        const int64_t min_blocks = 16 * 128 / geo.hd;
         if (small && geo.segments_opt == 0)
             wave_slots = std::max<int64_t>(1, kv_blocks * geo.Hkv <= 24576 ? wave_slots / 2 : wave_slots * 2 / 3);
-        int64_t runs = geo.segments_opt > 0 ? geo.segments_opt : std::min<int64_t>(wave_slots, (kv_blocks + min_blocks - 1) / min_blocks);
+        int64_t runs = geo.segments_opt > 0 ? geo.segments_opt
+                                            : std::min<int64_t>(wave_slots, std::max<int64_t>((kv_blocks + min_blocks - 1) / min_blocks, short_seqs ? dec_seqs : 0));
         runs = std::max<int64_t>(1, std::min<int64_t>(runs, dec_blocks));
         for (;;) {
             // weighted runs come in groups of one run per XCD
