@@ -146,6 +146,187 @@ PlanStorage carve_storage(int32_t *base, size_t seqs_cap)
 }
 constexpr size_t storage_ints(size_t seqs_cap) { return (seqs_cap + 1) + (2 * seqs_cap + 1 + kListEntries) + seqs_cap; }
 
+// What build_plan knows of the batch's prefill part when it decides how the tiles' keys are cut into parts.
+struct PrefillFacts {
+    int64_t tiles, tile_steps, max_tile_steps;   // tiles per kv head, their 64-key steps in all, steps of the longest
+    size_t n_order;                              // prefill chunks
+    const int32_t *st;                           // with the tile list: steps of the listed tiles, in list order
+    int pf_waves;
+    int64_t dec_blocks, kv_blocks;               // decode part: units of its line, KV blocks
+    double pf_pairs;                             // visible (query row, key) pairs of all chunks
+};
+
+// Prefill tiles cut along the context when there are too few of them to occupy the GPU, or when a few of them are far
+// longer than the rest: chooses the parts of every tile, rewrites the tile list as (tile, part) entries, fills
+// out.pf_split / pf_slots / pf_table / pf_size.  `tab` is the tile list inside the plan's prefill array.
+void plan_prefill_parts(const PlanGeometry &geo, const PrefillFacts &f, int32_t *const tab, HostPlan &out)
+{
+    const int64_t tiles = f.tiles, tile_steps = f.tile_steps, max_tile_steps = f.max_tile_steps;
+    const size_t n_order = f.n_order;
+    const int32_t *const st = f.st;
+    const int pf_waves = f.pf_waves;
+    const int64_t dec_blocks = f.dec_blocks, kv_blocks = f.kv_blocks;
+    const double pf_pairs = f.pf_pairs;
+    const int BS = geo.BS;
+    const int64_t units = tiles * geo.Hkv;
+    int64_t split = 1;
+    const size_t part_bytes = (size_t)(32 * pf_waves) * (geo.hd + 2) * sizeof(float);
+    const size_t left = geo.ws_bytes - std::min(geo.ws_bytes, ((size_t)out.slots * slot_bytes(geo) + 255) / 256 * 256);
+    const double cus = (double)geo.num_cus;
+    // Estimated time in microseconds of a launch of w workgroups in all, the longest of them `longest` 64-key steps,
+    // fitted to sweeps of 28 batches of equal chunks x 8 forced splits on MI355X (the choice is within 2.5 % of the best
+    // forced split on every one of them, and better than any forced split on chunks of unequal contexts).  A workgroup's step takes 1.08 us while at most every other compute unit
+    // holds a workgroup, 1.3 us with one workgroup on every unit, 1.95 us with two (the unit then completes a step
+    // every 0.98 us, and further workgroups queue behind); the last workgroup of a tile merges the partial results
+    // of its parts, which costs 2 us + 0.03 us per workgroup of the launch up to two per unit + 0.04 us for every
+    // further one (their partial results then meet in memory at the same time).  The launch takes as long as its
+    // average workgroup at the launch's occupancy or as its longest one beside what the others leave of a unit
+    // (a chunk on a long context among chunks on short ones), whichever is more.
+    auto step_us = [&](double r) {   // r = workgroups per compute unit
+        if (r <= 0.5) return 1.08;
+        if (r <= 1.0) return 1.08 + 0.44 * (r - 0.5);
+        if (r <= 2.0) return 1.3 + 0.65 * (r - 1.0);
+        return 0.975 * r;
+    };
+    // (the longest workgroup shares its unit with as many others as the launch has per unit, but no more than the
+    // launch's work provides over its lifetime; a workgroup's start-up and epilogue, 2.5 us, come once per
+    // workgroup that a unit holds at a time)
+    // A compute unit holds ONE prefill workgroup, not two, when the workgroups have eight waves or when decode waves
+    // share its registers (a batch with both kinds of work): such a workgroup counts as two, and beside decode
+    // waves it never has a unit to itself.
+    // (... a decode part, that is, which by its bytes lasts at least half as long as the prefill part by its FLOPs)
+    const bool beside_decode = dec_blocks > 0 && !geo.fused &&
+                               (double)kv_blocks * BS * 2.0 * geo.Hkv * geo.hd * 2.0 / 6.8e12 >= 0.5 * 4.0 * geo.Hq * geo.hd * pf_pairs / 1.05e15;
+    const double wg_weight = beside_decode || pf_waves == 8 ? 2.0 : 1.0;
+    const double all_steps = (double)tile_steps * geo.Hkv;   // 64-key steps of all workgroups together
+    // w workgroups, w_big of them at least half as long as the longest one (`longest` steps), w_parts of them parts
+    // of split tiles (which write partial results that the last of them merges)
+    auto est = [&](double w, double w_big, double w_parts, double longest) {
+        const bool merges = w_parts > 0.0;
+        const double r = wg_weight * w / cus;
+        const double beside = beside_decode ? 2.0 : std::min(std::min(r, 2.0), wg_weight * all_steps / (longest * cus));
+        const double merge = merges ? 2.0 + 0.03 * std::min(w_parts, 2.0 * cus) + 0.04 * std::max(0.0, w_parts - 2.0 * cus) : 0.0;
+        double average = all_steps / w * step_us(r);
+        if (r > 2.0 && merges) {
+            // more workgroups than fit at a time: the units work through them at full occupancy, and the long ones
+            // go in rounds (up to four rounds count whole: the parts of a split tile are equally long, and 2.5
+            // rounds of them take as long as 3; whole tiles of many lengths pack better than that)
+            double rounds = wg_weight * w_big / (2.0 * cus);
+            if (rounds <= 4.0) rounds = std::ceil(rounds - 1e-9);
+            average = std::max(average, rounds * longest * 1.95);
+        }
+        return std::max(average, longest * step_us(beside)) + merge + 2.5 * std::ceil(std::min(r, 2.0));
+    };
+    // With the tile list every tile gets parts by its own number of steps: the longest tile k parts, the others as
+    // many as keep their parts no longer than that tile's (a tile of a short chunk stays whole beside a long one).
+    // Without it (more than kSortedTiles tiles, or a forced value) every tile gets the same number.
+    auto parts_of = [&](int64_t s, int64_t k, bool by_steps) -> int64_t {
+        if (!by_steps) return std::min(k, s);
+        const int64_t longest = (max_tile_steps + k - 1) / k;
+        return std::min((s + longest - 1) / longest, s);
+    };
+    auto entries_of = [&](int64_t k, bool by_steps, int64_t *big = nullptr, int64_t *split_ones = nullptr) -> int64_t {
+        const int64_t longest = (max_tile_steps + k - 1) / k;
+        int64_t e = 0, b = 0, sp = 0;
+        for (int64_t i = 0; i < tiles; ++i) {
+            const int64_t parts = parts_of(st[i], k, by_steps);
+            e += parts;
+            if (2 * ((st[i] + parts - 1) / parts) >= longest) b += parts;
+            if (parts > 1) sp += parts;
+        }
+        if (big) *big = b;
+        if (split_ones) *split_ones = sp;
+        return e;
+    };
+    // what a list of e entries, e_parts of them parts of split tiles, must fit: the kernel arguments; the counters
+    // and the workspace (the parts come first in the list, and an entry's index is its partial-result slot)
+    auto list_fits = [&](int64_t e, int64_t e_parts) {
+        return e <= kListEntries && 2 * n_order + 1 + (size_t)e <= (size_t)kInlineSeqs + 1 &&
+               e_parts * geo.Hkv <= kPrefillSplitUnits && (size_t)e_parts * geo.Hkv * part_bytes <= left;
+    };
+    bool by_steps = false;
+    if (units <= kPrefillSplitUnits) {
+        if (geo.pf_split_opt > 0) {
+            split = std::min<int64_t>(std::min<int64_t>(geo.pf_split_opt, kMaxPrefillSplit), max_tile_steps);
+        } else if (out.pf_table) {
+            by_steps = true;
+            int64_t big = 0, split_ones = 0;
+            (void)entries_of(1, true, &big);
+            double best = est((double)units, (double)(big * geo.Hkv), 0.0, (double)max_tile_steps) * 0.97;   // a split must win 3 %
+            // (a launch of two or more workgroups per unit whose longest tile is no longer than the units' average
+            // load cannot gain from more workgroups)
+            const bool full = wg_weight * (double)units >= 2.0 * cus && wg_weight * all_steps / cus * 0.975 >= (double)max_tile_steps * 1.95;
+            for (int64_t k = 2; !full && k <= kMaxPrefillSplit && k <= max_tile_steps; ++k) {
+                const int64_t e = entries_of(k, true, &big, &split_ones);
+                if (!list_fits(e, split_ones)) break;
+                const double t = est((double)(e * geo.Hkv), (double)(big * geo.Hkv), (double)(split_ones * geo.Hkv),
+                                     (double)((max_tile_steps + k - 1) / k));
+                if (t < best) {
+                    best = t;
+                    split = k;
+                } else if (k >= split + 4) {
+                    break;   // (four values in a row without a gain: the estimate only grows from here)
+                }
+            }
+        } else {
+            const double steps = (double)tile_steps / (double)tiles;   // (every tile the same number of parts)
+            double best = est((double)units, (double)units, 0.0, (double)max_tile_steps) * 0.97;
+            for (int64_t sp = 2; sp <= kMaxPrefillSplit && sp <= (int64_t)steps; ++sp) {
+                const double t = est((double)(units * sp), (double)(units * sp), (double)(units * sp), (double)((max_tile_steps + sp - 1) / sp));
+                if (t < best) {
+                    best = t;
+                    split = sp;
+                }
+            }
+        }
+    }
+    int64_t forced_parts = 0;
+    if (out.pf_table && split > 1 && !by_steps && !list_fits(entries_of(split, false, nullptr, &forced_parts), forced_parts)) {
+        // a forced number of parts whose list would not fit: the same parts without the list (chunk by chunk)
+        out.pf_size -= (size_t)out.pf_table;
+        out.pf_table = 0;
+    }
+    if (!out.pf_table)
+        while (split > 1 && (size_t)units * (size_t)split * part_bytes > left) --split;
+    if (out.pf_table && split > 1) {
+        // (tile, part) entries: first the parts of the split tiles, then the whole tiles, each by decreasing number of
+        // steps; the parts of a tile stay together, in part order; ties keep the chunk order and, inside a chunk,
+        // the later tile first.  Sorted as plain numbers.
+        uint64_t keys[kListEntries];
+        size_t e = 0;
+        int64_t most = 1;
+        for (int64_t i = 0; i < tiles; ++i) {
+            const int64_t s_i = st[i], parts = parts_of(s_i, split, by_steps), per = (s_i + parts - 1) / parts;
+            most = std::max(most, parts);
+            for (int64_t j = 0; j < parts; ++j)
+                keys[e++] = ((uint64_t)(parts == 1) << 52) | ((uint64_t)(0xFFFFF - per) << 32) | ((uint32_t)entry_chunk(tab[i]) << 22) |
+                            ((uint32_t)(1023 - entry_tile(tab[i])) << 12) | ((uint32_t)j << 6) | (uint32_t)(parts - 1);
+        }
+        std::sort(keys, keys + e);
+        for (size_t i = 0; i < e; ++i) {
+            const uint32_t k = (uint32_t)keys[i];
+            tab[i] = list_entry((int)(k >> 22), 1023 - (int)((k >> 12) & 1023u), (int)((k >> 6) & 63u), (int)(k & 63u) + 1);
+        }
+        out.pf_size += e - (size_t)out.pf_table;
+        out.pf_table = (int32_t)e;
+        split = most;
+        for (size_t i = 0; i < e && entry_parts(tab[i]) > 1; ++i) ++out.pf_slots;   // (the parts come first)
+    } else if (split > 1) {
+        out.pf_slots = tiles * split;
+    }
+    out.pf_split = (int32_t)split;
+    // A launch of at most two four-wave workgroups per compute unit is one round: the hardware gives workgroups w
+    // and w + CUs the same unit, and two workgroups that share a unit each advance at half its rate.  The tile
+    // list then pairs the tile with the most steps with the one with the fewest, and so on (the second half of
+    // the list ascending), so that every unit gets about the same number of steps: on MI355X one chunk of 2048
+    // rows on 1662 cached tokens 102.1 -> 99.6 us, two of 1024 rows 67.5 -> 65.1 us (option "prefill_sorted" = 2
+    // keeps the plain descending order).
+    if (out.pf_table && geo.pf_table_opt == 1 && split == 1 && out.pf_waves == 4 && geo.num_cus % geo.Hkv == 0) {
+        const int64_t half = geo.num_cus / geo.Hkv;   // tile positions whose workgroups arrive first on their unit
+        if (tiles > half && tiles <= 2 * half) std::reverse(tab + half, tab + tiles);
+    }
+}
+
 // Validates the length arrays and builds the plan.  Pure host code, no allocation.
 ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_seq_lens,
                        const int32_t *h_query_start_loc, const int32_t *h_ctx_lens, const PlanStorage &store,
@@ -387,166 +568,10 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
             runs = (runs + 1) / 2;
         }
     }
-    // ---- prefill tiles cut along the context when there are too few of them to occupy the GPU
+    // ---- prefill tiles cut along the context (see plan_prefill_parts)
     if (tiles > 0) {
-        const int64_t units = tiles * geo.Hkv;
-        int64_t split = 1;
-        int32_t *const tab = store.pf + (2 * (size_t)out.num_pf + 1);
-        const size_t part_bytes = (size_t)(32 * pf_waves) * (geo.hd + 2) * sizeof(float);
-        const size_t left = geo.ws_bytes - std::min(geo.ws_bytes, ((size_t)out.slots * slot_bytes(geo) + 255) / 256 * 256);
-        const double cus = (double)geo.num_cus;
-        // Estimated time in microseconds of a launch of w workgroups in all, the longest of them `longest` 64-key steps,
-        // fitted to a sweep of 24 batches of equal chunks x 7 splits on MI355X (the choice is within 5 % of the best
-        // measured split on every one of them).  A workgroup's step takes 1.08 us while at most every other compute unit
-        // holds a workgroup, 1.3 us with one workgroup on every unit, 1.95 us with two (the unit then completes a step
-        // every 0.98 us, and further workgroups queue behind); the last workgroup of a tile merges the partial results
-        // of its parts, which costs 2 us + 0.03 us per workgroup of the launch up to two per unit + 0.04 us for every
-        // further one (their partial results then meet in memory at the same time).  The launch takes as long as its
-        // average workgroup at the launch's occupancy or as its longest one beside what the others leave of a unit
-        // (a chunk on a long context among chunks on short ones), whichever is more.
-        auto step_us = [&](double r) {   // r = workgroups per compute unit
-            if (r <= 0.5) return 1.08;
-            if (r <= 1.0) return 1.08 + 0.44 * (r - 0.5);
-            if (r <= 2.0) return 1.3 + 0.65 * (r - 1.0);
-            return 0.975 * r;
-        };
-        // (the longest workgroup shares its unit with as many others as the launch has per unit, but no more than the
-        // launch's work provides over its lifetime; a workgroup's start-up and epilogue, 2.5 us, come once per
-        // workgroup that a unit holds at a time)
-        // A compute unit holds ONE prefill workgroup, not two, when the workgroups have eight waves or when decode waves
-        // share its registers (a batch with both kinds of work): such a workgroup counts as two, and beside decode
-        // waves it never has a unit to itself.
-        // (... a decode part, that is, which by its bytes lasts at least half as long as the prefill part by its FLOPs)
-        const bool beside_decode = dec_blocks > 0 && !geo.fused &&
-                                   (double)kv_blocks * BS * 2.0 * geo.Hkv * geo.hd * 2.0 / 6.8e12 >= 0.5 * 4.0 * geo.Hq * geo.hd * pf_pairs / 1.05e15;
-        const double wg_weight = beside_decode || pf_waves == 8 ? 2.0 : 1.0;
-        const double all_steps = (double)tile_steps * geo.Hkv;   // 64-key steps of all workgroups together
-        // w workgroups, w_big of them at least half as long as the longest one (`longest` steps), w_parts of them parts
-        // of split tiles (which write partial results that the last of them merges)
-        auto est = [&](double w, double w_big, double w_parts, double longest) {
-            const bool merges = w_parts > 0.0;
-            const double r = wg_weight * w / cus;
-            const double beside = beside_decode ? 2.0 : std::min(std::min(r, 2.0), wg_weight * all_steps / (longest * cus));
-            const double merge = merges ? 2.0 + 0.03 * std::min(w_parts, 2.0 * cus) + 0.04 * std::max(0.0, w_parts - 2.0 * cus) : 0.0;
-            double average = all_steps / w * step_us(r);
-            if (r > 2.0 && merges) {
-                // more workgroups than fit at a time: the units work through them at full occupancy, and the long ones
-                // go in rounds (up to four rounds count whole: the parts of a split tile are equally long, and 2.5
-                // rounds of them take as long as 3; whole tiles of many lengths pack better than that)
-                double rounds = wg_weight * w_big / (2.0 * cus);
-                if (rounds <= 4.0) rounds = std::ceil(rounds - 1e-9);
-                average = std::max(average, rounds * longest * 1.95);
-            }
-            return std::max(average, longest * step_us(beside)) + merge + 2.5 * std::ceil(std::min(r, 2.0));
-        };
-        // With the tile list every tile gets parts by its own number of steps: the longest tile k parts, the others as
-        // many as keep their parts no longer than that tile's (a tile of a short chunk stays whole beside a long one).
-        // Without it (more than kSortedTiles tiles, or a forced value) every tile gets the same number.
-        auto parts_of = [&](int64_t s, int64_t k, bool by_steps) -> int64_t {
-            if (!by_steps) return std::min(k, s);
-            const int64_t longest = (max_tile_steps + k - 1) / k;
-            return std::min((s + longest - 1) / longest, s);
-        };
-        auto entries_of = [&](int64_t k, bool by_steps, int64_t *big = nullptr, int64_t *split_ones = nullptr) -> int64_t {
-            const int64_t longest = (max_tile_steps + k - 1) / k;
-            int64_t e = 0, b = 0, sp = 0;
-            for (int64_t i = 0; i < tiles; ++i) {
-                const int64_t parts = parts_of(st[i], k, by_steps);
-                e += parts;
-                if (2 * ((st[i] + parts - 1) / parts) >= longest) b += parts;
-                if (parts > 1) sp += parts;
-            }
-            if (big) *big = b;
-            if (split_ones) *split_ones = sp;
-            return e;
-        };
-        // what a list of e entries, e_parts of them parts of split tiles, must fit: the kernel arguments; the counters
-        // and the workspace (the parts come first in the list, and an entry's index is its partial-result slot)
-        auto list_fits = [&](int64_t e, int64_t e_parts) {
-            return e <= kListEntries && 2 * n_order + 1 + (size_t)e <= (size_t)kInlineSeqs + 1 &&
-                   e_parts * geo.Hkv <= kPrefillSplitUnits && (size_t)e_parts * geo.Hkv * part_bytes <= left;
-        };
-        bool by_steps = false;
-        if (units <= kPrefillSplitUnits) {
-            if (geo.pf_split_opt > 0) {
-                split = std::min<int64_t>(std::min<int64_t>(geo.pf_split_opt, kMaxPrefillSplit), max_tile_steps);
-            } else if (out.pf_table) {
-                by_steps = true;
-                int64_t big = 0, split_ones = 0;
-                (void)entries_of(1, true, &big);
-                double best = est((double)units, (double)(big * geo.Hkv), 0.0, (double)max_tile_steps) * 0.97;   // a split must win 3 %
-                // (a launch of two or more workgroups per unit whose longest tile is no longer than the units' average
-                // load cannot gain from more workgroups)
-                const bool full = wg_weight * (double)units >= 2.0 * cus && wg_weight * all_steps / cus * 0.975 >= (double)max_tile_steps * 1.95;
-                for (int64_t k = 2; !full && k <= kMaxPrefillSplit && k <= max_tile_steps; ++k) {
-                    const int64_t e = entries_of(k, true, &big, &split_ones);
-                    if (!list_fits(e, split_ones)) break;
-                    const double t = est((double)(e * geo.Hkv), (double)(big * geo.Hkv), (double)(split_ones * geo.Hkv),
-                                         (double)((max_tile_steps + k - 1) / k));
-                    if (t < best) {
-                        best = t;
-                        split = k;
-                    } else if (k >= split + 4) {
-                        break;   // (four values in a row without a gain: the estimate only grows from here)
-                    }
-                }
-            } else {
-                const double steps = (double)tile_steps / (double)tiles;   // (every tile the same number of parts)
-                double best = est((double)units, (double)units, 0.0, (double)max_tile_steps) * 0.97;
-                for (int64_t sp = 2; sp <= kMaxPrefillSplit && sp <= (int64_t)steps; ++sp) {
-                    const double t = est((double)(units * sp), (double)(units * sp), (double)(units * sp), (double)((max_tile_steps + sp - 1) / sp));
-                    if (t < best) {
-                        best = t;
-                        split = sp;
-                    }
-                }
-            }
-        }
-        int64_t forced_parts = 0;
-        if (out.pf_table && split > 1 && !by_steps && !list_fits(entries_of(split, false, nullptr, &forced_parts), forced_parts)) {
-            // a forced number of parts whose list would not fit: the same parts without the list (chunk by chunk)
-            out.pf_size -= (size_t)out.pf_table;
-            out.pf_table = 0;
-        }
-        if (!out.pf_table)
-            while (split > 1 && (size_t)units * (size_t)split * part_bytes > left) --split;
-        if (out.pf_table && split > 1) {
-            // (tile, part) entries: first the parts of the split tiles, then the whole tiles, each by decreasing number of
-            // steps; the parts of a tile stay together, in part order; ties keep the chunk order and, inside a chunk,
-            // the later tile first.  Sorted as plain numbers.
-            uint64_t keys[kListEntries];
-            size_t e = 0;
-            int64_t most = 1;
-            for (int64_t i = 0; i < tiles; ++i) {
-                const int64_t s_i = st[i], parts = parts_of(s_i, split, by_steps), per = (s_i + parts - 1) / parts;
-                most = std::max(most, parts);
-                for (int64_t j = 0; j < parts; ++j)
-                    keys[e++] = ((uint64_t)(parts == 1) << 52) | ((uint64_t)(0xFFFFF - per) << 32) | ((uint32_t)entry_chunk(tab[i]) << 22) |
-                                ((uint32_t)(1023 - entry_tile(tab[i])) << 12) | ((uint32_t)j << 6) | (uint32_t)(parts - 1);
-            }
-            std::sort(keys, keys + e);
-            for (size_t i = 0; i < e; ++i) {
-                const uint32_t k = (uint32_t)keys[i];
-                tab[i] = list_entry((int)(k >> 22), 1023 - (int)((k >> 12) & 1023u), (int)((k >> 6) & 63u), (int)(k & 63u) + 1);
-            }
-            out.pf_size += e - (size_t)out.pf_table;
-            out.pf_table = (int32_t)e;
-            split = most;
-            for (size_t i = 0; i < e && entry_parts(tab[i]) > 1; ++i) ++out.pf_slots;   // (the parts come first)
-        } else if (split > 1) {
-            out.pf_slots = tiles * split;
-        }
-        out.pf_split = (int32_t)split;
-        // A launch of at most two four-wave workgroups per compute unit is one round: the hardware gives workgroups w
-        // and w + CUs the same unit, and two workgroups that share a unit each advance at half its rate.  The tile
-        // list then pairs the tile with the most steps with the one with the fewest, and so on (the second half of
-        // the list ascending), so that every unit gets about the same number of steps: on MI355X one chunk of 2048
-        // rows on 1662 cached tokens 102.1 -> 99.6 us, two of 1024 rows 67.5 -> 65.1 us (option "prefill_sorted" = 2
-        // keeps the plain descending order).
-        if (out.pf_table && geo.pf_table_opt == 1 && split == 1 && out.pf_waves == 4 && geo.num_cus % geo.Hkv == 0) {
-            const int64_t half = geo.num_cus / geo.Hkv;   // tile positions whose workgroups arrive first on their unit
-            if (tiles > half && tiles <= 2 * half) std::reverse(tab + half, tab + tiles);
-        }
+        const PrefillFacts facts = {tiles, tile_steps, max_tile_steps, n_order, st, pf_waves, dec_blocks, kv_blocks, pf_pairs};
+        plan_prefill_parts(geo, facts, store.pf + (2 * (size_t)out.num_pf + 1), out);
     }
     return OOCO_OK;
 }
