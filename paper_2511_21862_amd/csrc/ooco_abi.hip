@@ -146,6 +146,76 @@ PlanStorage carve_storage(int32_t *base, size_t seqs_cap)
 }
 constexpr size_t storage_ints(size_t seqs_cap) { return (seqs_cap + 1) + (2 * seqs_cap + 1 + kListEntries) + seqs_cap; }
 
+// Run layout of the decode block line (see ooco_internal.h): how many static runs, their XCD weights, the dynamic tail,
+// the partial-result slots; fills out.static_runs / static_blocks / tail_runs / slots / cw / nbi.
+// dec_blocks: units of the line (blocks + piece pads), kv_blocks: KV blocks of all decode sequences, dec_seqs: decode
+// sequences that hold a block, lean: the batch runs the register-lean pair of kernels.
+void plan_decode_runs(const PlanGeometry &geo, int num_seqs, int64_t dec_blocks, int64_t kv_blocks, int64_t dec_seqs, bool lean,
+                      HostPlan &out)
+{
+    // static runs: by default three waves per CU (measured best on MI355X: enough loads in
+    // flight to saturate HBM, few enough waves that start-up and partial results stay small)
+    // and at least ~16 blocks of head_dim 128 per wave (a small batch is a chain of dependent blocks per wave:
+    // one sequence of 512 blocks takes 27 us in 16 runs, 21 us in 32, 26 us in 64; eight sequences of 1121 blocks
+    // 30 us in 36 runs, 25 us in 64)
+    // (mixed kernel: eight decode waves on every decoding unit, one run each)
+    int64_t wave_slots = lean ? std::max<int64_t>(1, (int64_t)geo.num_cus * 4 / geo.Hkv) : out.dec_cus == 99 ? std::max<int64_t>(1, (int64_t)geo.num_cus * 4 / geo.Hkv)
+                               : out.dec_cus > 0 ? std::max<int64_t>(1, (int64_t)out.dec_cus * kXcds * 8 / geo.Hkv)
+                                               : std::max<int64_t>(1, (int64_t)geo.num_cus * 3 / geo.Hkv);
+    // A small batch (at most 36,864 (block, kv head) tiles of head_dim 128) cannot keep HBM busy anyway: what
+    // counts is the length of every wave's chain of dependent steps.  Two blocks per step and at most half the
+    // usual number of runs: one 8K-token sequence 21.0 -> 18.3 us, eight sequences (1121 blocks) 25.9 -> 21.4 us,
+    // sixteen (2277 blocks) 35.2 -> 31.9 us; from 32 sequences (5296 blocks) on the usual layout is faster.
+    // (between 24,576 and 36,864 tiles two thirds of the usual runs: 3814 blocks 49.2 -> 46.6 us; at 4739 blocks the
+    // two layouts are level)
+    // A batch of SHORT sequences (24 blocks = 384 tokens on average, or fewer) is a line of many short pieces, each
+    // with its own start (query vectors, first tiles): four waves per compute unit hide those better than three, and
+    // one block per step wastes no padded step.  512 sequences of 128 tokens 58.5 -> 50.9 us, 900 of 64 71.9 -> 62.0,
+    // 2048 of 256 403 -> 382, 1024 of 384 285 -> 275; 4096 of 512 tokens are faster with three waves (1430 / 1449 us).
+    const bool short_seqs = geo.hd == 128 && !lean && out.dec_cus == 0 && dec_seqs > 0 && kv_blocks <= 24 * dec_seqs;
+    const bool small = geo.hd == 128 && !lean && out.dec_cus == 0 && !short_seqs && kv_blocks * geo.Hkv <= 36864;
+    // (up to 16,384 tiles of them two blocks per step, and as many runs as sequences even if those hold fewer than 16
+    // blocks: 32 sequences of 128 tokens 13.0 -> 10.2 us, 64 of 256 15.2 -> 13.2, 128 of 128 17.7 -> 14.8; 128 of 384
+    // tokens, 24,576 tiles: 34.5 / 33.7 us)
+    if (small) out.nbi = 2;
+    if (short_seqs) out.nbi = kv_blocks * geo.Hkv <= 16384 ? 2 : 1;
+    if (short_seqs && geo.segments_opt == 0) wave_slots = std::max<int64_t>(1, (int64_t)geo.num_cus * 4 / geo.Hkv);
+    const int64_t min_blocks = 16 * 128 / geo.hd;
+    if (small && geo.segments_opt == 0)
+        wave_slots = std::max<int64_t>(1, kv_blocks * geo.Hkv <= 24576 ? wave_slots / 2 : wave_slots * 2 / 3);
+    int64_t runs = geo.segments_opt > 0 ? geo.segments_opt
+                                        : std::min<int64_t>(wave_slots, std::max<int64_t>((kv_blocks + min_blocks - 1) / min_blocks, short_seqs ? dec_seqs : 0));
+    runs = std::max<int64_t>(1, std::min<int64_t>(runs, dec_blocks));
+    for (;;) {
+        // weighted runs come in groups of one run per XCD
+        bool weighted = geo.xcd_cw[kXcds - 1] != 0 && runs >= kXcds && out.dec_cus == 0;
+        if (weighted) runs -= runs % kXcds;
+        // dynamic tail: only when a static run is much longer than a tail run
+        int64_t tail_blk = 0, tails = 0;
+        if (geo.tail_pct > 0 && geo.tail_blocks > 0 && dec_blocks / runs >= 4 * geo.tail_blocks && out.dec_cus == 0) {
+            tail_blk = std::min<int64_t>(dec_blocks - runs, dec_blocks * std::min<int64_t>(geo.tail_pct, 90) / 100);
+            tails = (tail_blk + geo.tail_blocks - 1) / geo.tail_blocks;
+            if (tails == 0) tail_blk = 0;
+        }
+        // ... and only for runs long enough that no weight (they differ by at most 4x) empties one
+        if (dec_blocks - tail_blk < 16 * runs) weighted = false;
+        // partial slots: (run index) + seq < runs + tails + num_seqs; one run never splits a sequence
+        const int64_t slots = (runs + tails > 1) ? runs + tails + num_seqs : 0;
+        if ((size_t)slots * slot_bytes(geo) <= geo.ws_bytes || runs == 1) {
+            if ((size_t)slots * slot_bytes(geo) > geo.ws_bytes) {   // a single run, no tail, needs no slots
+                tail_blk = tails = 0;
+            }
+            out.static_runs = (int32_t)runs;
+            for (int k = 0; k < kXcds; ++k) out.cw[k] = weighted ? geo.xcd_cw[k] : 0;
+            out.static_blocks = (int32_t)(dec_blocks - tail_blk);
+            out.tail_runs = (int32_t)tails;
+            out.slots = (runs + tails > 1) ? runs + tails + num_seqs : 0;
+            break;
+        }
+        runs = (runs + 1) / 2;
+    }
+}
+
 // What build_plan knows of the batch's prefill part when it decides how the tiles' keys are cut into parts.
 struct PrefillFacts {
     int64_t tiles, tile_steps, max_tile_steps;   // tiles per kv head, their 64-key steps in all, steps of the longest
@@ -504,70 +574,8 @@ ooco_status build_plan(const PlanGeometry &geo, int num_seqs, const int32_t *h_s
         if (geo.dec_cus_opt == 99) dec = 99;   // every unit runs both kinds (one workgroup each): for measurements
         out.dec_cus = dec;
     }
-    // ---- run layout of the decode block line (see ooco_internal.h)
-    if (dec_blocks > 0) {
-        // static runs: by default three waves per CU (measured best on MI355X: enough loads in
-        // flight to saturate HBM, few enough waves that start-up and partial results stay small)
-        // and at least ~16 blocks of head_dim 128 per wave (a small batch is a chain of dependent blocks per wave:
-        // one sequence of 512 blocks takes 27 us in 16 runs, 21 us in 32, 26 us in 64; eight sequences of 1121 blocks
-        // 30 us in 36 runs, 25 us in 64)
-        // (mixed kernel: eight decode waves on every decoding unit, one run each)
-        int64_t wave_slots = lean ? std::max<int64_t>(1, (int64_t)geo.num_cus * 4 / geo.Hkv) : out.dec_cus == 99 ? std::max<int64_t>(1, (int64_t)geo.num_cus * 4 / geo.Hkv)
-                                   : out.dec_cus > 0 ? std::max<int64_t>(1, (int64_t)out.dec_cus * kXcds * 8 / geo.Hkv)
-                                                   : std::max<int64_t>(1, (int64_t)geo.num_cus * 3 / geo.Hkv);
-        // A small batch (at most 36,864 (block, kv head) tiles of head_dim 128) cannot keep HBM busy anyway: what
-        // counts is the length of every wave's chain of dependent steps.  Two blocks per step and at most half the
-        // usual number of runs: one 8K-token sequence 21.0 -> 18.3 us, eight sequences (1121 blocks) 25.9 -> 21.4 us,
-        // sixteen (2277 blocks) 35.2 -> 31.9 us; from 32 sequences (5296 blocks) on the usual layout is faster.
-        // (between 24,576 and 36,864 tiles two thirds of the usual runs: 3814 blocks 49.2 -> 46.6 us; at 4739 blocks the
-        // two layouts are level)
-        // A batch of SHORT sequences (24 blocks = 384 tokens on average, or fewer) is a line of many short pieces, each
-        // with its own start (query vectors, first tiles): four waves per compute unit hide those better than three, and
-        // one block per step wastes no padded step.  512 sequences of 128 tokens 58.5 -> 50.9 us, 900 of 64 71.9 -> 62.0,
-        // 2048 of 256 403 -> 382, 1024 of 384 285 -> 275; 4096 of 512 tokens are faster with three waves (1430 / 1449 us).
-        const bool short_seqs = geo.hd == 128 && !lean && out.dec_cus == 0 && dec_seqs > 0 && kv_blocks <= 24 * dec_seqs;
-        const bool small = geo.hd == 128 && !lean && out.dec_cus == 0 && !short_seqs && kv_blocks * geo.Hkv <= 36864;
-        // (up to 16,384 tiles of them two blocks per step, and as many runs as sequences even if those hold fewer than 16
-        // blocks: 32 sequences of 128 tokens 13.0 -> 10.2 us, 64 of 256 15.2 -> 13.2, 128 of 128 17.7 -> 14.8; 128 of 384
-        // tokens, 24,576 tiles: 34.5 / 33.7 us)
-        if (small) out.nbi = 2;
-        if (short_seqs) out.nbi = kv_blocks * geo.Hkv <= 16384 ? 2 : 1;
-        if (short_seqs && geo.segments_opt == 0) wave_slots = std::max<int64_t>(1, (int64_t)geo.num_cus * 4 / geo.Hkv);
-        const int64_t min_blocks = 16 * 128 / geo.hd;
-        if (small && geo.segments_opt == 0)
-            wave_slots = std::max<int64_t>(1, kv_blocks * geo.Hkv <= 24576 ? wave_slots / 2 : wave_slots * 2 / 3);
-        int64_t runs = geo.segments_opt > 0 ? geo.segments_opt
-                                            : std::min<int64_t>(wave_slots, std::max<int64_t>((kv_blocks + min_blocks - 1) / min_blocks, short_seqs ? dec_seqs : 0));
-        runs = std::max<int64_t>(1, std::min<int64_t>(runs, dec_blocks));
-        for (;;) {
-            // weighted runs come in groups of one run per XCD
-            bool weighted = geo.xcd_cw[kXcds - 1] != 0 && runs >= kXcds && out.dec_cus == 0;
-            if (weighted) runs -= runs % kXcds;
-            // dynamic tail: only when a static run is much longer than a tail run
-            int64_t tail_blk = 0, tails = 0;
-            if (geo.tail_pct > 0 && geo.tail_blocks > 0 && dec_blocks / runs >= 4 * geo.tail_blocks && out.dec_cus == 0) {
-                tail_blk = std::min<int64_t>(dec_blocks - runs, dec_blocks * std::min<int64_t>(geo.tail_pct, 90) / 100);
-                tails = (tail_blk + geo.tail_blocks - 1) / geo.tail_blocks;
-                if (tails == 0) tail_blk = 0;
-            }
-            // ... and only for runs long enough that no weight (they differ by at most 4x) empties one
-            if (dec_blocks - tail_blk < 16 * runs) weighted = false;
-            // partial slots: (run index) + seq < runs + tails + num_seqs; one run never splits a sequence
-            const int64_t slots = (runs + tails > 1) ? runs + tails + num_seqs : 0;
-            if ((size_t)slots * slot_bytes(geo) <= geo.ws_bytes || runs == 1) {
-                if ((size_t)slots * slot_bytes(geo) > geo.ws_bytes) {   // a single run, no tail, needs no slots
-                    tail_blk = tails = 0;
-                }
-                out.static_runs = (int32_t)runs;
-                for (int k = 0; k < kXcds; ++k) out.cw[k] = weighted ? geo.xcd_cw[k] : 0;
-                out.static_blocks = (int32_t)(dec_blocks - tail_blk);
-                out.tail_runs = (int32_t)tails;
-                out.slots = (runs + tails > 1) ? runs + tails + num_seqs : 0;
-                break;
-            }
-            runs = (runs + 1) / 2;
-        }
-    }
+    // ---- run layout of the decode block line (see plan_decode_runs)
+    if (dec_blocks > 0) plan_decode_runs(geo, num_seqs, dec_blocks, kv_blocks, dec_seqs, lean, out);
     // ---- prefill tiles cut along the context (see plan_prefill_parts)
     if (tiles > 0) {
         const PrefillFacts facts = {tiles, tile_steps, max_tile_steps, n_order, st, pf_waves, dec_blocks, kv_blocks, pf_pairs};
