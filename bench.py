@@ -429,11 +429,12 @@ def wg_timeline(ctx, b, run_step, torch, reps=5):
         base = t0.min()
         t0, t1 = t0 - base, t1 - base
         n = len(t0)
-        steps = np.repeat(steps_tile, n // len(steps_tile))
+        # (with split tiles the list holds (tile, part) entries in an order of its own: no per-workgroup steps then, -1)
+        steps = np.repeat(steps_tile, n // len(steps_tile)) if n == len(steps_tile) * b.Hkv else np.full(n, -1.0)
         r = {"workgroups": n, "compute_units": int(len(np.unique(cu))), "span_us": float(t1.max()),
              "all_first_round_started_by_us": float(np.sort(t0)[min(n, 2 * len(np.unique(cu))) - 1]),
              "slot_busy_us_mean": float((t1 - t0).sum() / (2 * len(np.unique(cu)))),
-             "steps_total": int(steps.sum())}
+             "steps_total": int(steps_tile.sum()) * b.Hkv}
         ends = np.array([t1[cu == c].max() for c in np.unique(cu)])
         r["cu_last_end_us_min_mean_max"] = [float(ends.min()), float(ends.mean()), float(ends.max())]
         eighth = []
