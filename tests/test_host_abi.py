@@ -282,6 +282,33 @@ def test_tiles_get_parts_by_their_own_number_of_steps():
     assert len(set(eq["prefill_tiles"][:, 4].tolist())) == 1 and eq["prefill_parts"] > 1
 
 
+def test_planned_parts_match_the_measured_best_on_the_profiled_batches():
+    # the choices that profiles/prefill_split_rule.md and profiles/mixed_lean_rule.md measure as best or within a few
+    # per cent of the best (256 compute units, 32/8 heads): a change of the cost model that moves one of them needs a new
+    # measurement
+    def parts(ql, cx):
+        ql, cx = np.asarray(ql, np.int32), np.asarray(cx, np.int32)
+        qsl = np.zeros(len(ql) + 1, np.int32)
+        qsl[1:] = np.cumsum(ql)
+        t = dry(cx + ql, qsl, cx)["prefill_tiles"]
+        return {int(i): sorted(set(t[t[:, 0] == i][:, 4].tolist())) for i in np.flatnonzero(ql > 1)}, int(t[:, 2].max())
+    for (n, c, pc), want in (((1, 128, 8192), 8), ((1, 128, 32768), 16), ((4, 128, 8192), 4), ((1, 512, 8192), 4),
+                             ((2, 512, 4096), 2), ((2, 512, 1000), 1), ((8, 128, 2048), 1), ((10, 128, 8192), 1),
+                             ((3, 512, 8192), 1), ((1, 2048, 8192), 1), ((16, 128, 1000), 1)):
+        got, _ = parts([c] * n, [pc] * n)
+        assert all(v == [want] for v in got.values()), ((n, c, pc), got)
+    # chunks on unequal contexts: the long chunk's tiles are cut up, the others stay whole
+    got, _ = parts([256] * 9, [32768] + [512] * 8)
+    assert got[0] == [7] and all(got[i] == [1] for i in range(1, 9))
+    got, _ = parts([2048, 128], [0, 30000])
+    assert got[0] == [1] and 8 <= got[1][0] <= 12
+    # an online chunk on a long prefix beside 128 decode sequences: the lean pair (64-row tiles), one round of workgroups
+    got, rows = parts([512] + [1] * 128, [30000] + [2048] * 128)
+    assert rows == 64 and got[0] == [4]
+    got, rows = parts([512] + [1] * 32, [30000] + [2048] * 32)          # a short decode part: planned as a prefill batch
+    assert rows == 32 and got[0] == [4]
+
+
 def test_few_prefill_tiles_are_dispatched_longest_first_across_chunks():
     # up to 896 tiles: one list entry per tile, by decreasing number of 64-key steps whatever the chunk; ties keep
     # the chunk order (longest sequence first) and the later tile of a chunk first
