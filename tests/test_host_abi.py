@@ -282,6 +282,17 @@ def test_tiles_get_parts_by_their_own_number_of_steps():
     assert len(set(eq["prefill_tiles"][:, 4].tolist())) == 1 and eq["prefill_parts"] > 1
 
 
+def test_decode_runs_of_short_sequence_batches():
+    # profiles/decode_short_sequences_rule.md: sequences of 24 blocks or fewer on average get four waves per compute
+    # unit (128 runs for 8 kv heads) and as many runs as sequences; longer ones three waves and runs of 16 blocks at least
+    def runs(n, tokens):
+        return dry([tokens] * n, list(range(n + 1)), [tokens - 1] * n)["decode_runs"]
+    assert runs(512, 128) == 128 and runs(2048, 256) == 128 and runs(1024, 384) == 128
+    assert runs(32, 128) == 32 and runs(32, 64) == 32 and runs(64, 256) == 64 and runs(8, 128) == 8
+    assert runs(4096, 512) == 96 and runs(256, 8192) == 96 and runs(64, 32768) == 96
+    assert runs(1, 8192) == 32                    # a small batch of one long sequence: 16 blocks per run
+
+
 def test_planned_parts_match_the_measured_best_on_the_profiled_batches():
     # the choices that profiles/prefill_split_rule.md and profiles/mixed_lean_rule.md measure as best or within a few
     # per cent of the best (256 compute units, 32/8 heads): a change of the cost model that moves one of them needs a new
