@@ -626,8 +626,9 @@ OOCO_DEV int plan_entry(const KernArgs &a, int idx)
     return v;
 }
 
-// One workgroup's work on virtual block index `vb` (what blockIdx.x is in the stand-alone kernel): unit vb / split
-// = (tile, kv head), part vb % split of its keys.  `cum_at(i)` reads the prefill array of the plan.  All 256
+// One workgroup's work on virtual block index `vb` (what blockIdx.x is in the stand-alone kernel): with the plan's
+// tile list, entry vb / Hkv of the list -- a (tile, part of its keys) pair -- for kv head vb % Hkv; without it, unit
+// vb / split = (tile, kv head), part vb % split of its keys.  `cum_at(i)` reads the prefill array of the plan.  All
 // threads of the workgroup call it together; every return is workgroup-uniform.
 // NW = waves per workgroup: 4 (128 query columns) or 8 (256 columns: the same K/V tiles in LDS serve twice as many
 // columns, which halves the traffic from L2 into the compute unit per unit of matrix work).
