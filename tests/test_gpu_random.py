@@ -26,6 +26,9 @@ OPTIONS = [{}, {}, {"prefill_split": 2}, {"prefill_split": 5}, {"prefill_sorted"
            {"prefill_waves": 8}, {"mixed_fused": 1}, {"rotate_heads": 0}, {"decode_piece_pad": 5}, {"xcd_weights": sum(w << (8 * k) for k, w in enumerate([100, 60, 140, 95, 105, 85, 115, 100])), "decode_segments": 16}, {"decode_first": 0}]
 bits = lambda t: t.view(torch.int16).cpu().numpy().view(np.uint16)
 N_CASES = int(os.environ.get("OOCO_RANDOM_CASES", "24"))      # set higher for a longer run (400 cases take 90 s)
+FIRST = int(os.environ.get("OOCO_RANDOM_FIRST", "0"))         # first case number (other seeds for a longer run)
+N_LARGER = int(os.environ.get("OOCO_RANDOM_LARGER", "6"))     # larger batches (a few seconds of oracle time each)
+N_LONG = int(os.environ.get("OOCO_RANDOM_LONG", "10"))        # batches of long and short contexts
 
 
 def draw(case):
@@ -47,7 +50,7 @@ def draw(case):
     return rng, b, opts
 
 
-@pytest.mark.parametrize("case", range(N_CASES))
+@pytest.mark.parametrize("case", range(FIRST, FIRST + N_CASES))
 def test_random_batch_attention(case):
     rng, b, opts = draw(case)
     say(f"case: random {case}: {b.Hq}/{b.Hkv}/{b.hd} q_lens={b.q_lens.tolist()} ctx={b.ctx_lens.tolist()} options={opts}")
@@ -64,7 +67,7 @@ def test_random_batch_attention(case):
     assert np.array_equal(bits(out), want), "the entry point that allocates nothing differs from ooco_attn_mixed"
 
 
-@pytest.mark.parametrize("case", range(6))
+@pytest.mark.parametrize("case", range(N_LARGER))
 def test_random_larger_batch_attention(case):
     # batches that fill the GPU for more than one round of workgroups: up to 150 sequences, contexts up to 16K tokens,
     # chunks up to 700 rows (capped so that the oracle stays within a few seconds per case)
@@ -81,7 +84,7 @@ def test_random_larger_batch_attention(case):
         ql[i] = max(1, ql[i] // 2)
         pairs = ql * cx + ql * (ql + 1) // 2
     nblk = int(((cx + ql + 15) // 16).sum()) + 64
-    opts = [{}, {"mixed_lean": 2}, {"overlap": 2}, {}, {"mixed_fused": 1}, {"prefill_split": 3}][case]
+    opts = [{}, {"mixed_lean": 2}, {"overlap": 2}, {}, {"mixed_fused": 1}, {"prefill_split": 3}][case % 6]
     b = W.build_batch(Hq=Hq, Hkv=Hkv, hd=hd, q_lens=ql.astype(np.int32), ctx_lens=cx.astype(np.int32), num_blocks=nblk,
                       seed=7100 + case, poison=True)
     say(f"case: larger random {case}: {Hq}/{Hkv}/{hd}, {n} sequences, {int(ql.sum())} query rows in chunks of up to "
@@ -90,7 +93,7 @@ def test_random_larger_batch_attention(case):
     assert_parity(run_gpu(b, options=opts), ref, f"larger random {case}")
 
 
-@pytest.mark.parametrize("case", range(10))
+@pytest.mark.parametrize("case", range(N_LONG))
 def test_random_long_and_short_contexts(case):
     # one to three chunks on 4K-40K cached tokens among chunks on short contexts and decode sequences: the planner
     # cuts the long chunks' tiles into parts by their own number of steps (parts first in its list, whole tiles after)
@@ -103,7 +106,7 @@ def test_random_long_and_short_contexts(case):
     perm = rng.permutation(len(ql))
     ql, cx = ql[perm].astype(np.int32), cx[perm].astype(np.int32)
     nblk = int(((cx + ql + 15) // 16).sum()) + 32
-    opts = [{}, {}, {"overlap": 2}, {"prefill_waves": 8}, {}, {"mixed_lean": 2}, {"prefill_sorted": 0}, {}, {"prefill_split": 7}, {}][case]
+    opts = [{}, {}, {"overlap": 2}, {"prefill_waves": 8}, {}, {"mixed_lean": 2}, {"prefill_sorted": 0}, {}, {"prefill_split": 7}, {}][case % 10]
     if hd != 128:
         opts = {k: v for k, v in opts.items() if k not in ("prefill_waves", "mixed_lean")}
     b = W.build_batch(Hq=Hq, Hkv=Hkv, hd=hd, q_lens=ql, ctx_lens=cx, num_blocks=nblk, seed=7200 + case, poison=True)
@@ -119,7 +122,7 @@ def test_random_long_and_short_contexts(case):
     assert np.array_equal(first, again)
 
 
-@pytest.mark.parametrize("case", range(N_CASES))
+@pytest.mark.parametrize("case", range(FIRST, FIRST + N_CASES))
 def test_random_batch_append_and_copy(case):
     rng, b, _ = draw(case)
     say(f"case: random {case} append + copy: {b.Hq}/{b.Hkv}/{b.hd} q_lens={b.q_lens.tolist()} ctx={b.ctx_lens.tolist()}")
