@@ -1217,7 +1217,9 @@ ooco_status ooco_attn_mixed(ooco_ctx *ctx, const void *q, const void *k_cache, c
         // (what the kernels will address, once more against what the context owns: a plan that does not fit is an error of
         // this library, reported instead of launched)
         const size_t pf_end = (dec_floats + parts * (size_t)(32 * pl.pf_waves) * (ctx->hd + 2)) * sizeof(float);
-        if ((pl.pf_split > 1 && (pf_end > ctx->ws_bytes || parts > (size_t)kPrefillSplitUnits)) ||
+        // (arrival counters: one per part-0 slot with the tile list, one per (tile, kv head) without it)
+        const size_t pf_counters_used = pl.pf_table ? parts : (size_t)pl.n_tiles * ctx->Hkv;
+        if ((pl.pf_split > 1 && (pf_end > ctx->ws_bytes || pf_counters_used > (size_t)kPrefillSplitUnits)) ||
             (size_t)pl.slots * ctx->Hq * (ctx->hd + 2) * sizeof(float) > ctx->ws_bytes)
             return fail(ctx, OOCO_EINVAL, "ooco_attn_mixed: internal error: the plan's partial results (%zu bytes) do not fit the workspace (%zu bytes)",
                         pf_end, ctx->ws_bytes);

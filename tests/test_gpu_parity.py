@@ -129,6 +129,18 @@ def test_chunks_on_long_and_short_contexts_split_by_their_own_steps(opts):
     assert_parity(first, oracle(c), f"prefill-only, long and short contexts {opts}")
 
 
+def test_many_tiles_in_forced_parts_without_the_tile_list():
+    # 66 tiles forced into 16 parts each: 1,056 (tile, part) entries do not fit the tile list, so every tile gets its
+    # parts chunk by chunk -- 8,448 partial results (more than there are arrival counters, which count per tile here)
+    # in a workspace of 1 GiB
+    b = W.build_batch(Hq=32, Hkv=8, hd=128, q_lens=[1056, 1056], ctx_lens=[1100, 1100], num_blocks=300, seed=89, poison=True)
+    plan = B.ooco_plan_dry_run(32, 8, 128, 16, b.max_blocks_per_seq, 256, 1 << 30, b.seq_lens, b.query_start_loc, b.ctx_lens,
+                               prefill_split=16)
+    assert len(plan["prefill_tiles"]) == 66 and plan["prefill_parts"] == 16
+    say("case: 66 tiles in 16 forced parts each, no tile list")
+    assert_parity(run_gpu(b, options={"prefill_split": 16}, workspace_bytes=1 << 30), oracle(b), "66 tiles x 16 parts")
+
+
 @pytest.mark.parametrize("opts", [{}, {"prefill_sorted": 0}, {"prefill_sorted": 2}, {"prefill_split": 3}, {"prefill_waves": 8}, {"mixed_lean": 2},
                                   {"mixed_fused": 1}, {"overlap": 0}, {"overlap": 2}, {"overlap": 2, "mixed_lean": 2}],
                          ids=lambda o: "-".join(f"{k}{v}" for k, v in o.items()) or "default")

@@ -124,6 +124,20 @@ def test_plan_covers_every_block_and_row_once(cfg):
         check_cover(b, plan)
 
 
+def check_workspace(plan, Hq, Hkv, hd, workspace_bytes):
+    """What the kernels will write of partial results lies inside the workspace: the decode slots (fp32 accumulator,
+    maximum and sum per slot and query head), then, 256-byte aligned, one part per (part entry, kv head) of the split
+    prefill tiles (fp32, per query column of the tile)."""
+    dec = (plan["slots"] * Hq * (hd + 2) * 4 + 255) // 256 * 256
+    t = plan["prefill_tiles"]
+    entries = int(t[t[:, 4] > 1][:, 4].sum()) if len(t) else 0
+    cols = 256 if len(t) and int(t[:, 2].max()) * (Hq // Hkv) > 128 else 128
+    assert min(entries, len(t)) * Hkv <= 8192      # arrival counters: per part-0 slot with the tile list, per tile without
+    assert entries == 0 or dec + entries * Hkv * cols * (hd + 2) * 4 <= workspace_bytes
+    assert plan["slots"] * Hq * (hd + 2) * 4 <= workspace_bytes
+    assert plan["prefill_parts"] == (int(t[:, 4].max()) if len(t) else 1)
+
+
 def test_plans_of_random_batches_cover_every_block_and_row_once():
     # 300 seeded batches: 1-400 sequences, a random mix of empty / decode / chunk sequences, lengths over four orders of
     # magnitude, head shapes, compute-unit counts, workspace sizes and every planner option that shapes the work lists
@@ -146,7 +160,9 @@ def test_plans_of_random_batches_cover_every_block_and_row_once():
         b = W.Batch(Hq=Hq, Hkv=Hkv, hd=hd, BS=16, num_blocks=1, block_tables=np.zeros((n, 1), np.int32), seq_lens=cx + ql,
                     ctx_lens=cx, query_start_loc=qsl, q=None, k_cache=None, v_cache=None)
         try:
-            check_cover(b, dry(b.seq_lens, b.query_start_loc, b.ctx_lens, **kw))
+            plan = dry(b.seq_lens, b.query_start_loc, b.ctx_lens, **kw)
+            check_cover(b, plan)
+            check_workspace(plan, Hq, Hkv, hd, kw["workspace_bytes"])
         except Exception as e:
             raise AssertionError(f"case {case}: q_lens {ql.tolist()} ctx {cx.tolist()} {kw}") from e
 
