@@ -25,6 +25,14 @@ if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2511_21862_amd.build` "
                       "(the HIP library is the only implementation; there is no fallback)")
 
+# torch first: its wheel brings a HIP runtime of its own, and the one that is loaded first serves the whole process --
+# with libooco.so (linked against the system's runtime) loaded before torch, the process holds two runtimes and the
+# second to touch the GPU finds no device
+try:
+    import torch  # noqa: F401
+except ImportError:      # host-only use (planner, model, scheduling functions)
+    pass
+
 _lib = ctypes.CDLL(LIB_PATH)
 _P = ctypes.c_void_p
 _lib.ooco_ctx_create.restype = ctypes.c_int

@@ -1,6 +1,8 @@
 """GPU parity: libooco (through the C ABI) against the float64 CPU oracle, element by element,
 on seeded inputs.  Gates: max-abs <= 2e-2, mean-abs <= 2e-3, relative L2 <= 1e-2; block copy and
 run-to-run determinism bit-exact."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -127,6 +129,19 @@ def test_chunks_on_long_and_short_contexts_split_by_their_own_steps(opts):
         again = run_gpu(c, ctx=ctx)
         assert np.array_equal(first, again)
     assert_parity(first, oracle(c), f"prefill-only, long and short contexts {opts}")
+
+
+def test_binding_imported_before_torch_finds_the_gpu():
+    # a fresh process that imports the binding first and torch after it: the binding brings torch's HIP runtime in
+    # before the library's, so that the process holds one runtime and the context finds the device
+    import subprocess
+    import sys
+    code = ("import paper_2511_21862_amd.binding as B, torch; ctx = B.Context(32, 8, 128, 16, 64, 8); ctx.close(); "
+            "x = torch.zeros(4, device='cuda'); torch.cuda.synchronize(); print('context ok')")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    say("case: binding imported before torch, fresh process")
+    res = subprocess.run([sys.executable, "-c", code], cwd=root, capture_output=True, text=True, timeout=300)
+    assert res.returncode == 0 and "context ok" in res.stdout, res.stderr[-2000:]
 
 
 def test_many_tiles_in_forced_parts_without_the_tile_list():
