@@ -52,7 +52,9 @@
  *   the cache).  Query head h uses kv head h / (Hq/Hkv).  q_len_i == 1 is a decode request,
  *   q_len_i > 1 a prefill chunk, q_len_i == 0 contributes nothing.  Cache slots past
  *   seq_lens[i], unreferenced blocks and unused block-table columns are never used as values
- *   (they may hold NaN/Inf or invalid ids).
+ *   (they may hold NaN/Inf or invalid ids).  The ids in the USED columns, block_tables[i][0 ..
+ *   ceil(seq_lens[i]/BS) - 1], must lie in [0, num_blocks): the attention kernels read through them
+ *   unchecked.
  *   out = softmax(scale * q K^T) V with fp32 accumulation, rounded to bf16 (nearest even).
  */
 #ifndef OOCO_H
